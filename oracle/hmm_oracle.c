@@ -1,0 +1,165 @@
+/*
+ * CPU oracle for HMM smoothing and Viterbi decoding -- TEST INFRASTRUCTURE ONLY.
+ *
+ * Plain, sequential, single-threaded fp64 implementations of the two classical
+ * recursions that the paper's parallel-scan method is algebraically equivalent to
+ * (Sec. VI states the parallel and sequential methods are algebraically
+ * equivalent; Theorems 1-2 and Propositions 2-3 identify the scan results with
+ * the forward/backward potentials).  Nothing here is shared with the GPU library:
+ * no headers, no helpers, no tables.  Only tests, the smoke check and the
+ * benchmark's CPU-baseline leg may call it.
+ *
+ * Inputs are the same float32 arrays the GPU path consumes, widened to double.
+ *   prior[D]         p(x_1)
+ *   A[D][D]          A[i][j] = p(x_k = j | x_{k-1} = i)
+ *   ll[T][D]         ll[t][j] = log p(y_{t+1} | x_{t+1} = j)   (t is 0-based)
+ * Potentials (Sec. II): psi_1(x_1) = p(y_1|x_1) p(x_1),
+ *                       psi_k(x_{k-1}, x_k) = p(y_k|x_k) p(x_k|x_{k-1}).
+ *
+ * Pins (see tests/test_oracle_*.py): brute-force enumeration of all D^T sequences
+ * (the definitions of the marginals, of Z and of the MAP sequence in Sec. II and
+ * Sec. IV-A), closed forms (identical transition rows, identity transitions,
+ * constant evidence), D = 1, T = 1, and invariants.
+ */
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+
+/*
+ * Forward-backward recursion of Algorithm 1 with the marginal of the equation
+ * p(x_k) = psi^f_{1,k}(x_k) psi^b_{k,T}(x_k) / Z_k (Sec. III-A).
+ *
+ * The paper's recursion is stated on raw potentials, which underflow for long
+ * sequences; the only change made here is the classical per-step rescaling:
+ * the forward vector is divided by its sum (making it the filtering
+ * distribution p(x_k | y_{1:k})) and the removed factors are accumulated in the
+ * log domain, so that log Z = log p(y_{1:T}) is their total; the backward
+ * vector is divided by its largest entry (its scale cancels in Z_k).
+ *
+ * marginals[T][D], filtered[T][D] (may be NULL), *loglik.  Returns 0, or 1 on
+ * allocation failure / bad sizes.
+ */
+int hmm_oracle_smooth(const float *prior, const float *A, const float *ll,
+                      long T, int D, double *marginals, double *filtered, double *loglik)
+{
+    if (T < 1 || D < 1) return 1;
+    double *f = (double *)malloc(sizeof(double) * (size_t)T * D);   /* scaled psi^f_{1,k} */
+    double *b = (double *)malloc(sizeof(double) * D);               /* scaled psi^b_{k,T} */
+    double *bn = (double *)malloc(sizeof(double) * D);
+    double *g = (double *)malloc(sizeof(double) * D);
+    if (!f || !b || !bn || !g) { free(f); free(b); free(bn); free(g); return 1; }
+
+    double L = 0.0;
+    /* forward pass: psi^f_{1,1} = psi_1; psi^f_{1,k}(x_k) = sum_{x_{k-1}} psi^f_{1,k-1} psi_k */
+    for (long k = 0; k < T; ++k) {
+        const float *llk = ll + (size_t)k * D;
+        double m = -INFINITY;
+        for (int j = 0; j < D; ++j) if ((double)llk[j] > m) m = (double)llk[j];
+        double c = 0.0;
+        for (int j = 0; j < D; ++j) {
+            double pred;
+            if (k == 0) {
+                pred = (double)prior[j];
+            } else {
+                const double *fp = f + (size_t)(k - 1) * D;
+                pred = 0.0;
+                for (int i = 0; i < D; ++i) pred += fp[i] * (double)A[(size_t)i * D + j];
+            }
+            g[j] = pred * exp((double)llk[j] - m);
+            c += g[j];
+        }
+        for (int j = 0; j < D; ++j) f[(size_t)k * D + j] = g[j] / c;
+        L += m + log(c);
+    }
+    *loglik = L;
+    if (filtered) memcpy(filtered, f, sizeof(double) * (size_t)T * D);
+
+    /* backward pass: psi^b_{T,T} = 1; psi^b_{k,T}(x_k) = sum_{x_{k+1}} psi_{k+1}(x_k,x_{k+1}) psi^b_{k+1,T} */
+    for (int j = 0; j < D; ++j) b[j] = 1.0;
+    for (long k = T - 1; k >= 0; --k) {
+        /* marginal at step k from f_k and b_k */
+        double z = 0.0;
+        for (int j = 0; j < D; ++j) z += f[(size_t)k * D + j] * b[j];
+        for (int j = 0; j < D; ++j) marginals[(size_t)k * D + j] = f[(size_t)k * D + j] * b[j] / z;
+        if (k == 0) break;
+        const float *llk = ll + (size_t)k * D;
+        double m = -INFINITY;
+        for (int j = 0; j < D; ++j) if ((double)llk[j] > m) m = (double)llk[j];
+        for (int j = 0; j < D; ++j) g[j] = exp((double)llk[j] - m) * b[j];
+        double hm = 0.0;
+        for (int i = 0; i < D; ++i) {
+            double h = 0.0;
+            for (int j = 0; j < D; ++j) h += (double)A[(size_t)i * D + j] * g[j];
+            bn[i] = h;
+            if (h > hm) hm = h;
+        }
+        for (int i = 0; i < D; ++i) b[i] = bn[i] / hm;
+    }
+    free(f); free(b); free(bn); free(g);
+    return 0;
+}
+
+static double log_or_neginf(double p) { return p > 0.0 ? log(p) : -INFINITY; }
+
+/*
+ * Classical Viterbi recursion of Algorithm 4, carried out on logarithms of the
+ * potentials (a monotone transform, so every max and argmax is unchanged):
+ *   V_1(x_1) = log psi_1(x_1)
+ *   V_k(x_k) = max_{x_{k-1}} [log psi_k(x_{k-1},x_k) + V_{k-1}(x_{k-1})],  u_{k-1}(x_k) = argmax
+ *   x*_T = argmax V_T,  x*_{k-1} = u_{k-1}(x*_k).
+ * Ties (which the paper excludes by assuming a unique MAP sequence) are resolved
+ * towards the lowest state index.  *logprob = V_T(x*_T) = log p(y_{1:T}, x*_{1:T})
+ * (Corollary 1: the first component of a~_{0:T+1}).
+ */
+int hmm_oracle_viterbi(const float *prior, const float *A, const float *ll,
+                       long T, int D, int *path, double *logprob)
+{
+    if (T < 1 || D < 1) return 1;
+    unsigned char *u8 = NULL; int *u32 = NULL;
+    size_t nu = (size_t)(T > 1 ? T - 1 : 1) * D;
+    if (D <= 256) u8 = (unsigned char *)malloc(nu); else u32 = (int *)malloc(sizeof(int) * nu);
+    double *V = (double *)malloc(sizeof(double) * D);
+    double *Vn = (double *)malloc(sizeof(double) * D);
+    double *logA = (double *)malloc(sizeof(double) * (size_t)D * D);
+    if ((!u8 && !u32) || !V || !Vn || !logA) { free(u8); free(u32); free(V); free(Vn); free(logA); return 1; }
+    for (size_t e = 0; e < (size_t)D * D; ++e) logA[e] = log_or_neginf((double)A[e]);
+    for (int j = 0; j < D; ++j) V[j] = log_or_neginf((double)prior[j]) + (double)ll[j];
+    for (long k = 1; k < T; ++k) {
+        const float *llk = ll + (size_t)k * D;
+        for (int j = 0; j < D; ++j) {
+            double best = -INFINITY; int arg = 0;
+            for (int i = 0; i < D; ++i) {
+                double v = V[i] + logA[(size_t)i * D + j];
+                if (v > best) { best = v; arg = i; }
+            }
+            Vn[j] = best + (double)llk[j];
+            if (u8) u8[(size_t)(k - 1) * D + j] = (unsigned char)arg; else u32[(size_t)(k - 1) * D + j] = arg;
+        }
+        double *t = V; V = Vn; Vn = t;
+    }
+    double best = -INFINITY; int arg = 0;
+    for (int j = 0; j < D; ++j) if (V[j] > best) { best = V[j]; arg = j; }
+    *logprob = best;
+    path[T - 1] = arg;
+    for (long k = T - 1; k >= 1; --k) {
+        arg = u8 ? (int)u8[(size_t)(k - 1) * D + arg] : u32[(size_t)(k - 1) * D + arg];
+        path[k - 1] = arg;
+    }
+    free(u8); free(u32); free(V); free(Vn); free(logA);
+    return 0;
+}
+
+/*
+ * log of the joint of Sec. II evaluated on a given state sequence:
+ * log psi_1(x_1) + sum_{k>=2} log psi_k(x_{k-1}, x_k).  Used to adjudicate
+ * decodings that differ from the oracle's only at numerical near-ties.
+ */
+double hmm_oracle_score(const float *prior, const float *A, const float *ll,
+                        long T, int D, const int *path)
+{
+    double s = log_or_neginf((double)prior[path[0]]) + (double)ll[path[0]];
+    for (long k = 1; k < T; ++k) {
+        s += log_or_neginf((double)A[(size_t)path[k - 1] * D + path[k]]) + (double)ll[(size_t)k * D + path[k]];
+    }
+    return s;
+}
