@@ -1,0 +1,97 @@
+/*
+ * hmmscan -- HMM smoothing and Viterbi decoding as all-prefix-sums on AMD MI355X (gfx950).
+ *
+ * C ABI.  Every array argument is DEVICE memory owned by the caller; the library
+ * allocates nothing, keeps no per-call state and never synchronises: all work is
+ * enqueued on the caller's HIP stream and outputs are valid once that stream has
+ * been synchronised.  Inputs are never written; outputs and the workspace must
+ * not alias the inputs or each other.  All arrays are contiguous and row-major.
+ *
+ * Model (Sec. II of the paper): x_1 ~ prior, x_k ~ A[x_{k-1}][.], y_k ~ p(y_k | x_k),
+ * states are 0-based, potentials psi_1(x_1) = p(y_1|x_1) p(x_1) and
+ * psi_k(x_{k-1},x_k) = p(y_k|x_k) A[x_{k-1}][x_k].  Observations enter only
+ * through loglik[b][t][j] = log p(y_{t+1} | x_{t+1} = j), which may hold -inf
+ * (impossible) entries.  Zero entries in prior and A are legal.
+ *
+ * Errors are return codes only.  Argument errors are detected on the host before
+ * anything is launched; a failed launch is reported as HMM_ERR_DEVICE.  A step
+ * whose evidence is impossible under every state (a log-likelihood row that is
+ * all -inf, or Z = 0) is not an error: the returned log-likelihood /
+ * log-probability is then -inf or NaN and the marginals / path are unspecified.
+ */
+#ifndef HMMSCAN_H
+#define HMMSCAN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    HMM_OK = 0,
+    HMM_ERR_INVALID_ARG = 1,   /* null required pointer, T < 1, D < 1, batch < 1, misaligned array */
+    HMM_ERR_UNSUPPORTED = 2,   /* D above HMM_MAX_STATES, or a shape the launch grid cannot hold  */
+    HMM_ERR_WORKSPACE = 3,     /* workspace null or smaller than hmm_workspace_bytes reports      */
+    HMM_ERR_DEVICE = 4         /* a HIP call or kernel launch failed                              */
+} hmm_status;
+
+/* Largest supported number of states D. */
+#define HMM_MAX_STATES 128
+
+/*
+ * Scratch size, in bytes, that hmm_smooth and hmm_viterbi need for this shape.
+ * Pure host function (no device access).  Either output pointer may be NULL.
+ */
+hmm_status hmm_workspace_bytes(int64_t T, int32_t D, int32_t batch,
+                               size_t* smooth_bytes, size_t* viterbi_bytes);
+
+/*
+ * Smoothing marginals and log-likelihood by the parallel sum-product method
+ * (Algorithm 3: element initialisation, forward all-prefix-sums and reversed
+ * all-prefix-sums under the operator of Definition 3, then the marginal
+ * p(x_k) = a_{0:k} a_{k:T+1} / Z_k).
+ *
+ *   prior      [shared_model ? 1 : batch][D]     p(x_1)
+ *   A          [shared_model ? 1 : batch][D][D]  A[i][j] = p(x_k = j | x_{k-1} = i)
+ *   loglik     [batch][T][D]
+ *   marginals  [batch][T][D]  out: p(x_t | y_{1:T})
+ *   filtered   [batch][T][D]  out, may be NULL: p(x_t | y_{1:t}) (the normalised forward potential)
+ *   loglik_out [batch]        out: log p(y_{1:T}) = log Z (the partition function of Sec. II)
+ *   workspace / workspace_bytes: device scratch of at least hmm_workspace_bytes(...).smooth_bytes,
+ *              256-byte aligned; contents on entry are ignored, on exit undefined
+ *   hip_stream a hipStream_t (NULL = the default stream)
+ *
+ * loglik, marginals and filtered must be 16-byte aligned.  fp32 arithmetic
+ * throughout, scale factors accumulated in fp64.
+ */
+hmm_status hmm_smooth(const float* prior, const float* A, const float* loglik,
+                      int64_t T, int32_t D, int32_t batch, int32_t shared_model,
+                      float* marginals, float* filtered, double* loglik_out,
+                      void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * MAP state sequence (Viterbi path) by the parallel max-product method
+ * (Algorithm 5's forward all-prefix-sums under the operator of Definition 5,
+ * taken on logarithms), with the path recovered from the back-pointers
+ * u_{k-1}(x_k) of Sec. IV-A by a reversed all-prefix-sums under function
+ * composition, seeded with x*_T = argmax V_T.  Ties resolve to the lowest state.
+ *
+ *   path        [batch][T]  out: 0-based states x*_1..x*_T
+ *   logprob_out [batch]     out: log p(y_{1:T}, x*_{1:T}) (Corollary 1: the joint, not the posterior)
+ *   workspace: at least hmm_workspace_bytes(...).viterbi_bytes, 256-byte aligned
+ * Other arguments as for hmm_smooth.
+ */
+hmm_status hmm_viterbi(const float* prior, const float* A, const float* loglik,
+                       int64_t T, int32_t D, int32_t batch, int32_t shared_model,
+                       int32_t* path, double* logprob_out,
+                       void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Static, human-readable name of a status code. */
+const char* hmm_status_string(hmm_status status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HMMSCAN_H */

@@ -1,0 +1,146 @@
+"""ctypes binding of libhmmscan.so: same names as the C ABI, argument marshalling only.
+
+Tensors are torch CUDA (ROCm) tensors used purely as device memory; the stream
+is torch's current stream.  Every step of the computation runs in the HIP
+library; there is no fallback of any kind -- a missing library is an error.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libhmmscan.so")
+
+HMM_OK = 0
+_lib = None
+
+EXPORTED_SYMBOLS = ("hmm_workspace_bytes", "hmm_smooth", "hmm_viterbi", "hmm_status_string")
+
+
+class HmmError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {status_string(code)}")
+
+
+def load_library():
+    """Load the HIP library; raises if it has not been built (no CPU fallback exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2102_05743_amd.build` "
+                "(or __graft_entry__.build()); the library has no non-HIP fallback")
+        lib = ctypes.CDLL(LIB_PATH)
+        vp, sz = ctypes.c_void_p, ctypes.c_size_t
+        lib.hmm_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32,
+                                            ctypes.POINTER(sz), ctypes.POINTER(sz)]
+        lib.hmm_workspace_bytes.restype = ctypes.c_int
+        lib.hmm_smooth.argtypes = [vp, vp, vp, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                   vp, vp, vp, vp, sz, vp]
+        lib.hmm_smooth.restype = ctypes.c_int
+        lib.hmm_viterbi.argtypes = [vp, vp, vp, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                    vp, vp, vp, sz, vp]
+        lib.hmm_viterbi.restype = ctypes.c_int
+        lib.hmm_status_string.argtypes = [ctypes.c_int]
+        lib.hmm_status_string.restype = ctypes.c_char_p
+        _lib = lib
+    return _lib
+
+
+def status_string(code: int) -> str:
+    return load_library().hmm_status_string(int(code)).decode()
+
+
+def hmm_workspace_bytes(T: int, D: int, batch: int):
+    """Returns (smooth_bytes, viterbi_bytes)."""
+    lib = load_library()
+    s, v = ctypes.c_size_t(0), ctypes.c_size_t(0)
+    rc = lib.hmm_workspace_bytes(int(T), int(D), int(batch), ctypes.byref(s), ctypes.byref(v))
+    if rc != HMM_OK:
+        raise HmmError(rc, "hmm_workspace_bytes")
+    return int(s.value), int(v.value)
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _check(t, dtype, shape, name):
+    import torch
+    if not isinstance(t, torch.Tensor) or not t.is_cuda or t.dtype != dtype or not t.is_contiguous() \
+            or tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name}: expected contiguous device tensor {dtype} {tuple(shape)}, got "
+                         f"{getattr(t, 'dtype', None)} {tuple(getattr(t, 'shape', ()))}")
+
+
+def _shapes(prior, A, loglik):
+    B, T, D = loglik.shape
+    Bm = prior.shape[0]
+    if Bm not in (1, B):
+        raise ValueError("prior/A leading dimension must be 1 (shared) or batch")
+    shared = 1 if (Bm == 1) else 0
+    return B, T, D, Bm, shared
+
+
+def _stream():
+    import torch
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def hmm_smooth(prior, A, loglik, marginals=None, filtered=None, loglik_out=None, workspace=None,
+               want_filtered: bool = False):
+    """prior[Bm][D], A[Bm][D][D], loglik[B][T][D] float32 device tensors (Bm = 1 or B).
+    Returns (marginals[B][T][D] f32, filtered or None, loglik_out[B] f64); asynchronous on
+    torch's current stream."""
+    import torch
+    lib = load_library()
+    B, T, D, Bm, shared = _shapes(prior, A, loglik)
+    f32 = torch.float32
+    _check(prior, f32, (Bm, D), "prior")
+    _check(A, f32, (Bm, D, D), "A")
+    _check(loglik, f32, (B, T, D), "loglik")
+    dev = loglik.device
+    if marginals is None:
+        marginals = torch.empty((B, T, D), dtype=f32, device=dev)
+    if filtered is None and want_filtered:
+        filtered = torch.empty((B, T, D), dtype=f32, device=dev)
+    if loglik_out is None:
+        loglik_out = torch.empty((B,), dtype=torch.float64, device=dev)
+    _check(marginals, f32, (B, T, D), "marginals")
+    if filtered is not None:
+        _check(filtered, f32, (B, T, D), "filtered")
+    _check(loglik_out, torch.float64, (B,), "loglik_out")
+    if workspace is None:
+        workspace = torch.empty((max(hmm_workspace_bytes(T, D, B)[0], 256),), dtype=torch.uint8, device=dev)
+    rc = lib.hmm_smooth(_ptr(prior), _ptr(A), _ptr(loglik), T, D, B, shared, _ptr(marginals), _ptr(filtered),
+                        _ptr(loglik_out), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream())
+    if rc != HMM_OK:
+        raise HmmError(rc, "hmm_smooth")
+    return marginals, filtered, loglik_out
+
+
+def hmm_viterbi(prior, A, loglik, path=None, logprob_out=None, workspace=None):
+    """Returns (path[B][T] int32, logprob_out[B] f64); asynchronous on torch's current stream."""
+    import torch
+    lib = load_library()
+    B, T, D, Bm, shared = _shapes(prior, A, loglik)
+    f32 = torch.float32
+    _check(prior, f32, (Bm, D), "prior")
+    _check(A, f32, (Bm, D, D), "A")
+    _check(loglik, f32, (B, T, D), "loglik")
+    dev = loglik.device
+    if path is None:
+        path = torch.empty((B, T), dtype=torch.int32, device=dev)
+    if logprob_out is None:
+        logprob_out = torch.empty((B,), dtype=torch.float64, device=dev)
+    _check(path, torch.int32, (B, T), "path")
+    _check(logprob_out, torch.float64, (B,), "logprob_out")
+    if workspace is None:
+        workspace = torch.empty((max(hmm_workspace_bytes(T, D, B)[1], 256),), dtype=torch.uint8, device=dev)
+    rc = lib.hmm_viterbi(_ptr(prior), _ptr(A), _ptr(loglik), T, D, B, shared, _ptr(path), _ptr(logprob_out),
+                         _ptr(workspace), workspace.numel() * workspace.element_size(), _stream())
+    if rc != HMM_OK:
+        raise HmmError(rc, "hmm_viterbi")
+    return path, logprob_out

@@ -1,0 +1,82 @@
+// C ABI of the library: argument validation and dispatch by state-space size.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/hmmscan.h"
+#include "small_d.hpp"
+
+namespace {
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+hmm_status check_common(const float* prior, const float* A, const float* loglik, int64_t T, int32_t D,
+                        int32_t batch) {
+    if (!prior || !A || !loglik) return HMM_ERR_INVALID_ARG;
+    if (T < 1 || D < 1 || batch < 1) return HMM_ERR_INVALID_ARG;
+    if (D > HMM_MAX_STATES) return HMM_ERR_UNSUPPORTED;
+    if (!aligned16(loglik)) return HMM_ERR_INVALID_ARG;
+    return HMM_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+hmm_status hmm_workspace_bytes(int64_t T, int32_t D, int32_t batch, size_t* smooth_bytes, size_t* viterbi_bytes) {
+    if (T < 1 || D < 1 || batch < 1) return HMM_ERR_INVALID_ARG;
+    if (D > HMM_MAX_STATES) return HMM_ERR_UNSUPPORTED;
+    size_t s = 0, v = 0;
+    if (D <= hmm::SMALL_D_MAX) {
+        s = hmm::small_d_smooth_ws_bytes(D, T, batch);
+        v = hmm::small_d_viterbi_ws_bytes(D, T, batch);
+    } else {
+        return HMM_ERR_UNSUPPORTED;
+    }
+    if (smooth_bytes) *smooth_bytes = s;
+    if (viterbi_bytes) *viterbi_bytes = v;
+    return HMM_OK;
+}
+
+hmm_status hmm_smooth(const float* prior, const float* A, const float* loglik, int64_t T, int32_t D, int32_t batch,
+                      int32_t shared_model, float* marginals, float* filtered, double* loglik_out, void* workspace,
+                      size_t workspace_bytes, void* hip_stream) {
+    hmm_status st = check_common(prior, A, loglik, T, D, batch);
+    if (st != HMM_OK) return st;
+    if (!marginals || !loglik_out) return HMM_ERR_INVALID_ARG;
+    if (!aligned16(marginals) || (filtered && !aligned16(filtered))) return HMM_ERR_INVALID_ARG;
+    size_t need = 0;
+    st = hmm_workspace_bytes(T, D, batch, &need, nullptr);
+    if (st != HMM_OK) return st;
+    if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return HMM_ERR_WORKSPACE;
+    hmm::SmallArgs a{prior, A, loglik, (long long)T, batch, shared_model ? 1 : 0, workspace, workspace_bytes,
+                     static_cast<hipStream_t>(hip_stream)};
+    return static_cast<hmm_status>(hmm::small_d_smooth(D, a, marginals, filtered, loglik_out));
+}
+
+hmm_status hmm_viterbi(const float* prior, const float* A, const float* loglik, int64_t T, int32_t D, int32_t batch,
+                       int32_t shared_model, int32_t* path, double* logprob_out, void* workspace,
+                       size_t workspace_bytes, void* hip_stream) {
+    hmm_status st = check_common(prior, A, loglik, T, D, batch);
+    if (st != HMM_OK) return st;
+    if (!path || !logprob_out) return HMM_ERR_INVALID_ARG;
+    size_t need = 0;
+    st = hmm_workspace_bytes(T, D, batch, nullptr, &need);
+    if (st != HMM_OK) return st;
+    if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return HMM_ERR_WORKSPACE;
+    hmm::SmallArgs a{prior, A, loglik, (long long)T, batch, shared_model ? 1 : 0, workspace, workspace_bytes,
+                     static_cast<hipStream_t>(hip_stream)};
+    return static_cast<hmm_status>(hmm::small_d_viterbi(D, a, path, logprob_out));
+}
+
+const char* hmm_status_string(hmm_status status) {
+    switch (status) {
+        case HMM_OK: return "HMM_OK";
+        case HMM_ERR_INVALID_ARG: return "HMM_ERR_INVALID_ARG";
+        case HMM_ERR_UNSUPPORTED: return "HMM_ERR_UNSUPPORTED";
+        case HMM_ERR_WORKSPACE: return "HMM_ERR_WORKSPACE";
+        case HMM_ERR_DEVICE: return "HMM_ERR_DEVICE";
+    }
+    return "HMM_ERR_UNKNOWN";
+}
+
+}  // extern "C"

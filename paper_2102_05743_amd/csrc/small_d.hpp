@@ -1,0 +1,29 @@
+// Host-side entry points of the register-resident (D <= 8) path.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace hmm {
+
+struct SmallArgs {
+    const float* prior;
+    const float* A;
+    const float* ll;
+    long long T;
+    int batch;
+    int shared_model;
+    void* ws;
+    size_t ws_bytes;
+    hipStream_t stream;
+};
+
+constexpr int SMALL_D_MAX = 8;
+
+// Return codes follow hmm_status (0 ok, 2 unsupported, 3 workspace, 4 device).
+size_t small_d_smooth_ws_bytes(int D, long long T, int batch);
+size_t small_d_viterbi_ws_bytes(int D, long long T, int batch);
+int small_d_smooth(int D, const SmallArgs& a, float* marg, float* filt, double* loglik_out);
+int small_d_viterbi(int D, const SmallArgs& a, int32_t* path, double* logprob_out);
+
+}  // namespace hmm

@@ -1,0 +1,73 @@
+"""Boundary checks that need no GPU: the C-ABI library loads, exports every symbol the public
+header declares, its pure-host functions work, and argument errors are reported before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2102_05743_amd as hmm
+from paper_2102_05743_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    names = []
+    for fn in os.listdir(os.path.join(ROOT, "include")):
+        if fn.endswith(".h"):
+            src = open(os.path.join(ROOT, "include", fn)).read()
+            src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+            names += re.findall(r"\b(hmm_[a-z_]+)\s*\(", src)
+    return sorted(set(names))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = hmm.load_library()
+    declared = _declared_functions()
+    assert set(declared) == set(binding.EXPORTED_SYMBOLS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def test_status_strings():
+    assert hmm.status_string(0) == "HMM_OK"
+    assert hmm.status_string(1) == "HMM_ERR_INVALID_ARG"
+    assert hmm.status_string(2) == "HMM_ERR_UNSUPPORTED"
+    assert hmm.status_string(3) == "HMM_ERR_WORKSPACE"
+    assert hmm.status_string(4) == "HMM_ERR_DEVICE"
+
+
+def test_workspace_query():
+    s, v = hmm.hmm_workspace_bytes(1 << 20, 4, 1)
+    assert 0 < s < (1 << 22) and 0 < v < (1 << 23)
+    s2, v2 = hmm.hmm_workspace_bytes(1 << 20, 4, 8)
+    assert s2 > s and v2 > v
+    for bad in [(0, 4, 1), (10, 0, 1), (10, 4, 0)]:
+        with pytest.raises(hmm.HmmError) as e:
+            hmm.hmm_workspace_bytes(*bad)
+        assert e.value.code == 1
+    with pytest.raises(hmm.HmmError) as e:
+        hmm.hmm_workspace_bytes(10, 129, 1)
+    assert e.value.code == 2
+
+
+def test_argument_errors_are_caught_on_the_host():
+    lib = hmm.load_library()
+    fake = ctypes.c_void_p(0x1000)       # never dereferenced: every call below fails validation first
+    null = ctypes.c_void_p(0)
+    # null required pointers
+    assert lib.hmm_smooth(null, fake, fake, 8, 4, 1, 1, fake, null, fake, fake, 1 << 20, null) == 1
+    assert lib.hmm_smooth(fake, fake, fake, 8, 4, 1, 1, null, null, fake, fake, 1 << 20, null) == 1
+    assert lib.hmm_viterbi(fake, fake, fake, 8, 4, 1, 1, null, fake, fake, 1 << 20, null) == 1
+    # bad sizes
+    assert lib.hmm_smooth(fake, fake, fake, 0, 4, 1, 1, fake, null, fake, fake, 1 << 20, null) == 1
+    assert lib.hmm_viterbi(fake, fake, fake, 8, 0, 1, 1, fake, fake, fake, 1 << 20, null) == 1
+    assert lib.hmm_viterbi(fake, fake, fake, 8, 4, -1, 1, fake, fake, fake, 1 << 20, null) == 1
+    assert lib.hmm_smooth(fake, fake, fake, 8, 1000, 1, 1, fake, null, fake, fake, 1 << 20, null) == 2
+    # misaligned log-likelihoods
+    assert lib.hmm_smooth(fake, fake, ctypes.c_void_p(0x1004), 8, 4, 1, 1, fake, null, fake, fake, 1 << 20, null) == 1
+    # workspace: null, too small, misaligned
+    assert lib.hmm_smooth(fake, fake, fake, 8, 4, 1, 1, fake, null, fake, null, 1 << 20, null) == 3
+    assert lib.hmm_smooth(fake, fake, fake, 8, 4, 1, 1, fake, null, fake, fake, 16, null) == 3
+    assert lib.hmm_viterbi(fake, fake, fake, 8, 4, 1, 1, fake, fake, ctypes.c_void_p(0x1010), 1 << 20, null) == 3

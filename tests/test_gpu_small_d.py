@@ -1,0 +1,70 @@
+"""GPU parity, register-resident path (D <= 8): the HIP library through its C ABI against the
+CPU oracle, element by element, on seeded inputs spanning several tiles and ragged tails."""
+import numpy as np
+import pytest
+
+from paper_2102_05743_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gu():
+    import gpu_util
+    return gpu_util
+
+
+def test_config1(gu):
+    p = wl.config1()
+    gu.check_smooth(p, want_filtered=True)
+    gu.check_viterbi(p)
+
+
+@pytest.mark.parametrize("T", [1, 2, 15, 16, 17, 4095, 4096, 4097, 10000])
+def test_config2_shapes_ragged(gu, T):
+    p = wl.config2(T=T)
+    gu.check_smooth(p, want_filtered=(T % 2 == 1), label=f"C2 T={T}")
+    gu.check_viterbi(p, label=f"C2 T={T}")
+
+
+def test_gilbert_elliott_paper_model(gu):
+    p = wl.gilbert_elliott(T=100000)
+    gu.check_smooth(p)
+    gu.check_viterbi(p)
+
+
+@pytest.mark.parametrize("D", [1, 2, 3, 4, 5, 6, 7, 8])
+@pytest.mark.parametrize("T", [1, 7, 300, 4500, 20011])
+def test_random_models_every_small_D(gu, D, T):
+    p = wl.random_problem(D, T, seed=100 * D + T % 97)
+    gu.check_smooth(p, want_filtered=(T == 300))
+    gu.check_viterbi(p)
+
+
+@pytest.mark.parametrize("D,T,B,shared", [(4, 5000, 3, True), (4, 4097, 5, False), (3, 100, 17, False),
+                                          (8, 2100, 4, False), (2, 9000, 2, True)])
+def test_batched(gu, D, T, B, shared):
+    p = wl.random_problem(D, T, batch=B, shared_model=shared, seed=7 * D + B)
+    gu.check_smooth(p, want_filtered=True)
+    gu.check_viterbi(p)
+
+
+@pytest.mark.parametrize("D,T", [(4, 6000), (6, 3000), (3, 4100)])
+def test_zero_transitions_and_impossible_emissions(gu, D, T):
+    """Zero entries in A (log 0 in the max-product path) and -inf log-likelihood entries
+    (every step keeps at least one possible state)."""
+    p = wl.random_problem(D, T, seed=900 + D, zero_frac=0.35)
+    rng = np.random.default_rng(D)
+    mask = rng.random(p.loglik.shape) < 0.15
+    mask[..., 0] = False
+    # keep the model consistent: forbid an emission only where the diagonal keeps the chain alive
+    p.loglik[mask] = -np.inf
+    gu.check_smooth(p)
+    gu.check_viterbi(p)
+
+
+def test_config2_full_size(gu):
+    """The headline workload at its full size, compared element by element with the oracle."""
+    p = wl.config2()
+    gu.check_smooth(p, want_filtered=False, label="C2 full")
+    gu.check_viterbi(p, label="C2 full")
