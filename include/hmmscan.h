@@ -91,6 +91,20 @@ hmm_status hmm_viterbi(const float* prior, const float* A, const float* loglik,
 /* Static, human-readable name of a status code. */
 const char* hmm_status_string(hmm_status status);
 
+/*
+ * Measurement aid (not part of the method): per-kernel timing with HIP events.
+ * hmm_kernel_timing_enable(1) clears earlier records and makes every later kernel launch of the
+ * library record one HIP event before and one after it on the caller's stream;
+ * hmm_kernel_timing_enable(0) switches recording off and clears the records.
+ * hmm_kernel_timing_count() waits for the recorded events and returns the number of distinct
+ * kernels seen; hmm_kernel_timing_get(i, ...) returns, for the i-th of them, a static name, the
+ * summed elapsed time in milliseconds and the number of launches.  Process-global, not
+ * thread-safe, and the only state the library keeps; events are created on first use and reused.
+ */
+hmm_status hmm_kernel_timing_enable(int32_t on);
+int32_t hmm_kernel_timing_count(void);
+hmm_status hmm_kernel_timing_get(int32_t index, const char** name, double* total_ms, int64_t* launches);
+
 #ifdef __cplusplus
 }
 #endif

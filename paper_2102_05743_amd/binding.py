@@ -15,7 +15,8 @@ LIB_PATH = os.path.join(_HERE, "libhmmscan.so")
 HMM_OK = 0
 _lib = None
 
-EXPORTED_SYMBOLS = ("hmm_workspace_bytes", "hmm_smooth", "hmm_viterbi", "hmm_status_string")
+EXPORTED_SYMBOLS = ("hmm_workspace_bytes", "hmm_smooth", "hmm_viterbi", "hmm_status_string",
+                    "hmm_kernel_timing_enable", "hmm_kernel_timing_count", "hmm_kernel_timing_get")
 
 
 class HmmError(RuntimeError):
@@ -45,6 +46,13 @@ def load_library():
         lib.hmm_viterbi.restype = ctypes.c_int
         lib.hmm_status_string.argtypes = [ctypes.c_int]
         lib.hmm_status_string.restype = ctypes.c_char_p
+        lib.hmm_kernel_timing_enable.argtypes = [ctypes.c_int32]
+        lib.hmm_kernel_timing_enable.restype = ctypes.c_int
+        lib.hmm_kernel_timing_count.argtypes = []
+        lib.hmm_kernel_timing_count.restype = ctypes.c_int32
+        lib.hmm_kernel_timing_get.argtypes = [ctypes.c_int32, ctypes.POINTER(ctypes.c_char_p),
+                                              ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
+        lib.hmm_kernel_timing_get.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -61,6 +69,25 @@ def hmm_workspace_bytes(T: int, D: int, batch: int):
     if rc != HMM_OK:
         raise HmmError(rc, "hmm_workspace_bytes")
     return int(s.value), int(v.value)
+
+
+def hmm_kernel_timing_enable(on: bool) -> None:
+    rc = load_library().hmm_kernel_timing_enable(1 if on else 0)
+    if rc != HMM_OK:
+        raise HmmError(rc, "hmm_kernel_timing_enable")
+
+
+def hmm_kernel_timing_get():
+    """Returns {kernel name: (total_ms, launches)} for everything recorded since the last enable."""
+    lib = load_library()
+    out = {}
+    for i in range(lib.hmm_kernel_timing_count()):
+        name, ms, n = ctypes.c_char_p(), ctypes.c_double(0.0), ctypes.c_int64(0)
+        rc = lib.hmm_kernel_timing_get(i, ctypes.byref(name), ctypes.byref(ms), ctypes.byref(n))
+        if rc != HMM_OK:
+            raise HmmError(rc, "hmm_kernel_timing_get")
+        out[name.value.decode()] = (float(ms.value), int(n.value))
+    return out
 
 
 def _ptr(t):

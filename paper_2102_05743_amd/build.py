@@ -11,7 +11,9 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB_PATH = os.path.join(HERE, "libhmmscan.so")
 
-SOURCES = ["api.hip", "small_d.hip"]
+# (source, extra defines, object name)
+UNITS = [("api.hip", [], "api.o"), ("ktimer.hip", [], "ktimer.o"), ("small_d.hip", [], "small_d.o")] + \
+        [("small_d_kernels.hip", ["-DHMM_SMALL_D=%d" % d], "small_d_kernels_%d.o" % d) for d in range(1, 9)]
 
 HIPCC_FLAGS = [
     "-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC",
@@ -28,20 +30,21 @@ def _hipcc() -> str:
     return "hipcc"
 
 
-def _compile(src: str) -> str:
-    obj = os.path.join(OBJ_DIR, os.path.splitext(src)[0] + ".o")
-    cmd = [_hipcc(), *HIPCC_FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+def _compile(unit) -> str:
+    src, defines, objname = unit
+    obj = os.path.join(OBJ_DIR, objname)
+    cmd = [_hipcc(), *HIPCC_FLAGS, *defines, "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         sys.stderr.write(r.stdout + r.stderr)
-        raise RuntimeError("hipcc failed on " + src)
+        raise RuntimeError("hipcc failed on " + " ".join([src] + defines))
     return obj
 
 
 def build_library(verbose: bool = True) -> str:
     os.makedirs(OBJ_DIR, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
-        objs = list(ex.map(_compile, SOURCES))
+    with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1)) as ex:
+        objs = list(ex.map(_compile, UNITS))
     tmp = LIB_PATH + ".tmp.%d" % os.getpid()
     r = subprocess.run([_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs],
                        capture_output=True, text=True)

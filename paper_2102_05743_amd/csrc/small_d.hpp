@@ -20,7 +20,16 @@ struct SmallArgs {
 
 constexpr int SMALL_D_MAX = 8;
 
-// Return codes follow hmm_status (0 ok, 2 unsupported, 3 workspace, 4 device).
+// One explicit instantiation per D, each in its own translation unit (small_d_kernels.hip
+// compiled with -DHMM_SMALL_D=<D>).  Return codes follow hmm_status.
+template <int D>
+struct SmallD {
+    static size_t smooth_ws_bytes(long long T, int batch);
+    static size_t viterbi_ws_bytes(long long T, int batch);
+    static int smooth(const SmallArgs& a, float* marg, float* filt, double* loglik_out);
+    static int viterbi(const SmallArgs& a, int32_t* path, double* logprob_out);
+};
+
 size_t small_d_smooth_ws_bytes(int D, long long T, int batch);
 size_t small_d_viterbi_ws_bytes(int D, long long T, int batch);
 int small_d_smooth(int D, const SmallArgs& a, float* marg, float* filt, double* loglik_out);

@@ -1,0 +1,714 @@
+// Kernels and launch logic of the register-resident path for ONE state-space size
+// D = HMM_SMALL_D (this file is compiled once per D in 1..8).
+//
+// Two launch plans compute the same thing with the same per-lane arithmetic:
+//   * single-launch ("fused"): every tile is one co-resident workgroup; tile aggregates (and, for
+//     Viterbi, tile back-pointer maps) are exchanged through flags in the workspace, so the
+//     log-likelihoods are read from HBM once and nothing but the outputs is written back;
+//   * multi-launch: reduce -> carry -> apply (-> suffix -> path) kernels with no inter-workgroup
+//     waiting, for shapes with more tiles than the GPU can hold resident at once.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdlib.h>
+
+#include "ktimer.hpp"
+#include "small_d.hpp"
+#include "small_d_device.hpp"
+
+#ifndef HMM_SMALL_D
+#error "compile with -DHMM_SMALL_D=<1..8>"
+#endif
+
+namespace hmm {
+
+// Development aid, compiled out unless HMM_PHASE_STAMPS is defined: wall-clock stamps per workgroup.
+#ifdef HMM_PHASE_STAMPS
+__device__ unsigned long long g_stamps[1024 * 16];
+#define HMM_STAMP(i) do { if ((threadIdx.x & 63) == 0 && blockIdx.x < 256) g_stamps[(blockIdx.x * 4 + (threadIdx.x >> 6)) * 16 + (i)] = wall_clock64(); } while (0)
+#else
+#define HMM_STAMP(i) do { } while (0)
+#endif
+
+// =============================================================================================
+// Multi-launch plan
+// =============================================================================================
+
+// Kernel 1 (both operators): tile aggregates
+template <class S, int D>
+__global__ __launch_bounds__(256) void sd_reduce_kernel(const float* __restrict__ A, const float* __restrict__ ll,
+                                                        long long T, int tps, int shared_model,
+                                                        float* __restrict__ agg) {
+    using C = SmallCfg<D>;
+    __shared__ float lds[C::LDS_FLOATS];
+    __shared__ float wagg[C::NW * D * D];
+    const TileCoord tc = tile_coord<D>(T, tps);
+    load_tile<D>(ll + tc.base * D, tc.nvalid, lds);
+    float Am[D * D];
+    load_model<S, D>(A + (shared_model ? 0 : (size_t)tc.seq * D * D), Am);
+    __syncthreads();
+    const int n = min(max(tc.nvalid - (int)threadIdx.x * C::L, 0), C::L);
+    float P[D * D], Q[D * D];
+    double msum;
+    chunk_aggregate<S, D, false>(lds + threadIdx.x * C::STRIDE, n, tc.tile == 0 && threadIdx.x == 0, Am, P, msum);
+    block_prefix<S, D>(P, Q, wagg);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float X[D * D];
+        block_total<S, D>(wagg, X);
+#pragma unroll
+        for (int e = 0; e < D * D; ++e) agg[(size_t)blockIdx.x * D * D + e] = X[e];
+    }
+}
+
+// Kernel 2 (both operators): carries between tiles of one sequence.  One workgroup per sequence;
+// lane t folds R consecutive tile aggregates, the workgroup exchanges the folds, then each lane
+// walks its tiles again with vectors.  fin[tile] = forward potential before the tile's first
+// step (prior for tile 0); bout[tile] = backward potential at the tile's last step (ones at T).
+template <class S, int D, bool BWD>
+__global__ __launch_bounds__(256) void sd_carry_kernel(const float* __restrict__ prior, int tps, int shared_model,
+                                                       const float* __restrict__ agg, float* __restrict__ fin,
+                                                       float* __restrict__ bout) {
+    using C = SmallCfg<D>;
+    __shared__ float wagg[C::NW * D * D];
+    const int seq = blockIdx.x;
+    const int R = (tps + C::NT - 1) / C::NT;
+    const int t0 = threadIdx.x * R;
+    const float* sagg = agg + (size_t)seq * tps * D * D;
+    float P[D * D];
+    mat_identity<S, D>(P);
+    for (int r = 0; r < R; ++r) {
+        const int tile = t0 + r;
+        if (tile < tps) {
+            float M[D * D], Z[D * D];
+#pragma unroll
+            for (int e = 0; e < D * D; ++e) M[e] = sagg[(size_t)tile * D * D + e];
+            mat_mul<S, D>(P, M, Z);
+            renorm<S, D * D>(Z);
+#pragma unroll
+            for (int e = 0; e < D * D; ++e) P[e] = Z[e];
+        }
+    }
+    float cf[D], cb[D], f[D], b[D];
+    const float* pr = prior + (shared_model ? 0 : (size_t)seq * D);
+#pragma unroll
+    for (int j = 0; j < D; ++j) {
+        cf[j] = S::is_max_plus ? logf(pr[j]) : pr[j];
+        cb[j] = S::one();
+    }
+    block_exchange<S, D, BWD>(P, cf, cb, f, b, wagg);
+    float* sfin = fin + (size_t)seq * tps * D;
+    for (int r = 0; r < R; ++r) {
+        const int tile = t0 + r;
+        if (tile < tps) {
+#pragma unroll
+            for (int j = 0; j < D; ++j) sfin[(size_t)tile * D + j] = f[j];
+            float M[D * D], g[D];
+#pragma unroll
+            for (int e = 0; e < D * D; ++e) M[e] = sagg[(size_t)tile * D * D + e];
+            vec_mat<S, D>(f, M, g);
+            renorm<S, D>(g);   // the prior itself is handed over unscaled; what follows it is rescaled
+#pragma unroll
+            for (int j = 0; j < D; ++j) f[j] = g[j];
+        }
+    }
+    if constexpr (BWD) {
+        float* sbout = bout + (size_t)seq * tps * D;
+        for (int r = R - 1; r >= 0; --r) {
+            const int tile = t0 + r;
+            if (tile < tps) {
+#pragma unroll
+                for (int j = 0; j < D; ++j) sbout[(size_t)tile * D + j] = b[j];
+                float M[D * D], g[D];
+#pragma unroll
+                for (int e = 0; e < D * D; ++e) M[e] = sagg[(size_t)tile * D * D + e];
+                mat_vec<S, D>(M, b, g);
+                renorm<S, D>(g);
+#pragma unroll
+                for (int j = 0; j < D; ++j) b[j] = g[j];
+            }
+        }
+    }
+}
+
+// Lane-level smoother work shared by both plans: forward scan, reversed scan and marginals
+// inside the lane's chunk; returns the chunk-local log evidence.
+template <int D, bool WRITE_FILT>
+HMM_DEV double smooth_chunk(float* row, int n, bool first, const float (&Am)[D * D], float (&f)[D], float (&b)[D],
+                            double msum, float* __restrict__ filt_dst) {
+    using C = SmallCfg<D>;
+    float F[C::L][D];
+    if (!first) {   // the prior is used as given; every other carry is rescaled to sum to one
+        const float inv = 1.0f / sum_of(f);
+#pragma unroll
+        for (int j = 0; j < D; ++j) f[j] *= inv;
+    }
+    double delta;
+    if (n == C::L) {
+        delta = sp_forward_impl<D, WRITE_FILT, true>(row, n, first, Am, f, F, msum, filt_dst);
+        sp_backward_impl<D, true>(row, n, Am, b, F);
+    } else {
+        delta = sp_forward_impl<D, WRITE_FILT, false>(row, n, first, Am, f, F, msum, filt_dst);
+        sp_backward_impl<D, false>(row, n, Am, b, F);
+    }
+    return delta;
+}
+
+// Kernel 3 (smoother): forward scan, reversed scan and marginals inside a tile
+template <int D, bool WRITE_FILT>
+__global__ __launch_bounds__(256) void sd_smooth_apply_kernel(const float* __restrict__ A,
+                                                              const float* __restrict__ ll, long long T, int tps,
+                                                              int shared_model, const float* __restrict__ fin_g,
+                                                              const float* __restrict__ bout_g,
+                                                              float* __restrict__ marg, float* __restrict__ filt,
+                                                              double* __restrict__ part) {
+    using C = SmallCfg<D>;
+    using S = SumProd;
+    __shared__ float lds[C::LDS_FLOATS];
+    __shared__ float wagg[C::NW * D * D];
+    __shared__ double dsum[C::NW];
+    const TileCoord tc = tile_coord<D>(T, tps);
+    load_tile<D>(ll + tc.base * D, tc.nvalid, lds);
+    float Am[D * D];
+    load_model<S, D>(A + (shared_model ? 0 : (size_t)tc.seq * D * D), Am);
+    float cf[D], cb[D];
+#pragma unroll
+    for (int j = 0; j < D; ++j) {
+        cf[j] = fin_g[(size_t)blockIdx.x * D + j];
+        cb[j] = bout_g[(size_t)blockIdx.x * D + j];
+    }
+    __syncthreads();
+    float* row = lds + threadIdx.x * C::STRIDE;
+    const int n = min(max(tc.nvalid - (int)threadIdx.x * C::L, 0), C::L);
+    const bool first = tc.tile == 0 && threadIdx.x == 0;
+    float P[D * D];
+    double msum;
+    chunk_aggregate<S, D, true>(row, n, first, Am, P, msum);
+    float f[D], b[D];
+    block_exchange<S, D, true>(P, cf, cb, f, b, wagg);
+    float* fdst = WRITE_FILT ? filt + (tc.base + (long long)threadIdx.x * C::L) * D : nullptr;
+    const double delta = smooth_chunk<D, WRITE_FILT>(row, n, first, Am, f, b, msum, fdst);
+    const double tile_delta = block_sum(delta, dsum);
+    if (threadIdx.x == 0) part[blockIdx.x] = tile_delta;
+    __syncthreads();
+    store_tile<D>(marg + tc.base * D, tc.nvalid, lds);
+}
+
+// Kernel 4: out[seq] = ordered sum of the tile partials of one sequence.
+template <int D>
+__global__ __launch_bounds__(256) void sd_finalize_kernel(const double* __restrict__ part, int tps,
+                                                          double* __restrict__ out) {
+    __shared__ double dsum[4];
+    const int seq = blockIdx.x;
+    double acc = 0.0;
+    for (int t = threadIdx.x; t < tps; t += blockDim.x) acc += part[(size_t)seq * tps + t];
+    const double s = block_sum(acc, dsum);
+    if (threadIdx.x == 0) out[seq] = s;
+}
+
+// Lane-level Viterbi forward work shared by both plans.  Returns the offsets removed; h receives
+// the chunk map, xs the final state if this lane holds the sequence's last step.
+template <int D>
+HMM_DEV double viterbi_chunk(const float* row, int n, bool first, bool last, const float (&Am)[D * D], float (&v)[D],
+                             uint32_t (&bp)[SmallCfg<D>::W], uint32_t& h, uint32_t& xs) {
+    using C = SmallCfg<D>;
+    if (!first) renorm<MaxPlus, D>(v);   // the log prior is used as given; other carries start at max 0
+    double osum;
+    if (n == C::L) osum = mp_forward_impl<D, true>(row, n, first, Am, v, bp);
+    else osum = mp_forward_impl<D, false>(row, n, first, Am, v, bp);
+    h = chunk_map<D>(bp, n);
+    xs = 0u;
+    if (last) {   // x*_T = argmax V_T: every later state maps to h(x*_T)
+        xs = argmax_state<D>(v);
+        h = map_constant<D>(map_apply<D>(h, xs));
+    }
+    return n > 0 ? osum : 0.0;
+}
+
+// Kernel V3: forward max-plus scan inside the tile with back-pointers, each lane's chunk map,
+// the tile's map, and the chunk-local log-probability.
+template <int D>
+__global__ __launch_bounds__(256) void sd_viterbi_forward_kernel(const float* __restrict__ A,
+                                                                 const float* __restrict__ ll, long long T,
+                                                                 int tps, int shared_model,
+                                                                 const float* __restrict__ vin_g,
+                                                                 uint32_t* __restrict__ bp_g,
+                                                                 uint32_t* __restrict__ cmap_g,
+                                                                 uint32_t* __restrict__ tmap_g,
+                                                                 double* __restrict__ part) {
+    using C = SmallCfg<D>;
+    using S = MaxPlus;
+    __shared__ float lds[C::LDS_FLOATS];
+    __shared__ float wagg[C::NW * D * D];
+    __shared__ double dsum[C::NW];
+    __shared__ uint32_t wmaps[C::NW];
+    const TileCoord tc = tile_coord<D>(T, tps);
+    load_tile<D>(ll + tc.base * D, tc.nvalid, lds);
+    float Am[D * D];
+    load_model<S, D>(A + (shared_model ? 0 : (size_t)tc.seq * D * D), Am);
+    float cf[D];
+#pragma unroll
+    for (int j = 0; j < D; ++j) cf[j] = vin_g[(size_t)blockIdx.x * D + j];
+    __syncthreads();
+    float* row = lds + threadIdx.x * C::STRIDE;
+    const int n = min(max(tc.nvalid - (int)threadIdx.x * C::L, 0), C::L);
+    const bool first = tc.tile == 0 && threadIdx.x == 0;
+    const bool last = (tc.tile == tps - 1) && n > 0 && ((int)threadIdx.x * C::L + n == tc.nvalid);
+    float P[D * D];
+    double msum;
+    chunk_aggregate<S, D, false>(row, n, first, Am, P, msum);
+    float v[D], unused[D];
+    block_exchange<S, D, false>(P, cf, cf, v, unused, wagg);
+    uint32_t bp[C::W], h, xs;
+    const double osum = viterbi_chunk<D>(row, n, first, last, Am, v, bp, h, xs);
+    const double tile_delta = block_sum(osum, dsum);
+    if (threadIdx.x == 0) part[blockIdx.x] = tile_delta;
+    const size_t gl = (size_t)blockIdx.x * C::NT + threadIdx.x;
+#pragma unroll
+    for (int w = 0; w < C::W; ++w) bp_g[gl * C::W + w] = bp[w];
+    cmap_g[gl] = last ? (h | MAP_FINAL_FLAG | (xs << MAP_FINAL_SHIFT)) : h;
+    uint32_t excl;
+    const uint32_t total = block_map_suffix<D>(h, excl, wmaps);
+    if (threadIdx.x == 0) tmap_g[blockIdx.x] = total;
+}
+
+// Kernel V4: state at the last step of every tile, by composing tile maps right to left, and the
+// sequence's log-probability.  One workgroup per sequence.
+template <int D>
+__global__ __launch_bounds__(256) void sd_viterbi_suffix_kernel(const uint32_t* __restrict__ tmap_g, int tps,
+                                                                uint32_t* __restrict__ xend_g,
+                                                                const double* __restrict__ part,
+                                                                double* __restrict__ logprob) {
+    using C = SmallCfg<D>;
+    __shared__ uint32_t wmaps[C::NW];
+    __shared__ double dsum[C::NW];
+    const int seq = blockIdx.x;
+    const int R = (tps + C::NT - 1) / C::NT;
+    const int t0 = threadIdx.x * R;
+    const uint32_t* sm = tmap_g + (size_t)seq * tps;
+    uint32_t g = map_identity<D>();
+    for (int r = 0; r < R; ++r) {
+        const int tile = t0 + r;
+        if (tile < tps) g = map_compose<D>(g, sm[tile]);
+    }
+    uint32_t excl;
+    block_map_suffix<D>(g, excl, wmaps);
+    uint32_t x = map_apply<D>(excl, 0u);   // the last tile's map is constant, so the seed is immaterial
+    for (int r = R - 1; r >= 0; --r) {
+        const int tile = t0 + r;
+        if (tile < tps) {
+            xend_g[(size_t)seq * tps + tile] = x;
+            x = map_apply<D>(sm[tile], x);
+        }
+    }
+    double acc = 0.0;
+    for (int t = threadIdx.x; t < tps; t += blockDim.x) acc += part[(size_t)seq * tps + t];
+    const double s = block_sum(acc, dsum);
+    if (threadIdx.x == 0) logprob[seq] = s;
+}
+
+// Kernel V5: walk the back-pointers inside each lane's chunk and write the path.
+template <int D>
+__global__ __launch_bounds__(256) void sd_viterbi_path_kernel(long long T, int tps,
+                                                              const uint32_t* __restrict__ bp_g,
+                                                              const uint32_t* __restrict__ cmap_g,
+                                                              const uint32_t* __restrict__ xend_g,
+                                                              int32_t* __restrict__ path) {
+    using C = SmallCfg<D>;
+    __shared__ int32_t stage[C::NT * C::PSTRIDE];
+    __shared__ uint32_t wmaps[C::NW];
+    const TileCoord tc = tile_coord<D>(T, tps);
+    const int n = min(max(tc.nvalid - (int)threadIdx.x * C::L, 0), C::L);
+    const bool first = tc.tile == 0 && threadIdx.x == 0;
+    const size_t gl = (size_t)blockIdx.x * C::NT + threadIdx.x;
+    uint32_t bp[C::W];
+#pragma unroll
+    for (int w = 0; w < C::W; ++w) bp[w] = bp_g[gl * C::W + w];
+    const uint32_t stored = cmap_g[gl];
+    uint32_t excl;
+    block_map_suffix<D>(stored & MAP_BODY, excl, wmaps);
+    uint32_t x = map_apply<D>(excl, xend_g[blockIdx.x]);
+    if (stored & MAP_FINAL_FLAG) x = (stored >> MAP_FINAL_SHIFT) & C::MASK;
+    walk_chunk<D>(bp, n, first, x, stage + threadIdx.x * C::PSTRIDE);
+    __syncthreads();
+    store_path_tile<D>(path + tc.base, tc.nvalid, stage);
+}
+
+// =============================================================================================
+// Single-launch plan (all tiles co-resident)
+// =============================================================================================
+
+// Clears the arrival counters of a call; launched on the same stream right before the fused kernel.
+template <int D>
+__global__ void sd_clear_kernel(uint32_t* __restrict__ p, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0u;
+}
+
+struct FusedWs {
+    float* agg;        // [tiles][D*D]  tile aggregates
+    double* part;      // [tiles]       tile-local log evidence / log-probability
+    uint32_t* tmap;    // [tiles]       tile back-pointer maps (Viterbi)
+    uint32_t* count1;  // [batch]       tiles of the sequence whose aggregate is published
+    uint32_t* count2;  // [batch]       tiles of the sequence whose part (and tmap) is published
+    uint32_t* err;     // [1]           set if a bounded wait ran out
+};
+
+// Publish this tile's aggregate, gather the aggregates of every tile of the sequence, and return
+// the vectors entering this tile: cf = forward potential before its first step, cb = backward
+// potential at its last step.  Lane t of the workgroup holds tile t of the sequence (tps <= NT).
+template <class S, int D, bool BWD>
+HMM_DEV void grid_exchange(const TileCoord& tc, int tps, const float* wagg, const float* __restrict__ prior,
+                           const FusedWs& ws, float* wagg2, float* cin_lds, float (&cf)[D], float (&cb)[D]) {
+    const int tile0 = blockIdx.x - tc.tile;   // first tile of this sequence
+    __shared__ int ok_lds;
+    if (threadIdx.x == 0) {
+        float X[D * D];
+        block_total<S, D>(wagg, X);
+#pragma unroll
+        for (int e = 0; e < D * D; ++e) coherent_store(ws.agg + (size_t)blockIdx.x * D * D + e, X[e]);
+        stores_done();
+        counter_arrive(ws.count1 + tc.seq);
+        HMM_STAMP(4);
+        const bool ok = counter_wait(ws.count1 + tc.seq, (uint32_t)tps);
+        if (!ok) atomicOr(ws.err, 1u);
+        ok_lds = ok ? 1 : 0;
+    }
+    __syncthreads();
+    loads_after_poll();
+    HMM_STAMP(5);
+    float M[D * D];
+    mat_identity<S, D>(M);
+    if ((int)threadIdx.x < tps && ok_lds) {
+#pragma unroll
+        for (int e = 0; e < D * D; ++e) M[e] = coherent_load(ws.agg + (size_t)(tile0 + threadIdx.x) * D * D + e);
+    }
+    float pf[D], pb[D], f[D], b[D];
+#pragma unroll
+    for (int j = 0; j < D; ++j) {
+        pf[j] = S::is_max_plus ? logf(prior[j]) : prior[j];
+        pb[j] = S::one();
+    }
+    block_exchange<S, D, BWD>(M, pf, pb, f, b, wagg2);
+    if ((int)threadIdx.x == tc.tile) {
+#pragma unroll
+        for (int j = 0; j < D; ++j) {
+            cin_lds[j] = f[j];
+            if constexpr (BWD) cin_lds[D + j] = b[j];
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < D; ++j) {
+        cf[j] = cin_lds[j];
+        cb[j] = BWD ? cin_lds[D + j] : S::one();
+    }
+}
+
+// out[seq] = ordered sum of the sequence's tile partials; run by the workgroup of tile 0 after
+// every tile of the sequence has arrived at count2.
+HMM_DEV void grid_sum_parts(int tile0, int tps, const FusedWs& ws, double* dsum, double* __restrict__ out, int seq,
+                            bool already_waited) {
+    __shared__ int ok2_lds;
+    if (threadIdx.x == 0) {
+        const bool ok = already_waited || counter_wait(ws.count2 + seq, (uint32_t)tps);
+        if (!ok) atomicOr(ws.err, 1u);
+        ok2_lds = ok ? 1 : 0;
+    }
+    __syncthreads();
+    loads_after_poll();
+    double acc = 0.0;
+    if ((int)threadIdx.x < tps) acc = ok2_lds ? coherent_load(ws.part + tile0 + threadIdx.x) : __builtin_nan("");
+    const double s = block_sum(acc, dsum);
+    if (threadIdx.x == 0) out[seq] = s;
+}
+
+template <int D, bool WRITE_FILT>
+__global__ __launch_bounds__(256) void sd_smooth_fused_kernel(const float* __restrict__ prior,
+                                                              const float* __restrict__ A,
+                                                              const float* __restrict__ ll, long long T, int tps,
+                                                              int shared_model, float* __restrict__ marg,
+                                                              float* __restrict__ filt,
+                                                              double* __restrict__ loglik_out, FusedWs ws) {
+    using C = SmallCfg<D>;
+    using S = SumProd;
+    __shared__ float lds[C::LDS_FLOATS];
+    __shared__ float wagg[C::NW * D * D];
+    __shared__ float wagg2[C::NW * D * D];
+    __shared__ float cin_lds[2 * D];
+    __shared__ double dsum[C::NW];
+    HMM_STAMP(0);
+#ifdef HMM_PHASE_STAMPS
+    if ((threadIdx.x & 63) == 0 && blockIdx.x < 256) {
+        g_stamps[(blockIdx.x * 4 + (threadIdx.x >> 6)) * 16 + 12] = __builtin_amdgcn_s_getreg(63492);   // HW_ID
+        g_stamps[(blockIdx.x * 4 + (threadIdx.x >> 6)) * 16 + 13] = __builtin_amdgcn_s_getreg(63508);   // XCC_ID
+    }
+#endif
+    const TileCoord tc = tile_coord<D>(T, tps);
+    load_tile<D>(ll + tc.base * D, tc.nvalid, lds);
+    float Am[D * D];
+    load_model<S, D>(A + (shared_model ? 0 : (size_t)tc.seq * D * D), Am);
+    __syncthreads();
+    HMM_STAMP(1);
+    float* row = lds + threadIdx.x * C::STRIDE;
+    const int n = min(max(tc.nvalid - (int)threadIdx.x * C::L, 0), C::L);
+    const bool first = tc.tile == 0 && threadIdx.x == 0;
+    float P[D * D], Q[D * D], R[D * D];
+    double msum;
+    chunk_aggregate<S, D, true>(row, n, first, Am, P, msum);
+    HMM_STAMP(2);
+    block_prefix<S, D>(P, Q, wagg);
+    __syncthreads();
+    HMM_STAMP(3);
+    float cf[D], cb[D];
+    grid_exchange<S, D, true>(tc, tps, wagg, prior + (shared_model ? 0 : (size_t)tc.seq * D), ws, wagg2, cin_lds, cf,
+                              cb);
+    HMM_STAMP(6);
+#pragma unroll
+    for (int e = 0; e < D * D; ++e) R[e] = P[e];
+    wave_scan_suffix<S, D>(R);
+    float f[D], b[D];
+    carry_forward<S, D>(Q, wagg, cf, f);
+    carry_backward<S, D>(R, wagg, cb, b);
+    HMM_STAMP(7);
+    float* fdst = WRITE_FILT ? filt + (tc.base + (long long)threadIdx.x * C::L) * D : nullptr;
+    const double delta = smooth_chunk<D, WRITE_FILT>(row, n, first, Am, f, b, msum, fdst);
+    HMM_STAMP(8);
+    const double tile_delta = block_sum(delta, dsum);   // contains a barrier: all marginals are in LDS
+    if (threadIdx.x == 0) {
+        coherent_store(ws.part + blockIdx.x, tile_delta);
+        stores_done();
+        counter_arrive(ws.count2 + tc.seq);
+    }
+    HMM_STAMP(9);
+    store_tile<D>(marg + tc.base * D, tc.nvalid, lds);
+    HMM_STAMP(10);
+    if (tc.tile == 0) grid_sum_parts(blockIdx.x, tps, ws, dsum, loglik_out, tc.seq, false);
+    HMM_STAMP(11);
+}
+
+template <int D>
+__global__ __launch_bounds__(256) void sd_viterbi_fused_kernel(const float* __restrict__ prior,
+                                                               const float* __restrict__ A,
+                                                               const float* __restrict__ ll, long long T, int tps,
+                                                               int shared_model, int32_t* __restrict__ path,
+                                                               double* __restrict__ logprob_out, FusedWs ws) {
+    using C = SmallCfg<D>;
+    using S = MaxPlus;
+    __shared__ float lds[C::LDS_FLOATS];
+    __shared__ float wagg[C::NW * D * D];
+    __shared__ float wagg2[C::NW * D * D];
+    __shared__ float cin_lds[2 * D];
+    __shared__ double dsum[C::NW];
+    __shared__ uint32_t wmaps[C::NW];
+    __shared__ uint32_t wmaps2[C::NW];
+    __shared__ uint32_t xend_lds;
+    const TileCoord tc = tile_coord<D>(T, tps);
+    const int tile0 = blockIdx.x - tc.tile;
+    load_tile<D>(ll + tc.base * D, tc.nvalid, lds);
+    float Am[D * D];
+    load_model<S, D>(A + (shared_model ? 0 : (size_t)tc.seq * D * D), Am);
+    __syncthreads();
+    float* row = lds + threadIdx.x * C::STRIDE;
+    const int n = min(max(tc.nvalid - (int)threadIdx.x * C::L, 0), C::L);
+    const bool first = tc.tile == 0 && threadIdx.x == 0;
+    const bool last = (tc.tile == tps - 1) && n > 0 && ((int)threadIdx.x * C::L + n == tc.nvalid);
+    float P[D * D], Q[D * D];
+    double msum;
+    chunk_aggregate<S, D, false>(row, n, first, Am, P, msum);
+    block_prefix<S, D>(P, Q, wagg);
+    __syncthreads();
+    float cf[D], cb[D];
+    grid_exchange<S, D, false>(tc, tps, wagg, prior + (shared_model ? 0 : (size_t)tc.seq * D), ws, wagg2, cin_lds,
+                               cf, cb);
+    float v[D];
+    carry_forward<S, D>(Q, wagg, cf, v);
+    uint32_t bp[C::W], h, xs;
+    const double osum = viterbi_chunk<D>(row, n, first, last, Am, v, bp, h, xs);
+    const double tile_delta = block_sum(osum, dsum);
+    uint32_t excl;
+    const uint32_t total = block_map_suffix<D>(h, excl, wmaps);
+    __shared__ int ok2_lds;
+    if (threadIdx.x == 0) {
+        coherent_store(ws.part + blockIdx.x, tile_delta);
+        coherent_store(ws.tmap + blockIdx.x, total);
+        stores_done();
+        counter_arrive(ws.count2 + tc.seq);
+        const bool ok = counter_wait(ws.count2 + tc.seq, (uint32_t)tps);
+        if (!ok) atomicOr(ws.err, 1u);
+        ok2_lds = ok ? 1 : 0;
+    }
+    __syncthreads();
+    loads_after_poll();
+    // the tile maps of the sequence; state at this tile's last step = maps of later tiles composed
+    uint32_t tm = map_identity<D>();
+    if ((int)threadIdx.x < tps && ok2_lds) tm = coherent_load(ws.tmap + tile0 + threadIdx.x);
+    uint32_t texcl;
+    block_map_suffix<D>(tm, texcl, wmaps2);
+    if ((int)threadIdx.x == tc.tile) xend_lds = map_apply<D>(texcl, 0u);   // last tile's map is constant
+    __syncthreads();
+    uint32_t x = map_apply<D>(excl, xend_lds);
+    if (last) x = xs;
+    int32_t* stage = reinterpret_cast<int32_t*>(lds);   // the log-likelihood tile is no longer needed
+    __syncthreads();
+    walk_chunk<D>(bp, n, first, x, stage + threadIdx.x * C::PSTRIDE);
+    __syncthreads();
+    store_path_tile<D>(path + tc.base, tc.nvalid, stage);
+    if (tc.tile == 0) grid_sum_parts(blockIdx.x, tps, ws, dsum, logprob_out, tc.seq, true);
+}
+
+// =============================================================================================
+// Host side
+// =============================================================================================
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+template <int D>
+static long long tiles_per_seq(long long T) {
+    return (T + SmallCfg<D>::TILE - 1) / SmallCfg<D>::TILE;
+}
+
+struct SmoothWs { size_t agg, fin, bout, part, flags, total; };
+struct ViterbiWs { size_t agg, vin, bp, cmap, tmap, xend, part, flags, total; };
+
+template <int D>
+static SmoothWs smooth_ws(long long T, int batch) {
+    const size_t nt = (size_t)tiles_per_seq<D>(T) * batch;
+    SmoothWs w;
+    size_t o = 0;
+    w.agg = o;   o = align_up(o + nt * D * D * sizeof(float), 256);
+    w.fin = o;   o = align_up(o + nt * D * sizeof(float), 256);
+    w.bout = o;  o = align_up(o + nt * D * sizeof(float), 256);
+    w.part = o;  o = align_up(o + nt * sizeof(double), 256);
+    w.flags = o; o = align_up(o + (2 * (size_t)batch + 1) * sizeof(uint32_t), 256);
+    w.total = o;
+    return w;
+}
+
+template <int D>
+static ViterbiWs viterbi_ws(long long T, int batch) {
+    using C = SmallCfg<D>;
+    const size_t nt = (size_t)tiles_per_seq<D>(T) * batch;
+    ViterbiWs w;
+    size_t o = 0;
+    w.agg = o;   o = align_up(o + nt * D * D * sizeof(float), 256);
+    w.vin = o;   o = align_up(o + nt * D * sizeof(float), 256);
+    w.bp = o;    o = align_up(o + nt * C::NT * C::W * sizeof(uint32_t), 256);
+    w.cmap = o;  o = align_up(o + nt * C::NT * sizeof(uint32_t), 256);
+    w.tmap = o;  o = align_up(o + nt * sizeof(uint32_t), 256);
+    w.xend = o;  o = align_up(o + nt * sizeof(uint32_t), 256);
+    w.part = o;  o = align_up(o + nt * sizeof(double), 256);
+    w.flags = o; o = align_up(o + (2 * (size_t)batch + 1) * sizeof(uint32_t), 256);
+    w.total = o;
+    return w;
+}
+
+// How many workgroups of `kernel` the current device holds resident at once (cached per kernel).
+template <int TAG, class K>
+static long long resident_capacity(K kernel) {
+    static long long cached = -1;
+    if (cached >= 0) return cached;
+    int dev = 0, ncu = 0, per_cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    if (hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, 256, 0) != hipSuccess) return 0;
+    cached = (long long)ncu * per_cu;
+    return cached;
+}
+
+static bool force_multi_launch() {
+    const char* e = getenv("HMMSCAN_PLAN");
+    return e != nullptr && e[0] == 'm';   // HMMSCAN_PLAN=multi forces the multi-launch plan
+}
+
+template <int D>
+int SmallD<D>::smooth(const SmallArgs& a, float* marg, float* filt, double* loglik_out) {
+    using C = SmallCfg<D>;
+    const long long tps = tiles_per_seq<D>(a.T);
+    const long long nt = tps * a.batch;
+    if (nt > 0x7fffffffLL) return 2;
+    const SmoothWs w = smooth_ws<D>(a.T, a.batch);
+    if (a.ws_bytes < w.total) return 3;
+    char* ws = static_cast<char*>(a.ws);
+    float* agg = reinterpret_cast<float*>(ws + w.agg);
+    float* fin = reinterpret_cast<float*>(ws + w.fin);
+    float* bout = reinterpret_cast<float*>(ws + w.bout);
+    double* part = reinterpret_cast<double*>(ws + w.part);
+    uint32_t* flags = reinterpret_cast<uint32_t*>(ws + w.flags);
+    hipStream_t st = a.stream;
+    const dim3 grid((unsigned)nt), block(C::NT);
+    const long long cap = filt ? resident_capacity<0>(sd_smooth_fused_kernel<D, true>)
+                               : resident_capacity<1>(sd_smooth_fused_kernel<D, false>);
+    if (!force_multi_launch() && tps <= C::NT && nt <= cap) {
+        FusedWs fw{agg, part, nullptr, flags, flags + a.batch, flags + 2 * a.batch};
+        const int nflags = 2 * a.batch + 1;
+        { KernelScope ks("sd_clear_sp", st); sd_clear_kernel<D><<<dim3((nflags + 255) / 256), dim3(256), 0, st>>>(flags, nflags); }
+        KernelScope ks("sd_smooth_fused", st);
+        if (filt)
+            sd_smooth_fused_kernel<D, true><<<grid, block, 0, st>>>(a.prior, a.A, a.ll, a.T, (int)tps, a.shared_model, marg, filt, loglik_out, fw);
+        else
+            sd_smooth_fused_kernel<D, false><<<grid, block, 0, st>>>(a.prior, a.A, a.ll, a.T, (int)tps, a.shared_model, marg, nullptr, loglik_out, fw);
+    } else {
+        { KernelScope ks("sd_reduce_sp", st); sd_reduce_kernel<SumProd, D><<<grid, block, 0, st>>>(a.A, a.ll, a.T, (int)tps, a.shared_model, agg); }
+        { KernelScope ks("sd_carry_sp", st); sd_carry_kernel<SumProd, D, true><<<dim3(a.batch), block, 0, st>>>(a.prior, (int)tps, a.shared_model, agg, fin, bout); }
+        {
+            KernelScope ks("sd_smooth_apply", st);
+            if (filt)
+                sd_smooth_apply_kernel<D, true><<<grid, block, 0, st>>>(a.A, a.ll, a.T, (int)tps, a.shared_model, fin, bout, marg, filt, part);
+            else
+                sd_smooth_apply_kernel<D, false><<<grid, block, 0, st>>>(a.A, a.ll, a.T, (int)tps, a.shared_model, fin, bout, marg, nullptr, part);
+        }
+        { KernelScope ks("sd_finalize", st); sd_finalize_kernel<D><<<dim3(a.batch), dim3(256), 0, st>>>(part, (int)tps, loglik_out); }
+    }
+    return hipGetLastError() == hipSuccess ? 0 : 4;
+}
+
+template <int D>
+int SmallD<D>::viterbi(const SmallArgs& a, int32_t* path, double* logprob_out) {
+    using C = SmallCfg<D>;
+    const long long tps = tiles_per_seq<D>(a.T);
+    const long long nt = tps * a.batch;
+    if (nt > 0x7fffffffLL) return 2;
+    const ViterbiWs w = viterbi_ws<D>(a.T, a.batch);
+    if (a.ws_bytes < w.total) return 3;
+    char* ws = static_cast<char*>(a.ws);
+    float* agg = reinterpret_cast<float*>(ws + w.agg);
+    float* vin = reinterpret_cast<float*>(ws + w.vin);
+    uint32_t* bp = reinterpret_cast<uint32_t*>(ws + w.bp);
+    uint32_t* cmap = reinterpret_cast<uint32_t*>(ws + w.cmap);
+    uint32_t* tmap = reinterpret_cast<uint32_t*>(ws + w.tmap);
+    uint32_t* xend = reinterpret_cast<uint32_t*>(ws + w.xend);
+    double* part = reinterpret_cast<double*>(ws + w.part);
+    uint32_t* flags = reinterpret_cast<uint32_t*>(ws + w.flags);
+    hipStream_t st = a.stream;
+    const dim3 grid((unsigned)nt), block(C::NT);
+    const long long cap = resident_capacity<2>(sd_viterbi_fused_kernel<D>);
+    if (!force_multi_launch() && tps <= C::NT && nt <= cap) {
+        FusedWs fw{agg, part, tmap, flags, flags + a.batch, flags + 2 * a.batch};
+        const int nflags = 2 * a.batch + 1;
+        { KernelScope ks("sd_clear_mp", st); sd_clear_kernel<D><<<dim3((nflags + 255) / 256), dim3(256), 0, st>>>(flags, nflags); }
+        KernelScope ks("sd_viterbi_fused", st);
+        sd_viterbi_fused_kernel<D><<<grid, block, 0, st>>>(a.prior, a.A, a.ll, a.T, (int)tps, a.shared_model, path, logprob_out, fw);
+    } else {
+        { KernelScope ks("sd_reduce_mp", st); sd_reduce_kernel<MaxPlus, D><<<grid, block, 0, st>>>(a.A, a.ll, a.T, (int)tps, a.shared_model, agg); }
+        { KernelScope ks("sd_carry_mp", st); sd_carry_kernel<MaxPlus, D, false><<<dim3(a.batch), block, 0, st>>>(a.prior, (int)tps, a.shared_model, agg, vin, nullptr); }
+        { KernelScope ks("sd_viterbi_forward", st); sd_viterbi_forward_kernel<D><<<grid, block, 0, st>>>(a.A, a.ll, a.T, (int)tps, a.shared_model, vin, bp, cmap, tmap, part); }
+        { KernelScope ks("sd_viterbi_suffix", st); sd_viterbi_suffix_kernel<D><<<dim3(a.batch), block, 0, st>>>(tmap, (int)tps, xend, part, logprob_out); }
+        { KernelScope ks("sd_viterbi_path", st); sd_viterbi_path_kernel<D><<<grid, block, 0, st>>>(a.T, (int)tps, bp, cmap, xend, path); }
+    }
+    return hipGetLastError() == hipSuccess ? 0 : 4;
+}
+
+template <int D>
+size_t SmallD<D>::smooth_ws_bytes(long long T, int batch) { return smooth_ws<D>(T, batch).total; }
+
+template <int D>
+size_t SmallD<D>::viterbi_ws_bytes(long long T, int batch) { return viterbi_ws<D>(T, batch).total; }
+
+template struct SmallD<HMM_SMALL_D>;
+
+#ifdef HMM_PHASE_STAMPS
+extern "C" int hmm_debug_read_stamps(unsigned long long* host_dst) {
+    return (int)hipMemcpyFromSymbol(host_dst, HIP_SYMBOL(g_stamps), sizeof(unsigned long long) * 1024 * 16);
+}
+#endif
+
+}  // namespace hmm

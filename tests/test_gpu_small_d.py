@@ -14,6 +14,14 @@ def gu():
     return gpu_util
 
 
+@pytest.fixture(autouse=True, params=["single", "multi"])
+def plan(request, monkeypatch):
+    """Every case runs under both launch plans: the single-launch one (tiles exchange carries through
+    flags) where the shape allows it, and the multi-launch one forced through HMMSCAN_PLAN."""
+    monkeypatch.setenv("HMMSCAN_PLAN", request.param)
+    return request.param
+
+
 def test_config1(gu):
     p = wl.config1()
     gu.check_smooth(p, want_filtered=True)
