@@ -170,8 +170,9 @@ HMM_DEV float emission(float (&ev)[D]) {
     } else {
         const float m = max_of(ev);
         const float ms = (m == -INFINITY) ? 0.0f : m;
+        const float c = -1.4426950408889634f * ms;          // exp(x - m) = exp2(x * log2(e) - m * log2(e))
 #pragma unroll
-        for (int j = 0; j < D; ++j) ev[j] = __expf(ev[j] - ms);
+        for (int j = 0; j < D; ++j) ev[j] = __builtin_amdgcn_exp2f(fmaf(ev[j], 1.4426950408889634f, c));
         return m;
     }
 }
@@ -203,7 +204,7 @@ HMM_DEV void chunk_aggregate_impl(float* row, int n, bool first, const float (&A
                                   double& msum) {
     using C = SmallCfg<D>;
     mat_identity<S, D>(P);
-    double ms = 0.0;
+    float ms = 0.0f;   // sum of at most L maxima: float is ample, the caller accumulates in double
 #pragma unroll
     for (int k = 0; k < C::L; ++k) {
         if (FULL || k < n) {
@@ -212,13 +213,24 @@ HMM_DEV void chunk_aggregate_impl(float* row, int n, bool first, const float (&A
             const float m = emission<S, D>(ev);
             if constexpr (STORE_E) {
                 lds_write_vec<D>(row + k * D, ev);
-                ms += (double)m;
+                ms += m;
             }
-            absorb<S, D>(P, Am, ev, k == 0 && first);
+            if (k == 0) {
+                // P is still the neutral element: P (op) psi = psi, no product needed
+#pragma unroll
+                for (int i = 0; i < D; ++i)
+#pragma unroll
+                    for (int j = 0; j < D; ++j) {
+                        const float a = first ? ((i == j) ? S::one() : S::zero()) : Am[i * D + j];
+                        P[i * D + j] = S::times(a, ev[j]);
+                    }
+            } else {
+                absorb<S, D>(P, Am, ev, false);
+            }
             if ((k & 3) == 3) renorm<S, D * D>(P);
         }
     }
-    msum = ms;
+    msum = (double)ms;
 }
 
 template <class S, int D, bool STORE_E>
@@ -662,41 +674,21 @@ HMM_DEV void store_path_tile(int32_t* __restrict__ dst, int nvalid, const int32_
 }
 
 // ---------------------------------------------------------------------------------------------
-// Arrival counters between co-resident workgroups (single-launch kernels).
+// Exchange between co-resident workgroups (single-launch kernels) through self-validating words.
 //
-// A producer writes its payload with agent-scope (write-through, cache-bypassing) stores, waits
-// until those stores have completed, then increments the sequence's arrival counter with an
-// agent-scope atomic.  One lane per consumer workgroup polls the counter; after the workgroup
-// barrier that follows, every lane reads payloads with agent-scope (cache-bypassing) loads.
-// No agent-scope release/acquire FENCE is used on purpose: on this multi-die part such a fence
-// writes back / invalidates the whole L2 of the die, which costs microseconds when earlier
-// kernels left it dirty; write-through stores plus a completed-store wait give the same
-// ordering for the few words exchanged here.
+// Before the kernel starts, every exchange slot in the workspace holds the all-ones bit pattern
+// (a NaN as float or double, an impossible back-pointer map).  A producer overwrites its slots
+// with agent-scope (write-through, cache-bypassing) stores of real values, none of which has
+// that pattern; consumers poll the slots with agent-scope (cache-bypassing) loads until no
+// sentinel is left.  Each 32/64-bit word is written by one store, so a consumer never sees a
+// torn word, and no ordering between different words is relied upon: there are no flags, no
+// fences (an agent-scope fence writes back / invalidates a whole L2 on this multi-die part) and
+// no read-modify-write atomics (a few hundred on one address serialise for microseconds).
 // The poll is bounded so that every wave terminates even if the workgroups were, against the
 // host's residency check, not all resident.
-constexpr int SPIN_LIMIT = 1 << 22;
-
-HMM_DEV void stores_done() {
-    // orders the payload stores before the counter increment: workgroup-scope release makes the
-    // compiler keep the order and emits the wait for outstanding vector-memory stores
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    __builtin_amdgcn_s_waitcnt(0);
-}
-
-HMM_DEV void counter_arrive(uint32_t* counter) {
-    __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
-HMM_DEV bool counter_wait(const uint32_t* counter, uint32_t target) {
-    for (int spin = 0; spin < SPIN_LIMIT; ++spin) {
-        if (__hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= target) return true;
-        __builtin_amdgcn_s_sleep(1);
-    }
-    return false;
-}
-
-// keeps later payload loads after the poll that allowed them
-HMM_DEV void loads_after_poll() { __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup"); }
+constexpr int SPIN_LIMIT = 1 << 20;
+constexpr uint32_t SENTINEL32 = 0xffffffffu;
+constexpr unsigned long long SENTINEL64 = 0xffffffffffffffffull;
 
 template <class T>
 HMM_DEV void coherent_store(T* p, T v) {
@@ -705,6 +697,12 @@ HMM_DEV void coherent_store(T* p, T v) {
 template <class T>
 HMM_DEV T coherent_load(const T* p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Bits of a float to publish: any NaN becomes the canonical quiet NaN, which is not the sentinel.
+HMM_DEV uint32_t publish_bits(float x) { return (x != x) ? 0x7fc00000u : __float_as_uint(x); }
+HMM_DEV unsigned long long publish_bits(double x) {
+    return (x != x) ? 0x7ff8000000000000ull : (unsigned long long)__double_as_longlong(x);
 }
 
 }  // namespace hmm

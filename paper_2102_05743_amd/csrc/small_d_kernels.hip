@@ -3,7 +3,7 @@
 //
 // Two launch plans compute the same thing with the same per-lane arithmetic:
 //   * single-launch ("fused"): every tile is one co-resident workgroup; tile aggregates (and, for
-//     Viterbi, tile back-pointer maps) are exchanged through flags in the workspace, so the
+//     Viterbi, tile back-pointer maps) are exchanged through the workspace, so the
 //     log-likelihoods are read from HBM once and nothing but the outputs is written back;
 //   * multi-launch: reduce -> carry -> apply (-> suffix -> path) kernels with no inter-workgroup
 //     waiting, for shapes with more tiles than the GPU can hold resident at once.
@@ -337,87 +337,186 @@ __global__ __launch_bounds__(256) void sd_viterbi_path_kernel(long long T, int t
 // Single-launch plan (all tiles co-resident)
 // =============================================================================================
 
-// Clears the arrival counters of a call; launched on the same stream right before the fused kernel.
+// Fills the exchange slots of a call with the sentinel pattern; launched on the same stream right
+// before the fused kernel.
 template <int D>
 __global__ void sd_clear_kernel(uint32_t* __restrict__ p, int n) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) p[i] = 0u;
+    if (i < n) p[i] = (i == n - 1) ? 0u : SENTINEL32;   // the last word is the error flag
 }
 
 struct FusedWs {
     float* agg;        // [tiles][D*D]  tile aggregates
     double* part;      // [tiles]       tile-local log evidence / log-probability
     uint32_t* tmap;    // [tiles]       tile back-pointer maps (Viterbi)
-    uint32_t* count1;  // [batch]       tiles of the sequence whose aggregate is published
-    uint32_t* count2;  // [batch]       tiles of the sequence whose part (and tmap) is published
     uint32_t* err;     // [1]           set if a bounded wait ran out
 };
 
-// Publish this tile's aggregate, gather the aggregates of every tile of the sequence, and return
-// the vectors entering this tile: cf = forward potential before its first step, cb = backward
-// potential at its last step.  Lane t of the workgroup holds tile t of the sequence (tps <= NT).
-template <class S, int D, bool BWD>
-HMM_DEV void grid_exchange(const TileCoord& tc, int tps, const float* wagg, const float* __restrict__ prior,
-                           const FusedWs& ws, float* wagg2, float* cin_lds, float (&cf)[D], float (&cb)[D]) {
-    const int tile0 = blockIdx.x - tc.tile;   // first tile of this sequence
-    __shared__ int ok_lds;
+// LDS scratch of the inter-tile exchange.  Staged aggregates are stored in pairs of tiles, each
+// pair padded by four floats so that 64 lanes reading one pair each do not collide on LDS banks.
+template <int D>
+struct GridLds {
+    static constexpr int PAIR = 2 * D * D;
+    static constexpr int PSTR = PAIR + 4;
+    float red[SmallCfg<D>::NW * D * D];               // per-wave reductions of tile aggregates
+    float aggs[(SmallCfg<D>::NT / 2) * PSTR];         // the sequence's tile aggregates, staged
+};
+
+// Lane 0 publishes this tile's aggregate (the product of the wave totals in wagg).
+template <class S, int D>
+HMM_DEV void grid_publish(const float* wagg, const FusedWs& ws) {
     if (threadIdx.x == 0) {
         float X[D * D];
         block_total<S, D>(wagg, X);
+        float* dst = ws.agg + (size_t)blockIdx.x * D * D;
+        if ((reinterpret_cast<uintptr_t>(dst) & 7u) == 0) {
 #pragma unroll
-        for (int e = 0; e < D * D; ++e) coherent_store(ws.agg + (size_t)blockIdx.x * D * D + e, X[e]);
-        stores_done();
-        counter_arrive(ws.count1 + tc.seq);
-        HMM_STAMP(4);
-        const bool ok = counter_wait(ws.count1 + tc.seq, (uint32_t)tps);
-        if (!ok) atomicOr(ws.err, 1u);
-        ok_lds = ok ? 1 : 0;
-    }
-    __syncthreads();
-    loads_after_poll();
-    HMM_STAMP(5);
-    float M[D * D];
-    mat_identity<S, D>(M);
-    if ((int)threadIdx.x < tps && ok_lds) {
+            for (int e = 0; e + 1 < D * D; e += 2)
+                coherent_store(reinterpret_cast<unsigned long long*>(dst + e),
+                               (unsigned long long)publish_bits(X[e]) |
+                                   ((unsigned long long)publish_bits(X[e + 1]) << 32));
+            if constexpr ((D * D) % 2 == 1)
+                coherent_store(reinterpret_cast<uint32_t*>(dst + D * D - 1), publish_bits(X[D * D - 1]));
+        } else {
 #pragma unroll
-        for (int e = 0; e < D * D; ++e) M[e] = coherent_load(ws.agg + (size_t)(tile0 + threadIdx.x) * D * D + e);
-    }
-    float pf[D], pb[D], f[D], b[D];
-#pragma unroll
-    for (int j = 0; j < D; ++j) {
-        pf[j] = S::is_max_plus ? logf(prior[j]) : prior[j];
-        pb[j] = S::one();
-    }
-    block_exchange<S, D, BWD>(M, pf, pb, f, b, wagg2);
-    if ((int)threadIdx.x == tc.tile) {
-#pragma unroll
-        for (int j = 0; j < D; ++j) {
-            cin_lds[j] = f[j];
-            if constexpr (BWD) cin_lds[D + j] = b[j];
+            for (int e = 0; e < D * D; ++e) coherent_store(reinterpret_cast<uint32_t*>(dst + e), publish_bits(X[e]));
         }
-    }
-    __syncthreads();
-#pragma unroll
-    for (int j = 0; j < D; ++j) {
-        cf[j] = cin_lds[j];
-        cb[j] = BWD ? cin_lds[D + j] : S::one();
     }
 }
 
-// out[seq] = ordered sum of the sequence's tile partials; run by the workgroup of tile 0 after
-// every tile of the sequence has arrived at count2.
-HMM_DEV void grid_sum_parts(int tile0, int tps, const FusedWs& ws, double* dsum, double* __restrict__ out, int seq,
-                            bool already_waited) {
-    __shared__ int ok2_lds;
-    if (threadIdx.x == 0) {
-        const bool ok = already_waited || counter_wait(ws.count2 + seq, (uint32_t)tps);
-        if (!ok) atomicOr(ws.err, 1u);
-        ok2_lds = ok ? 1 : 0;
+// All lanes: poll n consecutive floats at `src` (slots written by other workgroups) until none
+// holds the sentinel, staging them into LDS in the padded pair layout.  Coalesced 8-byte loads
+// when the base is 8-byte aligned.  Returns false if the bounded wait ran out.
+template <int D>
+HMM_DEV bool gather_aggregates(const float* src, int n, float* dst_lds) {
+    using G = GridLds<D>;
+    const bool wide = (reinterpret_cast<uintptr_t>(src) & 7u) == 0;
+    for (int spin = 0; spin < SPIN_LIMIT; ++spin) {
+        bool valid = true;
+        if (wide) {
+            const unsigned long long* s2 = reinterpret_cast<const unsigned long long*>(src);
+            const int n2 = n >> 1;
+            for (int i = threadIdx.x; i < n2; i += blockDim.x) {
+                const unsigned long long w = coherent_load(s2 + i);
+                const uint32_t lo = (uint32_t)w, hi = (uint32_t)(w >> 32);
+                valid = valid && lo != SENTINEL32 && hi != SENTINEL32;
+                const int f = 2 * i;
+                const int d0 = (f / G::PAIR) * G::PSTR + f % G::PAIR;
+                const int d1 = ((f + 1) / G::PAIR) * G::PSTR + (f + 1) % G::PAIR;
+                dst_lds[d0] = __uint_as_float(lo);
+                dst_lds[d1] = __uint_as_float(hi);
+            }
+            if ((n & 1) && threadIdx.x == 0) {
+                const uint32_t w = coherent_load(reinterpret_cast<const uint32_t*>(src) + n - 1);
+                valid = valid && w != SENTINEL32;
+                dst_lds[((n - 1) / G::PAIR) * G::PSTR + (n - 1) % G::PAIR] = __uint_as_float(w);
+            }
+        } else {
+            for (int i = threadIdx.x; i < n; i += blockDim.x) {
+                const uint32_t w = coherent_load(reinterpret_cast<const uint32_t*>(src) + i);
+                valid = valid && w != SENTINEL32;
+                dst_lds[(i / G::PAIR) * G::PSTR + i % G::PAIR] = __uint_as_float(w);
+            }
+        }
+        if (__syncthreads_and(valid ? 1 : 0)) return true;
+        __builtin_amdgcn_s_sleep(1);
+    }
+    return false;
+}
+
+// Gather the aggregates of the sequence's tiles and return the vectors entering this tile:
+// cf = forward potential before its first step (prior (op) M_0 (op) ... (op) M_{c-1}),
+// cb = backward potential at its last step (M_{c+1} (op) ... (op) M_{tps-1} (op) ones).
+// The two ordered products are masked reductions over at most 2*128 tile slots: the first two
+// waves reduce the tiles before c, the last two the tiles after c (tps <= NT).
+template <class S, int D, bool BWD>
+HMM_DEV void grid_gather(const TileCoord& tc, int tps, const float* __restrict__ prior, const FusedWs& ws,
+                         GridLds<D>& gl, float (&cf)[D], float (&cb)[D]) {
+    using C = SmallCfg<D>;
+    using G = GridLds<D>;
+    static_assert(C::NW == 4, "the split below assumes four waves");
+    const int tile0 = blockIdx.x - tc.tile;   // first tile of this sequence
+    const bool ok = gather_aggregates<D>(ws.agg + (size_t)tile0 * D * D, tps * D * D, gl.aggs);
+    if (!ok && threadIdx.x == 0) atomicOr(ws.err, 1u);
+    HMM_STAMP(14);
+    const int wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const bool fwd_half = wave < 2;
+    if (fwd_half || BWD) {
+        const int u = (int)threadIdx.x & 127;             // pair index 0..127 inside the half
+        float Ma[D * D], Mb[D * D], X[D * D];
+        const int ta = 2 * u, tb = 2 * u + 1;
+        const bool use_a = ok && ta < tps && (fwd_half ? (ta < tc.tile) : (ta > tc.tile));
+        const bool use_b = ok && tb < tps && (fwd_half ? (tb < tc.tile) : (tb > tc.tile));
+        const float* pa = gl.aggs + u * G::PSTR;
+#pragma unroll
+        for (int i = 0; i < D; ++i)
+#pragma unroll
+            for (int j = 0; j < D; ++j) {
+                const float id = (i == j) ? S::one() : S::zero();
+                Ma[i * D + j] = use_a ? pa[i * D + j] : id;
+                Mb[i * D + j] = use_b ? pa[D * D + i * D + j] : id;
+            }
+        mat_mul<S, D>(Ma, Mb, X);
+        wave_scan_prefix<S, D>(X);                        // lane 63 ends with the wave's ordered product
+        if (lane == 63) {
+#pragma unroll
+            for (int e = 0; e < D * D; ++e) gl.red[wave * D * D + e] = X[e];
+        }
     }
     __syncthreads();
-    loads_after_poll();
+    HMM_STAMP(15);
+    float pr[D], v[D], r[D], Wm[D * D];
+#pragma unroll
+    for (int j = 0; j < D; ++j) v[j] = pr[j] = S::is_max_plus ? logf(prior[j]) : prior[j];
+#pragma unroll
+    for (int w = 0; w < 2; ++w) {
+#pragma unroll
+        for (int e = 0; e < D * D; ++e) Wm[e] = gl.red[w * D * D + e];
+        vec_mat<S, D>(v, Wm, r);
+        renorm<S, D>(r);
+#pragma unroll
+        for (int j = 0; j < D; ++j) v[j] = r[j];
+    }
+    // the first tile starts from the prior exactly as given (its scale is part of the evidence);
+    // every later tile's carry is scale-free
+#pragma unroll
+    for (int j = 0; j < D; ++j) cf[j] = (tc.tile == 0) ? pr[j] : v[j];
+#pragma unroll
+    for (int j = 0; j < D; ++j) cb[j] = S::one();
+    if constexpr (BWD) {
+#pragma unroll
+        for (int w = 3; w >= 2; --w) {
+#pragma unroll
+            for (int e = 0; e < D * D; ++e) Wm[e] = gl.red[w * D * D + e];
+            mat_vec<S, D>(Wm, cb, r);
+            renorm<S, D>(r);
+#pragma unroll
+            for (int j = 0; j < D; ++j) cb[j] = r[j];
+        }
+    }
+}
+
+// All lanes: poll the sequence's tile partials until all are published, then out[seq] = their
+// ordered sum.  Run by the workgroup of tile 0.
+HMM_DEV void grid_sum_parts(int tile0, int tps, const FusedWs& ws, double* dsum, double* __restrict__ out, int seq) {
     double acc = 0.0;
-    if ((int)threadIdx.x < tps) acc = ok2_lds ? coherent_load(ws.part + tile0 + threadIdx.x) : __builtin_nan("");
+    bool ok = false;
+    for (int spin = 0; spin < SPIN_LIMIT; ++spin) {
+        bool valid = true;
+        acc = 0.0;
+        if ((int)threadIdx.x < tps) {
+            const unsigned long long w = coherent_load(reinterpret_cast<const unsigned long long*>(ws.part) + tile0 + threadIdx.x);
+            valid = w != SENTINEL64;
+            acc = __longlong_as_double((long long)w);
+        }
+        if (__syncthreads_and(valid ? 1 : 0)) { ok = true; break; }
+        __builtin_amdgcn_s_sleep(1);
+    }
+    if (!ok) {
+        if (threadIdx.x == 0) atomicOr(ws.err, 1u);
+        acc = __builtin_nan("");
+    }
     const double s = block_sum(acc, dsum);
     if (threadIdx.x == 0) out[seq] = s;
 }
@@ -433,8 +532,7 @@ __global__ __launch_bounds__(256) void sd_smooth_fused_kernel(const float* __res
     using S = SumProd;
     __shared__ float lds[C::LDS_FLOATS];
     __shared__ float wagg[C::NW * D * D];
-    __shared__ float wagg2[C::NW * D * D];
-    __shared__ float cin_lds[2 * D];
+    __shared__ GridLds<D> gl;
     __shared__ double dsum[C::NW];
     HMM_STAMP(0);
 #ifdef HMM_PHASE_STAMPS
@@ -459,13 +557,15 @@ __global__ __launch_bounds__(256) void sd_smooth_fused_kernel(const float* __res
     block_prefix<S, D>(P, Q, wagg);
     __syncthreads();
     HMM_STAMP(3);
-    float cf[D], cb[D];
-    grid_exchange<S, D, true>(tc, tps, wagg, prior + (shared_model ? 0 : (size_t)tc.seq * D), ws, wagg2, cin_lds, cf,
-                              cb);
-    HMM_STAMP(6);
+    grid_publish<S, D>(wagg, ws);
+    HMM_STAMP(4);
+    // the suffix scan needs nothing from other tiles: it runs while their aggregates arrive
 #pragma unroll
     for (int e = 0; e < D * D; ++e) R[e] = P[e];
     wave_scan_suffix<S, D>(R);
+    float cf[D], cb[D];
+    grid_gather<S, D, true>(tc, tps, prior + (shared_model ? 0 : (size_t)tc.seq * D), ws, gl, cf, cb);
+    HMM_STAMP(6);
     float f[D], b[D];
     carry_forward<S, D>(Q, wagg, cf, f);
     carry_backward<S, D>(R, wagg, cb, b);
@@ -474,15 +574,12 @@ __global__ __launch_bounds__(256) void sd_smooth_fused_kernel(const float* __res
     const double delta = smooth_chunk<D, WRITE_FILT>(row, n, first, Am, f, b, msum, fdst);
     HMM_STAMP(8);
     const double tile_delta = block_sum(delta, dsum);   // contains a barrier: all marginals are in LDS
-    if (threadIdx.x == 0) {
-        coherent_store(ws.part + blockIdx.x, tile_delta);
-        stores_done();
-        counter_arrive(ws.count2 + tc.seq);
-    }
+    if (threadIdx.x == 0)
+        coherent_store(reinterpret_cast<unsigned long long*>(ws.part) + blockIdx.x, publish_bits(tile_delta));
     HMM_STAMP(9);
     store_tile<D>(marg + tc.base * D, tc.nvalid, lds);
     HMM_STAMP(10);
-    if (tc.tile == 0) grid_sum_parts(blockIdx.x, tps, ws, dsum, loglik_out, tc.seq, false);
+    if (tc.tile == 0) grid_sum_parts(blockIdx.x, tps, ws, dsum, loglik_out, tc.seq);
     HMM_STAMP(11);
 }
 
@@ -496,8 +593,7 @@ __global__ __launch_bounds__(256) void sd_viterbi_fused_kernel(const float* __re
     using S = MaxPlus;
     __shared__ float lds[C::LDS_FLOATS];
     __shared__ float wagg[C::NW * D * D];
-    __shared__ float wagg2[C::NW * D * D];
-    __shared__ float cin_lds[2 * D];
+    __shared__ GridLds<D> gl;
     __shared__ double dsum[C::NW];
     __shared__ uint32_t wmaps[C::NW];
     __shared__ uint32_t wmaps2[C::NW];
@@ -517,9 +613,9 @@ __global__ __launch_bounds__(256) void sd_viterbi_fused_kernel(const float* __re
     chunk_aggregate<S, D, false>(row, n, first, Am, P, msum);
     block_prefix<S, D>(P, Q, wagg);
     __syncthreads();
+    grid_publish<S, D>(wagg, ws);
     float cf[D], cb[D];
-    grid_exchange<S, D, false>(tc, tps, wagg, prior + (shared_model ? 0 : (size_t)tc.seq * D), ws, wagg2, cin_lds,
-                               cf, cb);
+    grid_gather<S, D, false>(tc, tps, prior + (shared_model ? 0 : (size_t)tc.seq * D), ws, gl, cf, cb);
     float v[D];
     carry_forward<S, D>(Q, wagg, cf, v);
     uint32_t bp[C::W], h, xs;
@@ -527,21 +623,26 @@ __global__ __launch_bounds__(256) void sd_viterbi_fused_kernel(const float* __re
     const double tile_delta = block_sum(osum, dsum);
     uint32_t excl;
     const uint32_t total = block_map_suffix<D>(h, excl, wmaps);
-    __shared__ int ok2_lds;
     if (threadIdx.x == 0) {
-        coherent_store(ws.part + blockIdx.x, tile_delta);
-        coherent_store(ws.tmap + blockIdx.x, total);
-        stores_done();
-        counter_arrive(ws.count2 + tc.seq);
-        const bool ok = counter_wait(ws.count2 + tc.seq, (uint32_t)tps);
-        if (!ok) atomicOr(ws.err, 1u);
-        ok2_lds = ok ? 1 : 0;
+        coherent_store(reinterpret_cast<unsigned long long*>(ws.part) + blockIdx.x, publish_bits(tile_delta));
+        coherent_store(ws.tmap + blockIdx.x, total);   // a map uses 24 bits: never the sentinel
     }
-    __syncthreads();
-    loads_after_poll();
     // the tile maps of the sequence; state at this tile's last step = maps of later tiles composed
     uint32_t tm = map_identity<D>();
-    if ((int)threadIdx.x < tps && ok2_lds) tm = coherent_load(ws.tmap + tile0 + threadIdx.x);
+    bool ok2 = false;
+    for (int spin = 0; spin < SPIN_LIMIT; ++spin) {
+        bool valid = true;
+        if ((int)threadIdx.x < tps) {
+            tm = coherent_load(ws.tmap + tile0 + threadIdx.x);
+            valid = tm != SENTINEL32;
+        }
+        if (__syncthreads_and(valid ? 1 : 0)) { ok2 = true; break; }
+        __builtin_amdgcn_s_sleep(1);
+    }
+    if (!ok2) {
+        if (threadIdx.x == 0) atomicOr(ws.err, 1u);
+        tm = map_identity<D>();
+    }
     uint32_t texcl;
     block_map_suffix<D>(tm, texcl, wmaps2);
     if ((int)threadIdx.x == tc.tile) xend_lds = map_apply<D>(texcl, 0u);   // last tile's map is constant
@@ -549,11 +650,10 @@ __global__ __launch_bounds__(256) void sd_viterbi_fused_kernel(const float* __re
     uint32_t x = map_apply<D>(excl, xend_lds);
     if (last) x = xs;
     int32_t* stage = reinterpret_cast<int32_t*>(lds);   // the log-likelihood tile is no longer needed
-    __syncthreads();
     walk_chunk<D>(bp, n, first, x, stage + threadIdx.x * C::PSTRIDE);
     __syncthreads();
     store_path_tile<D>(path + tc.base, tc.nvalid, stage);
-    if (tc.tile == 0) grid_sum_parts(blockIdx.x, tps, ws, dsum, logprob_out, tc.seq, true);
+    if (tc.tile == 0) grid_sum_parts(blockIdx.x, tps, ws, dsum, logprob_out, tc.seq);
 }
 
 // =============================================================================================
@@ -566,8 +666,22 @@ static long long tiles_per_seq(long long T) {
     return (T + SmallCfg<D>::TILE - 1) / SmallCfg<D>::TILE;
 }
 
-struct SmoothWs { size_t agg, fin, bout, part, flags, total; };
-struct ViterbiWs { size_t agg, vin, bp, cmap, tmap, xend, part, flags, total; };
+struct SmoothWs { size_t agg, fin, bout, part, xch, total; };
+struct ViterbiWs { size_t agg, vin, bp, cmap, tmap, xend, part, xch, total; };
+
+// Exchange region of the single-launch plan, in 32-bit words: [aggregates][parts][maps][error flag]
+struct XchLayout { size_t agg, part, tmap, err, words; };
+template <int D>
+static XchLayout xch_layout(size_t nt) {
+    XchLayout x;
+    size_t o = 0;
+    x.agg = o;  o += (nt * D * D + 1) / 2 * 2;   // keeps the doubles that follow 8-byte aligned
+    x.part = o; o += 2 * nt;
+    x.tmap = o; o += nt;
+    x.err = o;  o += 1;
+    x.words = o;
+    return x;
+}
 
 template <int D>
 static SmoothWs smooth_ws(long long T, int batch) {
@@ -578,7 +692,7 @@ static SmoothWs smooth_ws(long long T, int batch) {
     w.fin = o;   o = align_up(o + nt * D * sizeof(float), 256);
     w.bout = o;  o = align_up(o + nt * D * sizeof(float), 256);
     w.part = o;  o = align_up(o + nt * sizeof(double), 256);
-    w.flags = o; o = align_up(o + (2 * (size_t)batch + 1) * sizeof(uint32_t), 256);
+    w.xch = o;  o = align_up(o + xch_layout<D>(nt).words * sizeof(uint32_t), 256);
     w.total = o;
     return w;
 }
@@ -596,7 +710,7 @@ static ViterbiWs viterbi_ws(long long T, int batch) {
     w.tmap = o;  o = align_up(o + nt * sizeof(uint32_t), 256);
     w.xend = o;  o = align_up(o + nt * sizeof(uint32_t), 256);
     w.part = o;  o = align_up(o + nt * sizeof(double), 256);
-    w.flags = o; o = align_up(o + (2 * (size_t)batch + 1) * sizeof(uint32_t), 256);
+    w.xch = o;  o = align_up(o + xch_layout<D>(nt).words * sizeof(uint32_t), 256);
     w.total = o;
     return w;
 }
@@ -632,15 +746,17 @@ int SmallD<D>::smooth(const SmallArgs& a, float* marg, float* filt, double* logl
     float* fin = reinterpret_cast<float*>(ws + w.fin);
     float* bout = reinterpret_cast<float*>(ws + w.bout);
     double* part = reinterpret_cast<double*>(ws + w.part);
-    uint32_t* flags = reinterpret_cast<uint32_t*>(ws + w.flags);
+    uint32_t* xch = reinterpret_cast<uint32_t*>(ws + w.xch);
     hipStream_t st = a.stream;
     const dim3 grid((unsigned)nt), block(C::NT);
     const long long cap = filt ? resident_capacity<0>(sd_smooth_fused_kernel<D, true>)
                                : resident_capacity<1>(sd_smooth_fused_kernel<D, false>);
     if (!force_multi_launch() && tps <= C::NT && nt <= cap) {
-        FusedWs fw{agg, part, nullptr, flags, flags + a.batch, flags + 2 * a.batch};
-        const int nflags = 2 * a.batch + 1;
-        { KernelScope ks("sd_clear_sp", st); sd_clear_kernel<D><<<dim3((nflags + 255) / 256), dim3(256), 0, st>>>(flags, nflags); }
+        const XchLayout xl = xch_layout<D>((size_t)nt);
+        FusedWs fw{reinterpret_cast<float*>(xch + xl.agg), reinterpret_cast<double*>(xch + xl.part), xch + xl.tmap,
+                   xch + xl.err};
+        const int nwords = (int)xl.words;
+        { KernelScope ks("sd_clear_sp", st); sd_clear_kernel<D><<<dim3((nwords + 255) / 256), dim3(256), 0, st>>>(xch, nwords); }
         KernelScope ks("sd_smooth_fused", st);
         if (filt)
             sd_smooth_fused_kernel<D, true><<<grid, block, 0, st>>>(a.prior, a.A, a.ll, a.T, (int)tps, a.shared_model, marg, filt, loglik_out, fw);
@@ -677,14 +793,16 @@ int SmallD<D>::viterbi(const SmallArgs& a, int32_t* path, double* logprob_out) {
     uint32_t* tmap = reinterpret_cast<uint32_t*>(ws + w.tmap);
     uint32_t* xend = reinterpret_cast<uint32_t*>(ws + w.xend);
     double* part = reinterpret_cast<double*>(ws + w.part);
-    uint32_t* flags = reinterpret_cast<uint32_t*>(ws + w.flags);
+    uint32_t* xch = reinterpret_cast<uint32_t*>(ws + w.xch);
     hipStream_t st = a.stream;
     const dim3 grid((unsigned)nt), block(C::NT);
     const long long cap = resident_capacity<2>(sd_viterbi_fused_kernel<D>);
     if (!force_multi_launch() && tps <= C::NT && nt <= cap) {
-        FusedWs fw{agg, part, tmap, flags, flags + a.batch, flags + 2 * a.batch};
-        const int nflags = 2 * a.batch + 1;
-        { KernelScope ks("sd_clear_mp", st); sd_clear_kernel<D><<<dim3((nflags + 255) / 256), dim3(256), 0, st>>>(flags, nflags); }
+        const XchLayout xl = xch_layout<D>((size_t)nt);
+        FusedWs fw{reinterpret_cast<float*>(xch + xl.agg), reinterpret_cast<double*>(xch + xl.part), xch + xl.tmap,
+                   xch + xl.err};
+        const int nwords = (int)xl.words;
+        { KernelScope ks("sd_clear_mp", st); sd_clear_kernel<D><<<dim3((nwords + 255) / 256), dim3(256), 0, st>>>(xch, nwords); }
         KernelScope ks("sd_viterbi_fused", st);
         sd_viterbi_fused_kernel<D><<<grid, block, 0, st>>>(a.prior, a.A, a.ll, a.T, (int)tps, a.shared_model, path, logprob_out, fw);
     } else {
