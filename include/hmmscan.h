@@ -94,7 +94,8 @@ const char* hmm_status_string(hmm_status status);
 /*
  * Measurement aid (not part of the method): per-kernel timing with HIP events.
  * hmm_kernel_timing_enable(1) clears earlier records and makes every later kernel launch of the
- * library record one HIP event before and one after it on the caller's stream;
+ * library carry a start and a stop HIP event attached to that kernel's own dispatch on the
+ * caller's stream (hipExtLaunchKernel), so their difference is the kernel's execution time;
  * hmm_kernel_timing_enable(0) switches recording off and clears the records.
  * hmm_kernel_timing_count() waits for the recorded events and returns the number of distinct
  * kernels seen; hmm_kernel_timing_get(i, ...) returns, for the i-th of them, a static name, the

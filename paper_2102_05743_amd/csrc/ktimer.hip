@@ -55,17 +55,12 @@ void aggregate() {
 
 bool ktimer_enabled() { return g_on; }
 
-void ktimer_begin(const char* name, hipStream_t stream) {
+void ktimer_new_record(const char* name, hipEvent_t* start, hipEvent_t* stop) {
     Record r{name_id(name), take_event(), take_event()};
-    if (r.e0) (void)hipEventRecord(r.e0, stream);
     g_records.push_back(r);
     g_agg_valid = false;
-}
-
-void ktimer_end(hipStream_t stream) {
-    if (g_records.empty()) return;
-    Record& r = g_records.back();
-    if (r.e1) (void)hipEventRecord(r.e1, stream);
+    *start = r.e0;
+    *stop = r.e1;
 }
 
 }  // namespace hmm

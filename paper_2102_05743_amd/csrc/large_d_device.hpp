@@ -1,0 +1,96 @@
+// Device-side building blocks shared by the large-state-space kernels (D in {16, 32, 64, 128}).
+//
+// The sum-product operator of Definition 3 is a dense D x D matrix product; chunk aggregates
+// ("block-wise elements", Sec. V-B) are built on the FP32 matrix cores.  A chunk's running
+// product P is advanced one time step at a time,
+//     P <- P * (A diag(e_t)),      e_t(j) = exp(ll_t(j) - max_j ll_t(j)),
+// which is computed transposed, P^T <- diag(e_t) (A^T P^T): the constant A^T is the MFMA's first
+// operand (read from LDS) and P^T, which lives in the accumulators, is the second.  An MFMA
+// result register of lane l holds rows {row(mt, r, l / TS)} of a column l % TS, and the second
+// operand wants one row per lane group, so result registers can be fed straight back as second
+// operands if the reduction index k is enumerated in exactly that row order; the first operand
+// is stored in LDS in the matching (permuted) order.  No register ever has to change lanes.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace hmm {
+
+#define HMM_DEV __device__ __forceinline__
+
+template <int D>
+struct LargeCfg {
+    static_assert(D == 16 || D == 32 || D == 64 || D == 128, "supported padded sizes");
+    static constexpr int NT = 256;                       // lanes per workgroup (4 waves)
+    static constexpr int TS = (D >= 64) ? 32 : 16;       // MFMA tile edge: 32x32x2 or 16x16x4
+    static constexpr int NG = 64 / TS;                   // lane groups = reduction depth of one MFMA
+    static constexpr int NACC = TS * TS / 64;            // result registers per tile
+    static constexpr int MT = D / TS;                    // tiles along a column of P^T
+    static constexpr int WPC = D / TS;                   // waves per chunk (one TS-column strip each)
+    static constexpr int CPW = 4 / WPC;                  // chunks per workgroup
+    static constexpr int NS = MT * NACC;                 // MFMAs per result tile (= D * TS / 64)
+    static constexpr int ASTR = NS + 4;                  // padded LDS row of first operands
+    static constexpr int AT_FLOATS = MT * 64 * ASTR;     // permuted A^T of one chunk
+    static constexpr int EB = 16;                        // time steps per emission batch in LDS
+    static constexpr int NORM_EVERY = (D >= 32) ? 4 : 8; // steps between power-of-two rescalings
+    // vector apply kernels: lane = (column inside the wave, part of the summation range)
+    static constexpr int CPWV = (D < 32) ? D : 32;       // columns per wave
+    static constexpr int PARTS = 64 / CPWV;              // lane groups splitting the summation
+    static constexpr int RPP = D / PARTS;                // summation terms per lane
+    static constexpr int VWPC = D / CPWV;                // waves per chunk in the apply kernels
+    static constexpr int VCPW = 4 / VWPC;                // chunks per workgroup in the apply kernels
+};
+
+// Row of P^T held by result register r of tile mt in lane group g.
+template <int D>
+HMM_DEV constexpr int mfma_row(int mt, int r, int g) {
+    using C = LargeCfg<D>;
+    return C::TS * mt + (4 * C::NG) * (r / 4) + 4 * g + (r % 4);
+}
+
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+template <int TS> struct AccT;
+template <> struct AccT<32> { typedef v16f type; };
+template <> struct AccT<16> { typedef v4f type; };
+
+template <int TS>
+HMM_DEV typename AccT<TS>::type mfma_step(float a, float b, typename AccT<TS>::type c) {
+    if constexpr (TS == 32) return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
+    else return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+}
+
+// max over the 64 lanes of a wave, result in every lane
+HMM_DEV float wave_max(float v) {
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) v = fmaxf(v, __shfl_xor(v, d, 64));
+    return v;
+}
+
+// sum over the 64 lanes of a wave, result in every lane
+HMM_DEV float wave_sum(float v) {
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
+    return v;
+}
+
+struct ChunkCoord {
+    int seq;        // sequence
+    int cidx;       // chunk index inside the sequence
+    long long t0;   // first time step of the chunk inside the sequence
+    int nsteps;     // valid steps (0 if the chunk id is out of range)
+};
+
+HMM_DEV ChunkCoord chunk_coord(long long chunk, long long nchunks, int cps, long long T, int Lc) {
+    ChunkCoord c;
+    if (chunk >= nchunks) { c.seq = 0; c.cidx = 0; c.t0 = 0; c.nsteps = 0; return c; }
+    c.seq = (int)(chunk / cps);
+    c.cidx = (int)(chunk - (long long)c.seq * cps);
+    c.t0 = (long long)c.cidx * Lc;
+    const long long rem = T - c.t0;
+    c.nsteps = rem < Lc ? (int)rem : Lc;
+    return c;
+}
+
+}  // namespace hmm

@@ -1,0 +1,585 @@
+// Sum-product smoother for large state spaces (9 <= D <= 128, padded to 16 / 32 / 64 / 128).
+//
+// Chunked all-prefix-sums ("block-wise elements", Sec. V-B): time is cut into chunks of Lc steps.
+//   rowmax     m_t = max_j ll_t(j)                                   (one pass over the input)
+//   aggregate  chunk aggregates a_{k0-1:k0} (x) ... (x) a_{k1-2:k1-1} on the FP32 matrix cores
+//   carry      forward / backward potentials at chunk boundaries (vector x aggregate, sequential
+//              over the chunks of a sequence, both directions concurrently)
+//   forward    a_{0:k} inside each chunk (Theorem 1), written normalised = filtering distribution
+//   backward   a_{k:T+1} inside each chunk (Theorem 2)
+//   combine    p(x_k) = a_{0:k} a_{k:T+1} / Z_k, and log Z from the chunk-local evidences
+// Elements are never stored: each step's psi_k = A diag(e_k) is rebuilt from A and ll_k.
+// States D..DP-1 of the padded model are unreachable (prior 0, self-loop only, e = 0).
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "ktimer.hpp"
+#include "large_d.hpp"
+#include "large_d_device.hpp"
+
+namespace hmm {
+
+constexpr float LOG2E = 1.4426950408889634f;
+
+// ---------------------------------------------------------------------------------------------
+// m_t = max_j ll_t(j): one wave per row batch, coalesced.
+__global__ __launch_bounds__(256) void ld_rowmax_kernel(const float* __restrict__ ll, long long rows, int Dr,
+                                                        float* __restrict__ rowmax) {
+    const long long row = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= rows) return;
+    const int lane = threadIdx.x & 63;
+    float m = -INFINITY;
+    for (int j = lane; j < Dr; j += 64) m = fmaxf(m, ll[row * Dr + j]);
+    m = wave_max(m);
+    if (lane == 0) rowmax[row] = m;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Chunk aggregates on the matrix cores.  One wave owns a TS-column strip of P^T (= TS rows of P,
+// which evolve independently); WPC waves make a chunk, CPW chunks share a workgroup.
+template <int D>
+__global__ __launch_bounds__(256) void ld_aggregate_kernel(const float* __restrict__ A, const float* __restrict__ ll,
+                                                           const float* __restrict__ rowmax, long long T, int Dr,
+                                                           int Lc, int cps, long long nchunks, int shared_model,
+                                                           float* __restrict__ agg, float* __restrict__ aggT,
+                                                           int* __restrict__ exps) {
+    using C = LargeCfg<D>;
+    using Acc = typename AccT<C::TS>::type;
+    constexpr int EPT = C::EB * D / (C::WPC * 64);   // emission values per lane per batch
+    __shared__ __align__(16) float at_all[C::CPW * C::AT_FLOATS];
+    __shared__ __align__(16) float e_all[2 * C::CPW * C::EB * D];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int cl = wave / C::WPC, strip = wave % C::WPC;
+    const int tic = threadIdx.x - cl * C::WPC * 64;   // lane index inside the chunk's group of waves
+    const int g = lane / C::TS;
+    const long long chunk = (long long)blockIdx.x * C::CPW + cl;
+    const ChunkCoord cc = chunk_coord(chunk, nchunks, cps, T, Lc);
+    float* at = at_all + cl * C::AT_FLOATS;
+
+    // A^T in first-operand order: at[(mo*64 + l)*ASTR + s] = A[mfma_row(s)][TS*mo + l % TS]
+    {
+        const float* Am = A + (shared_model ? 0 : (size_t)cc.seq * Dr * Dr);
+        for (int idx = tic; idx < C::MT * 64 * C::NS; idx += C::WPC * 64) {
+            const int s = idx % C::NS, l = (idx / C::NS) % 64, mo = idx / (C::NS * 64);
+            const int k = mfma_row<D>(s / C::NACC, s % C::NACC, l / C::TS);
+            const int m = C::TS * mo + l % C::TS;
+            float a = (k == m) ? 1.0f : 0.0f;
+            if (k < Dr && m < Dr) a = Am[(size_t)k * Dr + m];
+            at[(mo * 64 + l) * C::ASTR + s] = a;
+        }
+    }
+    const float* lseq = ll + (size_t)cc.seq * T * Dr;
+    const float* mseq = rowmax + (size_t)cc.seq * T;
+    auto load_batch = [&](int b, float (&er)[EPT]) {
+#pragma unroll
+        for (int q = 0; q < EPT; ++q) {
+            const int idx = q * (C::WPC * 64) + tic;
+            const int sb = idx / D, j = idx - sb * D;
+            const int step = b * C::EB + sb;
+            float x = -INFINITY, m = 0.0f;
+            if (step < cc.nsteps) {
+                m = mseq[cc.t0 + step];
+                if (j < Dr) x = lseq[(size_t)(cc.t0 + step) * Dr + j];
+            }
+            m = (m == -INFINITY) ? 0.0f : m;
+            er[q] = __builtin_amdgcn_exp2f(fmaf(x, LOG2E, -LOG2E * m));
+        }
+    };
+    auto store_batch = [&](int b, const float (&er)[EPT]) {
+        float* eb = e_all + ((b & 1) * C::CPW + cl) * C::EB * D;
+#pragma unroll
+        for (int q = 0; q < EPT; ++q) eb[q * (C::WPC * 64) + tic] = er[q];
+    };
+
+    Acc acc[C::MT];
+    const int ncol = C::TS * strip + lane % C::TS;
+#pragma unroll
+    for (int mt = 0; mt < C::MT; ++mt)
+#pragma unroll
+        for (int r = 0; r < C::NACC; ++r) acc[mt][r] = (mfma_row<D>(mt, r, g) == ncol) ? 1.0f : 0.0f;
+    int exsum = 0;
+    auto rescale = [&]() {
+        float m = 0.0f;
+#pragma unroll
+        for (int mt = 0; mt < C::MT; ++mt)
+#pragma unroll
+            for (int r = 0; r < C::NACC; ++r) m = fmaxf(m, acc[mt][r]);
+        m = wave_max(m);
+        const int ex = __builtin_amdgcn_frexp_expf(m);
+        const float sc = ldexpf(1.0f, -ex);
+#pragma unroll
+        for (int mt = 0; mt < C::MT; ++mt)
+#pragma unroll
+            for (int r = 0; r < C::NACC; ++r) acc[mt][r] *= sc;
+        exsum += ex;
+    };
+
+    const int nb = (Lc + C::EB - 1) / C::EB;
+    float er[EPT];
+    load_batch(0, er);
+    store_batch(0, er);
+    __syncthreads();
+    const float* arow = at + lane * C::ASTR;
+    for (int b = 0; b < nb; ++b) {
+        if (b + 1 < nb) load_batch(b + 1, er);
+        const float* eb = e_all + ((b & 1) * C::CPW + cl) * C::EB * D;
+#pragma unroll 1
+        for (int sb = 0; sb < C::EB; ++sb) {
+            const int step = b * C::EB + sb;
+            if (step < cc.nsteps) {
+                if (cc.t0 + step != 0) {   // the sequence's first element has no transition part
+                    Acc nw[C::MT];
+#pragma unroll
+                    for (int mo = 0; mo < C::MT; ++mo) {
+#pragma unroll
+                        for (int r = 0; r < C::NACC; ++r) nw[mo][r] = 0.0f;
+#pragma unroll
+                        for (int s4 = 0; s4 < C::NS; s4 += 4) {
+                            const float4 a4 = *reinterpret_cast<const float4*>(arow + mo * 64 * C::ASTR + s4);
+                            nw[mo] = mfma_step<C::TS>(a4.x, acc[(s4 + 0) / C::NACC][(s4 + 0) % C::NACC], nw[mo]);
+                            nw[mo] = mfma_step<C::TS>(a4.y, acc[(s4 + 1) / C::NACC][(s4 + 1) % C::NACC], nw[mo]);
+                            nw[mo] = mfma_step<C::TS>(a4.z, acc[(s4 + 2) / C::NACC][(s4 + 2) % C::NACC], nw[mo]);
+                            nw[mo] = mfma_step<C::TS>(a4.w, acc[(s4 + 3) / C::NACC][(s4 + 3) % C::NACC], nw[mo]);
+                        }
+                    }
+#pragma unroll
+                    for (int mo = 0; mo < C::MT; ++mo) acc[mo] = nw[mo];
+                }
+                // rows of P^T scaled by this step's emission factors
+#pragma unroll
+                for (int mo = 0; mo < C::MT; ++mo)
+#pragma unroll
+                    for (int q = 0; q < C::NACC / 4; ++q) {
+                        const float4 e4 = *reinterpret_cast<const float4*>(eb + sb * D + mfma_row<D>(mo, 4 * q, g));
+                        acc[mo][4 * q + 0] *= e4.x;
+                        acc[mo][4 * q + 1] *= e4.y;
+                        acc[mo][4 * q + 2] *= e4.z;
+                        acc[mo][4 * q + 3] *= e4.w;
+                    }
+                if ((step % C::NORM_EVERY) == C::NORM_EVERY - 1) rescale();
+            }
+        }
+        if (b + 1 < nb) store_batch(b + 1, er);
+        __syncthreads();
+    }
+    if (cc.nsteps > 0) {
+        rescale();
+        float* dst = agg + (size_t)chunk * D * D;     // P[n][k]
+        float* dstT = aggT + (size_t)chunk * D * D;   // P^T[k][n]
+#pragma unroll
+        for (int mt = 0; mt < C::MT; ++mt) {
+#pragma unroll
+            for (int q = 0; q < C::NACC / 4; ++q)
+                *reinterpret_cast<float4*>(dst + (size_t)ncol * D + mfma_row<D>(mt, 4 * q, g)) =
+                    make_float4(acc[mt][4 * q], acc[mt][4 * q + 1], acc[mt][4 * q + 2], acc[mt][4 * q + 3]);
+#pragma unroll
+            for (int r = 0; r < C::NACC; ++r) dstT[(size_t)mfma_row<D>(mt, r, g) * D + ncol] = acc[mt][r];
+        }
+        if (lane == 0) exps[chunk * C::WPC + strip] = exsum;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Carries between the chunks of a sequence.  blockIdx = 2*seq + dir; dir 0 walks the chunks left
+// to right with v <- v P_c (matrix = agg), dir 1 right to left with v <- P_c v (matrix = aggT,
+// read row by row so that both directions stream memory the same way).  Strips of an aggregate
+// carry their own power-of-two scale, reconciled here.
+template <int D>
+__global__ __launch_bounds__(256) void ld_carry_kernel(const float* __restrict__ prior, int Dr, int cps,
+                                                       int shared_model, const float* __restrict__ agg,
+                                                       const float* __restrict__ aggT, const int* __restrict__ exps,
+                                                       float* __restrict__ fin, float* __restrict__ bout) {
+    using C = LargeCfg<D>;
+    constexpr int Q = 256 / D;          // lane groups splitting the summation
+    constexpr int RPT = D / Q;          // summation terms per lane
+    __shared__ float vec[D];            // current vector (pre-scaled for dir 0)
+    __shared__ float partial[Q * D];
+    __shared__ float total_lds;
+    const int seq = blockIdx.x >> 1, dir = blockIdx.x & 1;
+    const int j = threadIdx.x % D, q = threadIdx.x / D;
+    const float* mats = (dir == 0 ? agg : aggT) + (size_t)seq * cps * D * D;
+    const int* ex = exps + (size_t)seq * cps * C::WPC;
+    float* out = (dir == 0 ? fin : bout) + (size_t)seq * cps * D;
+    float v = 0.0f;   // component j of the current vector (meaningful where q == 0)
+    if (dir == 0) v = (j < Dr) ? prior[(shared_model ? 0 : (size_t)seq * Dr) + j] : 0.0f;
+    else v = (j < Dr) ? 1.0f : 0.0f;
+    float pv[RPT];
+    auto load_mat = [&](int c) {
+        const float* M = mats + (size_t)c * D * D;
+#pragma unroll
+        for (int r = 0; r < RPT; ++r) pv[r] = M[(size_t)(q * RPT + r) * D + j];
+    };
+    int c = dir == 0 ? 0 : cps - 1;
+    load_mat(c);
+    for (int it = 0; it < cps; ++it) {
+        if (q == 0) out[(size_t)c * D + j] = v;
+        int exmax = ex[c * C::WPC];
+#pragma unroll
+        for (int s = 1; s < C::WPC; ++s) exmax = max(exmax, ex[c * C::WPC + s]);
+        // dir 0 sums over rows of P, whose scale depends on the row's strip: fold it into the vector
+        if (q == 0) vec[j] = (dir == 0) ? ldexpf(v, ex[c * C::WPC + j / C::TS] - exmax) : v;
+        __syncthreads();
+        float acc = 0.0f;
+#pragma unroll
+        for (int r = 0; r < RPT; ++r) acc = fmaf(vec[q * RPT + r], pv[r], acc);
+        const int cn = dir == 0 ? c + 1 : c - 1;
+        if (it + 1 < cps) load_mat(cn);   // next aggregate streams in while this one is reduced
+        partial[q * D + j] = acc;
+        __syncthreads();
+        float gsum = 0.0f;
+        if (q == 0) {
+#pragma unroll
+            for (int p = 0; p < Q; ++p) gsum += partial[p * D + j];
+            // dir 1 produces rows of P: scale by the row's strip
+            if (dir == 1) gsum = ldexpf(gsum, ex[c * C::WPC + j / C::TS] - exmax);
+        }
+        // normalise by the sum (wave 0 adds the components up)
+        if (threadIdx.x < 64) {
+            float s = 0.0f;
+            for (int jj = threadIdx.x; jj < D; jj += 64) {
+                float t = 0.0f;
+#pragma unroll
+                for (int p = 0; p < Q; ++p) t += partial[p * D + jj];
+                if (dir == 1) t = ldexpf(t, ex[c * C::WPC + jj / C::TS] - exmax);
+                s += t;
+            }
+            s = wave_sum(s);
+            if (threadIdx.x == 0) total_lds = s;
+        }
+        __syncthreads();
+        v = gsum / total_lds;
+        c = cn;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Forward potentials inside the chunks (Theorem 1): f_k = (f_{k-1} A) o e_k, written normalised
+// (= p(x_k | y_{1:k})), plus each chunk's log evidence log p(y_chunk | y_before).
+// Lane = (column j inside the wave, part h of the summation over i); A stays in registers.
+template <int D>
+__global__ __launch_bounds__(256) void ld_forward_kernel(const float* __restrict__ prior, const float* __restrict__ A,
+                                                         const float* __restrict__ ll,
+                                                         const float* __restrict__ rowmax, long long T, int Dr, int Lc,
+                                                         int cps, long long nchunks, int shared_model,
+                                                         const float* __restrict__ fin, float* __restrict__ F,
+                                                         double* __restrict__ part) {
+    using C = LargeCfg<D>;
+    __shared__ __align__(16) float fbuf[2 * C::VCPW * D];
+    __shared__ float wsum[2 * C::VCPW * C::VWPC];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int cl = wave / C::VWPC, wv = wave % C::VWPC;
+    const int jl = lane % C::CPWV, h = lane / C::CPWV;
+    const int j = C::CPWV * wv + jl;
+    const long long chunk = (long long)blockIdx.x * C::VCPW + cl;
+    const ChunkCoord cc = chunk_coord(chunk, nchunks, cps, T, Lc);
+    const float* Am = A + (shared_model ? 0 : (size_t)cc.seq * Dr * Dr);
+    float areg[C::RPP];
+#pragma unroll
+    for (int r = 0; r < C::RPP; ++r) {
+        const int i = h * C::RPP + r;
+        areg[r] = (i == j) ? 1.0f : 0.0f;
+        if (i < Dr && j < Dr) areg[r] = Am[(size_t)i * Dr + j];
+    }
+    const float* lseq = ll + (size_t)cc.seq * T * Dr;
+    const float* mseq = rowmax + (size_t)cc.seq * T;
+    float* Fseq = F + (size_t)cc.seq * T * Dr;
+    // carry into the chunk; every chunk but the sequence's first starts from a vector summing to one
+    float f0 = 0.0f;
+    if (cc.nsteps > 0) {
+        if (chunk % cps == 0) f0 = (j < Dr) ? prior[(shared_model ? 0 : (size_t)cc.seq * Dr) + j] : 0.0f;
+        else f0 = fin[(size_t)chunk * D + j];
+    }
+    float* fb = fbuf + cl * D;
+    float* ws = wsum + cl * C::VWPC;
+    if (h == 0) fb[j] = f0;
+    {
+        const float s = wave_sum(h == 0 ? f0 : 0.0f);
+        if (lane == 0) ws[wv] = s;
+    }
+    __syncthreads();
+    float inv = 1.0f;
+    if (chunk % cps != 0) {
+        float tot = 0.0f;
+#pragma unroll
+        for (int w = 0; w < C::VWPC; ++w) tot += ws[w];
+        inv = 1.0f / tot;
+    }
+    double dacc = 0.0;
+    int cur = 0;
+    float xn = -INFINITY, mn = 0.0f;   // next step's log-likelihood and row maximum, prefetched
+    if (cc.nsteps > 0) {
+        mn = mseq[cc.t0];
+        if (j < Dr) xn = lseq[(size_t)cc.t0 * Dr + j];
+    }
+    for (int s = 0; s < Lc; ++s) {
+        const bool active = s < cc.nsteps;
+        const float x = xn, m = mn;
+        if (s + 1 < cc.nsteps) {
+            mn = mseq[cc.t0 + s + 1];
+            if (j < Dr) xn = lseq[(size_t)(cc.t0 + s + 1) * Dr + j];
+        }
+        const float* fc = fbuf + (cur * C::VCPW + cl) * D;
+        float* fn = fbuf + ((cur ^ 1) * C::VCPW + cl) * D;
+        float* wn = wsum + ((cur ^ 1) * C::VCPW + cl) * C::VWPC;
+        float gval = 0.0f;
+        if (active) {
+            const float msafe = (m == -INFINITY) ? 0.0f : m;
+            const float e = __builtin_amdgcn_exp2f(fmaf(x, LOG2E, -LOG2E * msafe));
+            if (cc.t0 + s == 0) {
+                gval = fc[j] * e;   // psi_1 = prior o e_1: no transition
+            } else {
+                float acc = 0.0f;
+#pragma unroll
+                for (int r4 = 0; r4 < C::RPP; r4 += 4) {
+                    const float4 f4 = *reinterpret_cast<const float4*>(fc + h * C::RPP + r4);
+                    acc = fmaf(f4.x, areg[r4], acc);
+                    acc = fmaf(f4.y, areg[r4 + 1], acc);
+                    acc = fmaf(f4.z, areg[r4 + 2], acc);
+                    acc = fmaf(f4.w, areg[r4 + 3], acc);
+                }
+#pragma unroll
+                for (int d = C::CPWV; d < 64; d <<= 1) acc += __shfl_xor(acc, d, 64);
+                gval = acc * inv * e;
+            }
+            if (h == 0) fn[j] = gval;
+            const float sw = wave_sum(h == 0 ? gval : 0.0f);
+            if (lane == 0) wn[wv] = sw;
+        }
+        __syncthreads();
+        if (active) {
+            float tot = 0.0f;
+#pragma unroll
+            for (int w = 0; w < C::VWPC; ++w) tot += wn[w];
+            inv = 1.0f / tot;
+            if (h == 0 && j < Dr) Fseq[(size_t)(cc.t0 + s) * Dr + j] = gval * inv;
+            if (lane == 0 && wv == 0) dacc += (double)m + (double)__logf(tot);
+        }
+        cur ^= 1;
+    }
+    if (cc.nsteps > 0 && lane == 0 && wv == 0) part[chunk] = dacc;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Backward potentials inside the chunks (Theorem 2): b_{k-1} = A (e_k o b_k), stored with an
+// arbitrary positive scale per step.  Lane = (row i inside the wave, part h of the summation
+// over j); A stays in registers.
+template <int D>
+__global__ __launch_bounds__(256) void ld_backward_kernel(const float* __restrict__ A, const float* __restrict__ ll,
+                                                          const float* __restrict__ rowmax, long long T, int Dr,
+                                                          int Lc, int cps, long long nchunks, int shared_model,
+                                                          const float* __restrict__ bout, float* __restrict__ Bv) {
+    using C = LargeCfg<D>;
+    __shared__ __align__(16) float ubuf[2 * C::VCPW * D];
+    __shared__ float wsum[2 * C::VCPW * C::VWPC];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int cl = wave / C::VWPC, wv = wave % C::VWPC;
+    const int il = lane % C::CPWV, h = lane / C::CPWV;
+    const int i = C::CPWV * wv + il;
+    const long long chunk = (long long)blockIdx.x * C::VCPW + cl;
+    const ChunkCoord cc = chunk_coord(chunk, nchunks, cps, T, Lc);
+    const float* Am = A + (shared_model ? 0 : (size_t)cc.seq * Dr * Dr);
+    float areg[C::RPP];
+#pragma unroll
+    for (int r = 0; r < C::RPP; ++r) {
+        const int jj = h * C::RPP + r;
+        areg[r] = (i == jj) ? 1.0f : 0.0f;
+        if (i < Dr && jj < Dr) areg[r] = Am[(size_t)i * Dr + jj];
+    }
+    const float* lseq = ll + (size_t)cc.seq * T * Dr;
+    const float* mseq = rowmax + (size_t)cc.seq * T;
+    float* Bseq = Bv + (size_t)cc.seq * T * Dr;
+    float b = (cc.nsteps > 0) ? bout[(size_t)chunk * D + i] : 0.0f;   // b at the chunk's last step
+    float inv = 1.0f;
+    int cur = 0;
+    float xn = -INFINITY, mn = 0.0f;
+    if (cc.nsteps > 0) {
+        mn = mseq[cc.t0 + cc.nsteps - 1];
+        if (i < Dr) xn = lseq[(size_t)(cc.t0 + cc.nsteps - 1) * Dr + i];
+    }
+    for (int s = Lc - 1; s >= 0; --s) {
+        const bool active = s < cc.nsteps;
+        float* un = ubuf + ((cur ^ 1) * C::VCPW + cl) * D;
+        float* wn = wsum + ((cur ^ 1) * C::VCPW + cl) * C::VWPC;
+        if (active) {
+            const float x = xn, m = mn;
+            if (s > 0) {
+                mn = mseq[cc.t0 + s - 1];
+                if (i < Dr) xn = lseq[(size_t)(cc.t0 + s - 1) * Dr + i];
+            }
+            const float bs = b * inv;   // scaled by the previous step's normaliser: any positive scale will do
+            if (h == 0 && i < Dr) Bseq[(size_t)(cc.t0 + s) * Dr + i] = bs;
+            const float msafe = (m == -INFINITY) ? 0.0f : m;
+            const float e = __builtin_amdgcn_exp2f(fmaf(x, LOG2E, -LOG2E * msafe));
+            if (h == 0) un[i] = e * bs;
+            const float sw = wave_sum(h == 0 ? bs : 0.0f);
+            if (lane == 0) wn[wv] = sw;
+        }
+        __syncthreads();
+        if (active && s > 0) {
+            float tot = 0.0f;
+#pragma unroll
+            for (int w = 0; w < C::VWPC; ++w) tot += wn[w];
+            inv = 1.0f / tot;
+            float acc = 0.0f;
+#pragma unroll
+            for (int r4 = 0; r4 < C::RPP; r4 += 4) {
+                const float4 u4 = *reinterpret_cast<const float4*>(un + h * C::RPP + r4);
+                acc = fmaf(u4.x, areg[r4], acc);
+                acc = fmaf(u4.y, areg[r4 + 1], acc);
+                acc = fmaf(u4.z, areg[r4 + 2], acc);
+                acc = fmaf(u4.w, areg[r4 + 3], acc);
+            }
+#pragma unroll
+            for (int d = C::CPWV; d < 64; d <<= 1) acc += __shfl_xor(acc, d, 64);
+            b = acc;
+        }
+        cur ^= 1;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// p(x_k) = f_k b_k / Z_k.  Four consecutive states per lane; a row is reduced inside a wave.
+__global__ __launch_bounds__(256) void ld_combine_kernel(const float* __restrict__ F, const float* __restrict__ Bv,
+                                                         long long rows, int Dr, float* __restrict__ marg) {
+    const int lpr = (Dr + 3) / 4;                  // lanes per row
+    int width = 1;
+    while (width < lpr) width <<= 1;               // power of two <= 32 for Dr <= 128
+    const int rows_per_wave = 64 / width;
+    const int lane = threadIdx.x & 63;
+    const long long wave = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const long long row = wave * rows_per_wave + lane / width;
+    const int sub = lane % width;
+    float g[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    const bool live = row < rows && sub < lpr;
+    if (live) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int j = 4 * sub + q;
+            if (j < Dr) g[q] = F[row * Dr + j] * Bv[row * Dr + j];
+        }
+    }
+    float s = g[0] + g[1] + g[2] + g[3];
+    for (int d = 1; d < width; d <<= 1) s += __shfl_xor(s, d, 64);
+    if (live) {
+        const float inv = 1.0f / s;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int j = 4 * sub + q;
+            if (j < Dr) marg[row * Dr + j] = g[q] * inv;
+        }
+    }
+}
+
+// out[seq] = ordered sum of the chunk evidences of one sequence
+__global__ __launch_bounds__(256) void ld_finalize_kernel(const double* __restrict__ part, int cps,
+                                                          double* __restrict__ out) {
+    __shared__ double sh[256];
+    const int seq = blockIdx.x;
+    double acc = 0.0;
+    for (int c = threadIdx.x; c < cps; c += 256) acc += part[(size_t)seq * cps + c];
+    sh[threadIdx.x] = acc;
+    __syncthreads();
+    for (int d = 128; d >= 1; d >>= 1) {
+        if ((int)threadIdx.x < d) sh[threadIdx.x] += sh[threadIdx.x + d];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) out[seq] = sh[0];
+}
+
+// =============================================================================================
+// Host side
+// =============================================================================================
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+LargePlan large_plan(int Dr, long long T, int batch) {
+    LargePlan p;
+    p.DP = Dr <= 16 ? 16 : Dr <= 32 ? 32 : Dr <= 64 ? 64 : 128;
+    // chunks: enough to occupy every matrix core, few enough that the sequential carry stays short
+    const long long target = p.DP >= 128 ? 256 : p.DP >= 64 ? 512 : 1024;
+    long long cps = (target + batch - 1) / batch;
+    if (cps < 1) cps = 1;
+    long long Lc = (T + cps - 1) / cps;
+    Lc = (Lc + 15) / 16 * 16;
+    if (Lc < 16) Lc = 16;
+    p.Lc = (int)(Lc > 0x3fffffff ? 0x3fffffff : Lc);
+    p.cps = (int)((T + p.Lc - 1) / p.Lc);
+    p.nchunks = (long long)p.cps * batch;
+    return p;
+}
+
+struct LargeSmoothWs { size_t rowmax, agg, aggT, exps, fin, bout, F, Bv, part, total; };
+
+static LargeSmoothWs large_smooth_ws(int Dr, long long T, int batch, bool own_F) {
+    const LargePlan p = large_plan(Dr, T, batch);
+    const size_t D = p.DP, nc = (size_t)p.nchunks, rows = (size_t)T * batch;
+    LargeSmoothWs w;
+    size_t o = 0;
+    w.rowmax = o; o = align_up(o + rows * sizeof(float), 256);
+    w.agg = o;    o = align_up(o + nc * D * D * sizeof(float), 256);
+    w.aggT = o;   o = align_up(o + nc * D * D * sizeof(float), 256);
+    w.exps = o;   o = align_up(o + nc * 8 * sizeof(int), 256);
+    w.fin = o;    o = align_up(o + nc * D * sizeof(float), 256);
+    w.bout = o;   o = align_up(o + nc * D * sizeof(float), 256);
+    w.F = o;      o = align_up(o + (own_F ? rows * Dr * sizeof(float) : 0), 256);
+    w.Bv = o;     o = align_up(o + rows * Dr * sizeof(float), 256);
+    w.part = o;   o = align_up(o + nc * sizeof(double), 256);
+    w.total = o;
+    return w;
+}
+
+size_t large_d_smooth_ws_bytes(int Dr, long long T, int batch) {
+    return large_smooth_ws(Dr, T, batch, true).total;   // sized for the case without a filtered output
+}
+
+template <int D>
+static int large_smooth_impl(const LargeArgs& a, float* marg, float* filt, double* loglik_out) {
+    using C = LargeCfg<D>;
+    const LargePlan p = large_plan(a.D, a.T, a.batch);
+    const LargeSmoothWs w = large_smooth_ws(a.D, a.T, a.batch, true);
+    if (a.ws_bytes < w.total) return 3;
+    const long long rows = a.T * a.batch;
+    if (rows > 0x7fffffffLL * 4 || p.nchunks > 0x7fffffffLL) return 2;
+    char* ws = static_cast<char*>(a.ws);
+    float* rowmax = reinterpret_cast<float*>(ws + w.rowmax);
+    float* agg = reinterpret_cast<float*>(ws + w.agg);
+    float* aggT = reinterpret_cast<float*>(ws + w.aggT);
+    int* exps = reinterpret_cast<int*>(ws + w.exps);
+    float* fin = reinterpret_cast<float*>(ws + w.fin);
+    float* bout = reinterpret_cast<float*>(ws + w.bout);
+    float* F = filt ? filt : reinterpret_cast<float*>(ws + w.F);
+    float* Bv = reinterpret_cast<float*>(ws + w.Bv);
+    double* part = reinterpret_cast<double*>(ws + w.part);
+    hipStream_t st = a.stream;
+    const dim3 block(256);
+    launch("ld_rowmax", ld_rowmax_kernel, dim3((unsigned)((rows + 3) / 4)), block, st, a.ll, rows, a.D, rowmax);
+    launch("ld_aggregate", ld_aggregate_kernel<D>, dim3((unsigned)((p.nchunks + C::CPW - 1) / C::CPW)), block, st, a.A,
+           a.ll, rowmax, a.T, a.D, p.Lc, p.cps, p.nchunks, a.shared_model, agg, aggT, exps);
+    launch("ld_carry", ld_carry_kernel<D>, dim3(2u * (unsigned)a.batch), block, st, a.prior, a.D, p.cps, a.shared_model,
+           agg, aggT, exps, fin, bout);
+    const dim3 vgrid((unsigned)((p.nchunks + C::VCPW - 1) / C::VCPW));
+    launch("ld_forward", ld_forward_kernel<D>, vgrid, block, st, a.prior, a.A, a.ll, rowmax, a.T, a.D, p.Lc, p.cps,
+           p.nchunks, a.shared_model, fin, F, part);
+    launch("ld_backward", ld_backward_kernel<D>, vgrid, block, st, a.A, a.ll, rowmax, a.T, a.D, p.Lc, p.cps, p.nchunks,
+           a.shared_model, bout, Bv);
+    const int lpr = (a.D + 3) / 4;
+    int width = 1;
+    while (width < lpr) width <<= 1;
+    const long long rows_per_block = 4LL * (64 / width);
+    launch("ld_combine", ld_combine_kernel, dim3((unsigned)((rows + rows_per_block - 1) / rows_per_block)), block, st, F, Bv,
+           rows, a.D, marg);
+    launch("ld_finalize", ld_finalize_kernel, dim3((unsigned)a.batch), block, st, part, p.cps, loglik_out);
+    return hipGetLastError() == hipSuccess ? 0 : 4;
+}
+
+int large_d_smooth(const LargeArgs& a, float* marg, float* filt, double* loglik_out) {
+    const int DP = large_plan(a.D, a.T, a.batch).DP;
+    switch (DP) {
+        case 16: return large_smooth_impl<16>(a, marg, filt, loglik_out);
+        case 32: return large_smooth_impl<32>(a, marg, filt, loglik_out);
+        case 64: return large_smooth_impl<64>(a, marg, filt, loglik_out);
+        case 128: return large_smooth_impl<128>(a, marg, filt, loglik_out);
+        default: return 2;
+    }
+}
+
+}  // namespace hmm

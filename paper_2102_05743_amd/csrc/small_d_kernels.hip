@@ -598,12 +598,14 @@ __global__ __launch_bounds__(256) void sd_viterbi_fused_kernel(const float* __re
     __shared__ uint32_t wmaps[C::NW];
     __shared__ uint32_t wmaps2[C::NW];
     __shared__ uint32_t xend_lds;
+    HMM_STAMP(0);
     const TileCoord tc = tile_coord<D>(T, tps);
     const int tile0 = blockIdx.x - tc.tile;
     load_tile<D>(ll + tc.base * D, tc.nvalid, lds);
     float Am[D * D];
     load_model<S, D>(A + (shared_model ? 0 : (size_t)tc.seq * D * D), Am);
     __syncthreads();
+    HMM_STAMP(1);
     float* row = lds + threadIdx.x * C::STRIDE;
     const int n = min(max(tc.nvalid - (int)threadIdx.x * C::L, 0), C::L);
     const bool first = tc.tile == 0 && threadIdx.x == 0;
@@ -611,18 +613,25 @@ __global__ __launch_bounds__(256) void sd_viterbi_fused_kernel(const float* __re
     float P[D * D], Q[D * D];
     double msum;
     chunk_aggregate<S, D, false>(row, n, first, Am, P, msum);
+    HMM_STAMP(2);
     block_prefix<S, D>(P, Q, wagg);
     __syncthreads();
+    HMM_STAMP(3);
     grid_publish<S, D>(wagg, ws);
+    HMM_STAMP(4);
     float cf[D], cb[D];
     grid_gather<S, D, false>(tc, tps, prior + (shared_model ? 0 : (size_t)tc.seq * D), ws, gl, cf, cb);
+    HMM_STAMP(6);
     float v[D];
     carry_forward<S, D>(Q, wagg, cf, v);
+    HMM_STAMP(7);
     uint32_t bp[C::W], h, xs;
     const double osum = viterbi_chunk<D>(row, n, first, last, Am, v, bp, h, xs);
+    HMM_STAMP(8);
     const double tile_delta = block_sum(osum, dsum);
     uint32_t excl;
     const uint32_t total = block_map_suffix<D>(h, excl, wmaps);
+    HMM_STAMP(9);
     if (threadIdx.x == 0) {
         coherent_store(reinterpret_cast<unsigned long long*>(ws.part) + blockIdx.x, publish_bits(tile_delta));
         coherent_store(ws.tmap + blockIdx.x, total);   // a map uses 24 bits: never the sentinel
@@ -643,16 +652,20 @@ __global__ __launch_bounds__(256) void sd_viterbi_fused_kernel(const float* __re
         if (threadIdx.x == 0) atomicOr(ws.err, 1u);
         tm = map_identity<D>();
     }
+    HMM_STAMP(10);
     uint32_t texcl;
     block_map_suffix<D>(tm, texcl, wmaps2);
     if ((int)threadIdx.x == tc.tile) xend_lds = map_apply<D>(texcl, 0u);   // last tile's map is constant
     __syncthreads();
     uint32_t x = map_apply<D>(excl, xend_lds);
     if (last) x = xs;
+    HMM_STAMP(11);
     int32_t* stage = reinterpret_cast<int32_t*>(lds);   // the log-likelihood tile is no longer needed
     walk_chunk<D>(bp, n, first, x, stage + threadIdx.x * C::PSTRIDE);
     __syncthreads();
+    HMM_STAMP(12);
     store_path_tile<D>(path + tc.base, tc.nvalid, stage);
+    HMM_STAMP(13);
     if (tc.tile == 0) grid_sum_parts(blockIdx.x, tps, ws, dsum, logprob_out, tc.seq);
 }
 
@@ -748,7 +761,8 @@ int SmallD<D>::smooth(const SmallArgs& a, float* marg, float* filt, double* logl
     double* part = reinterpret_cast<double*>(ws + w.part);
     uint32_t* xch = reinterpret_cast<uint32_t*>(ws + w.xch);
     hipStream_t st = a.stream;
-    const dim3 grid((unsigned)nt), block(C::NT);
+    const dim3 grid((unsigned)nt), block(C::NT), seqs((unsigned)a.batch);
+    const int itps = (int)tps;
     const long long cap = filt ? resident_capacity<0>(sd_smooth_fused_kernel<D, true>)
                                : resident_capacity<1>(sd_smooth_fused_kernel<D, false>);
     if (!force_multi_launch() && tps <= C::NT && nt <= cap) {
@@ -756,23 +770,24 @@ int SmallD<D>::smooth(const SmallArgs& a, float* marg, float* filt, double* logl
         FusedWs fw{reinterpret_cast<float*>(xch + xl.agg), reinterpret_cast<double*>(xch + xl.part), xch + xl.tmap,
                    xch + xl.err};
         const int nwords = (int)xl.words;
-        { KernelScope ks("sd_clear_sp", st); sd_clear_kernel<D><<<dim3((nwords + 255) / 256), dim3(256), 0, st>>>(xch, nwords); }
-        KernelScope ks("sd_smooth_fused", st);
+        launch("sd_clear_sp", sd_clear_kernel<D>, dim3((nwords + 255) / 256), dim3(256), st, xch, nwords);
         if (filt)
-            sd_smooth_fused_kernel<D, true><<<grid, block, 0, st>>>(a.prior, a.A, a.ll, a.T, (int)tps, a.shared_model, marg, filt, loglik_out, fw);
+            launch("sd_smooth_fused", sd_smooth_fused_kernel<D, true>, grid, block, st, a.prior, a.A, a.ll, a.T, itps,
+                   a.shared_model, marg, filt, loglik_out, fw);
         else
-            sd_smooth_fused_kernel<D, false><<<grid, block, 0, st>>>(a.prior, a.A, a.ll, a.T, (int)tps, a.shared_model, marg, nullptr, loglik_out, fw);
+            launch("sd_smooth_fused", sd_smooth_fused_kernel<D, false>, grid, block, st, a.prior, a.A, a.ll, a.T, itps,
+                   a.shared_model, marg, filt, loglik_out, fw);
     } else {
-        { KernelScope ks("sd_reduce_sp", st); sd_reduce_kernel<SumProd, D><<<grid, block, 0, st>>>(a.A, a.ll, a.T, (int)tps, a.shared_model, agg); }
-        { KernelScope ks("sd_carry_sp", st); sd_carry_kernel<SumProd, D, true><<<dim3(a.batch), block, 0, st>>>(a.prior, (int)tps, a.shared_model, agg, fin, bout); }
-        {
-            KernelScope ks("sd_smooth_apply", st);
-            if (filt)
-                sd_smooth_apply_kernel<D, true><<<grid, block, 0, st>>>(a.A, a.ll, a.T, (int)tps, a.shared_model, fin, bout, marg, filt, part);
-            else
-                sd_smooth_apply_kernel<D, false><<<grid, block, 0, st>>>(a.A, a.ll, a.T, (int)tps, a.shared_model, fin, bout, marg, nullptr, part);
-        }
-        { KernelScope ks("sd_finalize", st); sd_finalize_kernel<D><<<dim3(a.batch), dim3(256), 0, st>>>(part, (int)tps, loglik_out); }
+        launch("sd_reduce_sp", sd_reduce_kernel<SumProd, D>, grid, block, st, a.A, a.ll, a.T, itps, a.shared_model, agg);
+        launch("sd_carry_sp", sd_carry_kernel<SumProd, D, true>, seqs, block, st, a.prior, itps, a.shared_model, agg, fin,
+               bout);
+        if (filt)
+            launch("sd_smooth_apply", sd_smooth_apply_kernel<D, true>, grid, block, st, a.A, a.ll, a.T, itps,
+                   a.shared_model, fin, bout, marg, filt, part);
+        else
+            launch("sd_smooth_apply", sd_smooth_apply_kernel<D, false>, grid, block, st, a.A, a.ll, a.T, itps,
+                   a.shared_model, fin, bout, marg, filt, part);
+        launch("sd_finalize", sd_finalize_kernel<D>, seqs, dim3(256), st, part, itps, loglik_out);
     }
     return hipGetLastError() == hipSuccess ? 0 : 4;
 }
@@ -795,22 +810,25 @@ int SmallD<D>::viterbi(const SmallArgs& a, int32_t* path, double* logprob_out) {
     double* part = reinterpret_cast<double*>(ws + w.part);
     uint32_t* xch = reinterpret_cast<uint32_t*>(ws + w.xch);
     hipStream_t st = a.stream;
-    const dim3 grid((unsigned)nt), block(C::NT);
+    const dim3 grid((unsigned)nt), block(C::NT), seqs((unsigned)a.batch);
+    const int itps = (int)tps;
     const long long cap = resident_capacity<2>(sd_viterbi_fused_kernel<D>);
     if (!force_multi_launch() && tps <= C::NT && nt <= cap) {
         const XchLayout xl = xch_layout<D>((size_t)nt);
         FusedWs fw{reinterpret_cast<float*>(xch + xl.agg), reinterpret_cast<double*>(xch + xl.part), xch + xl.tmap,
                    xch + xl.err};
         const int nwords = (int)xl.words;
-        { KernelScope ks("sd_clear_mp", st); sd_clear_kernel<D><<<dim3((nwords + 255) / 256), dim3(256), 0, st>>>(xch, nwords); }
-        KernelScope ks("sd_viterbi_fused", st);
-        sd_viterbi_fused_kernel<D><<<grid, block, 0, st>>>(a.prior, a.A, a.ll, a.T, (int)tps, a.shared_model, path, logprob_out, fw);
+        launch("sd_clear_mp", sd_clear_kernel<D>, dim3((nwords + 255) / 256), dim3(256), st, xch, nwords);
+        launch("sd_viterbi_fused", sd_viterbi_fused_kernel<D>, grid, block, st, a.prior, a.A, a.ll, a.T, itps,
+               a.shared_model, path, logprob_out, fw);
     } else {
-        { KernelScope ks("sd_reduce_mp", st); sd_reduce_kernel<MaxPlus, D><<<grid, block, 0, st>>>(a.A, a.ll, a.T, (int)tps, a.shared_model, agg); }
-        { KernelScope ks("sd_carry_mp", st); sd_carry_kernel<MaxPlus, D, false><<<dim3(a.batch), block, 0, st>>>(a.prior, (int)tps, a.shared_model, agg, vin, nullptr); }
-        { KernelScope ks("sd_viterbi_forward", st); sd_viterbi_forward_kernel<D><<<grid, block, 0, st>>>(a.A, a.ll, a.T, (int)tps, a.shared_model, vin, bp, cmap, tmap, part); }
-        { KernelScope ks("sd_viterbi_suffix", st); sd_viterbi_suffix_kernel<D><<<dim3(a.batch), block, 0, st>>>(tmap, (int)tps, xend, part, logprob_out); }
-        { KernelScope ks("sd_viterbi_path", st); sd_viterbi_path_kernel<D><<<grid, block, 0, st>>>(a.T, (int)tps, bp, cmap, xend, path); }
+        launch("sd_reduce_mp", sd_reduce_kernel<MaxPlus, D>, grid, block, st, a.A, a.ll, a.T, itps, a.shared_model, agg);
+        launch("sd_carry_mp", sd_carry_kernel<MaxPlus, D, false>, seqs, block, st, a.prior, itps, a.shared_model, agg, vin,
+               static_cast<float*>(nullptr));
+        launch("sd_viterbi_forward", sd_viterbi_forward_kernel<D>, grid, block, st, a.A, a.ll, a.T, itps, a.shared_model,
+               vin, bp, cmap, tmap, part);
+        launch("sd_viterbi_suffix", sd_viterbi_suffix_kernel<D>, seqs, block, st, tmap, itps, xend, part, logprob_out);
+        launch("sd_viterbi_path", sd_viterbi_path_kernel<D>, grid, block, st, a.T, itps, bp, cmap, xend, path);
     }
     return hipGetLastError() == hipSuccess ? 0 : 4;
 }

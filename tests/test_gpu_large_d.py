@@ -1,0 +1,49 @@
+"""GPU parity, large state spaces (9 <= D <= 128): the matrix-core sum-product path through the
+C ABI against the CPU oracle, element by element."""
+import numpy as np
+import pytest
+
+from paper_2102_05743_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gu():
+    import gpu_util
+    return gpu_util
+
+
+@pytest.mark.parametrize("D", [9, 16, 20, 32, 48, 64, 100, 128])
+@pytest.mark.parametrize("T", [1, 17, 700, 3001])
+def test_random_models_smoother(gu, D, T):
+    p = wl.random_problem(D, T, seed=1000 + 10 * D + T % 7)
+    gu.check_smooth(p, want_filtered=(T == 700))
+
+
+@pytest.mark.parametrize("D,T,B,shared", [(16, 900, 5, False), (32, 1500, 3, True), (64, 257, 4, False),
+                                          (128, 130, 3, False), (24, 64, 40, False)])
+def test_batched_smoother(gu, D, T, B, shared):
+    p = wl.random_problem(D, T, batch=B, shared_model=shared, seed=50 + D + B)
+    gu.check_smooth(p, want_filtered=True)
+
+
+def test_config3_shape(gu):
+    gu.check_smooth(wl.config3(T=20000), want_filtered=True, label="C3 T=20000")
+
+
+def test_config4_shape(gu):
+    gu.check_smooth(wl.config4(batch=12, T=4096), label="C4 B=12")
+
+
+def test_config5_shape(gu):
+    gu.check_smooth(wl.config5(T=6000), want_filtered=True, label="C5 T=6000")
+
+
+def test_sparse_transitions_and_impossible_emissions(gu):
+    p = wl.random_problem(32, 2500, seed=77, zero_frac=0.6)
+    rng = np.random.default_rng(5)
+    mask = rng.random(p.loglik.shape) < 0.2
+    mask[..., 0] = False
+    p.loglik[mask] = -np.inf
+    gu.check_smooth(p, want_filtered=True)
