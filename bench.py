@@ -35,6 +35,9 @@ def main() -> int:
     ap.add_argument("--sets", type=int, default=24, help="distinct buffer sets rotated over (cold-cache timing)")
     ap.add_argument("--T", type=int, default=1 << 20, help="sequence length (default: the headline 2^20)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain device copy of 32 MiB per step (a kernel of known traffic, for scaling "
+                         "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -67,8 +70,15 @@ def main() -> int:
     ws_smooth = torch.empty((max(ws_s, 256),), dtype=torch.uint8, device=dev)
     ws_viterbi = torch.empty((max(ws_v, 256),), dtype=torch.uint8, device=dev)
 
+    cal_src = cal_dst = None
+    if args.copy_calibration:
+        cal_src = torch.ones((8 << 20,), dtype=torch.float32, device=dev)     # 32 MiB
+        cal_dst = torch.empty_like(cal_src)
+
     def step(i: int) -> None:
         s = i % nsets
+        if cal_src is not None:
+            cal_dst.copy_(cal_src)
         hmm.hmm_smooth(prior, A, lls[s], marginals=margs[s], loglik_out=logliks[s], workspace=ws_smooth)
         hmm.hmm_viterbi(prior, A, lls[s], path=paths[s], logprob_out=logprobs[s], workspace=ws_viterbi)
 
