@@ -32,7 +32,7 @@ hmm_status hmm_workspace_bytes(int64_t T, int32_t D, int32_t batch, size_t* smoo
         v = hmm::small_d_viterbi_ws_bytes(D, T, batch);
     } else {
         s = hmm::large_d_smooth_ws_bytes(D, T, batch);
-        v = 0;   // large-D Viterbi: not built yet (hmm_viterbi reports HMM_ERR_UNSUPPORTED)
+        v = hmm::large_d_viterbi_ws_bytes(D, T, batch);
     }
     if (smooth_bytes) *smooth_bytes = s;
     if (viterbi_bytes) *viterbi_bytes = v;
@@ -66,11 +66,15 @@ hmm_status hmm_viterbi(const float* prior, const float* A, const float* loglik, 
     hmm_status st = check_common(prior, A, loglik, T, D, batch);
     if (st != HMM_OK) return st;
     if (!path || !logprob_out) return HMM_ERR_INVALID_ARG;
-    if (D > hmm::SMALL_D_MAX) return HMM_ERR_UNSUPPORTED;
     size_t need = 0;
     st = hmm_workspace_bytes(T, D, batch, nullptr, &need);
     if (st != HMM_OK) return st;
     if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return HMM_ERR_WORKSPACE;
+    if (D > hmm::SMALL_D_MAX) {
+        hmm::LargeArgs la{prior, A, loglik, (long long)T, D, batch, shared_model ? 1 : 0, workspace, workspace_bytes,
+                          static_cast<hipStream_t>(hip_stream)};
+        return static_cast<hmm_status>(hmm::large_d_viterbi(la, path, logprob_out));
+    }
     hmm::SmallArgs a{prior, A, loglik, (long long)T, batch, shared_model ? 1 : 0, workspace, workspace_bytes,
                      static_cast<hipStream_t>(hip_stream)};
     return static_cast<hmm_status>(hmm::small_d_viterbi(D, a, path, logprob_out));

@@ -25,4 +25,17 @@ inline void launch(const char* name, void (*kernel)(KArgs...), dim3 grid, dim3 b
     }
 }
 
+// Same with dynamic LDS.
+template <class... KArgs, class... Args>
+inline void launch_dyn(const char* name, void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t lds_bytes,
+                       hipStream_t stream, Args&&... args) {
+    if (ktimer_enabled()) {
+        hipEvent_t e0 = nullptr, e1 = nullptr;
+        ktimer_new_record(name, &e0, &e1);
+        hipExtLaunchKernelGGL(kernel, grid, block, (uint32_t)lds_bytes, stream, e0, e1, 0, static_cast<KArgs>(args)...);
+    } else {
+        hipLaunchKernelGGL(kernel, grid, block, (uint32_t)lds_bytes, stream, static_cast<KArgs>(args)...);
+    }
+}
+
 }  // namespace hmm

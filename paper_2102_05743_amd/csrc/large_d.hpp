@@ -31,5 +31,7 @@ LargePlan large_plan(int D, long long T, int batch);
 // Return codes follow hmm_status (0 ok, 2 unsupported, 3 workspace, 4 device).
 size_t large_d_smooth_ws_bytes(int D, long long T, int batch);
 int large_d_smooth(const LargeArgs& a, float* marg, float* filt, double* loglik_out);
+size_t large_d_viterbi_ws_bytes(int D, long long T, int batch);
+int large_d_viterbi(const LargeArgs& a, int32_t* path, double* logprob_out);
 
 }  // namespace hmm

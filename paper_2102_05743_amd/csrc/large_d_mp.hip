@@ -1,0 +1,519 @@
+// Viterbi / MAP decoding for large state spaces (9 <= D <= 128, padded to 16 / 32 / 64 / 128).
+//
+// Max-product operator of Definition 5 on logarithms, (a v b)(i,k) = max_j [a(i,j) + b(j,k)]:
+// no matrix-core form exists for (max,+), so chunk aggregates are built on the vector ALUs.
+//   aggregate  chunk aggregates P_c = psi_{k0} v ... v psi_{k1-1}, psi_k(i,j) = log A(i,j) + ll_k(j)
+//   carry      V at chunk boundaries: v <- v v P_c, sequential over the chunks of a sequence
+//   forward    V_k and back-pointers u_{k-1}(x_k) inside each chunk (Sec. IV-A), the chunk's
+//              back-pointer map (state at its last step -> state at the previous chunk's last
+//              step), x*_T = argmax V_T in the sequence's last chunk, chunk-local log-probability
+//   suffix     reversed all-prefix-sums under composition over the chunk maps, collapsed to the
+//              single state it is applied to: the state at every chunk's last step; log-probability
+//   path       back-pointer walk inside each chunk
+// Aggregates and carries are scale-free (offsets are dropped); the log-probability is the sum of the
+// chunk-local growths of max_j V, each measured from a carry renormalised to max 0.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "ktimer.hpp"
+#include "large_d.hpp"
+#include "large_d_device.hpp"
+
+namespace hmm {
+
+template <int D>
+struct MpCfg {
+    static constexpr int WPC = (D >= 64) ? 4 : 1;        // waves per chunk
+    static constexpr int CPW = 4 / WPC;                  // chunks per workgroup
+    static constexpr int LPC = WPC * 64;                 // lanes per chunk
+    static constexpr int RG = LPC / D;                   // row groups: lane = (row group, column)
+    static constexpr int RPG = D / RG;                   // rows (of P) or summation terms per lane
+};
+
+HMM_DEV float max3f(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
+
+template <int D>
+HMM_DEV void chunk_sync() {
+    if constexpr (MpCfg<D>::WPC == 4) __syncthreads();
+    else __builtin_amdgcn_wave_barrier();
+}
+
+HMM_DEV float safe_log(float p) { return p > 0.0f ? logf(p) : -INFINITY; }
+
+// ---------------------------------------------------------------------------------------------
+// Chunk aggregates.  Lane = (row group rg, column j); the lane keeps column j of log A in registers
+// and produces P'(i,j) = max_k [P(i,k) + log A(k,j)] + ll(j) for the rows i of its group, reading
+// P(i,k) as LDS broadcasts.  P is double-buffered in LDS; its running maximum is removed one step
+// late through the ll(j) term.
+template <int D>
+__global__ __launch_bounds__(256) void lv_aggregate_kernel(const float* __restrict__ A, const float* __restrict__ ll,
+                                                           long long T, int Dr, int Lc, int cps, long long nchunks,
+                                                           int shared_model, float* __restrict__ agg) {
+    using M = MpCfg<D>;
+    __shared__ __align__(16) float pbuf[2 * M::CPW * D * D];
+    __shared__ float wmax[2 * 4];
+    const int wave = threadIdx.x >> 6;
+    const int cl = wave / M::WPC;
+    const int u = threadIdx.x - cl * M::LPC;
+    const int j = u % D, rg = u / D;
+    const long long chunk = (long long)blockIdx.x * M::CPW + cl;
+    const ChunkCoord cc = chunk_coord(chunk, nchunks, cps, T, Lc);
+    const float* Am = A + (shared_model ? 0 : (size_t)cc.seq * Dr * Dr);
+    float la[D];   // column j of log A
+#pragma unroll
+    for (int k = 0; k < D; ++k) {
+        float v = (k == j) ? 0.0f : -INFINITY;
+        if (k < Dr && j < Dr) v = safe_log(Am[(size_t)k * Dr + j]);
+        la[k] = v;
+    }
+    const float* lseq = ll + (size_t)cc.seq * T * Dr;
+    float* p0 = pbuf + (size_t)cl * D * D;
+    float* p1 = pbuf + (size_t)(M::CPW + cl) * D * D;
+    // neutral element: 0 on the diagonal, -inf elsewhere
+#pragma unroll 4
+    for (int r = 0; r < M::RPG; ++r) {
+        const int i = rg * M::RPG + r;
+        p0[i * D + j] = (i == j) ? 0.0f : -INFINITY;
+    }
+    chunk_sync<D>();
+    float off = 0.0f;
+    int cur = 0;
+    float xn = -INFINITY;
+    if (cc.nsteps > 0 && j < Dr) xn = lseq[(size_t)cc.t0 * Dr + j];
+    for (int s = 0; s < Lc; ++s) {
+        const bool active = s < cc.nsteps;
+        const float x = xn;
+        if (s + 1 < cc.nsteps && j < Dr) xn = lseq[(size_t)(cc.t0 + s + 1) * Dr + j];
+        const float* po = cur ? p1 : p0;
+        float* pn = cur ? p0 : p1;
+        float lmax = -INFINITY;
+        if (active) {
+            const float add = x - off;
+            const bool no_transition = (cc.t0 + s == 0);
+#pragma unroll 1
+            for (int r = 0; r < M::RPG; ++r) {
+                const int i = rg * M::RPG + r;
+                const float* prow = po + i * D;
+                float acc;
+                if (no_transition) {
+                    acc = prow[j];
+                } else {
+                    acc = -INFINITY;
+#pragma unroll
+                    for (int k4 = 0; k4 < D; k4 += 4) {
+                        const float4 p4 = *reinterpret_cast<const float4*>(prow + k4);
+                        acc = max3f(acc, p4.x + la[k4], p4.y + la[k4 + 1]);
+                        acc = max3f(acc, p4.z + la[k4 + 2], p4.w + la[k4 + 3]);
+                    }
+                }
+                acc += add;
+                lmax = fmaxf(lmax, acc);
+                pn[i * D + j] = acc;
+            }
+        }
+        lmax = wave_max(lmax);
+        if ((threadIdx.x & 63) == 0) wmax[(cur ^ 1) * 4 + wave] = lmax;
+        chunk_sync<D>();
+        if (active) {
+            float m;
+            if constexpr (M::WPC == 4) {
+                m = fmaxf(fmaxf(wmax[(cur ^ 1) * 4], wmax[(cur ^ 1) * 4 + 1]),
+                          fmaxf(wmax[(cur ^ 1) * 4 + 2], wmax[(cur ^ 1) * 4 + 3]));
+            } else {
+                m = lmax;   // one wave per chunk: the wave's maximum is the chunk's
+            }
+            off = (m == -INFINITY) ? 0.0f : m;
+        }
+        cur ^= 1;
+    }
+    if (cc.nsteps > 0) {
+        const float* pf = cur ? p1 : p0;
+        float* dst = agg + (size_t)chunk * D * D;
+#pragma unroll 4
+        for (int r = 0; r < M::RPG; ++r) {
+            const int i = rg * M::RPG + r;
+            dst[(size_t)i * D + j] = pf[i * D + j] - off;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// V at chunk boundaries.  One workgroup per sequence; lane = (column j, part q of the max over i).
+// vin[c] = V just before chunk c (log prior for c = 0, afterwards shifted to max 0).
+template <int D>
+__global__ __launch_bounds__(256) void lv_carry_kernel(const float* __restrict__ prior, int Dr, int cps,
+                                                       int shared_model, const float* __restrict__ agg,
+                                                       float* __restrict__ vin) {
+    constexpr int Q = 256 / D;
+    constexpr int RPT = D / Q;
+    __shared__ float vec[D];
+    __shared__ float partial[Q * D];
+    __shared__ float max_lds;
+    const int seq = blockIdx.x;
+    const int j = threadIdx.x % D, q = threadIdx.x / D;
+    const float* mats = agg + (size_t)seq * cps * D * D;
+    float* out = vin + (size_t)seq * cps * D;
+    float v = (j < Dr) ? safe_log(prior[(shared_model ? 0 : (size_t)seq * Dr) + j]) : -INFINITY;
+    float pv[RPT];
+    auto load_mat = [&](int c) {
+        const float* Mx = mats + (size_t)c * D * D;
+#pragma unroll
+        for (int r = 0; r < RPT; ++r) pv[r] = Mx[(size_t)(q * RPT + r) * D + j];
+    };
+    load_mat(0);
+    for (int c = 0; c < cps; ++c) {
+        if (q == 0) {
+            out[(size_t)c * D + j] = v;
+            vec[j] = v;
+        }
+        __syncthreads();
+        float acc = -INFINITY;
+#pragma unroll
+        for (int r = 0; r < RPT; ++r) acc = fmaxf(acc, vec[q * RPT + r] + pv[r]);
+        if (c + 1 < cps) load_mat(c + 1);
+        partial[q * D + j] = acc;
+        __syncthreads();
+        float g = -INFINITY;
+        if (q == 0) {
+#pragma unroll
+            for (int p = 0; p < Q; ++p) g = fmaxf(g, partial[p * D + j]);
+        }
+        if (threadIdx.x < 64) {
+            float m = -INFINITY;
+            for (int jj = threadIdx.x; jj < D; jj += 64) {
+#pragma unroll
+                for (int p = 0; p < Q; ++p) m = fmaxf(m, partial[p * D + jj]);
+            }
+            m = wave_max(m);
+            if (threadIdx.x == 0) max_lds = (m == -INFINITY) ? 0.0f : m;
+        }
+        __syncthreads();
+        v = g - max_lds;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Forward max-plus recursion with back-pointers inside the chunks, the chunk's back-pointer map
+// and log-probability growth.  Lane = (column j inside the wave, part h of the max over i), log A
+// in registers; back-pointers are kept in LDS for the map composition and copied to the workspace.
+template <int D>
+__global__ __launch_bounds__(256) void lv_forward_kernel(const float* __restrict__ prior, const float* __restrict__ A,
+                                                         const float* __restrict__ ll, long long T, int Dr, int Lc,
+                                                         int cps, long long nchunks, int shared_model,
+                                                         const float* __restrict__ vin, uint8_t* __restrict__ bp,
+                                                         uint8_t* __restrict__ cmap, int* __restrict__ xstar,
+                                                         double* __restrict__ part) {
+    using C = LargeCfg<D>;
+    extern __shared__ __align__(16) unsigned char dyn_lds[];   // back-pointers of the workgroup's chunks
+    __shared__ __align__(16) float vbuf[2 * C::VCPW * D];
+    __shared__ float wmaxs[2 * C::VCPW * C::VWPC];
+    __shared__ float red_v[C::VCPW * 4];
+    __shared__ int red_i[C::VCPW * 4];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int cl = wave / C::VWPC, wv = wave % C::VWPC;
+    const int jl = lane % C::CPWV, h = lane / C::CPWV;
+    const int j = C::CPWV * wv + jl;
+    const long long chunk = (long long)blockIdx.x * C::VCPW + cl;
+    const ChunkCoord cc = chunk_coord(chunk, nchunks, cps, T, Lc);
+    const float* Am = A + (shared_model ? 0 : (size_t)cc.seq * Dr * Dr);
+    uint8_t* bpl = dyn_lds + (size_t)cl * Lc * D;
+    float lareg[C::RPP];
+#pragma unroll
+    for (int r = 0; r < C::RPP; ++r) {
+        const int i = h * C::RPP + r;
+        float v = (i == j) ? 0.0f : -INFINITY;
+        if (i < Dr && j < Dr) v = safe_log(Am[(size_t)i * Dr + j]);
+        lareg[r] = v;
+    }
+    const float* lseq = ll + (size_t)cc.seq * T * Dr;
+    const bool first_chunk = (chunk % cps) == 0;
+    float v0 = -INFINITY;
+    if (cc.nsteps > 0) {
+        if (first_chunk) v0 = (j < Dr) ? safe_log(prior[(shared_model ? 0 : (size_t)cc.seq * Dr) + j]) : -INFINITY;
+        else v0 = vin[(size_t)chunk * D + j];
+    }
+    if (h == 0) vbuf[cl * D + j] = v0;
+    {
+        const float m = wave_max(v0);
+        if (lane == 0) wmaxs[cl * C::VWPC + wv] = m;
+    }
+    __syncthreads();
+    // level the chunk starts from: 0 for the log prior (nothing is removed at the first step), else the
+    // carry's maximum (0 up to rounding, since the carry kernel shifts it there)
+    float start = 0.0f;
+    if (!first_chunk) {
+        start = wmaxs[cl * C::VWPC];
+#pragma unroll
+        for (int w = 1; w < C::VWPC; ++w) start = fmaxf(start, wmaxs[cl * C::VWPC + w]);
+        start = (start == -INFINITY) ? 0.0f : start;
+    }
+    __syncthreads();
+    // offset applied one step late
+    float off = start;
+    double osum = 0.0;
+    int cur = 0;
+    float xn = -INFINITY;
+    if (cc.nsteps > 0 && j < Dr) xn = lseq[(size_t)cc.t0 * Dr + j];
+    float vlast = v0;
+    for (int s = 0; s < Lc; ++s) {
+        const bool active = s < cc.nsteps;
+        const float x = xn;
+        if (s + 1 < cc.nsteps && j < Dr) xn = lseq[(size_t)(cc.t0 + s + 1) * Dr + j];
+        const float* vc = vbuf + (cur * C::VCPW + cl) * D;
+        float* vn = vbuf + ((cur ^ 1) * C::VCPW + cl) * D;
+        float* wn = wmaxs + ((cur ^ 1) * C::VCPW + cl) * C::VWPC;
+        float gval = -INFINITY;
+        if (active) {
+            int arg = j;
+            if (cc.t0 + s == 0) {
+                gval = vc[j] + x;   // V_1 = log prior + ll_1
+            } else {
+                float best = -INFINITY;
+                int bi = h * C::RPP;
+#pragma unroll
+                for (int r4 = 0; r4 < C::RPP; r4 += 4) {
+                    const float4 v4 = *reinterpret_cast<const float4*>(vc + h * C::RPP + r4);
+                    const float c0 = v4.x + lareg[r4], c1 = v4.y + lareg[r4 + 1];
+                    const float c2 = v4.z + lareg[r4 + 2], c3 = v4.w + lareg[r4 + 3];
+                    if (c0 > best) { best = c0; bi = h * C::RPP + r4; }        // strict: lowest index wins ties
+                    if (c1 > best) { best = c1; bi = h * C::RPP + r4 + 1; }
+                    if (c2 > best) { best = c2; bi = h * C::RPP + r4 + 2; }
+                    if (c3 > best) { best = c3; bi = h * C::RPP + r4 + 3; }
+                }
+                // combine the parts: a higher part wins only if strictly better
+#pragma unroll
+                for (int d = C::CPWV; d < 64; d <<= 1) {
+                    const float ob = __shfl_xor(best, d, 64);
+                    const int oi = __shfl_xor(bi, d, 64);
+                    const bool take = (ob > best) || (ob == best && oi < bi);
+                    best = take ? ob : best;
+                    bi = take ? oi : bi;
+                }
+                gval = best + (x - off);
+                arg = bi;
+            }
+            if (h == 0) {
+                vn[j] = gval;
+                bpl[(size_t)s * D + j] = (uint8_t)arg;
+            }
+            const float mw = wave_max(gval);
+            if (lane == 0) wn[wv] = mw;
+        }
+        __syncthreads();
+        if (active) {
+            float m = wn[0];
+#pragma unroll
+            for (int w = 1; w < C::VWPC; ++w) m = fmaxf(m, wn[w]);
+            // V_s as stored equals the true V_s minus the offsets removed so far; its max is the next offset
+            osum += (double)((cc.t0 + s == 0) ? 0.0f : off);
+            off = (m == -INFINITY) ? 0.0f : m;
+            vlast = gval;
+        }
+        cur ^= 1;
+    }
+    // chunk-local growth of max_j V: offsets removed plus what is left in the last stored vector
+    const bool live = cc.nsteps > 0;
+    if (live && lane == 0 && wv == 0) part[chunk] = osum + (double)off - (double)start;
+    __syncthreads();
+    // copy the chunk's back-pointers to the workspace (coalesced)
+    if (live) {
+        uint8_t* dst = bp + ((size_t)cc.seq * T + cc.t0) * D;
+        const int nbytes = cc.nsteps * D;
+        const int tic = threadIdx.x - cl * C::VWPC * 64;
+        for (int idx = tic * 4; idx < nbytes; idx += C::VWPC * 64 * 4)
+            *reinterpret_cast<uint32_t*>(dst + idx) = *reinterpret_cast<const uint32_t*>(bpl + idx);
+    }
+    // x*_T in the sequence's last chunk: argmax over j of the last V, lowest index on ties
+    const bool last_chunk = live && (chunk % cps) == cps - 1;
+    int xs = 0;
+    if (last_chunk) {
+        float bv = (h == 0) ? vlast : -INFINITY;
+        int bi = j;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const float ob = __shfl_xor(bv, d, 64);
+            const int oi = __shfl_xor(bi, d, 64);
+            const bool take = (ob > bv) || (ob == bv && oi < bi);
+            bv = take ? ob : bv;
+            bi = take ? oi : bi;
+        }
+        if (lane == 0) { red_v[cl * 4 + wv] = bv; red_i[cl * 4 + wv] = bi; }
+    }
+    __syncthreads();
+    if (last_chunk) {
+        float bv = red_v[cl * 4];
+        xs = red_i[cl * 4];
+#pragma unroll
+        for (int w = 1; w < C::VWPC; ++w) {
+            const float ob = red_v[cl * 4 + w];
+            const int oi = red_i[cl * 4 + w];
+            if (ob > bv || (ob == bv && oi < xs)) { bv = ob; xs = oi; }
+        }
+        if (lane == 0 && wv == 0) xstar[cc.seq] = xs;
+    }
+    // chunk map: hmap(j) = state at the step before the chunk given state j at its last step
+    if (live && h == 0) {
+        int hm = j;
+        for (int s = cc.nsteps - 1; s >= 0; --s) hm = bpl[(size_t)s * D + hm];
+        if (last_chunk) {
+            // every state maps to the image of x*_T
+            int hx = xs;
+            for (int s = cc.nsteps - 1; s >= 0; --s) hx = bpl[(size_t)s * D + hx];
+            hm = hx;
+        }
+        cmap[(size_t)chunk * D + j] = (uint8_t)hm;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// State at every chunk's last step (chunk maps applied right to left from x*_T) and the
+// sequence's log-probability.  One workgroup per sequence; the maps are chased through LDS.
+template <int D>
+__global__ __launch_bounds__(256) void lv_suffix_kernel(const uint8_t* __restrict__ cmap, const int* __restrict__ xstar,
+                                                        int cps, int* __restrict__ xend,
+                                                        const double* __restrict__ part, double* __restrict__ logprob) {
+    constexpr int PIECE = 128;                       // chunk maps staged per round
+    __shared__ __align__(16) uint8_t maps[PIECE * D];
+    __shared__ double sh[256];
+    __shared__ int xcur;
+    const int seq = blockIdx.x;
+    if (threadIdx.x == 0) xcur = xstar[seq];
+    for (int hi = cps; hi > 0; hi -= PIECE) {
+        const int lo = hi > PIECE ? hi - PIECE : 0;
+        const int n = (hi - lo) * D;
+        const uint8_t* src = cmap + ((size_t)seq * cps + lo) * D;
+        for (int idx = threadIdx.x * 4; idx < n; idx += 256 * 4)
+            *reinterpret_cast<uint32_t*>(maps + idx) = *reinterpret_cast<const uint32_t*>(src + idx);
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            int x = xcur;
+            for (int c = hi - 1; c >= lo; --c) {
+                xend[(size_t)seq * cps + c] = x;
+                x = maps[(c - lo) * D + x];
+            }
+            xcur = x;
+        }
+        __syncthreads();
+    }
+    double acc = 0.0;
+    for (int c = threadIdx.x; c < cps; c += 256) acc += part[(size_t)seq * cps + c];
+    sh[threadIdx.x] = acc;
+    __syncthreads();
+    for (int d = 128; d >= 1; d >>= 1) {
+        if ((int)threadIdx.x < d) sh[threadIdx.x] += sh[threadIdx.x + d];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) logprob[seq] = sh[0];
+}
+
+// ---------------------------------------------------------------------------------------------
+// Back-pointer walk inside each chunk from the state at its last step; coalesced path write.
+template <int D>
+__global__ __launch_bounds__(256) void lv_path_kernel(long long T, int Lc, int cps, long long nchunks,
+                                                      const uint8_t* __restrict__ bp, const int* __restrict__ xend,
+                                                      int32_t* __restrict__ path) {
+    extern __shared__ __align__(16) unsigned char dyn_lds[];   // [Lc*D] back-pointers, then [Lc] path (int32)
+    const long long chunk = blockIdx.x;
+    const ChunkCoord cc = chunk_coord(chunk, nchunks, cps, T, Lc);
+    uint8_t* bpl = dyn_lds;
+    int32_t* pl = reinterpret_cast<int32_t*>(dyn_lds + (size_t)Lc * D);
+    const uint8_t* src = bp + ((size_t)cc.seq * T + cc.t0) * D;
+    const int nbytes = cc.nsteps * D;
+    for (int idx = threadIdx.x * 4; idx < nbytes; idx += 256 * 4)
+        *reinterpret_cast<uint32_t*>(bpl + idx) = *reinterpret_cast<const uint32_t*>(src + idx);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int x = xend[chunk];
+        for (int s = cc.nsteps - 1; s >= 0; --s) {
+            pl[s] = x;
+            x = bpl[(size_t)s * D + x];
+        }
+    }
+    __syncthreads();
+    int32_t* dst = path + (size_t)cc.seq * T + cc.t0;
+    for (int s = threadIdx.x; s < cc.nsteps; s += 256) dst[s] = pl[s];
+}
+
+// =============================================================================================
+// Host side
+// =============================================================================================
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Chunking for the max-plus path: the back-pointers of a chunk must fit in LDS (Lc * DP <= 48 KiB).
+static LargePlan viterbi_plan(int Dr, long long T, int batch) {
+    LargePlan p = large_plan(Dr, T, batch);
+    const int vcpw = p.DP >= 128 ? 1 : p.DP >= 64 ? 2 : 4;   // chunks sharing a workgroup in the forward kernel
+    const int cap = (48 * 1024) / (p.DP * vcpw) / 16 * 16;
+    if (p.Lc > cap) {
+        p.Lc = cap;
+        p.cps = (int)((T + p.Lc - 1) / p.Lc);
+        p.nchunks = (long long)p.cps * batch;
+    }
+    return p;
+}
+
+struct LargeViterbiWs { size_t agg, vin, bp, cmap, xend, xstar, part, total; };
+
+static LargeViterbiWs large_viterbi_ws(int Dr, long long T, int batch) {
+    const LargePlan p = viterbi_plan(Dr, T, batch);
+    const size_t D = p.DP, nc = (size_t)p.nchunks, rows = (size_t)T * batch;
+    LargeViterbiWs w;
+    size_t o = 0;
+    w.agg = o;   o = align_up(o + nc * D * D * sizeof(float), 256);
+    w.vin = o;   o = align_up(o + nc * D * sizeof(float), 256);
+    w.bp = o;    o = align_up(o + rows * D + 16, 256);
+    w.cmap = o;  o = align_up(o + nc * D, 256);
+    w.xend = o;  o = align_up(o + nc * sizeof(int), 256);
+    w.xstar = o; o = align_up(o + (size_t)batch * sizeof(int), 256);
+    w.part = o;  o = align_up(o + nc * sizeof(double), 256);
+    w.total = o;
+    return w;
+}
+
+size_t large_d_viterbi_ws_bytes(int Dr, long long T, int batch) { return large_viterbi_ws(Dr, T, batch).total; }
+
+template <int D>
+static int large_viterbi_impl(const LargeArgs& a, int32_t* path, double* logprob_out) {
+    using C = LargeCfg<D>;
+    using M = MpCfg<D>;
+    const LargePlan p = viterbi_plan(a.D, a.T, a.batch);
+    const LargeViterbiWs w = large_viterbi_ws(a.D, a.T, a.batch);
+    if (a.ws_bytes < w.total) return 3;
+    if (p.nchunks > 0x7fffffffLL) return 2;
+    char* ws = static_cast<char*>(a.ws);
+    float* agg = reinterpret_cast<float*>(ws + w.agg);
+    float* vin = reinterpret_cast<float*>(ws + w.vin);
+    uint8_t* bp = reinterpret_cast<uint8_t*>(ws + w.bp);
+    uint8_t* cmap = reinterpret_cast<uint8_t*>(ws + w.cmap);
+    int* xend = reinterpret_cast<int*>(ws + w.xend);
+    int* xstar = reinterpret_cast<int*>(ws + w.xstar);
+    double* part = reinterpret_cast<double*>(ws + w.part);
+    hipStream_t st = a.stream;
+    const dim3 block(256);
+    launch("lv_aggregate", lv_aggregate_kernel<D>, dim3((unsigned)((p.nchunks + M::CPW - 1) / M::CPW)), block, st, a.A,
+           a.ll, a.T, a.D, p.Lc, p.cps, p.nchunks, a.shared_model, agg);
+    launch("lv_carry", lv_carry_kernel<D>, dim3((unsigned)a.batch), block, st, a.prior, a.D, p.cps, a.shared_model, agg,
+           vin);
+    const size_t fwd_lds = (size_t)C::VCPW * p.Lc * D;
+    launch_dyn("lv_forward", lv_forward_kernel<D>, dim3((unsigned)((p.nchunks + C::VCPW - 1) / C::VCPW)), block, fwd_lds,
+               st, a.prior, a.A, a.ll, a.T, a.D, p.Lc, p.cps, p.nchunks, a.shared_model, vin, bp, cmap, xstar, part);
+    launch("lv_suffix", lv_suffix_kernel<D>, dim3((unsigned)a.batch), block, st, cmap, xstar, p.cps, xend, part,
+           logprob_out);
+    const size_t path_lds = (size_t)p.Lc * D + (size_t)p.Lc * sizeof(int32_t);
+    launch_dyn("lv_path", lv_path_kernel<D>, dim3((unsigned)p.nchunks), block, path_lds, st, a.T, p.Lc, p.cps, p.nchunks,
+               bp, xend, path);
+    return hipGetLastError() == hipSuccess ? 0 : 4;
+}
+
+int large_d_viterbi(const LargeArgs& a, int32_t* path, double* logprob_out) {
+    const int DP = large_plan(a.D, a.T, a.batch).DP;
+    switch (DP) {
+        case 16: return large_viterbi_impl<16>(a, path, logprob_out);
+        case 32: return large_viterbi_impl<32>(a, path, logprob_out);
+        case 64: return large_viterbi_impl<64>(a, path, logprob_out);
+        case 128: return large_viterbi_impl<128>(a, path, logprob_out);
+        default: return 2;
+    }
+}
+
+}  // namespace hmm

@@ -1,5 +1,5 @@
-"""GPU parity, large state spaces (9 <= D <= 128): the matrix-core sum-product path through the
-C ABI against the CPU oracle, element by element."""
+"""GPU parity, large state spaces (9 <= D <= 128): the matrix-core sum-product path and the
+vector-ALU max-plus path through the C ABI against the CPU oracle, element by element."""
 import numpy as np
 import pytest
 
@@ -19,6 +19,7 @@ def gu():
 def test_random_models_smoother(gu, D, T):
     p = wl.random_problem(D, T, seed=1000 + 10 * D + T % 7)
     gu.check_smooth(p, want_filtered=(T == 700))
+    gu.check_viterbi(p)
 
 
 @pytest.mark.parametrize("D,T,B,shared", [(16, 900, 5, False), (32, 1500, 3, True), (64, 257, 4, False),
@@ -26,18 +27,25 @@ def test_random_models_smoother(gu, D, T):
 def test_batched_smoother(gu, D, T, B, shared):
     p = wl.random_problem(D, T, batch=B, shared_model=shared, seed=50 + D + B)
     gu.check_smooth(p, want_filtered=True)
+    gu.check_viterbi(p)
 
 
 def test_config3_shape(gu):
-    gu.check_smooth(wl.config3(T=20000), want_filtered=True, label="C3 T=20000")
+    p = wl.config3(T=20000)
+    gu.check_smooth(p, want_filtered=True, label="C3 T=20000")
+    gu.check_viterbi(p, label="C3 T=20000")
 
 
 def test_config4_shape(gu):
-    gu.check_smooth(wl.config4(batch=12, T=4096), label="C4 B=12")
+    p = wl.config4(batch=12, T=4096)
+    gu.check_smooth(p, label="C4 B=12")
+    gu.check_viterbi(p, label="C4 B=12")
 
 
 def test_config5_shape(gu):
-    gu.check_smooth(wl.config5(T=6000), want_filtered=True, label="C5 T=6000")
+    p = wl.config5(T=6000)
+    gu.check_smooth(p, want_filtered=True, label="C5 T=6000")
+    gu.check_viterbi(p, label="C5 T=6000")
 
 
 def test_sparse_transitions_and_impossible_emissions(gu):
@@ -47,3 +55,4 @@ def test_sparse_transitions_and_impossible_emissions(gu):
     mask[..., 0] = False
     p.loglik[mask] = -np.inf
     gu.check_smooth(p, want_filtered=True)
+    gu.check_viterbi(p)
