@@ -61,19 +61,40 @@ HMM_DEV typename AccT<TS>::type mfma_step(float a, float b, typename AccT<TS>::t
     else return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
 }
 
-// max over the 64 lanes of a wave, result in every lane
-HMM_DEV float wave_max(float v) {
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) v = fmaxf(v, __shfl_xor(v, d, 64));
-    return v;
+// Wave-wide reductions with DPP moves (four shifts inside each row of 16 lanes, then the last lane
+// of a row broadcast into the following rows); lane 63 ends with the total, which is then
+// broadcast through a scalar register.  Lanes without a source at some level take the neutral value.
+template <int CTRL, int ROW_MASK>
+HMM_DEV float dpp_take(float neutral, float src) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(neutral), __float_as_int(src), CTRL, ROW_MASK,
+                                                      0xF, false));
 }
 
-// sum over the 64 lanes of a wave, result in every lane
-HMM_DEV float wave_sum(float v) {
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
-    return v;
+HMM_DEV float wave_max(float v) {
+    v = fmaxf(v, dpp_take<0x111, 0xF>(-INFINITY, v));   // row_shr:1
+    v = fmaxf(v, dpp_take<0x112, 0xF>(-INFINITY, v));   // row_shr:2
+    v = fmaxf(v, dpp_take<0x114, 0xF>(-INFINITY, v));   // row_shr:4
+    v = fmaxf(v, dpp_take<0x118, 0xF>(-INFINITY, v));   // row_shr:8
+    v = fmaxf(v, dpp_take<0x142, 0xA>(-INFINITY, v));   // row_bcast:15
+    v = fmaxf(v, dpp_take<0x143, 0xC>(-INFINITY, v));   // row_bcast:31
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
+
+HMM_DEV float wave_sum(float v) {
+    v += dpp_take<0x111, 0xF>(0.0f, v);
+    v += dpp_take<0x112, 0xF>(0.0f, v);
+    v += dpp_take<0x114, 0xF>(0.0f, v);
+    v += dpp_take<0x118, 0xF>(0.0f, v);
+    v += dpp_take<0x142, 0xA>(0.0f, v);
+    v += dpp_take<0x143, 0xC>(0.0f, v);
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
+
+// value of the lane whose index differs in bit 0 / bit 1 (inside a quad)
+HMM_DEV float quad_xor1(float v) { return dpp_take<0xB1, 0xF>(v, v); }   // quad_perm [1,0,3,2]
+HMM_DEV float quad_xor2(float v) { return dpp_take<0x4E, 0xF>(v, v); }   // quad_perm [2,3,0,1]
+HMM_DEV int quad_xor1(int v) { return __builtin_amdgcn_update_dpp(v, v, 0xB1, 0xF, 0xF, false); }
+HMM_DEV int quad_xor2(int v) { return __builtin_amdgcn_update_dpp(v, v, 0x4E, 0xF, 0xF, false); }
 
 struct ChunkCoord {
     int seq;        // sequence

@@ -253,24 +253,36 @@ __global__ __launch_bounds__(256) void ld_carry_kernel(const float* __restrict__
 }
 
 // ---------------------------------------------------------------------------------------------
-// Forward potentials inside the chunks (Theorem 1): f_k = (f_{k-1} A) o e_k, written normalised
-// (= p(x_k | y_{1:k})), plus each chunk's log evidence log p(y_chunk | y_before).
-// Lane = (column j inside the wave, part h of the summation over i); A stays in registers.
+// Vector recursions inside the chunks.  Lane = (column or row c inside the wave, part h of the
+// summation range), with h in the lowest lane bits so that parts are combined with quad
+// permutes; A stays in registers.  A chunk of D <= 32 is one wave and needs no workgroup barrier.
 template <int D>
-__global__ __launch_bounds__(256) void ld_forward_kernel(const float* __restrict__ prior, const float* __restrict__ A,
-                                                         const float* __restrict__ ll,
-                                                         const float* __restrict__ rowmax, long long T, int Dr, int Lc,
-                                                         int cps, long long nchunks, int shared_model,
-                                                         const float* __restrict__ fin, float* __restrict__ F,
-                                                         double* __restrict__ part) {
+HMM_DEV void apply_sync() {
+    if constexpr (LargeCfg<D>::VWPC > 1) __syncthreads();
+    else __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+}
+
+template <int D>
+HMM_DEV float combine_parts(float acc) {
     using C = LargeCfg<D>;
-    __shared__ __align__(16) float fbuf[2 * C::VCPW * D];
-    __shared__ float wsum[2 * C::VCPW * C::VWPC];
+    acc += quad_xor1(acc);
+    if constexpr (C::PARTS == 4) acc += quad_xor2(acc);
+    return acc;
+}
+
+// Forward potentials (Theorem 1): f_k = (f_{k-1} A) o e_k, written normalised (= p(x_k | y_{1:k})),
+// plus the chunk's log evidence log p(y_chunk | y_before).
+template <int D>
+HMM_DEV void forward_chunk(const float* __restrict__ prior, const float* __restrict__ A, const float* __restrict__ ll,
+                           const float* __restrict__ rowmax, long long T, int Dr, int Lc, int cps, long long nchunks,
+                           int shared_model, const float* __restrict__ fin, float* __restrict__ F,
+                           double* __restrict__ part, long long chunk0, float* fbuf, float* wsum) {
+    using C = LargeCfg<D>;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int cl = wave / C::VWPC, wv = wave % C::VWPC;
-    const int jl = lane % C::CPWV, h = lane / C::CPWV;
-    const int j = C::CPWV * wv + jl;
-    const long long chunk = (long long)blockIdx.x * C::VCPW + cl;
+    const int h = lane % C::PARTS;
+    const int j = C::CPWV * wv + lane / C::PARTS;
+    const long long chunk = chunk0 + cl;
     const ChunkCoord cc = chunk_coord(chunk, nchunks, cps, T, Lc);
     const float* Am = A + (shared_model ? 0 : (size_t)cc.seq * Dr * Dr);
     float areg[C::RPP];
@@ -283,26 +295,25 @@ __global__ __launch_bounds__(256) void ld_forward_kernel(const float* __restrict
     const float* lseq = ll + (size_t)cc.seq * T * Dr;
     const float* mseq = rowmax + (size_t)cc.seq * T;
     float* Fseq = F + (size_t)cc.seq * T * Dr;
+    const bool first_chunk = (chunk % cps) == 0;
     // carry into the chunk; every chunk but the sequence's first starts from a vector summing to one
     float f0 = 0.0f;
     if (cc.nsteps > 0) {
-        if (chunk % cps == 0) f0 = (j < Dr) ? prior[(shared_model ? 0 : (size_t)cc.seq * Dr) + j] : 0.0f;
+        if (first_chunk) f0 = (j < Dr) ? prior[(shared_model ? 0 : (size_t)cc.seq * Dr) + j] : 0.0f;
         else f0 = fin[(size_t)chunk * D + j];
     }
-    float* fb = fbuf + cl * D;
-    float* ws = wsum + cl * C::VWPC;
-    if (h == 0) fb[j] = f0;
+    if (h == 0) fbuf[cl * D + j] = f0;
     {
         const float s = wave_sum(h == 0 ? f0 : 0.0f);
-        if (lane == 0) ws[wv] = s;
+        if (lane == 0) wsum[cl * C::VWPC + wv] = s;
     }
-    __syncthreads();
+    apply_sync<D>();
     float inv = 1.0f;
-    if (chunk % cps != 0) {
+    if (!first_chunk) {
         float tot = 0.0f;
 #pragma unroll
-        for (int w = 0; w < C::VWPC; ++w) tot += ws[w];
-        inv = 1.0f / tot;
+        for (int w = 0; w < C::VWPC; ++w) tot += wsum[cl * C::VWPC + w];
+        inv = __builtin_amdgcn_rcpf(tot);
     }
     double dacc = 0.0;
     int cur = 0;
@@ -311,7 +322,8 @@ __global__ __launch_bounds__(256) void ld_forward_kernel(const float* __restrict
         mn = mseq[cc.t0];
         if (j < Dr) xn = lseq[(size_t)cc.t0 * Dr + j];
     }
-    for (int s = 0; s < Lc; ++s) {
+    const int nloop = (C::VWPC > 1) ? Lc : cc.nsteps;   // with workgroup barriers every wave runs the full count
+    for (int s = 0; s < nloop; ++s) {
         const bool active = s < cc.nsteps;
         const float x = xn, m = mn;
         if (s + 1 < cc.nsteps) {
@@ -337,20 +349,19 @@ __global__ __launch_bounds__(256) void ld_forward_kernel(const float* __restrict
                     acc = fmaf(f4.z, areg[r4 + 2], acc);
                     acc = fmaf(f4.w, areg[r4 + 3], acc);
                 }
-#pragma unroll
-                for (int d = C::CPWV; d < 64; d <<= 1) acc += __shfl_xor(acc, d, 64);
+                acc = combine_parts<D>(acc);
                 gval = acc * inv * e;
             }
             if (h == 0) fn[j] = gval;
             const float sw = wave_sum(h == 0 ? gval : 0.0f);
             if (lane == 0) wn[wv] = sw;
         }
-        __syncthreads();
+        apply_sync<D>();
         if (active) {
             float tot = 0.0f;
 #pragma unroll
             for (int w = 0; w < C::VWPC; ++w) tot += wn[w];
-            inv = 1.0f / tot;
+            inv = __builtin_amdgcn_rcpf(tot);
             if (h == 0 && j < Dr) Fseq[(size_t)(cc.t0 + s) * Dr + j] = gval * inv;
             if (lane == 0 && wv == 0) dacc += (double)m + (double)__logf(tot);
         }
@@ -359,23 +370,19 @@ __global__ __launch_bounds__(256) void ld_forward_kernel(const float* __restrict
     if (cc.nsteps > 0 && lane == 0 && wv == 0) part[chunk] = dacc;
 }
 
-// ---------------------------------------------------------------------------------------------
-// Backward potentials inside the chunks (Theorem 2): b_{k-1} = A (e_k o b_k), stored with an
-// arbitrary positive scale per step.  Lane = (row i inside the wave, part h of the summation
-// over j); A stays in registers.
+// Backward potentials (Theorem 2): b_{k-1} = A (e_k o b_k), stored with an arbitrary positive
+// scale per step (the marginal is normalised afterwards).
 template <int D>
-__global__ __launch_bounds__(256) void ld_backward_kernel(const float* __restrict__ A, const float* __restrict__ ll,
-                                                          const float* __restrict__ rowmax, long long T, int Dr,
-                                                          int Lc, int cps, long long nchunks, int shared_model,
-                                                          const float* __restrict__ bout, float* __restrict__ Bv) {
+HMM_DEV void backward_chunk(const float* __restrict__ A, const float* __restrict__ ll,
+                            const float* __restrict__ rowmax, long long T, int Dr, int Lc, int cps, long long nchunks,
+                            int shared_model, const float* __restrict__ bout, float* __restrict__ Bv,
+                            long long chunk0, float* ubuf, float* wsum) {
     using C = LargeCfg<D>;
-    __shared__ __align__(16) float ubuf[2 * C::VCPW * D];
-    __shared__ float wsum[2 * C::VCPW * C::VWPC];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int cl = wave / C::VWPC, wv = wave % C::VWPC;
-    const int il = lane % C::CPWV, h = lane / C::CPWV;
-    const int i = C::CPWV * wv + il;
-    const long long chunk = (long long)blockIdx.x * C::VCPW + cl;
+    const int h = lane % C::PARTS;
+    const int i = C::CPWV * wv + lane / C::PARTS;
+    const long long chunk = chunk0 + cl;
     const ChunkCoord cc = chunk_coord(chunk, nchunks, cps, T, Lc);
     const float* Am = A + (shared_model ? 0 : (size_t)cc.seq * Dr * Dr);
     float areg[C::RPP];
@@ -396,7 +403,8 @@ __global__ __launch_bounds__(256) void ld_backward_kernel(const float* __restric
         mn = mseq[cc.t0 + cc.nsteps - 1];
         if (i < Dr) xn = lseq[(size_t)(cc.t0 + cc.nsteps - 1) * Dr + i];
     }
-    for (int s = Lc - 1; s >= 0; --s) {
+    const int nloop = (C::VWPC > 1) ? Lc : cc.nsteps;
+    for (int s = nloop - 1; s >= 0; --s) {
         const bool active = s < cc.nsteps;
         float* un = ubuf + ((cur ^ 1) * C::VCPW + cl) * D;
         float* wn = wsum + ((cur ^ 1) * C::VCPW + cl) * C::VWPC;
@@ -414,12 +422,12 @@ __global__ __launch_bounds__(256) void ld_backward_kernel(const float* __restric
             const float sw = wave_sum(h == 0 ? bs : 0.0f);
             if (lane == 0) wn[wv] = sw;
         }
-        __syncthreads();
+        apply_sync<D>();
         if (active && s > 0) {
             float tot = 0.0f;
 #pragma unroll
             for (int w = 0; w < C::VWPC; ++w) tot += wn[w];
-            inv = 1.0f / tot;
+            inv = __builtin_amdgcn_rcpf(tot);
             float acc = 0.0f;
 #pragma unroll
             for (int r4 = 0; r4 < C::RPP; r4 += 4) {
@@ -429,12 +437,30 @@ __global__ __launch_bounds__(256) void ld_backward_kernel(const float* __restric
                 acc = fmaf(u4.z, areg[r4 + 2], acc);
                 acc = fmaf(u4.w, areg[r4 + 3], acc);
             }
-#pragma unroll
-            for (int d = C::CPWV; d < 64; d <<= 1) acc += __shfl_xor(acc, d, 64);
-            b = acc;
+            b = combine_parts<D>(acc);
         }
         cur ^= 1;
     }
+}
+
+// One launch for both directions: the first half of the grid runs the forward recursion of its
+// chunks, the second half the backward recursion of the same chunks, concurrently.
+template <int D>
+__global__ __launch_bounds__(256) void ld_apply_kernel(const float* __restrict__ prior, const float* __restrict__ A,
+                                                       const float* __restrict__ ll, const float* __restrict__ rowmax,
+                                                       long long T, int Dr, int Lc, int cps, long long nchunks,
+                                                       int shared_model, const float* __restrict__ fin,
+                                                       const float* __restrict__ bout, float* __restrict__ F,
+                                                       float* __restrict__ Bv, double* __restrict__ part, int half) {
+    using C = LargeCfg<D>;
+    __shared__ __align__(16) float vbuf[2 * C::VCPW * D];
+    __shared__ float wsum[2 * C::VCPW * C::VWPC];
+    if ((int)blockIdx.x < half)
+        forward_chunk<D>(prior, A, ll, rowmax, T, Dr, Lc, cps, nchunks, shared_model, fin, F, part,
+                         (long long)blockIdx.x * C::VCPW, vbuf, wsum);
+    else
+        backward_chunk<D>(A, ll, rowmax, T, Dr, Lc, cps, nchunks, shared_model, bout, Bv,
+                          (long long)(blockIdx.x - half) * C::VCPW, vbuf, wsum);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -494,13 +520,15 @@ static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; 
 LargePlan large_plan(int Dr, long long T, int batch) {
     LargePlan p;
     p.DP = Dr <= 16 ? 16 : Dr <= 32 ? 32 : Dr <= 64 ? 64 : 128;
-    // chunks: enough to occupy every matrix core, few enough that the sequential carry stays short
-    const long long target = p.DP >= 128 ? 256 : p.DP >= 64 ? 512 : 1024;
+    // chunks: enough to occupy every matrix core (smaller states need more, shorter chunks), but no
+    // more than 512 per sequence, because the carry between the chunks of one sequence is sequential
+    const long long target = p.DP >= 128 ? 256 : p.DP >= 64 ? 512 : p.DP >= 32 ? 2048 : 8192;
     long long cps = (target + batch - 1) / batch;
     if (cps < 1) cps = 1;
+    if (cps > 512) cps = 512;
     long long Lc = (T + cps - 1) / cps;
     Lc = (Lc + 15) / 16 * 16;
-    if (Lc < 16) Lc = 16;
+    if (Lc < 32) Lc = 32;
     p.Lc = (int)(Lc > 0x3fffffff ? 0x3fffffff : Lc);
     p.cps = (int)((T + p.Lc - 1) / p.Lc);
     p.nchunks = (long long)p.cps * batch;
@@ -556,11 +584,9 @@ static int large_smooth_impl(const LargeArgs& a, float* marg, float* filt, doubl
            a.ll, rowmax, a.T, a.D, p.Lc, p.cps, p.nchunks, a.shared_model, agg, aggT, exps);
     launch("ld_carry", ld_carry_kernel<D>, dim3(2u * (unsigned)a.batch), block, st, a.prior, a.D, p.cps, a.shared_model,
            agg, aggT, exps, fin, bout);
-    const dim3 vgrid((unsigned)((p.nchunks + C::VCPW - 1) / C::VCPW));
-    launch("ld_forward", ld_forward_kernel<D>, vgrid, block, st, a.prior, a.A, a.ll, rowmax, a.T, a.D, p.Lc, p.cps,
-           p.nchunks, a.shared_model, fin, F, part);
-    launch("ld_backward", ld_backward_kernel<D>, vgrid, block, st, a.A, a.ll, rowmax, a.T, a.D, p.Lc, p.cps, p.nchunks,
-           a.shared_model, bout, Bv);
+    const int half = (int)((p.nchunks + C::VCPW - 1) / C::VCPW);
+    launch("ld_apply", ld_apply_kernel<D>, dim3(2u * (unsigned)half), block, st, a.prior, a.A, a.ll, rowmax, a.T, a.D,
+           p.Lc, p.cps, p.nchunks, a.shared_model, fin, bout, F, Bv, part, half);
     const int lpr = (a.D + 3) / 4;
     int width = 1;
     while (width < lpr) width <<= 1;
