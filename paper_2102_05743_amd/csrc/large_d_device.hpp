@@ -96,6 +96,11 @@ HMM_DEV float quad_xor2(float v) { return dpp_take<0x4E, 0xF>(v, v); }   // quad
 HMM_DEV int quad_xor1(int v) { return __builtin_amdgcn_update_dpp(v, v, 0xB1, 0xF, 0xF, false); }
 HMM_DEV int quad_xor2(int v) { return __builtin_amdgcn_update_dpp(v, v, 0x4E, 0xF, 0xF, false); }
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every outstanding
+// global load and store of the wave (its fence covers global memory), which puts a full memory
+// round trip on the critical path of loops that store a result or prefetch an input per step.
+HMM_DEV void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 struct ChunkCoord {
     int seq;        // sequence
     int cidx;       // chunk index inside the sequence

@@ -34,7 +34,7 @@ HMM_DEV float max3f(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
 
 template <int D>
 HMM_DEV void chunk_sync() {
-    if constexpr (MpCfg<D>::WPC == 4) __syncthreads();
+    if constexpr (MpCfg<D>::WPC == 4) lds_barrier();
     else __builtin_amdgcn_wave_barrier();
 }
 
@@ -166,13 +166,13 @@ __global__ __launch_bounds__(256) void lv_carry_kernel(const float* __restrict__
             out[(size_t)c * D + j] = v;
             vec[j] = v;
         }
-        __syncthreads();
+        lds_barrier();
         float acc = -INFINITY;
 #pragma unroll
         for (int r = 0; r < RPT; ++r) acc = fmaxf(acc, vec[q * RPT + r] + pv[r]);
         if (c + 1 < cps) load_mat(c + 1);
         partial[q * D + j] = acc;
-        __syncthreads();
+        lds_barrier();
         float g = -INFINITY;
         if (q == 0) {
 #pragma unroll
@@ -187,7 +187,7 @@ __global__ __launch_bounds__(256) void lv_carry_kernel(const float* __restrict__
             m = wave_max(m);
             if (threadIdx.x == 0) max_lds = (m == -INFINITY) ? 0.0f : m;
         }
-        __syncthreads();
+        lds_barrier();
         v = g - max_lds;
     }
 }
@@ -299,7 +299,7 @@ __global__ __launch_bounds__(256) void lv_forward_kernel(const float* __restrict
             const float mw = wave_max(gval);
             if (lane == 0) wn[wv] = mw;
         }
-        __syncthreads();
+        lds_barrier();
         if (active) {
             float m = wn[0];
 #pragma unroll

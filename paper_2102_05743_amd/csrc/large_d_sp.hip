@@ -190,64 +190,86 @@ __global__ __launch_bounds__(256) void ld_carry_kernel(const float* __restrict__
                                                        const float* __restrict__ aggT, const int* __restrict__ exps,
                                                        float* __restrict__ fin, float* __restrict__ bout) {
     using C = LargeCfg<D>;
-    constexpr int Q = 256 / D;          // lane groups splitting the summation
-    constexpr int RPT = D / Q;          // summation terms per lane
-    __shared__ float vec[D];            // current vector (pre-scaled for dir 0)
-    __shared__ float partial[Q * D];
-    __shared__ float total_lds;
+    constexpr int CG = D / 4;                                   // groups of four columns
+    constexpr int RP = (256 / CG < D) ? 256 / CG : D;           // lane groups splitting the summation
+    constexpr int RPT = D / RP;                                 // summation terms per lane
+    __shared__ __align__(16) float vec[D];                      // current vector (pre-scaled for dir 0)
+    __shared__ __align__(16) float partial[RP * D];
+    __shared__ float wmx[4];
     const int seq = blockIdx.x >> 1, dir = blockIdx.x & 1;
-    const int j = threadIdx.x % D, q = threadIdx.x / D;
+    const int tid = threadIdx.x;
+    const bool worker = tid < CG * RP;
+    const int cg = tid % CG, rp = tid / CG;
+    const int j = tid;                                          // component owned by lanes tid < D
     const float* mats = (dir == 0 ? agg : aggT) + (size_t)seq * cps * D * D;
     const int* ex = exps + (size_t)seq * cps * C::WPC;
     float* out = (dir == 0 ? fin : bout) + (size_t)seq * cps * D;
-    float v = 0.0f;   // component j of the current vector (meaningful where q == 0)
-    if (dir == 0) v = (j < Dr) ? prior[(shared_model ? 0 : (size_t)seq * Dr) + j] : 0.0f;
-    else v = (j < Dr) ? 1.0f : 0.0f;
-    float pv[RPT];
-    auto load_mat = [&](int c) {
+    float v = 0.0f;
+    if (j < D) {
+        if (dir == 0) v = (j < Dr) ? prior[(shared_model ? 0 : (size_t)seq * Dr) + j] : 0.0f;
+        else v = (j < Dr) ? 1.0f : 0.0f;
+    }
+    float4 pm[RPT];
+    int exn[C::WPC];
+    auto load_mat = [&](int c) {   // aggregate c and its strip exponents, prefetched one hop ahead
         const float* M = mats + (size_t)c * D * D;
+        if (worker) {
 #pragma unroll
-        for (int r = 0; r < RPT; ++r) pv[r] = M[(size_t)(q * RPT + r) * D + j];
+            for (int r = 0; r < RPT; ++r) pm[r] = *reinterpret_cast<const float4*>(M + (size_t)(rp * RPT + r) * D + 4 * cg);
+        }
+#pragma unroll
+        for (int s = 0; s < C::WPC; ++s) exn[s] = ex[c * C::WPC + s];
+    };
+    auto strip_exp = [&](const int (&e)[C::WPC], int col) {
+        const int st = col / C::TS;
+        int r = e[0];
+#pragma unroll
+        for (int s = 1; s < C::WPC; ++s) r = (st == s) ? e[s] : r;
+        return r;
     };
     int c = dir == 0 ? 0 : cps - 1;
     load_mat(c);
     for (int it = 0; it < cps; ++it) {
-        if (q == 0) out[(size_t)c * D + j] = v;
-        int exmax = ex[c * C::WPC];
+        int exc[C::WPC];
+        int exmax = exn[0];
 #pragma unroll
-        for (int s = 1; s < C::WPC; ++s) exmax = max(exmax, ex[c * C::WPC + s]);
-        // dir 0 sums over rows of P, whose scale depends on the row's strip: fold it into the vector
-        if (q == 0) vec[j] = (dir == 0) ? ldexpf(v, ex[c * C::WPC + j / C::TS] - exmax) : v;
-        __syncthreads();
-        float acc = 0.0f;
-#pragma unroll
-        for (int r = 0; r < RPT; ++r) acc = fmaf(vec[q * RPT + r], pv[r], acc);
-        const int cn = dir == 0 ? c + 1 : c - 1;
-        if (it + 1 < cps) load_mat(cn);   // next aggregate streams in while this one is reduced
-        partial[q * D + j] = acc;
-        __syncthreads();
-        float gsum = 0.0f;
-        if (q == 0) {
-#pragma unroll
-            for (int p = 0; p < Q; ++p) gsum += partial[p * D + j];
-            // dir 1 produces rows of P: scale by the row's strip
-            if (dir == 1) gsum = ldexpf(gsum, ex[c * C::WPC + j / C::TS] - exmax);
+        for (int s = 0; s < C::WPC; ++s) { exc[s] = exn[s]; exmax = max(exmax, exn[s]); }
+        if (j < D) {
+            out[(size_t)c * D + j] = v;
+            // dir 0 sums over rows of P, whose scale depends on the row's strip: fold it into the vector
+            vec[j] = (dir == 0) ? ldexpf(v, strip_exp(exc, j) - exmax) : v;
         }
-        // normalise by the sum (wave 0 adds the components up)
-        if (threadIdx.x < 64) {
-            float s = 0.0f;
-            for (int jj = threadIdx.x; jj < D; jj += 64) {
-                float t = 0.0f;
+        lds_barrier();
+        float4 acc = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        if (worker) {
 #pragma unroll
-                for (int p = 0; p < Q; ++p) t += partial[p * D + jj];
-                if (dir == 1) t = ldexpf(t, ex[c * C::WPC + jj / C::TS] - exmax);
-                s += t;
+            for (int r = 0; r < RPT; ++r) {
+                const float x = vec[rp * RPT + r];
+                acc.x = fmaf(x, pm[r].x, acc.x);
+                acc.y = fmaf(x, pm[r].y, acc.y);
+                acc.z = fmaf(x, pm[r].z, acc.z);
+                acc.w = fmaf(x, pm[r].w, acc.w);
             }
-            s = wave_sum(s);
-            if (threadIdx.x == 0) total_lds = s;
         }
-        __syncthreads();
-        v = gsum / total_lds;
+        const int cn = dir == 0 ? c + 1 : c - 1;
+        if (it + 1 < cps) load_mat(cn);   // the next aggregate streams in while this one is reduced
+        if (worker) *reinterpret_cast<float4*>(partial + rp * D + 4 * cg) = acc;
+        lds_barrier();
+        float g = 0.0f;
+        if (j < D) {
+#pragma unroll 8
+            for (int p = 0; p < RP; ++p) g += partial[p * D + j];
+            // dir 1 produces rows of P: scale by the row's strip
+            if (dir == 1) g = ldexpf(g, strip_exp(exc, j) - exmax);
+        }
+        // keep the vector in range with an exact power of two (its scale is irrelevant downstream)
+        float m = wave_max(j < D ? g : 0.0f);
+        if constexpr (D > 64) {
+            if ((tid & 63) == 0) wmx[tid >> 6] = m;
+            lds_barrier();
+            m = fmaxf(wmx[0], wmx[1]);
+        }
+        v = ldexpf(g, -__builtin_amdgcn_frexp_expf(m));
         c = cn;
     }
 }
@@ -258,7 +280,7 @@ __global__ __launch_bounds__(256) void ld_carry_kernel(const float* __restrict__
 // permutes; A stays in registers.  A chunk of D <= 32 is one wave and needs no workgroup barrier.
 template <int D>
 HMM_DEV void apply_sync() {
-    if constexpr (LargeCfg<D>::VWPC > 1) __syncthreads();
+    if constexpr (LargeCfg<D>::VWPC > 1) lds_barrier();
     else __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
 }
 
@@ -270,14 +292,74 @@ HMM_DEV float combine_parts(float acc) {
     return acc;
 }
 
+// Emission factors of a chunk, produced EB steps at a time by all lanes of the chunk and kept in
+// double-buffered LDS, so that no global load and no exponential sits on the per-step critical path.
+// Steps are numbered in processing order: rev = false walks t0, t0+1, ...; rev = true walks from
+// the loop's last step downwards.
+template <int D>
+struct EmissionBatches {
+    using C = LargeCfg<D>;
+    static constexpr int EB = 16;
+    static constexpr int LPCH = C::VWPC * 64;            // lanes per chunk
+    static constexpr int EPT = EB * D / LPCH;            // values per lane per batch
+    const float* lseq;
+    const float* mseq;
+    float* e_lds;    // [2][EB*D] of this chunk
+    float* m_lds;    // [2][EB]
+    long long t0;
+    int nsteps, nloop, Dr, tic;
+    bool rev;
+    float er[EPT];
+    float mr;
+
+    HMM_DEV int step_of(int pos) const { return rev ? nloop - 1 - pos : pos; }
+    HMM_DEV void load(int b) {
+#pragma unroll
+        for (int q = 0; q < EPT; ++q) {
+            const int idx = q * LPCH + tic;
+            const int sb = idx / D, jj = idx - sb * D;
+            const int st = step_of(b * EB + sb);
+            float x = -INFINITY, m = 0.0f;
+            if (st >= 0 && st < nsteps) {
+                m = mseq[t0 + st];
+                if (jj < Dr) x = lseq[(size_t)(t0 + st) * Dr + jj];
+            }
+            m = (m == -INFINITY) ? 0.0f : m;
+            er[q] = __builtin_amdgcn_exp2f(fmaf(x, LOG2E, -LOG2E * m));
+        }
+        mr = 0.0f;
+        if (tic < EB) {
+            const int st = step_of(b * EB + tic);
+            if (st >= 0 && st < nsteps) mr = mseq[t0 + st];
+        }
+    }
+    HMM_DEV void store(int b) {
+        float* eb = e_lds + (b & 1) * EB * D;
+#pragma unroll
+        for (int q = 0; q < EPT; ++q) eb[q * LPCH + tic] = er[q];
+        if (tic < EB) m_lds[(b & 1) * EB + tic] = mr;
+    }
+};
+
+// LDS of the apply kernel, per workgroup
+template <int D>
+struct ApplyLds {
+    using C = LargeCfg<D>;
+    __align__(16) float vbuf[2 * C::VCPW * D];
+    float wsum[2 * C::VCPW * C::VWPC];
+    __align__(16) float e[C::VCPW * 2 * 16 * D];
+    float m[C::VCPW * 2 * 16];
+};
+
 // Forward potentials (Theorem 1): f_k = (f_{k-1} A) o e_k, written normalised (= p(x_k | y_{1:k})),
 // plus the chunk's log evidence log p(y_chunk | y_before).
 template <int D>
 HMM_DEV void forward_chunk(const float* __restrict__ prior, const float* __restrict__ A, const float* __restrict__ ll,
                            const float* __restrict__ rowmax, long long T, int Dr, int Lc, int cps, long long nchunks,
                            int shared_model, const float* __restrict__ fin, float* __restrict__ F,
-                           double* __restrict__ part, long long chunk0, float* fbuf, float* wsum) {
+                           double* __restrict__ part, long long chunk0, ApplyLds<D>& L) {
     using C = LargeCfg<D>;
+    using EBt = EmissionBatches<D>;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int cl = wave / C::VWPC, wv = wave % C::VWPC;
     const int h = lane % C::PARTS;
@@ -292,10 +374,18 @@ HMM_DEV void forward_chunk(const float* __restrict__ prior, const float* __restr
         areg[r] = (i == j) ? 1.0f : 0.0f;
         if (i < Dr && j < Dr) areg[r] = Am[(size_t)i * Dr + j];
     }
-    const float* lseq = ll + (size_t)cc.seq * T * Dr;
-    const float* mseq = rowmax + (size_t)cc.seq * T;
     float* Fseq = F + (size_t)cc.seq * T * Dr;
     const bool first_chunk = (chunk % cps) == 0;
+    const int nloop = (C::VWPC > 1) ? Lc : cc.nsteps;   // with workgroup barriers every wave runs the full count
+    EBt eb;
+    eb.lseq = ll + (size_t)cc.seq * T * Dr;
+    eb.mseq = rowmax + (size_t)cc.seq * T;
+    eb.e_lds = L.e + cl * 2 * EBt::EB * D;
+    eb.m_lds = L.m + cl * 2 * EBt::EB;
+    eb.t0 = cc.t0; eb.nsteps = cc.nsteps; eb.nloop = nloop; eb.Dr = Dr; eb.rev = false;
+    eb.tic = threadIdx.x - cl * EBt::LPCH;
+    float* fbuf = L.vbuf;
+    float* wsum = L.wsum;
     // carry into the chunk; every chunk but the sequence's first starts from a vector summing to one
     float f0 = 0.0f;
     if (cc.nsteps > 0) {
@@ -307,6 +397,8 @@ HMM_DEV void forward_chunk(const float* __restrict__ prior, const float* __restr
         const float s = wave_sum(h == 0 ? f0 : 0.0f);
         if (lane == 0) wsum[cl * C::VWPC + wv] = s;
     }
+    const int nb = (nloop + EBt::EB - 1) / EBt::EB;
+    if (nb > 0) { eb.load(0); eb.store(0); }
     apply_sync<D>();
     float inv = 1.0f;
     if (!first_chunk) {
@@ -317,55 +409,51 @@ HMM_DEV void forward_chunk(const float* __restrict__ prior, const float* __restr
     }
     double dacc = 0.0;
     int cur = 0;
-    float xn = -INFINITY, mn = 0.0f;   // next step's log-likelihood and row maximum, prefetched
-    if (cc.nsteps > 0) {
-        mn = mseq[cc.t0];
-        if (j < Dr) xn = lseq[(size_t)cc.t0 * Dr + j];
-    }
-    const int nloop = (C::VWPC > 1) ? Lc : cc.nsteps;   // with workgroup barriers every wave runs the full count
-    for (int s = 0; s < nloop; ++s) {
-        const bool active = s < cc.nsteps;
-        const float x = xn, m = mn;
-        if (s + 1 < cc.nsteps) {
-            mn = mseq[cc.t0 + s + 1];
-            if (j < Dr) xn = lseq[(size_t)(cc.t0 + s + 1) * Dr + j];
-        }
-        const float* fc = fbuf + (cur * C::VCPW + cl) * D;
-        float* fn = fbuf + ((cur ^ 1) * C::VCPW + cl) * D;
-        float* wn = wsum + ((cur ^ 1) * C::VCPW + cl) * C::VWPC;
-        float gval = 0.0f;
-        if (active) {
-            const float msafe = (m == -INFINITY) ? 0.0f : m;
-            const float e = __builtin_amdgcn_exp2f(fmaf(x, LOG2E, -LOG2E * msafe));
-            if (cc.t0 + s == 0) {
-                gval = fc[j] * e;   // psi_1 = prior o e_1: no transition
-            } else {
-                float acc = 0.0f;
+    for (int b = 0; b < nb; ++b) {
+        if (b + 1 < nb) eb.load(b + 1);
+        const float* ebuf = eb.e_lds + (b & 1) * EBt::EB * D;
+        const float* mbuf = eb.m_lds + (b & 1) * EBt::EB;
+        const int send = min(EBt::EB, nloop - b * EBt::EB);
+        for (int sb = 0; sb < send; ++sb) {
+            const int s = b * EBt::EB + sb;
+            const bool active = s < cc.nsteps;
+            const float* fc = fbuf + (cur * C::VCPW + cl) * D;
+            float* fn = fbuf + ((cur ^ 1) * C::VCPW + cl) * D;
+            float* wn = wsum + ((cur ^ 1) * C::VCPW + cl) * C::VWPC;
+            float gval = 0.0f;
+            if (active) {
+                const float e = ebuf[sb * D + j];
+                if (cc.t0 + s == 0) {
+                    gval = fc[j] * e;   // psi_1 = prior o e_1: no transition
+                } else {
+                    float acc = 0.0f;
 #pragma unroll
-                for (int r4 = 0; r4 < C::RPP; r4 += 4) {
-                    const float4 f4 = *reinterpret_cast<const float4*>(fc + h * C::RPP + r4);
-                    acc = fmaf(f4.x, areg[r4], acc);
-                    acc = fmaf(f4.y, areg[r4 + 1], acc);
-                    acc = fmaf(f4.z, areg[r4 + 2], acc);
-                    acc = fmaf(f4.w, areg[r4 + 3], acc);
+                    for (int r4 = 0; r4 < C::RPP; r4 += 4) {
+                        const float4 f4 = *reinterpret_cast<const float4*>(fc + h * C::RPP + r4);
+                        acc = fmaf(f4.x, areg[r4], acc);
+                        acc = fmaf(f4.y, areg[r4 + 1], acc);
+                        acc = fmaf(f4.z, areg[r4 + 2], acc);
+                        acc = fmaf(f4.w, areg[r4 + 3], acc);
+                    }
+                    acc = combine_parts<D>(acc);
+                    gval = acc * inv * e;
                 }
-                acc = combine_parts<D>(acc);
-                gval = acc * inv * e;
+                if (h == 0) fn[j] = gval;
+                const float sw = wave_sum(h == 0 ? gval : 0.0f);
+                if (lane == 0) wn[wv] = sw;
             }
-            if (h == 0) fn[j] = gval;
-            const float sw = wave_sum(h == 0 ? gval : 0.0f);
-            if (lane == 0) wn[wv] = sw;
-        }
-        apply_sync<D>();
-        if (active) {
-            float tot = 0.0f;
+            if (sb == send - 1 && b + 1 < nb) eb.store(b + 1);
+            apply_sync<D>();
+            if (active) {
+                float tot = 0.0f;
 #pragma unroll
-            for (int w = 0; w < C::VWPC; ++w) tot += wn[w];
-            inv = __builtin_amdgcn_rcpf(tot);
-            if (h == 0 && j < Dr) Fseq[(size_t)(cc.t0 + s) * Dr + j] = gval * inv;
-            if (lane == 0 && wv == 0) dacc += (double)m + (double)__logf(tot);
+                for (int w = 0; w < C::VWPC; ++w) tot += wn[w];
+                inv = __builtin_amdgcn_rcpf(tot);
+                if (h == 0 && j < Dr) Fseq[(size_t)(cc.t0 + s) * Dr + j] = gval * inv;
+                if (lane == 0 && wv == 0) dacc += (double)mbuf[sb] + (double)__logf(tot);
+            }
+            cur ^= 1;
         }
-        cur ^= 1;
     }
     if (cc.nsteps > 0 && lane == 0 && wv == 0) part[chunk] = dacc;
 }
@@ -376,8 +464,9 @@ template <int D>
 HMM_DEV void backward_chunk(const float* __restrict__ A, const float* __restrict__ ll,
                             const float* __restrict__ rowmax, long long T, int Dr, int Lc, int cps, long long nchunks,
                             int shared_model, const float* __restrict__ bout, float* __restrict__ Bv,
-                            long long chunk0, float* ubuf, float* wsum) {
+                            long long chunk0, ApplyLds<D>& L) {
     using C = LargeCfg<D>;
+    using EBt = EmissionBatches<D>;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int cl = wave / C::VWPC, wv = wave % C::VWPC;
     const int h = lane % C::PARTS;
@@ -392,54 +481,59 @@ HMM_DEV void backward_chunk(const float* __restrict__ A, const float* __restrict
         areg[r] = (i == jj) ? 1.0f : 0.0f;
         if (i < Dr && jj < Dr) areg[r] = Am[(size_t)i * Dr + jj];
     }
-    const float* lseq = ll + (size_t)cc.seq * T * Dr;
-    const float* mseq = rowmax + (size_t)cc.seq * T;
     float* Bseq = Bv + (size_t)cc.seq * T * Dr;
+    const int nloop = (C::VWPC > 1) ? Lc : cc.nsteps;
+    EBt eb;
+    eb.lseq = ll + (size_t)cc.seq * T * Dr;
+    eb.mseq = rowmax + (size_t)cc.seq * T;
+    eb.e_lds = L.e + cl * 2 * EBt::EB * D;
+    eb.m_lds = L.m + cl * 2 * EBt::EB;
+    eb.t0 = cc.t0; eb.nsteps = cc.nsteps; eb.nloop = nloop; eb.Dr = Dr; eb.rev = true;
+    eb.tic = threadIdx.x - cl * EBt::LPCH;
+    float* ubuf = L.vbuf;
+    float* wsum = L.wsum;
     float b = (cc.nsteps > 0) ? bout[(size_t)chunk * D + i] : 0.0f;   // b at the chunk's last step
     float inv = 1.0f;
     int cur = 0;
-    float xn = -INFINITY, mn = 0.0f;
-    if (cc.nsteps > 0) {
-        mn = mseq[cc.t0 + cc.nsteps - 1];
-        if (i < Dr) xn = lseq[(size_t)(cc.t0 + cc.nsteps - 1) * Dr + i];
-    }
-    const int nloop = (C::VWPC > 1) ? Lc : cc.nsteps;
-    for (int s = nloop - 1; s >= 0; --s) {
-        const bool active = s < cc.nsteps;
-        float* un = ubuf + ((cur ^ 1) * C::VCPW + cl) * D;
-        float* wn = wsum + ((cur ^ 1) * C::VCPW + cl) * C::VWPC;
-        if (active) {
-            const float x = xn, m = mn;
-            if (s > 0) {
-                mn = mseq[cc.t0 + s - 1];
-                if (i < Dr) xn = lseq[(size_t)(cc.t0 + s - 1) * Dr + i];
+    const int nb = (nloop + EBt::EB - 1) / EBt::EB;
+    if (nb > 0) { eb.load(0); eb.store(0); }
+    apply_sync<D>();
+    for (int bb = 0; bb < nb; ++bb) {
+        if (bb + 1 < nb) eb.load(bb + 1);
+        const float* ebuf = eb.e_lds + (bb & 1) * EBt::EB * D;
+        const int send = min(EBt::EB, nloop - bb * EBt::EB);
+        for (int sb = 0; sb < send; ++sb) {
+            const int s = nloop - 1 - (bb * EBt::EB + sb);
+            const bool active = s < cc.nsteps;
+            float* un = ubuf + ((cur ^ 1) * C::VCPW + cl) * D;
+            float* wn = wsum + ((cur ^ 1) * C::VCPW + cl) * C::VWPC;
+            if (active) {
+                const float bs = b * inv;   // scaled by the previous step's normaliser: any positive scale will do
+                if (h == 0 && i < Dr) Bseq[(size_t)(cc.t0 + s) * Dr + i] = bs;
+                if (h == 0) un[i] = ebuf[sb * D + i] * bs;
+                const float sw = wave_sum(h == 0 ? bs : 0.0f);
+                if (lane == 0) wn[wv] = sw;
             }
-            const float bs = b * inv;   // scaled by the previous step's normaliser: any positive scale will do
-            if (h == 0 && i < Dr) Bseq[(size_t)(cc.t0 + s) * Dr + i] = bs;
-            const float msafe = (m == -INFINITY) ? 0.0f : m;
-            const float e = __builtin_amdgcn_exp2f(fmaf(x, LOG2E, -LOG2E * msafe));
-            if (h == 0) un[i] = e * bs;
-            const float sw = wave_sum(h == 0 ? bs : 0.0f);
-            if (lane == 0) wn[wv] = sw;
-        }
-        apply_sync<D>();
-        if (active && s > 0) {
-            float tot = 0.0f;
+            if (sb == send - 1 && bb + 1 < nb) eb.store(bb + 1);
+            apply_sync<D>();
+            if (active && s > 0) {
+                float tot = 0.0f;
 #pragma unroll
-            for (int w = 0; w < C::VWPC; ++w) tot += wn[w];
-            inv = __builtin_amdgcn_rcpf(tot);
-            float acc = 0.0f;
+                for (int w = 0; w < C::VWPC; ++w) tot += wn[w];
+                inv = __builtin_amdgcn_rcpf(tot);
+                float acc = 0.0f;
 #pragma unroll
-            for (int r4 = 0; r4 < C::RPP; r4 += 4) {
-                const float4 u4 = *reinterpret_cast<const float4*>(un + h * C::RPP + r4);
-                acc = fmaf(u4.x, areg[r4], acc);
-                acc = fmaf(u4.y, areg[r4 + 1], acc);
-                acc = fmaf(u4.z, areg[r4 + 2], acc);
-                acc = fmaf(u4.w, areg[r4 + 3], acc);
+                for (int r4 = 0; r4 < C::RPP; r4 += 4) {
+                    const float4 u4 = *reinterpret_cast<const float4*>(un + h * C::RPP + r4);
+                    acc = fmaf(u4.x, areg[r4], acc);
+                    acc = fmaf(u4.y, areg[r4 + 1], acc);
+                    acc = fmaf(u4.z, areg[r4 + 2], acc);
+                    acc = fmaf(u4.w, areg[r4 + 3], acc);
+                }
+                b = combine_parts<D>(acc);
             }
-            b = combine_parts<D>(acc);
+            cur ^= 1;
         }
-        cur ^= 1;
     }
 }
 
@@ -453,14 +547,13 @@ __global__ __launch_bounds__(256) void ld_apply_kernel(const float* __restrict__
                                                        const float* __restrict__ bout, float* __restrict__ F,
                                                        float* __restrict__ Bv, double* __restrict__ part, int half) {
     using C = LargeCfg<D>;
-    __shared__ __align__(16) float vbuf[2 * C::VCPW * D];
-    __shared__ float wsum[2 * C::VCPW * C::VWPC];
+    __shared__ ApplyLds<D> L;
     if ((int)blockIdx.x < half)
         forward_chunk<D>(prior, A, ll, rowmax, T, Dr, Lc, cps, nchunks, shared_model, fin, F, part,
-                         (long long)blockIdx.x * C::VCPW, vbuf, wsum);
+                         (long long)blockIdx.x * C::VCPW, L);
     else
         backward_chunk<D>(A, ll, rowmax, T, Dr, Lc, cps, nchunks, shared_model, bout, Bv,
-                          (long long)(blockIdx.x - half) * C::VCPW, vbuf, wsum);
+                          (long long)(blockIdx.x - half) * C::VCPW, L);
 }
 
 // ---------------------------------------------------------------------------------------------
