@@ -138,6 +138,118 @@ __global__ __launch_bounds__(256) void lv_aggregate_kernel(const float* __restri
 }
 
 // ---------------------------------------------------------------------------------------------
+// Chunk aggregates for D >= 64 without any operand broadcast: a systolic arrangement inside each
+// DPP row of 16 lanes.  A row of lanes owns 16 columns j = 16*cb + l of P' and works through its
+// share of the rows i of P.  For one row i, lane l holds P(i, 16q + l) for every q; the term
+// P(i,k) + log A(k,j) needs k = 16q + (l - r) mod 16 at rotation r, which is exactly what a DPP
+// row rotation by r delivers as an operand of the add, and the matching log A(k,j) sits in a
+// register fixed per (q, r).  Every add therefore reads one rotated register and one constant
+// register: 1.5 vector instructions per term (add + half a three-way max), no LDS traffic, no
+// scalar loads, no data movement instruction in the inner loop.
+template <int R>
+HMM_DEV float row_rotate(float v) {
+    if constexpr (R == 0) return v;
+    else return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x120 + R, 0xF, 0xF, true));
+}
+
+template <int D, int Q, int R>
+HMM_DEV void systolic_terms(const float (&pr)[D / 16], const float (&la)[D], float& acc) {
+    if constexpr (R < 16) {
+        const float t0 = row_rotate<R>(pr[Q]) + la[Q * 16 + R];
+        const float t1 = row_rotate<R + 1>(pr[Q]) + la[Q * 16 + R + 1];
+        acc = max3f(acc, t0, t1);
+        systolic_terms<D, Q, R + 2>(pr, la, acc);
+    } else if constexpr (Q + 1 < D / 16) {
+        systolic_terms<D, Q + 1, 0>(pr, la, acc);
+    }
+}
+
+template <int D>
+__global__ __launch_bounds__(256) void lv_aggregate_systolic_kernel(const float* __restrict__ A,
+                                                                    const float* __restrict__ ll, long long T, int Dr,
+                                                                    int Lc, int cps, long long nchunks,
+                                                                    int shared_model, float* __restrict__ agg) {
+    constexpr int NQ = D / 16;             // column blocks = registers per lane for one row of P
+    constexpr int RSPLIT = 16 / NQ;        // row ranges (16 DPP rows per workgroup / column blocks)
+    constexpr int RPD = D / RSPLIT;        // rows of P per DPP row
+    __shared__ __align__(16) float pbuf[2 * D * D];   // P, double-buffered: [i][l][q] with k = 16q + l
+    __shared__ float wmax[2 * 4];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int drow = wave * 4 + lane / 16;             // DPP row 0..15
+    const int l = lane & 15;
+    const int cb = drow % NQ, rs = drow / NQ;
+    const int j = 16 * cb + l;
+    const long long chunk = blockIdx.x;
+    const ChunkCoord cc = chunk_coord(chunk, nchunks, cps, T, Lc);
+    const float* Am = A + (shared_model ? 0 : (size_t)cc.seq * Dr * Dr);
+    float la[D];   // la[16q + r] = log A(16q + (l - r) mod 16, j)
+#pragma unroll
+    for (int q = 0; q < NQ; ++q)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int k = 16 * q + ((l - r) & 15);
+            float v = (k == j) ? 0.0f : -INFINITY;
+            if (k < Dr && j < Dr) v = safe_log(Am[(size_t)k * Dr + j]);
+            la[16 * q + r] = v;
+        }
+    const float* lseq = ll + (size_t)cc.seq * T * Dr;
+    float* p0 = pbuf;
+    float* p1 = pbuf + D * D;
+    // neutral element: 0 on the diagonal, -inf elsewhere; element (i, k) lives at i*D + (k%16)*NQ + k/16
+    for (int r = 0; r < RPD; ++r) {
+        const int i = rs * RPD + r;
+        p0[i * D + l * NQ + cb] = (i == j) ? 0.0f : -INFINITY;
+    }
+    lds_barrier();
+    float off = 0.0f;
+    int cur = 0;
+    float xn = -INFINITY;
+    if (j < Dr) xn = lseq[(size_t)cc.t0 * Dr + j];
+    for (int s = 0; s < cc.nsteps; ++s) {
+        const float x = xn;
+        if (s + 1 < cc.nsteps && j < Dr) xn = lseq[(size_t)(cc.t0 + s + 1) * Dr + j];
+        const float* po = cur ? p1 : p0;
+        float* pn = cur ? p0 : p1;
+        const float add = x - off;
+        const bool no_transition = (cc.t0 + s == 0);
+        float lmax = -INFINITY;
+#pragma unroll 1
+        for (int r = 0; r < RPD; ++r) {
+            const int i = rs * RPD + r;
+            float pr[NQ];
+#pragma unroll
+            for (int q4 = 0; q4 < NQ; q4 += 4) {
+                const float4 v4 = *reinterpret_cast<const float4*>(po + i * D + l * NQ + q4);
+                pr[q4] = v4.x; pr[q4 + 1] = v4.y; pr[q4 + 2] = v4.z; pr[q4 + 3] = v4.w;
+            }
+            float acc;
+            if (no_transition) {
+                acc = pr[cb];   // P is still the neutral element: P(i, j) itself
+            } else {
+                acc = -INFINITY;
+                systolic_terms<D, 0, 0>(pr, la, acc);
+            }
+            acc += add;
+            lmax = fmaxf(lmax, acc);
+            pn[i * D + l * NQ + cb] = acc;
+        }
+        lmax = wave_max(lmax);
+        if (lane == 0) wmax[(cur ^ 1) * 4 + wave] = lmax;
+        lds_barrier();
+        const float m = fmaxf(fmaxf(wmax[(cur ^ 1) * 4], wmax[(cur ^ 1) * 4 + 1]),
+                              fmaxf(wmax[(cur ^ 1) * 4 + 2], wmax[(cur ^ 1) * 4 + 3]));
+        off = (m == -INFINITY) ? 0.0f : m;
+        cur ^= 1;
+    }
+    const float* pf = cur ? p1 : p0;
+    float* dst = agg + (size_t)chunk * D * D;
+    for (int r = 0; r < RPD; ++r) {
+        const int i = rs * RPD + r;
+        dst[(size_t)i * D + j] = pf[i * D + l * NQ + cb] - off;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // V at chunk boundaries.  One workgroup per sequence; lane = (column j, part q of the max over i).
 // vin[c] = V just before chunk c (log prior for c = 0, afterwards shifted to max 0).
 template <int D>
@@ -490,8 +602,12 @@ static int large_viterbi_impl(const LargeArgs& a, int32_t* path, double* logprob
     double* part = reinterpret_cast<double*>(ws + w.part);
     hipStream_t st = a.stream;
     const dim3 block(256);
-    launch("lv_aggregate", lv_aggregate_kernel<D>, dim3((unsigned)((p.nchunks + M::CPW - 1) / M::CPW)), block, st, a.A,
-           a.ll, a.T, a.D, p.Lc, p.cps, p.nchunks, a.shared_model, agg);
+    if constexpr (D >= 64)
+        launch("lv_aggregate", lv_aggregate_systolic_kernel<D>, dim3((unsigned)p.nchunks), block, st, a.A, a.ll, a.T,
+               a.D, p.Lc, p.cps, p.nchunks, a.shared_model, agg);
+    else
+        launch("lv_aggregate", lv_aggregate_kernel<D>, dim3((unsigned)((p.nchunks + M::CPW - 1) / M::CPW)), block, st,
+               a.A, a.ll, a.T, a.D, p.Lc, p.cps, p.nchunks, a.shared_model, agg);
     launch("lv_carry", lv_carry_kernel<D>, dim3((unsigned)a.batch), block, st, a.prior, a.D, p.cps, a.shared_model, agg,
            vin);
     const size_t fwd_lds = (size_t)C::VCPW * p.Lc * D;
