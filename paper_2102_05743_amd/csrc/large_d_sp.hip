@@ -20,6 +20,7 @@
 namespace hmm {
 
 constexpr float LOG2E = 1.4426950408889634f;
+constexpr int ZERO_STRIP_EXP = -(1 << 28);   // power-of-two scale recorded for an all-zero strip of an aggregate
 
 // ---------------------------------------------------------------------------------------------
 // m_t = max_j ll_t(j): one wave per row batch, coalesced.
@@ -98,7 +99,7 @@ __global__ __launch_bounds__(256) void ld_aggregate_kernel(const float* __restri
 #pragma unroll
         for (int r = 0; r < C::NACC; ++r) acc[mt][r] = (mfma_row<D>(mt, r, g) == ncol) ? 1.0f : 0.0f;
     int exsum = 0;
-    auto rescale = [&]() {
+    auto rescale = [&]() -> float {
         float m = 0.0f;
 #pragma unroll
         for (int mt = 0; mt < C::MT; ++mt)
@@ -112,6 +113,7 @@ __global__ __launch_bounds__(256) void ld_aggregate_kernel(const float* __restri
 #pragma unroll
             for (int r = 0; r < C::NACC; ++r) acc[mt][r] *= sc;
         exsum += ex;
+        return m;
     };
 
     const int nb = (Lc + C::EB - 1) / C::EB;
@@ -163,7 +165,9 @@ __global__ __launch_bounds__(256) void ld_aggregate_kernel(const float* __restri
         __syncthreads();
     }
     if (cc.nsteps > 0) {
-        rescale();
+        // a strip of zeros (start states the first observation excludes) has no scale of its own: give
+        // it the lowest one, so that it cannot set the common scale when strips are reconciled
+        if (rescale() == 0.0f) exsum = ZERO_STRIP_EXP;
         float* dst = agg + (size_t)chunk * D * D;     // P[n][k]
         float* dstT = aggT + (size_t)chunk * D * D;   // P^T[k][n]
 #pragma unroll

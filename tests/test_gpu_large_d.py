@@ -56,3 +56,37 @@ def test_sparse_transitions_and_impossible_emissions(gu):
     p.loglik[mask] = -np.inf
     gu.check_smooth(p, want_filtered=True)
     gu.check_viterbi(p)
+
+
+@pytest.mark.parametrize("D,T", [(128, 40000), (64, 90000), (32, 70000)])
+def test_first_observation_excludes_a_block_of_states(gu, D, T):
+    """Long chunks whose first element zeroes whole blocks of rows of the chunk aggregate.
+
+    The first element of a sequence has no transition part (Sec. IV-A, the element a_{0:1}), so a
+    state the first observation rules out leaves an all-zero row in the first chunk's product; with
+    chunks long enough that the other rows' scale falls far below single-precision range, such rows
+    must not take part in reconciling the scales.
+    """
+    p = wl.config5(T=T, D=D, seed=4242 + D)
+    p.loglik[0, 0, D // 4:] = -np.inf
+    gu.check_smooth(p, want_filtered=True, label=f"excluded block D={D}")
+    gu.check_viterbi(p, label=f"excluded block D={D}")
+
+
+# ---- the configurations at their full sizes, element by element against the oracle ----
+def test_config3_full_size(gu):
+    p = wl.config3()
+    gu.check_smooth(p, label="C3 full")
+    gu.check_viterbi(p, label="C3 full")
+
+
+def test_config4_full_size(gu):
+    p = wl.config4()
+    gu.check_smooth(p, label="C4 full")
+    gu.check_viterbi(p, label="C4 full")
+
+
+def test_config5_full_size(gu):
+    p = wl.config5()
+    gu.check_smooth(p, label="C5 full")
+    gu.check_viterbi(p, label="C5 full")
