@@ -7,7 +7,10 @@ D=4, T=2^20 burst-channel workload, inputs resident in HBM.  Steps rotate over s
 input/output buffer sets so that consecutive steps do not find their data in the 256 MB
 Infinity Cache.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2|C3|C4|C5]
+
+--workload selects one of the other synthetic configurations (D=32 long sequence, 256 x D=16
+batch, D=128 compute-bound) for the same measurement; the headline line is the default, C2.
 """
 from __future__ import annotations
 
@@ -22,23 +25,66 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
-SMOOTH_KERNELS = ("sd_reduce_sp", "sd_carry_sp", "sd_smooth_apply", "sd_finalize", "sd_clear_sp", "sd_smooth_fused")
+MFMA_F32_PEAK_TFLOPS = 157.3   # MI355X published dense FP32 matrix-core rate
+# Max-plus is one add and one max per term and the two do not fuse into one instruction: the vector
+# units issue 256 CUs x 128 lanes x 2.4 GHz = 78.6e12 such instructions per second (half the FMA-based
+# 157.3 TFLOP/s figure, which counts two operations per lane and clock).
+VALU_F32_PEAK_TOPS = 78.6
+SMOOTH_KERNELS = ("sd_reduce_sp", "sd_carry_sp", "sd_smooth_apply", "sd_finalize", "sd_clear_sp", "sd_smooth_fused",
+                  "ld_rowmax", "ld_aggregate", "ld_carry", "ld_apply", "ld_combine", "ld_finalize")
 VITERBI_KERNELS = ("sd_reduce_mp", "sd_carry_mp", "sd_viterbi_forward", "sd_viterbi_suffix", "sd_viterbi_path",
-                   "sd_clear_mp", "sd_viterbi_fused")
+                   "sd_clear_mp", "sd_viterbi_fused",
+                   "lv_aggregate", "lv_carry", "lv_forward", "lv_suffix", "lv_path")
+WORKLOADS = {
+    "C2": ("config2", "single HMM, D=4, T=2^20, burst-channel-style model, binary observations", 24, 300, 30),
+    "C3": ("config3", "single HMM, D=32, T=2^18, Dirichlet(0.5) transitions, Gaussian emissions", 8, 40, 5),
+    "C4": ("config4", "256 independent HMMs, D=16, T=4096 each, categorical emissions over 8 symbols", 6, 40, 5),
+    "C5": ("config5", "single HMM, D=128, T=2^16, banded-plus-noise transitions, Gaussian emissions on a grid", 8, 20, 3),
+}
+
+
+def kernel_roofline(name: str, avg_us: float, B: int, T: int, D: int) -> dict:
+    """Roofline entry of one kernel: what bounds it, its algorithmic work per launch, the rate achieved."""
+    sec = avg_us * 1e-6
+    if name == "ld_aggregate":
+        # one D x D by D x D product per element of the sequence (Definition 3): 2 D^3 flops
+        work = 2.0 * D ** 3 * B * T
+        ach = work / sec / 1e12
+        return {"bound": "mfma", "kernel": name, "avg_us": avg_us, "achieved": ach, "peak": MFMA_F32_PEAK_TFLOPS,
+                "unit": "TFLOP/s", "frac": ach / MFMA_F32_PEAK_TFLOPS, "traffic": None,
+                "algorithmic_flops_per_launch": work}
+    if name == "lv_aggregate":
+        # one max-plus D x D by D x D product per element (Definition 5): D^3 adds and D^3 maxima
+        work = 2.0 * D ** 3 * B * T
+        ach = work / sec / 1e12
+        return {"bound": "alu", "kernel": name, "avg_us": avg_us, "achieved": ach, "peak": VALU_F32_PEAK_TOPS,
+                "unit": "TOP/s", "frac": ach / VALU_F32_PEAK_TOPS, "traffic": None,
+                "algorithmic_ops_per_launch": work}
+    # streaming kernels: smoother reads log-likelihoods and writes marginals (8 D bytes per step of the
+    # sequence), Viterbi reads log-likelihoods and writes the int32 path (4 D + 4)
+    alg_bytes = B * T * (8 * D if name in SMOOTH_KERNELS else 4 * D + 4)
+    ach = alg_bytes / sec / 1e9
+    return {"bound": "hbm", "kernel": name, "avg_us": avg_us, "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": ach / HBM_PEAK_GBS, "traffic": None, "algorithmic_bytes_per_launch": alg_bytes}
 
 
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=300)
-    ap.add_argument("--warmup", type=int, default=30)
-    ap.add_argument("--sets", type=int, default=24, help="distinct buffer sets rotated over (cold-cache timing)")
-    ap.add_argument("--T", type=int, default=1 << 20, help="sequence length (default: the headline 2^20)")
+    ap.add_argument("--workload", choices=sorted(WORKLOADS), default="C2")
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--sets", type=int, default=None, help="distinct buffer sets rotated over (cold-cache timing)")
+    ap.add_argument("--T", type=int, default=None, help="sequence length (default: the configuration's own)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain device copy of 32 MiB per step (a kernel of known traffic, for scaling "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
+    gen_name, wl_text, d_sets, d_steps, d_warmup = WORKLOADS[args.workload]
+    args.steps = d_steps if args.steps is None else args.steps
+    args.warmup = d_warmup if args.warmup is None else args.warmup
+    args.sets = d_sets if args.sets is None else args.sets
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
               "run it with --gpus 1", file=sys.stderr)
@@ -55,7 +101,8 @@ def main() -> int:
         return 3
     hmm.load_library()            # fails loudly if the HIP library is missing
     dev = torch.device("cuda:0")
-    p = wl.config2(T=args.T)
+    gen = getattr(wl, gen_name)
+    p = gen() if args.T is None else gen(T=args.T)
     T, D, B = p.T, p.D, p.batch
     nsets = max(1, args.sets)
     prior = torch.from_numpy(p.prior).to(dev)
@@ -126,56 +173,60 @@ def main() -> int:
     viterbi_us = sum(v["avg_us"] * v["launches"] for k, v in per_kernel.items() if k in VITERBI_KERNELS) / args.steps
     dom = max(per_kernel.items(), key=lambda kv: kv[1]["avg_us"] * kv[1]["launches"])
     dom_name, dom_us = dom[0], dom[1]["avg_us"]
-    # algorithmic bytes per step of the sequence: smoother 8*D (read log-likelihoods, write marginals),
-    # Viterbi 4*D + 4 (read log-likelihoods, write the int32 path); one launch covers all B*T steps
-    alg_bytes = B * T * (8 * D if dom_name in SMOOTH_KERNELS else 4 * D + 4)
-    achieved = alg_bytes / (dom_us * 1e-6) / 1e9
-    traffic = None
-    tfile = os.path.join(ROOT, "profiles", "traffic_" + dom_name + "_C2.json")
+    roofline = kernel_roofline(dom_name, dom_us, B, T, D)
+    tfile = os.path.join(ROOT, "profiles", "traffic_" + dom_name + "_" + args.workload + ".json")
     if os.path.exists(tfile):
         try:
-            traffic = json.load(open(tfile)).get("traffic_bytes_per_launch")
+            roofline["traffic"] = json.load(open(tfile)).get("traffic_bytes_per_launch")
         except Exception:
-            traffic = None
-    roofline = {"bound": "hbm", "kernel": dom_name, "avg_us": dom_us, "achieved": achieved, "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                "algorithmic_bytes_per_launch": alg_bytes,
-                "smooth_call": {"kernel_us": smooth_us, "frac": (B * T * 8 * D) / (smooth_us * 1e-6) / 1e9 / HBM_PEAK_GBS
-                                if smooth_us > 0 else None},
-                "viterbi_call": {"kernel_us": viterbi_us,
-                                 "frac": (B * T * (4 * D + 4)) / (viterbi_us * 1e-6) / 1e9 / HBM_PEAK_GBS
-                                 if viterbi_us > 0 else None}}
+            pass
+    roofline["smooth_call"] = {"kernel_us": smooth_us,
+                               "frac": (B * T * 8 * D) / (smooth_us * 1e-6) / 1e9 / HBM_PEAK_GBS if smooth_us > 0 else None}
+    roofline["viterbi_call"] = {"kernel_us": viterbi_us,
+                                "frac": (B * T * (4 * D + 4)) / (viterbi_us * 1e-6) / 1e9 / HBM_PEAK_GBS
+                                if viterbi_us > 0 else None}
+    # every kernel that takes at least a tenth of the step, against its own bound
+    other_rooflines = [kernel_roofline(k, v["avg_us"], B, T, D) for k, v in per_kernel.items()
+                       if k != dom_name and v["avg_us"] * v["launches"] / args.steps >= 0.1 * (smooth_us + viterbi_us)]
 
     cpu_baseline = None
     if not args.no_cpu_baseline:
         import oracle
         best_s, best_v = float("inf"), float("inf")
-        reps = 3
+        reps = 3 if args.workload == "C2" else 1
+        nseq = min(B, 64)          # bounded sample of a batched workload: its first sequences
         for _ in range(reps):
             c0 = time.perf_counter()
-            oracle.smooth(p.prior[0], p.A[0], p.loglik[0], want_filtered=False)
+            for b in range(nseq):
+                m = 0 if p.shared_model else b
+                oracle.smooth(p.prior[m], p.A[m], p.loglik[b], want_filtered=False)
             c1 = time.perf_counter()
-            oracle.viterbi(p.prior[0], p.A[0], p.loglik[0])
+            for b in range(nseq):
+                m = 0 if p.shared_model else b
+                oracle.viterbi(p.prior[m], p.A[m], p.loglik[b])
             c2 = time.perf_counter()
             best_s, best_v = min(best_s, c1 - c0), min(best_v, c2 - c1)
-        cpu_baseline = {"value": state_steps / (best_s + best_v), "unit": "state-steps/s", "cores": 1,
-                        "kind": "oracle", "sample": f"the full workload (one sequence, T={T}, D={D}), smoother + "
-                        f"Viterbi, best of {reps}; the recursion is sequential in T so one thread is all it can use",
+        sample = (f"the full workload (one sequence, T={T}, D={D})" if B == 1 else
+                  f"{nseq} of the {B} sequences (T={T}, D={D} each)")
+        cpu_baseline = {"value": nseq * T * D / (best_s + best_v), "unit": "state-steps/s", "cores": 1,
+                        "kind": "oracle", "sample": sample + f", smoother + Viterbi, best of {reps}; the recursion is "
+                        "sequential in T so one thread is all it can use",
                         "smooth_s": best_s, "viterbi_s": best_v}
 
+    t_text = f"2^{T.bit_length() - 1}" if T & (T - 1) == 0 else str(T)
     out = {
-        "metric": "state-steps/sec (T*D/s), smoother + Viterbi, D=4, T=2^20",
+        "metric": f"state-steps/sec (T*D/s), smoother + Viterbi, D={D}, T={t_text}" + (f", batch {B}" if B > 1 else ""),
         "value": value, "unit": "state-steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"C2: single HMM, D={D}, T={T}, burst-channel-style model, binary observations",
+        "config": {"workload": f"{args.workload}: {wl_text}" + ("" if args.T is None else f" (T overridden: {T})"),
                    "batch": B, "buffer_sets": nsets, "step": "hmm_smooth + hmm_viterbi"},
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
         "extra": {"ms_per_step_with_kernel_events": ms_per_step_events, "ms_per_step_warm_cache": ms_per_step_warm,
                   "smooth_state_steps_per_s": state_steps / (smooth_us * 1e-6) if smooth_us > 0 else None,
                   "viterbi_state_steps_per_s": state_steps / (viterbi_us * 1e-6) if viterbi_us > 0 else None,
-                  "per_kernel": per_kernel,
+                  "per_kernel": per_kernel, "other_rooflines": other_rooflines,
                   "loglik": float(logliks[0, 0]), "logprob": float(logprobs[0, 0])},
     }
     print(json.dumps(out))

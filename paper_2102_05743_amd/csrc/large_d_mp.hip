@@ -23,11 +23,8 @@ namespace hmm {
 
 template <int D>
 struct MpCfg {
-    static constexpr int WPC = (D >= 64) ? 4 : 1;        // waves per chunk
+    static constexpr int WPC = (D >= 32) ? 4 : 1;        // waves per chunk in the aggregate kernel
     static constexpr int CPW = 4 / WPC;                  // chunks per workgroup
-    static constexpr int LPC = WPC * 64;                 // lanes per chunk
-    static constexpr int RG = LPC / D;                   // row groups: lane = (row group, column)
-    static constexpr int RPG = D / RG;                   // rows (of P) or summation terms per lane
 };
 
 HMM_DEV float max3f(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
@@ -41,104 +38,7 @@ HMM_DEV void chunk_sync() {
 HMM_DEV float safe_log(float p) { return p > 0.0f ? logf(p) : -INFINITY; }
 
 // ---------------------------------------------------------------------------------------------
-// Chunk aggregates.  Lane = (row group rg, column j); the lane keeps column j of log A in registers
-// and produces P'(i,j) = max_k [P(i,k) + log A(k,j)] + ll(j) for the rows i of its group, reading
-// P(i,k) as LDS broadcasts.  P is double-buffered in LDS; its running maximum is removed one step
-// late through the ll(j) term.
-template <int D>
-__global__ __launch_bounds__(256) void lv_aggregate_kernel(const float* __restrict__ A, const float* __restrict__ ll,
-                                                           long long T, int Dr, int Lc, int cps, long long nchunks,
-                                                           int shared_model, float* __restrict__ agg) {
-    using M = MpCfg<D>;
-    __shared__ __align__(16) float pbuf[2 * M::CPW * D * D];
-    __shared__ float wmax[2 * 4];
-    const int wave = threadIdx.x >> 6;
-    const int cl = wave / M::WPC;
-    const int u = threadIdx.x - cl * M::LPC;
-    const int j = u % D, rg = u / D;
-    const long long chunk = (long long)blockIdx.x * M::CPW + cl;
-    const ChunkCoord cc = chunk_coord(chunk, nchunks, cps, T, Lc);
-    const float* Am = A + (shared_model ? 0 : (size_t)cc.seq * Dr * Dr);
-    float la[D];   // column j of log A
-#pragma unroll
-    for (int k = 0; k < D; ++k) {
-        float v = (k == j) ? 0.0f : -INFINITY;
-        if (k < Dr && j < Dr) v = safe_log(Am[(size_t)k * Dr + j]);
-        la[k] = v;
-    }
-    const float* lseq = ll + (size_t)cc.seq * T * Dr;
-    float* p0 = pbuf + (size_t)cl * D * D;
-    float* p1 = pbuf + (size_t)(M::CPW + cl) * D * D;
-    // neutral element: 0 on the diagonal, -inf elsewhere
-#pragma unroll 4
-    for (int r = 0; r < M::RPG; ++r) {
-        const int i = rg * M::RPG + r;
-        p0[i * D + j] = (i == j) ? 0.0f : -INFINITY;
-    }
-    chunk_sync<D>();
-    float off = 0.0f;
-    int cur = 0;
-    float xn = -INFINITY;
-    if (cc.nsteps > 0 && j < Dr) xn = lseq[(size_t)cc.t0 * Dr + j];
-    for (int s = 0; s < Lc; ++s) {
-        const bool active = s < cc.nsteps;
-        const float x = xn;
-        if (s + 1 < cc.nsteps && j < Dr) xn = lseq[(size_t)(cc.t0 + s + 1) * Dr + j];
-        const float* po = cur ? p1 : p0;
-        float* pn = cur ? p0 : p1;
-        float lmax = -INFINITY;
-        if (active) {
-            const float add = x - off;
-            const bool no_transition = (cc.t0 + s == 0);
-#pragma unroll 1
-            for (int r = 0; r < M::RPG; ++r) {
-                const int i = rg * M::RPG + r;
-                const float* prow = po + i * D;
-                float acc;
-                if (no_transition) {
-                    acc = prow[j];
-                } else {
-                    acc = -INFINITY;
-#pragma unroll
-                    for (int k4 = 0; k4 < D; k4 += 4) {
-                        const float4 p4 = *reinterpret_cast<const float4*>(prow + k4);
-                        acc = max3f(acc, p4.x + la[k4], p4.y + la[k4 + 1]);
-                        acc = max3f(acc, p4.z + la[k4 + 2], p4.w + la[k4 + 3]);
-                    }
-                }
-                acc += add;
-                lmax = fmaxf(lmax, acc);
-                pn[i * D + j] = acc;
-            }
-        }
-        lmax = wave_max(lmax);
-        if ((threadIdx.x & 63) == 0) wmax[(cur ^ 1) * 4 + wave] = lmax;
-        chunk_sync<D>();
-        if (active) {
-            float m;
-            if constexpr (M::WPC == 4) {
-                m = fmaxf(fmaxf(wmax[(cur ^ 1) * 4], wmax[(cur ^ 1) * 4 + 1]),
-                          fmaxf(wmax[(cur ^ 1) * 4 + 2], wmax[(cur ^ 1) * 4 + 3]));
-            } else {
-                m = lmax;   // one wave per chunk: the wave's maximum is the chunk's
-            }
-            off = (m == -INFINITY) ? 0.0f : m;
-        }
-        cur ^= 1;
-    }
-    if (cc.nsteps > 0) {
-        const float* pf = cur ? p1 : p0;
-        float* dst = agg + (size_t)chunk * D * D;
-#pragma unroll 4
-        for (int r = 0; r < M::RPG; ++r) {
-            const int i = rg * M::RPG + r;
-            dst[(size_t)i * D + j] = pf[i * D + j] - off;
-        }
-    }
-}
-
-// ---------------------------------------------------------------------------------------------
-// Chunk aggregates for D >= 64 without any operand broadcast: a systolic arrangement inside each
+// Chunk aggregates without any operand broadcast: a systolic arrangement inside each
 // DPP row of 16 lanes.  A row of lanes owns 16 columns j = 16*cb + l of P' and works through its
 // share of the rows i of P.  For one row i, lane l holds P(i, 16q + l) for every q; the term
 // P(i,k) + log A(k,j) needs k = 16q + (l - r) mod 16 at rotation r, which is exactly what a DPP
@@ -170,16 +70,19 @@ __global__ __launch_bounds__(256) void lv_aggregate_systolic_kernel(const float*
                                                                     int Lc, int cps, long long nchunks,
                                                                     int shared_model, float* __restrict__ agg) {
     constexpr int NQ = D / 16;             // column blocks = registers per lane for one row of P
-    constexpr int RSPLIT = 16 / NQ;        // row ranges (16 DPP rows per workgroup / column blocks)
+    constexpr int WPCH = MpCfg<D>::WPC;    // waves per chunk: a workgroup for D >= 32, else one wave
+    constexpr int CPWG = 4 / WPCH;         // chunks per workgroup
+    constexpr int RSPLIT = 4 * WPCH / NQ;  // row ranges (DPP rows of the chunk / column blocks)
     constexpr int RPD = D / RSPLIT;        // rows of P per DPP row
-    __shared__ __align__(16) float pbuf[2 * D * D];   // P, double-buffered: [i][l][q] with k = 16q + l
+    __shared__ __align__(16) float pbuf[CPWG * 2 * D * D];   // P, double-buffered: [i][l][q] with k = 16q + l
     __shared__ float wmax[2 * 4];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int drow = wave * 4 + lane / 16;             // DPP row 0..15
+    const int cl = wave / WPCH;                                  // chunk inside the workgroup
+    const int drow = (wave % WPCH) * 4 + lane / 16;              // DPP row inside the chunk
     const int l = lane & 15;
     const int cb = drow % NQ, rs = drow / NQ;
     const int j = 16 * cb + l;
-    const long long chunk = blockIdx.x;
+    const long long chunk = (long long)blockIdx.x * CPWG + cl;
     const ChunkCoord cc = chunk_coord(chunk, nchunks, cps, T, Lc);
     const float* Am = A + (shared_model ? 0 : (size_t)cc.seq * Dr * Dr);
     float la[D];   // la[16q + r] = log A(16q + (l - r) mod 16, j)
@@ -193,18 +96,18 @@ __global__ __launch_bounds__(256) void lv_aggregate_systolic_kernel(const float*
             la[16 * q + r] = v;
         }
     const float* lseq = ll + (size_t)cc.seq * T * Dr;
-    float* p0 = pbuf;
-    float* p1 = pbuf + D * D;
+    float* p0 = pbuf + cl * 2 * D * D;
+    float* p1 = p0 + D * D;
     // neutral element: 0 on the diagonal, -inf elsewhere; element (i, k) lives at i*D + (k%16)*NQ + k/16
     for (int r = 0; r < RPD; ++r) {
         const int i = rs * RPD + r;
         p0[i * D + l * NQ + cb] = (i == j) ? 0.0f : -INFINITY;
     }
-    lds_barrier();
+    chunk_sync<D>();
     float off = 0.0f;
     int cur = 0;
     float xn = -INFINITY;
-    if (j < Dr) xn = lseq[(size_t)cc.t0 * Dr + j];
+    if (j < Dr && cc.nsteps > 0) xn = lseq[(size_t)cc.t0 * Dr + j];
     for (int s = 0; s < cc.nsteps; ++s) {
         const float x = xn;
         if (s + 1 < cc.nsteps && j < Dr) xn = lseq[(size_t)(cc.t0 + s + 1) * Dr + j];
@@ -213,14 +116,22 @@ __global__ __launch_bounds__(256) void lv_aggregate_systolic_kernel(const float*
         const float add = x - off;
         const bool no_transition = (cc.t0 + s == 0);
         float lmax = -INFINITY;
-#pragma unroll 1
+#pragma unroll(RPD <= 4 ? RPD : 1)
         for (int r = 0; r < RPD; ++r) {
             const int i = rs * RPD + r;
             float pr[NQ];
+            const float* src = po + i * D + l * NQ;
+            if constexpr (NQ >= 4) {
 #pragma unroll
-            for (int q4 = 0; q4 < NQ; q4 += 4) {
-                const float4 v4 = *reinterpret_cast<const float4*>(po + i * D + l * NQ + q4);
-                pr[q4] = v4.x; pr[q4 + 1] = v4.y; pr[q4 + 2] = v4.z; pr[q4 + 3] = v4.w;
+                for (int q4 = 0; q4 < NQ; q4 += 4) {
+                    const float4 v4 = *reinterpret_cast<const float4*>(src + q4);
+                    pr[q4] = v4.x; pr[q4 + 1] = v4.y; pr[q4 + 2] = v4.z; pr[q4 + 3] = v4.w;
+                }
+            } else if constexpr (NQ == 2) {
+                const float2 v2 = *reinterpret_cast<const float2*>(src);
+                pr[0] = v2.x; pr[1] = v2.y;
+            } else {
+                pr[0] = src[0];
             }
             float acc;
             if (no_transition) {
@@ -233,19 +144,25 @@ __global__ __launch_bounds__(256) void lv_aggregate_systolic_kernel(const float*
             lmax = fmaxf(lmax, acc);
             pn[i * D + l * NQ + cb] = acc;
         }
-        lmax = wave_max(lmax);
-        if (lane == 0) wmax[(cur ^ 1) * 4 + wave] = lmax;
-        lds_barrier();
-        const float m = fmaxf(fmaxf(wmax[(cur ^ 1) * 4], wmax[(cur ^ 1) * 4 + 1]),
-                              fmaxf(wmax[(cur ^ 1) * 4 + 2], wmax[(cur ^ 1) * 4 + 3]));
+        float m = wave_max(lmax);
+        if constexpr (WPCH == 4) {
+            if (lane == 0) wmax[(cur ^ 1) * 4 + wave] = m;
+            lds_barrier();
+            m = fmaxf(fmaxf(wmax[(cur ^ 1) * 4], wmax[(cur ^ 1) * 4 + 1]),
+                      fmaxf(wmax[(cur ^ 1) * 4 + 2], wmax[(cur ^ 1) * 4 + 3]));
+        } else {
+            chunk_sync<D>();
+        }
         off = (m == -INFINITY) ? 0.0f : m;
         cur ^= 1;
     }
-    const float* pf = cur ? p1 : p0;
-    float* dst = agg + (size_t)chunk * D * D;
-    for (int r = 0; r < RPD; ++r) {
-        const int i = rs * RPD + r;
-        dst[(size_t)i * D + j] = pf[i * D + l * NQ + cb] - off;
+    if (cc.nsteps > 0) {
+        const float* pf = cur ? p1 : p0;
+        float* dst = agg + (size_t)chunk * D * D;
+        for (int r = 0; r < RPD; ++r) {
+            const int i = rs * RPD + r;
+            dst[(size_t)i * D + j] = pf[i * D + l * NQ + cb] - off;
+        }
     }
 }
 
@@ -602,12 +519,8 @@ static int large_viterbi_impl(const LargeArgs& a, int32_t* path, double* logprob
     double* part = reinterpret_cast<double*>(ws + w.part);
     hipStream_t st = a.stream;
     const dim3 block(256);
-    if constexpr (D >= 64)
-        launch("lv_aggregate", lv_aggregate_systolic_kernel<D>, dim3((unsigned)p.nchunks), block, st, a.A, a.ll, a.T,
-               a.D, p.Lc, p.cps, p.nchunks, a.shared_model, agg);
-    else
-        launch("lv_aggregate", lv_aggregate_kernel<D>, dim3((unsigned)((p.nchunks + M::CPW - 1) / M::CPW)), block, st,
-               a.A, a.ll, a.T, a.D, p.Lc, p.cps, p.nchunks, a.shared_model, agg);
+    launch("lv_aggregate", lv_aggregate_systolic_kernel<D>, dim3((unsigned)((p.nchunks + M::CPW - 1) / M::CPW)), block,
+           st, a.A, a.ll, a.T, a.D, p.Lc, p.cps, p.nchunks, a.shared_model, agg);
     launch("lv_carry", lv_carry_kernel<D>, dim3((unsigned)a.batch), block, st, a.prior, a.D, p.cps, a.shared_model, agg,
            vin);
     const size_t fwd_lds = (size_t)C::VCPW * p.Lc * D;
