@@ -71,7 +71,9 @@ HMM_DEV void load_tile(const float* __restrict__ g, int nvalid_steps, float* lds
 #pragma unroll
         for (int it = 0; it < NIT; ++it) {
             const int v = it * C::NT + threadIdx.x;
-            x[it] = g4[v < last ? v : last];
+            typedef float nt4 __attribute__((ext_vector_type(4)));
+            const nt4 y = __builtin_nontemporal_load(reinterpret_cast<const nt4*>(g4 + (v < last ? v : last)));
+            x[it] = make_float4(y.x, y.y, y.z, y.w);
         }
 #pragma unroll
         for (int it = 0; it < NIT; ++it) {
@@ -111,8 +113,9 @@ HMM_DEV void store_tile(float* __restrict__ g, int nvalid_steps, const float* ld
             const int v = it * C::NT + threadIdx.x;
             const int fl = v * 4;
             const int owner = fl / C::ROW;
-            const float4 x = *reinterpret_cast<const float4*>(lds + owner * C::STRIDE + (fl - owner * C::ROW));
-            if (fl < nfl) g4[v] = x;
+            typedef float nt4 __attribute__((ext_vector_type(4)));
+            const nt4 x = *reinterpret_cast<const nt4*>(lds + owner * C::STRIDE + (fl - owner * C::ROW));
+            if (fl < nfl) __builtin_nontemporal_store(x, reinterpret_cast<nt4*>(g4 + v));
         }
     } else {
 #pragma unroll 8
@@ -669,7 +672,7 @@ HMM_DEV void store_path_tile(int32_t* __restrict__ dst, int nvalid, const int32_
 #pragma unroll
     for (int it = 0; it < C::L; ++it) {
         const int s = it * C::NT + threadIdx.x;
-        if (s < nvalid) dst[s] = stage[(s / C::L) * C::PSTRIDE + (s % C::L)];
+        if (s < nvalid) __builtin_nontemporal_store(stage[(s / C::L) * C::PSTRIDE + (s % C::L)], dst + s);
     }
 }
 
