@@ -362,25 +362,41 @@ struct GridLds {
     float aggs[(SmallCfg<D>::NT / 2) * PSTR];         // the sequence's tile aggregates, staged
 };
 
-// Lane 0 publishes this tile's aggregate (the product of the wave totals in wagg).
+// Largest value over the wavefront (every lane must call; all lanes get the result).
+HMM_DEV float wave_all_max(float v) {
+    v = fmaxf(v, dpp_move<0x111, 0xF>(-INFINITY, v));   // row_shr:1
+    v = fmaxf(v, dpp_move<0x112, 0xF>(-INFINITY, v));   // row_shr:2
+    v = fmaxf(v, dpp_move<0x114, 0xF>(-INFINITY, v));   // row_shr:4
+    v = fmaxf(v, dpp_move<0x118, 0xF>(-INFINITY, v));   // row_shr:8
+    v = fmaxf(v, dpp_move<0x142, 0xA>(-INFINITY, v));   // row_bcast:15
+    v = fmaxf(v, dpp_move<0x143, 0xC>(-INFINITY, v));   // row_bcast:31
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
+
+// The first wave publishes this tile's aggregate, the ordered product of the wave totals in wagg.
+// Lane e < D*D owns entry (e / D, e % D) of the running product: its row comes from the other
+// lanes by shuffles, the next wave total's column from LDS, so the chain of products costs a few
+// instructions per lane instead of whole matrix products in a single lane.
 template <class S, int D>
 HMM_DEV void grid_publish(const float* wagg, const FusedWs& ws) {
-    if (threadIdx.x == 0) {
-        float X[D * D];
-        block_total<S, D>(wagg, X);
-        float* dst = ws.agg + (size_t)blockIdx.x * D * D;
-        if ((reinterpret_cast<uintptr_t>(dst) & 7u) == 0) {
+    using C = SmallCfg<D>;
+    static_assert(D * D <= 64, "one lane per entry of the aggregate");
+    if (threadIdx.x < 64) {
+        const int lane = threadIdx.x;
+        const int e = lane < D * D ? lane : 0;   // spare lanes shadow entry 0 and never store
+        const int i = e / D, j = e % D;
+        float x = wagg[e];
 #pragma unroll
-            for (int e = 0; e + 1 < D * D; e += 2)
-                coherent_store(reinterpret_cast<unsigned long long*>(dst + e),
-                               (unsigned long long)publish_bits(X[e]) |
-                                   ((unsigned long long)publish_bits(X[e + 1]) << 32));
-            if constexpr ((D * D) % 2 == 1)
-                coherent_store(reinterpret_cast<uint32_t*>(dst + D * D - 1), publish_bits(X[D * D - 1]));
-        } else {
+        for (int w = 1; w < C::NW; ++w) {
+            float acc = S::zero();
 #pragma unroll
-            for (int e = 0; e < D * D; ++e) coherent_store(reinterpret_cast<uint32_t*>(dst + e), publish_bits(X[e]));
+            for (int k = 0; k < D; ++k) acc = S::mul_add(acc, __shfl(x, i * D + k, 64), wagg[(w * D + k) * D + j]);
+            const float m = wave_all_max(acc);
+            if constexpr (S::is_max_plus) x = acc - ((m == -INFINITY) ? 0.0f : m);
+            else x = ldexpf(acc, -__builtin_amdgcn_frexp_expf(m));
         }
+        if (lane < D * D)
+            coherent_store(reinterpret_cast<uint32_t*>(ws.agg + (size_t)blockIdx.x * D * D) + e, publish_bits(x));
     }
 }
 
@@ -542,9 +558,9 @@ __global__ __launch_bounds__(256) void sd_smooth_fused_kernel(const float* __res
     }
 #endif
     const TileCoord tc = tile_coord<D>(T, tps);
-    load_tile<D>(ll + tc.base * D, tc.nvalid, lds);
     float Am[D * D];
-    load_model<S, D>(A + (shared_model ? 0 : (size_t)tc.seq * D * D), Am);
+    load_model<S, D>(A + (shared_model ? 0 : (size_t)tc.seq * D * D), Am);   // issued ahead of the tile's loads
+    load_tile<D>(ll + tc.base * D, tc.nvalid, lds);
     __syncthreads();
     HMM_STAMP(1);
     float* row = lds + threadIdx.x * C::STRIDE;
@@ -601,9 +617,9 @@ __global__ __launch_bounds__(256) void sd_viterbi_fused_kernel(const float* __re
     HMM_STAMP(0);
     const TileCoord tc = tile_coord<D>(T, tps);
     const int tile0 = blockIdx.x - tc.tile;
-    load_tile<D>(ll + tc.base * D, tc.nvalid, lds);
     float Am[D * D];
-    load_model<S, D>(A + (shared_model ? 0 : (size_t)tc.seq * D * D), Am);
+    load_model<S, D>(A + (shared_model ? 0 : (size_t)tc.seq * D * D), Am);   // issued ahead of the tile's loads
+    load_tile<D>(ll + tc.base * D, tc.nvalid, lds);
     __syncthreads();
     HMM_STAMP(1);
     float* row = lds + threadIdx.x * C::STRIDE;
@@ -628,14 +644,13 @@ __global__ __launch_bounds__(256) void sd_viterbi_fused_kernel(const float* __re
     uint32_t bp[C::W], h, xs;
     const double osum = viterbi_chunk<D>(row, n, first, last, Am, v, bp, h, xs);
     HMM_STAMP(8);
-    const double tile_delta = block_sum(osum, dsum);
     uint32_t excl;
     const uint32_t total = block_map_suffix<D>(h, excl, wmaps);
+    if (threadIdx.x == 0) coherent_store(ws.tmap + blockIdx.x, total);   // a map uses 24 bits: never the sentinel
     HMM_STAMP(9);
-    if (threadIdx.x == 0) {
+    const double tile_delta = block_sum(osum, dsum);   // other tiles wait for the map, not for this
+    if (threadIdx.x == 0)
         coherent_store(reinterpret_cast<unsigned long long*>(ws.part) + blockIdx.x, publish_bits(tile_delta));
-        coherent_store(ws.tmap + blockIdx.x, total);   // a map uses 24 bits: never the sentinel
-    }
     // the tile maps of the sequence; state at this tile's last step = maps of later tiles composed
     uint32_t tm = map_identity<D>();
     bool ok2 = false;
