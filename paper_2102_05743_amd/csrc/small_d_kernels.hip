@@ -412,15 +412,27 @@ HMM_DEV bool gather_aggregates(const float* src, int n, float* dst_lds) {
         if (wide) {
             const unsigned long long* s2 = reinterpret_cast<const unsigned long long*>(src);
             const int n2 = n >> 1;
-            for (int i = threadIdx.x; i < n2; i += blockDim.x) {
-                const unsigned long long w = coherent_load(s2 + i);
-                const uint32_t lo = (uint32_t)w, hi = (uint32_t)(w >> 32);
-                valid = valid && lo != SENTINEL32 && hi != SENTINEL32;
-                const int f = 2 * i;
-                const int d0 = (f / G::PAIR) * G::PSTR + f % G::PAIR;
-                const int d1 = ((f + 1) / G::PAIR) * G::PSTR + (f + 1) % G::PAIR;
-                dst_lds[d0] = __uint_as_float(lo);
-                dst_lds[d1] = __uint_as_float(hi);
+            constexpr int NB = 8;   // loads in flight per lane: issued together, then checked and staged
+            for (int base = 0; base < n2; base += NB * (int)blockDim.x) {
+                unsigned long long w[NB];
+#pragma unroll
+                for (int q = 0; q < NB; ++q) {
+                    const int i = base + q * (int)blockDim.x + (int)threadIdx.x;
+                    w[q] = coherent_load(s2 + (i < n2 ? i : n2 - 1));
+                }
+#pragma unroll
+                for (int q = 0; q < NB; ++q) {
+                    const int i = base + q * (int)blockDim.x + (int)threadIdx.x;
+                    if (i < n2) {
+                        const uint32_t lo = (uint32_t)w[q], hi = (uint32_t)(w[q] >> 32);
+                        valid = valid && lo != SENTINEL32 && hi != SENTINEL32;
+                        const int f = 2 * i;
+                        const int d0 = (f / G::PAIR) * G::PSTR + f % G::PAIR;
+                        const int d1 = ((f + 1) / G::PAIR) * G::PSTR + (f + 1) % G::PAIR;
+                        dst_lds[d0] = __uint_as_float(lo);
+                        dst_lds[d1] = __uint_as_float(hi);
+                    }
+                }
             }
             if ((n & 1) && threadIdx.x == 0) {
                 const uint32_t w = coherent_load(reinterpret_cast<const uint32_t*>(src) + n - 1);
@@ -434,7 +446,12 @@ HMM_DEV bool gather_aggregates(const float* src, int n, float* dst_lds) {
                 dst_lds[(i / G::PAIR) * G::PSTR + i % G::PAIR] = __uint_as_float(w);
             }
         }
-        if (__syncthreads_and(valid ? 1 : 0)) return true;
+        if (__syncthreads_and(valid ? 1 : 0)) {
+#ifdef HMM_PHASE_STAMPS
+            if ((threadIdx.x & 63) == 0 && blockIdx.x < 256) g_stamps[(blockIdx.x * 4 + (threadIdx.x >> 6)) * 16 + 5] = spin;
+#endif
+            return true;
+        }
         __builtin_amdgcn_s_sleep(1);
     }
     return false;
