@@ -59,8 +59,12 @@ HMM_DEV TileCoord tile_coord(long long T, int tps) {
 // Tile <-> LDS staging: coalesced on the global side, one padded row per lane on the LDS side.
 // All global loads of a tile are issued before the first LDS write so they overlap; addresses
 // past the valid part are clamped (the rows they fill are never read).
-template <int D>
-HMM_DEV void load_tile(const float* __restrict__ g, int nvalid_steps, float* lds) {
+struct NoWork { HMM_DEV void operator()() const {} };
+
+// `between` runs after the tile's loads have been issued and before their data is needed: work
+// placed there (such as taking logarithms of the model) is hidden behind the memory latency.
+template <int D, class F = NoWork>
+HMM_DEV void load_tile(const float* __restrict__ g, int nvalid_steps, float* lds, F between = F()) {
     using C = SmallCfg<D>;
     const int nfl = nvalid_steps * D;
     if constexpr (C::VEC == 4) {
@@ -75,6 +79,7 @@ HMM_DEV void load_tile(const float* __restrict__ g, int nvalid_steps, float* lds
             const nt4 y = __builtin_nontemporal_load(reinterpret_cast<const nt4*>(g4 + (v < last ? v : last)));
             x[it] = make_float4(y.x, y.y, y.z, y.w);
         }
+        between();
 #pragma unroll
         for (int it = 0; it < NIT; ++it) {
             const int fl = (it * C::NT + threadIdx.x) * 4;
@@ -92,6 +97,7 @@ HMM_DEV void load_tile(const float* __restrict__ g, int nvalid_steps, float* lds
                 const int fl = (it0 + q) * C::NT + threadIdx.x;
                 x[q] = g[fl < last ? fl : last];
             }
+            if (it0 == 0) between();
 #pragma unroll
             for (int q = 0; q < CH; ++q) {
                 const int fl = (it0 + q) * C::NT + threadIdx.x;
@@ -161,6 +167,22 @@ HMM_DEV void load_model(const float* __restrict__ A, float (&Am)[D * D]) {
     for (int e = 0; e < D * D; ++e) {
         const float a = A[e];
         Am[e] = S::is_max_plus ? logf(a) : a;
+    }
+}
+
+// The same in two parts, so that other loads can be issued between the model's loads and the
+// arithmetic on them.
+template <int D>
+HMM_DEV void load_model_raw(const float* __restrict__ A, float (&Am)[D * D]) {
+#pragma unroll
+    for (int e = 0; e < D * D; ++e) Am[e] = A[e];
+}
+
+template <class S, int D>
+HMM_DEV void model_to_domain(float (&Am)[D * D]) {
+    if constexpr (S::is_max_plus) {
+#pragma unroll
+        for (int e = 0; e < D * D; ++e) Am[e] = logf(Am[e]);
     }
 }
 
@@ -590,19 +612,62 @@ constexpr uint32_t MAP_FINAL_FLAG = 0x80000000u;   // lane holds the sequence's 
 constexpr int MAP_FINAL_SHIFT = 24;                // ... and x*_T is stored here
 constexpr uint32_t MAP_BODY = 0x00ffffffu;
 
+// For D <= 4 a map also fits one byte per entry, and then composition is a single byte-permute
+// instruction (result byte j = byte h(j) of g); chains of compositions convert once on the way
+// in and once on the way out.
+template <int D>
+HMM_DEV uint32_t map_to_bytes(uint32_t g) {
+    using C = SmallCfg<D>;
+    if constexpr (D == 4) {
+        return (g | (g << 6) | (g << 12) | (g << 18)) & 0x03030303u;
+    } else {
+        uint32_t r = 0;
+#pragma unroll
+        for (int j = 0; j < D; ++j) r |= ((g >> (j * C::BITS)) & C::MASK) << (8 * j);
+        return r;
+    }
+}
+
+template <int D>
+HMM_DEV uint32_t map_from_bytes(uint32_t m) {
+    using C = SmallCfg<D>;
+    if constexpr (D == 4) {
+        return (m | (m >> 6) | (m >> 12) | (m >> 18)) & 0xffu;
+    } else {
+        uint32_t r = 0;
+#pragma unroll
+        for (int j = 0; j < D; ++j) r |= ((m >> (8 * j)) & C::MASK) << (j * C::BITS);
+        return r;
+    }
+}
+
+HMM_DEV uint32_t bytes_compose(uint32_t g, uint32_t h) { return __builtin_amdgcn_perm(0u, g, h); }
+
 // Chunk map: x at the chunk's last step -> x at the step before the chunk.
 template <int D>
 HMM_DEV uint32_t chunk_map(const uint32_t (&bp)[SmallCfg<D>::W], int n) {
     using C = SmallCfg<D>;
-    uint32_t h = map_identity<D>();
+    if constexpr (D <= 4) {
+        uint32_t h = 0x03020100u;   // identity, one byte per entry
 #pragma unroll
-    for (int k = C::L - 1; k >= 0; --k) {
-        if (k < n) {
-            const uint32_t u = (bp[k / C::SPW] >> ((k % C::SPW) * C::STEP_BITS)) & C::STEP_MASK;
-            h = map_compose<D>(u, h);
+        for (int k = C::L - 1; k >= 0; --k) {
+            if (k < n) {
+                const uint32_t u = (bp[k / C::SPW] >> ((k % C::SPW) * C::STEP_BITS)) & C::STEP_MASK;
+                h = bytes_compose(map_to_bytes<D>(u), h);
+            }
         }
+        return map_from_bytes<D>(h);
+    } else {
+        uint32_t h = map_identity<D>();
+#pragma unroll
+        for (int k = C::L - 1; k >= 0; --k) {
+            if (k < n) {
+                const uint32_t u = (bp[k / C::SPW] >> ((k % C::SPW) * C::STEP_BITS)) & C::STEP_MASK;
+                h = map_compose<D>(u, h);
+            }
+        }
+        return h;
     }
-    return h;
 }
 
 // x*_T = argmax_j V_T(j), lowest index on ties
@@ -625,27 +690,37 @@ HMM_DEV uint32_t argmax_state(const float (&v)[D]) {
 template <int D>
 HMM_DEV uint32_t block_map_suffix(uint32_t g, uint32_t& excl, uint32_t* wmaps) {
     using C = SmallCfg<D>;
+    constexpr bool BYTES = D <= 4;   // compose in the byte form, convert at both ends
+    auto comp = [](uint32_t a, uint32_t b) {
+        if constexpr (BYTES) return bytes_compose(a, b);
+        else return map_compose<D>(a, b);
+    };
+    const uint32_t ident = BYTES ? 0x03020100u : map_identity<D>();
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
-    uint32_t G = g;   // inclusive: g_t o ... o g_63 within the wave
+    uint32_t G = BYTES ? map_to_bytes<D>(g) : g;   // inclusive: g_t o ... o g_63 within the wave
 #pragma unroll
     for (int d = 1; d < 64; d <<= 1) {
         const uint32_t o = __shfl_down(G, d, 64);
-        const uint32_t c = map_compose<D>(G, o);
+        const uint32_t c = comp(G, o);
         G = (lane + d < 64) ? c : G;
     }
     if (lane == 0) wmaps[wave] = G;
     __syncthreads();
-    uint32_t tail = map_identity<D>();   // composition of the waves after mine
+    uint32_t tail = ident;   // composition of the waves after mine
 #pragma unroll
     for (int w = C::NW - 1; w > 0; --w)
-        if (w > wave) tail = map_compose<D>(wmaps[w], tail);
+        if (w > wave) tail = comp(wmaps[w], tail);
     uint32_t nxt = __shfl_down(G, 1, 64);
-    nxt = (lane == 63) ? map_identity<D>() : nxt;
-    excl = map_compose<D>(nxt, tail);
-    uint32_t total = map_identity<D>();
+    nxt = (lane == 63) ? ident : nxt;
+    excl = comp(nxt, tail);
+    uint32_t total = ident;
 #pragma unroll
-    for (int w = C::NW - 1; w >= 0; --w) total = map_compose<D>(wmaps[w], total);
+    for (int w = C::NW - 1; w >= 0; --w) total = comp(wmaps[w], total);
+    if constexpr (BYTES) {
+        excl = map_from_bytes<D>(excl);
+        total = map_from_bytes<D>(total);
+    }
     return total;
 }
 

@@ -576,8 +576,8 @@ __global__ __launch_bounds__(256) void sd_smooth_fused_kernel(const float* __res
 #endif
     const TileCoord tc = tile_coord<D>(T, tps);
     float Am[D * D];
-    load_model<S, D>(A + (shared_model ? 0 : (size_t)tc.seq * D * D), Am);   // issued ahead of the tile's loads
-    load_tile<D>(ll + tc.base * D, tc.nvalid, lds);
+    load_model_raw<D>(A + (shared_model ? 0 : (size_t)tc.seq * D * D), Am);   // issued ahead of the tile's loads
+    load_tile<D>(ll + tc.base * D, tc.nvalid, lds, [&]() { model_to_domain<S, D>(Am); });
     __syncthreads();
     HMM_STAMP(1);
     float* row = lds + threadIdx.x * C::STRIDE;
@@ -635,8 +635,8 @@ __global__ __launch_bounds__(256) void sd_viterbi_fused_kernel(const float* __re
     const TileCoord tc = tile_coord<D>(T, tps);
     const int tile0 = blockIdx.x - tc.tile;
     float Am[D * D];
-    load_model<S, D>(A + (shared_model ? 0 : (size_t)tc.seq * D * D), Am);   // issued ahead of the tile's loads
-    load_tile<D>(ll + tc.base * D, tc.nvalid, lds);
+    load_model_raw<D>(A + (shared_model ? 0 : (size_t)tc.seq * D * D), Am);   // issued ahead of the tile's loads
+    load_tile<D>(ll + tc.base * D, tc.nvalid, lds, [&]() { model_to_domain<S, D>(Am); });
     __syncthreads();
     HMM_STAMP(1);
     float* row = lds + threadIdx.x * C::STRIDE;
