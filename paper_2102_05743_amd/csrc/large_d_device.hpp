@@ -101,6 +101,16 @@ HMM_DEV int quad_xor2(int v) { return __builtin_amdgcn_update_dpp(v, v, 0x4E, 0x
 // round trip on the critical path of loops that store a result or prefetch an input per step.
 HMM_DEV void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
+// Ordering point for LDS traffic inside ONE wave: a wave's LDS instructions execute in order, so a
+// write followed by a read of another lane's slot needs no wait, only that the compiler keeps the
+// order and re-reads LDS afterwards.  (A wavefront-scope fence would do that too, but it also waits
+// for every outstanding global load and store, which serialises loops that prefetch.)
+HMM_DEV void wave_lds_sync() { __builtin_amdgcn_wave_barrier(); }
+
+// Wait for the wave's outstanding global loads and mark `v` as produced here, so that later waits
+// on loop-carried uses of it do not drain loads issued in between.
+HMM_DEV void settle_loaded(float& v) { asm volatile("s_waitcnt vmcnt(0)\n\tv_mov_b32 %0, %0" : "+v"(v)::"memory"); }
+
 struct ChunkCoord {
     int seq;        // sequence
     int cidx;       // chunk index inside the sequence

@@ -161,7 +161,8 @@ __global__ __launch_bounds__(256) void lv_aggregate_systolic_kernel(const float*
         float* dst = agg + (size_t)chunk * D * D;
         for (int r = 0; r < RPD; ++r) {
             const int i = rs * RPD + r;
-            dst[(size_t)i * D + j] = pf[i * D + l * NQ + cb] - off;
+            // D <= 32: stored transposed, the one-wave carry reads the terms of a column contiguously
+            dst[(D <= 32) ? ((size_t)j * D + i) : ((size_t)i * D + j)] = pf[i * D + l * NQ + cb] - off;
         }
     }
 }
@@ -219,6 +220,70 @@ __global__ __launch_bounds__(256) void lv_carry_kernel(const float* __restrict__
         lds_barrier();
         v = g - max_lds;
     }
+}
+
+// The same for D <= 32 by a single wave per sequence (lane = (column j, part h of the max over i),
+// parts combined with quad permutes, wave-level ordering only, aggregates prefetched PF hops ahead):
+// a hop costs a few hundred cycles, which is what bounds a long sequence.
+template <int D>
+__global__ __launch_bounds__(64) void lv_carry_wave_kernel(const float* __restrict__ prior, int Dr, int cps,
+                                                           int shared_model, const float* __restrict__ agg,
+                                                           float* __restrict__ vin) {
+    static_assert(D <= 32, "one wave covers the columns");
+    constexpr int PARTS = 64 / D;
+    constexpr int RPT = D / PARTS;
+    constexpr int PF = 8;
+    __shared__ __align__(16) float vec[D];
+    const int seq = blockIdx.x;
+    const int lane = threadIdx.x;
+    const int h = lane % PARTS, j = lane / PARTS;
+    const float* mats = agg + (size_t)seq * cps * D * D;
+    float* out = vin + (size_t)seq * cps * D;
+    float v = (j < Dr) ? safe_log(prior[(shared_model ? 0 : (size_t)seq * Dr) + j]) : -INFINITY;
+    settle_loaded(v);
+    float pv[PF][RPT];
+    // unconditional loads (clamped hop index): the compiler can count outstanding loads exactly
+    auto load_mat = [&](int c, float (&m)[RPT]) {
+        const float* Mx = mats + (size_t)(c < cps ? c : cps - 1) * D * D + (size_t)j * D + h * RPT;   // stored transposed
+#pragma unroll
+        for (int r4 = 0; r4 < RPT; r4 += 4) {
+            const float4 x = *reinterpret_cast<const float4*>(Mx + r4);
+            m[r4] = x.x; m[r4 + 1] = x.y; m[r4 + 2] = x.z; m[r4 + 3] = x.w;
+        }
+    };
+    auto hop = [&](int c, const float (&m)[RPT]) {
+        if (h == 0) {
+            out[(size_t)c * D + j] = v;
+            vec[j] = v;
+        }
+        wave_lds_sync();
+        float a0 = -INFINITY, a1 = -INFINITY;   // independent chains
+#pragma unroll
+        for (int r4 = 0; r4 < RPT; r4 += 4) {
+            const float4 x = *reinterpret_cast<const float4*>(vec + h * RPT + r4);
+            a0 = max3f(a0, x.x + m[r4], x.y + m[r4 + 1]);
+            a1 = max3f(a1, x.z + m[r4 + 2], x.w + m[r4 + 3]);
+        }
+        wave_lds_sync();
+        float acc = fmaxf(a0, a1);
+        acc = fmaxf(acc, quad_xor1(acc));
+        if constexpr (PARTS == 4) acc = fmaxf(acc, quad_xor2(acc));
+        const float mx = wave_max(acc);
+        v = acc - ((mx == -INFINITY) ? 0.0f : mx);
+    };
+#pragma unroll
+    for (int p = 0; p < PF; ++p) load_mat(p, pv[p]);
+    const int nfull = cps / PF * PF;
+    for (int c0 = 0; c0 < nfull; c0 += PF) {
+#pragma unroll
+        for (int p = 0; p < PF; ++p) {
+            hop(c0 + p, pv[p]);
+            load_mat(c0 + p + PF, pv[p]);
+        }
+    }
+#pragma unroll
+    for (int p = 0; p < PF; ++p)
+        if (nfull + p < cps) hop(nfull + p, pv[p]);   // slot p holds hop nfull + p
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -521,8 +586,12 @@ static int large_viterbi_impl(const LargeArgs& a, int32_t* path, double* logprob
     const dim3 block(256);
     launch("lv_aggregate", lv_aggregate_systolic_kernel<D>, dim3((unsigned)((p.nchunks + M::CPW - 1) / M::CPW)), block,
            st, a.A, a.ll, a.T, a.D, p.Lc, p.cps, p.nchunks, a.shared_model, agg);
-    launch("lv_carry", lv_carry_kernel<D>, dim3((unsigned)a.batch), block, st, a.prior, a.D, p.cps, a.shared_model, agg,
-           vin);
+    if constexpr (D <= 32)
+        launch("lv_carry", lv_carry_wave_kernel<D>, dim3((unsigned)a.batch), dim3(64), st, a.prior, a.D, p.cps,
+               a.shared_model, agg, vin);
+    else
+        launch("lv_carry", lv_carry_kernel<D>, dim3((unsigned)a.batch), block, st, a.prior, a.D, p.cps, a.shared_model,
+               agg, vin);
     const size_t fwd_lds = (size_t)C::VCPW * p.Lc * D;
     launch_dyn("lv_forward", lv_forward_kernel<D>, dim3((unsigned)((p.nchunks + C::VCPW - 1) / C::VCPW)), block, fwd_lds,
                st, a.prior, a.A, a.ll, a.T, a.D, p.Lc, p.cps, p.nchunks, a.shared_model, vin, bp, cmap, xstar, part);

@@ -278,6 +278,100 @@ __global__ __launch_bounds__(256) void ld_carry_kernel(const float* __restrict__
     }
 }
 
+// The same carries for D <= 32 by a single wave per (sequence, direction): lane = (column j, part h
+// of the summation range), parts combined with quad permutes, the vector passed through LDS with
+// wave-level ordering only.  A hop costs a few hundred cycles instead of three workgroup barriers,
+// which is what bounds a long sequence (its chunks are visited one after the other); aggregates are
+// prefetched PF hops ahead because a hop is much shorter than a memory round trip.
+template <int D>
+__global__ __launch_bounds__(64) void ld_carry_wave_kernel(const float* __restrict__ prior, int Dr, int cps,
+                                                           int shared_model, const float* __restrict__ agg,
+                                                           const float* __restrict__ aggT,
+                                                           const int* __restrict__ exps, float* __restrict__ fin,
+                                                           float* __restrict__ bout) {
+    using C = LargeCfg<D>;
+    static_assert(D <= 32, "one wave covers the columns");
+    constexpr int PARTS = 64 / D;       // 2 or 4 lanes per column
+    constexpr int RPT = D / PARTS;      // summation terms per lane
+    constexpr int PF = 8;               // prefetch distance in hops
+    __shared__ __align__(16) float vec[D];
+    const int seq = blockIdx.x >> 1, dir = blockIdx.x & 1;
+    const int lane = threadIdx.x;
+    const int h = lane % PARTS, j = lane / PARTS;
+    // the lane's terms M(h*RPT + r, j) are contiguous in the transposed copy: 16-byte loads
+    const float* mats = (dir == 0 ? aggT : agg) + (size_t)seq * cps * D * D;
+    const int* ex = exps + (size_t)seq * cps * C::WPC;
+    float* out = (dir == 0 ? fin : bout) + (size_t)seq * cps * D;
+    float v;
+    if (dir == 0) v = (j < Dr) ? prior[(shared_model ? 0 : (size_t)seq * Dr) + j] : 0.0f;
+    else v = (j < Dr) ? 1.0f : 0.0f;
+    settle_loaded(v);
+    float pm[PF][RPT];
+    int exn[PF][C::WPC];
+    auto chunk_of = [&](int it) { return dir == 0 ? it : cps - 1 - it; };
+    // Loads are unconditional (the hop index is clamped) and the exponents come through vector loads:
+    // the compiler can then count outstanding loads exactly and wait only for the slot it needs,
+    // where a conditional or scalar load would make every hop wait for the newest prefetch.
+    const int lane_zero = __builtin_amdgcn_mbcnt_lo(0u, 0u);   // 0, but not known to be uniform
+    auto load_mat = [&](int it, float (&m)[RPT], int (&e)[C::WPC]) {
+        const int c = chunk_of(it < cps ? it : cps - 1);
+        const float* M = mats + (size_t)c * D * D + (size_t)j * D + h * RPT;
+#pragma unroll
+        for (int r4 = 0; r4 < RPT; r4 += 4) {
+            const float4 x = *reinterpret_cast<const float4*>(M + r4);
+            m[r4] = x.x; m[r4 + 1] = x.y; m[r4 + 2] = x.z; m[r4 + 3] = x.w;
+        }
+#pragma unroll
+        for (int s = 0; s < C::WPC; ++s) e[s] = ex[c * C::WPC + s + lane_zero];
+    };
+    auto hop = [&](int it, const float (&m)[RPT], const int (&e)[C::WPC]) {
+        const int c = chunk_of(it);
+        int exmax = e[0];
+#pragma unroll
+        for (int s = 1; s < C::WPC; ++s) exmax = max(exmax, e[s]);
+        int exj = e[0];    // exponent of the strip that row j of P belongs to
+#pragma unroll
+        for (int s = 1; s < C::WPC; ++s) exj = (j / C::TS == s) ? e[s] : exj;
+        if (h == 0) {
+            out[(size_t)c * D + j] = v;
+            // dir 0 sums over rows of P, whose scale depends on the row's strip: fold it into the vector
+            vec[j] = (dir == 0) ? ldexpf(v, exj - exmax) : v;
+        }
+        wave_lds_sync();
+        float a0 = 0.0f, a1 = 0.0f, a2 = 0.0f, a3 = 0.0f;   // independent chains
+#pragma unroll
+        for (int r4 = 0; r4 < RPT; r4 += 4) {
+            const float4 x = *reinterpret_cast<const float4*>(vec + h * RPT + r4);
+            a0 = fmaf(x.x, m[r4], a0);
+            a1 = fmaf(x.y, m[r4 + 1], a1);
+            a2 = fmaf(x.z, m[r4 + 2], a2);
+            a3 = fmaf(x.w, m[r4 + 3], a3);
+        }
+        wave_lds_sync();
+        float acc = (a0 + a1) + (a2 + a3);
+        acc += quad_xor1(acc);
+        if constexpr (PARTS == 4) acc += quad_xor2(acc);
+        // dir 1 produces rows of P: scale by the row's strip
+        const float g = (dir == 1) ? ldexpf(acc, exj - exmax) : acc;
+        // keep the vector in range with an exact power of two (its scale is irrelevant downstream)
+        const float mx = wave_max(g);
+        v = ldexpf(g, -__builtin_amdgcn_frexp_expf(mx));
+    };
+#pragma unroll
+    for (int p = 0; p < PF; ++p) load_mat(p, pm[p], exn[p]);
+    const int nfull = cps / PF * PF;
+    for (int it0 = 0; it0 < nfull; it0 += PF) {
+#pragma unroll
+        for (int p = 0; p < PF; ++p) {
+            hop(it0 + p, pm[p], exn[p]);
+            load_mat(it0 + p + PF, pm[p], exn[p]);
+        }
+    }
+#pragma unroll
+    for (int p = 0; p < PF; ++p)
+        if (nfull + p < cps) hop(nfull + p, pm[p], exn[p]);   // slot p holds hop nfull + p
+}
+
 // ---------------------------------------------------------------------------------------------
 // Vector recursions inside the chunks.  Lane = (column or row c inside the wave, part h of the
 // summation range), with h in the lowest lane bits so that parts are combined with quad
@@ -285,7 +379,7 @@ __global__ __launch_bounds__(256) void ld_carry_kernel(const float* __restrict__
 template <int D>
 HMM_DEV void apply_sync() {
     if constexpr (LargeCfg<D>::VWPC > 1) lds_barrier();
-    else __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    else wave_lds_sync();
 }
 
 template <int D>
@@ -679,8 +773,12 @@ static int large_smooth_impl(const LargeArgs& a, float* marg, float* filt, doubl
     launch("ld_rowmax", ld_rowmax_kernel, dim3((unsigned)((rows + 3) / 4)), block, st, a.ll, rows, a.D, rowmax);
     launch("ld_aggregate", ld_aggregate_kernel<D>, dim3((unsigned)((p.nchunks + C::CPW - 1) / C::CPW)), block, st, a.A,
            a.ll, rowmax, a.T, a.D, p.Lc, p.cps, p.nchunks, a.shared_model, agg, aggT, exps);
-    launch("ld_carry", ld_carry_kernel<D>, dim3(2u * (unsigned)a.batch), block, st, a.prior, a.D, p.cps, a.shared_model,
-           agg, aggT, exps, fin, bout);
+    if constexpr (D <= 32)
+        launch("ld_carry", ld_carry_wave_kernel<D>, dim3(2u * (unsigned)a.batch), dim3(64), st, a.prior, a.D, p.cps,
+               a.shared_model, agg, aggT, exps, fin, bout);
+    else
+        launch("ld_carry", ld_carry_kernel<D>, dim3(2u * (unsigned)a.batch), block, st, a.prior, a.D, p.cps,
+               a.shared_model, agg, aggT, exps, fin, bout);
     const int half = (int)((p.nchunks + C::VCPW - 1) / C::VCPW);
     launch("ld_apply", ld_apply_kernel<D>, dim3(2u * (unsigned)half), block, st, a.prior, a.A, a.ll, rowmax, a.T, a.D,
            p.Lc, p.cps, p.nchunks, a.shared_model, fin, bout, F, Bv, part, half);
