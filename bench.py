@@ -8,6 +8,7 @@ input/output buffer sets so that consecutive steps do not find their data in the
 Infinity Cache.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2|C3|C4|C5]
+    python bench.py --ge-sweep      (the paper's Gilbert-Elliott model over a range of T, Sec. VI)
 
 --workload selects one of the other synthetic configurations (D=32 long sequence, 256 x D=16
 batch, D=128 compute-bound) for the same measurement; the headline line is the default, C2.
@@ -68,6 +69,63 @@ def kernel_roofline(name: str, avg_us: float, B: int, T: int, D: int) -> dict:
             "frac": ach / HBM_PEAK_GBS, "traffic": None, "algorithmic_bytes_per_launch": alg_bytes}
 
 
+def ge_sweep() -> int:
+    """Run time against sequence length on the paper's Gilbert-Elliott model (Sec. VI, Figs. 5-6):
+    one JSON line with, per T, the median time of an hmm_smooth and an hmm_viterbi call (inputs
+    resident, back-to-back enqueue of `reps` calls / reps) and the sequential fp64 oracle beside it."""
+    import numpy as np
+    import torch
+
+    import paper_2102_05743_amd as hmm
+    from paper_2102_05743_amd import workloads as wl
+    import oracle
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    hmm.load_library()
+    dev = torch.device("cuda:0")
+    rows = []
+    for T in (100, 1000, 10_000, 100_000, 1 << 20, 1 << 22, 1 << 24):
+        p = wl.gilbert_elliott(T=T)
+        prior = torch.from_numpy(p.prior).to(dev)
+        A = torch.from_numpy(p.A).to(dev)
+        ll = torch.from_numpy(p.loglik).to(dev)
+        marg = torch.empty_like(ll)
+        path = torch.empty((1, T), dtype=torch.int32, device=dev)
+        out = torch.empty((2, 1), dtype=torch.float64, device=dev)
+        ws_s, ws_v = hmm.hmm_workspace_bytes(T, p.D, 1)
+        ws = torch.empty((max(ws_s, ws_v, 256),), dtype=torch.uint8, device=dev)
+        calls = {"smooth": hmm.hmm_smooth_prepare(prior, A, ll, marginals=marg, loglik_out=out[0], workspace=ws),
+                 "viterbi": hmm.hmm_viterbi_prepare(prior, A, ll, path=path, logprob_out=out[1], workspace=ws)}
+        row = {"T": T}
+        reps = 100 if T <= (1 << 20) else 20
+        for name, fn in calls.items():
+            for _ in range(5):
+                fn()
+            torch.cuda.synchronize()
+            times = []
+            for _ in range(5):
+                t0 = time.perf_counter()
+                for _ in range(reps):
+                    fn()
+                torch.cuda.synchronize()
+                times.append((time.perf_counter() - t0) / reps)
+            row[name + "_us"] = 1e6 * float(np.median(times))
+        if T <= (1 << 22):
+            c0 = time.perf_counter()
+            oracle.smooth(p.prior[0], p.A[0], p.loglik[0], want_filtered=False)
+            c1 = time.perf_counter()
+            oracle.viterbi(p.prior[0], p.A[0], p.loglik[0])
+            c2 = time.perf_counter()
+            row["oracle_smooth_us"] = 1e6 * (c1 - c0)
+            row["oracle_viterbi_us"] = 1e6 * (c2 - c1)
+        rows.append(row)
+    print(json.dumps({"sweep": "Gilbert-Elliott model (Sec. VI), D=4, one sequence", "unit": "us per call",
+                      "rows": rows}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -80,7 +138,14 @@ def main() -> int:
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain device copy of 32 MiB per step (a kernel of known traffic, for scaling "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings)")
+    ap.add_argument("--ge-sweep", action="store_true",
+                    help="time both calls on the paper's Gilbert-Elliott model for T = 1e2 ... 2^24 instead")
     args = ap.parse_args()
+    if args.ge_sweep:
+        if args.gpus != 1:
+            print("bench.py: this build runs on ONE GPU only; run it with --gpus 1", file=sys.stderr)
+            return 2
+        return ge_sweep()
     gen_name, wl_text, d_sets, d_steps, d_warmup = WORKLOADS[args.workload]
     args.steps = d_steps if args.steps is None else args.steps
     args.warmup = d_warmup if args.warmup is None else args.warmup
@@ -122,12 +187,18 @@ def main() -> int:
         cal_src = torch.ones((8 << 20,), dtype=torch.float32, device=dev)     # 32 MiB
         cal_dst = torch.empty_like(cal_src)
 
+    # arguments marshalled once per buffer set: a step is then two bare C-ABI calls
+    smooth_calls = [hmm.hmm_smooth_prepare(prior, A, lls[s], marginals=margs[s], loglik_out=logliks[s],
+                                           workspace=ws_smooth) for s in range(nsets)]
+    viterbi_calls = [hmm.hmm_viterbi_prepare(prior, A, lls[s], path=paths[s], logprob_out=logprobs[s],
+                                             workspace=ws_viterbi) for s in range(nsets)]
+
     def step(i: int) -> None:
         s = i % nsets
         if cal_src is not None:
             cal_dst.copy_(cal_src)
-        hmm.hmm_smooth(prior, A, lls[s], marginals=margs[s], loglik_out=logliks[s], workspace=ws_smooth)
-        hmm.hmm_viterbi(prior, A, lls[s], path=paths[s], logprob_out=logprobs[s], workspace=ws_viterbi)
+        smooth_calls[s]()
+        viterbi_calls[s]()
 
     for i in range(args.warmup):
         step(i)

@@ -45,6 +45,8 @@ def _load():
         lib.hmm_oracle_viterbi.restype = ctypes.c_int
         lib.hmm_oracle_score.argtypes = [fp, fp, fp, ctypes.c_long, ctypes.c_int, ip]
         lib.hmm_oracle_score.restype = ctypes.c_double
+        lib.hmm_oracle_max_product.argtypes = [fp, fp, fp, ctypes.c_long, ctypes.c_int, dp, ip, dp]
+        lib.hmm_oracle_max_product.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -101,6 +103,31 @@ def score(prior, A, loglik, path) -> float:
     path = np.ascontiguousarray(path, dtype=np.int32)
     assert path.shape == (T,) and path.min() >= 0 and path.max() < D
     return float(lib.hmm_oracle_score(pp, pa, pl, T, D, path.ctypes.data_as(ctypes.POINTER(ctypes.c_int))))
+
+
+def max_product(prior, A, loglik):
+    """One sequence: the max-product forward/backward recursions (Sec. IV-C) and Theorem 4.
+    Returns (maxmarg[T][D] f64 = log p*(x_k) - log max joint weight, path[T] int32, logprob f64)."""
+    lib = _load()
+    prior, pp = _f32(prior)
+    A, pa = _f32(A)
+    loglik, pl = _f32(loglik)
+    T, D = loglik.shape
+    assert prior.shape == (D,) and A.shape == (D, D)
+    mm = np.empty((T, D), dtype=np.float64)
+    path = np.empty(T, dtype=np.int32)
+    lp = ctypes.c_double(0.0)
+    rc = lib.hmm_oracle_max_product(pp, pa, pl, T, D, mm.ctypes.data_as(ctypes.POINTER(ctypes.c_double)),
+                                    path.ctypes.data_as(ctypes.POINTER(ctypes.c_int)), ctypes.byref(lp))
+    if rc != 0:
+        raise RuntimeError("hmm_oracle_max_product failed")
+    return mm, path, float(lp.value)
+
+
+def max_product_batch(prior, A, loglik, shared_model: bool):
+    B = loglik.shape[0]
+    outs = [max_product(prior[0 if shared_model else b], A[0 if shared_model else b], loglik[b]) for b in range(B)]
+    return np.stack([o[0] for o in outs]), np.stack([o[1] for o in outs]), np.array([o[2] for o in outs])
 
 
 def smooth_batch(prior, A, loglik, shared_model: bool, want_filtered: bool = True):

@@ -163,3 +163,68 @@ double hmm_oracle_score(const float *prior, const float *A, const float *ll,
     }
     return s;
 }
+
+/*
+ * Max-product forward/backward recursions (the lemma of Sec. IV-C) on logarithms
+ * of the potentials, and the per-step maximiser of Theorem 4:
+ *   f_1(x_1) = log psi_1(x_1),  f_k(x_k) = max_{x_{k-1}} [log psi_k(x_{k-1},x_k) + f_{k-1}(x_{k-1})]
+ *   b_T(x_T) = 0,               b_k(x_k) = max_{x_{k+1}} [log psi_{k+1}(x_k,x_{k+1}) + b_{k+1}(x_{k+1})]
+ *   x*_k = argmax_{x_k} [f_k(x_k) + b_k(x_k)]        (lowest index on ties)
+ * f_k + b_k is the logarithm of the max-marginal p*(x_k) of Sec. II (the largest
+ * joint weight over all sequences that pass through x_k at step k).  It is
+ * returned relative to its own maximum over x_k, which is the same for every k
+ * and equals *logprob = log of the largest joint weight:
+ *   maxmarg[k][j] = f_k(j) + b_k(j) - logprob   (<= 0, and 0 at x*_k).
+ * Returns 0, or 1 on allocation failure / bad sizes.
+ */
+int hmm_oracle_max_product(const float *prior, const float *A, const float *ll,
+                           long T, int D, double *maxmarg, int *path, double *logprob)
+{
+    if (T < 1 || D < 1) return 1;
+    double *f = (double *)malloc(sizeof(double) * (size_t)T * D);
+    double *b = (double *)malloc(sizeof(double) * D);
+    double *bn = (double *)malloc(sizeof(double) * D);
+    double *logA = (double *)malloc(sizeof(double) * (size_t)D * D);
+    if (!f || !b || !bn || !logA) { free(f); free(b); free(bn); free(logA); return 1; }
+    for (size_t e = 0; e < (size_t)D * D; ++e) logA[e] = log_or_neginf((double)A[e]);
+    for (int j = 0; j < D; ++j) f[j] = log_or_neginf((double)prior[j]) + (double)ll[j];
+    for (long k = 1; k < T; ++k) {
+        const double *fp = f + (size_t)(k - 1) * D;
+        double *fk = f + (size_t)k * D;
+        for (int j = 0; j < D; ++j) {
+            double best = -INFINITY;
+            for (int i = 0; i < D; ++i) {
+                double v = fp[i] + logA[(size_t)i * D + j];
+                if (v > best) best = v;
+            }
+            fk[j] = best + (double)ll[(size_t)k * D + j];
+        }
+    }
+    double top = -INFINITY;
+    for (int j = 0; j < D; ++j) if (f[(size_t)(T - 1) * D + j] > top) top = f[(size_t)(T - 1) * D + j];
+    *logprob = top;
+    for (int j = 0; j < D; ++j) b[j] = 0.0;
+    for (long k = T - 1; k >= 0; --k) {
+        const double *fk = f + (size_t)k * D;
+        double best = -INFINITY; int arg = 0;
+        for (int j = 0; j < D; ++j) {
+            double v = fk[j] + b[j];
+            if (v > best) { best = v; arg = j; }
+        }
+        path[k] = arg;
+        for (int j = 0; j < D; ++j) maxmarg[(size_t)k * D + j] = fk[j] + b[j] - top;
+        if (k > 0) {
+            for (int i = 0; i < D; ++i) {
+                double m = -INFINITY;
+                for (int j = 0; j < D; ++j) {
+                    double v = logA[(size_t)i * D + j] + (double)ll[(size_t)k * D + j] + b[j];
+                    if (v > m) m = v;
+                }
+                bn[i] = m;
+            }
+            double *t = b; b = bn; bn = t;
+        }
+    }
+    free(f); free(b); free(bn); free(logA);
+    return 0;
+}

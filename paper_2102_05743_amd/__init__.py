@@ -3,5 +3,6 @@
 ``binding`` wraps the C-ABI HIP library (libhmmscan.so); ``workloads`` holds the
 seeded synthetic inputs; ``build`` compiles the library in-tree.
 """
-from .binding import (HmmError, hmm_kernel_timing_enable, hmm_kernel_timing_get, hmm_smooth,  # noqa: F401
-                      hmm_viterbi, hmm_workspace_bytes, load_library, status_string)
+from .binding import (HmmError, PreparedCall, hmm_kernel_timing_enable, hmm_kernel_timing_get,  # noqa: F401
+                      hmm_smooth, hmm_smooth_prepare, hmm_viterbi, hmm_viterbi_prepare, hmm_workspace_bytes,
+                      load_library, status_string)

@@ -116,11 +116,24 @@ def _stream():
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
 
 
-def hmm_smooth(prior, A, loglik, marginals=None, filtered=None, loglik_out=None, workspace=None,
-               want_filtered: bool = False):
-    """prior[Bm][D], A[Bm][D][D], loglik[B][T][D] float32 device tensors (Bm = 1 or B).
-    Returns (marginals[B][T][D] f32, filtered or None, loglik_out[B] f64); asynchronous on
-    torch's current stream."""
+class PreparedCall:
+    """One C-ABI call with its arguments marshalled once: calling the object enqueues it again on the
+    stream that was current at preparation.  For loops that repeat a call on the same buffers, where
+    re-validating tensors and rebuilding ctypes arguments would cost more host time than the call."""
+
+    def __init__(self, fn, where, cargs, keep, result):
+        self._fn, self._where, self._cargs, self._keep, self.result = fn, where, cargs, keep, result
+
+    def __call__(self):
+        rc = self._fn(*self._cargs)
+        if rc != HMM_OK:
+            raise HmmError(rc, self._where)
+        return self.result
+
+
+def hmm_smooth_prepare(prior, A, loglik, marginals=None, filtered=None, loglik_out=None, workspace=None,
+                       want_filtered: bool = False) -> PreparedCall:
+    """Validates and marshals an hmm_smooth call; see hmm_smooth for the arguments."""
     import torch
     lib = load_library()
     B, T, D, Bm, shared = _shapes(prior, A, loglik)
@@ -141,15 +154,22 @@ def hmm_smooth(prior, A, loglik, marginals=None, filtered=None, loglik_out=None,
     _check(loglik_out, torch.float64, (B,), "loglik_out")
     if workspace is None:
         workspace = torch.empty((max(hmm_workspace_bytes(T, D, B)[0], 256),), dtype=torch.uint8, device=dev)
-    rc = lib.hmm_smooth(_ptr(prior), _ptr(A), _ptr(loglik), T, D, B, shared, _ptr(marginals), _ptr(filtered),
-                        _ptr(loglik_out), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream())
-    if rc != HMM_OK:
-        raise HmmError(rc, "hmm_smooth")
-    return marginals, filtered, loglik_out
+    cargs = (_ptr(prior), _ptr(A), _ptr(loglik), T, D, B, shared, _ptr(marginals), _ptr(filtered),
+             _ptr(loglik_out), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream())
+    return PreparedCall(lib.hmm_smooth, "hmm_smooth", cargs, (prior, A, loglik, workspace),
+                        (marginals, filtered, loglik_out))
 
 
-def hmm_viterbi(prior, A, loglik, path=None, logprob_out=None, workspace=None):
-    """Returns (path[B][T] int32, logprob_out[B] f64); asynchronous on torch's current stream."""
+def hmm_smooth(prior, A, loglik, marginals=None, filtered=None, loglik_out=None, workspace=None,
+               want_filtered: bool = False):
+    """prior[Bm][D], A[Bm][D][D], loglik[B][T][D] float32 device tensors (Bm = 1 or B).
+    Returns (marginals[B][T][D] f32, filtered or None, loglik_out[B] f64); asynchronous on
+    torch's current stream."""
+    return hmm_smooth_prepare(prior, A, loglik, marginals, filtered, loglik_out, workspace, want_filtered)()
+
+
+def hmm_viterbi_prepare(prior, A, loglik, path=None, logprob_out=None, workspace=None) -> PreparedCall:
+    """Validates and marshals an hmm_viterbi call; see hmm_viterbi for the arguments."""
     import torch
     lib = load_library()
     B, T, D, Bm, shared = _shapes(prior, A, loglik)
@@ -166,8 +186,11 @@ def hmm_viterbi(prior, A, loglik, path=None, logprob_out=None, workspace=None):
     _check(logprob_out, torch.float64, (B,), "logprob_out")
     if workspace is None:
         workspace = torch.empty((max(hmm_workspace_bytes(T, D, B)[1], 256),), dtype=torch.uint8, device=dev)
-    rc = lib.hmm_viterbi(_ptr(prior), _ptr(A), _ptr(loglik), T, D, B, shared, _ptr(path), _ptr(logprob_out),
-                         _ptr(workspace), workspace.numel() * workspace.element_size(), _stream())
-    if rc != HMM_OK:
-        raise HmmError(rc, "hmm_viterbi")
-    return path, logprob_out
+    cargs = (_ptr(prior), _ptr(A), _ptr(loglik), T, D, B, shared, _ptr(path), _ptr(logprob_out),
+             _ptr(workspace), workspace.numel() * workspace.element_size(), _stream())
+    return PreparedCall(lib.hmm_viterbi, "hmm_viterbi", cargs, (prior, A, loglik, workspace), (path, logprob_out))
+
+
+def hmm_viterbi(prior, A, loglik, path=None, logprob_out=None, workspace=None):
+    """Returns (path[B][T] int32, logprob_out[B] f64); asynchronous on torch's current stream."""
+    return hmm_viterbi_prepare(prior, A, loglik, path, logprob_out, workspace)()

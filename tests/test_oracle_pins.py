@@ -206,3 +206,55 @@ def test_ties_resolve_to_the_lowest_state():
     assert abs(lp - T * np.log(np.float64(np.float32(1.0 / 3)))) < 1e-12
     seqs, best = bf.map_sequence(prior, A, ll)
     assert seqs.shape[0] == D ** T and abs(best - lp) < 1e-12
+
+
+# ------------------------------------------------------------------ max-product forward/backward (Sec. IV-C, Theorem 4)
+@pytest.mark.parametrize("D,T,seed,zf", [(3, 8, 30, 0.0), (3, 8, 31, 0.3), (2, 1, 32, 0.0), (2, 12, 33, 0.0),
+                                         (4, 5, 34, 0.25), (5, 4, 35, 0.0), (2, 2, 36, 0.0)])
+def test_max_product_matches_enumeration(D, T, seed, zf):
+    """log p*(x_k) (the max-marginal of Sec. II) by enumeration of all D^T sequences."""
+    prior, A, ll = _tiny(D, T, seed, zf)
+    mm, path, lp = oracle.max_product(prior, A, ll)
+    pstar = bf.max_marginals(prior, A, ll)
+    best_seqs, best_lp = bf.map_sequence(prior, A, ll)
+    assert abs(lp - best_lp) < 1e-12 * max(1.0, abs(best_lp))
+    with np.errstate(divide="ignore"):
+        want = np.log(pstar) - best_lp
+    finite = np.isfinite(want)
+    assert (np.isneginf(mm[~finite])).all()
+    assert np.abs(mm[finite] - want[finite]).max() < 1e-11
+    assert best_seqs.shape[0] == 1 and (path == best_seqs[0]).all()
+
+
+@pytest.mark.parametrize("gen", [lambda: wl.config1(), lambda: wl.config2(T=5000), lambda: wl.gilbert_elliott(T=3000),
+                                 lambda: wl.config3(T=500), lambda: wl.config5(T=300)])
+def test_max_product_invariants(gen):
+    """max_x [f_k(x) + b_k(x)] is the same for every k (proof of Theorem 4) and equals the Viterbi
+    log-probability; on inputs with a unique MAP sequence the per-step maximiser is the Viterbi path."""
+    p = gen()
+    prior, A, ll = p.prior[0], p.A[0], p.loglik[0]
+    mm, path, lp = oracle.max_product(prior, A, ll)
+    vpath, vlp = oracle.viterbi(prior, A, ll)
+    assert abs(lp - vlp) < 1e-9 * abs(vlp)
+    assert np.abs(mm.max(axis=1)).max() < 1e-7          # every step's best max-marginal is the MAP weight
+    assert (mm <= 1e-7).all()
+    k = np.arange(p.T)
+    assert np.abs(mm[k, vpath]).max() < 1e-7            # the Viterbi path runs through maximisers only
+    unique = (mm > -1e-9).sum(axis=1) == 1              # steps whose maximiser is unique (all of them without ties;
+    assert (path[unique] == vpath[unique]).all()        # the Gilbert-Elliott model has exactly tied sequences)
+    if p.name != "GE":
+        assert unique.all()
+    # the max-marginal of a state dominates the weight of any sequence through it: here the sampled one
+    sc = oracle.score(prior, A, ll, p.states[0])
+    assert (mm[k, p.states[0]] + lp >= sc - 1e-6).all()
+
+
+def test_max_product_single_state_and_single_step():
+    ll = np.array([[-0.3], [-1.2], [-0.1]], np.float32)
+    mm, path, lp = oracle.max_product(np.ones(1, np.float32), np.ones((1, 1), np.float32), ll)
+    assert (mm == 0).all() and (path == 0).all() and abs(lp - float(ll.astype(np.float64).sum())) < 1e-12
+    prior = np.array([0.2, 0.5, 0.3], np.float32)
+    ll1 = np.array([[-1.0, -2.0, -0.5]], np.float32)
+    mm, path, lp = oracle.max_product(prior, np.full((3, 3), 1 / 3, np.float32), ll1)
+    w = np.log(prior.astype(np.float64)) + ll1[0]
+    assert path[0] == w.argmax() and abs(lp - w.max()) < 1e-15 and np.abs(mm[0] - (w - w.max())).max() < 1e-15

@@ -84,6 +84,9 @@ def test_algorithm5_equals_classical_viterbi(D, T, seed):
         mm = bf.max_marginals(prior, A, ll)
         with np.errstate(divide="ignore"):
             assert np.abs(tab - np.log(mm)).max() < 1e-11
+    # the sequential max-product recursions (the oracle of hmm_max_product) give the same table
+    mm_o, path_o, lp_o = oracle.max_product(prior, A, ll)
+    assert np.abs((tab - lp) - mm_o).max() < 1e-9 and (path_o == path).all() and abs(lp_o - lp) < 1e-10 * max(1.0, abs(lp))
 
 
 def test_gilbert_elliott_long_sequence():
