@@ -88,6 +88,30 @@ hmm_status hmm_viterbi(const float* prior, const float* A, const float* loglik,
                        int32_t* path, double* logprob_out,
                        void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/*
+ * Max-marginals and the per-step MAP states by the paper's parallel max-product
+ * algorithm as printed (Algorithm 5): forward all-prefix-sums and reversed
+ * all-prefix-sums under the operator of Definition 5 (on logarithms) give the
+ * maximum forward and backward potentials psi~^f_k and psi~^b_k (the lemma of
+ * Sec. IV-C), and Theorem 4 takes x*_k = argmax_{x_k} psi~^f_k(x_k) psi~^b_k(x_k).
+ *
+ *   max_marginals [batch][T][D]  out: log p*(x_t = j) - logprob_out, where p*(x_t) is the
+ *                 max-marginal of Sec. II (the largest joint weight of a state sequence that
+ *                 passes through j at step t): every entry is <= 0 and the step's largest is 0
+ *   path          [batch][T]     out, may be NULL: per-step maximiser (lowest state on ties).
+ *                 With a unique MAP sequence this is the Viterbi path (Theorem 4); with tied
+ *                 sequences the per-step choice may splice several of them -- use hmm_viterbi
+ *                 when one consistent path is required
+ *   logprob_out   [batch]        out: log of the largest joint weight, as in hmm_viterbi
+ *   workspace: at least hmm_workspace_bytes(...).smooth_bytes, 256-byte aligned
+ * Other arguments as for hmm_smooth; loglik and max_marginals must be 16-byte aligned.
+ * Supported for D <= 8; larger D returns HMM_ERR_UNSUPPORTED.
+ */
+hmm_status hmm_max_product(const float* prior, const float* A, const float* loglik,
+                           int64_t T, int32_t D, int32_t batch, int32_t shared_model,
+                           float* max_marginals, int32_t* path, double* logprob_out,
+                           void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Static, human-readable name of a status code. */
 const char* hmm_status_string(hmm_status status);
 

@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libhmmscan.so")
 HMM_OK = 0
 _lib = None
 
-EXPORTED_SYMBOLS = ("hmm_workspace_bytes", "hmm_smooth", "hmm_viterbi", "hmm_status_string",
+EXPORTED_SYMBOLS = ("hmm_workspace_bytes", "hmm_smooth", "hmm_viterbi", "hmm_max_product", "hmm_status_string",
                     "hmm_kernel_timing_enable", "hmm_kernel_timing_count", "hmm_kernel_timing_get")
 
 
@@ -44,6 +44,9 @@ def load_library():
         lib.hmm_viterbi.argtypes = [vp, vp, vp, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                                     vp, vp, vp, sz, vp]
         lib.hmm_viterbi.restype = ctypes.c_int
+        lib.hmm_max_product.argtypes = [vp, vp, vp, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                        vp, vp, vp, vp, sz, vp]
+        lib.hmm_max_product.restype = ctypes.c_int
         lib.hmm_status_string.argtypes = [ctypes.c_int]
         lib.hmm_status_string.restype = ctypes.c_char_p
         lib.hmm_kernel_timing_enable.argtypes = [ctypes.c_int32]
@@ -194,3 +197,39 @@ def hmm_viterbi_prepare(prior, A, loglik, path=None, logprob_out=None, workspace
 def hmm_viterbi(prior, A, loglik, path=None, logprob_out=None, workspace=None):
     """Returns (path[B][T] int32, logprob_out[B] f64); asynchronous on torch's current stream."""
     return hmm_viterbi_prepare(prior, A, loglik, path, logprob_out, workspace)()
+
+
+def hmm_max_product_prepare(prior, A, loglik, max_marginals=None, path=None, logprob_out=None, workspace=None,
+                            want_path: bool = True) -> PreparedCall:
+    """Validates and marshals an hmm_max_product call; see hmm_max_product for the arguments."""
+    import torch
+    lib = load_library()
+    B, T, D, Bm, shared = _shapes(prior, A, loglik)
+    f32 = torch.float32
+    _check(prior, f32, (Bm, D), "prior")
+    _check(A, f32, (Bm, D, D), "A")
+    _check(loglik, f32, (B, T, D), "loglik")
+    dev = loglik.device
+    if max_marginals is None:
+        max_marginals = torch.empty((B, T, D), dtype=f32, device=dev)
+    if path is None and want_path:
+        path = torch.empty((B, T), dtype=torch.int32, device=dev)
+    if logprob_out is None:
+        logprob_out = torch.empty((B,), dtype=torch.float64, device=dev)
+    _check(max_marginals, f32, (B, T, D), "max_marginals")
+    if path is not None:
+        _check(path, torch.int32, (B, T), "path")
+    _check(logprob_out, torch.float64, (B,), "logprob_out")
+    if workspace is None:
+        workspace = torch.empty((max(hmm_workspace_bytes(T, D, B)[0], 256),), dtype=torch.uint8, device=dev)
+    cargs = (_ptr(prior), _ptr(A), _ptr(loglik), T, D, B, shared, _ptr(max_marginals), _ptr(path),
+             _ptr(logprob_out), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream())
+    return PreparedCall(lib.hmm_max_product, "hmm_max_product", cargs, (prior, A, loglik, workspace),
+                        (max_marginals, path, logprob_out))
+
+
+def hmm_max_product(prior, A, loglik, max_marginals=None, path=None, logprob_out=None, workspace=None,
+                    want_path: bool = True):
+    """Returns (max_marginals[B][T][D] f32 (log, largest entry of a step is 0), path[B][T] int32 or None,
+    logprob_out[B] f64); asynchronous on torch's current stream."""
+    return hmm_max_product_prepare(prior, A, loglik, max_marginals, path, logprob_out, workspace, want_path)()

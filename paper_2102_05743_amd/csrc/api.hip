@@ -80,6 +80,23 @@ hmm_status hmm_viterbi(const float* prior, const float* A, const float* loglik, 
     return static_cast<hmm_status>(hmm::small_d_viterbi(D, a, path, logprob_out));
 }
 
+hmm_status hmm_max_product(const float* prior, const float* A, const float* loglik, int64_t T, int32_t D,
+                           int32_t batch, int32_t shared_model, float* max_marginals, int32_t* path,
+                           double* logprob_out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    hmm_status st = check_common(prior, A, loglik, T, D, batch);
+    if (st != HMM_OK) return st;
+    if (!max_marginals || !logprob_out) return HMM_ERR_INVALID_ARG;
+    if (!aligned16(max_marginals)) return HMM_ERR_INVALID_ARG;
+    if (D > hmm::SMALL_D_MAX) return HMM_ERR_UNSUPPORTED;
+    size_t need = 0;
+    st = hmm_workspace_bytes(T, D, batch, &need, nullptr);
+    if (st != HMM_OK) return st;
+    if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return HMM_ERR_WORKSPACE;
+    hmm::SmallArgs a{prior, A, loglik, (long long)T, batch, shared_model ? 1 : 0, workspace, workspace_bytes,
+                     static_cast<hipStream_t>(hip_stream)};
+    return static_cast<hmm_status>(hmm::small_d_max_product(D, a, max_marginals, path, logprob_out));
+}
+
 const char* hmm_status_string(hmm_status status) {
     switch (status) {
         case HMM_OK: return "HMM_OK";

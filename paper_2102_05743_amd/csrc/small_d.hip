@@ -45,4 +45,9 @@ int small_d_viterbi(int D, const SmallArgs& a, int32_t* path, double* logprob_ou
     return 2;
 }
 
+int small_d_max_product(int D, const SmallArgs& a, float* maxmarg, int32_t* path, double* logprob_out) {
+    HMM_DISPATCH_SMALL_D(D, max_product(a, maxmarg, path, logprob_out))
+    return 2;
+}
+
 }  // namespace hmm

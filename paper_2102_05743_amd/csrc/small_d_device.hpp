@@ -570,6 +570,94 @@ HMM_DEV double mp_forward_impl(const float* row, int n, bool first, const float 
 }
 
 // ---------------------------------------------------------------------------------------------
+// Max-product forward/backward work inside a lane's chunk (the lemma of Sec. IV-C on logarithms).
+
+// Forward: psi~^f_k for the lane's steps, kept in registers as F, each step shifted to max 0.
+// v enters as the carry (max 0, or the log prior for the sequence's first chunk); returns the sum
+// of the shifts, i.e. the chunk-local growth of the log of the best joint weight.
+template <int D, bool FULL>
+HMM_DEV double mpv_forward_impl(const float* row, int n, bool first, const float (&Am)[D * D], float (&v)[D],
+                                float (&F)[SmallCfg<D>::L][D]) {
+    using C = SmallCfg<D>;
+    using S = MaxPlus;
+    double osum = 0.0;
+#pragma unroll
+    for (int k = 0; k < C::L; ++k) {
+        if (FULL || k < n) {
+            float lk[D], g[D];
+            lds_read_vec<D>(row + k * D, lk);
+            if (k == 0 && first) {
+#pragma unroll
+                for (int j = 0; j < D; ++j) g[j] = v[j] + lk[j];
+            } else {
+                vec_mat<S, D>(v, Am, g);
+#pragma unroll
+                for (int j = 0; j < D; ++j) g[j] += lk[j];
+            }
+            osum += (double)renorm<S, D>(g);
+#pragma unroll
+            for (int j = 0; j < D; ++j) F[k][j] = v[j] = g[j];
+        }
+    }
+    return (!FULL && n == 0) ? 0.0 : osum;
+}
+
+// Backward: psi~^b_k and the max-marginal log psi~^f_k + log psi~^b_k (Theorem 4), shifted so that its
+// largest entry is 0 and written over the log-likelihoods in LDS.  b enters as the backward
+// potential at the chunk's last step.
+template <int D, bool FULL>
+HMM_DEV void mpv_backward_impl(float* row, int n, const float (&Am)[D * D], float (&b)[D],
+                               const float (&F)[SmallCfg<D>::L][D]) {
+    using C = SmallCfg<D>;
+    using S = MaxPlus;
+    renorm<S, D>(b);
+#pragma unroll
+    for (int k = C::L - 1; k >= 0; --k) {
+        if (FULL || k < n) {
+            float lk[D], gam[D];
+            lds_read_vec<D>(row + k * D, lk);
+#pragma unroll
+            for (int j = 0; j < D; ++j) gam[j] = F[k][j] + b[j];
+            renorm<S, D>(gam);
+            lds_write_vec<D>(row + k * D, gam);
+            if (k > 0) {
+                float t[D], r[D];
+#pragma unroll
+                for (int j = 0; j < D; ++j) t[j] = lk[j] + b[j];
+                mat_vec<S, D>(Am, t, r);
+                renorm<S, D>(r);
+#pragma unroll
+                for (int j = 0; j < D; ++j) b[j] = r[j];
+            }
+        }
+    }
+}
+
+// x_k = argmax_j of the D values of every valid step of the tile in LDS (lowest index on ties),
+// written coalesced.
+template <int D>
+HMM_DEV void store_argmax_tile(int32_t* __restrict__ dst, int nvalid, const float* lds) {
+    using C = SmallCfg<D>;
+#pragma unroll 4
+    for (int it = 0; it < C::L; ++it) {
+        const int s = it * C::NT + threadIdx.x;
+        if (s < nvalid) {
+            const float* p = lds + (s / C::L) * C::STRIDE + (s % C::L) * D;
+            float best = p[0];
+            int arg = 0;
+#pragma unroll
+            for (int j = 1; j < D; ++j) {
+                const float x = p[j];
+                const bool gt = x > best;
+                best = gt ? x : best;
+                arg = gt ? j : arg;
+            }
+            __builtin_nontemporal_store((int32_t)arg, dst + s);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // Viterbi back-pointer maps: a map [D] -> [D] packed BITS per entry into one 32-bit word.
 template <int D>
 HMM_DEV uint32_t map_identity() {

@@ -130,39 +130,53 @@ __global__ __launch_bounds__(256) void sd_carry_kernel(const float* __restrict__
     }
 }
 
-// Lane-level smoother work shared by both plans: forward scan, reversed scan and marginals
-// inside the lane's chunk; returns the chunk-local log evidence.
-template <int D, bool WRITE_FILT>
+// Lane-level two-filter work shared by both plans: forward scan, reversed scan and their per-step
+// combination inside the lane's chunk.  SumProd: marginals (Alg. 3), returns the chunk-local log
+// evidence.  MaxPlus: max-marginals (Alg. 5 / Theorem 4), returns the chunk-local growth of the log
+// of the best joint weight.
+template <class S, int D, bool WRITE_FILT>
 HMM_DEV double smooth_chunk(float* row, int n, bool first, const float (&Am)[D * D], float (&f)[D], float (&b)[D],
                             double msum, float* __restrict__ filt_dst) {
     using C = SmallCfg<D>;
     float F[C::L][D];
-    if (!first) {   // the prior is used as given; every other carry is rescaled to sum to one
-        const float inv = 1.0f / sum_of(f);
-#pragma unroll
-        for (int j = 0; j < D; ++j) f[j] *= inv;
-    }
     double delta;
-    if (n == C::L) {
-        delta = sp_forward_impl<D, WRITE_FILT, true>(row, n, first, Am, f, F, msum, filt_dst);
-        sp_backward_impl<D, true>(row, n, Am, b, F);
+    if constexpr (S::is_max_plus) {
+        if (!first) renorm<S, D>(f);   // the log prior is used as given; every other carry starts at max 0
+        if (n == C::L) {
+            delta = mpv_forward_impl<D, true>(row, n, first, Am, f, F);
+            mpv_backward_impl<D, true>(row, n, Am, b, F);
+        } else {
+            delta = mpv_forward_impl<D, false>(row, n, first, Am, f, F);
+            mpv_backward_impl<D, false>(row, n, Am, b, F);
+        }
     } else {
-        delta = sp_forward_impl<D, WRITE_FILT, false>(row, n, first, Am, f, F, msum, filt_dst);
-        sp_backward_impl<D, false>(row, n, Am, b, F);
+        if (!first) {   // the prior is used as given; every other carry is rescaled to sum to one
+            const float inv = 1.0f / sum_of(f);
+#pragma unroll
+            for (int j = 0; j < D; ++j) f[j] *= inv;
+        }
+        if (n == C::L) {
+            delta = sp_forward_impl<D, WRITE_FILT, true>(row, n, first, Am, f, F, msum, filt_dst);
+            sp_backward_impl<D, true>(row, n, Am, b, F);
+        } else {
+            delta = sp_forward_impl<D, WRITE_FILT, false>(row, n, first, Am, f, F, msum, filt_dst);
+            sp_backward_impl<D, false>(row, n, Am, b, F);
+        }
     }
     return delta;
 }
 
-// Kernel 3 (smoother): forward scan, reversed scan and marginals inside a tile
-template <int D, bool WRITE_FILT>
+// Kernel 3 (smoother, max-product): forward scan, reversed scan and (max-)marginals inside a tile;
+// `argmax`, if given, receives the per-step maximiser (Theorem 4).
+template <class S, int D, bool WRITE_FILT>
 __global__ __launch_bounds__(256) void sd_smooth_apply_kernel(const float* __restrict__ A,
                                                               const float* __restrict__ ll, long long T, int tps,
                                                               int shared_model, const float* __restrict__ fin_g,
                                                               const float* __restrict__ bout_g,
                                                               float* __restrict__ marg, float* __restrict__ filt,
+                                                              int32_t* __restrict__ argmax,
                                                               double* __restrict__ part) {
     using C = SmallCfg<D>;
-    using S = SumProd;
     __shared__ float lds[C::LDS_FLOATS];
     __shared__ float wagg[C::NW * D * D];
     __shared__ double dsum[C::NW];
@@ -186,11 +200,12 @@ __global__ __launch_bounds__(256) void sd_smooth_apply_kernel(const float* __res
     float f[D], b[D];
     block_exchange<S, D, true>(P, cf, cb, f, b, wagg);
     float* fdst = WRITE_FILT ? filt + (tc.base + (long long)threadIdx.x * C::L) * D : nullptr;
-    const double delta = smooth_chunk<D, WRITE_FILT>(row, n, first, Am, f, b, msum, fdst);
+    const double delta = smooth_chunk<S, D, WRITE_FILT>(row, n, first, Am, f, b, msum, fdst);
     const double tile_delta = block_sum(delta, dsum);
     if (threadIdx.x == 0) part[blockIdx.x] = tile_delta;
     __syncthreads();
     store_tile<D>(marg + tc.base * D, tc.nvalid, lds);
+    if (argmax != nullptr) store_argmax_tile<D>(argmax + tc.base, tc.nvalid, lds);
 }
 
 // Kernel 4: out[seq] = ordered sum of the tile partials of one sequence.
@@ -554,15 +569,14 @@ HMM_DEV void grid_sum_parts(int tile0, int tps, const FusedWs& ws, double* dsum,
     if (threadIdx.x == 0) out[seq] = s;
 }
 
-template <int D, bool WRITE_FILT>
+template <class S, int D, bool WRITE_FILT>
 __global__ __launch_bounds__(256) void sd_smooth_fused_kernel(const float* __restrict__ prior,
                                                               const float* __restrict__ A,
                                                               const float* __restrict__ ll, long long T, int tps,
                                                               int shared_model, float* __restrict__ marg,
-                                                              float* __restrict__ filt,
+                                                              float* __restrict__ filt, int32_t* __restrict__ argmax,
                                                               double* __restrict__ loglik_out, FusedWs ws) {
     using C = SmallCfg<D>;
-    using S = SumProd;
     __shared__ float lds[C::LDS_FLOATS];
     __shared__ float wagg[C::NW * D * D];
     __shared__ GridLds<D> gl;
@@ -604,13 +618,14 @@ __global__ __launch_bounds__(256) void sd_smooth_fused_kernel(const float* __res
     carry_backward<S, D>(R, wagg, cb, b);
     HMM_STAMP(7);
     float* fdst = WRITE_FILT ? filt + (tc.base + (long long)threadIdx.x * C::L) * D : nullptr;
-    const double delta = smooth_chunk<D, WRITE_FILT>(row, n, first, Am, f, b, msum, fdst);
+    const double delta = smooth_chunk<S, D, WRITE_FILT>(row, n, first, Am, f, b, msum, fdst);
     HMM_STAMP(8);
     const double tile_delta = block_sum(delta, dsum);   // contains a barrier: all marginals are in LDS
     if (threadIdx.x == 0)
         coherent_store(reinterpret_cast<unsigned long long*>(ws.part) + blockIdx.x, publish_bits(tile_delta));
     HMM_STAMP(9);
     store_tile<D>(marg + tc.base * D, tc.nvalid, lds);
+    if (argmax != nullptr) store_argmax_tile<D>(argmax + tc.base, tc.nvalid, lds);
     HMM_STAMP(10);
     if (tc.tile == 0) grid_sum_parts(blockIdx.x, tps, ws, dsum, loglik_out, tc.seq);
     HMM_STAMP(11);
@@ -778,9 +793,12 @@ static bool force_multi_launch() {
     return e != nullptr && e[0] == 'm';   // HMMSCAN_PLAN=multi forces the multi-launch plan
 }
 
-template <int D>
-int SmallD<D>::smooth(const SmallArgs& a, float* marg, float* filt, double* loglik_out) {
+// The two-filter plans for either operator: marginals + optional filtered + log evidence (SumProd),
+// or max-marginals + optional per-step maximiser + log of the best joint weight (MaxPlus).
+template <class S, int D>
+static int two_filter(const SmallArgs& a, float* marg, float* filt, int32_t* argmax, double* out) {
     using C = SmallCfg<D>;
+    constexpr bool MP = S::is_max_plus;
     const long long tps = tiles_per_seq<D>(a.T);
     const long long nt = tps * a.batch;
     if (nt > 0x7fffffffLL) return 2;
@@ -795,33 +813,55 @@ int SmallD<D>::smooth(const SmallArgs& a, float* marg, float* filt, double* logl
     hipStream_t st = a.stream;
     const dim3 grid((unsigned)nt), block(C::NT), seqs((unsigned)a.batch);
     const int itps = (int)tps;
-    const long long cap = filt ? resident_capacity<0>(sd_smooth_fused_kernel<D, true>)
-                               : resident_capacity<1>(sd_smooth_fused_kernel<D, false>);
+    long long cap = 0;
+    if constexpr (!MP) {
+        if (filt) cap = resident_capacity<0>(sd_smooth_fused_kernel<S, D, true>);
+    }
+    if (!filt) cap = resident_capacity<(MP ? 5 : 1)>(sd_smooth_fused_kernel<S, D, false>);
+    if (MP && filt) return 2;   // no filtered output is defined for the max-product plan
     if (!force_multi_launch() && tps <= C::NT && nt <= cap) {
         const XchLayout xl = xch_layout<D>((size_t)nt);
         FusedWs fw{reinterpret_cast<float*>(xch + xl.agg), reinterpret_cast<double*>(xch + xl.part), xch + xl.tmap,
                    xch + xl.err};
         const int nwords = (int)xl.words;
-        launch("sd_clear_sp", sd_clear_kernel<D>, dim3((nwords + 255) / 256), dim3(256), st, xch, nwords);
-        if (filt)
-            launch("sd_smooth_fused", sd_smooth_fused_kernel<D, true>, grid, block, st, a.prior, a.A, a.ll, a.T, itps,
-                   a.shared_model, marg, filt, loglik_out, fw);
-        else
-            launch("sd_smooth_fused", sd_smooth_fused_kernel<D, false>, grid, block, st, a.prior, a.A, a.ll, a.T, itps,
-                   a.shared_model, marg, filt, loglik_out, fw);
+        launch(MP ? "sd_clear_mm" : "sd_clear_sp", sd_clear_kernel<D>, dim3((nwords + 255) / 256), dim3(256), st, xch,
+               nwords);
+        const char* name = MP ? "sd_maxprod_fused" : "sd_smooth_fused";
+        if constexpr (!MP) {
+            if (filt)
+                launch(name, sd_smooth_fused_kernel<S, D, true>, grid, block, st, a.prior, a.A, a.ll, a.T, itps,
+                       a.shared_model, marg, filt, argmax, out, fw);
+        }
+        if (!filt)
+            launch(name, sd_smooth_fused_kernel<S, D, false>, grid, block, st, a.prior, a.A, a.ll, a.T, itps,
+                   a.shared_model, marg, filt, argmax, out, fw);
     } else {
-        launch("sd_reduce_sp", sd_reduce_kernel<SumProd, D>, grid, block, st, a.A, a.ll, a.T, itps, a.shared_model, agg);
-        launch("sd_carry_sp", sd_carry_kernel<SumProd, D, true>, seqs, block, st, a.prior, itps, a.shared_model, agg, fin,
-               bout);
-        if (filt)
-            launch("sd_smooth_apply", sd_smooth_apply_kernel<D, true>, grid, block, st, a.A, a.ll, a.T, itps,
-                   a.shared_model, fin, bout, marg, filt, part);
-        else
-            launch("sd_smooth_apply", sd_smooth_apply_kernel<D, false>, grid, block, st, a.A, a.ll, a.T, itps,
-                   a.shared_model, fin, bout, marg, filt, part);
-        launch("sd_finalize", sd_finalize_kernel<D>, seqs, dim3(256), st, part, itps, loglik_out);
+        launch(MP ? "sd_reduce_mp" : "sd_reduce_sp", sd_reduce_kernel<S, D>, grid, block, st, a.A, a.ll, a.T, itps,
+               a.shared_model, agg);
+        launch(MP ? "sd_carry_mm" : "sd_carry_sp", sd_carry_kernel<S, D, true>, seqs, block, st, a.prior, itps,
+               a.shared_model, agg, fin, bout);
+        const char* name = MP ? "sd_maxprod_apply" : "sd_smooth_apply";
+        if constexpr (!MP) {
+            if (filt)
+                launch(name, sd_smooth_apply_kernel<S, D, true>, grid, block, st, a.A, a.ll, a.T, itps, a.shared_model,
+                       fin, bout, marg, filt, argmax, part);
+        }
+        if (!filt)
+            launch(name, sd_smooth_apply_kernel<S, D, false>, grid, block, st, a.A, a.ll, a.T, itps, a.shared_model,
+                   fin, bout, marg, filt, argmax, part);
+        launch("sd_finalize", sd_finalize_kernel<D>, seqs, dim3(256), st, part, itps, out);
     }
     return hipGetLastError() == hipSuccess ? 0 : 4;
+}
+
+template <int D>
+int SmallD<D>::smooth(const SmallArgs& a, float* marg, float* filt, double* loglik_out) {
+    return two_filter<SumProd, D>(a, marg, filt, nullptr, loglik_out);
+}
+
+template <int D>
+int SmallD<D>::max_product(const SmallArgs& a, float* maxmarg, int32_t* path, double* logprob_out) {
+    return two_filter<MaxPlus, D>(a, maxmarg, nullptr, path, logprob_out);
 }
 
 template <int D>

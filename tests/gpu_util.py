@@ -68,3 +68,43 @@ def check_viterbi(p, label=""):
     print(f"[viterbi {label or p.name}] B={p.batch} T={p.T} D={p.D} path mismatches={total_mismatch} "
           f"rel dlogprob={rel:.3e}", flush=True)
     return total_mismatch
+
+
+MAXMARG_ATOL = 1e-4      # on entries above -10; scaled with |value| / 10 below that
+
+
+def run_max_product(p):
+    prior, A, ll = to_dev(p)
+    mm, path, lp = hmm.hmm_max_product(prior, A, ll)
+    torch.cuda.synchronize()
+    return mm.cpu().numpy(), path.cpu().numpy(), lp.cpu().numpy()
+
+
+def check_max_product(p, label=""):
+    """hmm_max_product (the paper's Algorithm 5 with Theorem 4's per-step argmax) against the fp64
+    sequential max-product recursions.  Max-marginals: |error| <= 1e-4 * max(1, |value| / 10), -inf where
+    the oracle has -inf.  Per-step maximiser: equal to the oracle's wherever the oracle's best and second
+    best max-marginal are further apart than the tolerance; elsewhere any state within the tolerance of
+    the best is accepted (several results are correct at ties)."""
+    mm, path, lp = run_max_product(p)
+    mm0, path0, lp0 = oracle.max_product_batch(p.prior, p.A, p.loglik, p.shared_model)
+    assert path.min() >= 0 and path.max() < p.D, f"{label}: state out of range"
+    rel = float(np.abs((lp - lp0) / np.where(lp0 == 0, 1, lp0)).max())
+    assert rel <= LOGPROB_RTOL, f"{label}: logprob {lp} vs oracle {lp0}"
+    fin = np.isfinite(mm0)
+    assert (np.isneginf(mm[~fin])).all(), f"{label}: impossible states must have max-marginal -inf"
+    tol = MAXMARG_ATOL * np.maximum(1.0, np.abs(mm0[fin]) / 10.0)
+    err = np.abs(mm[fin] - mm0[fin])
+    worst = float((err / tol).max()) if err.size else 0.0
+    assert worst <= 1.0, f"{label}: max-marginals off by {worst:.2f} tolerances (max abs err {float(err.max()):.3e})"
+    assert float(mm.max(axis=2).max()) == 0.0 and float(mm.max(axis=2).min()) == 0.0, f"{label}: a step's best must be 0"
+    srt = np.sort(np.where(fin, mm0, -np.inf), axis=2)
+    clear = (srt[..., -1] - srt[..., -2]) > 2 * MAXMARG_ATOL if p.D > 1 else np.ones(path.shape, bool)
+    assert (path[clear] == path0[clear]).all(), f"{label}: per-step maximiser differs where it is unambiguous"
+    chosen = np.take_along_axis(mm0, path[..., None].astype(np.int64), axis=2)[..., 0]
+    assert (chosen >= -2 * MAXMARG_ATOL).all(), f"{label}: a chosen state is not a maximiser"
+    nm = int((path != path0).sum())
+    print(f"[max-product {label or p.name}] B={p.batch} T={p.T} D={p.D} max err/tol={worst:.3f} "
+          f"max|dmm|={float(err.max()) if err.size else 0:.3e} ambiguous steps={int((~clear).sum())} "
+          f"argmax mismatches={nm} rel dlogprob={rel:.3e}", flush=True)
+    return worst

@@ -26,6 +26,7 @@ def test_config1(gu):
     p = wl.config1()
     gu.check_smooth(p, want_filtered=True)
     gu.check_viterbi(p)
+    gu.check_max_product(p)
 
 
 @pytest.mark.parametrize("T", [1, 2, 15, 16, 17, 4095, 4096, 4097, 10000])
@@ -33,12 +34,14 @@ def test_config2_shapes_ragged(gu, T):
     p = wl.config2(T=T)
     gu.check_smooth(p, want_filtered=(T % 2 == 1), label=f"C2 T={T}")
     gu.check_viterbi(p, label=f"C2 T={T}")
+    gu.check_max_product(p, label=f"C2 T={T}")
 
 
 def test_gilbert_elliott_paper_model(gu):
     p = wl.gilbert_elliott(T=100000)
     gu.check_smooth(p)
     gu.check_viterbi(p)
+    gu.check_max_product(p)     # binary evidence: exactly tied sequences, many ambiguous steps
 
 
 @pytest.mark.parametrize("D", [1, 2, 3, 4, 5, 6, 7, 8])
@@ -47,6 +50,7 @@ def test_random_models_every_small_D(gu, D, T):
     p = wl.random_problem(D, T, seed=100 * D + T % 97)
     gu.check_smooth(p, want_filtered=(T == 300))
     gu.check_viterbi(p)
+    gu.check_max_product(p)
 
 
 @pytest.mark.parametrize("D,T,B,shared", [(4, 5000, 3, True), (4, 4097, 5, False), (3, 100, 17, False),
@@ -55,6 +59,7 @@ def test_batched(gu, D, T, B, shared):
     p = wl.random_problem(D, T, batch=B, shared_model=shared, seed=7 * D + B)
     gu.check_smooth(p, want_filtered=True)
     gu.check_viterbi(p)
+    gu.check_max_product(p)
 
 
 @pytest.mark.parametrize("D,T", [(4, 6000), (6, 3000), (3, 4100)])
@@ -69,6 +74,7 @@ def test_zero_transitions_and_impossible_emissions(gu, D, T):
     p.loglik[mask] = -np.inf
     gu.check_smooth(p)
     gu.check_viterbi(p)
+    gu.check_max_product(p)
 
 
 def test_config2_full_size(gu):
@@ -76,3 +82,4 @@ def test_config2_full_size(gu):
     p = wl.config2()
     gu.check_smooth(p, want_filtered=False, label="C2 full")
     gu.check_viterbi(p, label="C2 full")
+    gu.check_max_product(p, label="C2 full")
