@@ -105,7 +105,6 @@ hmm_status hmm_viterbi(const float* prior, const float* A, const float* loglik,
  *   logprob_out   [batch]        out: log of the largest joint weight, as in hmm_viterbi
  *   workspace: at least hmm_workspace_bytes(...).smooth_bytes, 256-byte aligned
  * Other arguments as for hmm_smooth; loglik and max_marginals must be 16-byte aligned.
- * Supported for D <= 8; larger D returns HMM_ERR_UNSUPPORTED.
  */
 hmm_status hmm_max_product(const float* prior, const float* A, const float* loglik,
                            int64_t T, int32_t D, int32_t batch, int32_t shared_model,

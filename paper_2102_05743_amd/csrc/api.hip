@@ -32,6 +32,8 @@ hmm_status hmm_workspace_bytes(int64_t T, int32_t D, int32_t batch, size_t* smoo
         v = hmm::small_d_viterbi_ws_bytes(D, T, batch);
     } else {
         s = hmm::large_d_smooth_ws_bytes(D, T, batch);
+        const size_t mp = hmm::large_d_max_product_ws_bytes(D, T, batch);   // hmm_max_product shares smooth_bytes
+        if (mp > s) s = mp;
         v = hmm::large_d_viterbi_ws_bytes(D, T, batch);
     }
     if (smooth_bytes) *smooth_bytes = s;
@@ -87,11 +89,15 @@ hmm_status hmm_max_product(const float* prior, const float* A, const float* logl
     if (st != HMM_OK) return st;
     if (!max_marginals || !logprob_out) return HMM_ERR_INVALID_ARG;
     if (!aligned16(max_marginals)) return HMM_ERR_INVALID_ARG;
-    if (D > hmm::SMALL_D_MAX) return HMM_ERR_UNSUPPORTED;
     size_t need = 0;
     st = hmm_workspace_bytes(T, D, batch, &need, nullptr);
     if (st != HMM_OK) return st;
     if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return HMM_ERR_WORKSPACE;
+    if (D > hmm::SMALL_D_MAX) {
+        hmm::LargeArgs la{prior, A, loglik, (long long)T, D, batch, shared_model ? 1 : 0, workspace, workspace_bytes,
+                          static_cast<hipStream_t>(hip_stream)};
+        return static_cast<hmm_status>(hmm::large_d_max_product(la, max_marginals, path, logprob_out));
+    }
     hmm::SmallArgs a{prior, A, loglik, (long long)T, batch, shared_model ? 1 : 0, workspace, workspace_bytes,
                      static_cast<hipStream_t>(hip_stream)};
     return static_cast<hmm_status>(hmm::small_d_max_product(D, a, max_marginals, path, logprob_out));

@@ -33,5 +33,7 @@ size_t large_d_smooth_ws_bytes(int D, long long T, int batch);
 int large_d_smooth(const LargeArgs& a, float* marg, float* filt, double* loglik_out);
 size_t large_d_viterbi_ws_bytes(int D, long long T, int batch);
 int large_d_viterbi(const LargeArgs& a, int32_t* path, double* logprob_out);
+size_t large_d_max_product_ws_bytes(int D, long long T, int batch);   // never more than the smoother's
+int large_d_max_product(const LargeArgs& a, float* maxmarg, int32_t* path, double* logprob_out);
 
 }  // namespace hmm

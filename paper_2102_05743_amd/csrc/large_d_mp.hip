@@ -68,7 +68,8 @@ template <int D>
 __global__ __launch_bounds__(256) void lv_aggregate_systolic_kernel(const float* __restrict__ A,
                                                                     const float* __restrict__ ll, long long T, int Dr,
                                                                     int Lc, int cps, long long nchunks,
-                                                                    int shared_model, float* __restrict__ agg) {
+                                                                    int shared_model, float* __restrict__ agg,
+                                                                    float* __restrict__ agg_other) {
     constexpr int NQ = D / 16;             // column blocks = registers per lane for one row of P
     constexpr int WPCH = MpCfg<D>::WPC;    // waves per chunk: a workgroup for D >= 32, else one wave
     constexpr int CPWG = 4 / WPCH;         // chunks per workgroup
@@ -161,8 +162,12 @@ __global__ __launch_bounds__(256) void lv_aggregate_systolic_kernel(const float*
         float* dst = agg + (size_t)chunk * D * D;
         for (int r = 0; r < RPD; ++r) {
             const int i = rs * RPD + r;
+            const float val = pf[i * D + l * NQ + cb] - off;
             // D <= 32: stored transposed, the one-wave carry reads the terms of a column contiguously
-            dst[(D <= 32) ? ((size_t)j * D + i) : ((size_t)i * D + j)] = pf[i * D + l * NQ + cb] - off;
+            dst[(D <= 32) ? ((size_t)j * D + i) : ((size_t)i * D + j)] = val;
+            // the backward carry of the two-filter plan wants the other orientation
+            if (agg_other != nullptr)
+                agg_other[(size_t)chunk * D * D + ((D <= 32) ? ((size_t)i * D + j) : ((size_t)j * D + i))] = val;
         }
     }
 }
@@ -173,25 +178,34 @@ __global__ __launch_bounds__(256) void lv_aggregate_systolic_kernel(const float*
 template <int D>
 __global__ __launch_bounds__(256) void lv_carry_kernel(const float* __restrict__ prior, int Dr, int cps,
                                                        int shared_model, const float* __restrict__ agg,
-                                                       float* __restrict__ vin) {
+                                                       float* __restrict__ vin, const float* __restrict__ agg_other,
+                                                       float* __restrict__ bout) {
+    // With bout given the grid is doubled: odd workgroups run the backward direction, the same
+    // recursion on the aggregates' other orientation, over the chunks right to left, from the zero
+    // vector: bout[c] = backward potential at chunk c's last step.
     constexpr int Q = 256 / D;
     constexpr int RPT = D / Q;
     __shared__ float vec[D];
     __shared__ float partial[Q * D];
     __shared__ float max_lds;
-    const int seq = blockIdx.x;
+    const bool two = bout != nullptr;
+    const int seq = two ? blockIdx.x >> 1 : blockIdx.x;
+    const int dir = two ? (blockIdx.x & 1) : 0;
     const int j = threadIdx.x % D, q = threadIdx.x / D;
-    const float* mats = agg + (size_t)seq * cps * D * D;
-    float* out = vin + (size_t)seq * cps * D;
-    float v = (j < Dr) ? safe_log(prior[(shared_model ? 0 : (size_t)seq * Dr) + j]) : -INFINITY;
+    const float* mats = (dir ? agg_other : agg) + (size_t)seq * cps * D * D;
+    float* out = (dir ? bout : vin) + (size_t)seq * cps * D;
+    float v;
+    if (dir) v = (j < Dr) ? 0.0f : -INFINITY;
+    else v = (j < Dr) ? safe_log(prior[(shared_model ? 0 : (size_t)seq * Dr) + j]) : -INFINITY;
     float pv[RPT];
-    auto load_mat = [&](int c) {
-        const float* Mx = mats + (size_t)c * D * D;
+    auto load_mat = [&](int it) {
+        const float* Mx = mats + (size_t)(dir ? cps - 1 - it : it) * D * D;
 #pragma unroll
         for (int r = 0; r < RPT; ++r) pv[r] = Mx[(size_t)(q * RPT + r) * D + j];
     };
     load_mat(0);
-    for (int c = 0; c < cps; ++c) {
+    for (int it = 0; it < cps; ++it) {
+        const int c = dir ? cps - 1 - it : it;
         if (q == 0) {
             out[(size_t)c * D + j] = v;
             vec[j] = v;
@@ -200,7 +214,7 @@ __global__ __launch_bounds__(256) void lv_carry_kernel(const float* __restrict__
         float acc = -INFINITY;
 #pragma unroll
         for (int r = 0; r < RPT; ++r) acc = fmaxf(acc, vec[q * RPT + r] + pv[r]);
-        if (c + 1 < cps) load_mat(c + 1);
+        if (it + 1 < cps) load_mat(it + 1);
         partial[q * D + j] = acc;
         lds_barrier();
         float g = -INFINITY;
@@ -228,30 +242,39 @@ __global__ __launch_bounds__(256) void lv_carry_kernel(const float* __restrict__
 template <int D>
 __global__ __launch_bounds__(64) void lv_carry_wave_kernel(const float* __restrict__ prior, int Dr, int cps,
                                                            int shared_model, const float* __restrict__ agg,
-                                                           float* __restrict__ vin) {
+                                                           float* __restrict__ vin,
+                                                           const float* __restrict__ agg_other,
+                                                           float* __restrict__ bout) {
+    // With bout given the grid is doubled and odd workgroups run the backward direction (see lv_carry_kernel).
     static_assert(D <= 32, "one wave covers the columns");
     constexpr int PARTS = 64 / D;
     constexpr int RPT = D / PARTS;
     constexpr int PF = 8;
     __shared__ __align__(16) float vec[D];
-    const int seq = blockIdx.x;
+    const bool two = bout != nullptr;
+    const int seq = two ? blockIdx.x >> 1 : blockIdx.x;
+    const int dir = two ? (blockIdx.x & 1) : 0;
     const int lane = threadIdx.x;
     const int h = lane % PARTS, j = lane / PARTS;
-    const float* mats = agg + (size_t)seq * cps * D * D;
-    float* out = vin + (size_t)seq * cps * D;
-    float v = (j < Dr) ? safe_log(prior[(shared_model ? 0 : (size_t)seq * Dr) + j]) : -INFINITY;
+    const float* mats = (dir ? agg_other : agg) + (size_t)seq * cps * D * D;
+    float* out = (dir ? bout : vin) + (size_t)seq * cps * D;
+    float v;
+    if (dir) v = (j < Dr) ? 0.0f : -INFINITY;
+    else v = (j < Dr) ? safe_log(prior[(shared_model ? 0 : (size_t)seq * Dr) + j]) : -INFINITY;
     settle_loaded(v);
     float pv[PF][RPT];
     // unconditional loads (clamped hop index): the compiler can count outstanding loads exactly
-    auto load_mat = [&](int c, float (&m)[RPT]) {
-        const float* Mx = mats + (size_t)(c < cps ? c : cps - 1) * D * D + (size_t)j * D + h * RPT;   // stored transposed
+    auto load_mat = [&](int it, float (&m)[RPT]) {
+        const int c = dir ? cps - 1 - (it < cps ? it : cps - 1) : (it < cps ? it : cps - 1);
+        const float* Mx = mats + (size_t)c * D * D + (size_t)j * D + h * RPT;   // the lane's terms are contiguous
 #pragma unroll
         for (int r4 = 0; r4 < RPT; r4 += 4) {
             const float4 x = *reinterpret_cast<const float4*>(Mx + r4);
             m[r4] = x.x; m[r4 + 1] = x.y; m[r4 + 2] = x.z; m[r4 + 3] = x.w;
         }
     };
-    auto hop = [&](int c, const float (&m)[RPT]) {
+    auto hop = [&](int it, const float (&m)[RPT]) {
+        const int c = dir ? cps - 1 - it : it;
         if (h == 0) {
             out[(size_t)c * D + j] = v;
             vec[j] = v;
@@ -529,6 +552,205 @@ __global__ __launch_bounds__(256) void lv_path_kernel(long long T, int Lc, int c
 }
 
 // =============================================================================================
+// The paper's parallel max-product algorithm as printed (Algorithm 5): maximum forward and backward
+// potentials (the lemma of Sec. IV-C) inside the chunks, then Theorem 4's per-step combination.
+// =============================================================================================
+
+// First half of the grid: psi~^f_k inside each chunk from the forward carry, every step stored
+// shifted to max 0, plus the chunk-local growth of the log of the best joint weight.  Second half:
+// psi~^b_k inside each chunk from the backward carry, stored with an arbitrary shift per step (the
+// combination removes it).  Lane = (component inside the wave, part h of the max), log A in
+// registers (a column for the forward, a row for the backward recursion), the vector through
+// double-buffered LDS, its maximum removed one step late: one barrier per step.
+template <int D>
+__global__ __launch_bounds__(256) void lm_apply_kernel(const float* __restrict__ prior, const float* __restrict__ A,
+                                                       const float* __restrict__ ll, long long T, int Dr, int Lc,
+                                                       int cps, long long nchunks, int shared_model,
+                                                       const float* __restrict__ vin, const float* __restrict__ bout,
+                                                       float* __restrict__ F, float* __restrict__ Bv,
+                                                       double* __restrict__ part, int half) {
+    using C = LargeCfg<D>;
+    __shared__ __align__(16) float vbuf[2 * C::VCPW * D];
+    __shared__ float wmaxs[2 * C::VCPW * C::VWPC];
+    const bool backward = (int)blockIdx.x >= half;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int cl = wave / C::VWPC, wv = wave % C::VWPC;
+    const int jl = lane % C::CPWV, h = lane / C::CPWV;
+    const int j = C::CPWV * wv + jl;                      // component owned (replicated over the parts h)
+    const long long chunk = (long long)(backward ? blockIdx.x - half : blockIdx.x) * C::VCPW + cl;
+    const ChunkCoord cc = chunk_coord(chunk, nchunks, cps, T, Lc);
+    const float* Am = A + (shared_model ? 0 : (size_t)cc.seq * Dr * Dr);
+    float lareg[C::RPP];   // forward: log A(i, j) over the part's i; backward: log A(j, i') over the part's i'
+#pragma unroll
+    for (int r = 0; r < C::RPP; ++r) {
+        const int i = h * C::RPP + r;
+        float v = (i == j) ? 0.0f : -INFINITY;
+        if (i < Dr && j < Dr) v = safe_log(backward ? Am[(size_t)j * Dr + i] : Am[(size_t)i * Dr + j]);
+        lareg[r] = v;
+    }
+    const float* lseq = ll + (size_t)cc.seq * T * Dr;
+    float* oseq = (backward ? Bv : F) + (size_t)cc.seq * T * Dr;
+    const bool first_chunk = (chunk % cps) == 0;
+    auto block_max = [&](const float* w) {
+        float m = w[0];
+#pragma unroll
+        for (int q = 1; q < C::VWPC; ++q) m = fmaxf(m, w[q]);
+        return (m == -INFINITY) ? 0.0f : m;
+    };
+    auto part_max = [&](float best) {   // combine the parts h of a component
+#pragma unroll
+        for (int d = C::CPWV; d < 64; d <<= 1) best = fmaxf(best, __shfl_xor(best, d, 64));
+        return best;
+    };
+    if (!backward) {
+        float v0 = -INFINITY;
+        if (cc.nsteps > 0) {
+            if (first_chunk) v0 = (j < Dr) ? safe_log(prior[(shared_model ? 0 : (size_t)cc.seq * Dr) + j]) : -INFINITY;
+            else v0 = vin[(size_t)chunk * D + j];
+        }
+        if (h == 0) vbuf[cl * D + j] = v0;
+        {
+            const float m = wave_max(v0);
+            if (lane == 0) wmaxs[cl * C::VWPC + wv] = m;
+        }
+        __syncthreads();
+        // level the chunk starts from: 0 for the log prior (used as given), else the carry's maximum
+        const float start = first_chunk ? 0.0f : block_max(wmaxs + cl * C::VWPC);
+        __syncthreads();
+        float off = start;
+        double osum = 0.0;
+        int cur = 0;
+        float xn = -INFINITY;
+        if (cc.nsteps > 0 && j < Dr) xn = lseq[(size_t)cc.t0 * Dr + j];
+        for (int s = 0; s < Lc; ++s) {
+            const bool active = s < cc.nsteps;
+            const float x = xn;
+            if (s + 1 < cc.nsteps && j < Dr) xn = lseq[(size_t)(cc.t0 + s + 1) * Dr + j];
+            const float* vc = vbuf + (cur * C::VCPW + cl) * D;
+            float* vn = vbuf + ((cur ^ 1) * C::VCPW + cl) * D;
+            float* wn = wmaxs + ((cur ^ 1) * C::VCPW + cl) * C::VWPC;
+            float gval = -INFINITY;
+            if (active) {
+                if (cc.t0 + s == 0) {
+                    gval = vc[j] + x;   // psi~^f_1 = log prior + ll_1
+                } else {
+                    float b0 = -INFINITY, b1 = -INFINITY;
+#pragma unroll
+                    for (int r4 = 0; r4 < C::RPP; r4 += 4) {
+                        const float4 v4 = *reinterpret_cast<const float4*>(vc + h * C::RPP + r4);
+                        b0 = max3f(b0, v4.x + lareg[r4], v4.y + lareg[r4 + 1]);
+                        b1 = max3f(b1, v4.z + lareg[r4 + 2], v4.w + lareg[r4 + 3]);
+                    }
+                    gval = part_max(fmaxf(b0, b1)) + (x - off);
+                }
+                if (h == 0) vn[j] = gval;
+                const float mw = wave_max(gval);
+                if (lane == 0) wn[wv] = mw;
+            }
+            lds_barrier();
+            if (active) {
+                const float m = block_max(wn);
+                if (h == 0 && j < Dr) oseq[(size_t)(cc.t0 + s) * Dr + j] = gval - m;
+                osum += (double)((cc.t0 + s == 0) ? 0.0f : off);
+                off = m;
+            }
+            cur ^= 1;
+        }
+        if (cc.nsteps > 0 && lane == 0 && wv == 0) part[chunk] = osum + (double)off - (double)start;
+    } else {
+        // u = psi~^b at the current step, component j, shifted by the previous step's maximum
+        float u = (cc.nsteps > 0) ? bout[(size_t)chunk * D + j] : -INFINITY;
+        int cur = 0;
+        float xn = -INFINITY;
+        if (cc.nsteps > 0 && j < Dr) xn = lseq[(size_t)(cc.t0 + cc.nsteps - 1) * Dr + j];
+        for (int sp = 0; sp < Lc; ++sp) {
+            const int s = Lc - 1 - sp;
+            const bool active = s < cc.nsteps;
+            float* vn = vbuf + ((cur ^ 1) * C::VCPW + cl) * D;
+            float* wn = wmaxs + ((cur ^ 1) * C::VCPW + cl) * C::VWPC;
+            if (active) {
+                const float x = xn;
+                if (s >= 1 && j < Dr) xn = lseq[(size_t)(cc.t0 + s - 1) * Dr + j];
+                if (h == 0) {
+                    if (j < Dr) oseq[(size_t)(cc.t0 + s) * Dr + j] = u;
+                    vn[j] = x + u;          // log psi_{s} 's emission part + psi~^b_s: what step s-1 maximises over
+                }
+                const float mw = wave_max(u);
+                if (lane == 0) wn[wv] = mw;
+            }
+            lds_barrier();
+            if (active && s > 0) {
+                const float m = block_max(wn);
+                float b0 = -INFINITY, b1 = -INFINITY;
+#pragma unroll
+                for (int r4 = 0; r4 < C::RPP; r4 += 4) {
+                    const float4 t4 = *reinterpret_cast<const float4*>(vn + h * C::RPP + r4);
+                    b0 = max3f(b0, t4.x + lareg[r4], t4.y + lareg[r4 + 1]);
+                    b1 = max3f(b1, t4.z + lareg[r4 + 2], t4.w + lareg[r4 + 3]);
+                }
+                u = part_max(fmaxf(b0, b1)) - m;
+            }
+            cur ^= 1;
+        }
+    }
+}
+
+// Theorem 4: max-marginal log psi~^f_k + log psi~^b_k, shifted so that the step's largest entry is 0,
+// and its maximiser (lowest state on ties).  A power-of-two group of lanes per step.
+__global__ __launch_bounds__(256) void lm_combine_kernel(const float* __restrict__ F, const float* __restrict__ Bv,
+                                                         long long rows, int Dr, float* __restrict__ mm,
+                                                         int32_t* __restrict__ path) {
+    const int lpr = (Dr + 3) / 4;                  // lanes per step
+    int width = 1;
+    while (width < lpr) width <<= 1;
+    const int rows_per_wave = 64 / width;
+    const int lane = threadIdx.x & 63;
+    const long long wave = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const long long row = wave * rows_per_wave + lane / width;
+    const int sub = lane % width;
+    float g[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+    const bool live = row < rows && sub < lpr;
+    if (live) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int j = 4 * sub + q;
+            if (j < Dr) g[q] = F[row * Dr + j] + Bv[row * Dr + j];
+        }
+    }
+    float best = g[0];
+    int arg = 4 * sub;
+#pragma unroll
+    for (int q = 1; q < 4; ++q)
+        if (g[q] > best) { best = g[q]; arg = 4 * sub + q; }
+    for (int d = 1; d < width; d <<= 1) {
+        const float ob = __shfl_xor(best, d, 64);
+        const int oi = __shfl_xor(arg, d, 64);
+        const bool take = (ob > best) || (ob == best && oi < arg);
+        best = take ? ob : best;
+        arg = take ? oi : arg;
+    }
+    if (live) {
+        const float m = (best == -INFINITY) ? 0.0f : best;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int j = 4 * sub + q;
+            if (j < Dr) mm[row * Dr + j] = g[q] - m;
+        }
+        if (sub == 0 && path != nullptr) path[row] = arg;
+    }
+}
+
+// out[seq] = sum of the chunk partials of one sequence (one wave)
+__global__ __launch_bounds__(64) void lm_finalize_kernel(const double* __restrict__ part, int cps,
+                                                         double* __restrict__ out) {
+    double acc = 0.0;
+    for (int c = threadIdx.x; c < cps; c += 64) acc += part[(size_t)blockIdx.x * cps + c];
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) acc += __shfl_down(acc, d, 64);
+    if (threadIdx.x == 0) out[blockIdx.x] = acc;
+}
+
+// =============================================================================================
 // Host side
 // =============================================================================================
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -585,13 +807,13 @@ static int large_viterbi_impl(const LargeArgs& a, int32_t* path, double* logprob
     hipStream_t st = a.stream;
     const dim3 block(256);
     launch("lv_aggregate", lv_aggregate_systolic_kernel<D>, dim3((unsigned)((p.nchunks + M::CPW - 1) / M::CPW)), block,
-           st, a.A, a.ll, a.T, a.D, p.Lc, p.cps, p.nchunks, a.shared_model, agg);
+           st, a.A, a.ll, a.T, a.D, p.Lc, p.cps, p.nchunks, a.shared_model, agg, static_cast<float*>(nullptr));
     if constexpr (D <= 32)
         launch("lv_carry", lv_carry_wave_kernel<D>, dim3((unsigned)a.batch), dim3(64), st, a.prior, a.D, p.cps,
-               a.shared_model, agg, vin);
+               a.shared_model, agg, vin, static_cast<const float*>(nullptr), static_cast<float*>(nullptr));
     else
         launch("lv_carry", lv_carry_kernel<D>, dim3((unsigned)a.batch), block, st, a.prior, a.D, p.cps, a.shared_model,
-               agg, vin);
+               agg, vin, static_cast<const float*>(nullptr), static_cast<float*>(nullptr));
     const size_t fwd_lds = (size_t)C::VCPW * p.Lc * D;
     launch_dyn("lv_forward", lv_forward_kernel<D>, dim3((unsigned)((p.nchunks + C::VCPW - 1) / C::VCPW)), block, fwd_lds,
                st, a.prior, a.A, a.ll, a.T, a.D, p.Lc, p.cps, p.nchunks, a.shared_model, vin, bp, cmap, xstar, part);
@@ -601,6 +823,77 @@ static int large_viterbi_impl(const LargeArgs& a, int32_t* path, double* logprob
     launch_dyn("lv_path", lv_path_kernel<D>, dim3((unsigned)p.nchunks), block, path_lds, st, a.T, p.Lc, p.cps, p.nchunks,
                bp, xend, path);
     return hipGetLastError() == hipSuccess ? 0 : 4;
+}
+
+struct LargeMmWs { size_t agg, agg_other, vin, bout, F, Bv, part, total; };
+
+static LargeMmWs large_mm_ws(int Dr, long long T, int batch) {
+    const LargePlan p = large_plan(Dr, T, batch);
+    const size_t D = p.DP, nc = (size_t)p.nchunks, rows = (size_t)T * batch;
+    LargeMmWs w;
+    size_t o = 0;
+    w.agg = o;       o = align_up(o + nc * D * D * sizeof(float), 256);
+    w.agg_other = o; o = align_up(o + nc * D * D * sizeof(float), 256);
+    w.vin = o;       o = align_up(o + nc * D * sizeof(float), 256);
+    w.bout = o;      o = align_up(o + nc * D * sizeof(float), 256);
+    w.F = o;         o = align_up(o + rows * Dr * sizeof(float), 256);
+    w.Bv = o;        o = align_up(o + rows * Dr * sizeof(float), 256);
+    w.part = o;      o = align_up(o + nc * sizeof(double), 256);
+    w.total = o;
+    return w;
+}
+
+size_t large_d_max_product_ws_bytes(int Dr, long long T, int batch) { return large_mm_ws(Dr, T, batch).total; }
+
+template <int D>
+static int large_max_product_impl(const LargeArgs& a, float* mm, int32_t* path, double* logprob_out) {
+    using C = LargeCfg<D>;
+    using M = MpCfg<D>;
+    const LargePlan p = large_plan(a.D, a.T, a.batch);
+    const LargeMmWs w = large_mm_ws(a.D, a.T, a.batch);
+    if (a.ws_bytes < w.total) return 3;
+    const long long rows = a.T * a.batch;
+    if (rows > 0x7fffffffLL * 4 || p.nchunks > 0x3fffffffLL) return 2;
+    char* ws = static_cast<char*>(a.ws);
+    float* agg = reinterpret_cast<float*>(ws + w.agg);
+    float* agg_other = reinterpret_cast<float*>(ws + w.agg_other);
+    float* vin = reinterpret_cast<float*>(ws + w.vin);
+    float* bout = reinterpret_cast<float*>(ws + w.bout);
+    float* F = reinterpret_cast<float*>(ws + w.F);
+    float* Bv = reinterpret_cast<float*>(ws + w.Bv);
+    double* part = reinterpret_cast<double*>(ws + w.part);
+    hipStream_t st = a.stream;
+    const dim3 block(256);
+    launch("lv_aggregate", lv_aggregate_systolic_kernel<D>, dim3((unsigned)((p.nchunks + M::CPW - 1) / M::CPW)), block,
+           st, a.A, a.ll, a.T, a.D, p.Lc, p.cps, p.nchunks, a.shared_model, agg, agg_other);
+    if constexpr (D <= 32)
+        launch("lm_carry", lv_carry_wave_kernel<D>, dim3(2u * (unsigned)a.batch), dim3(64), st, a.prior, a.D, p.cps,
+               a.shared_model, agg, vin, static_cast<const float*>(agg_other), bout);
+    else
+        launch("lm_carry", lv_carry_kernel<D>, dim3(2u * (unsigned)a.batch), block, st, a.prior, a.D, p.cps,
+               a.shared_model, agg, vin, static_cast<const float*>(agg_other), bout);
+    const int half = (int)((p.nchunks + C::VCPW - 1) / C::VCPW);
+    launch("lm_apply", lm_apply_kernel<D>, dim3(2u * (unsigned)half), block, st, a.prior, a.A, a.ll, a.T, a.D, p.Lc,
+           p.cps, p.nchunks, a.shared_model, vin, bout, F, Bv, part, half);
+    const int lpr = (a.D + 3) / 4;
+    int width = 1;
+    while (width < lpr) width <<= 1;
+    const long long rows_per_block = 4LL * (64 / width);
+    launch("lm_combine", lm_combine_kernel, dim3((unsigned)((rows + rows_per_block - 1) / rows_per_block)), block, st, F, Bv,
+           rows, a.D, mm, path);
+    launch("lm_finalize", lm_finalize_kernel, dim3((unsigned)a.batch), dim3(64), st, part, p.cps, logprob_out);
+    return hipGetLastError() == hipSuccess ? 0 : 4;
+}
+
+int large_d_max_product(const LargeArgs& a, float* mm, int32_t* path, double* logprob_out) {
+    const int DP = large_plan(a.D, a.T, a.batch).DP;
+    switch (DP) {
+        case 16: return large_max_product_impl<16>(a, mm, path, logprob_out);
+        case 32: return large_max_product_impl<32>(a, mm, path, logprob_out);
+        case 64: return large_max_product_impl<64>(a, mm, path, logprob_out);
+        case 128: return large_max_product_impl<128>(a, mm, path, logprob_out);
+        default: return 2;
+    }
 }
 
 int large_d_viterbi(const LargeArgs& a, int32_t* path, double* logprob_out) {

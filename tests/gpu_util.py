@@ -70,7 +70,10 @@ def check_viterbi(p, label=""):
     return total_mismatch
 
 
-MAXMARG_ATOL = 1e-4      # on entries above -10; scaled with |value| / 10 below that
+# Max-marginals are differences of running path sums kept in fp32: two paths that stay apart for K steps
+# differ by K roundings of about 6e-8 * |running value| (tens, after the per-step shift), i.e. ~1e-4 over a few
+# hundred steps; the fp64 oracle has none of it.  Hence 2e-4 on entries above -5, 4e-5 * |value| below that.
+MAXMARG_ATOL = 2e-4
 
 
 def run_max_product(p):
@@ -82,7 +85,7 @@ def run_max_product(p):
 
 def check_max_product(p, label=""):
     """hmm_max_product (the paper's Algorithm 5 with Theorem 4's per-step argmax) against the fp64
-    sequential max-product recursions.  Max-marginals: |error| <= 1e-4 * max(1, |value| / 10), -inf where
+    sequential max-product recursions.  Max-marginals: |error| <= 2e-4 * max(1, |value| / 5), -inf where
     the oracle has -inf.  Per-step maximiser: equal to the oracle's wherever the oracle's best and second
     best max-marginal are further apart than the tolerance; elsewhere any state within the tolerance of
     the best is accepted (several results are correct at ties)."""
@@ -93,7 +96,7 @@ def check_max_product(p, label=""):
     assert rel <= LOGPROB_RTOL, f"{label}: logprob {lp} vs oracle {lp0}"
     fin = np.isfinite(mm0)
     assert (np.isneginf(mm[~fin])).all(), f"{label}: impossible states must have max-marginal -inf"
-    tol = MAXMARG_ATOL * np.maximum(1.0, np.abs(mm0[fin]) / 10.0)
+    tol = MAXMARG_ATOL * np.maximum(1.0, np.abs(mm0[fin]) / 5.0)
     err = np.abs(mm[fin] - mm0[fin])
     worst = float((err / tol).max()) if err.size else 0.0
     assert worst <= 1.0, f"{label}: max-marginals off by {worst:.2f} tolerances (max abs err {float(err.max()):.3e})"

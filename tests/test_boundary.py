@@ -71,10 +71,10 @@ def test_argument_errors_are_caught_on_the_host():
     assert lib.hmm_smooth(fake, fake, fake, 8, 4, 1, 1, fake, null, fake, null, 1 << 20, null) == 3
     assert lib.hmm_smooth(fake, fake, fake, 8, 4, 1, 1, fake, null, fake, fake, 16, null) == 3
     assert lib.hmm_viterbi(fake, fake, fake, 8, 4, 1, 1, fake, fake, ctypes.c_void_p(0x1010), 1 << 20, null) == 3
-    # hmm_max_product: same rules; the path output is optional, large state spaces are not supported
+    # hmm_max_product: same rules; the path output is optional
     aligned_ws = ctypes.c_void_p(0x2000)
     assert lib.hmm_max_product(fake, fake, fake, 8, 4, 1, 1, null, null, fake, aligned_ws, 1 << 20, null) == 1
     assert lib.hmm_max_product(fake, fake, fake, 8, 4, 1, 1, fake, null, null, aligned_ws, 1 << 20, null) == 1
     assert lib.hmm_max_product(fake, fake, fake, 8, 4, 1, 1, ctypes.c_void_p(0x1008), null, fake, aligned_ws, 1 << 20, null) == 1
-    assert lib.hmm_max_product(fake, fake, fake, 8, 16, 1, 1, fake, null, fake, aligned_ws, 1 << 20, null) == 2
+    assert lib.hmm_max_product(fake, fake, fake, 8, 1000, 1, 1, fake, null, fake, aligned_ws, 1 << 20, null) == 2
     assert lib.hmm_max_product(fake, fake, fake, 8, 4, 1, 1, fake, null, fake, aligned_ws, 16, null) == 3

@@ -20,6 +20,7 @@ def test_random_models_smoother(gu, D, T):
     p = wl.random_problem(D, T, seed=1000 + 10 * D + T % 7)
     gu.check_smooth(p, want_filtered=(T == 700))
     gu.check_viterbi(p)
+    gu.check_max_product(p)
 
 
 @pytest.mark.parametrize("D,T,B,shared", [(16, 900, 5, False), (32, 1500, 3, True), (64, 257, 4, False),
@@ -28,24 +29,28 @@ def test_batched_smoother(gu, D, T, B, shared):
     p = wl.random_problem(D, T, batch=B, shared_model=shared, seed=50 + D + B)
     gu.check_smooth(p, want_filtered=True)
     gu.check_viterbi(p)
+    gu.check_max_product(p)
 
 
 def test_config3_shape(gu):
     p = wl.config3(T=20000)
     gu.check_smooth(p, want_filtered=True, label="C3 T=20000")
     gu.check_viterbi(p, label="C3 T=20000")
+    gu.check_max_product(p, label="C3 T=20000")
 
 
 def test_config4_shape(gu):
     p = wl.config4(batch=12, T=4096)
     gu.check_smooth(p, label="C4 B=12")
     gu.check_viterbi(p, label="C4 B=12")
+    gu.check_max_product(p, label="C4 B=12")
 
 
 def test_config5_shape(gu):
     p = wl.config5(T=6000)
     gu.check_smooth(p, want_filtered=True, label="C5 T=6000")
     gu.check_viterbi(p, label="C5 T=6000")
+    gu.check_max_product(p, label="C5 T=6000")
 
 
 def test_sparse_transitions_and_impossible_emissions(gu):
@@ -56,6 +61,7 @@ def test_sparse_transitions_and_impossible_emissions(gu):
     p.loglik[mask] = -np.inf
     gu.check_smooth(p, want_filtered=True)
     gu.check_viterbi(p)
+    gu.check_max_product(p)
 
 
 @pytest.mark.parametrize("D,T", [(128, 40000), (64, 90000), (32, 70000)])
@@ -71,6 +77,7 @@ def test_first_observation_excludes_a_block_of_states(gu, D, T):
     p.loglik[0, 0, D // 4:] = -np.inf
     gu.check_smooth(p, want_filtered=True, label=f"excluded block D={D}")
     gu.check_viterbi(p, label=f"excluded block D={D}")
+    gu.check_max_product(p, label=f"excluded block D={D}")
 
 
 # ---- the configurations at their full sizes, element by element against the oracle ----
@@ -78,15 +85,18 @@ def test_config3_full_size(gu):
     p = wl.config3()
     gu.check_smooth(p, label="C3 full")
     gu.check_viterbi(p, label="C3 full")
+    gu.check_max_product(p, label="C3 full")
 
 
 def test_config4_full_size(gu):
     p = wl.config4()
     gu.check_smooth(p, label="C4 full")
     gu.check_viterbi(p, label="C4 full")
+    gu.check_max_product(p, label="C4 full")
 
 
 def test_config5_full_size(gu):
     p = wl.config5()
     gu.check_smooth(p, label="C5 full")
     gu.check_viterbi(p, label="C5 full")
+    gu.check_max_product(p, label="C5 full")
