@@ -18,6 +18,16 @@
  * whose evidence is impossible under every state (a log-likelihood row that is
  * all -inf, or Z = 0) is not an error: the returned log-likelihood /
  * log-probability is then -inf or NaN and the marginals / path are unspecified.
+ *
+ * Concurrency.  Calls may be enqueued back to back on one stream.  For small state
+ * spaces (D <= 8) and shapes whose tiles all fit the device at once, a call is a
+ * single kernel whose workgroups wait for one another's partial results, which
+ * needs them all resident together; the host checks this against an otherwise
+ * idle device.  If other work (another stream, another process) occupies compute
+ * units for the whole duration, the wait is bounded: the kernel then terminates
+ * by itself and the call's floating-point outputs are NaN.  Setting the
+ * environment variable HMMSCAN_PLAN=multi selects the plan without such waits for
+ * every shape.  Two calls must not share one workspace concurrently.
  */
 #ifndef HMMSCAN_H
 #define HMMSCAN_H
