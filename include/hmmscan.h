@@ -25,7 +25,8 @@
  * needs them all resident together; the host checks this against an otherwise
  * idle device.  If other work (another stream, another process) occupies compute
  * units for the whole duration, the wait is bounded: the kernel then terminates
- * by itself and the call's floating-point outputs are NaN.  Setting the
+ * by itself and the call's log-likelihood / log-probability output is NaN (its
+ * other outputs are then meaningless).  Setting the
  * environment variable HMMSCAN_PLAN=multi selects the plan without such waits for
  * every shape.  Two calls must not share one workspace concurrently.
  */

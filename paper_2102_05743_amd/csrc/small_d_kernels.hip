@@ -478,7 +478,7 @@ HMM_DEV bool gather_aggregates(const float* src, int n, float* dst_lds) {
 // The two ordered products are masked reductions over at most 2*128 tile slots: the first two
 // waves reduce the tiles before c, the last two the tiles after c (tps <= NT).
 template <class S, int D, bool BWD>
-HMM_DEV void grid_gather(const TileCoord& tc, int tps, const float* __restrict__ prior, const FusedWs& ws,
+HMM_DEV bool grid_gather(const TileCoord& tc, int tps, const float* __restrict__ prior, const FusedWs& ws,
                          GridLds<D>& gl, float (&cf)[D], float (&cb)[D]) {
     using C = SmallCfg<D>;
     using G = GridLds<D>;
@@ -543,6 +543,7 @@ HMM_DEV void grid_gather(const TileCoord& tc, int tps, const float* __restrict__
             for (int j = 0; j < D; ++j) cb[j] = r[j];
         }
     }
+    return ok;   // false: the bounded wait ran out (the tiles were not all resident); the caller poisons its evidence
 }
 
 // All lanes: poll the sequence's tile partials until all are published, then out[seq] = their
@@ -611,14 +612,15 @@ __global__ __launch_bounds__(256) void sd_smooth_fused_kernel(const float* __res
     for (int e = 0; e < D * D; ++e) R[e] = P[e];
     wave_scan_suffix<S, D>(R);
     float cf[D], cb[D];
-    grid_gather<S, D, true>(tc, tps, prior + (shared_model ? 0 : (size_t)tc.seq * D), ws, gl, cf, cb);
+    const bool ok = grid_gather<S, D, true>(tc, tps, prior + (shared_model ? 0 : (size_t)tc.seq * D), ws, gl, cf, cb);
     HMM_STAMP(6);
     float f[D], b[D];
     carry_forward<S, D>(Q, wagg, cf, f);
     carry_backward<S, D>(R, wagg, cb, b);
     HMM_STAMP(7);
     float* fdst = WRITE_FILT ? filt + (tc.base + (long long)threadIdx.x * C::L) * D : nullptr;
-    const double delta = smooth_chunk<S, D, WRITE_FILT>(row, n, first, Am, f, b, msum, fdst);
+    double delta = smooth_chunk<S, D, WRITE_FILT>(row, n, first, Am, f, b, msum, fdst);
+    if (!ok) delta = __builtin_nan("");   // an expired wait makes the call's log evidence NaN
     HMM_STAMP(8);
     const double tile_delta = block_sum(delta, dsum);   // contains a barrier: all marginals are in LDS
     if (threadIdx.x == 0)
@@ -668,13 +670,14 @@ __global__ __launch_bounds__(256) void sd_viterbi_fused_kernel(const float* __re
     grid_publish<S, D>(wagg, ws);
     HMM_STAMP(4);
     float cf[D], cb[D];
-    grid_gather<S, D, false>(tc, tps, prior + (shared_model ? 0 : (size_t)tc.seq * D), ws, gl, cf, cb);
+    const bool ok = grid_gather<S, D, false>(tc, tps, prior + (shared_model ? 0 : (size_t)tc.seq * D), ws, gl, cf, cb);
     HMM_STAMP(6);
     float v[D];
     carry_forward<S, D>(Q, wagg, cf, v);
     HMM_STAMP(7);
     uint32_t bp[C::W], h, xs;
-    const double osum = viterbi_chunk<D>(row, n, first, last, Am, v, bp, h, xs);
+    double osum = viterbi_chunk<D>(row, n, first, last, Am, v, bp, h, xs);
+    if (!ok) osum = __builtin_nan("");   // an expired wait makes the call's log-probability NaN
     HMM_STAMP(8);
     uint32_t excl;
     const uint32_t total = block_map_suffix<D>(h, excl, wmaps);
@@ -713,7 +716,10 @@ __global__ __launch_bounds__(256) void sd_viterbi_fused_kernel(const float* __re
     HMM_STAMP(12);
     store_path_tile<D>(path + tc.base, tc.nvalid, stage);
     HMM_STAMP(13);
-    if (tc.tile == 0) grid_sum_parts(blockIdx.x, tps, ws, dsum, logprob_out, tc.seq);
+    if (tc.tile == 0) {
+        if (ok2) grid_sum_parts(blockIdx.x, tps, ws, dsum, logprob_out, tc.seq);
+        else if (threadIdx.x == 0) logprob_out[tc.seq] = __builtin_nan("");   // the wait for the tile maps ran out
+    }
 }
 
 // =============================================================================================
