@@ -47,6 +47,8 @@ def _load():
         lib.hmm_oracle_score.restype = ctypes.c_double
         lib.hmm_oracle_max_product.argtypes = [fp, fp, fp, ctypes.c_long, ctypes.c_int, dp, ip, dp]
         lib.hmm_oracle_max_product.restype = ctypes.c_int
+        lib.hmm_oracle_transition_counts.argtypes = [fp, fp, fp, ctypes.c_long, ctypes.c_int, dp]
+        lib.hmm_oracle_transition_counts.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -122,6 +124,28 @@ def max_product(prior, A, loglik):
     if rc != 0:
         raise RuntimeError("hmm_oracle_max_product failed")
     return mm, path, float(lp.value)
+
+
+def transition_counts(prior, A, loglik):
+    """One sequence: expected transition counts sum_k p(x_{k-1}=i, x_k=j | y_{1:T}) (the Baum-Welch
+    expectation step's statistic for the transition matrix).  Returns counts[D][D] f64."""
+    lib = _load()
+    prior, pp = _f32(prior)
+    A, pa = _f32(A)
+    loglik, pl = _f32(loglik)
+    T, D = loglik.shape
+    assert prior.shape == (D,) and A.shape == (D, D)
+    counts = np.empty((D, D), dtype=np.float64)
+    rc = lib.hmm_oracle_transition_counts(pp, pa, pl, T, D, counts.ctypes.data_as(ctypes.POINTER(ctypes.c_double)))
+    if rc != 0:
+        raise RuntimeError("hmm_oracle_transition_counts failed")
+    return counts
+
+
+def transition_counts_batch(prior, A, loglik, shared_model: bool):
+    B = loglik.shape[0]
+    return np.stack([transition_counts(prior[0 if shared_model else b], A[0 if shared_model else b], loglik[b])
+                     for b in range(B)])
 
 
 def max_product_batch(prior, A, loglik, shared_model: bool):

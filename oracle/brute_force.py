@@ -64,3 +64,15 @@ def max_marginals(prior, A, loglik):
             sel = w[seqs[:, k] == j]
             out[k, j] = sel.max() if sel.size else 0.0
     return out
+
+
+def transition_counts(prior, A, loglik):
+    """sum_k p(x_{k-1} = i, x_k = j | y_{1:T}) straight from the joint of Sec. II."""
+    seqs, w = enumerate_weights(prior, A, loglik)
+    T = seqs.shape[1]
+    D = np.asarray(prior).shape[0]
+    Z = w.sum()
+    out = np.zeros((D, D))
+    for k in range(1, T):
+        np.add.at(out, (seqs[:, k - 1], seqs[:, k]), w / Z)
+    return out

@@ -228,3 +228,63 @@ int hmm_oracle_max_product(const float *prior, const float *A, const float *ll,
     free(f); free(b); free(bn); free(logA);
     return 0;
 }
+
+/*
+ * Expected transition counts of the Baum-Welch expectation step (Sec. V-C names the
+ * forward-backward recursion as its core): the pairwise posterior of the chain of Sec. II,
+ *   p(x_{k-1}, x_k | y_{1:T}) = psi^f_{1,k-1}(x_{k-1}) psi_k(x_{k-1}, x_k) psi^b_{k,T}(x_k) / Z,
+ * summed over k = 2..T:  counts[i][j] = sum_k p(x_{k-1} = i, x_k = j | y_{1:T}).
+ * Same scaled forward and backward vectors as in hmm_oracle_smooth; each step's table is
+ * normalised by its own total (every scale factor cancels).  counts[D][D]; returns 0 or 1.
+ */
+int hmm_oracle_transition_counts(const float *prior, const float *A, const float *ll,
+                                 long T, int D, double *counts)
+{
+    if (T < 1 || D < 1) return 1;
+    double *f = (double *)malloc(sizeof(double) * (size_t)T * D);
+    double *b = (double *)malloc(sizeof(double) * D);
+    double *bn = (double *)malloc(sizeof(double) * D);
+    double *g = (double *)malloc(sizeof(double) * D);
+    double *xi = (double *)malloc(sizeof(double) * (size_t)D * D);
+    if (!f || !b || !bn || !g || !xi) { free(f); free(b); free(bn); free(g); free(xi); return 1; }
+    for (size_t e = 0; e < (size_t)D * D; ++e) counts[e] = 0.0;
+    for (long k = 0; k < T; ++k) {
+        const float *llk = ll + (size_t)k * D;
+        double m = -INFINITY;
+        for (int j = 0; j < D; ++j) if ((double)llk[j] > m) m = (double)llk[j];
+        double c = 0.0;
+        for (int j = 0; j < D; ++j) {
+            double pred = 0.0;
+            if (k == 0) pred = (double)prior[j];
+            else for (int i = 0; i < D; ++i) pred += f[(size_t)(k - 1) * D + i] * (double)A[(size_t)i * D + j];
+            g[j] = pred * exp((double)llk[j] - m);
+            c += g[j];
+        }
+        for (int j = 0; j < D; ++j) f[(size_t)k * D + j] = g[j] / c;
+    }
+    for (int j = 0; j < D; ++j) b[j] = 1.0;
+    for (long k = T - 1; k >= 1; --k) {
+        const float *llk = ll + (size_t)k * D;
+        double m = -INFINITY;
+        for (int j = 0; j < D; ++j) if ((double)llk[j] > m) m = (double)llk[j];
+        for (int j = 0; j < D; ++j) g[j] = exp((double)llk[j] - m) * b[j];     /* e_k(x_k) psi^b_{k,T}(x_k) */
+        double tot = 0.0;
+        for (int i = 0; i < D; ++i)
+            for (int j = 0; j < D; ++j) {
+                double v = f[(size_t)(k - 1) * D + i] * (double)A[(size_t)i * D + j] * g[j];
+                xi[(size_t)i * D + j] = v;
+                tot += v;
+            }
+        for (size_t e = 0; e < (size_t)D * D; ++e) counts[e] += xi[e] / tot;
+        double hm = 0.0;
+        for (int i = 0; i < D; ++i) {
+            double h = 0.0;
+            for (int j = 0; j < D; ++j) h += (double)A[(size_t)i * D + j] * g[j];
+            bn[i] = h;
+            if (h > hm) hm = h;
+        }
+        for (int i = 0; i < D; ++i) b[i] = bn[i] / hm;
+    }
+    free(f); free(b); free(bn); free(g); free(xi);
+    return 0;
+}

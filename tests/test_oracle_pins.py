@@ -258,3 +258,41 @@ def test_max_product_single_state_and_single_step():
     mm, path, lp = oracle.max_product(prior, np.full((3, 3), 1 / 3, np.float32), ll1)
     w = np.log(prior.astype(np.float64)) + ll1[0]
     assert path[0] == w.argmax() and abs(lp - w.max()) < 1e-15 and np.abs(mm[0] - (w - w.max())).max() < 1e-15
+
+
+# ------------------------------------------------------------------ expected transition counts (Sec. V-C, E-step)
+@pytest.mark.parametrize("D,T,seed,zf", [(3, 8, 40, 0.0), (3, 8, 41, 0.3), (2, 1, 42, 0.0), (2, 2, 43, 0.0),
+                                         (2, 12, 44, 0.0), (4, 5, 45, 0.25), (5, 4, 46, 0.0)])
+def test_transition_counts_match_enumeration(D, T, seed, zf):
+    prior, A, ll = _tiny(D, T, seed, zf)
+    N = oracle.transition_counts(prior, A, ll)
+    assert np.abs(N - bf.transition_counts(prior, A, ll)).max() < 1e-12
+
+
+@pytest.mark.parametrize("gen", [lambda: wl.config1(), lambda: wl.gilbert_elliott(T=3000), lambda: wl.config3(T=400),
+                                 lambda: wl.random_problem(6, 700, seed=3, zero_frac=0.4)])
+def test_transition_counts_invariants(gen):
+    """Row sums are the summed marginals of steps 1..T-1, column sums those of steps 2..T, the total is
+    T-1, and a transition the model forbids is never counted."""
+    p = gen()
+    prior, A, ll = p.prior[0], p.A[0], p.loglik[0]
+    N = oracle.transition_counts(prior, A, ll)
+    marg, _, _ = oracle.smooth(prior, A, ll)
+    assert np.abs(N.sum(axis=1) - marg[:-1].sum(axis=0)).max() < 1e-8 * p.T
+    assert np.abs(N.sum(axis=0) - marg[1:].sum(axis=0)).max() < 1e-8 * p.T
+    assert abs(N.sum() - (p.T - 1)) < 1e-8 * p.T
+    assert (N[A == 0] == 0).all() and (N >= 0).all()
+
+
+def test_transition_counts_identical_rows_closed_form():
+    """With identical transition rows the steps are independent: p(x_{k-1}, x_k | y) = gamma_{k-1} gamma_k^T."""
+    rng = np.random.default_rng(9)
+    D, T = 4, 60
+    r = rng.dirichlet(np.ones(D)).astype(np.float32)
+    A = np.tile(r, (D, 1))
+    prior = rng.dirichlet(np.ones(D)).astype(np.float32)
+    ll = np.log(rng.uniform(0.05, 1.0, size=(T, D))).astype(np.float32)
+    N = oracle.transition_counts(prior, A, ll)
+    marg, _, _ = oracle.smooth(prior, A, ll)
+    want = sum(np.outer(marg[k - 1], marg[k]) for k in range(1, T))
+    assert np.abs(N - want).max() < 1e-10
