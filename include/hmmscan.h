@@ -122,6 +122,28 @@ hmm_status hmm_max_product(const float* prior, const float* A, const float* logl
                            float* max_marginals, int32_t* path, double* logprob_out,
                            void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/*
+ * Expected transition counts, the statistic of the Baum-Welch expectation step for
+ * the transition matrix (Sec. V-C: the expectation step is the forward-backward
+ * recursion, i.e. hmm_smooth, followed by this sum):
+ *     counts[b][i][j] = sum_{k=2..T} p(x_{k-1} = i, x_k = j | y_{1:T}).
+ * It is formed from hmm_smooth's own outputs: with pred_k(j) = sum_i filtered_{k-1}(i) A[i][j],
+ *     counts[i][j] = A[i][j] * sum_k filtered_{k-1}(i) * marginals_k(j) / pred_k(j).
+ * (The other statistics of the expectation step are the marginals themselves: their first row
+ * for the prior, their sums against the observations for the emission model.)
+ *
+ *   A          as for hmm_smooth
+ *   filtered   [batch][T][D]  hmm_smooth's filtered output
+ *   marginals  [batch][T][D]  hmm_smooth's marginals output
+ *   counts     [batch][D][D]  out, fp64; all zero for T = 1
+ *   workspace: at least hmm_transition_counts_workspace_bytes(...), 256-byte aligned
+ */
+hmm_status hmm_transition_counts_workspace_bytes(int64_t T, int32_t D, int32_t batch, size_t* bytes);
+hmm_status hmm_transition_counts(const float* A, const float* filtered, const float* marginals,
+                                 int64_t T, int32_t D, int32_t batch, int32_t shared_model,
+                                 double* counts,
+                                 void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Static, human-readable name of a status code. */
 const char* hmm_status_string(hmm_status status);
 

@@ -15,7 +15,8 @@ LIB_PATH = os.path.join(_HERE, "libhmmscan.so")
 HMM_OK = 0
 _lib = None
 
-EXPORTED_SYMBOLS = ("hmm_workspace_bytes", "hmm_smooth", "hmm_viterbi", "hmm_max_product", "hmm_status_string",
+EXPORTED_SYMBOLS = ("hmm_workspace_bytes", "hmm_smooth", "hmm_viterbi", "hmm_max_product",
+                    "hmm_transition_counts_workspace_bytes", "hmm_transition_counts", "hmm_status_string",
                     "hmm_kernel_timing_enable", "hmm_kernel_timing_count", "hmm_kernel_timing_get")
 
 
@@ -47,6 +48,12 @@ def load_library():
         lib.hmm_max_product.argtypes = [vp, vp, vp, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                                         vp, vp, vp, vp, sz, vp]
         lib.hmm_max_product.restype = ctypes.c_int
+        lib.hmm_transition_counts_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32,
+                                                              ctypes.POINTER(sz)]
+        lib.hmm_transition_counts_workspace_bytes.restype = ctypes.c_int
+        lib.hmm_transition_counts.argtypes = [vp, vp, vp, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                              vp, vp, sz, vp]
+        lib.hmm_transition_counts.restype = ctypes.c_int
         lib.hmm_status_string.argtypes = [ctypes.c_int]
         lib.hmm_status_string.restype = ctypes.c_char_p
         lib.hmm_kernel_timing_enable.argtypes = [ctypes.c_int32]
@@ -233,3 +240,38 @@ def hmm_max_product(prior, A, loglik, max_marginals=None, path=None, logprob_out
     """Returns (max_marginals[B][T][D] f32 (log, largest entry of a step is 0), path[B][T] int32 or None,
     logprob_out[B] f64); asynchronous on torch's current stream."""
     return hmm_max_product_prepare(prior, A, loglik, max_marginals, path, logprob_out, workspace, want_path)()
+
+
+def hmm_transition_counts_workspace_bytes(T: int, D: int, batch: int) -> int:
+    lib = load_library()
+    n = ctypes.c_size_t(0)
+    rc = lib.hmm_transition_counts_workspace_bytes(int(T), int(D), int(batch), ctypes.byref(n))
+    if rc != HMM_OK:
+        raise HmmError(rc, "hmm_transition_counts_workspace_bytes")
+    return int(n.value)
+
+
+def hmm_transition_counts(A, filtered, marginals, counts=None, workspace=None):
+    """A[Bm][D][D], filtered[B][T][D] and marginals[B][T][D] as returned by hmm_smooth.
+    Returns counts[B][D][D] f64 (expected transition counts); asynchronous on torch's current stream."""
+    import torch
+    lib = load_library()
+    B, T, D = marginals.shape
+    Bm = A.shape[0]
+    if Bm not in (1, B):
+        raise ValueError("A's leading dimension must be 1 (shared) or batch")
+    f32 = torch.float32
+    _check(A, f32, (Bm, D, D), "A")
+    _check(filtered, f32, (B, T, D), "filtered")
+    _check(marginals, f32, (B, T, D), "marginals")
+    dev = marginals.device
+    if counts is None:
+        counts = torch.empty((B, D, D), dtype=torch.float64, device=dev)
+    _check(counts, torch.float64, (B, D, D), "counts")
+    if workspace is None:
+        workspace = torch.empty((max(hmm_transition_counts_workspace_bytes(T, D, B), 256),), dtype=torch.uint8, device=dev)
+    rc = lib.hmm_transition_counts(_ptr(A), _ptr(filtered), _ptr(marginals), T, D, B, 1 if Bm == 1 else 0, _ptr(counts),
+                                   _ptr(workspace), workspace.numel() * workspace.element_size(), _stream())
+    if rc != HMM_OK:
+        raise HmmError(rc, "hmm_transition_counts")
+    return counts

@@ -3,6 +3,7 @@
 #include <stdint.h>
 
 #include "../../include/hmmscan.h"
+#include "estep.hpp"
 #include "large_d.hpp"
 #include "small_d.hpp"
 
@@ -101,6 +102,26 @@ hmm_status hmm_max_product(const float* prior, const float* A, const float* logl
     hmm::SmallArgs a{prior, A, loglik, (long long)T, batch, shared_model ? 1 : 0, workspace, workspace_bytes,
                      static_cast<hipStream_t>(hip_stream)};
     return static_cast<hmm_status>(hmm::small_d_max_product(D, a, max_marginals, path, logprob_out));
+}
+
+hmm_status hmm_transition_counts_workspace_bytes(int64_t T, int32_t D, int32_t batch, size_t* bytes) {
+    if (T < 1 || D < 1 || batch < 1 || !bytes) return HMM_ERR_INVALID_ARG;
+    if (D > HMM_MAX_STATES) return HMM_ERR_UNSUPPORTED;
+    *bytes = hmm::transition_counts_ws_bytes(D, T, batch);
+    return HMM_OK;
+}
+
+hmm_status hmm_transition_counts(const float* A, const float* filtered, const float* marginals, int64_t T, int32_t D,
+                                 int32_t batch, int32_t shared_model, double* counts, void* workspace,
+                                 size_t workspace_bytes, void* hip_stream) {
+    if (!A || !filtered || !marginals || !counts) return HMM_ERR_INVALID_ARG;
+    if (T < 1 || D < 1 || batch < 1) return HMM_ERR_INVALID_ARG;
+    if (D > HMM_MAX_STATES) return HMM_ERR_UNSUPPORTED;
+    const size_t need = hmm::transition_counts_ws_bytes(D, T, batch);
+    if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return HMM_ERR_WORKSPACE;
+    hmm::EstepArgs a{A, filtered, marginals, (long long)T, D, batch, shared_model ? 1 : 0, workspace, workspace_bytes,
+                     static_cast<hipStream_t>(hip_stream)};
+    return static_cast<hmm_status>(hmm::transition_counts(a, counts));
 }
 
 const char* hmm_status_string(hmm_status status) {

@@ -1,0 +1,248 @@
+// Expected transition counts of the Baum-Welch expectation step (Sec. V-C: its core is the
+// forward-backward recursion, i.e. hmm_smooth), computed from the smoother's own outputs.
+//
+// The pairwise posterior of the chain, p(x_{k-1}=i, x_k=j | y_{1:T}) = psi^f_{k-1}(i) psi_k(i,j) psi^b_k(j) / Z,
+// summed over j gives the marginal of step k-1 and summed over i the marginal gamma_k(j) of step k.
+// With the filtering distribution fh_{k-1}(i) = p(x_{k-1}=i | y_{1:k-1}) and its one-step prediction
+// pred_k(j) = sum_i fh_{k-1}(i) A(i,j), every factor that depends on j alone collects into
+// gamma_k(j) / pred_k(j), so
+//     counts(i,j) = A(i,j) * sum_{k=2..T} fh_{k-1}(i) * gamma_k(j) / pred_k(j)            (0 where pred_k(j) = 0):
+// a pass over the filtered and smoothed arrays with 2 D^2 multiply-adds per step.  Steps are split
+// over workgroups, each leaves a partial D x D sum in the workspace, a last kernel adds them in fp64.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "estep.hpp"
+#include "ktimer.hpp"
+
+namespace hmm {
+
+#define HMM_DEV __device__ __forceinline__
+
+// transitions k = 1..T-1 (0-based step index of the later state) of one sequence, split over G workgroups
+struct StepRange { long long k0, k1; };
+HMM_DEV StepRange step_range(long long T, int G, int g) {
+    const long long n = T - 1;
+    const long long per = (n + G - 1) / G;
+    StepRange r;
+    r.k0 = 1 + (long long)g * per;
+    r.k1 = r.k0 + per;
+    if (r.k1 > T) r.k1 = T;
+    if (r.k0 > T) r.k0 = T;
+    return r;
+}
+
+// ---------------------------------------------------------------------------------------------
+// D <= 8: one lane per step, the D x D accumulator in registers.
+template <int D>
+__global__ __launch_bounds__(256) void tc_small_kernel(const float* __restrict__ A, const float* __restrict__ filt,
+                                                       const float* __restrict__ marg, long long T, int G,
+                                                       int shared_model, float* __restrict__ partial) {
+    __shared__ float red[4 * D * D];
+    const int seq = blockIdx.x / G, g = blockIdx.x % G;
+    const StepRange sr = step_range(T, G, g);
+    const float* Am = A + (shared_model ? 0 : (size_t)seq * D * D);
+    float a[D * D], acc[D * D];
+#pragma unroll
+    for (int e = 0; e < D * D; ++e) { a[e] = Am[e]; acc[e] = 0.0f; }
+    const float* fs = filt + (size_t)seq * T * D;
+    const float* ms = marg + (size_t)seq * T * D;
+    for (long long k = sr.k0 + threadIdx.x; k < sr.k1; k += 256) {
+        float f[D], gm[D];
+#pragma unroll
+        for (int j = 0; j < D; ++j) { f[j] = fs[(size_t)(k - 1) * D + j]; gm[j] = ms[(size_t)k * D + j]; }
+        float w[D];
+#pragma unroll
+        for (int j = 0; j < D; ++j) {
+            float pred = 0.0f;
+#pragma unroll
+            for (int i = 0; i < D; ++i) pred = fmaf(f[i], a[i * D + j], pred);
+            w[j] = pred > 0.0f ? gm[j] / pred : 0.0f;
+        }
+#pragma unroll
+        for (int i = 0; i < D; ++i)
+#pragma unroll
+            for (int j = 0; j < D; ++j) acc[i * D + j] = fmaf(f[i], w[j], acc[i * D + j]);
+    }
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int e = 0; e < D * D; ++e) {
+        float v = acc[e] * a[e];
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) v += __shfl_down(v, d, 64);
+        if (lane == 0) red[wave * D * D + e] = v;
+    }
+    __syncthreads();
+    if (threadIdx.x < D * D)
+        partial[(size_t)blockIdx.x * D * D + threadIdx.x] =
+            (red[threadIdx.x] + red[D * D + threadIdx.x]) + (red[2 * D * D + threadIdx.x] + red[3 * D * D + threadIdx.x]);
+}
+
+// ---------------------------------------------------------------------------------------------
+// 9 <= D <= 128 (padded to DP): the workgroup's 16 x 16 threads each own a (DP/16)^2 block of the
+// matrix; SB steps are staged through LDS per round, their predictions reduced over the thread rows.
+template <int DP>
+__global__ __launch_bounds__(256) void tc_large_kernel(const float* __restrict__ A, const float* __restrict__ filt,
+                                                       const float* __restrict__ marg, long long T, int Dr, int G,
+                                                       int shared_model, float* __restrict__ partial) {
+    constexpr int TT = DP / 16;   // edge of a thread's block
+    constexpr int SB = 4;         // steps per round
+    __shared__ float fbuf[SB * DP];       // fh_{k-1} of the round's steps
+    __shared__ float gbuf[SB * DP];       // gamma_k
+    __shared__ float pbuf[4 * SB * DP];   // per-wave partial predictions
+    const int seq = blockIdx.x / G, g = blockIdx.x % G;
+    const StepRange sr = step_range(T, G, g);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int ti = tid / 16, tj = tid % 16;
+    const float* Am = A + (shared_model ? 0 : (size_t)seq * Dr * Dr);
+    float a[TT][TT], acc[TT][TT];
+#pragma unroll
+    for (int r = 0; r < TT; ++r)
+#pragma unroll
+        for (int c = 0; c < TT; ++c) {
+            const int i = ti * TT + r, j = tj * TT + c;
+            a[r][c] = (i < Dr && j < Dr) ? Am[(size_t)i * Dr + j] : 0.0f;
+            acc[r][c] = 0.0f;
+        }
+    const float* fs = filt + (size_t)seq * T * Dr;
+    const float* ms = marg + (size_t)seq * T * Dr;
+    for (long long kb = sr.k0; kb < sr.k1; kb += SB) {
+        for (int idx = tid; idx < SB * DP; idx += 256) {
+            const int s = idx / DP, j = idx % DP;
+            const bool valid = (kb + s < sr.k1) && j < Dr;
+            fbuf[idx] = valid ? fs[(size_t)(kb + s - 1) * Dr + j] : 0.0f;
+            gbuf[idx] = valid ? ms[(size_t)(kb + s) * Dr + j] : 0.0f;
+        }
+        __syncthreads();
+        float fr[SB][TT], pp[SB][TT];
+#pragma unroll
+        for (int s = 0; s < SB; ++s) {
+#pragma unroll
+            for (int r = 0; r < TT; ++r) fr[s][r] = fbuf[s * DP + ti * TT + r];
+#pragma unroll
+            for (int c = 0; c < TT; ++c) {
+                float v = 0.0f;
+#pragma unroll
+                for (int r = 0; r < TT; ++r) v = fmaf(fr[s][r], a[r][c], v);
+                v += __shfl_xor(v, 16, 64);   // the wave's four thread rows
+                v += __shfl_xor(v, 32, 64);
+                pp[s][c] = v;
+            }
+        }
+        if (lane < 16) {
+#pragma unroll
+            for (int s = 0; s < SB; ++s)
+#pragma unroll
+                for (int c = 0; c < TT; ++c) pbuf[(wave * SB + s) * DP + tj * TT + c] = pp[s][c];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int s = 0; s < SB; ++s) {
+            float w[TT];
+#pragma unroll
+            for (int c = 0; c < TT; ++c) {
+                const int j = tj * TT + c;
+                const float pred = (pbuf[(0 * SB + s) * DP + j] + pbuf[(1 * SB + s) * DP + j]) +
+                                   (pbuf[(2 * SB + s) * DP + j] + pbuf[(3 * SB + s) * DP + j]);
+                w[c] = pred > 0.0f ? gbuf[s * DP + j] / pred : 0.0f;
+            }
+#pragma unroll
+            for (int r = 0; r < TT; ++r)
+#pragma unroll
+                for (int c = 0; c < TT; ++c) acc[r][c] = fmaf(fr[s][r], w[c], acc[r][c]);
+        }
+        __syncthreads();   // the next round overwrites the staging buffers
+    }
+#pragma unroll
+    for (int r = 0; r < TT; ++r)
+#pragma unroll
+        for (int c = 0; c < TT; ++c)
+            partial[(size_t)blockIdx.x * DP * DP + (size_t)(ti * TT + r) * DP + tj * TT + c] = acc[r][c] * a[r][c];
+}
+
+// counts[seq][i][j] = sum over the sequence's G partial sums, in fp64.  blockIdx.x = sequence,
+// blockIdx.y = group of EPB entries; the 256 threads are (entry, slice of the partial sums), slices
+// added in a fixed order.
+__global__ __launch_bounds__(256) void tc_reduce_kernel(const float* __restrict__ partial, int G, int PS, int Dr,
+                                                        int EPB, double* __restrict__ counts) {
+    __shared__ double red[256];
+    const int seq = blockIdx.x;
+    const int SL = 256 / EPB;
+    const int el = threadIdx.x % EPB, slice = threadIdx.x / EPB;
+    const int e = blockIdx.y * EPB + el;
+    double acc = 0.0;
+    if (e < Dr * Dr) {
+        const int i = e / Dr, j = e % Dr;
+        const float* src = partial + (size_t)seq * G * PS * PS + (size_t)i * PS + j;
+#pragma unroll 4
+        for (int g = slice; g < G; g += SL) acc += (double)src[(size_t)g * PS * PS];
+    }
+    red[threadIdx.x] = acc;
+    __syncthreads();
+    if (slice == 0 && e < Dr * Dr) {
+        double tot = 0.0;
+        for (int sl = 0; sl < SL; ++sl) tot += red[sl * EPB + el];
+        counts[(size_t)seq * Dr * Dr + e] = tot;
+    }
+}
+
+// =============================================================================================
+static int padded(int D) { return D <= 8 ? D : D <= 16 ? 16 : D <= 32 ? 32 : D <= 64 ? 64 : 128; }
+
+static int groups_per_sequence(int D, long long T, int batch) {
+    // about four workgroups per compute unit in total; one per unit where a partial sum is large (64 KiB at D > 64)
+    const int total = D > 64 ? 256 : D > 16 ? 512 : 1024;
+    long long G = (total + batch - 1) / batch;
+    const long long most = (T - 1 + 255) / 256;               // at least 256 steps each
+    if (G > most) G = most;
+    if (G < 1) G = 1;
+    return (int)G;
+}
+
+size_t transition_counts_ws_bytes(int D, long long T, int batch) {
+    const size_t PS = (size_t)padded(D);
+    return ((size_t)batch * groups_per_sequence(D, T, batch) * PS * PS * sizeof(float) + 255) / 256 * 256;
+}
+
+template <int D>
+static void launch_small(const EstepArgs& a, int G, float* partial) {
+    launch("tc_accumulate", tc_small_kernel<D>, dim3((unsigned)(a.batch * G)), dim3(256), a.stream, a.A, a.filtered,
+           a.marginals, a.T, G, a.shared_model, partial);
+}
+
+template <int DP>
+static void launch_large(const EstepArgs& a, int G, float* partial) {
+    launch("tc_accumulate", tc_large_kernel<DP>, dim3((unsigned)(a.batch * G)), dim3(256), a.stream, a.A, a.filtered,
+           a.marginals, a.T, a.D, G, a.shared_model, partial);
+}
+
+int transition_counts(const EstepArgs& a, double* counts) {
+    const int G = groups_per_sequence(a.D, a.T, a.batch);
+    if ((long long)a.batch * G > 0x7fffffffLL) return 2;
+    if (a.ws_bytes < transition_counts_ws_bytes(a.D, a.T, a.batch)) return 3;
+    float* partial = static_cast<float*>(a.ws);
+    const int PS = padded(a.D);
+    switch (PS) {
+        case 1: launch_small<1>(a, G, partial); break;
+        case 2: launch_small<2>(a, G, partial); break;
+        case 3: launch_small<3>(a, G, partial); break;
+        case 4: launch_small<4>(a, G, partial); break;
+        case 5: launch_small<5>(a, G, partial); break;
+        case 6: launch_small<6>(a, G, partial); break;
+        case 7: launch_small<7>(a, G, partial); break;
+        case 8: launch_small<8>(a, G, partial); break;
+        case 16: launch_large<16>(a, G, partial); break;
+        case 32: launch_large<32>(a, G, partial); break;
+        case 64: launch_large<64>(a, G, partial); break;
+        case 128: launch_large<128>(a, G, partial); break;
+        default: return 2;
+    }
+    const int E = a.D * a.D;
+    int EPB = 1;
+    while (EPB < E && EPB < 256) EPB <<= 1;
+    launch("tc_reduce", tc_reduce_kernel, dim3((unsigned)a.batch, (unsigned)((E + EPB - 1) / EPB)), dim3(256), a.stream,
+           (const float*)partial, G, PS, a.D, EPB, counts);
+    return hipGetLastError() == hipSuccess ? 0 : 4;
+}
+
+}  // namespace hmm

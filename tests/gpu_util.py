@@ -111,3 +111,27 @@ def check_max_product(p, label=""):
           f"max|dmm|={float(err.max()) if err.size else 0:.3e} ambiguous steps={int((~clear).sum())} "
           f"argmax mismatches={nm} rel dlogprob={rel:.3e}", flush=True)
     return worst
+
+
+def check_transition_counts(p, label=""):
+    """hmm_smooth (filtered + marginals) followed by hmm_transition_counts against the oracle's expected
+    transition counts.  Each of the T-1 pairwise posteriors inherits the marginals' 1e-4 absolute bound;
+    errors of independent steps do not add coherently, so the sum is held to 1e-4 * sqrt(T-1) + 1e-6 * (T-1)
+    per entry, the row and column sums (sums of marginals) to the same, the total to 1e-5 * (T-1)."""
+    prior, A, ll = to_dev(p)
+    marg, filt, _ = hmm.hmm_smooth(prior, A, ll, want_filtered=True)
+    counts = hmm.hmm_transition_counts(A, filt, marg)
+    torch.cuda.synchronize()
+    N = counts.cpu().numpy()
+    N0 = oracle.transition_counts_batch(p.prior, p.A, p.loglik, p.shared_model)
+    n = max(p.T - 1, 0)
+    tol = 1e-4 * np.sqrt(n) + 1e-6 * n + 1e-12
+    err = float(np.abs(N - N0).max()) if n else float(np.abs(N).max())
+    print(f"[transition counts {label or p.name}] B={p.batch} T={p.T} D={p.D} max|dN|={err:.3e} (tol {tol:.3e}) "
+          f"total err={float(np.abs(N.sum(axis=(1, 2)) - n).max()):.3e}", flush=True)
+    assert np.isfinite(N).all() and (N >= 0).all(), f"{label}: counts must be finite and non-negative"
+    assert err <= tol, f"{label}: transition counts off by {err} (tolerance {tol})"
+    assert np.abs(N.sum(axis=(1, 2)) - n).max() <= 1e-5 * n + 1e-9, f"{label}: counts must sum to T-1"
+    Am = np.broadcast_to(p.A, (p.batch,) + p.A.shape[1:])
+    assert (N[Am == 0] == 0).all(), f"{label}: a forbidden transition was counted"
+    return err

@@ -78,3 +78,11 @@ def test_argument_errors_are_caught_on_the_host():
     assert lib.hmm_max_product(fake, fake, fake, 8, 4, 1, 1, ctypes.c_void_p(0x1008), null, fake, aligned_ws, 1 << 20, null) == 1
     assert lib.hmm_max_product(fake, fake, fake, 8, 1000, 1, 1, fake, null, fake, aligned_ws, 1 << 20, null) == 2
     assert lib.hmm_max_product(fake, fake, fake, 8, 4, 1, 1, fake, null, fake, aligned_ws, 16, null) == 3
+    # hmm_transition_counts
+    assert lib.hmm_transition_counts(null, fake, fake, 8, 4, 1, 1, fake, aligned_ws, 1 << 20, null) == 1
+    assert lib.hmm_transition_counts(fake, fake, fake, 8, 4, 1, 1, null, aligned_ws, 1 << 20, null) == 1
+    assert lib.hmm_transition_counts(fake, fake, fake, 0, 4, 1, 1, fake, aligned_ws, 1 << 20, null) == 1
+    assert lib.hmm_transition_counts(fake, fake, fake, 8, 200, 1, 1, fake, aligned_ws, 1 << 20, null) == 2
+    assert lib.hmm_transition_counts(fake, fake, fake, 8, 4, 1, 1, fake, aligned_ws, 8, null) == 3
+    assert hmm.hmm_transition_counts_workspace_bytes(1 << 20, 4, 1) >= 64
+    assert hmm.hmm_transition_counts_workspace_bytes(1, 128, 3) == 3 * 128 * 128 * 4

@@ -21,6 +21,7 @@ def test_random_models_smoother(gu, D, T):
     gu.check_smooth(p, want_filtered=(T == 700))
     gu.check_viterbi(p)
     gu.check_max_product(p)
+    gu.check_transition_counts(p)
 
 
 @pytest.mark.parametrize("D,T,B,shared", [(16, 900, 5, False), (32, 1500, 3, True), (64, 257, 4, False),
@@ -30,6 +31,7 @@ def test_batched_smoother(gu, D, T, B, shared):
     gu.check_smooth(p, want_filtered=True)
     gu.check_viterbi(p)
     gu.check_max_product(p)
+    gu.check_transition_counts(p)
 
 
 def test_config3_shape(gu):
@@ -37,6 +39,7 @@ def test_config3_shape(gu):
     gu.check_smooth(p, want_filtered=True, label="C3 T=20000")
     gu.check_viterbi(p, label="C3 T=20000")
     gu.check_max_product(p, label="C3 T=20000")
+    gu.check_transition_counts(p, label="C3 T=20000")
 
 
 def test_config4_shape(gu):
@@ -44,6 +47,7 @@ def test_config4_shape(gu):
     gu.check_smooth(p, label="C4 B=12")
     gu.check_viterbi(p, label="C4 B=12")
     gu.check_max_product(p, label="C4 B=12")
+    gu.check_transition_counts(p, label="C4 B=12")
 
 
 def test_config5_shape(gu):
@@ -51,6 +55,7 @@ def test_config5_shape(gu):
     gu.check_smooth(p, want_filtered=True, label="C5 T=6000")
     gu.check_viterbi(p, label="C5 T=6000")
     gu.check_max_product(p, label="C5 T=6000")
+    gu.check_transition_counts(p, label="C5 T=6000")
 
 
 def test_sparse_transitions_and_impossible_emissions(gu):
@@ -62,6 +67,7 @@ def test_sparse_transitions_and_impossible_emissions(gu):
     gu.check_smooth(p, want_filtered=True)
     gu.check_viterbi(p)
     gu.check_max_product(p)
+    gu.check_transition_counts(p)
 
 
 @pytest.mark.parametrize("D,T", [(128, 40000), (64, 90000), (32, 70000)])
@@ -78,6 +84,7 @@ def test_first_observation_excludes_a_block_of_states(gu, D, T):
     gu.check_smooth(p, want_filtered=True, label=f"excluded block D={D}")
     gu.check_viterbi(p, label=f"excluded block D={D}")
     gu.check_max_product(p, label=f"excluded block D={D}")
+    gu.check_transition_counts(p, label=f"excluded block D={D}")
 
 
 # ---- the configurations at their full sizes, element by element against the oracle ----
@@ -86,6 +93,7 @@ def test_config3_full_size(gu):
     gu.check_smooth(p, label="C3 full")
     gu.check_viterbi(p, label="C3 full")
     gu.check_max_product(p, label="C3 full")
+    gu.check_transition_counts(p, label="C3 full")
 
 
 def test_config4_full_size(gu):
@@ -93,6 +101,7 @@ def test_config4_full_size(gu):
     gu.check_smooth(p, label="C4 full")
     gu.check_viterbi(p, label="C4 full")
     gu.check_max_product(p, label="C4 full")
+    gu.check_transition_counts(p, label="C4 full")
 
 
 def test_config5_full_size(gu):
@@ -100,3 +109,4 @@ def test_config5_full_size(gu):
     gu.check_smooth(p, label="C5 full")
     gu.check_viterbi(p, label="C5 full")
     gu.check_max_product(p, label="C5 full")
+    gu.check_transition_counts(p, label="C5 full")

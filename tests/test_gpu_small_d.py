@@ -27,6 +27,7 @@ def test_config1(gu):
     gu.check_smooth(p, want_filtered=True)
     gu.check_viterbi(p)
     gu.check_max_product(p)
+    gu.check_transition_counts(p)
 
 
 @pytest.mark.parametrize("T", [1, 2, 15, 16, 17, 4095, 4096, 4097, 10000])
@@ -35,6 +36,7 @@ def test_config2_shapes_ragged(gu, T):
     gu.check_smooth(p, want_filtered=(T % 2 == 1), label=f"C2 T={T}")
     gu.check_viterbi(p, label=f"C2 T={T}")
     gu.check_max_product(p, label=f"C2 T={T}")
+    gu.check_transition_counts(p, label=f"C2 T={T}")
 
 
 def test_gilbert_elliott_paper_model(gu):
@@ -42,6 +44,7 @@ def test_gilbert_elliott_paper_model(gu):
     gu.check_smooth(p)
     gu.check_viterbi(p)
     gu.check_max_product(p)     # binary evidence: exactly tied sequences, many ambiguous steps
+    gu.check_transition_counts(p)
 
 
 @pytest.mark.parametrize("D", [1, 2, 3, 4, 5, 6, 7, 8])
@@ -51,6 +54,7 @@ def test_random_models_every_small_D(gu, D, T):
     gu.check_smooth(p, want_filtered=(T == 300))
     gu.check_viterbi(p)
     gu.check_max_product(p)
+    gu.check_transition_counts(p)
 
 
 @pytest.mark.parametrize("D,T,B,shared", [(4, 5000, 3, True), (4, 4097, 5, False), (3, 100, 17, False),
@@ -60,6 +64,7 @@ def test_batched(gu, D, T, B, shared):
     gu.check_smooth(p, want_filtered=True)
     gu.check_viterbi(p)
     gu.check_max_product(p)
+    gu.check_transition_counts(p)
 
 
 @pytest.mark.parametrize("D,T", [(4, 6000), (6, 3000), (3, 4100)])
@@ -75,6 +80,7 @@ def test_zero_transitions_and_impossible_emissions(gu, D, T):
     gu.check_smooth(p)
     gu.check_viterbi(p)
     gu.check_max_product(p)
+    gu.check_transition_counts(p)
 
 
 def test_config2_full_size(gu):
@@ -83,3 +89,4 @@ def test_config2_full_size(gu):
     gu.check_smooth(p, want_filtered=False, label="C2 full")
     gu.check_viterbi(p, label="C2 full")
     gu.check_max_product(p, label="C2 full")
+    gu.check_transition_counts(p, label="C2 full")
