@@ -23,16 +23,33 @@ constexpr float LOG2E = 1.4426950408889634f;
 constexpr int ZERO_STRIP_EXP = -(1 << 28);   // power-of-two scale recorded for an all-zero strip of an aggregate
 
 // ---------------------------------------------------------------------------------------------
-// m_t = max_j ll_t(j): one wave per row batch, coalesced.
+// m_t = max_j ll_t(j).  A power-of-two group of lanes per row, four consecutive values per lane, so
+// that a wave reads whole consecutive rows (coalesced for every D); 16-byte loads when rows are
+// 16-byte aligned (D a multiple of four).
 __global__ __launch_bounds__(256) void ld_rowmax_kernel(const float* __restrict__ ll, long long rows, int Dr,
                                                         float* __restrict__ rowmax) {
-    const long long row = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (row >= rows) return;
+    const int lpr = (Dr + 3) / 4;                  // lanes per row
+    int width = 1;
+    while (width < lpr) width <<= 1;               // power of two <= 32 for Dr <= 128
+    const int rows_per_wave = 64 / width;
     const int lane = threadIdx.x & 63;
+    const long long wave = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const long long row = wave * rows_per_wave + lane / width;
+    const int sub = lane % width;
     float m = -INFINITY;
-    for (int j = lane; j < Dr; j += 64) m = fmaxf(m, ll[row * Dr + j]);
-    m = wave_max(m);
-    if (lane == 0) rowmax[row] = m;
+    if (row < rows && sub < lpr) {
+        const float* p = ll + row * Dr + 4 * sub;
+        if ((Dr & 3) == 0) {
+            const float4 x = *reinterpret_cast<const float4*>(p);
+            m = fmaxf(fmaxf(x.x, x.y), fmaxf(x.z, x.w));
+        } else {
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (4 * sub + q < Dr) m = fmaxf(m, p[q]);
+        }
+    }
+    for (int d = 1; d < width; d <<= 1) m = fmaxf(m, __shfl_xor(m, d, 64));
+    if (row < rows && sub == 0) rowmax[row] = m;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -770,7 +787,12 @@ static int large_smooth_impl(const LargeArgs& a, float* marg, float* filt, doubl
     double* part = reinterpret_cast<double*>(ws + w.part);
     hipStream_t st = a.stream;
     const dim3 block(256);
-    launch("ld_rowmax", ld_rowmax_kernel, dim3((unsigned)((rows + 3) / 4)), block, st, a.ll, rows, a.D, rowmax);
+    {
+        int width = 1;
+        while (width < (a.D + 3) / 4) width <<= 1;
+        const long long rpb = 4LL * (64 / width);   // rows per workgroup
+        launch("ld_rowmax", ld_rowmax_kernel, dim3((unsigned)((rows + rpb - 1) / rpb)), block, st, a.ll, rows, a.D, rowmax);
+    }
     launch("ld_aggregate", ld_aggregate_kernel<D>, dim3((unsigned)((p.nchunks + C::CPW - 1) / C::CPW)), block, st, a.A,
            a.ll, rowmax, a.T, a.D, p.Lc, p.cps, p.nchunks, a.shared_model, agg, aggT, exps);
     if constexpr (D <= 32)
