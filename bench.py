@@ -134,6 +134,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--sets", type=int, default=None, help="distinct buffer sets rotated over (cold-cache timing)")
     ap.add_argument("--T", type=int, default=None, help="sequence length (default: the configuration's own)")
+    ap.add_argument("--batch-copies", type=int, default=1,
+                    help="run this many copies of the workload's sequences as one batch (a scaled run that shows the "
+                         "kernels' streaming rate; supporting evidence, not the configured shape)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain device copy of 32 MiB per step (a kernel of known traffic, for scaling "
@@ -168,6 +171,11 @@ def main() -> int:
     dev = torch.device("cuda:0")
     gen = getattr(wl, gen_name)
     p = gen() if args.T is None else gen(T=args.T)
+    if args.batch_copies > 1:
+        p.loglik = np.ascontiguousarray(np.tile(p.loglik, (args.batch_copies, 1, 1)))
+        if not p.shared_model:
+            p.prior = np.ascontiguousarray(np.tile(p.prior, (args.batch_copies, 1)))
+            p.A = np.ascontiguousarray(np.tile(p.A, (args.batch_copies, 1, 1)))
     T, D, B = p.T, p.D, p.batch
     nsets = max(1, args.sets)
     prior = torch.from_numpy(p.prior).to(dev)
@@ -290,7 +298,8 @@ def main() -> int:
         "value": value, "unit": "state-steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"{args.workload}: {wl_text}" + ("" if args.T is None else f" (T overridden: {T})"),
+        "config": {"workload": f"{args.workload}: {wl_text}" + ("" if args.T is None else f" (T overridden: {T})") +
+                   ("" if args.batch_copies == 1 else f" (scaled run: {args.batch_copies} copies as one batch)"),
                    "batch": B, "buffer_sets": nsets, "step": "hmm_smooth + hmm_viterbi"},
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
