@@ -12,6 +12,10 @@
 //   path       back-pointer walk inside each chunk
 // Aggregates and carries are scale-free (offsets are dropped); the log-probability is the sum of the
 // chunk-local growths of max_j V, each measured from a carry renormalised to max 0.
+//
+// The same aggregates and carries, run in both directions, also serve the paper's parallel
+// max-product algorithm as printed (Algorithm 5): maximum forward and backward potentials inside
+// the chunks and Theorem 4's per-step combination (lm_apply, lm_combine, lm_finalize below).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 

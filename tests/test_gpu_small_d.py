@@ -16,8 +16,8 @@ def gu():
 
 @pytest.fixture(autouse=True, params=["single", "multi"])
 def plan(request, monkeypatch):
-    """Every case runs under both launch plans: the single-launch one (tiles exchange carries through
-    flags) where the shape allows it, and the multi-launch one forced through HMMSCAN_PLAN."""
+    """Every case runs under both launch plans: the single-launch one (tiles exchange their aggregates
+    through self-validating workspace slots) where the shape allows it, and the multi-launch one forced through HMMSCAN_PLAN."""
     monkeypatch.setenv("HMMSCAN_PLAN", request.param)
     return request.param
 
