@@ -1,0 +1,42 @@
+"""GPU parity on randomly drawn shapes: state counts that are not padded sizes, lengths around tile and
+chunk boundaries, small and large batches, shared and per-sequence models -- every call of the library
+against the CPU oracle on each."""
+import numpy as np
+import pytest
+
+from paper_2102_05743_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gu():
+    import gpu_util
+    return gpu_util
+
+
+def _draw(seed):
+    rng = np.random.default_rng(seed)
+    D = int(rng.choice([1, 2, 3, 4, 5, 7, 8, 9, 11, 15, 16, 17, 24, 31, 32, 33, 48, 63, 64, 65, 96, 127, 128]))
+    budget = 3_000_000                      # D^2 * T * B kept small enough for the oracle
+    B = int(rng.choice([1, 1, 1, 2, 3, 7, 19]))
+    tmax = max(1, min(30000, budget // (D * D * B)))
+    T = int(rng.integers(1, tmax + 1))
+    if rng.random() < 0.4:                  # snap to a boundary of the tiling and step around it
+        base = int(rng.choice([16, 32, 64, 128, 256, 2048, 4096]))
+        T = max(1, min(tmax, base * int(rng.integers(1, 5)) + int(rng.integers(-1, 2))))
+    shared = bool(rng.random() < 0.5) or B == 1
+    zf = float(rng.choice([0.0, 0.0, 0.3]))
+    return D, T, B, shared, zf
+
+
+@pytest.mark.parametrize("seed", list(range(100)))
+def test_random_shape(gu, seed):
+    D, T, B, shared, zf = _draw(seed)
+    p = wl.random_problem(D, T, batch=B, shared_model=shared, seed=5000 + seed, zero_frac=zf)
+    label = f"seed {seed}: D={D} T={T} B={B} shared={shared} zero_frac={zf}"
+    print(label, flush=True)
+    gu.check_smooth(p, want_filtered=(seed % 2 == 0), label=label)
+    gu.check_viterbi(p, label=label)
+    gu.check_max_product(p, label=label)
+    gu.check_transition_counts(p, label=label)
