@@ -11,6 +11,7 @@
 // Elements are never stored: each step's psi_k = A diag(e_k) is rebuilt from A and ll_k.
 // States D..DP-1 of the padded model are unreachable (prior 0, self-loop only, e = 0).
 #include <hip/hip_runtime.h>
+#include <math.h>
 #include <stdint.h>
 
 #include "ktimer.hpp"
@@ -728,12 +729,18 @@ static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; 
 LargePlan large_plan(int Dr, long long T, int batch) {
     LargePlan p;
     p.DP = Dr <= 16 ? 16 : Dr <= 32 ? 32 : Dr <= 64 ? 64 : 128;
-    // chunks: enough to occupy every matrix core (smaller states need more, shorter chunks), but no
-    // more than 512 per sequence, because the carry between the chunks of one sequence is sequential
+    // chunks: enough to occupy every matrix core (smaller states need more, shorter chunks).  The
+    // carry between the chunks of one sequence is sequential, and so are the steps inside a chunk:
+    // with a hop costing about as much as one (D >= 64) or half a (D <= 32) step of the in-chunk
+    // recursions, their sum is smallest near sqrt(T) resp. sqrt(2T) chunks per sequence, which bounds
+    // the count from above.
     const long long target = p.DP >= 128 ? 256 : p.DP >= 64 ? 512 : p.DP >= 32 ? 2048 : 8192;
     long long cps = (target + batch - 1) / batch;
     if (cps < 1) cps = 1;
-    if (cps > 512) cps = 512;
+    long long most = (long long)sqrt((p.DP >= 64 ? 1.0 : 2.0) * (double)T);
+    if (most < 256) most = 256;
+    if (most > 8192) most = 8192;
+    if (cps > most) cps = most;
     long long Lc = (T + cps - 1) / cps;
     Lc = (Lc + 15) / 16 * 16;
     if (Lc < 32) Lc = 32;
