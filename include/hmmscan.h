@@ -26,7 +26,8 @@
  * idle device.  If other work (another stream, another process) occupies compute
  * units for the whole duration, the wait is bounded: the kernel then terminates
  * by itself and the call's log-likelihood / log-probability output is NaN (its
- * other outputs are then meaningless).  Setting the
+ * other outputs are then meaningless).  HMMSCAN_SPIN_LIMIT=<polls> overrides the
+ * bound (0: give up at once, for exercising this path).  Setting the
  * environment variable HMMSCAN_PLAN=multi selects the plan without such waits for
  * every shape.  Two calls must not share one workspace concurrently.
  */

@@ -365,6 +365,7 @@ struct FusedWs {
     double* part;      // [tiles]       tile-local log evidence / log-probability
     uint32_t* tmap;    // [tiles]       tile back-pointer maps (Viterbi)
     uint32_t* err;     // [1]           set if a bounded wait ran out
+    int spin_limit;    // polls before a wait gives up (every wave terminates whatever the other workgroups do)
 };
 
 // LDS scratch of the inter-tile exchange.  Staged aggregates are stored in pairs of tiles, each
@@ -419,10 +420,10 @@ HMM_DEV void grid_publish(const float* wagg, const FusedWs& ws) {
 // holds the sentinel, staging them into LDS in the padded pair layout.  Coalesced 8-byte loads
 // when the base is 8-byte aligned.  Returns false if the bounded wait ran out.
 template <int D>
-HMM_DEV bool gather_aggregates(const float* src, int n, float* dst_lds) {
+HMM_DEV bool gather_aggregates(const float* src, int n, float* dst_lds, int spin_limit) {
     using G = GridLds<D>;
     const bool wide = (reinterpret_cast<uintptr_t>(src) & 7u) == 0;
-    for (int spin = 0; spin < SPIN_LIMIT; ++spin) {
+    for (int spin = 0; spin < spin_limit; ++spin) {
         bool valid = true;
         if (wide) {
             const unsigned long long* s2 = reinterpret_cast<const unsigned long long*>(src);
@@ -484,7 +485,7 @@ HMM_DEV bool grid_gather(const TileCoord& tc, int tps, const float* __restrict__
     using G = GridLds<D>;
     static_assert(C::NW == 4, "the split below assumes four waves");
     const int tile0 = blockIdx.x - tc.tile;   // first tile of this sequence
-    const bool ok = gather_aggregates<D>(ws.agg + (size_t)tile0 * D * D, tps * D * D, gl.aggs);
+    const bool ok = gather_aggregates<D>(ws.agg + (size_t)tile0 * D * D, tps * D * D, gl.aggs, ws.spin_limit);
     if (!ok && threadIdx.x == 0) atomicOr(ws.err, 1u);
     HMM_STAMP(14);
     const int wave = threadIdx.x >> 6;
@@ -551,7 +552,7 @@ HMM_DEV bool grid_gather(const TileCoord& tc, int tps, const float* __restrict__
 HMM_DEV void grid_sum_parts(int tile0, int tps, const FusedWs& ws, double* dsum, double* __restrict__ out, int seq) {
     double acc = 0.0;
     bool ok = false;
-    for (int spin = 0; spin < SPIN_LIMIT; ++spin) {
+    for (int spin = 0; spin < ws.spin_limit; ++spin) {
         bool valid = true;
         acc = 0.0;
         if ((int)threadIdx.x < tps) {
@@ -689,7 +690,7 @@ __global__ __launch_bounds__(256) void sd_viterbi_fused_kernel(const float* __re
     // the tile maps of the sequence; state at this tile's last step = maps of later tiles composed
     uint32_t tm = map_identity<D>();
     bool ok2 = false;
-    for (int spin = 0; spin < SPIN_LIMIT; ++spin) {
+    for (int spin = 0; spin < ws.spin_limit; ++spin) {
         bool valid = true;
         if ((int)threadIdx.x < tps) {
             tm = coherent_load(ws.tmap + tile0 + threadIdx.x);
@@ -794,6 +795,15 @@ static long long resident_capacity(K kernel) {
     return cached;
 }
 
+// Polls before an inter-tile wait gives up.  HMMSCAN_SPIN_LIMIT overrides the default; 0 makes every
+// wait fail at once, which exercises the failure path (NaN evidence, all kernels still terminate).
+static int spin_limit() {
+    const char* e = getenv("HMMSCAN_SPIN_LIMIT");
+    if (e == nullptr) return SPIN_LIMIT;
+    const long v = strtol(e, nullptr, 10);
+    return (int)(v < 0 ? 0 : v > (1L << 24) ? (1L << 24) : v);
+}
+
 static bool force_multi_launch() {
     const char* e = getenv("HMMSCAN_PLAN");
     return e != nullptr && e[0] == 'm';   // HMMSCAN_PLAN=multi forces the multi-launch plan
@@ -828,7 +838,7 @@ static int two_filter(const SmallArgs& a, float* marg, float* filt, int32_t* arg
     if (!force_multi_launch() && tps <= C::NT && nt <= cap) {
         const XchLayout xl = xch_layout<D>((size_t)nt);
         FusedWs fw{reinterpret_cast<float*>(xch + xl.agg), reinterpret_cast<double*>(xch + xl.part), xch + xl.tmap,
-                   xch + xl.err};
+                   xch + xl.err, spin_limit()};
         const int nwords = (int)xl.words;
         launch(MP ? "sd_clear_mm" : "sd_clear_sp", sd_clear_kernel<D>, dim3((nwords + 255) / 256), dim3(256), st, xch,
                nwords);
@@ -894,7 +904,7 @@ int SmallD<D>::viterbi(const SmallArgs& a, int32_t* path, double* logprob_out) {
     if (!force_multi_launch() && tps <= C::NT && nt <= cap) {
         const XchLayout xl = xch_layout<D>((size_t)nt);
         FusedWs fw{reinterpret_cast<float*>(xch + xl.agg), reinterpret_cast<double*>(xch + xl.part), xch + xl.tmap,
-                   xch + xl.err};
+                   xch + xl.err, spin_limit()};
         const int nwords = (int)xl.words;
         launch("sd_clear_mp", sd_clear_kernel<D>, dim3((nwords + 255) / 256), dim3(256), st, xch, nwords);
         launch("sd_viterbi_fused", sd_viterbi_fused_kernel<D>, grid, block, st, a.prior, a.A, a.ll, a.T, itps,

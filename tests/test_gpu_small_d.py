@@ -90,3 +90,28 @@ def test_config2_full_size(gu):
     gu.check_viterbi(p, label="C2 full")
     gu.check_max_product(p, label="C2 full")
     gu.check_transition_counts(p, label="C2 full")
+
+
+def test_expired_wait_is_reported_not_hung(gu, plan, monkeypatch):
+    """Failure handling of the single-launch plan, forced from the host: with a poll limit of zero every
+    inter-tile wait gives up at once, all kernels still run to completion, and the evidence outputs are
+    NaN; the next call on the same workspace is correct again."""
+    import torch
+    import paper_2102_05743_amd as hmm
+    if plan != "single":
+        pytest.skip("the multi-launch plan has no inter-workgroup waits")
+    p = wl.config2(T=50000)
+    prior, A, ll = gu.to_dev(p)
+    ws_s, ws_v = hmm.hmm_workspace_bytes(p.T, p.D, 1)
+    ws = torch.empty((max(ws_s, ws_v),), dtype=torch.uint8, device=ll.device)
+    monkeypatch.setenv("HMMSCAN_SPIN_LIMIT", "0")
+    _, _, L = hmm.hmm_smooth(prior, A, ll, workspace=ws)
+    _, lp = hmm.hmm_viterbi(prior, A, ll, workspace=ws)
+    _, _, lpm = hmm.hmm_max_product(prior, A, ll, workspace=ws)
+    torch.cuda.synchronize()
+    assert np.isnan(L.cpu().numpy()).all() and np.isnan(lp.cpu().numpy()).all() and np.isnan(lpm.cpu().numpy()).all()
+    monkeypatch.delenv("HMMSCAN_SPIN_LIMIT")
+    marg, _, L = hmm.hmm_smooth(prior, A, ll, workspace=ws)
+    torch.cuda.synchronize()
+    m0, _, L0 = gu.oracle.smooth(p.prior[0], p.A[0], p.loglik[0], want_filtered=False)
+    assert np.abs(marg.cpu().numpy()[0] - m0).max() <= gu.MARG_ATOL and abs(float(L[0]) - L0) <= gu.LOGLIK_RTOL * abs(L0)
