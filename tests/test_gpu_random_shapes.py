@@ -40,3 +40,16 @@ def test_random_shape(gu, seed):
     gu.check_viterbi(p, label=label)
     gu.check_max_product(p, label=label)
     gu.check_transition_counts(p, label=label)
+
+
+@pytest.mark.parametrize("D,T,B,shared", [(4, 1, 70000, True), (4, 3, 70000, False), (2, 40, 20000, True),
+                                          (16, 2, 3000, False), (128, 1, 5, True), (128, 2, 5, False),
+                                          (8, 17, 9000, False), (32, 33, 700, True), (64, 1, 100, True)])
+def test_many_short_sequences(gu, D, T, B, shared):
+    """The other extreme from the long-horizon workloads: very many sequences of a few steps."""
+    p = wl.random_problem(D, T, batch=B, shared_model=shared, seed=D + T + B)
+    label = f"D={D} T={T} B={B} shared={shared}"
+    gu.check_smooth(p, want_filtered=True, label=label)
+    gu.check_viterbi(p, label=label)
+    gu.check_max_product(p, label=label)
+    gu.check_transition_counts(p, label=label)
