@@ -96,6 +96,29 @@ HMM_DEV float quad_xor2(float v) { return dpp_take<0x4E, 0xF>(v, v); }   // quad
 HMM_DEV int quad_xor1(int v) { return __builtin_amdgcn_update_dpp(v, v, 0xB1, 0xF, 0xF, false); }
 HMM_DEV int quad_xor2(int v) { return __builtin_amdgcn_update_dpp(v, v, 0x4E, 0xF, 0xF, false); }
 
+// Rotation inside each DPP row of 16 lanes: lane l receives the value of lane (l - R) mod 16 of its row.
+template <int R>
+HMM_DEV float row_rot(float v) {
+    if constexpr (R == 0) return v;
+    else return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x120 + R, 0xF, 0xF, true));
+}
+
+// Sum / maximum over the 16 lanes of a DPP row, delivered to every lane of the row.
+HMM_DEV float row_allsum(float v) {
+    v += row_rot<8>(v);
+    v += row_rot<4>(v);
+    v += row_rot<2>(v);
+    v += row_rot<1>(v);
+    return v;
+}
+HMM_DEV float row_allmax(float v) {
+    v = fmaxf(v, row_rot<8>(v));
+    v = fmaxf(v, row_rot<4>(v));
+    v = fmaxf(v, row_rot<2>(v));
+    v = fmaxf(v, row_rot<1>(v));
+    return v;
+}
+
 // Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every outstanding
 // global load and store of the wave (its fence covers global memory), which puts a full memory
 // round trip on the critical path of loops that store a result or prefetch an input per step.

@@ -673,6 +673,177 @@ __global__ __launch_bounds__(256) void ld_apply_kernel(const float* __restrict__
 }
 
 // ---------------------------------------------------------------------------------------------
+// The same vector recursions for D <= 32 with one chunk per DPP row of 16 lanes and no LDS at all.
+// Lane l of a row holds components l (and 16 + l for D = 32) of the vector; the product with A is
+// systolic: the term f(i) A(i,j) with i = (l - r) mod 16 reaches lane l as the row's vector rotated
+// by r lanes (a DPP modifier), multiplied by a register that is constant per (r, block pair).
+// Sixteen chunks advance per workgroup, independently; the normaliser of a step is computed beside
+// the next step's products and applied one step late, so a step's dependent chain is the products
+// and two multiplications.  First half of the grid: forward chunks, second half: backward chunks.
+template <int NQ, int QS, int R>
+HMM_DEV void row_matvec_terms(const float (&h)[NQ], const float (&a)[NQ * NQ * 16], float (&acc)[NQ][4]) {
+    if constexpr (R < 16) {
+        const float x = row_rot<R>(h[QS]);
+#pragma unroll
+        for (int qd = 0; qd < NQ; ++qd) acc[qd][R & 3] = fmaf(x, a[(QS * NQ + qd) * 16 + R], acc[qd][R & 3]);
+        row_matvec_terms<NQ, QS, R + 1>(h, a, acc);
+    } else if constexpr (QS + 1 < NQ) {
+        row_matvec_terms<NQ, QS + 1, 0>(h, a, acc);
+    }
+}
+
+template <int D>
+__global__ __launch_bounds__(256) void ld_apply_row_kernel(const float* __restrict__ prior, const float* __restrict__ A,
+                                                           const float* __restrict__ ll,
+                                                           const float* __restrict__ rowmax, long long T, int Dr,
+                                                           int Lc, int cps, long long nchunks, int shared_model,
+                                                           const float* __restrict__ fin,
+                                                           const float* __restrict__ bout, float* __restrict__ F,
+                                                           float* __restrict__ Bv, double* __restrict__ part,
+                                                           int half) {
+    static_assert(D == 16 || D == 32, "one DPP row per chunk");
+    constexpr int NQ = D / 16;
+    constexpr int PFD = 8;                                  // steps of log-likelihoods in flight
+    const bool backward = (int)blockIdx.x >= half;
+    const int l = threadIdx.x & 15;
+    const long long chunk = (long long)(backward ? blockIdx.x - half : blockIdx.x) * 16 + (threadIdx.x >> 4);
+    const ChunkCoord cc = chunk_coord(chunk, nchunks, cps, T, Lc);
+    const float* Am = A + (shared_model ? 0 : (size_t)cc.seq * Dr * Dr);
+    // forward: a[(qs, qd, r)] = A(16 qs + (l - r) mod 16, 16 qd + l); backward: A(16 qd + l, 16 qs + (l - r) mod 16)
+    float a[NQ * NQ * 16];
+#pragma unroll
+    for (int qs = 0; qs < NQ; ++qs)
+#pragma unroll
+        for (int qd = 0; qd < NQ; ++qd)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int src = 16 * qs + ((l - r) & 15), dst = 16 * qd + l;
+                const int i = backward ? dst : src, j = backward ? src : dst;
+                float v = (i == j) ? 1.0f : 0.0f;
+                if (i < Dr && j < Dr) v = Am[(size_t)i * Dr + j];
+                a[(qs * NQ + qd) * 16 + r] = v;
+            }
+    const float* lseq = ll + (size_t)cc.seq * T * Dr;
+    const float* mseq = rowmax + (size_t)cc.seq * T;
+    float* oseq = (backward ? Bv : F) + (size_t)cc.seq * T * Dr;
+    const bool first_chunk = cc.nsteps > 0 && (chunk % cps) == 0;
+    // step order: forward s = 0, 1, ...; backward s = nsteps-1, nsteps-2, ...  (pos = position in that order)
+    auto step_at = [&](int pos) { return backward ? cc.nsteps - 1 - pos : pos; };
+    float xq[PFD][NQ], mq[PFD];
+    // Running pointers instead of index arithmetic per step.  Fetches are unconditional (the compiler
+    // can then count outstanding loads exactly); past the chunk's end they repeat its last position.
+    const int s_first = cc.nsteps > 0 ? step_at(0) : 0;
+    const long long stride = backward ? -(long long)Dr : (long long)Dr;
+    const float* lp = lseq + (size_t)(cc.t0 + s_first) * Dr;
+    const float* mp = mseq + (cc.t0 + s_first);
+    float* op = oseq + (size_t)(cc.t0 + s_first) * Dr;
+    int colq[NQ];
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) colq[q] = (16 * q + l) < Dr ? 16 * q + l : 0;
+    int fetched = 0;
+    auto fetch = [&](float (&x)[NQ], float& m) {
+        m = *mp;
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) x[q] = lp[colq[q]];
+        ++fetched;
+        if (fetched < cc.nsteps) {
+            lp += stride;
+            mp += backward ? -1 : 1;
+        }
+    };
+    float h[NQ];
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) {
+        const int j = 16 * q + l;
+        float v = 0.0f;
+        if (cc.nsteps > 0) {
+            if (backward) v = bout[(size_t)chunk * D + j];
+            else if (first_chunk) v = (j < Dr) ? prior[(shared_model ? 0 : (size_t)cc.seq * Dr) + j] : 0.0f;
+            else v = fin[(size_t)chunk * D + j];
+        }
+        h[q] = v;
+    }
+#pragma unroll
+    for (int p = 0; p < PFD; ++p) fetch(xq[p], mq[p]);
+    float hs = h[0];
+#pragma unroll
+    for (int q = 1; q < NQ; ++q) hs += h[q];
+    // forward: every chunk but the sequence's first starts from a vector summing to one; backward: any scale
+    float inv = (!backward && first_chunk) ? 1.0f : __builtin_amdgcn_rcpf(row_allsum(hs));
+    float msum = 0.0f, lsum = 0.0f;
+    for (int p0 = 0; p0 < Lc; p0 += PFD) {
+#pragma unroll
+        for (int p = 0; p < PFD; ++p) {
+            const int pos = p0 + p;
+            const bool active = pos < cc.nsteps;
+            const int s = step_at(pos);
+            const long long t = cc.t0 + s;
+            const float mm = (mq[p] == -INFINITY) ? 0.0f : mq[p];
+            float e[NQ];
+#pragma unroll
+            for (int q = 0; q < NQ; ++q) {
+                const float x = (16 * q + l) < Dr ? xq[p][q] : -INFINITY;
+                e[q] = __builtin_amdgcn_exp2f(fmaf(x, LOG2E, -LOG2E * mm));
+            }
+            fetch(xq[p], mq[p]);
+            if (!backward) {
+                float g[NQ];
+                float acc[NQ][4];
+#pragma unroll
+                for (int q = 0; q < NQ; ++q) acc[q][0] = acc[q][1] = acc[q][2] = acc[q][3] = 0.0f;
+                row_matvec_terms<NQ, 0, 0>(h, a, acc);
+#pragma unroll
+                for (int q = 0; q < NQ; ++q) {
+                    const float moved = ((acc[q][0] + acc[q][1]) + (acc[q][2] + acc[q][3])) * inv;
+                    g[q] = ((t == 0) ? h[q] : moved) * e[q];   // psi_1 = prior o e_1: no transition at the first step
+                }
+                float gs = g[0];
+#pragma unroll
+                for (int q = 1; q < NQ; ++q) gs += g[q];
+                const float c = row_allsum(gs);            // p(y_t | y_{<t}) e^{-m_t} (times the prior's mass at t = 0)
+                const float ic = __builtin_amdgcn_rcpf(c);
+                if (active) {
+#pragma unroll
+                    for (int q = 0; q < NQ; ++q) {
+                        if (16 * q + l < Dr) op[16 * q + l] = g[q] * ic;   // p(x_t | y_{1:t})
+                        h[q] = g[q];
+                    }
+                    op += stride;
+                    inv = ic;
+                    msum += mm;
+                    lsum += __logf(c);
+                }
+            } else {
+                float bs[NQ], u[NQ];
+#pragma unroll
+                for (int q = 0; q < NQ; ++q) {
+                    bs[q] = h[q] * inv;        // any positive scale will do: the marginal is normalised afterwards
+                    u[q] = e[q] * bs[q];
+                }
+                float ss = bs[0];
+#pragma unroll
+                for (int q = 1; q < NQ; ++q) ss += bs[q];
+                const float ic = __builtin_amdgcn_rcpf(row_allsum(ss));
+                float acc[NQ][4];
+#pragma unroll
+                for (int q = 0; q < NQ; ++q) acc[q][0] = acc[q][1] = acc[q][2] = acc[q][3] = 0.0f;
+                row_matvec_terms<NQ, 0, 0>(u, a, acc);
+                if (active) {
+#pragma unroll
+                    for (int q = 0; q < NQ; ++q) {
+                        if (16 * q + l < Dr) op[16 * q + l] = bs[q];
+                        if (t > 0) h[q] = (acc[q][0] + acc[q][1]) + (acc[q][2] + acc[q][3]);
+                    }
+                    op += stride;
+                    inv = ic;
+                }
+            }
+        }
+    }
+    if (!backward && cc.nsteps > 0 && l == 0) part[chunk] = (double)msum + (double)lsum;
+}
+
+// ---------------------------------------------------------------------------------------------
 // p(x_k) = f_k b_k / Z_k.  Four consecutive states per lane; a row is reduced inside a wave.
 __global__ __launch_bounds__(256) void ld_combine_kernel(const float* __restrict__ F, const float* __restrict__ Bv,
                                                          long long rows, int Dr, float* __restrict__ marg) {
@@ -809,8 +980,14 @@ static int large_smooth_impl(const LargeArgs& a, float* marg, float* filt, doubl
         launch("ld_carry", ld_carry_kernel<D>, dim3(2u * (unsigned)a.batch), block, st, a.prior, a.D, p.cps,
                a.shared_model, agg, aggT, exps, fin, bout);
     const int half = (int)((p.nchunks + C::VCPW - 1) / C::VCPW);
-    launch("ld_apply", ld_apply_kernel<D>, dim3(2u * (unsigned)half), block, st, a.prior, a.A, a.ll, rowmax, a.T, a.D,
-           p.Lc, p.cps, p.nchunks, a.shared_model, fin, bout, F, Bv, part, half);
+    if constexpr (D <= 32) {
+        const int rhalf = (int)((p.nchunks + 15) / 16);
+        launch("ld_apply", ld_apply_row_kernel<D>, dim3(2u * (unsigned)rhalf), block, st, a.prior, a.A, a.ll, rowmax, a.T,
+               a.D, p.Lc, p.cps, p.nchunks, a.shared_model, fin, bout, F, Bv, part, rhalf);
+    } else {
+        launch("ld_apply", ld_apply_kernel<D>, dim3(2u * (unsigned)half), block, st, a.prior, a.A, a.ll, rowmax, a.T, a.D,
+               p.Lc, p.cps, p.nchunks, a.shared_model, fin, bout, F, Bv, part, half);
+    }
     const int lpr = (a.D + 3) / 4;
     int width = 1;
     while (width < lpr) width <<= 1;
