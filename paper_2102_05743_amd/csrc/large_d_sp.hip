@@ -202,6 +202,119 @@ __global__ __launch_bounds__(256) void ld_aggregate_kernel(const float* __restri
 }
 
 // ---------------------------------------------------------------------------------------------
+// Second level of the scan: the aggregate of a group of consecutive chunks, X = P_c0 P_c0+1 ... ,
+// so that the carries of a long sequence need about 2 sqrt(chunks) sequential hops instead of one
+// per chunk.  Same scheme as the chunk aggregates, X^T <- P_c^T X^T with X^T fed back from the
+// accumulators, except that the first operand changes with every hop: P_c is brought into LDS in
+// first-operand order (from its transposed copy, whose rows hold the reduction index contiguously),
+// its strips reconciled to one scale on the way.  Output in the same format as the chunk aggregates.
+template <int D>
+__global__ __launch_bounds__(256) void ld_product_kernel(const float* __restrict__ aggT, const int* __restrict__ exps,
+                                                         int cps, int g, int G, long long ngroups,
+                                                         float* __restrict__ gagg, float* __restrict__ gaggT,
+                                                         int* __restrict__ gexps) {
+    using C = LargeCfg<D>;
+    using Acc = typename AccT<C::TS>::type;
+    __shared__ __align__(16) float at_all[C::CPW * C::AT_FLOATS];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int cl = wave / C::WPC, strip = wave % C::WPC;
+    const int tic = threadIdx.x - cl * C::WPC * 64;   // lane index inside the group's waves
+    const int gl = lane / C::TS;
+    const long long gidx = (long long)blockIdx.x * C::CPW + cl;
+    const bool live = gidx < ngroups;
+    const int seq = live ? (int)(gidx / G) : 0, grp = live ? (int)(gidx % G) : 0;
+    const int c0 = grp * g;
+    const int nh = live ? min(cps, c0 + g) - c0 : 0;
+    float* at = at_all + cl * C::AT_FLOATS;
+    Acc acc[C::MT];
+    const int ncol = C::TS * strip + lane % C::TS;
+#pragma unroll
+    for (int mt = 0; mt < C::MT; ++mt)
+#pragma unroll
+        for (int r = 0; r < C::NACC; ++r) acc[mt][r] = (mfma_row<D>(mt, r, gl) == ncol) ? 1.0f : 0.0f;
+    int exsum = 0;
+    auto rescale = [&]() -> float {
+        float m = 0.0f;
+#pragma unroll
+        for (int mt = 0; mt < C::MT; ++mt)
+#pragma unroll
+            for (int r = 0; r < C::NACC; ++r) m = fmaxf(m, acc[mt][r]);
+        m = wave_max(m);
+        const int ex = __builtin_amdgcn_frexp_expf(m);
+        const float sc = ldexpf(1.0f, -ex);
+#pragma unroll
+        for (int mt = 0; mt < C::MT; ++mt)
+#pragma unroll
+            for (int r = 0; r < C::NACC; ++r) acc[mt][r] *= sc;
+        exsum += ex;
+        return m;
+    };
+    const float* arow = at + lane * C::ASTR;
+    for (int hop = 0; hop < g; ++hop) {     // every wave runs g hops (barriers inside); idle hops do nothing else
+        const bool active = hop < nh;
+        __syncthreads();                    // the previous hop's reads of the operand are done
+        if (active) {
+            const float* MT_ = aggT + ((size_t)seq * cps + c0 + hop) * D * D;   // P^T[m][k]
+            const int* ex = exps + ((size_t)seq * cps + c0 + hop) * C::WPC;
+            int exv[C::WPC];
+            int exmax = ex[0];
+#pragma unroll
+            for (int w = 0; w < C::WPC; ++w) { exv[w] = ex[w]; exmax = max(exmax, exv[w]); }
+            // at[(mo*64 + l)*ASTR + s] = P(k, m) 2^(ex[strip of k] - exmax), k = mfma_row(s), m = TS*mo + l % TS,
+            // four consecutive s (= four consecutive k) per access
+            for (int idx = tic; idx < C::MT * 64 * (C::NS / 4); idx += C::WPC * 64) {
+                const int s4 = idx % (C::NS / 4), l = (idx / (C::NS / 4)) % 64, mo = idx / ((C::NS / 4) * 64);
+                const int s = 4 * s4;
+                const int k = mfma_row<D>(s / C::NACC, s % C::NACC, l / C::TS);
+                const int m = C::TS * mo + l % C::TS;
+                float4 x = *reinterpret_cast<const float4*>(MT_ + (size_t)m * D + k);
+                int ek = exv[0];
+#pragma unroll
+                for (int w = 1; w < C::WPC; ++w) ek = (k / C::TS == w) ? exv[w] : ek;
+                const float sc = ldexpf(1.0f, max(ek - exmax, -126));
+                x.x *= sc; x.y *= sc; x.z *= sc; x.w *= sc;
+                *reinterpret_cast<float4*>(at + (mo * 64 + l) * C::ASTR + s) = x;
+            }
+        }
+        __syncthreads();
+        if (active) {
+            Acc nw[C::MT];
+#pragma unroll
+            for (int mo = 0; mo < C::MT; ++mo) {
+#pragma unroll
+                for (int r = 0; r < C::NACC; ++r) nw[mo][r] = 0.0f;
+#pragma unroll
+                for (int s4 = 0; s4 < C::NS; s4 += 4) {
+                    const float4 a4 = *reinterpret_cast<const float4*>(arow + mo * 64 * C::ASTR + s4);
+                    nw[mo] = mfma_step<C::TS>(a4.x, acc[(s4 + 0) / C::NACC][(s4 + 0) % C::NACC], nw[mo]);
+                    nw[mo] = mfma_step<C::TS>(a4.y, acc[(s4 + 1) / C::NACC][(s4 + 1) % C::NACC], nw[mo]);
+                    nw[mo] = mfma_step<C::TS>(a4.z, acc[(s4 + 2) / C::NACC][(s4 + 2) % C::NACC], nw[mo]);
+                    nw[mo] = mfma_step<C::TS>(a4.w, acc[(s4 + 3) / C::NACC][(s4 + 3) % C::NACC], nw[mo]);
+                }
+            }
+#pragma unroll
+            for (int mo = 0; mo < C::MT; ++mo) acc[mo] = nw[mo];
+            rescale();
+        }
+    }
+    if (nh > 0) {
+        if (rescale() == 0.0f) exsum = ZERO_STRIP_EXP;
+        float* dst = gagg + (size_t)gidx * D * D;     // X[n][k]
+        float* dstT = gaggT + (size_t)gidx * D * D;   // X^T[k][n]
+#pragma unroll
+        for (int mt = 0; mt < C::MT; ++mt) {
+#pragma unroll
+            for (int q = 0; q < C::NACC / 4; ++q)
+                *reinterpret_cast<float4*>(dst + (size_t)ncol * D + mfma_row<D>(mt, 4 * q, gl)) =
+                    make_float4(acc[mt][4 * q], acc[mt][4 * q + 1], acc[mt][4 * q + 2], acc[mt][4 * q + 3]);
+#pragma unroll
+            for (int r = 0; r < C::NACC; ++r) dstT[(size_t)mfma_row<D>(mt, r, gl) * D + ncol] = acc[mt][r];
+        }
+        if (lane == 0) gexps[gidx * C::WPC + strip] = exsum;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // Carries between the chunks of a sequence.  blockIdx = 2*seq + dir; dir 0 walks the chunks left
 // to right with v <- v P_c (matrix = agg), dir 1 right to left with v <- P_c v (matrix = aggT,
 // read row by row so that both directions stream memory the same way).  Strips of an aggregate
@@ -210,7 +323,13 @@ template <int D>
 __global__ __launch_bounds__(256) void ld_carry_kernel(const float* __restrict__ prior, int Dr, int cps,
                                                        int shared_model, const float* __restrict__ agg,
                                                        const float* __restrict__ aggT, const int* __restrict__ exps,
-                                                       float* __restrict__ fin, float* __restrict__ bout) {
+                                                       float* __restrict__ fin, float* __restrict__ bout,
+                                                       int seglen, int nseg, const float* __restrict__ start_f,
+                                                       const float* __restrict__ start_b) {
+    // The chunks of a sequence may be cut into nseg segments of seglen chunks that are walked
+    // independently (blockIdx = 2*(seq*nseg + seg) + dir), each from its own start vector: the
+    // forward potential before the segment (start_f) or the backward potential at its last step
+    // (start_b).  Without start vectors (nseg = 1) the walk starts from the prior / the ones vector.
     using C = LargeCfg<D>;
     constexpr int CG = D / 4;                                   // groups of four columns
     constexpr int RP = (256 / CG < D) ? 256 / CG : D;           // lane groups splitting the summation
@@ -218,7 +337,10 @@ __global__ __launch_bounds__(256) void ld_carry_kernel(const float* __restrict__
     __shared__ __align__(16) float vec[D];                      // current vector (pre-scaled for dir 0)
     __shared__ __align__(16) float partial[RP * D];
     __shared__ float wmx[4];
-    const int seq = blockIdx.x >> 1, dir = blockIdx.x & 1;
+    const int unit = blockIdx.x >> 1, dir = blockIdx.x & 1;
+    const int seq = unit / nseg, seg = unit % nseg;
+    const int c_begin = seg * seglen, c_end = min(cps, c_begin + seglen);
+    const int nhops = c_end - c_begin;
     const int tid = threadIdx.x;
     const bool worker = tid < CG * RP;
     const int cg = tid % CG, rp = tid / CG;
@@ -228,8 +350,13 @@ __global__ __launch_bounds__(256) void ld_carry_kernel(const float* __restrict__
     float* out = (dir == 0 ? fin : bout) + (size_t)seq * cps * D;
     float v = 0.0f;
     if (j < D) {
-        if (dir == 0) v = (j < Dr) ? prior[(shared_model ? 0 : (size_t)seq * Dr) + j] : 0.0f;
-        else v = (j < Dr) ? 1.0f : 0.0f;
+        if (dir == 0) {
+            if (start_f != nullptr) v = start_f[(size_t)unit * D + j];
+            else v = (j < Dr) ? prior[(shared_model ? 0 : (size_t)seq * Dr) + j] : 0.0f;
+        } else {
+            if (start_b != nullptr) v = start_b[(size_t)unit * D + j];
+            else v = (j < Dr) ? 1.0f : 0.0f;
+        }
     }
     float4 pm[RPT];
     int exn[C::WPC];
@@ -249,9 +376,9 @@ __global__ __launch_bounds__(256) void ld_carry_kernel(const float* __restrict__
         for (int s = 1; s < C::WPC; ++s) r = (st == s) ? e[s] : r;
         return r;
     };
-    int c = dir == 0 ? 0 : cps - 1;
+    int c = dir == 0 ? c_begin : c_end - 1;
     load_mat(c);
-    for (int it = 0; it < cps; ++it) {
+    for (int it = 0; it < nhops; ++it) {
         int exc[C::WPC];
         int exmax = exn[0];
 #pragma unroll
@@ -274,7 +401,7 @@ __global__ __launch_bounds__(256) void ld_carry_kernel(const float* __restrict__
             }
         }
         const int cn = dir == 0 ? c + 1 : c - 1;
-        if (it + 1 < cps) load_mat(cn);   // the next aggregate streams in while this one is reduced
+        if (it + 1 < nhops) load_mat(cn);   // the next aggregate streams in while this one is reduced
         if (worker) *reinterpret_cast<float4*>(partial + rp * D + 4 * cg) = acc;
         lds_barrier();
         float g = 0.0f;
@@ -306,14 +433,19 @@ __global__ __launch_bounds__(64) void ld_carry_wave_kernel(const float* __restri
                                                            int shared_model, const float* __restrict__ agg,
                                                            const float* __restrict__ aggT,
                                                            const int* __restrict__ exps, float* __restrict__ fin,
-                                                           float* __restrict__ bout) {
+                                                           float* __restrict__ bout, int seglen, int nseg,
+                                                           const float* __restrict__ start_f,
+                                                           const float* __restrict__ start_b) {
     using C = LargeCfg<D>;
     static_assert(D <= 32, "one wave covers the columns");
     constexpr int PARTS = 64 / D;       // 2 or 4 lanes per column
     constexpr int RPT = D / PARTS;      // summation terms per lane
     constexpr int PF = 8;               // prefetch distance in hops
     __shared__ __align__(16) float vec[D];
-    const int seq = blockIdx.x >> 1, dir = blockIdx.x & 1;
+    const int unit = blockIdx.x >> 1, dir = blockIdx.x & 1;   // segments as in ld_carry_kernel
+    const int seq = unit / nseg, seg = unit % nseg;
+    const int c_begin = seg * seglen, c_end = min(cps, c_begin + seglen);
+    const int nhops = c_end - c_begin;
     const int lane = threadIdx.x;
     const int h = lane % PARTS, j = lane / PARTS;
     // the lane's terms M(h*RPT + r, j) are contiguous in the transposed copy: 16-byte loads
@@ -321,18 +453,23 @@ __global__ __launch_bounds__(64) void ld_carry_wave_kernel(const float* __restri
     const int* ex = exps + (size_t)seq * cps * C::WPC;
     float* out = (dir == 0 ? fin : bout) + (size_t)seq * cps * D;
     float v;
-    if (dir == 0) v = (j < Dr) ? prior[(shared_model ? 0 : (size_t)seq * Dr) + j] : 0.0f;
-    else v = (j < Dr) ? 1.0f : 0.0f;
+    if (dir == 0) {
+        if (start_f != nullptr) v = start_f[(size_t)unit * D + j];
+        else v = (j < Dr) ? prior[(shared_model ? 0 : (size_t)seq * Dr) + j] : 0.0f;
+    } else {
+        if (start_b != nullptr) v = start_b[(size_t)unit * D + j];
+        else v = (j < Dr) ? 1.0f : 0.0f;
+    }
     settle_loaded(v);
     float pm[PF][RPT];
     int exn[PF][C::WPC];
-    auto chunk_of = [&](int it) { return dir == 0 ? it : cps - 1 - it; };
+    auto chunk_of = [&](int it) { return dir == 0 ? c_begin + it : c_end - 1 - it; };
     // Loads are unconditional (the hop index is clamped) and the exponents come through vector loads:
     // the compiler can then count outstanding loads exactly and wait only for the slot it needs,
     // where a conditional or scalar load would make every hop wait for the newest prefetch.
     const int lane_zero = __builtin_amdgcn_mbcnt_lo(0u, 0u);   // 0, but not known to be uniform
     auto load_mat = [&](int it, float (&m)[RPT], int (&e)[C::WPC]) {
-        const int c = chunk_of(it < cps ? it : cps - 1);
+        const int c = chunk_of(it < nhops ? it : nhops - 1);
         const float* M = mats + (size_t)c * D * D + (size_t)j * D + h * RPT;
 #pragma unroll
         for (int r4 = 0; r4 < RPT; r4 += 4) {
@@ -377,7 +514,7 @@ __global__ __launch_bounds__(64) void ld_carry_wave_kernel(const float* __restri
     };
 #pragma unroll
     for (int p = 0; p < PF; ++p) load_mat(p, pm[p], exn[p]);
-    const int nfull = cps / PF * PF;
+    const int nfull = nhops / PF * PF;
     for (int it0 = 0; it0 < nfull; it0 += PF) {
 #pragma unroll
         for (int p = 0; p < PF; ++p) {
@@ -387,7 +524,7 @@ __global__ __launch_bounds__(64) void ld_carry_wave_kernel(const float* __restri
     }
 #pragma unroll
     for (int p = 0; p < PF; ++p)
-        if (nfull + p < cps) hop(nfull + p, pm[p], exn[p]);   // slot p holds hop nfull + p
+        if (nfull + p < nhops) hop(nfull + p, pm[p], exn[p]);   // slot p holds hop nfull + p
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -921,11 +1058,45 @@ LargePlan large_plan(int Dr, long long T, int batch) {
     return p;
 }
 
-struct LargeSmoothWs { size_t rowmax, agg, aggT, exps, fin, bout, F, Bv, part, total; };
+// Plan of the smoother: chunks of at most 256 (D >= 64) or 128 steps, so that a long sequence gets
+// more chunks rather than longer ones, and above 96 chunks per sequence a second scan level: groups
+// of g chunks whose aggregates are formed by ld_product.  With a product hop costing about 8.4
+// (D >= 64) or 5.4 (D <= 32) vector hops, g + chunks/g vector hops and g product hops are fewest in
+// total near g = sqrt(0.106 chunks) resp. sqrt(0.156 chunks).
+struct SmoothPlan { int DP, Lc, cps; long long nchunks; int g, G; bool two_level; };
+
+static SmoothPlan smooth_plan(int Dr, long long T, int batch) {
+    SmoothPlan p;
+    p.DP = Dr <= 16 ? 16 : Dr <= 32 ? 32 : Dr <= 64 ? 64 : 128;
+    const long long target = p.DP >= 128 ? 256 : p.DP >= 64 ? 512 : p.DP >= 32 ? 2048 : 8192;
+    long long cps = (target + batch - 1) / batch;
+    if (cps < 1) cps = 1;
+    const long long lmax = p.DP >= 64 ? 256 : 128;
+    long long Lc = (T + cps - 1) / cps;
+    Lc = (Lc + 15) / 16 * 16;
+    if (Lc < 32) Lc = 32;
+    if (Lc > lmax) Lc = lmax;
+    p.Lc = (int)Lc;
+    p.cps = (int)((T + p.Lc - 1) / p.Lc);
+    p.nchunks = (long long)p.cps * batch;
+    p.two_level = p.cps > 96;
+    if (p.two_level) {
+        int g = (int)sqrt((p.DP >= 64 ? 0.106 : 0.156) * (double)p.cps);
+        p.g = g < 2 ? 2 : g;
+        p.G = (p.cps + p.g - 1) / p.g;
+    } else {
+        p.g = p.cps;
+        p.G = 1;
+    }
+    return p;
+}
+
+struct LargeSmoothWs { size_t rowmax, agg, aggT, exps, fin, bout, gagg, gaggT, gexps, gfin, gbout, F, Bv, part, total; };
 
 static LargeSmoothWs large_smooth_ws(int Dr, long long T, int batch, bool own_F) {
-    const LargePlan p = large_plan(Dr, T, batch);
+    const SmoothPlan p = smooth_plan(Dr, T, batch);
     const size_t D = p.DP, nc = (size_t)p.nchunks, rows = (size_t)T * batch;
+    const size_t ng = p.two_level ? (size_t)p.G * batch : 0;
     LargeSmoothWs w;
     size_t o = 0;
     w.rowmax = o; o = align_up(o + rows * sizeof(float), 256);
@@ -934,6 +1105,11 @@ static LargeSmoothWs large_smooth_ws(int Dr, long long T, int batch, bool own_F)
     w.exps = o;   o = align_up(o + nc * 8 * sizeof(int), 256);
     w.fin = o;    o = align_up(o + nc * D * sizeof(float), 256);
     w.bout = o;   o = align_up(o + nc * D * sizeof(float), 256);
+    w.gagg = o;   o = align_up(o + ng * D * D * sizeof(float), 256);
+    w.gaggT = o;  o = align_up(o + ng * D * D * sizeof(float), 256);
+    w.gexps = o;  o = align_up(o + ng * 8 * sizeof(int), 256);
+    w.gfin = o;   o = align_up(o + ng * D * sizeof(float), 256);
+    w.gbout = o;  o = align_up(o + ng * D * sizeof(float), 256);
     w.F = o;      o = align_up(o + (own_F ? rows * Dr * sizeof(float) : 0), 256);
     w.Bv = o;     o = align_up(o + rows * Dr * sizeof(float), 256);
     w.part = o;   o = align_up(o + nc * sizeof(double), 256);
@@ -946,13 +1122,26 @@ size_t large_d_smooth_ws_bytes(int Dr, long long T, int batch) {
 }
 
 template <int D>
+static void launch_carry(hipStream_t st, const LargeArgs& a, int cps, const float* agg, const float* aggT,
+                         const int* exps, float* fin, float* bout, int seglen, int nseg, const float* start_f,
+                         const float* start_b) {
+    const unsigned blocks = 2u * (unsigned)a.batch * (unsigned)nseg;
+    if constexpr (D <= 32)
+        launch("ld_carry", ld_carry_wave_kernel<D>, dim3(blocks), dim3(64), st, a.prior, a.D, cps, a.shared_model, agg,
+               aggT, exps, fin, bout, seglen, nseg, start_f, start_b);
+    else
+        launch("ld_carry", ld_carry_kernel<D>, dim3(blocks), dim3(256), st, a.prior, a.D, cps, a.shared_model, agg, aggT,
+               exps, fin, bout, seglen, nseg, start_f, start_b);
+}
+
+template <int D>
 static int large_smooth_impl(const LargeArgs& a, float* marg, float* filt, double* loglik_out) {
     using C = LargeCfg<D>;
-    const LargePlan p = large_plan(a.D, a.T, a.batch);
+    const SmoothPlan p = smooth_plan(a.D, a.T, a.batch);
     const LargeSmoothWs w = large_smooth_ws(a.D, a.T, a.batch, true);
     if (a.ws_bytes < w.total) return 3;
     const long long rows = a.T * a.batch;
-    if (rows > 0x7fffffffLL * 4 || p.nchunks > 0x7fffffffLL) return 2;
+    if (rows > 0x7fffffffLL * 4 || p.nchunks > 0x3fffffffLL) return 2;
     char* ws = static_cast<char*>(a.ws);
     float* rowmax = reinterpret_cast<float*>(ws + w.rowmax);
     float* agg = reinterpret_cast<float*>(ws + w.agg);
@@ -960,6 +1149,11 @@ static int large_smooth_impl(const LargeArgs& a, float* marg, float* filt, doubl
     int* exps = reinterpret_cast<int*>(ws + w.exps);
     float* fin = reinterpret_cast<float*>(ws + w.fin);
     float* bout = reinterpret_cast<float*>(ws + w.bout);
+    float* gagg = reinterpret_cast<float*>(ws + w.gagg);
+    float* gaggT = reinterpret_cast<float*>(ws + w.gaggT);
+    int* gexps = reinterpret_cast<int*>(ws + w.gexps);
+    float* gfin = reinterpret_cast<float*>(ws + w.gfin);
+    float* gbout = reinterpret_cast<float*>(ws + w.gbout);
     float* F = filt ? filt : reinterpret_cast<float*>(ws + w.F);
     float* Bv = reinterpret_cast<float*>(ws + w.Bv);
     double* part = reinterpret_cast<double*>(ws + w.part);
@@ -973,12 +1167,16 @@ static int large_smooth_impl(const LargeArgs& a, float* marg, float* filt, doubl
     }
     launch("ld_aggregate", ld_aggregate_kernel<D>, dim3((unsigned)((p.nchunks + C::CPW - 1) / C::CPW)), block, st, a.A,
            a.ll, rowmax, a.T, a.D, p.Lc, p.cps, p.nchunks, a.shared_model, agg, aggT, exps);
-    if constexpr (D <= 32)
-        launch("ld_carry", ld_carry_wave_kernel<D>, dim3(2u * (unsigned)a.batch), dim3(64), st, a.prior, a.D, p.cps,
-               a.shared_model, agg, aggT, exps, fin, bout);
-    else
-        launch("ld_carry", ld_carry_kernel<D>, dim3(2u * (unsigned)a.batch), block, st, a.prior, a.D, p.cps,
-               a.shared_model, agg, aggT, exps, fin, bout);
+    if (p.two_level) {
+        const long long ngroups = (long long)p.G * a.batch;
+        launch("ld_product", ld_product_kernel<D>, dim3((unsigned)((ngroups + C::CPW - 1) / C::CPW)), block, st,
+               (const float*)aggT, (const int*)exps, p.cps, p.g, p.G, ngroups, gagg, gaggT, gexps);
+        // carries at the group boundaries, then inside every group from those
+        launch_carry<D>(st, a, p.G, gagg, gaggT, gexps, gfin, gbout, p.G, 1, nullptr, nullptr);
+        launch_carry<D>(st, a, p.cps, agg, aggT, exps, fin, bout, p.g, p.G, gfin, gbout);
+    } else {
+        launch_carry<D>(st, a, p.cps, agg, aggT, exps, fin, bout, p.cps, 1, nullptr, nullptr);
+    }
     const int half = (int)((p.nchunks + C::VCPW - 1) / C::VCPW);
     if constexpr (D <= 32) {
         const int rhalf = (int)((p.nchunks + 15) / 16);
