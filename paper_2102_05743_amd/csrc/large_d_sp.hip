@@ -1058,8 +1058,9 @@ LargePlan large_plan(int Dr, long long T, int batch) {
     return p;
 }
 
-// Plan of the smoother: chunks of at most 256 (D >= 64) or 128 steps, so that a long sequence gets
-// more chunks rather than longer ones, and above 96 chunks per sequence a second scan level: groups
+// Plan of the smoother: enough chunks for two workgroups per compute unit at D >= 64 (the in-chunk
+// recursions are latency-bound, so shorter chunks pay as long as the carries stay cheap), chunks of at
+// most 256 (D >= 64) or 128 steps, so that a long sequence gets more chunks rather than longer ones, and above 96 chunks per sequence a second scan level: groups
 // of g chunks whose aggregates are formed by ld_product.  With a product hop costing about 8.4
 // (D >= 64) or 5.4 (D <= 32) vector hops, g + chunks/g vector hops and g product hops are fewest in
 // total near g = sqrt(0.106 chunks) resp. sqrt(0.156 chunks).
@@ -1068,7 +1069,7 @@ struct SmoothPlan { int DP, Lc, cps; long long nchunks; int g, G; bool two_level
 static SmoothPlan smooth_plan(int Dr, long long T, int batch) {
     SmoothPlan p;
     p.DP = Dr <= 16 ? 16 : Dr <= 32 ? 32 : Dr <= 64 ? 64 : 128;
-    const long long target = p.DP >= 128 ? 256 : p.DP >= 64 ? 512 : p.DP >= 32 ? 2048 : 8192;
+    const long long target = p.DP >= 128 ? 512 : p.DP >= 64 ? 1024 : p.DP >= 32 ? 2048 : 8192;
     long long cps = (target + batch - 1) / batch;
     if (cps < 1) cps = 1;
     const long long lmax = p.DP >= 64 ? 256 : 128;
