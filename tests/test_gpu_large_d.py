@@ -87,6 +87,16 @@ def test_first_observation_excludes_a_block_of_states(gu, D, T):
     gu.check_transition_counts(p, label=f"excluded block D={D}")
 
 
+@pytest.mark.parametrize("D,T,B,shared", [(16, 200000, 1, True), (24, 100001, 1, True), (64, 50000, 1, True),
+                                          (32, 40000, 3, False), (100, 30000, 2, True)])
+def test_long_sequences_use_the_second_scan_level(gu, D, T, B, shared):
+    """Long enough for hundreds to thousands of chunks per sequence: the smoother then forms aggregates
+    of groups of chunks and runs its carries on two levels (ragged last group, several sequences)."""
+    p = wl.random_problem(D, T, batch=B, shared_model=shared, seed=31 * D + B)
+    gu.check_smooth(p, want_filtered=True, label=f"two-level D={D} T={T} B={B}")
+    gu.check_viterbi(p, label=f"two-level D={D} T={T} B={B}")
+
+
 # ---- the configurations at their full sizes, element by element against the oracle ----
 def test_config3_full_size(gu):
     p = wl.config3()
