@@ -49,6 +49,10 @@ def _load():
         lib.hmm_oracle_max_product.restype = ctypes.c_int
         lib.hmm_oracle_transition_counts.argtypes = [fp, fp, fp, ctypes.c_long, ctypes.c_int, dp]
         lib.hmm_oracle_transition_counts.restype = ctypes.c_int
+        lib.hmm_oracle_block_element.argtypes = [fp, fp, ctypes.c_long, ctypes.c_int, ctypes.c_int, dp, dp]
+        lib.hmm_oracle_block_element.restype = ctypes.c_int
+        lib.hmm_oracle_block_carries.argtypes = [fp, fp, fp, dp, ctypes.c_int, ctypes.c_int, ctypes.c_int, dp, dp, dp]
+        lib.hmm_oracle_block_carries.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -140,6 +144,48 @@ def transition_counts(prior, A, loglik):
     if rc != 0:
         raise RuntimeError("hmm_oracle_transition_counts failed")
     return counts
+
+
+def block_element(A, loglik, max_product: bool = False):
+    """Element of a block of consecutive steps (Sec. V-B): W(i,j) = joint weight of the block's
+    observations and its last state j given its first state i (sum or max over the states between).
+    Returns (element[D][D] f64, log_scale f64): sum-product element = W / max W, log_scale = log max W;
+    max-product element = log W - max, log_scale = max log W."""
+    lib = _load()
+    A, pa = _f32(A)
+    loglik, pl = _f32(loglik)
+    T, D = loglik.shape
+    assert A.shape == (D, D)
+    el = np.empty((D, D), dtype=np.float64)
+    ls = ctypes.c_double(0.0)
+    rc = lib.hmm_oracle_block_element(pa, pl, T, D, 1 if max_product else 0,
+                                      el.ctypes.data_as(ctypes.POINTER(ctypes.c_double)), ctypes.byref(ls))
+    if rc != 0:
+        raise RuntimeError("hmm_oracle_block_element failed")
+    return el, float(ls.value)
+
+
+def block_carries(prior, A, elements, log_scales, max_product: bool = False):
+    """Carries between the S blocks of one sequence from their elements (float32 elements[S][D][D],
+    float64 log_scales[S]).  Returns (carry_rows[S][D], lookahead_rows[S][D], total): the
+    log-domain pseudo-observation rows to put in front of / behind each block, and log Z
+    (sum-product) or the log of the largest joint weight (max-product)."""
+    lib = _load()
+    prior, pp = _f32(prior)
+    A, pa = _f32(A)
+    elements, pe = _f32(elements)
+    S, D, _ = elements.shape
+    log_scales = np.ascontiguousarray(log_scales, dtype=np.float64)
+    assert prior.shape == (D,) and A.shape == (D, D) and log_scales.shape == (S,)
+    cr = np.empty((S, D), dtype=np.float64)
+    lr = np.empty((S, D), dtype=np.float64)
+    tot = ctypes.c_double(0.0)
+    dp = ctypes.POINTER(ctypes.c_double)
+    rc = lib.hmm_oracle_block_carries(pp, pa, pe, log_scales.ctypes.data_as(dp), S, D, 1 if max_product else 0,
+                                      cr.ctypes.data_as(dp), lr.ctypes.data_as(dp), ctypes.byref(tot))
+    if rc != 0:
+        raise RuntimeError("hmm_oracle_block_carries failed")
+    return cr, lr, float(tot.value)
 
 
 def transition_counts_batch(prior, A, loglik, shared_model: bool):

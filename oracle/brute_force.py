@@ -76,3 +76,17 @@ def transition_counts(prior, A, loglik):
     for k in range(1, T):
         np.add.at(out, (seqs[:, k - 1], seqs[:, k]), w / Z)
     return out
+
+
+def block_element(A, loglik, max_product=False):
+    """Element of a block of consecutive steps (Sec. V-B) from the definition: W(i, j) = the sum (or
+    the maximum) over all state sequences of the block with first state i and last state j of
+    e_1(x_1) prod_{k>=2} A(x_{k-1}, x_k) e_k(x_k) -- no transition into the first step."""
+    D = np.asarray(A).shape[0]
+    seqs, w = enumerate_weights(np.ones(D), A, loglik)
+    W = np.zeros((D, D))
+    for i in range(D):
+        for j in range(D):
+            sel = w[(seqs[:, 0] == i) & (seqs[:, -1] == j)]
+            W[i, j] = (sel.max() if sel.size else 0.0) if max_product else sel.sum()
+    return W

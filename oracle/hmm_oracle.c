@@ -288,3 +288,159 @@ int hmm_oracle_transition_counts(const float *prior, const float *A, const float
     free(f); free(b); free(bn); free(g); free(xi);
     return 0;
 }
+
+/*
+ * Block-wise element (Sec. V-B: a block of consecutive observations and states taken as ONE element
+ * of the scan).  For a block with log-likelihood rows ll[0..T-1] its element is, by Definition 3
+ * (sum-product) or Definition 5 (max-product) applied to the block's own per-step elements,
+ *   W(i, j) = sum / max over x_2..x_{T-1} of  e_1(i) prod_{k=2..T} A(x_{k-1}, x_k) e_k(x_k),
+ *   x_1 = i, x_T = j, e_k(x) = exp(ll[k-1][x]),
+ * the joint weight of the block's observations and its last state given its first state (T = 1:
+ * diag(e_1)).  There is no transition into the block's first step: two adjacent blocks combine as
+ * W_a (x) A (x) W_b.  Written out as the plain left-to-right product, rescaled every step:
+ *   sum-product:  element = W / max W,      *log_scale = log max W   (element 0, -inf if W = 0)
+ *   max-product:  element = log W - max,    *log_scale = max log W
+ * element[D][D]; returns 0, or 1 on allocation failure / bad sizes.
+ */
+int hmm_oracle_block_element(const float *A, const float *ll, long T, int D, int max_product,
+                             double *element, double *log_scale)
+{
+    if (T < 1 || D < 1) return 1;
+    const size_t n = (size_t)D * D;
+    double *X = (double *)malloc(sizeof(double) * n);
+    double *Y = (double *)malloc(sizeof(double) * n);
+    double *M = (double *)malloc(sizeof(double) * n);
+    if (!X || !Y || !M) { free(X); free(Y); free(M); return 1; }
+    double ls = 0.0;
+    if (max_product) {
+        for (size_t e = 0; e < n; ++e) M[e] = log_or_neginf((double)A[e]);
+        for (int i = 0; i < D; ++i)
+            for (int j = 0; j < D; ++j) X[(size_t)i * D + j] = (i == j) ? (double)ll[j] : -INFINITY;
+    } else {
+        for (size_t e = 0; e < n; ++e) M[e] = (double)A[e];
+        for (int i = 0; i < D; ++i)
+            for (int j = 0; j < D; ++j) X[(size_t)i * D + j] = (i == j) ? exp((double)ll[j]) : 0.0;
+    }
+    for (long k = 0; k < T; ++k) {
+        if (k > 0) {
+            const float *llk = ll + (size_t)k * D;
+            for (int i = 0; i < D; ++i)
+                for (int j = 0; j < D; ++j) {
+                    double acc = max_product ? -INFINITY : 0.0;
+                    for (int h = 0; h < D; ++h) {
+                        if (max_product) {
+                            double v = X[(size_t)i * D + h] + M[(size_t)h * D + j];
+                            if (v > acc) acc = v;
+                        } else {
+                            acc += X[(size_t)i * D + h] * M[(size_t)h * D + j];
+                        }
+                    }
+                    Y[(size_t)i * D + j] = max_product ? acc + (double)llk[j] : acc * exp((double)llk[j]);
+                }
+            double *t = X; X = Y; Y = t;
+        }
+        double m = max_product ? -INFINITY : 0.0;
+        for (size_t e = 0; e < n; ++e) if (X[e] > m) m = X[e];
+        if (max_product) {
+            if (m > -INFINITY) { for (size_t e = 0; e < n; ++e) X[e] -= m; ls += m; }
+            else ls = -INFINITY;
+        } else {
+            if (m > 0.0) { for (size_t e = 0; e < n; ++e) X[e] /= m; ls += log(m); }
+            else ls = -INFINITY;
+        }
+    }
+    for (size_t e = 0; e < n; ++e) element[e] = X[e];
+    *log_scale = ls;
+    free(X); free(Y); free(M);
+    return 0;
+}
+
+/*
+ * Carries between the blocks of one sequence from the blocks' elements (Sec. V-B; Theorems 1-2 and
+ * the lemma of Sec. IV-C at block granularity).  elements[S][D][D] and log_scales[S] are as
+ * returned by hmm_oracle_block_element (given here as float / double, the arrays the GPU path
+ * consumes).  With p_0 = prior, for s = 0..S-1:
+ *     c_s = p_s (x) W_s      forward potential at the last step of block s, scaled to sum to one
+ *                            (sum-product: the filtering distribution) or to maximum zero (max-product)
+ *     p_{s+1} = c_s (x) A    its prediction for the first step of block s+1
+ * and with r_{S-1} = 1 (the neutral backward potential at the sequence's end), for s = S-1..1:
+ *     u_s = W_s (x) r_s      backward potential at the first step of block s INCLUDING that step's
+ *                            emission factor, scaled to maximum one (zero on logarithms)
+ *     r_{s-1} = A (x) u_s    backward potential at the last step of block s-1.
+ * carry_rows[s] = log c_{s-1} for s >= 1 (row 0: log of the prior scaled to maximum one);
+ * lookahead_rows[s] = log u_{s+1} for s <= S-2 (row S-1: zeros).  These are the rows that, put
+ * in front of / behind block s's own log-likelihood rows as one more pseudo-observation each,
+ * make a stand-alone recursion over [carry; block; lookahead] reproduce the whole sequence's
+ * results on the block's steps (with a uniform prior of ones for s >= 1, the true prior for s = 0).
+ * *total = log Z (sum-product) or the log of the largest joint weight (max-product).
+ */
+int hmm_oracle_block_carries(const float *prior, const float *A, const float *elements,
+                             const double *log_scales, int S, int D, int max_product,
+                             double *carry_rows, double *lookahead_rows, double *total)
+{
+    if (S < 1 || D < 1) return 1;
+    double *p = (double *)malloc(sizeof(double) * D);
+    double *c = (double *)malloc(sizeof(double) * D);
+    if (!p || !c) { free(p); free(c); return 1; }
+    double tot = 0.0, pm = 0.0;
+    for (int j = 0; j < D; ++j) if ((double)prior[j] > pm) pm = (double)prior[j];
+    for (int j = 0; j < D; ++j) {
+        p[j] = max_product ? log_or_neginf((double)prior[j]) : (double)prior[j];
+        carry_rows[j] = log_or_neginf((double)prior[j] / pm);
+    }
+    for (int s = 0; s < S; ++s) {
+        const float *W = elements + (size_t)s * D * D;
+        double nrm = max_product ? -INFINITY : 0.0;
+        for (int j = 0; j < D; ++j) {
+            double acc = max_product ? -INFINITY : 0.0;
+            for (int i = 0; i < D; ++i) {
+                if (max_product) { double v = p[i] + (double)W[(size_t)i * D + j]; if (v > acc) acc = v; }
+                else acc += p[i] * (double)W[(size_t)i * D + j];
+            }
+            c[j] = acc;
+            if (max_product) { if (acc > nrm) nrm = acc; } else nrm += acc;
+        }
+        tot += (max_product ? nrm : log(nrm)) + log_scales[s];
+        for (int j = 0; j < D; ++j) c[j] = max_product ? c[j] - nrm : c[j] / nrm;
+        if (s + 1 < S)
+            for (int j = 0; j < D; ++j) carry_rows[(size_t)(s + 1) * D + j] = max_product ? c[j] : log_or_neginf(c[j]);
+        for (int j = 0; j < D; ++j) {
+            double acc = max_product ? -INFINITY : 0.0;
+            for (int i = 0; i < D; ++i) {
+                if (max_product) { double v = c[i] + log_or_neginf((double)A[(size_t)i * D + j]); if (v > acc) acc = v; }
+                else acc += c[i] * (double)A[(size_t)i * D + j];
+            }
+            p[j] = acc;
+        }
+    }
+    *total = tot;
+    /* backward: p holds r_s, c holds u_s */
+    for (int i = 0; i < D; ++i) { p[i] = max_product ? 0.0 : 1.0; lookahead_rows[(size_t)(S - 1) * D + i] = 0.0; }
+    for (int s = S - 1; s >= 1; --s) {
+        const float *W = elements + (size_t)s * D * D;
+        double m = max_product ? -INFINITY : 0.0;
+        for (int i = 0; i < D; ++i) {
+            double acc = max_product ? -INFINITY : 0.0;
+            for (int j = 0; j < D; ++j) {
+                if (max_product) { double v = (double)W[(size_t)i * D + j] + p[j]; if (v > acc) acc = v; }
+                else acc += (double)W[(size_t)i * D + j] * p[j];
+            }
+            c[i] = acc;
+            if (acc > m) m = acc;
+        }
+        for (int i = 0; i < D; ++i) {
+            c[i] = max_product ? c[i] - m : c[i] / m;
+            lookahead_rows[(size_t)(s - 1) * D + i] = max_product ? c[i] : log_or_neginf(c[i]);
+        }
+        for (int i = 0; i < D; ++i) {
+            double acc = max_product ? -INFINITY : 0.0;
+            for (int j = 0; j < D; ++j) {
+                if (max_product) { double v = log_or_neginf((double)A[(size_t)i * D + j]) + c[j]; if (v > acc) acc = v; }
+                else acc += (double)A[(size_t)i * D + j] * c[j];
+            }
+            p[i] = acc;
+        }
+    }
+    free(p); free(c);
+    return 0;
+}
