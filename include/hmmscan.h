@@ -145,6 +145,53 @@ hmm_status hmm_transition_counts(const float* A, const float* filtered, const fl
                                  double* counts,
                                  void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/*
+ * Block-wise processing (Sec. V-B: a block of consecutive observations and states is ONE element of
+ * the scan).  For sequences that are not resident in device memory as a whole, or whose blocks are
+ * processed in different places: every block is reduced to its element, the elements give the
+ * carries between blocks, and each block is then processed on its own with the calls above.
+ *
+ * hmm_block_element: the element of the block with log-likelihood rows loglik[b][0..T-1],
+ *     W(i, j) = sum (max_product = 0; Definition 3) or max (max_product != 0; Definition 5) over the
+ *               states between of  e_1(x_1) prod_{k=2..T} A[x_{k-1}][x_k] e_k(x_k),  x_1 = i, x_T = j,
+ * with e_k(x) = exp(loglik[k-1][x]): the joint weight of the block's observations and its last state
+ * given its first state.  No transition enters the block's first step: adjacent blocks combine as
+ * W_a (x) A (x) W_b.
+ *   element   [batch][D][D]  out: W * exp(-log_scale) with its largest entry in [0.5, 1)  (sum-product),
+ *                                 log W - log_scale with its largest entry 0              (max-product)
+ *   log_scale [batch]        out (fp64); -inf if no state sequence of the block has any weight
+ *   workspace: at least hmm_block_element_workspace_bytes(...), 256-byte aligned
+ * A, loglik, shared_model, hip_stream as for hmm_smooth (loglik 16-byte aligned).
+ *
+ * hmm_block_carries: from the elements of the num_blocks consecutive blocks of each sequence,
+ *   elements   [num_blocks][batch][D][D], log_scales [num_blocks][batch]   (hmm_block_element's outputs, stacked)
+ *   carry_rows     [num_blocks][batch][D]  out: row s (s >= 1) = log of the forward potential at the last
+ *                  step of block s-1 (sum-product: log p(x | y up to there); max-product: V shifted to
+ *                  maximum 0); row 0 = log of the prior scaled to maximum one, for completeness
+ *   lookahead_rows [num_blocks][batch][D]  out: row s (s <= num_blocks-2) = log of the backward potential
+ *                  at the first step of block s+1 including that step's emission factor, shifted to
+ *                  maximum 0; the last row is zero
+ *   total      [batch]  out (fp64): log p(y_{1:T}) (sum-product) / log of the largest joint weight (max-product)
+ * No workspace.  Rows may hold -inf.
+ *
+ * Using the rows: block s of a sequence is processed by hmm_smooth / hmm_viterbi / hmm_max_product on the
+ * rows [carry_rows[s] ; the block's own rows ; lookahead_rows[s]] (no carry row and the true prior for
+ * s = 0, a prior of all ones otherwise; no lookahead row for the last block).  The results on the
+ * block's own steps are then those of the whole sequence: marginals, filtered distributions,
+ * max-marginals, and the MAP path if it is unique (with tied MAP sequences, pass the one-hot row of the
+ * next block's first decoded state as lookahead instead, last block first, to get one consistent
+ * path).  The per-block log-likelihood / log-probability outputs of those calls refer to the framed
+ * rows and are superseded by `total`.
+ */
+hmm_status hmm_block_element_workspace_bytes(int64_t T, int32_t D, int32_t batch, size_t* bytes);
+hmm_status hmm_block_element(const float* A, const float* loglik, int64_t T, int32_t D, int32_t batch,
+                             int32_t shared_model, int32_t max_product,
+                             float* element, double* log_scale,
+                             void* workspace, size_t workspace_bytes, void* hip_stream);
+hmm_status hmm_block_carries(const float* prior, const float* A, const float* elements, const double* log_scales,
+                             int32_t num_blocks, int32_t D, int32_t batch, int32_t shared_model, int32_t max_product,
+                             float* carry_rows, float* lookahead_rows, double* total, void* hip_stream);
+
 /* Static, human-readable name of a status code. */
 const char* hmm_status_string(hmm_status status);
 

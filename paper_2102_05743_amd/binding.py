@@ -16,7 +16,8 @@ HMM_OK = 0
 _lib = None
 
 EXPORTED_SYMBOLS = ("hmm_workspace_bytes", "hmm_smooth", "hmm_viterbi", "hmm_max_product",
-                    "hmm_transition_counts_workspace_bytes", "hmm_transition_counts", "hmm_status_string",
+                    "hmm_transition_counts_workspace_bytes", "hmm_transition_counts",
+                    "hmm_block_element_workspace_bytes", "hmm_block_element", "hmm_block_carries", "hmm_status_string",
                     "hmm_kernel_timing_enable", "hmm_kernel_timing_count", "hmm_kernel_timing_get")
 
 
@@ -54,6 +55,14 @@ def load_library():
         lib.hmm_transition_counts.argtypes = [vp, vp, vp, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                                               vp, vp, sz, vp]
         lib.hmm_transition_counts.restype = ctypes.c_int
+        lib.hmm_block_element_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.POINTER(sz)]
+        lib.hmm_block_element_workspace_bytes.restype = ctypes.c_int
+        lib.hmm_block_element.argtypes = [vp, vp, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                          ctypes.c_int32, vp, vp, vp, sz, vp]
+        lib.hmm_block_element.restype = ctypes.c_int
+        lib.hmm_block_carries.argtypes = [vp, vp, vp, vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                          ctypes.c_int32, vp, vp, vp, vp]
+        lib.hmm_block_carries.restype = ctypes.c_int
         lib.hmm_status_string.argtypes = [ctypes.c_int]
         lib.hmm_status_string.restype = ctypes.c_char_p
         lib.hmm_kernel_timing_enable.argtypes = [ctypes.c_int32]
@@ -275,3 +284,67 @@ def hmm_transition_counts(A, filtered, marginals, counts=None, workspace=None):
     if rc != HMM_OK:
         raise HmmError(rc, "hmm_transition_counts")
     return counts
+
+
+def hmm_block_element_workspace_bytes(T: int, D: int, batch: int) -> int:
+    lib = load_library()
+    n = ctypes.c_size_t(0)
+    rc = lib.hmm_block_element_workspace_bytes(int(T), int(D), int(batch), ctypes.byref(n))
+    if rc != HMM_OK:
+        raise HmmError(rc, "hmm_block_element_workspace_bytes")
+    return int(n.value)
+
+
+def hmm_block_element(A, loglik, max_product: bool = False, element=None, log_scale=None, workspace=None):
+    """A[Bm][D][D], loglik[B][T][D]: the rows of one block of each sequence.  Returns (element[B][D][D] f32,
+    log_scale[B] f64), the block's element under the sum-product or the max-product operator;
+    asynchronous on torch's current stream."""
+    import torch
+    lib = load_library()
+    B, T, D = loglik.shape
+    Bm = A.shape[0]
+    if Bm not in (1, B):
+        raise ValueError("A's leading dimension must be 1 (shared) or batch")
+    f32 = torch.float32
+    _check(A, f32, (Bm, D, D), "A")
+    _check(loglik, f32, (B, T, D), "loglik")
+    dev = loglik.device
+    if element is None:
+        element = torch.empty((B, D, D), dtype=f32, device=dev)
+    if log_scale is None:
+        log_scale = torch.empty((B,), dtype=torch.float64, device=dev)
+    _check(element, f32, (B, D, D), "element")
+    _check(log_scale, torch.float64, (B,), "log_scale")
+    if workspace is None:
+        workspace = torch.empty((max(hmm_block_element_workspace_bytes(T, D, B), 256),), dtype=torch.uint8, device=dev)
+    rc = lib.hmm_block_element(_ptr(A), _ptr(loglik), T, D, B, 1 if Bm == 1 else 0, 1 if max_product else 0, _ptr(element),
+                               _ptr(log_scale), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream())
+    if rc != HMM_OK:
+        raise HmmError(rc, "hmm_block_element")
+    return element, log_scale
+
+
+def hmm_block_carries(prior, A, elements, log_scales, max_product: bool = False):
+    """prior[Bm][D], A[Bm][D][D], elements[S][B][D][D] f32 and log_scales[S][B] f64 (hmm_block_element's
+    outputs for the S consecutive blocks, stacked).  Returns (carry_rows[S][B][D], lookahead_rows[S][B][D],
+    total[B] f64); asynchronous on torch's current stream."""
+    import torch
+    lib = load_library()
+    S, B, D, _ = elements.shape
+    Bm = prior.shape[0]
+    if Bm not in (1, B):
+        raise ValueError("prior/A leading dimension must be 1 (shared) or batch")
+    f32 = torch.float32
+    _check(prior, f32, (Bm, D), "prior")
+    _check(A, f32, (Bm, D, D), "A")
+    _check(elements, f32, (S, B, D, D), "elements")
+    _check(log_scales, torch.float64, (S, B), "log_scales")
+    dev = elements.device
+    carry = torch.empty((S, B, D), dtype=f32, device=dev)
+    look = torch.empty((S, B, D), dtype=f32, device=dev)
+    total = torch.empty((B,), dtype=torch.float64, device=dev)
+    rc = lib.hmm_block_carries(_ptr(prior), _ptr(A), _ptr(elements), _ptr(log_scales), S, D, B, 1 if Bm == 1 else 0,
+                               1 if max_product else 0, _ptr(carry), _ptr(look), _ptr(total), _stream())
+    if rc != HMM_OK:
+        raise HmmError(rc, "hmm_block_carries")
+    return carry, look, total

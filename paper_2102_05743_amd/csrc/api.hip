@@ -3,6 +3,7 @@
 #include <stdint.h>
 
 #include "../../include/hmmscan.h"
+#include "blocks.hpp"
 #include "estep.hpp"
 #include "large_d.hpp"
 #include "small_d.hpp"
@@ -122,6 +123,51 @@ hmm_status hmm_transition_counts(const float* A, const float* filtered, const fl
     hmm::EstepArgs a{A, filtered, marginals, (long long)T, D, batch, shared_model ? 1 : 0, workspace, workspace_bytes,
                      static_cast<hipStream_t>(hip_stream)};
     return static_cast<hmm_status>(hmm::transition_counts(a, counts));
+}
+
+hmm_status hmm_block_element_workspace_bytes(int64_t T, int32_t D, int32_t batch, size_t* bytes) {
+    if (T < 1 || D < 1 || batch < 1 || !bytes) return HMM_ERR_INVALID_ARG;
+    if (D > HMM_MAX_STATES) return HMM_ERR_UNSUPPORTED;
+    if (D <= hmm::SMALL_D_MAX) {
+        *bytes = hmm::small_d_element_ws_bytes(D, T, batch);
+    } else {
+        const size_t sp = hmm::large_d_element_sp_ws_bytes(D, T, batch), mp = hmm::large_d_element_mp_ws_bytes(D, T, batch);
+        *bytes = sp > mp ? sp : mp;
+    }
+    return HMM_OK;
+}
+
+hmm_status hmm_block_element(const float* A, const float* loglik, int64_t T, int32_t D, int32_t batch,
+                             int32_t shared_model, int32_t max_product, float* element, double* log_scale,
+                             void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!A || !loglik || !element || !log_scale) return HMM_ERR_INVALID_ARG;
+    if (T < 1 || D < 1 || batch < 1) return HMM_ERR_INVALID_ARG;
+    if (D > HMM_MAX_STATES) return HMM_ERR_UNSUPPORTED;
+    if (!aligned16(loglik)) return HMM_ERR_INVALID_ARG;
+    size_t need = 0;
+    hmm_status st = hmm_block_element_workspace_bytes(T, D, batch, &need);
+    if (st != HMM_OK) return st;
+    if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return HMM_ERR_WORKSPACE;
+    if (D > hmm::SMALL_D_MAX) {
+        hmm::LargeArgs la{nullptr, A, loglik, (long long)T, D, batch, shared_model ? 1 : 0, workspace, workspace_bytes,
+                          static_cast<hipStream_t>(hip_stream)};
+        return static_cast<hmm_status>(max_product ? hmm::large_d_element_mp(la, element, log_scale)
+                                                   : hmm::large_d_element_sp(la, element, log_scale));
+    }
+    hmm::SmallArgs a{nullptr, A, loglik, (long long)T, batch, shared_model ? 1 : 0, workspace, workspace_bytes,
+                     static_cast<hipStream_t>(hip_stream)};
+    return static_cast<hmm_status>(hmm::small_d_block_element(D, a, max_product ? 1 : 0, element, log_scale));
+}
+
+hmm_status hmm_block_carries(const float* prior, const float* A, const float* elements, const double* log_scales,
+                             int32_t num_blocks, int32_t D, int32_t batch, int32_t shared_model, int32_t max_product,
+                             float* carry_rows, float* lookahead_rows, double* total, void* hip_stream) {
+    if (!prior || !A || !elements || !log_scales || !carry_rows || !lookahead_rows || !total) return HMM_ERR_INVALID_ARG;
+    if (num_blocks < 1 || D < 1 || batch < 1) return HMM_ERR_INVALID_ARG;
+    if (D > HMM_MAX_STATES) return HMM_ERR_UNSUPPORTED;
+    hmm::BlockCarryArgs a{prior, A, elements, log_scales, num_blocks, D, batch, shared_model ? 1 : 0, max_product ? 1 : 0,
+                          static_cast<hipStream_t>(hip_stream)};
+    return static_cast<hmm_status>(hmm::block_carries(a, carry_rows, lookahead_rows, total));
 }
 
 const char* hmm_status_string(hmm_status status) {

@@ -36,4 +36,11 @@ int large_d_viterbi(const LargeArgs& a, int32_t* path, double* logprob_out);
 size_t large_d_max_product_ws_bytes(int D, long long T, int batch);   // never more than the smoother's
 int large_d_max_product(const LargeArgs& a, float* maxmarg, int32_t* path, double* logprob_out);
 
+// Block-wise elements (a.prior unused).
+LargePlan element_plan(int D, long long T, int batch);
+size_t large_d_element_sp_ws_bytes(int D, long long T, int batch);
+int large_d_element_sp(const LargeArgs& a, float* element, double* log_scale);
+size_t large_d_element_mp_ws_bytes(int D, long long T, int batch);
+int large_d_element_mp(const LargeArgs& a, float* element, double* log_scale);
+
 }  // namespace hmm

@@ -73,7 +73,8 @@ __global__ __launch_bounds__(256) void lv_aggregate_systolic_kernel(const float*
                                                                     const float* __restrict__ ll, long long T, int Dr,
                                                                     int Lc, int cps, long long nchunks,
                                                                     int shared_model, float* __restrict__ agg,
-                                                                    float* __restrict__ agg_other) {
+                                                                    float* __restrict__ agg_other,
+                                                                    double* __restrict__ agg_off) {
     constexpr int NQ = D / 16;             // column blocks = registers per lane for one row of P
     constexpr int WPCH = MpCfg<D>::WPC;    // waves per chunk: a workgroup for D >= 32, else one wave
     constexpr int CPWG = 4 / WPCH;         // chunks per workgroup
@@ -110,6 +111,7 @@ __global__ __launch_bounds__(256) void lv_aggregate_systolic_kernel(const float*
     }
     chunk_sync<D>();
     float off = 0.0f;
+    double offsum = 0.0;
     int cur = 0;
     float xn = -INFINITY;
     if (j < Dr && cc.nsteps > 0) xn = lseq[(size_t)cc.t0 * Dr + j];
@@ -159,9 +161,12 @@ __global__ __launch_bounds__(256) void lv_aggregate_systolic_kernel(const float*
             chunk_sync<D>();
         }
         off = (m == -INFINITY) ? 0.0f : m;
+        offsum += (double)off;
         cur ^= 1;
     }
     if (cc.nsteps > 0) {
+        // what the rescalings removed, for callers that need the aggregate's absolute level
+        if (agg_off != nullptr && (wave % WPCH) == 0 && lane == 0) agg_off[chunk] = offsum;
         const float* pf = cur ? p1 : p0;
         float* dst = agg + (size_t)chunk * D * D;
         for (int r = 0; r < RPD; ++r) {
@@ -754,6 +759,108 @@ __global__ __launch_bounds__(64) void lm_finalize_kernel(const double* __restric
     if (threadIdx.x == 0) out[blockIdx.x] = acc;
 }
 
+// ---------------------------------------------------------------------------------------------
+// Block-wise elements (Sec. V-B) under the max-product operator: the ordered product of a block's chunk
+// aggregates by a binary tree, one level per launch: out[o] = in[2o] v in[2o+1] (a copy if there is no
+// right neighbour).  A workgroup forms a slab of sixteen rows of one result; lane = (column j, a share
+// of the slab's rows), the slab of the left operand in LDS.  Shifting a result to maximum 0 needs all
+// of its slabs, so it is left to the reader: every slab records its own maximum (tmax), and a level
+// reads its operands as (value - largest slab maximum), adding what it took off to the result's offset.
+// Without tmax the inputs are the chunk aggregates, which have maximum 0 already.
+// `swap`: the matrices are stored transposed, so the operands trade places.
+template <int D>
+__global__ __launch_bounds__(256) void lv_tree_product_kernel(const float* __restrict__ in, const double* __restrict__ in_off,
+                                                              const float* __restrict__ in_tmax, int n_in, int n_out,
+                                                              int swap, float* __restrict__ out,
+                                                              double* __restrict__ out_off, float* __restrict__ out_tmax) {
+    constexpr int NT = D / 16;        // slabs per matrix
+    constexpr int NRG = 256 / D;      // row groups
+    constexpr int RPT = 16 / NRG;     // rows per lane
+    __shared__ float xs[16 * D];
+    __shared__ float red[4];
+    const int tid = threadIdx.x;
+    const int slab = blockIdx.x % NT;
+    const int res = blockIdx.x / NT;                 // seq * n_out + o
+    const int seq = res / n_out, o = res % n_out;
+    const size_t ia = (size_t)seq * n_in + 2 * o;
+    const bool pair = 2 * o + 1 < n_in;
+    auto shift_of = [&](size_t idx) {
+        if (in_tmax == nullptr) return 0.0f;
+        float m = -INFINITY;
+#pragma unroll
+        for (int t = 0; t < NT; ++t) m = fmaxf(m, in_tmax[idx * NT + t]);
+        return (m == -INFINITY) ? 0.0f : m;
+    };
+    const float ma = shift_of(ia), mb = pair ? shift_of(ia + 1) : 0.0f;
+    const float* Ma = in + ia * D * D;
+    const float* Mb = Ma + D * D;
+    float* Z = out + (size_t)res * D * D;
+    const int j = tid % D, rg = tid / D;
+    const int i0 = 16 * slab;
+    float lmax = -INFINITY;
+    if (!pair) {
+#pragma unroll
+        for (int r = 0; r < RPT; ++r) {
+            const float v = Ma[(size_t)(i0 + rg * RPT + r) * D + j] - ma;
+            Z[(size_t)(i0 + rg * RPT + r) * D + j] = v;
+            lmax = fmaxf(lmax, v);
+        }
+    } else {
+        const float* X = swap ? Mb : Ma;
+        const float* Y = swap ? Ma : Mb;
+        for (int idx = tid; idx < 16 * D; idx += 256) xs[idx] = X[(size_t)i0 * D + idx];
+        __syncthreads();
+        float acc[RPT];
+#pragma unroll
+        for (int r = 0; r < RPT; ++r) acc[r] = -INFINITY;
+#pragma unroll 4
+        for (int k = 0; k < D; ++k) {
+            const float y = Y[(size_t)k * D + j];
+#pragma unroll
+            for (int r = 0; r < RPT; ++r) acc[r] = fmaxf(acc[r], xs[(rg * RPT + r) * D + k] + y);
+        }
+#pragma unroll
+        for (int r = 0; r < RPT; ++r) {
+            const float v = acc[r] - (ma + mb);
+            Z[(size_t)(i0 + rg * RPT + r) * D + j] = v;
+            lmax = fmaxf(lmax, v);
+        }
+    }
+    lmax = wave_max(lmax);
+    if ((tid & 63) == 0) red[tid >> 6] = lmax;
+    __syncthreads();
+    if (tid == 0) {
+        out_tmax[(size_t)res * NT + slab] = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+        if (slab == 0) out_off[res] = in_off[ia] + (pair ? in_off[ia + 1] : 0.0) + (double)ma + (double)mb;
+    }
+}
+
+// The block's element from its single remaining aggregate: padding dropped, largest entry 0,
+// log_scale = accumulated offset (-inf if no sequence of the block has any weight).
+template <int D>
+__global__ __launch_bounds__(256) void lv_element_finish_kernel(const float* __restrict__ M, const double* __restrict__ off,
+                                                                int Dr, int transposed, float* __restrict__ element,
+                                                                double* __restrict__ log_scale) {
+    __shared__ float red[4];
+    const int seq = blockIdx.x, tid = threadIdx.x;
+    const float* X = M + (size_t)seq * D * D;
+    float lm = -INFINITY;
+    for (int idx = tid; idx < Dr * Dr; idx += 256) {
+        const int i = idx / Dr, j = idx - i * Dr;
+        lm = fmaxf(lm, X[transposed ? (size_t)j * D + i : (size_t)i * D + j]);
+    }
+    lm = wave_max(lm);
+    if ((tid & 63) == 0) red[tid >> 6] = lm;
+    __syncthreads();
+    const float m = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    const float sh = (m == -INFINITY) ? 0.0f : m;
+    for (int idx = tid; idx < Dr * Dr; idx += 256) {
+        const int i = idx / Dr, j = idx - i * Dr;
+        element[(size_t)seq * Dr * Dr + idx] = X[transposed ? (size_t)j * D + i : (size_t)i * D + j] - sh;
+    }
+    if (tid == 0) log_scale[seq] = (m == -INFINITY) ? -INFINITY : off[seq] + (double)m;
+}
+
 // =============================================================================================
 // Host side
 // =============================================================================================
@@ -811,7 +918,8 @@ static int large_viterbi_impl(const LargeArgs& a, int32_t* path, double* logprob
     hipStream_t st = a.stream;
     const dim3 block(256);
     launch("lv_aggregate", lv_aggregate_systolic_kernel<D>, dim3((unsigned)((p.nchunks + M::CPW - 1) / M::CPW)), block,
-           st, a.A, a.ll, a.T, a.D, p.Lc, p.cps, p.nchunks, a.shared_model, agg, static_cast<float*>(nullptr));
+           st, a.A, a.ll, a.T, a.D, p.Lc, p.cps, p.nchunks, a.shared_model, agg, static_cast<float*>(nullptr),
+           static_cast<double*>(nullptr));
     if constexpr (D <= 32)
         launch("lv_carry", lv_carry_wave_kernel<D>, dim3((unsigned)a.batch), dim3(64), st, a.prior, a.D, p.cps,
                a.shared_model, agg, vin, static_cast<const float*>(nullptr), static_cast<float*>(nullptr));
@@ -869,7 +977,8 @@ static int large_max_product_impl(const LargeArgs& a, float* mm, int32_t* path, 
     hipStream_t st = a.stream;
     const dim3 block(256);
     launch("lv_aggregate", lv_aggregate_systolic_kernel<D>, dim3((unsigned)((p.nchunks + M::CPW - 1) / M::CPW)), block,
-           st, a.A, a.ll, a.T, a.D, p.Lc, p.cps, p.nchunks, a.shared_model, agg, agg_other);
+           st, a.A, a.ll, a.T, a.D, p.Lc, p.cps, p.nchunks, a.shared_model, agg, agg_other,
+           static_cast<double*>(nullptr));
     if constexpr (D <= 32)
         launch("lm_carry", lv_carry_wave_kernel<D>, dim3(2u * (unsigned)a.batch), dim3(64), st, a.prior, a.D, p.cps,
                a.shared_model, agg, vin, static_cast<const float*>(agg_other), bout);
@@ -887,6 +996,74 @@ static int large_max_product_impl(const LargeArgs& a, float* mm, int32_t* path, 
            rows, a.D, mm, path);
     launch("lm_finalize", lm_finalize_kernel, dim3((unsigned)a.batch), dim3(64), st, part, p.cps, logprob_out);
     return hipGetLastError() == hipSuccess ? 0 : 4;
+}
+
+// Max-product block element: chunk aggregates with their offsets -> binary tree of products -> finish.
+struct ElementMpWs { size_t agg, off, lvl[2][3], total; };
+
+static ElementMpWs element_mp_ws(int Dr, long long T, int batch) {
+    const LargePlan p = element_plan(Dr, T, batch);
+    const size_t D = p.DP, nc = (size_t)p.nchunks;
+    ElementMpWs w;
+    size_t o = 0;
+    w.agg = o; o = align_up(o + nc * D * D * sizeof(float), 256);
+    w.off = o; o = align_up(o + nc * sizeof(double), 256);
+    size_t n = (size_t)p.cps;
+    for (int l = 0; l < 2; ++l) {
+        n = (n + 1) / 2;
+        w.lvl[l][0] = o; o = align_up(o + n * batch * D * D * sizeof(float), 256);
+        w.lvl[l][1] = o; o = align_up(o + n * batch * sizeof(double), 256);
+        w.lvl[l][2] = o; o = align_up(o + n * batch * 8 * sizeof(float), 256);
+    }
+    w.total = o;
+    return w;
+}
+
+size_t large_d_element_mp_ws_bytes(int Dr, long long T, int batch) { return element_mp_ws(Dr, T, batch).total; }
+
+template <int D>
+static int large_element_mp_impl(const LargeArgs& a, float* element, double* log_scale) {
+    using M = MpCfg<D>;
+    const LargePlan p = element_plan(a.D, a.T, a.batch);
+    const ElementMpWs w = element_mp_ws(a.D, a.T, a.batch);
+    if (a.ws_bytes < w.total) return 3;
+    if (p.nchunks > 0x0fffffffLL) return 2;   // the tree's first level launches nchunks / 2 * D / 16 workgroups
+    char* ws = static_cast<char*>(a.ws);
+    float* agg = reinterpret_cast<float*>(ws + w.agg);
+    double* off = reinterpret_cast<double*>(ws + w.off);
+    hipStream_t st = a.stream;
+    const dim3 block(256);
+    launch("lv_aggregate", lv_aggregate_systolic_kernel<D>, dim3((unsigned)((p.nchunks + M::CPW - 1) / M::CPW)), block,
+           st, a.A, a.ll, a.T, a.D, p.Lc, p.cps, p.nchunks, a.shared_model, agg, static_cast<float*>(nullptr), off);
+    constexpr int transposed = (D <= 32) ? 1 : 0;   // orientation in which the aggregate kernel stores its results
+    const float* cur = agg;
+    const double* curo = off;
+    const float* curm = nullptr;
+    int n = p.cps, l = 0;
+    while (n > 1) {
+        const int n_out = (n + 1) / 2;
+        float* o = reinterpret_cast<float*>(ws + w.lvl[l][0]);
+        double* oo = reinterpret_cast<double*>(ws + w.lvl[l][1]);
+        float* om = reinterpret_cast<float*>(ws + w.lvl[l][2]);
+        launch("lv_tree_product", lv_tree_product_kernel<D>, dim3((unsigned)((long long)n_out * a.batch * (D / 16))), block, st,
+               cur, curo, curm, n, n_out, transposed, o, oo, om);
+        cur = o; curo = oo; curm = om;
+        n = n_out;
+        l ^= 1;
+    }
+    launch("lv_element_finish", lv_element_finish_kernel<D>, dim3((unsigned)a.batch), block, st, cur, curo, a.D, transposed,
+           element, log_scale);
+    return hipGetLastError() == hipSuccess ? 0 : 4;
+}
+
+int large_d_element_mp(const LargeArgs& a, float* element, double* log_scale) {
+    switch (element_plan(a.D, a.T, a.batch).DP) {
+        case 16: return large_element_mp_impl<16>(a, element, log_scale);
+        case 32: return large_element_mp_impl<32>(a, element, log_scale);
+        case 64: return large_element_mp_impl<64>(a, element, log_scale);
+        case 128: return large_element_mp_impl<128>(a, element, log_scale);
+        default: return 2;
+    }
 }
 
 int large_d_max_product(const LargeArgs& a, float* mm, int32_t* path, double* logprob_out) {

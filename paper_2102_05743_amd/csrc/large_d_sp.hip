@@ -260,6 +260,7 @@ __global__ __launch_bounds__(256) void ld_product_kernel(const float* __restrict
             int exmax = ex[0];
 #pragma unroll
             for (int w = 0; w < C::WPC; ++w) { exv[w] = ex[w]; exmax = max(exmax, exv[w]); }
+            if (exmax != ZERO_STRIP_EXP) exsum += exmax;   // common to all strips: keeps the product's absolute scale
             // at[(mo*64 + l)*ASTR + s] = P(k, m) 2^(ex[strip of k] - exmax), k = mfma_row(s), m = TS*mo + l % TS,
             // four consecutive s (= four consecutive k) per access
             for (int idx = tic; idx < C::MT * 64 * (C::NS / 4); idx += C::WPC * 64) {
@@ -1029,6 +1030,63 @@ __global__ __launch_bounds__(256) void ld_finalize_kernel(const double* __restri
     if (threadIdx.x == 0) out[seq] = sh[0];
 }
 
+// ---------------------------------------------------------------------------------------------
+// Block-wise element (Sec. V-B) of a whole block from its single remaining aggregate: strips brought
+// to one power-of-two scale, largest entry in [0.5, 1), padding dropped;
+// log_scale = sum of the steps' emission maxima + ln 2 * (binary exponent).  One workgroup per sequence.
+template <int D>
+__global__ __launch_bounds__(256) void ld_element_finish_kernel(const float* __restrict__ agg, const int* __restrict__ exps,
+                                                                const float* __restrict__ rowmax, long long T, int Dr,
+                                                                float* __restrict__ element, double* __restrict__ log_scale) {
+    using C = LargeCfg<D>;
+    __shared__ double dred[4];
+    __shared__ float fred[4];
+    const int seq = blockIdx.x, tid = threadIdx.x;
+    const float* M = agg + (size_t)seq * D * D;
+    const int* ex = exps + (size_t)seq * C::WPC;
+    double ms = 0.0;
+    {
+        // eight independent loads in flight per lane: one workgroup adds up the whole block's maxima
+        const float* rm = rowmax + (size_t)seq * T;
+        constexpr int U = 8;
+        long long t = tid;
+        for (; t + (U - 1) * 256 < T; t += U * 256) {
+            float v[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) v[u] = rm[t + u * 256];
+#pragma unroll
+            for (int u = 0; u < U; ++u) ms += (v[u] == -INFINITY) ? 0.0 : (double)v[u];
+        }
+        for (; t < T; t += 256) {
+            const float m = rm[t];
+            ms += (m == -INFINITY) ? 0.0 : (double)m;
+        }
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) ms += __shfl_down(ms, d, 64);
+    int exmax = ex[0];
+#pragma unroll
+    for (int w = 1; w < C::WPC; ++w) exmax = max(exmax, ex[w]);
+    float lm = 0.0f;
+    for (int idx = tid; idx < Dr * Dr; idx += 256) {
+        const int i = idx / Dr, j = idx - i * Dr;
+        lm = fmaxf(lm, ldexpf(M[(size_t)i * D + j], max(ex[i / C::TS] - exmax, -200)));
+    }
+    lm = wave_max(lm);
+    if ((tid & 63) == 0) { dred[tid >> 6] = ms; fred[tid >> 6] = lm; }
+    __syncthreads();
+    const float m = fmaxf(fmaxf(fred[0], fred[1]), fmaxf(fred[2], fred[3]));
+    const int ex2 = __builtin_amdgcn_frexp_expf(m);
+    for (int idx = tid; idx < Dr * Dr; idx += 256) {
+        const int i = idx / Dr, j = idx - i * Dr;
+        element[(size_t)seq * Dr * Dr + idx] = ldexpf(M[(size_t)i * D + j], max(ex[i / C::TS] - exmax - ex2, -200));
+    }
+    if (tid == 0) {
+        const double total = dred[0] + dred[1] + dred[2] + dred[3];
+        log_scale[seq] = (m > 0.0f) ? total + 0.6931471805599453 * ((double)exmax + (double)ex2) : -INFINITY;
+    }
+}
+
 // =============================================================================================
 // Host side
 // =============================================================================================
@@ -1195,6 +1253,96 @@ static int large_smooth_impl(const LargeArgs& a, float* marg, float* filt, doubl
            rows, a.D, marg);
     launch("ld_finalize", ld_finalize_kernel, dim3((unsigned)a.batch), block, st, part, p.cps, loglik_out);
     return hipGetLastError() == hipSuccess ? 0 : 4;
+}
+
+// Chunking of the block-element path (both operators): the smoother's chunk lengths, no second-level plan.
+LargePlan element_plan(int Dr, long long T, int batch) {
+    const SmoothPlan sp = smooth_plan(Dr, T, batch);
+    LargePlan p;
+    p.DP = sp.DP; p.Lc = sp.Lc; p.cps = sp.cps; p.nchunks = sp.nchunks;
+    return p;
+}
+
+// Sum-product block element: rowmax -> chunk aggregates -> products of g aggregates at a time until one
+// is left per sequence -> finish.
+struct ElementSpWs { size_t rowmax, agg, aggT, exps, lvl[2][3], total; int g; };
+
+static ElementSpWs element_sp_ws(int Dr, long long T, int batch) {
+    const LargePlan p = element_plan(Dr, T, batch);
+    const size_t D = p.DP, nc = (size_t)p.nchunks, rows = (size_t)T * batch;
+    ElementSpWs w;
+    w.g = p.DP >= 64 ? 4 : 8;
+    size_t o = 0;
+    w.rowmax = o; o = align_up(o + rows * sizeof(float), 256);
+    w.agg = o;    o = align_up(o + nc * D * D * sizeof(float), 256);
+    w.aggT = o;   o = align_up(o + nc * D * D * sizeof(float), 256);
+    w.exps = o;   o = align_up(o + nc * 8 * sizeof(int), 256);
+    size_t n = (size_t)p.cps;
+    for (int l = 0; l < 2; ++l) {
+        n = (n + w.g - 1) / w.g;
+        const size_t cnt = n * batch;
+        w.lvl[l][0] = o; o = align_up(o + cnt * D * D * sizeof(float), 256);
+        w.lvl[l][1] = o; o = align_up(o + cnt * D * D * sizeof(float), 256);
+        w.lvl[l][2] = o; o = align_up(o + cnt * 8 * sizeof(int), 256);
+    }
+    w.total = o;
+    return w;
+}
+
+size_t large_d_element_sp_ws_bytes(int Dr, long long T, int batch) { return element_sp_ws(Dr, T, batch).total; }
+
+template <int D>
+static int large_element_sp_impl(const LargeArgs& a, float* element, double* log_scale) {
+    using C = LargeCfg<D>;
+    const LargePlan p = element_plan(a.D, a.T, a.batch);
+    const ElementSpWs w = element_sp_ws(a.D, a.T, a.batch);
+    if (a.ws_bytes < w.total) return 3;
+    const long long rows = a.T * a.batch;
+    if (rows > 0x7fffffffLL * 4 || p.nchunks > 0x3fffffffLL) return 2;
+    char* ws = static_cast<char*>(a.ws);
+    float* rowmax = reinterpret_cast<float*>(ws + w.rowmax);
+    float* agg = reinterpret_cast<float*>(ws + w.agg);
+    float* aggT = reinterpret_cast<float*>(ws + w.aggT);
+    int* exps = reinterpret_cast<int*>(ws + w.exps);
+    hipStream_t st = a.stream;
+    const dim3 block(256);
+    {
+        int width = 1;
+        while (width < (a.D + 3) / 4) width <<= 1;
+        const long long rpb = 4LL * (64 / width);
+        launch("ld_rowmax", ld_rowmax_kernel, dim3((unsigned)((rows + rpb - 1) / rpb)), block, st, a.ll, rows, a.D, rowmax);
+    }
+    launch("ld_aggregate", ld_aggregate_kernel<D>, dim3((unsigned)((p.nchunks + C::CPW - 1) / C::CPW)), block, st, a.A,
+           a.ll, rowmax, a.T, a.D, p.Lc, p.cps, p.nchunks, a.shared_model, agg, aggT, exps);
+    const float* cur = agg;
+    const float* curT = aggT;
+    const int* cure = exps;
+    int n = p.cps, l = 0;
+    while (n > 1) {
+        const int G = (n + w.g - 1) / w.g;
+        const long long ngroups = (long long)G * a.batch;
+        float* o = reinterpret_cast<float*>(ws + w.lvl[l][0]);
+        float* oT = reinterpret_cast<float*>(ws + w.lvl[l][1]);
+        int* oe = reinterpret_cast<int*>(ws + w.lvl[l][2]);
+        launch("ld_product", ld_product_kernel<D>, dim3((unsigned)((ngroups + C::CPW - 1) / C::CPW)), block, st, curT, cure, n,
+               w.g, G, ngroups, o, oT, oe);
+        cur = o; curT = oT; cure = oe;
+        n = G;
+        l ^= 1;
+    }
+    launch("ld_element_finish", ld_element_finish_kernel<D>, dim3((unsigned)a.batch), block, st, cur, cure,
+           (const float*)rowmax, a.T, a.D, element, log_scale);
+    return hipGetLastError() == hipSuccess ? 0 : 4;
+}
+
+int large_d_element_sp(const LargeArgs& a, float* element, double* log_scale) {
+    switch (element_plan(a.D, a.T, a.batch).DP) {
+        case 16: return large_element_sp_impl<16>(a, element, log_scale);
+        case 32: return large_element_sp_impl<32>(a, element, log_scale);
+        case 64: return large_element_sp_impl<64>(a, element, log_scale);
+        case 128: return large_element_sp_impl<128>(a, element, log_scale);
+        default: return 2;
+    }
 }
 
 int large_d_smooth(const LargeArgs& a, float* marg, float* filt, double* loglik_out) {

@@ -50,4 +50,14 @@ int small_d_max_product(int D, const SmallArgs& a, float* maxmarg, int32_t* path
     return 2;
 }
 
+size_t small_d_element_ws_bytes(int D, long long T, int batch) {
+    HMM_DISPATCH_SMALL_D(D, element_ws_bytes(T, batch))
+    return 0;
+}
+
+int small_d_block_element(int D, const SmallArgs& a, int max_product, float* element, double* log_scale) {
+    HMM_DISPATCH_SMALL_D(D, block_element(a, max_product, element, log_scale))
+    return 2;
+}
+
 }  // namespace hmm

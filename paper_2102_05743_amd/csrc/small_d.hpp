@@ -29,6 +29,8 @@ struct SmallD {
     static int smooth(const SmallArgs& a, float* marg, float* filt, double* loglik_out);
     static int viterbi(const SmallArgs& a, int32_t* path, double* logprob_out);
     static int max_product(const SmallArgs& a, float* maxmarg, int32_t* path, double* logprob_out);
+    static size_t element_ws_bytes(long long T, int batch);
+    static int block_element(const SmallArgs& a, int max_product, float* element, double* log_scale);   // a.prior unused
 };
 
 size_t small_d_smooth_ws_bytes(int D, long long T, int batch);
@@ -36,5 +38,7 @@ size_t small_d_viterbi_ws_bytes(int D, long long T, int batch);
 int small_d_smooth(int D, const SmallArgs& a, float* marg, float* filt, double* loglik_out);
 int small_d_viterbi(int D, const SmallArgs& a, int32_t* path, double* logprob_out);
 int small_d_max_product(int D, const SmallArgs& a, float* maxmarg, int32_t* path, double* logprob_out);
+size_t small_d_element_ws_bytes(int D, long long T, int batch);
+int small_d_block_element(int D, const SmallArgs& a, int max_product, float* element, double* log_scale);
 
 }  // namespace hmm

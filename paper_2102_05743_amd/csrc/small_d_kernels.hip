@@ -724,6 +724,137 @@ __global__ __launch_bounds__(256) void sd_viterbi_fused_kernel(const float* __re
 }
 
 // =============================================================================================
+// Block-wise elements (Sec. V-B): the element of the whole block, with its scale
+// =============================================================================================
+
+// Aggregate of the lane's chunk as in chunk_aggregate, but keeping what the rescalings remove:
+// the true aggregate is P * exp(scale) (SumProd) or P + scale (MaxPlus).
+template <class S, int D>
+HMM_DEV double chunk_element(const float* row, int n, bool first, const float (&Am)[D * D], float (&P)[D * D]) {
+    using C = SmallCfg<D>;
+    mat_identity<S, D>(P);
+    float ms = 0.0f, rs = 0.0f;   // sums of at most L emission maxima / L removed exponents or offsets
+#pragma unroll
+    for (int k = 0; k < C::L; ++k) {
+        if (k < n) {
+            float ev[D];
+            lds_read_vec<D>(row + k * D, ev);
+            ms += emission<S, D>(ev);
+            if (k == 0 && first) absorb<S, D>(P, Am, ev, true);
+            else absorb<S, D>(P, Am, ev, false);
+            if ((k & 3) == 3 || k == n - 1) rs += renorm<S, D * D>(P);
+        }
+    }
+    return (double)ms + (double)rs * (S::is_max_plus ? 1.0 : 0.6931471805599453);
+}
+
+// Ordered product of one (aggregate, scale) pair per lane over the workgroup; result in thread 0.
+// Inside a wave a binary tree over lane distances 1, 2, ..., 32 (lane t ends with the product of
+// lanes t .. t + 2^level - 1, of which only lane 0's is used); the four wave results are folded by
+// thread 0.  wred: NW * D * D floats, wsc: NW doubles.
+template <class S, int D>
+HMM_DEV void block_reduce_scaled(float (&P)[D * D], double& sc, float* wred, double* wsc) {
+    using C = SmallCfg<D>;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        float Y[D * D], Z[D * D];
+#pragma unroll
+        for (int e = 0; e < D * D; ++e) Y[e] = __shfl_down(P[e], d, 64);
+        const double ysc = __shfl_down(sc, d, 64);
+        if (lane + d < 64) {   // lanes without a partner keep their own pair (never used further up)
+            mat_mul<S, D>(P, Y, Z);
+            const float r = renorm<S, D * D>(Z);
+            sc += ysc + (double)r * (S::is_max_plus ? 1.0 : 0.6931471805599453);
+#pragma unroll
+            for (int e = 0; e < D * D; ++e) P[e] = Z[e];
+        }
+    }
+    if (lane == 0) {
+#pragma unroll
+        for (int e = 0; e < D * D; ++e) wred[wave * D * D + e] = P[e];
+        wsc[wave] = sc;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < C::NW; ++w) {
+            float Y[D * D], Z[D * D];
+#pragma unroll
+            for (int e = 0; e < D * D; ++e) Y[e] = wred[w * D * D + e];
+            mat_mul<S, D>(P, Y, Z);
+            const float r = renorm<S, D * D>(Z);
+            sc += wsc[w] + (double)r * (S::is_max_plus ? 1.0 : 0.6931471805599453);
+#pragma unroll
+            for (int e = 0; e < D * D; ++e) P[e] = Z[e];
+        }
+    }
+}
+
+// Kernel E1: (aggregate, scale) of every tile of the block.
+template <class S, int D>
+__global__ __launch_bounds__(256) void sd_element_tile_kernel(const float* __restrict__ A, const float* __restrict__ ll,
+                                                              long long T, int tps, int shared_model,
+                                                              float* __restrict__ tagg, double* __restrict__ tsc) {
+    using C = SmallCfg<D>;
+    __shared__ float lds[C::LDS_FLOATS];
+    __shared__ float wred[C::NW * D * D];
+    __shared__ double wsc[C::NW];
+    const TileCoord tc = tile_coord<D>(T, tps);
+    load_tile<D>(ll + tc.base * D, tc.nvalid, lds);
+    float Am[D * D];
+    load_model<S, D>(A + (shared_model ? 0 : (size_t)tc.seq * D * D), Am);
+    __syncthreads();
+    const int n = min(max(tc.nvalid - (int)threadIdx.x * C::L, 0), C::L);
+    float P[D * D];
+    double sc = chunk_element<S, D>(lds + threadIdx.x * C::STRIDE, n, tc.tile == 0 && threadIdx.x == 0, Am, P);
+    block_reduce_scaled<S, D>(P, sc, wred, wsc);
+    if (threadIdx.x == 0) {
+#pragma unroll
+        for (int e = 0; e < D * D; ++e) tagg[(size_t)blockIdx.x * D * D + e] = P[e];
+        tsc[blockIdx.x] = sc;
+    }
+}
+
+// Kernel E2: the block's element from its tiles.  One workgroup per sequence; lane t folds R
+// consecutive tiles, then the workgroup's ordered product.  SumProd: largest entry in [0.5, 1);
+// MaxPlus: largest entry 0.
+template <class S, int D>
+__global__ __launch_bounds__(256) void sd_element_fold_kernel(const float* __restrict__ tagg, const double* __restrict__ tsc,
+                                                              int tps, float* __restrict__ element,
+                                                              double* __restrict__ log_scale) {
+    using C = SmallCfg<D>;
+    __shared__ float wred[C::NW * D * D];
+    __shared__ double wsc[C::NW];
+    const int seq = blockIdx.x;
+    const int R = (tps + C::NT - 1) / C::NT;
+    const int t0 = threadIdx.x * R;
+    float P[D * D];
+    mat_identity<S, D>(P);
+    double sc = 0.0;
+    for (int r = 0; r < R; ++r) {
+        const int tile = t0 + r;
+        if (tile < tps) {
+            float M[D * D], Z[D * D];
+#pragma unroll
+            for (int e = 0; e < D * D; ++e) M[e] = tagg[((size_t)seq * tps + tile) * D * D + e];
+            mat_mul<S, D>(P, M, Z);
+            const float rr = renorm<S, D * D>(Z);
+            sc += tsc[(size_t)seq * tps + tile] + (double)rr * (S::is_max_plus ? 1.0 : 0.6931471805599453);
+#pragma unroll
+            for (int e = 0; e < D * D; ++e) P[e] = Z[e];
+        }
+    }
+    block_reduce_scaled<S, D>(P, sc, wred, wsc);
+    if (threadIdx.x == 0) {
+        const float m = max_of(P);
+        const bool none = S::is_max_plus ? (m == -INFINITY) : !(m > 0.0f);   // no sequence of the block has any weight
+#pragma unroll
+        for (int e = 0; e < D * D; ++e) element[(size_t)seq * D * D + e] = P[e];
+        log_scale[seq] = none ? -INFINITY : sc;
+    }
+}
+
+// =============================================================================================
 // Host side
 // =============================================================================================
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -917,6 +1048,37 @@ int SmallD<D>::viterbi(const SmallArgs& a, int32_t* path, double* logprob_out) {
                vin, bp, cmap, tmap, part);
         launch("sd_viterbi_suffix", sd_viterbi_suffix_kernel<D>, seqs, block, st, tmap, itps, xend, part, logprob_out);
         launch("sd_viterbi_path", sd_viterbi_path_kernel<D>, grid, block, st, a.T, itps, bp, cmap, xend, path);
+    }
+    return hipGetLastError() == hipSuccess ? 0 : 4;
+}
+
+template <int D>
+size_t SmallD<D>::element_ws_bytes(long long T, int batch) {
+    const size_t nt = (size_t)tiles_per_seq<D>(T) * batch;
+    return align_up(nt * D * D * sizeof(float), 256) + align_up(nt * sizeof(double), 256);
+}
+
+template <int D>
+int SmallD<D>::block_element(const SmallArgs& a, int max_product, float* element, double* log_scale) {
+    using C = SmallCfg<D>;
+    const long long tps = tiles_per_seq<D>(a.T);
+    const long long nt = tps * a.batch;
+    if (nt > 0x7fffffffLL) return 2;
+    if (a.ws_bytes < element_ws_bytes(a.T, a.batch)) return 3;
+    char* ws = static_cast<char*>(a.ws);
+    float* tagg = reinterpret_cast<float*>(ws);
+    double* tsc = reinterpret_cast<double*>(ws + align_up((size_t)nt * D * D * sizeof(float), 256));
+    const dim3 grid((unsigned)nt), block(C::NT), seqs((unsigned)a.batch);
+    if (max_product) {
+        launch("sd_element_tile_mp", sd_element_tile_kernel<MaxPlus, D>, grid, block, a.stream, a.A, a.ll, a.T, (int)tps,
+               a.shared_model, tagg, tsc);
+        launch("sd_element_fold_mp", sd_element_fold_kernel<MaxPlus, D>, seqs, block, a.stream, tagg, tsc, (int)tps,
+               element, log_scale);
+    } else {
+        launch("sd_element_tile_sp", sd_element_tile_kernel<SumProd, D>, grid, block, a.stream, a.A, a.ll, a.T, (int)tps,
+               a.shared_model, tagg, tsc);
+        launch("sd_element_fold_sp", sd_element_fold_kernel<SumProd, D>, seqs, block, a.stream, tagg, tsc, (int)tps,
+               element, log_scale);
     }
     return hipGetLastError() == hipSuccess ? 0 : 4;
 }
