@@ -86,3 +86,16 @@ def test_argument_errors_are_caught_on_the_host():
     assert lib.hmm_transition_counts(fake, fake, fake, 8, 4, 1, 1, fake, aligned_ws, 8, null) == 3
     assert hmm.hmm_transition_counts_workspace_bytes(1 << 20, 4, 1) >= 64
     assert hmm.hmm_transition_counts_workspace_bytes(1, 128, 3) == 3 * 128 * 128 * 4
+    # hmm_block_element / hmm_block_carries
+    assert lib.hmm_block_element(null, fake, 8, 4, 1, 1, 0, fake, fake, aligned_ws, 1 << 20, null) == 1
+    assert lib.hmm_block_element(fake, fake, 8, 4, 1, 1, 0, fake, null, aligned_ws, 1 << 20, null) == 1
+    assert lib.hmm_block_element(fake, fake, 0, 4, 1, 1, 1, fake, fake, aligned_ws, 1 << 20, null) == 1
+    assert lib.hmm_block_element(fake, ctypes.c_void_p(0x1004), 8, 4, 1, 1, 0, fake, fake, aligned_ws, 1 << 20, null) == 1
+    assert lib.hmm_block_element(fake, fake, 8, 300, 1, 1, 0, fake, fake, aligned_ws, 1 << 20, null) == 2
+    assert lib.hmm_block_element(fake, fake, 8, 4, 1, 1, 0, fake, fake, aligned_ws, 8, null) == 3
+    assert lib.hmm_block_element(fake, fake, 8, 64, 1, 1, 1, fake, fake, null, 1 << 30, null) == 3
+    assert lib.hmm_block_carries(fake, fake, null, fake, 3, 4, 1, 1, 0, fake, fake, fake, null) == 1
+    assert lib.hmm_block_carries(fake, fake, fake, fake, 0, 4, 1, 1, 0, fake, fake, fake, null) == 1
+    assert lib.hmm_block_carries(fake, fake, fake, fake, 3, 129, 1, 1, 1, fake, fake, fake, null) == 2
+    for shape in [(1 << 20, 4, 1), (1 << 16, 128, 1), (4096, 16, 256), (1, 9, 1)]:
+        assert hmm.hmm_block_element_workspace_bytes(*shape) >= 256
