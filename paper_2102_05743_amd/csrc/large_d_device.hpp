@@ -80,6 +80,25 @@ HMM_DEV float wave_max(float v) {
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 
+// The same for values that are known to be non-negative (and not NaN): their bit patterns order like
+// unsigned integers, and the integer maximum needs no canonicalisation of its operands, which halves
+// the instructions per level.
+template <int CTRL, int ROW_MASK>
+HMM_DEV unsigned dpp_take_u(unsigned src) {
+    return (unsigned)__builtin_amdgcn_update_dpp(0, (int)src, CTRL, ROW_MASK, 0xF, false);
+}
+
+HMM_DEV float wave_max_nonneg(float v) {
+    unsigned u = __float_as_uint(v);
+    u = max(u, dpp_take_u<0x111, 0xF>(u));
+    u = max(u, dpp_take_u<0x112, 0xF>(u));
+    u = max(u, dpp_take_u<0x114, 0xF>(u));
+    u = max(u, dpp_take_u<0x118, 0xF>(u));
+    u = max(u, dpp_take_u<0x142, 0xA>(u));
+    u = max(u, dpp_take_u<0x143, 0xC>(u));
+    return __uint_as_float((unsigned)__builtin_amdgcn_readlane((int)u, 63));
+}
+
 HMM_DEV float wave_sum(float v) {
     v += dpp_take<0x111, 0xF>(0.0f, v);
     v += dpp_take<0x112, 0xF>(0.0f, v);

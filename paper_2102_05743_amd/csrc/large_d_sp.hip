@@ -26,7 +26,10 @@ constexpr int ZERO_STRIP_EXP = -(1 << 28);   // power-of-two scale recorded for 
 // ---------------------------------------------------------------------------------------------
 // m_t = max_j ll_t(j).  A power-of-two group of lanes per row, four consecutive values per lane, so
 // that a wave reads whole consecutive rows (coalesced for every D); 16-byte loads when rows are
-// 16-byte aligned (D a multiple of four).
+// 16-byte aligned (D a multiple of four).  A wave takes STREAM_UNROLL such groups of rows, all loads
+// issued before the first is used: a streaming pass needs that many bytes in flight per lane.
+constexpr int STREAM_UNROLL = 4;
+
 __global__ __launch_bounds__(256) void ld_rowmax_kernel(const float* __restrict__ ll, long long rows, int Dr,
                                                         float* __restrict__ rowmax) {
     const int lpr = (Dr + 3) / 4;                  // lanes per row
@@ -35,29 +38,46 @@ __global__ __launch_bounds__(256) void ld_rowmax_kernel(const float* __restrict_
     const int rows_per_wave = 64 / width;
     const int lane = threadIdx.x & 63;
     const long long wave = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
-    const long long row = wave * rows_per_wave + lane / width;
     const int sub = lane % width;
-    float m = -INFINITY;
-    if (row < rows && sub < lpr) {
-        const float* p = ll + row * Dr + 4 * sub;
-        if ((Dr & 3) == 0) {
-            const float4 x = *reinterpret_cast<const float4*>(p);
-            m = fmaxf(fmaxf(x.x, x.y), fmaxf(x.z, x.w));
-        } else {
+    const long long row0 = wave * (STREAM_UNROLL * rows_per_wave) + lane / width;
+    float m[STREAM_UNROLL];
+    if ((Dr & 3) == 0) {
+        float4 x[STREAM_UNROLL];
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
-                if (4 * sub + q < Dr) m = fmaxf(m, p[q]);
+        for (int u = 0; u < STREAM_UNROLL; ++u) {
+            const long long row = row0 + u * rows_per_wave;
+            x[u] = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+            if (row < rows && sub < lpr)
+                x[u] = *reinterpret_cast<const float4*>(ll + row * Dr + 4 * sub);   // read again soon: keep it cached
+        }
+#pragma unroll
+        for (int u = 0; u < STREAM_UNROLL; ++u) m[u] = fmaxf(fmaxf(x[u].x, x[u].y), fmaxf(x[u].z, x[u].w));
+    } else {
+#pragma unroll
+        for (int u = 0; u < STREAM_UNROLL; ++u) {
+            const long long row = row0 + u * rows_per_wave;
+            m[u] = -INFINITY;
+            if (row < rows && sub < lpr) {
+                const float* p = ll + row * Dr + 4 * sub;
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if (4 * sub + q < Dr) m[u] = fmaxf(m[u], p[q]);
+            }
         }
     }
-    for (int d = 1; d < width; d <<= 1) m = fmaxf(m, __shfl_xor(m, d, 64));
-    if (row < rows && sub == 0) rowmax[row] = m;
+#pragma unroll
+    for (int u = 0; u < STREAM_UNROLL; ++u) {
+        for (int d = 1; d < width; d <<= 1) m[u] = fmaxf(m[u], __shfl_xor(m[u], d, 64));
+        const long long row = row0 + u * rows_per_wave;
+        if (row < rows && sub == 0) rowmax[row] = m[u];
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
 // Chunk aggregates on the matrix cores.  One wave owns a TS-column strip of P^T (= TS rows of P,
 // which evolve independently); WPC waves make a chunk, CPW chunks share a workgroup.
 template <int D>
-__global__ __launch_bounds__(256) void ld_aggregate_kernel(const float* __restrict__ A, const float* __restrict__ ll,
+__global__ __launch_bounds__(256, (D <= 32) ? 2 : 1) void ld_aggregate_kernel(const float* __restrict__ A, const float* __restrict__ ll,
                                                            const float* __restrict__ rowmax, long long T, int Dr,
                                                            int Lc, int cps, long long nchunks, int shared_model,
                                                            float* __restrict__ agg, float* __restrict__ aggT,
@@ -123,7 +143,7 @@ __global__ __launch_bounds__(256) void ld_aggregate_kernel(const float* __restri
         for (int mt = 0; mt < C::MT; ++mt)
 #pragma unroll
             for (int r = 0; r < C::NACC; ++r) m = fmaxf(m, acc[mt][r]);
-        m = wave_max(m);
+        m = wave_max_nonneg(m);   // products of non-negative factors
         const int ex = __builtin_amdgcn_frexp_expf(m);
         const float sc = ldexpf(1.0f, -ex);
 #pragma unroll
@@ -140,6 +160,59 @@ __global__ __launch_bounds__(256) void ld_aggregate_kernel(const float* __restri
     store_batch(0, er);
     __syncthreads();
     const float* arow = at + lane * C::ASTR;
+    if constexpr (D <= 32) {
+        // Small tiles: the first operands of a wave fit in registers (MT * NS values), and the emission
+        // factor of result row m multiplies the first operand's row m instead of the result, so a step
+        // is MFMAs fed by the previous step's results and nothing else touches the accumulators.  The
+        // sequence's first element (no transition part) uses the identity in place of A^T.
+        const int nsteps = __builtin_amdgcn_readfirstlane(cc.nsteps);   // uniform over the wave: scalar loop bounds
+        const bool seq_start = __builtin_amdgcn_readfirstlane(cc.t0 == 0 ? 1 : 0) != 0;
+        float areg[C::MT][C::NS];
+#pragma unroll
+        for (int mo = 0; mo < C::MT; ++mo)
+#pragma unroll
+            for (int s4 = 0; s4 < C::NS; s4 += 4) {
+                const float4 a4 = *reinterpret_cast<const float4*>(arow + mo * 64 * C::ASTR + s4);
+                areg[mo][s4] = a4.x; areg[mo][s4 + 1] = a4.y; areg[mo][s4 + 2] = a4.z; areg[mo][s4 + 3] = a4.w;
+            }
+        auto advance = [&](const float (&a)[C::MT][C::NS], const float* erow) {
+            Acc nw[C::MT];
+#pragma unroll
+            for (int mo = 0; mo < C::MT; ++mo) {
+                const float em = erow[C::TS * mo + lane % C::TS];
+#pragma unroll
+                for (int r = 0; r < C::NACC; ++r) nw[mo][r] = 0.0f;
+#pragma unroll
+                for (int s = 0; s < C::NS; ++s)
+                    nw[mo] = mfma_step<C::TS>(a[mo][s] * em, acc[s / C::NACC][s % C::NACC], nw[mo]);
+            }
+#pragma unroll
+            for (int mo = 0; mo < C::MT; ++mo) acc[mo] = nw[mo];
+        };
+        for (int b = 0; b < nb; ++b) {
+            if (b + 1 < nb) load_batch(b + 1, er);
+            const float* eb = e_all + ((b & 1) * C::CPW + cl) * C::EB * D;
+            const int s_end = min(C::EB, nsteps - b * C::EB);
+            int sb = 0;
+            if (b == 0 && seq_start && s_end > 0) {
+                float aid[C::MT][C::NS];
+#pragma unroll
+                for (int mo = 0; mo < C::MT; ++mo)
+#pragma unroll
+                    for (int s = 0; s < C::NS; ++s)
+                        aid[mo][s] = (mfma_row<D>(s / C::NACC, s % C::NACC, g) == C::TS * mo + lane % C::TS) ? 1.0f : 0.0f;
+                advance(aid, eb);
+                sb = 1;
+            }
+#pragma unroll 1
+            for (; sb < s_end; ++sb) {
+                advance(areg, eb + sb * D);
+                if (((b * C::EB + sb) % C::NORM_EVERY) == C::NORM_EVERY - 1) rescale();
+            }
+            if (b + 1 < nb) store_batch(b + 1, er);
+            __syncthreads();
+        }
+    } else
     for (int b = 0; b < nb; ++b) {
         if (b + 1 < nb) load_batch(b + 1, er);
         const float* eb = e_all + ((b & 1) * C::CPW + cl) * C::EB * D;
@@ -239,7 +312,7 @@ __global__ __launch_bounds__(256) void ld_product_kernel(const float* __restrict
         for (int mt = 0; mt < C::MT; ++mt)
 #pragma unroll
             for (int r = 0; r < C::NACC; ++r) m = fmaxf(m, acc[mt][r]);
-        m = wave_max(m);
+        m = wave_max_nonneg(m);   // products of non-negative factors
         const int ex = __builtin_amdgcn_frexp_expf(m);
         const float sc = ldexpf(1.0f, -ex);
 #pragma unroll
@@ -982,7 +1055,8 @@ __global__ __launch_bounds__(256) void ld_apply_row_kernel(const float* __restri
 }
 
 // ---------------------------------------------------------------------------------------------
-// p(x_k) = f_k b_k / Z_k.  Four consecutive states per lane; a row is reduced inside a wave.
+// p(x_k) = f_k b_k / Z_k.  Four consecutive states per lane; a row is reduced inside a wave; a wave
+// takes STREAM_UNROLL groups of rows with all loads issued first, 16-byte accesses when D is a multiple of four.
 __global__ __launch_bounds__(256) void ld_combine_kernel(const float* __restrict__ F, const float* __restrict__ Bv,
                                                          long long rows, int Dr, float* __restrict__ marg) {
     const int lpr = (Dr + 3) / 4;                  // lanes per row
@@ -991,25 +1065,57 @@ __global__ __launch_bounds__(256) void ld_combine_kernel(const float* __restrict
     const int rows_per_wave = 64 / width;
     const int lane = threadIdx.x & 63;
     const long long wave = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
-    const long long row = wave * rows_per_wave + lane / width;
     const int sub = lane % width;
-    float g[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-    const bool live = row < rows && sub < lpr;
-    if (live) {
+    const long long row0 = wave * (STREAM_UNROLL * rows_per_wave) + lane / width;
+    float g[STREAM_UNROLL][4];
+    bool live[STREAM_UNROLL];
+    if ((Dr & 3) == 0) {
+        float4 f[STREAM_UNROLL], b[STREAM_UNROLL];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int j = 4 * sub + q;
-            if (j < Dr) g[q] = F[row * Dr + j] * Bv[row * Dr + j];
+        for (int u = 0; u < STREAM_UNROLL; ++u) {
+            const long long row = row0 + u * rows_per_wave;
+            live[u] = row < rows && sub < lpr;
+            f[u] = b[u] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            if (live[u]) {
+                const v4f fv = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(F + row * Dr + 4 * sub));
+                const v4f bv = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(Bv + row * Dr + 4 * sub));
+                f[u] = make_float4(fv.x, fv.y, fv.z, fv.w);
+                b[u] = make_float4(bv.x, bv.y, bv.z, bv.w);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < STREAM_UNROLL; ++u) {
+            g[u][0] = f[u].x * b[u].x; g[u][1] = f[u].y * b[u].y; g[u][2] = f[u].z * b[u].z; g[u][3] = f[u].w * b[u].w;
+        }
+    } else {
+#pragma unroll
+        for (int u = 0; u < STREAM_UNROLL; ++u) {
+            const long long row = row0 + u * rows_per_wave;
+            live[u] = row < rows && sub < lpr;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int j = 4 * sub + q;
+                g[u][q] = (live[u] && j < Dr) ? F[row * Dr + j] * Bv[row * Dr + j] : 0.0f;
+            }
         }
     }
-    float s = g[0] + g[1] + g[2] + g[3];
-    for (int d = 1; d < width; d <<= 1) s += __shfl_xor(s, d, 64);
-    if (live) {
-        const float inv = 1.0f / s;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int j = 4 * sub + q;
-            if (j < Dr) marg[row * Dr + j] = g[q] * inv;
+    for (int u = 0; u < STREAM_UNROLL; ++u) {
+        const long long row = row0 + u * rows_per_wave;
+        float s = g[u][0] + g[u][1] + g[u][2] + g[u][3];
+        for (int d = 1; d < width; d <<= 1) s += __shfl_xor(s, d, 64);
+        if (live[u]) {
+            const float inv = 1.0f / s;
+            if ((Dr & 3) == 0) {
+                const v4f out = {g[u][0] * inv, g[u][1] * inv, g[u][2] * inv, g[u][3] * inv};
+                __builtin_nontemporal_store(out, reinterpret_cast<v4f*>(marg + row * Dr + 4 * sub));
+            } else {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int j = 4 * sub + q;
+                    if (j < Dr) marg[row * Dr + j] = g[u][q] * inv;
+                }
+            }
         }
     }
 }
@@ -1221,7 +1327,7 @@ static int large_smooth_impl(const LargeArgs& a, float* marg, float* filt, doubl
     {
         int width = 1;
         while (width < (a.D + 3) / 4) width <<= 1;
-        const long long rpb = 4LL * (64 / width);   // rows per workgroup
+        const long long rpb = 4LL * STREAM_UNROLL * (64 / width);   // rows per workgroup
         launch("ld_rowmax", ld_rowmax_kernel, dim3((unsigned)((rows + rpb - 1) / rpb)), block, st, a.ll, rows, a.D, rowmax);
     }
     launch("ld_aggregate", ld_aggregate_kernel<D>, dim3((unsigned)((p.nchunks + C::CPW - 1) / C::CPW)), block, st, a.A,
@@ -1248,7 +1354,7 @@ static int large_smooth_impl(const LargeArgs& a, float* marg, float* filt, doubl
     const int lpr = (a.D + 3) / 4;
     int width = 1;
     while (width < lpr) width <<= 1;
-    const long long rows_per_block = 4LL * (64 / width);
+    const long long rows_per_block = 4LL * STREAM_UNROLL * (64 / width);
     launch("ld_combine", ld_combine_kernel, dim3((unsigned)((rows + rows_per_block - 1) / rows_per_block)), block, st, F, Bv,
            rows, a.D, marg);
     launch("ld_finalize", ld_finalize_kernel, dim3((unsigned)a.batch), block, st, part, p.cps, loglik_out);
@@ -1309,7 +1415,7 @@ static int large_element_sp_impl(const LargeArgs& a, float* element, double* log
     {
         int width = 1;
         while (width < (a.D + 3) / 4) width <<= 1;
-        const long long rpb = 4LL * (64 / width);
+        const long long rpb = 4LL * STREAM_UNROLL * (64 / width);
         launch("ld_rowmax", ld_rowmax_kernel, dim3((unsigned)((rows + rpb - 1) / rpb)), block, st, a.ll, rows, a.D, rowmax);
     }
     launch("ld_aggregate", ld_aggregate_kernel<D>, dim3((unsigned)((p.nchunks + C::CPW - 1) / C::CPW)), block, st, a.A,
