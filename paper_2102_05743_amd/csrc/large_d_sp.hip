@@ -891,16 +891,70 @@ __global__ __launch_bounds__(256) void ld_apply_kernel(const float* __restrict__
 // Sixteen chunks advance per workgroup, independently; the normaliser of a step is computed beside
 // the next step's products and applied one step late, so a step's dependent chain is the products
 // and two multiplications.  First half of the grid: forward chunks, second half: backward chunks.
-template <int NQ, int QS, int R>
+// acc[r & 3] += (x rotated by r lanes inside its DPP row) * a[r] for r = 0..15: sixteen multiply-adds
+// whose first operand is read through the DPP rotation itself (v_fmac_f32 with a row_ror modifier),
+// so no instruction is spent on moving data.  Written out because the compiler emits a separate DPP
+// move per term here.  The leading s_nop covers the wait states a DPP read needs after a vector
+// instruction wrote its source register (or EXEC); nothing inside the block rewrites x.
+HMM_DEV void row_dot16(float x, const float* a, float (&acc)[4]) {
+    asm volatile(
+        "s_nop 4\n\t"
+        "v_fmac_f32 %0, %4, %5\n\t"
+        "v_fmac_f32_dpp %1, %4, %6 row_ror:1 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %2, %4, %7 row_ror:2 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %3, %4, %8 row_ror:3 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %0, %4, %9 row_ror:4 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %1, %4, %10 row_ror:5 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %2, %4, %11 row_ror:6 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %3, %4, %12 row_ror:7 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %0, %4, %13 row_ror:8 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %1, %4, %14 row_ror:9 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %2, %4, %15 row_ror:10 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %3, %4, %16 row_ror:11 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %0, %4, %17 row_ror:12 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %1, %4, %18 row_ror:13 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %2, %4, %19 row_ror:14 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %3, %4, %20 row_ror:15 row_mask:0xf bank_mask:0xf"
+        : "+v"(acc[0]), "+v"(acc[1]), "+v"(acc[2]), "+v"(acc[3])
+        : "v"(x), "v"(a[0]), "v"(a[1]), "v"(a[2]), "v"(a[3]), "v"(a[4]), "v"(a[5]), "v"(a[6]), "v"(a[7]), "v"(a[8]),
+          "v"(a[9]), "v"(a[10]), "v"(a[11]), "v"(a[12]), "v"(a[13]), "v"(a[14]), "v"(a[15]));
+}
+
+// The same starting the four accumulators (plain products for r = 0..3), so that they need no zeroing.
+// Outputs are early-clobber: they are written while inputs are still to be read.
+HMM_DEV void row_dot16_first(float x, const float* a, float (&acc)[4]) {
+    asm volatile(
+        "s_nop 4\n\t"
+        "v_mul_f32 %0, %4, %5\n\t"
+        "v_mul_f32_dpp %1, %4, %6 row_ror:1 row_mask:0xf bank_mask:0xf\n\t"
+        "v_mul_f32_dpp %2, %4, %7 row_ror:2 row_mask:0xf bank_mask:0xf\n\t"
+        "v_mul_f32_dpp %3, %4, %8 row_ror:3 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %0, %4, %9 row_ror:4 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %1, %4, %10 row_ror:5 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %2, %4, %11 row_ror:6 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %3, %4, %12 row_ror:7 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %0, %4, %13 row_ror:8 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %1, %4, %14 row_ror:9 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %2, %4, %15 row_ror:10 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %3, %4, %16 row_ror:11 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %0, %4, %17 row_ror:12 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %1, %4, %18 row_ror:13 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %2, %4, %19 row_ror:14 row_mask:0xf bank_mask:0xf\n\t"
+        "v_fmac_f32_dpp %3, %4, %20 row_ror:15 row_mask:0xf bank_mask:0xf"
+        : "=&v"(acc[0]), "=&v"(acc[1]), "=&v"(acc[2]), "=&v"(acc[3])
+        : "v"(x), "v"(a[0]), "v"(a[1]), "v"(a[2]), "v"(a[3]), "v"(a[4]), "v"(a[5]), "v"(a[6]), "v"(a[7]), "v"(a[8]),
+          "v"(a[9]), "v"(a[10]), "v"(a[11]), "v"(a[12]), "v"(a[13]), "v"(a[14]), "v"(a[15]));
+}
+
+// acc[qd] = terms of the product with the constant matrix held as a[(qs, qd, r)] (see the kernel below)
+template <int NQ>
 HMM_DEV void row_matvec_terms(const float (&h)[NQ], const float (&a)[NQ * NQ * 16], float (&acc)[NQ][4]) {
-    if constexpr (R < 16) {
-        const float x = row_rot<R>(h[QS]);
 #pragma unroll
-        for (int qd = 0; qd < NQ; ++qd) acc[qd][R & 3] = fmaf(x, a[(QS * NQ + qd) * 16 + R], acc[qd][R & 3]);
-        row_matvec_terms<NQ, QS, R + 1>(h, a, acc);
-    } else if constexpr (QS + 1 < NQ) {
-        row_matvec_terms<NQ, QS + 1, 0>(h, a, acc);
-    }
+    for (int qd = 0; qd < NQ; ++qd) row_dot16_first(h[0], &a[qd * 16], acc[qd]);
+#pragma unroll
+    for (int qs = 1; qs < NQ; ++qs)
+#pragma unroll
+        for (int qd = 0; qd < NQ; ++qd) row_dot16(h[qs], &a[(qs * NQ + qd) * 16], acc[qd]);
 }
 
 template <int D>
@@ -981,7 +1035,10 @@ __global__ __launch_bounds__(256) void ld_apply_row_kernel(const float* __restri
     for (int q = 1; q < NQ; ++q) hs += h[q];
     // forward: every chunk but the sequence's first starts from a vector summing to one; backward: any scale
     float inv = (!backward && first_chunk) ? 1.0f : __builtin_amdgcn_rcpf(row_allsum(hs));
-    float msum = 0.0f, lsum = 0.0f;
+    // chunk evidence: sum of the steps' emission maxima, and the product of the steps' normalisers kept as
+    // mantissa and binary exponent (one logarithm per chunk instead of one per step)
+    float msum = 0.0f, cmant = 1.0f;
+    int cexp = 0;
     for (int p0 = 0; p0 < Lc; p0 += PFD) {
 #pragma unroll
         for (int p = 0; p < PFD; ++p) {
@@ -1000,9 +1057,7 @@ __global__ __launch_bounds__(256) void ld_apply_row_kernel(const float* __restri
             if (!backward) {
                 float g[NQ];
                 float acc[NQ][4];
-#pragma unroll
-                for (int q = 0; q < NQ; ++q) acc[q][0] = acc[q][1] = acc[q][2] = acc[q][3] = 0.0f;
-                row_matvec_terms<NQ, 0, 0>(h, a, acc);
+                row_matvec_terms<NQ>(h, a, acc);
 #pragma unroll
                 for (int q = 0; q < NQ; ++q) {
                     const float moved = ((acc[q][0] + acc[q][1]) + (acc[q][2] + acc[q][3])) * inv;
@@ -1022,7 +1077,9 @@ __global__ __launch_bounds__(256) void ld_apply_row_kernel(const float* __restri
                     op += stride;
                     inv = ic;
                     msum += mm;
-                    lsum += __logf(c);
+                    const float cp = cmant * c;
+                    cmant = __builtin_amdgcn_frexp_mantf(cp);
+                    cexp += __builtin_amdgcn_frexp_expf(cp);
                 }
             } else {
                 float bs[NQ], u[NQ];
@@ -1036,9 +1093,7 @@ __global__ __launch_bounds__(256) void ld_apply_row_kernel(const float* __restri
                 for (int q = 1; q < NQ; ++q) ss += bs[q];
                 const float ic = __builtin_amdgcn_rcpf(row_allsum(ss));
                 float acc[NQ][4];
-#pragma unroll
-                for (int q = 0; q < NQ; ++q) acc[q][0] = acc[q][1] = acc[q][2] = acc[q][3] = 0.0f;
-                row_matvec_terms<NQ, 0, 0>(u, a, acc);
+                row_matvec_terms<NQ>(u, a, acc);
                 if (active) {
 #pragma unroll
                     for (int q = 0; q < NQ; ++q) {
@@ -1051,7 +1106,8 @@ __global__ __launch_bounds__(256) void ld_apply_row_kernel(const float* __restri
             }
         }
     }
-    if (!backward && cc.nsteps > 0 && l == 0) part[chunk] = (double)msum + (double)lsum;
+    if (!backward && cc.nsteps > 0 && l == 0)
+        part[chunk] = (double)msum + (double)logf(cmant) + 0.6931471805599453 * (double)cexp;
 }
 
 // ---------------------------------------------------------------------------------------------
