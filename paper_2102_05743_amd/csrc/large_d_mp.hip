@@ -491,6 +491,130 @@ __global__ __launch_bounds__(256) void lv_forward_kernel(const float* __restrict
     }
 }
 
+// t[r] = V((l - r) mod 16) + la[r] for the sixteen rotations of a DPP row
+template <int R>
+HMM_DEV void row_candidates(float v, const float (&la)[16], float (&t)[16]) {
+    if constexpr (R < 16) {
+        t[R] = row_rotate<R>(v) + la[R];
+        row_candidates<R + 1>(v, la, t);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// The same for D = 16 with one chunk per DPP row of 16 lanes (sixteen chunks per workgroup) and no
+// barrier: lane l holds V(l) of its chunk, the candidates V(k) + log A(k, l) with k = (l - r) mod 16
+// arrive as the row's vector rotated by r lanes (an operand modifier of the add), their maximum is a
+// chain of three-way maxima, and the back-pointer is the lowest k among the candidates that equal it.
+// The row's maximum (the next step's offset) is four rotate-and-max steps off the critical path.
+// Log-likelihoods are prefetched PFD steps ahead through a running pointer that stops at the
+// chunk's last step.
+template <int D>
+__global__ __launch_bounds__(256) void lv_forward_row_kernel(const float* __restrict__ prior, const float* __restrict__ A,
+                                                             const float* __restrict__ ll, long long T, int Dr, int Lc,
+                                                             int cps, long long nchunks, int shared_model,
+                                                             const float* __restrict__ vin, uint8_t* __restrict__ bp,
+                                                             uint8_t* __restrict__ cmap, int* __restrict__ xstar,
+                                                             double* __restrict__ part) {
+    static_assert(D == 16, "one DPP row per chunk");
+    constexpr int PFD = 8;
+    extern __shared__ __align__(16) unsigned char dyn_lds[];   // back-pointers: [16 chunks][Lc][16]
+    const int l = threadIdx.x & 15, cl = threadIdx.x >> 4;
+    const long long chunk = (long long)blockIdx.x * 16 + cl;
+    const ChunkCoord cc = chunk_coord(chunk, nchunks, cps, T, Lc);
+    const float* Am = A + (shared_model ? 0 : (size_t)cc.seq * Dr * Dr);
+    uint8_t* bpl = dyn_lds + (size_t)cl * Lc * D;
+    float la[16];
+    unsigned kr[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int k = (l - r) & 15;
+        float v = (k == l) ? 0.0f : -INFINITY;
+        if (k < Dr && l < Dr) v = safe_log(Am[(size_t)k * Dr + l]);
+        la[r] = v;
+        kr[r] = (unsigned)k;
+    }
+    const bool live = cc.nsteps > 0;
+    const bool first_chunk = (chunk % cps) == 0;
+    float v = -INFINITY;
+    if (live) {
+        if (first_chunk) v = (l < Dr) ? safe_log(prior[(shared_model ? 0 : (size_t)cc.seq * Dr) + l]) : -INFINITY;
+        else v = vin[(size_t)chunk * D + l];
+    }
+    // level the chunk starts from: 0 for the log prior, else the carry's maximum
+    float start = 0.0f;
+    if (!first_chunk) {
+        start = row_allmax(v);
+        start = (start == -INFINITY) ? 0.0f : start;
+    }
+    float off = start;
+    double osum = 0.0;
+    const float* lp = ll + ((size_t)cc.seq * T + cc.t0) * Dr + (l < Dr ? l : 0);
+    int fetched = 0;
+    float xq[PFD];
+    auto fetch = [&](float& x) {
+        x = *lp;
+        ++fetched;
+        if (fetched < cc.nsteps) lp += Dr;
+    };
+#pragma unroll
+    for (int p = 0; p < PFD; ++p) fetch(xq[p]);
+    for (int s0 = 0; s0 < Lc; s0 += PFD) {
+#pragma unroll
+        for (int p = 0; p < PFD; ++p) {
+            const int s = s0 + p;
+            const bool active = s < cc.nsteps;
+            const float x = (l < Dr) ? xq[p] : -INFINITY;
+            fetch(xq[p]);
+            float t[16];
+            row_candidates<0>(v, la, t);
+            float best = max3f(t[0], t[1], t[2]);
+#pragma unroll
+            for (int r = 3; r < 15; r += 2) best = max3f(best, t[r], t[r + 1]);
+            best = fmaxf(best, t[15]);
+            unsigned arg = 255u;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) arg = min(arg, (t[r] == best) ? kr[r] : 255u);   // lowest state among the maximisers
+            const bool seq_start = (cc.t0 + s == 0);            // V_1 = log prior + ll_1: no transition, no offset
+            const float gval = seq_start ? v + x : best + (x - off);
+            if (active) {
+                bpl[(size_t)s * D + l] = (uint8_t)(seq_start ? (unsigned)l : arg);
+                const float m = row_allmax(gval);
+                osum += (double)(seq_start ? 0.0f : off);
+                off = (m == -INFINITY) ? 0.0f : m;
+                v = gval;
+            }
+        }
+    }
+    if (live && l == 0) part[chunk] = osum + (double)off - (double)start;
+    wave_lds_sync();   // the chunk's back-pointers were written by its own row of lanes
+    if (live) {
+        uint8_t* dst = bp + ((size_t)cc.seq * T + cc.t0) * D;
+        const int nbytes = cc.nsteps * D;
+        for (int idx = l * 4; idx < nbytes; idx += 64)
+            *reinterpret_cast<uint32_t*>(dst + idx) = *reinterpret_cast<const uint32_t*>(bpl + idx);
+    }
+    // x*_T in the sequence's last chunk: argmax over the row, lowest index on ties
+    const bool last_chunk = live && (chunk % cps) == cps - 1;
+    float bv = v;
+    int bi = l;
+#pragma unroll
+    for (int d = 1; d < 16; d <<= 1) {
+        const float ob = __shfl_xor(bv, d, 64);
+        const int oi = __shfl_xor(bi, d, 64);
+        const bool take = (ob > bv) || (ob == bv && oi < bi);
+        bv = take ? ob : bv;
+        bi = take ? oi : bi;
+    }
+    if (last_chunk && l == 0) xstar[cc.seq] = bi;
+    // chunk map: state at the step before the chunk given state l at its last step (in the last chunk every
+    // state maps to the image of x*_T)
+    if (live) {
+        int hm = last_chunk ? bi : l;
+        for (int s = cc.nsteps - 1; s >= 0; --s) hm = bpl[(size_t)s * D + hm];
+        cmap[(size_t)chunk * D + l] = (uint8_t)hm;
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
 // State at every chunk's last step (chunk maps applied right to left from x*_T) and the
 // sequence's log-probability.  One workgroup per sequence; the maps are chased through LDS.
@@ -867,6 +991,10 @@ __global__ __launch_bounds__(256) void lv_element_finish_kernel(const float* __r
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 // Chunking for the max-plus path: the back-pointers of a chunk must fit in LDS (Lc * DP <= 48 KiB).
+// D = 16 with chunks of at most ROW_FORWARD_MAX_LC steps (batches of sequences, which need few chunks each) runs
+// the forward recursion with one chunk per DPP row, sixteen chunks' back-pointers per workgroup.
+constexpr int ROW_FORWARD_MAX_LC = 192;
+
 static LargePlan viterbi_plan(int Dr, long long T, int batch) {
     LargePlan p = large_plan(Dr, T, batch);
     const int vcpw = p.DP >= 128 ? 1 : p.DP >= 64 ? 2 : 4;   // chunks sharing a workgroup in the forward kernel
@@ -926,9 +1054,20 @@ static int large_viterbi_impl(const LargeArgs& a, int32_t* path, double* logprob
     else
         launch("lv_carry", lv_carry_kernel<D>, dim3((unsigned)a.batch), block, st, a.prior, a.D, p.cps, a.shared_model,
                agg, vin, static_cast<const float*>(nullptr), static_cast<float*>(nullptr));
-    const size_t fwd_lds = (size_t)C::VCPW * p.Lc * D;
-    launch_dyn("lv_forward", lv_forward_kernel<D>, dim3((unsigned)((p.nchunks + C::VCPW - 1) / C::VCPW)), block, fwd_lds,
-               st, a.prior, a.A, a.ll, a.T, a.D, p.Lc, p.cps, p.nchunks, a.shared_model, vin, bp, cmap, xstar, part);
+    bool row_forward = false;
+    if constexpr (D == 16) {
+        if (p.Lc <= ROW_FORWARD_MAX_LC) {
+            row_forward = true;
+            launch_dyn("lv_forward", lv_forward_row_kernel<D>, dim3((unsigned)((p.nchunks + 15) / 16)), block,
+                       (size_t)16 * p.Lc * D, st, a.prior, a.A, a.ll, a.T, a.D, p.Lc, p.cps, p.nchunks, a.shared_model, vin, bp,
+                       cmap, xstar, part);
+        }
+    }
+    if (!row_forward) {
+        const size_t fwd_lds = (size_t)C::VCPW * p.Lc * D;
+        launch_dyn("lv_forward", lv_forward_kernel<D>, dim3((unsigned)((p.nchunks + C::VCPW - 1) / C::VCPW)), block, fwd_lds,
+                   st, a.prior, a.A, a.ll, a.T, a.D, p.Lc, p.cps, p.nchunks, a.shared_model, vin, bp, cmap, xstar, part);
+    }
     launch("lv_suffix", lv_suffix_kernel<D>, dim3((unsigned)a.batch), block, st, cmap, xstar, p.cps, xend, part,
            logprob_out);
     const size_t path_lds = (size_t)p.Lc * D + (size_t)p.Lc * sizeof(int32_t);
