@@ -102,6 +102,53 @@ __global__ __launch_bounds__(256) void lv_aggregate_systolic_kernel(const float*
             la[16 * q + r] = v;
         }
     const float* lseq = ll + (size_t)cc.seq * T * Dr;
+    if constexpr (D == 16) {
+        // One column block: the row P(i, .) that a DPP row of lanes rotates is exactly what its lanes hold,
+        // so P never leaves the registers (four rows per DPP row of lanes), and its maximum is taken off
+        // every fourth step only.
+        float pr[RPD];
+#pragma unroll
+        for (int r = 0; r < RPD; ++r) pr[r] = (rs * RPD + r == j) ? 0.0f : -INFINITY;
+        float off = 0.0f;
+        double offsum = 0.0;
+        float xn = -INFINITY;
+        if (j < Dr && cc.nsteps > 0) xn = lseq[(size_t)cc.t0 * Dr + j];
+        for (int s = 0; s < cc.nsteps; ++s) {
+            const float add = xn - off;
+            if (s + 1 < cc.nsteps && j < Dr) xn = lseq[(size_t)(cc.t0 + s + 1) * Dr + j];
+            const bool no_transition = (cc.t0 + s == 0);
+            float lmax = -INFINITY;
+#pragma unroll
+            for (int r = 0; r < RPD; ++r) {
+                float acc = pr[r];   // neutral element so far: P(i, j) itself
+                if (!no_transition) {
+                    const float one[1] = {pr[r]};
+                    acc = -INFINITY;
+                    systolic_terms<D, 0, 0>(one, la, acc);
+                }
+                pr[r] = acc + add;
+                lmax = fmaxf(lmax, pr[r]);
+            }
+            off = 0.0f;
+            if ((s & 3) == 3 || s == cc.nsteps - 1) {
+                const float m = wave_max(lmax);
+                off = (m == -INFINITY) ? 0.0f : m;
+                offsum += (double)off;
+            }
+        }
+        if (cc.nsteps > 0) {
+            if (agg_off != nullptr && lane == 0) agg_off[chunk] = offsum;
+            float* dst = agg + (size_t)chunk * D * D;
+#pragma unroll
+            for (int r = 0; r < RPD; ++r) {
+                const int i = rs * RPD + r;
+                const float val = pr[r] - off;
+                dst[(size_t)j * D + i] = val;   // stored transposed, as the one-wave carry reads it
+                if (agg_other != nullptr) agg_other[(size_t)chunk * D * D + (size_t)i * D + j] = val;
+            }
+        }
+        return;
+    }
     float* p0 = pbuf + cl * 2 * D * D;
     float* p1 = p0 + D * D;
     // neutral element: 0 on the diagonal, -inf elsewhere; element (i, k) lives at i*D + (k%16)*NQ + k/16
