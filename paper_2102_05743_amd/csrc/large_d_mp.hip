@@ -1051,6 +1051,22 @@ static LargePlan viterbi_plan(int Dr, long long T, int batch) {
         p.cps = (int)((T + p.Lc - 1) / p.Lc);
         p.nchunks = (long long)p.cps * batch;
     }
+    // From D = 32 the aggregate kernel runs one workgroup per chunk, all resident at once: a chunk count
+    // just above a multiple of the 256 compute units leaves most of them idle while a few work through one
+    // chunk more (713 chunks take as long as 768).  Shorten the chunks so that the count fills the last round.
+    if (p.DP >= 32 && p.nchunks > 256 && p.nchunks % 256 != 0) {
+        const long long target = (p.nchunks + 255) / 256 * 256;
+        const long long cps_t = target / batch;
+        if (cps_t >= 1) {
+            long long Lc = (T + cps_t - 1) / cps_t;
+            Lc = (Lc + 7) / 8 * 8;
+            if (Lc >= 32 && Lc <= p.Lc) {
+                p.Lc = (int)Lc;
+                p.cps = (int)((T + p.Lc - 1) / p.Lc);
+                p.nchunks = (long long)p.cps * batch;
+            }
+        }
+    }
     return p;
 }
 
