@@ -68,13 +68,10 @@ HMM_DEV void systolic_terms(const float (&pr)[D / 16], const float (&la)[D], flo
     }
 }
 
-template <int D>
-__global__ __launch_bounds__(256) void lv_aggregate_systolic_kernel(const float* __restrict__ A,
-                                                                    const float* __restrict__ ll, long long T, int Dr,
-                                                                    int Lc, int cps, long long nchunks,
-                                                                    int shared_model, float* __restrict__ agg,
-                                                                    float* __restrict__ agg_other,
-                                                                    double* __restrict__ agg_off) {
+template <int D, bool WITH_OFFSETS>
+HMM_DEV void lv_aggregate_systolic_body(const float* __restrict__ A, const float* __restrict__ ll, long long T, int Dr,
+                                        int Lc, int cps, long long nchunks, int shared_model, float* __restrict__ agg,
+                                        float* __restrict__ agg_other, double* __restrict__ agg_off) {
     constexpr int NQ = D / 16;             // column blocks = registers per lane for one row of P
     constexpr int WPCH = MpCfg<D>::WPC;    // waves per chunk: a workgroup for D >= 32, else one wave
     constexpr int CPWG = 4 / WPCH;         // chunks per workgroup
@@ -137,7 +134,9 @@ __global__ __launch_bounds__(256) void lv_aggregate_systolic_kernel(const float*
             }
         }
         if (cc.nsteps > 0) {
-            if (agg_off != nullptr && lane == 0) agg_off[chunk] = offsum;
+            if constexpr (WITH_OFFSETS) {
+                if (lane == 0) agg_off[chunk] = offsum;
+            }
             float* dst = agg + (size_t)chunk * D * D;
 #pragma unroll
             for (int r = 0; r < RPD; ++r) {
@@ -208,12 +207,14 @@ __global__ __launch_bounds__(256) void lv_aggregate_systolic_kernel(const float*
             chunk_sync<D>();
         }
         off = (m == -INFINITY) ? 0.0f : m;
-        offsum += (double)off;
+        if constexpr (WITH_OFFSETS) offsum += (double)off;
         cur ^= 1;
     }
     if (cc.nsteps > 0) {
         // what the rescalings removed, for callers that need the aggregate's absolute level
-        if (agg_off != nullptr && (wave % WPCH) == 0 && lane == 0) agg_off[chunk] = offsum;
+        if constexpr (WITH_OFFSETS) {
+            if ((wave % WPCH) == 0 && lane == 0) agg_off[chunk] = offsum;
+        }
         const float* pf = cur ? p1 : p0;
         float* dst = agg + (size_t)chunk * D * D;
         for (int r = 0; r < RPD; ++r) {
@@ -226,6 +227,25 @@ __global__ __launch_bounds__(256) void lv_aggregate_systolic_kernel(const float*
                 agg_other[(size_t)chunk * D * D + ((D <= 32) ? ((size_t)i * D + j) : ((size_t)j * D + i))] = val;
         }
     }
+}
+
+template <int D>
+__global__ __launch_bounds__(256) void lv_aggregate_systolic_kernel(const float* __restrict__ A,
+                                                                    const float* __restrict__ ll, long long T, int Dr,
+                                                                    int Lc, int cps, long long nchunks,
+                                                                    int shared_model, float* __restrict__ agg,
+                                                                    float* __restrict__ agg_other) {
+    lv_aggregate_systolic_body<D, false>(A, ll, T, Dr, Lc, cps, nchunks, shared_model, agg, agg_other, nullptr);
+}
+
+// The same, also recording per chunk what the rescalings removed (block-wise elements need the
+// aggregates' absolute level).
+template <int D>
+__global__ __launch_bounds__(256) void lv_aggregate_offsets_kernel(const float* __restrict__ A, const float* __restrict__ ll,
+                                                                   long long T, int Dr, int Lc, int cps, long long nchunks,
+                                                                   int shared_model, float* __restrict__ agg,
+                                                                   double* __restrict__ agg_off) {
+    lv_aggregate_systolic_body<D, true>(A, ll, T, Dr, Lc, cps, nchunks, shared_model, agg, nullptr, agg_off);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1109,8 +1129,7 @@ static int large_viterbi_impl(const LargeArgs& a, int32_t* path, double* logprob
     hipStream_t st = a.stream;
     const dim3 block(256);
     launch("lv_aggregate", lv_aggregate_systolic_kernel<D>, dim3((unsigned)((p.nchunks + M::CPW - 1) / M::CPW)), block,
-           st, a.A, a.ll, a.T, a.D, p.Lc, p.cps, p.nchunks, a.shared_model, agg, static_cast<float*>(nullptr),
-           static_cast<double*>(nullptr));
+           st, a.A, a.ll, a.T, a.D, p.Lc, p.cps, p.nchunks, a.shared_model, agg, static_cast<float*>(nullptr));
     if constexpr (D <= 32)
         launch("lv_carry", lv_carry_wave_kernel<D>, dim3((unsigned)a.batch), dim3(64), st, a.prior, a.D, p.cps,
                a.shared_model, agg, vin, static_cast<const float*>(nullptr), static_cast<float*>(nullptr));
@@ -1179,8 +1198,7 @@ static int large_max_product_impl(const LargeArgs& a, float* mm, int32_t* path, 
     hipStream_t st = a.stream;
     const dim3 block(256);
     launch("lv_aggregate", lv_aggregate_systolic_kernel<D>, dim3((unsigned)((p.nchunks + M::CPW - 1) / M::CPW)), block,
-           st, a.A, a.ll, a.T, a.D, p.Lc, p.cps, p.nchunks, a.shared_model, agg, agg_other,
-           static_cast<double*>(nullptr));
+           st, a.A, a.ll, a.T, a.D, p.Lc, p.cps, p.nchunks, a.shared_model, agg, agg_other);
     if constexpr (D <= 32)
         launch("lm_carry", lv_carry_wave_kernel<D>, dim3(2u * (unsigned)a.batch), dim3(64), st, a.prior, a.D, p.cps,
                a.shared_model, agg, vin, static_cast<const float*>(agg_other), bout);
@@ -1235,8 +1253,8 @@ static int large_element_mp_impl(const LargeArgs& a, float* element, double* log
     double* off = reinterpret_cast<double*>(ws + w.off);
     hipStream_t st = a.stream;
     const dim3 block(256);
-    launch("lv_aggregate", lv_aggregate_systolic_kernel<D>, dim3((unsigned)((p.nchunks + M::CPW - 1) / M::CPW)), block,
-           st, a.A, a.ll, a.T, a.D, p.Lc, p.cps, p.nchunks, a.shared_model, agg, static_cast<float*>(nullptr), off);
+    launch("lv_aggregate", lv_aggregate_offsets_kernel<D>, dim3((unsigned)((p.nchunks + M::CPW - 1) / M::CPW)), block,
+           st, a.A, a.ll, a.T, a.D, p.Lc, p.cps, p.nchunks, a.shared_model, agg, off);
     constexpr int transposed = (D <= 32) ? 1 : 0;   // orientation in which the aggregate kernel stores its results
     const float* cur = agg;
     const double* curo = off;
