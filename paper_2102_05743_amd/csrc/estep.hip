@@ -14,10 +14,9 @@
 
 #include "estep.hpp"
 #include "ktimer.hpp"
+#include "large_d_device.hpp"
 
 namespace hmm {
-
-#define HMM_DEV __device__ __forceinline__
 
 // transitions k = 1..T-1 (0-based step index of the later state) of one sequence, split over G workgroups
 struct StepRange { long long k0, k1; };
@@ -160,6 +159,96 @@ __global__ __launch_bounds__(256) void tc_large_kernel(const float* __restrict__
             partial[(size_t)blockIdx.x * DP * DP + (size_t)(ti * TT + r) * DP + tj * TT + c] = acc[r][c] * a[r][c];
 }
 
+// ---------------------------------------------------------------------------------------------
+// 9 <= D <= 32 (padded to DP = 16 or 32): one time step per DPP row of 16 lanes, sixteen steps per
+// workgroup round, no LDS in the loop.  Lane l holds components 16 q + l of fh_{k-1} and gamma_k.  Both the
+// prediction pred_k(j) = sum_i fh_{k-1}(i) A(i,j) and the outer product fh_{k-1}(i) w_k(j) pair component
+// (l - r) mod 16 of one vector with component l of another: the first operand of a multiply-add read
+// through a rotation of the row by r lanes.  The lane accumulates entry (16 qs + (l - r) mod 16, 16 qd + l)
+// in acc[(qs, qd)][r].  Steps are independent, so four of a row's steps have their loads in flight at once.
+template <int DP>
+__global__ __launch_bounds__(256) void tc_row_kernel(const float* __restrict__ A, const float* __restrict__ filt,
+                                                     const float* __restrict__ marg, long long T, int Dr, int G,
+                                                     int shared_model, float* __restrict__ partial) {
+    static_assert(DP == 16 || DP == 32, "one DPP row per step");
+    constexpr int NQ = DP / 16;
+    constexpr int UNR = 4;
+    __shared__ float red[4 * DP * DP];
+    const int seq = blockIdx.x / G, g = blockIdx.x % G;
+    const StepRange sr = step_range(T, G, g);
+    const int l = threadIdx.x & 15, row = threadIdx.x >> 4;
+    const float* Am = A + (shared_model ? 0 : (size_t)seq * Dr * Dr);
+    float a[NQ * NQ * 16];
+#pragma unroll
+    for (int qs = 0; qs < NQ; ++qs)
+#pragma unroll
+        for (int qd = 0; qd < NQ; ++qd)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int i = 16 * qs + ((l - r) & 15), j = 16 * qd + l;
+                a[(qs * NQ + qd) * 16 + r] = (i < Dr && j < Dr) ? Am[(size_t)i * Dr + j] : 0.0f;
+            }
+    float acc[NQ * NQ][16];
+#pragma unroll
+    for (int b = 0; b < NQ * NQ; ++b)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[b][r] = 0.0f;
+    const float* fs = filt + (size_t)seq * T * Dr;
+    const float* ms = marg + (size_t)seq * T * Dr;
+    int col[NQ];
+    bool have[NQ];
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) { have[q] = 16 * q + l < Dr; col[q] = have[q] ? 16 * q + l : 0; }
+    for (long long kb = sr.k0 + row; kb < sr.k1; kb += 16 * UNR) {
+        float f[UNR][NQ], gm[UNR][NQ];
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const long long k = kb + 16 * u;
+            const long long kc = k < sr.k1 ? k : sr.k1 - 1;   // past the range: a valid step, contribution masked below
+#pragma unroll
+            for (int q = 0; q < NQ; ++q) {
+                f[u][q] = fs[(size_t)(kc - 1) * Dr + col[q]];
+                gm[u][q] = ms[(size_t)kc * Dr + col[q]];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const bool valid = kb + 16 * u < sr.k1;
+            float fv[NQ];
+#pragma unroll
+            for (int q = 0; q < NQ; ++q) fv[q] = (valid && have[q]) ? f[u][q] : 0.0f;
+            float pp[NQ][4];
+            row_matvec_terms<NQ>(fv, a, pp);
+#pragma unroll
+            for (int qd = 0; qd < NQ; ++qd) {
+                const float pred = (pp[qd][0] + pp[qd][1]) + (pp[qd][2] + pp[qd][3]);
+                const float w = (pred > 0.0f && have[qd]) ? gm[u][qd] * __builtin_amdgcn_rcpf(pred) : 0.0f;
+#pragma unroll
+                for (int qs = 0; qs < NQ; ++qs) row_outer16(fv[qs], w, acc[qs * NQ + qd]);
+            }
+        }
+    }
+    // entries times A(i, j), summed over the wave's four rows, then over the four waves through LDS
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int qs = 0; qs < NQ; ++qs)
+#pragma unroll
+        for (int qd = 0; qd < NQ; ++qd)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                float v = acc[qs * NQ + qd][r] * a[(qs * NQ + qd) * 16 + r];
+                v += __shfl_xor(v, 16, 64);
+                v += __shfl_xor(v, 32, 64);
+                if (lane < 16) {
+                    const int i = 16 * qs + ((l - r) & 15), j = 16 * qd + l;
+                    red[wave * DP * DP + i * DP + j] = v;
+                }
+            }
+    __syncthreads();
+    for (int e = threadIdx.x; e < DP * DP; e += 256)
+        partial[(size_t)blockIdx.x * DP * DP + e] = (red[e] + red[DP * DP + e]) + (red[2 * DP * DP + e] + red[3 * DP * DP + e]);
+}
+
 // counts[seq][i][j] = sum over the sequence's G partial sums, in fp64.  blockIdx.x = sequence,
 // blockIdx.y = group of EPB entries; the 256 threads are (entry, slice of the partial sums), slices
 // added in a fixed order.
@@ -216,6 +305,12 @@ static void launch_large(const EstepArgs& a, int G, float* partial) {
            a.marginals, a.T, a.D, G, a.shared_model, partial);
 }
 
+template <int DP>
+static void launch_row(const EstepArgs& a, int G, float* partial) {
+    launch("tc_accumulate", tc_row_kernel<DP>, dim3((unsigned)(a.batch * G)), dim3(256), a.stream, a.A, a.filtered,
+           a.marginals, a.T, a.D, G, a.shared_model, partial);
+}
+
 int transition_counts(const EstepArgs& a, double* counts) {
     const int G = groups_per_sequence(a.D, a.T, a.batch);
     if ((long long)a.batch * G > 0x7fffffffLL) return 2;
@@ -231,15 +326,15 @@ int transition_counts(const EstepArgs& a, double* counts) {
         case 6: launch_small<6>(a, G, partial); break;
         case 7: launch_small<7>(a, G, partial); break;
         case 8: launch_small<8>(a, G, partial); break;
-        case 16: launch_large<16>(a, G, partial); break;
-        case 32: launch_large<32>(a, G, partial); break;
+        case 16: launch_row<16>(a, G, partial); break;
+        case 32: launch_row<32>(a, G, partial); break;
         case 64: launch_large<64>(a, G, partial); break;
         case 128: launch_large<128>(a, G, partial); break;
         default: return 2;
     }
     const int E = a.D * a.D;
-    int EPB = 1;
-    while (EPB < E && EPB < 256) EPB <<= 1;
+    int EPB = 1;                       // entries per workgroup: few, so that many workgroups share the partial sums
+    while (EPB < E && EPB < 32) EPB <<= 1;
     launch("tc_reduce", tc_reduce_kernel, dim3((unsigned)a.batch, (unsigned)((E + EPB - 1) / EPB)), dim3(256), a.stream,
            (const float*)partial, G, PS, a.D, EPB, counts);
     return hipGetLastError() == hipSuccess ? 0 : 4;

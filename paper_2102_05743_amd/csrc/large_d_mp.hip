@@ -896,7 +896,10 @@ __global__ __launch_bounds__(256) void lm_apply_kernel(const float* __restrict__
 }
 
 // Theorem 4: max-marginal log psi~^f_k + log psi~^b_k, shifted so that the step's largest entry is 0,
-// and its maximiser (lowest state on ties).  A power-of-two group of lanes per step.
+// and its maximiser (lowest state on ties).  A power-of-two group of lanes per step; a wave takes
+// COMBINE_UNROLL groups of steps with all loads issued first (16-byte accesses when D is a multiple of four).
+constexpr int COMBINE_UNROLL = 4;
+
 __global__ __launch_bounds__(256) void lm_combine_kernel(const float* __restrict__ F, const float* __restrict__ Bv,
                                                          long long rows, int Dr, float* __restrict__ mm,
                                                          int32_t* __restrict__ path) {
@@ -906,37 +909,60 @@ __global__ __launch_bounds__(256) void lm_combine_kernel(const float* __restrict
     const int rows_per_wave = 64 / width;
     const int lane = threadIdx.x & 63;
     const long long wave = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
-    const long long row = wave * rows_per_wave + lane / width;
     const int sub = lane % width;
-    float g[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
-    const bool live = row < rows && sub < lpr;
-    if (live) {
+    const long long row0 = wave * (COMBINE_UNROLL * rows_per_wave) + lane / width;
+    float g[COMBINE_UNROLL][4];
+    bool live[COMBINE_UNROLL];
+    const bool vec = (Dr & 3) == 0;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int j = 4 * sub + q;
-            if (j < Dr) g[q] = F[row * Dr + j] + Bv[row * Dr + j];
+    for (int u = 0; u < COMBINE_UNROLL; ++u) {
+        const long long row = row0 + u * rows_per_wave;
+        live[u] = row < rows && sub < lpr;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) g[u][q] = -INFINITY;
+        if (live[u]) {
+            if (vec) {
+                const v4f f = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(F + row * Dr + 4 * sub));
+                const v4f b = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(Bv + row * Dr + 4 * sub));
+                g[u][0] = f.x + b.x; g[u][1] = f.y + b.y; g[u][2] = f.z + b.z; g[u][3] = f.w + b.w;
+            } else {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int j = 4 * sub + q;
+                    if (j < Dr) g[u][q] = F[row * Dr + j] + Bv[row * Dr + j];
+                }
+            }
         }
     }
-    float best = g[0];
-    int arg = 4 * sub;
 #pragma unroll
-    for (int q = 1; q < 4; ++q)
-        if (g[q] > best) { best = g[q]; arg = 4 * sub + q; }
-    for (int d = 1; d < width; d <<= 1) {
-        const float ob = __shfl_xor(best, d, 64);
-        const int oi = __shfl_xor(arg, d, 64);
-        const bool take = (ob > best) || (ob == best && oi < arg);
-        best = take ? ob : best;
-        arg = take ? oi : arg;
-    }
-    if (live) {
-        const float m = (best == -INFINITY) ? 0.0f : best;
+    for (int u = 0; u < COMBINE_UNROLL; ++u) {
+        const long long row = row0 + u * rows_per_wave;
+        float best = g[u][0];
+        int arg = 4 * sub;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int j = 4 * sub + q;
-            if (j < Dr) mm[row * Dr + j] = g[q] - m;
+        for (int q = 1; q < 4; ++q)
+            if (g[u][q] > best) { best = g[u][q]; arg = 4 * sub + q; }
+        for (int d = 1; d < width; d <<= 1) {
+            const float ob = __shfl_xor(best, d, 64);
+            const int oi = __shfl_xor(arg, d, 64);
+            const bool take = (ob > best) || (ob == best && oi < arg);
+            best = take ? ob : best;
+            arg = take ? oi : arg;
         }
-        if (sub == 0 && path != nullptr) path[row] = arg;
+        if (live[u]) {
+            const float m = (best == -INFINITY) ? 0.0f : best;
+            if (vec) {
+                const v4f out = {g[u][0] - m, g[u][1] - m, g[u][2] - m, g[u][3] - m};
+                __builtin_nontemporal_store(out, reinterpret_cast<v4f*>(mm + row * Dr + 4 * sub));
+            } else {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int j = 4 * sub + q;
+                    if (j < Dr) mm[row * Dr + j] = g[u][q] - m;
+                }
+            }
+            if (sub == 0 && path != nullptr) path[row] = arg;
+        }
     }
 }
 
@@ -1211,7 +1237,7 @@ static int large_max_product_impl(const LargeArgs& a, float* mm, int32_t* path, 
     const int lpr = (a.D + 3) / 4;
     int width = 1;
     while (width < lpr) width <<= 1;
-    const long long rows_per_block = 4LL * (64 / width);
+    const long long rows_per_block = 4LL * COMBINE_UNROLL * (64 / width);
     launch("lm_combine", lm_combine_kernel, dim3((unsigned)((rows + rows_per_block - 1) / rows_per_block)), block, st, F, Bv,
            rows, a.D, mm, path);
     launch("lm_finalize", lm_finalize_kernel, dim3((unsigned)a.batch), dim3(64), st, part, p.cps, logprob_out);

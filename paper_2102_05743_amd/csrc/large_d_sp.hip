@@ -891,72 +891,6 @@ __global__ __launch_bounds__(256) void ld_apply_kernel(const float* __restrict__
 // Sixteen chunks advance per workgroup, independently; the normaliser of a step is computed beside
 // the next step's products and applied one step late, so a step's dependent chain is the products
 // and two multiplications.  First half of the grid: forward chunks, second half: backward chunks.
-// acc[r & 3] += (x rotated by r lanes inside its DPP row) * a[r] for r = 0..15: sixteen multiply-adds
-// whose first operand is read through the DPP rotation itself (v_fmac_f32 with a row_ror modifier),
-// so no instruction is spent on moving data.  Written out because the compiler emits a separate DPP
-// move per term here.  The leading s_nop covers the wait states a DPP read needs after a vector
-// instruction wrote its source register (or EXEC); nothing inside the block rewrites x.
-HMM_DEV void row_dot16(float x, const float* a, float (&acc)[4]) {
-    asm volatile(
-        "s_nop 4\n\t"
-        "v_fmac_f32 %0, %4, %5\n\t"
-        "v_fmac_f32_dpp %1, %4, %6 row_ror:1 row_mask:0xf bank_mask:0xf\n\t"
-        "v_fmac_f32_dpp %2, %4, %7 row_ror:2 row_mask:0xf bank_mask:0xf\n\t"
-        "v_fmac_f32_dpp %3, %4, %8 row_ror:3 row_mask:0xf bank_mask:0xf\n\t"
-        "v_fmac_f32_dpp %0, %4, %9 row_ror:4 row_mask:0xf bank_mask:0xf\n\t"
-        "v_fmac_f32_dpp %1, %4, %10 row_ror:5 row_mask:0xf bank_mask:0xf\n\t"
-        "v_fmac_f32_dpp %2, %4, %11 row_ror:6 row_mask:0xf bank_mask:0xf\n\t"
-        "v_fmac_f32_dpp %3, %4, %12 row_ror:7 row_mask:0xf bank_mask:0xf\n\t"
-        "v_fmac_f32_dpp %0, %4, %13 row_ror:8 row_mask:0xf bank_mask:0xf\n\t"
-        "v_fmac_f32_dpp %1, %4, %14 row_ror:9 row_mask:0xf bank_mask:0xf\n\t"
-        "v_fmac_f32_dpp %2, %4, %15 row_ror:10 row_mask:0xf bank_mask:0xf\n\t"
-        "v_fmac_f32_dpp %3, %4, %16 row_ror:11 row_mask:0xf bank_mask:0xf\n\t"
-        "v_fmac_f32_dpp %0, %4, %17 row_ror:12 row_mask:0xf bank_mask:0xf\n\t"
-        "v_fmac_f32_dpp %1, %4, %18 row_ror:13 row_mask:0xf bank_mask:0xf\n\t"
-        "v_fmac_f32_dpp %2, %4, %19 row_ror:14 row_mask:0xf bank_mask:0xf\n\t"
-        "v_fmac_f32_dpp %3, %4, %20 row_ror:15 row_mask:0xf bank_mask:0xf"
-        : "+v"(acc[0]), "+v"(acc[1]), "+v"(acc[2]), "+v"(acc[3])
-        : "v"(x), "v"(a[0]), "v"(a[1]), "v"(a[2]), "v"(a[3]), "v"(a[4]), "v"(a[5]), "v"(a[6]), "v"(a[7]), "v"(a[8]),
-          "v"(a[9]), "v"(a[10]), "v"(a[11]), "v"(a[12]), "v"(a[13]), "v"(a[14]), "v"(a[15]));
-}
-
-// The same starting the four accumulators (plain products for r = 0..3), so that they need no zeroing.
-// Outputs are early-clobber: they are written while inputs are still to be read.
-HMM_DEV void row_dot16_first(float x, const float* a, float (&acc)[4]) {
-    asm volatile(
-        "s_nop 4\n\t"
-        "v_mul_f32 %0, %4, %5\n\t"
-        "v_mul_f32_dpp %1, %4, %6 row_ror:1 row_mask:0xf bank_mask:0xf\n\t"
-        "v_mul_f32_dpp %2, %4, %7 row_ror:2 row_mask:0xf bank_mask:0xf\n\t"
-        "v_mul_f32_dpp %3, %4, %8 row_ror:3 row_mask:0xf bank_mask:0xf\n\t"
-        "v_fmac_f32_dpp %0, %4, %9 row_ror:4 row_mask:0xf bank_mask:0xf\n\t"
-        "v_fmac_f32_dpp %1, %4, %10 row_ror:5 row_mask:0xf bank_mask:0xf\n\t"
-        "v_fmac_f32_dpp %2, %4, %11 row_ror:6 row_mask:0xf bank_mask:0xf\n\t"
-        "v_fmac_f32_dpp %3, %4, %12 row_ror:7 row_mask:0xf bank_mask:0xf\n\t"
-        "v_fmac_f32_dpp %0, %4, %13 row_ror:8 row_mask:0xf bank_mask:0xf\n\t"
-        "v_fmac_f32_dpp %1, %4, %14 row_ror:9 row_mask:0xf bank_mask:0xf\n\t"
-        "v_fmac_f32_dpp %2, %4, %15 row_ror:10 row_mask:0xf bank_mask:0xf\n\t"
-        "v_fmac_f32_dpp %3, %4, %16 row_ror:11 row_mask:0xf bank_mask:0xf\n\t"
-        "v_fmac_f32_dpp %0, %4, %17 row_ror:12 row_mask:0xf bank_mask:0xf\n\t"
-        "v_fmac_f32_dpp %1, %4, %18 row_ror:13 row_mask:0xf bank_mask:0xf\n\t"
-        "v_fmac_f32_dpp %2, %4, %19 row_ror:14 row_mask:0xf bank_mask:0xf\n\t"
-        "v_fmac_f32_dpp %3, %4, %20 row_ror:15 row_mask:0xf bank_mask:0xf"
-        : "=&v"(acc[0]), "=&v"(acc[1]), "=&v"(acc[2]), "=&v"(acc[3])
-        : "v"(x), "v"(a[0]), "v"(a[1]), "v"(a[2]), "v"(a[3]), "v"(a[4]), "v"(a[5]), "v"(a[6]), "v"(a[7]), "v"(a[8]),
-          "v"(a[9]), "v"(a[10]), "v"(a[11]), "v"(a[12]), "v"(a[13]), "v"(a[14]), "v"(a[15]));
-}
-
-// acc[qd] = terms of the product with the constant matrix held as a[(qs, qd, r)] (see the kernel below)
-template <int NQ>
-HMM_DEV void row_matvec_terms(const float (&h)[NQ], const float (&a)[NQ * NQ * 16], float (&acc)[NQ][4]) {
-#pragma unroll
-    for (int qd = 0; qd < NQ; ++qd) row_dot16_first(h[0], &a[qd * 16], acc[qd]);
-#pragma unroll
-    for (int qs = 1; qs < NQ; ++qs)
-#pragma unroll
-        for (int qd = 0; qd < NQ; ++qd) row_dot16(h[qs], &a[(qs * NQ + qd) * 16], acc[qd]);
-}
-
 template <int D>
 __global__ __launch_bounds__(256) void ld_apply_row_kernel(const float* __restrict__ prior, const float* __restrict__ A,
                                                            const float* __restrict__ ll,
