@@ -895,6 +895,147 @@ __global__ __launch_bounds__(256) void lm_apply_kernel(const float* __restrict__
     }
 }
 
+// The same for D <= 32 with one chunk per DPP row of 16 lanes (sixteen chunks per workgroup), no LDS and no
+// barrier: lane l holds components 16 q + l of the vector, the candidates of the maximum arrive as the
+// row's vector rotated by r lanes (an operand modifier of the add) against constants
+// la[qd][16 qs + r] = log A(16 qs + (l - r) mod 16, 16 qd + l)   (forward; transposed for the backward pass),
+// and the row's maximum takes four rotate-and-max steps.  Log-likelihoods are prefetched PFD steps ahead.
+template <int D>
+__global__ __launch_bounds__(256) void lm_apply_row_kernel(const float* __restrict__ prior, const float* __restrict__ A,
+                                                           const float* __restrict__ ll, long long T, int Dr, int Lc,
+                                                           int cps, long long nchunks, int shared_model,
+                                                           const float* __restrict__ vin, const float* __restrict__ bout,
+                                                           float* __restrict__ F, float* __restrict__ Bv,
+                                                           double* __restrict__ part, int half) {
+    static_assert(D == 16 || D == 32, "one DPP row per chunk");
+    constexpr int NQ = D / 16;
+    constexpr int PFD = 8;
+    const bool backward = (int)blockIdx.x >= half;
+    const int l = threadIdx.x & 15;
+    const long long chunk = (long long)(backward ? blockIdx.x - half : blockIdx.x) * 16 + (threadIdx.x >> 4);
+    const ChunkCoord cc = chunk_coord(chunk, nchunks, cps, T, Lc);
+    const float* Am = A + (shared_model ? 0 : (size_t)cc.seq * Dr * Dr);
+    float la[NQ][D];
+#pragma unroll
+    for (int qd = 0; qd < NQ; ++qd)
+#pragma unroll
+        for (int qs = 0; qs < NQ; ++qs)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int src = 16 * qs + ((l - r) & 15), dst = 16 * qd + l;
+                const int i = backward ? dst : src, j = backward ? src : dst;
+                float v = (i == j) ? 0.0f : -INFINITY;
+                if (i < Dr && j < Dr) v = safe_log(Am[(size_t)i * Dr + j]);
+                la[qd][16 * qs + r] = v;
+            }
+    const bool live = cc.nsteps > 0;
+    const bool first_chunk = (chunk % cps) == 0;
+    bool have[NQ];
+    int col[NQ];
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) { have[q] = 16 * q + l < Dr; col[q] = have[q] ? 16 * q + l : 0; }
+    const long long s_first = backward ? (long long)cc.nsteps - 1 : 0;
+    const long long stride = backward ? -(long long)Dr : (long long)Dr;
+    const float* lp = ll + ((size_t)cc.seq * T + cc.t0 + (live ? s_first : 0)) * Dr;
+    float* op = (backward ? Bv : F) + ((size_t)cc.seq * T + cc.t0 + (live ? s_first : 0)) * Dr;
+    int fetched = 0;
+    float xq[PFD][NQ];
+    auto fetch = [&](float (&x)[NQ]) {
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) x[q] = lp[col[q]];
+        ++fetched;
+        if (fetched < cc.nsteps) lp += stride;
+    };
+    auto row_max_of = [&](const float (&v)[NQ]) {
+        float m = v[0];
+#pragma unroll
+        for (int q = 1; q < NQ; ++q) m = fmaxf(m, v[q]);
+        m = row_allmax(m);
+        return (m == -INFINITY) ? 0.0f : m;
+    };
+    float v[NQ];
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) {
+        const int j = 16 * q + l;
+        float x = -INFINITY;
+        if (live) {
+            if (backward) x = bout[(size_t)chunk * D + j];
+            else if (first_chunk) x = have[q] ? safe_log(prior[(shared_model ? 0 : (size_t)cc.seq * Dr) + j]) : -INFINITY;
+            else x = vin[(size_t)chunk * D + j];
+        }
+        v[q] = x;
+    }
+#pragma unroll
+    for (int p = 0; p < PFD; ++p) fetch(xq[p]);
+    if (!backward) {
+        // level the chunk starts from: 0 for the log prior (used as given), else the carry's maximum
+        const float start = first_chunk ? 0.0f : row_max_of(v);
+        float off = start;
+        double osum = 0.0;
+        for (int s0 = 0; s0 < Lc; s0 += PFD) {
+#pragma unroll
+            for (int p = 0; p < PFD; ++p) {
+                const int s = s0 + p;
+                const bool active = s < cc.nsteps;
+                float x[NQ];
+#pragma unroll
+                for (int q = 0; q < NQ; ++q) x[q] = have[q] ? xq[p][q] : -INFINITY;
+                fetch(xq[p]);
+                const bool seq_start = (cc.t0 + s == 0);   // psi~^f_1 = log prior + ll_1
+                float g[NQ];
+#pragma unroll
+                for (int qd = 0; qd < NQ; ++qd) {
+                    float best = -INFINITY;
+                    systolic_terms<D, 0, 0>(v, la[qd], best);
+                    g[qd] = seq_start ? v[qd] + x[qd] : best + (x[qd] - off);
+                }
+                if (active) {
+                    const float m = row_max_of(g);
+#pragma unroll
+                    for (int q = 0; q < NQ; ++q) {
+                        if (have[q]) op[16 * q + l] = g[q] - m;
+                        v[q] = g[q];
+                    }
+                    op += stride;
+                    osum += (double)(seq_start ? 0.0f : off);
+                    off = m;
+                }
+            }
+        }
+        if (live && l == 0) part[chunk] = osum + (double)off - (double)start;
+    } else {
+        // v = psi~^b at the current step, shifted by the previous step's maximum
+        for (int s0 = 0; s0 < Lc; s0 += PFD) {
+#pragma unroll
+            for (int p = 0; p < PFD; ++p) {
+                const int pos = s0 + p;
+                const bool active = pos < cc.nsteps;
+                const int s = cc.nsteps - 1 - pos;
+                float t[NQ];
+#pragma unroll
+                for (int q = 0; q < NQ; ++q) t[q] = (have[q] ? xq[p][q] : -INFINITY) + v[q];   // emission part of psi_s + psi~^b_s
+                fetch(xq[p]);
+                float nv[NQ];
+                const float m = row_max_of(v);
+#pragma unroll
+                for (int qd = 0; qd < NQ; ++qd) {
+                    float best = -INFINITY;
+                    systolic_terms<D, 0, 0>(t, la[qd], best);
+                    nv[qd] = best - m;
+                }
+                if (active) {
+#pragma unroll
+                    for (int q = 0; q < NQ; ++q) {
+                        if (have[q]) op[16 * q + l] = v[q];
+                        if (s > 0) v[q] = nv[q];
+                    }
+                    op += stride;
+                }
+            }
+        }
+    }
+}
+
 // Theorem 4: max-marginal log psi~^f_k + log psi~^b_k, shifted so that the step's largest entry is 0,
 // and its maximiser (lowest state on ties).  A power-of-two group of lanes per step; a wave takes
 // COMBINE_UNROLL groups of steps with all loads issued first (16-byte accesses when D is a multiple of four).
@@ -1084,6 +1225,23 @@ __global__ __launch_bounds__(256) void lv_element_finish_kernel(const float* __r
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 // Chunking for the max-plus path: the back-pointers of a chunk must fit in LDS (Lc * DP <= 48 KiB).
+// From D = 32 the aggregate kernel runs one workgroup per chunk, all resident at once: a chunk count
+// just above a multiple of the 256 compute units leaves most of them idle while a few work through one
+// chunk more (713 chunks take as long as 768).  Shorten the chunks so that the count fills the last round.
+static void fill_last_round(LargePlan& p, long long T, int batch) {
+    if (p.DP < 32 || p.nchunks <= 256 || p.nchunks % 256 == 0) return;
+    const long long target = (p.nchunks + 255) / 256 * 256;
+    const long long cps_t = target / batch;
+    if (cps_t < 1) return;
+    long long Lc = (T + cps_t - 1) / cps_t;
+    Lc = (Lc + 7) / 8 * 8;
+    if (Lc >= 32 && Lc <= p.Lc) {
+        p.Lc = (int)Lc;
+        p.cps = (int)((T + p.Lc - 1) / p.Lc);
+        p.nchunks = (long long)p.cps * batch;
+    }
+}
+
 // D = 16 with chunks of at most ROW_FORWARD_MAX_LC steps (batches of sequences, which need few chunks each) runs
 // the forward recursion with one chunk per DPP row, sixteen chunks' back-pointers per workgroup.
 constexpr int ROW_FORWARD_MAX_LC = 192;
@@ -1097,22 +1255,7 @@ static LargePlan viterbi_plan(int Dr, long long T, int batch) {
         p.cps = (int)((T + p.Lc - 1) / p.Lc);
         p.nchunks = (long long)p.cps * batch;
     }
-    // From D = 32 the aggregate kernel runs one workgroup per chunk, all resident at once: a chunk count
-    // just above a multiple of the 256 compute units leaves most of them idle while a few work through one
-    // chunk more (713 chunks take as long as 768).  Shorten the chunks so that the count fills the last round.
-    if (p.DP >= 32 && p.nchunks > 256 && p.nchunks % 256 != 0) {
-        const long long target = (p.nchunks + 255) / 256 * 256;
-        const long long cps_t = target / batch;
-        if (cps_t >= 1) {
-            long long Lc = (T + cps_t - 1) / cps_t;
-            Lc = (Lc + 7) / 8 * 8;
-            if (Lc >= 32 && Lc <= p.Lc) {
-                p.Lc = (int)Lc;
-                p.cps = (int)((T + p.Lc - 1) / p.Lc);
-                p.nchunks = (long long)p.cps * batch;
-            }
-        }
-    }
+    fill_last_round(p, T, batch);
     return p;
 }
 
@@ -1186,8 +1329,14 @@ static int large_viterbi_impl(const LargeArgs& a, int32_t* path, double* logprob
 
 struct LargeMmWs { size_t agg, agg_other, vin, bout, F, Bv, part, total; };
 
+static LargePlan max_product_plan(int Dr, long long T, int batch) {
+    LargePlan p = large_plan(Dr, T, batch);
+    fill_last_round(p, T, batch);
+    return p;
+}
+
 static LargeMmWs large_mm_ws(int Dr, long long T, int batch) {
-    const LargePlan p = large_plan(Dr, T, batch);
+    const LargePlan p = max_product_plan(Dr, T, batch);
     const size_t D = p.DP, nc = (size_t)p.nchunks, rows = (size_t)T * batch;
     LargeMmWs w;
     size_t o = 0;
@@ -1208,7 +1357,7 @@ template <int D>
 static int large_max_product_impl(const LargeArgs& a, float* mm, int32_t* path, double* logprob_out) {
     using C = LargeCfg<D>;
     using M = MpCfg<D>;
-    const LargePlan p = large_plan(a.D, a.T, a.batch);
+    const LargePlan p = max_product_plan(a.D, a.T, a.batch);
     const LargeMmWs w = large_mm_ws(a.D, a.T, a.batch);
     if (a.ws_bytes < w.total) return 3;
     const long long rows = a.T * a.batch;
@@ -1231,9 +1380,15 @@ static int large_max_product_impl(const LargeArgs& a, float* mm, int32_t* path, 
     else
         launch("lm_carry", lv_carry_kernel<D>, dim3(2u * (unsigned)a.batch), block, st, a.prior, a.D, p.cps,
                a.shared_model, agg, vin, static_cast<const float*>(agg_other), bout);
-    const int half = (int)((p.nchunks + C::VCPW - 1) / C::VCPW);
-    launch("lm_apply", lm_apply_kernel<D>, dim3(2u * (unsigned)half), block, st, a.prior, a.A, a.ll, a.T, a.D, p.Lc,
-           p.cps, p.nchunks, a.shared_model, vin, bout, F, Bv, part, half);
+    if constexpr (D <= 32) {
+        const int half = (int)((p.nchunks + 15) / 16);
+        launch("lm_apply", lm_apply_row_kernel<D>, dim3(2u * (unsigned)half), block, st, a.prior, a.A, a.ll, a.T, a.D, p.Lc,
+               p.cps, p.nchunks, a.shared_model, vin, bout, F, Bv, part, half);
+    } else {
+        const int half = (int)((p.nchunks + C::VCPW - 1) / C::VCPW);
+        launch("lm_apply", lm_apply_kernel<D>, dim3(2u * (unsigned)half), block, st, a.prior, a.A, a.ll, a.T, a.D, p.Lc,
+               p.cps, p.nchunks, a.shared_model, vin, bout, F, Bv, part, half);
+    }
     const int lpr = (a.D + 3) / 4;
     int width = 1;
     while (width < lpr) width <<= 1;
