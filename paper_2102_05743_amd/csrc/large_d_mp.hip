@@ -255,33 +255,40 @@ template <int D>
 __global__ __launch_bounds__(256) void lv_carry_kernel(const float* __restrict__ prior, int Dr, int cps,
                                                        int shared_model, const float* __restrict__ agg,
                                                        float* __restrict__ vin, const float* __restrict__ agg_other,
-                                                       float* __restrict__ bout) {
+                                                       float* __restrict__ bout, int seglen, int nseg,
+                                                       const float* __restrict__ start) {
     // With bout given the grid is doubled: odd workgroups run the backward direction, the same
     // recursion on the aggregates' other orientation, over the chunks right to left, from the zero
     // vector: bout[c] = backward potential at chunk c's last step.
+    // Forward only: the chunks of a sequence may be cut into nseg segments of seglen chunks, walked
+    // independently (one workgroup each) from start[segment] = V just before the segment.
     constexpr int Q = 256 / D;
     constexpr int RPT = D / Q;
     __shared__ float vec[D];
     __shared__ float partial[Q * D];
     __shared__ float max_lds;
     const bool two = bout != nullptr;
-    const int seq = two ? blockIdx.x >> 1 : blockIdx.x;
+    const int unit = two ? blockIdx.x >> 1 : blockIdx.x;
     const int dir = two ? (blockIdx.x & 1) : 0;
+    const int seq = unit / nseg, seg = unit % nseg;
+    const int c_begin = seg * seglen, c_end = min(cps, c_begin + seglen);
+    const int nhops = c_end - c_begin;
     const int j = threadIdx.x % D, q = threadIdx.x / D;
     const float* mats = (dir ? agg_other : agg) + (size_t)seq * cps * D * D;
     float* out = (dir ? bout : vin) + (size_t)seq * cps * D;
     float v;
     if (dir) v = (j < Dr) ? 0.0f : -INFINITY;
+    else if (start != nullptr) v = start[(size_t)unit * D + j];
     else v = (j < Dr) ? safe_log(prior[(shared_model ? 0 : (size_t)seq * Dr) + j]) : -INFINITY;
     float pv[RPT];
     auto load_mat = [&](int it) {
-        const float* Mx = mats + (size_t)(dir ? cps - 1 - it : it) * D * D;
+        const float* Mx = mats + (size_t)(dir ? c_end - 1 - it : c_begin + it) * D * D;
 #pragma unroll
         for (int r = 0; r < RPT; ++r) pv[r] = Mx[(size_t)(q * RPT + r) * D + j];
     };
-    load_mat(0);
-    for (int it = 0; it < cps; ++it) {
-        const int c = dir ? cps - 1 - it : it;
+    if (nhops > 0) load_mat(0);
+    for (int it = 0; it < nhops; ++it) {
+        const int c = dir ? c_end - 1 - it : c_begin + it;
         if (q == 0) {
             out[(size_t)c * D + j] = v;
             vec[j] = v;
@@ -290,7 +297,7 @@ __global__ __launch_bounds__(256) void lv_carry_kernel(const float* __restrict__
         float acc = -INFINITY;
 #pragma unroll
         for (int r = 0; r < RPT; ++r) acc = fmaxf(acc, vec[q * RPT + r] + pv[r]);
-        if (it + 1 < cps) load_mat(it + 1);
+        if (it + 1 < nhops) load_mat(it + 1);
         partial[q * D + j] = acc;
         lds_barrier();
         float g = -INFINITY;
@@ -320,28 +327,36 @@ __global__ __launch_bounds__(64) void lv_carry_wave_kernel(const float* __restri
                                                            int shared_model, const float* __restrict__ agg,
                                                            float* __restrict__ vin,
                                                            const float* __restrict__ agg_other,
-                                                           float* __restrict__ bout) {
-    // With bout given the grid is doubled and odd workgroups run the backward direction (see lv_carry_kernel).
+                                                           float* __restrict__ bout, int seglen, int nseg,
+                                                           const float* __restrict__ start) {
+    // With bout given the grid is doubled and odd workgroups run the backward direction; forward walks may
+    // be cut into segments with their own start vectors (see lv_carry_kernel).
     static_assert(D <= 32, "one wave covers the columns");
     constexpr int PARTS = 64 / D;
     constexpr int RPT = D / PARTS;
     constexpr int PF = 8;
     __shared__ __align__(16) float vec[D];
     const bool two = bout != nullptr;
-    const int seq = two ? blockIdx.x >> 1 : blockIdx.x;
+    const int unit = two ? blockIdx.x >> 1 : blockIdx.x;
     const int dir = two ? (blockIdx.x & 1) : 0;
+    const int seq = unit / nseg, seg = unit % nseg;
+    const int c_begin = seg * seglen, c_end = min(cps, c_begin + seglen);
+    const int nhops = c_end - c_begin;
+    if (nhops <= 0) return;   // uniform over the wave
     const int lane = threadIdx.x;
     const int h = lane % PARTS, j = lane / PARTS;
     const float* mats = (dir ? agg_other : agg) + (size_t)seq * cps * D * D;
     float* out = (dir ? bout : vin) + (size_t)seq * cps * D;
     float v;
     if (dir) v = (j < Dr) ? 0.0f : -INFINITY;
+    else if (start != nullptr) v = start[(size_t)unit * D + j];
     else v = (j < Dr) ? safe_log(prior[(shared_model ? 0 : (size_t)seq * Dr) + j]) : -INFINITY;
     settle_loaded(v);
     float pv[PF][RPT];
     // unconditional loads (clamped hop index): the compiler can count outstanding loads exactly
     auto load_mat = [&](int it, float (&m)[RPT]) {
-        const int c = dir ? cps - 1 - (it < cps ? it : cps - 1) : (it < cps ? it : cps - 1);
+        const int itc = it < nhops ? it : nhops - 1;
+        const int c = dir ? c_end - 1 - itc : c_begin + itc;
         const float* Mx = mats + (size_t)c * D * D + (size_t)j * D + h * RPT;   // the lane's terms are contiguous
 #pragma unroll
         for (int r4 = 0; r4 < RPT; r4 += 4) {
@@ -350,7 +365,7 @@ __global__ __launch_bounds__(64) void lv_carry_wave_kernel(const float* __restri
         }
     };
     auto hop = [&](int it, const float (&m)[RPT]) {
-        const int c = dir ? cps - 1 - it : it;
+        const int c = dir ? c_end - 1 - it : c_begin + it;
         if (h == 0) {
             out[(size_t)c * D + j] = v;
             vec[j] = v;
@@ -372,7 +387,7 @@ __global__ __launch_bounds__(64) void lv_carry_wave_kernel(const float* __restri
     };
 #pragma unroll
     for (int p = 0; p < PF; ++p) load_mat(p, pv[p]);
-    const int nfull = cps / PF * PF;
+    const int nfull = nhops / PF * PF;
     for (int c0 = 0; c0 < nfull; c0 += PF) {
 #pragma unroll
         for (int p = 0; p < PF; ++p) {
@@ -382,7 +397,7 @@ __global__ __launch_bounds__(64) void lv_carry_wave_kernel(const float* __restri
     }
 #pragma unroll
     for (int p = 0; p < PF; ++p)
-        if (nfull + p < cps) hop(nfull + p, pv[p]);   // slot p holds hop nfull + p
+        if (nfull + p < nhops) hop(nfull + p, pv[p]);   // slot p holds hop nfull + p
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -688,7 +703,8 @@ __global__ __launch_bounds__(256) void lv_forward_row_kernel(const float* __rest
 template <int D>
 __global__ __launch_bounds__(256) void lv_suffix_kernel(const uint8_t* __restrict__ cmap, const int* __restrict__ xstar,
                                                         int cps, int* __restrict__ xend,
-                                                        const double* __restrict__ part, double* __restrict__ logprob) {
+                                                        const double* __restrict__ part, int nparts,
+                                                        double* __restrict__ logprob) {
     constexpr int PIECE = 128;                       // chunk maps staged per round
     __shared__ __align__(16) uint8_t maps[PIECE * D];
     __shared__ double sh[256];
@@ -713,7 +729,7 @@ __global__ __launch_bounds__(256) void lv_suffix_kernel(const uint8_t* __restric
         __syncthreads();
     }
     double acc = 0.0;
-    for (int c = threadIdx.x; c < cps; c += 256) acc += part[(size_t)seq * cps + c];
+    for (int c = threadIdx.x; c < nparts; c += 256) acc += part[(size_t)seq * nparts + c];
     sh[threadIdx.x] = acc;
     __syncthreads();
     for (int d = 128; d >= 1; d >>= 1) {
@@ -721,6 +737,50 @@ __global__ __launch_bounds__(256) void lv_suffix_kernel(const uint8_t* __restric
         __syncthreads();
     }
     if (threadIdx.x == 0) logprob[seq] = sh[0];
+}
+
+// ---------------------------------------------------------------------------------------------
+// Second level of the reversed scan over chunk maps for long sequences: the composed map of every
+// group of g consecutive chunks (state at the group's last step -> state before its first chunk), so
+// that lv_suffix walks groups instead of chunks, and then, for all groups in parallel, the walk
+// through each group's own chunks from the state lv_suffix found at its end.  The group's maps are
+// staged in LDS: a chain of dependent byte look-ups.
+template <int D>
+__global__ __launch_bounds__(128) void lv_group_maps_kernel(const uint8_t* __restrict__ cmap, int cps, int g, int G,
+                                                            uint8_t* __restrict__ gmap) {
+    extern __shared__ __align__(16) unsigned char dyn_lds[];
+    const int seq = blockIdx.x / G, grp = blockIdx.x % G;
+    const int c0 = grp * g, c1 = min(cps, c0 + g);
+    const uint8_t* src = cmap + ((size_t)seq * cps + c0) * D;
+    const int n = (c1 - c0) * D;
+    for (int idx = threadIdx.x * 4; idx < n; idx += 128 * 4)
+        *reinterpret_cast<uint32_t*>(dyn_lds + idx) = *reinterpret_cast<const uint32_t*>(src + idx);
+    __syncthreads();
+    if ((int)threadIdx.x < D) {
+        int x = threadIdx.x;
+        for (int c = c1 - 1; c >= c0; --c) x = dyn_lds[(c - c0) * D + x];
+        gmap[((size_t)seq * G + grp) * D + threadIdx.x] = (uint8_t)x;
+    }
+}
+
+template <int D>
+__global__ __launch_bounds__(128) void lv_group_chase_kernel(const uint8_t* __restrict__ cmap, const int* __restrict__ xg,
+                                                             int cps, int g, int G, int* __restrict__ xend) {
+    extern __shared__ __align__(16) unsigned char dyn_lds[];
+    const int seq = blockIdx.x / G, grp = blockIdx.x % G;
+    const int c0 = grp * g, c1 = min(cps, c0 + g);
+    const uint8_t* src = cmap + ((size_t)seq * cps + c0) * D;
+    const int n = (c1 - c0) * D;
+    for (int idx = threadIdx.x * 4; idx < n; idx += 128 * 4)
+        *reinterpret_cast<uint32_t*>(dyn_lds + idx) = *reinterpret_cast<const uint32_t*>(src + idx);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int x = xg[(size_t)seq * G + grp];
+        for (int c = c1 - 1; c >= c0; --c) {
+            xend[(size_t)seq * cps + c] = x;
+            x = dyn_lds[(c - c0) * D + x];
+        }
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1189,7 +1249,8 @@ __global__ __launch_bounds__(256) void lv_tree_product_kernel(const float* __res
     __syncthreads();
     if (tid == 0) {
         out_tmax[(size_t)res * NT + slab] = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
-        if (slab == 0) out_off[res] = in_off[ia] + (pair ? in_off[ia + 1] : 0.0) + (double)ma + (double)mb;
+        if (slab == 0 && out_off != nullptr)   // callers that only need the product's direction pass no offsets
+            out_off[res] = in_off[ia] + (pair ? in_off[ia + 1] : 0.0) + (double)ma + (double)mb;
     }
 }
 
@@ -1246,8 +1307,31 @@ static void fill_last_round(LargePlan& p, long long T, int batch) {
 // the forward recursion with one chunk per DPP row, sixteen chunks' back-pointers per workgroup.
 constexpr int ROW_FORWARD_MAX_LC = 192;
 
+// Long sequences get a second scan level (SCAN2_MIN_CHUNKS chunks per sequence and more): aggregates of
+// groups of g = 2^k consecutive chunks by k levels of lv_tree_product, V at the group boundaries by a walk
+// over the groups, then V at every chunk by walks inside all groups at once; the reversed scan over the
+// chunk maps is grouped the same way.  The sequential depth drops from chunks to about 2 sqrt(chunks), so
+// below D = 128 the chunks can be as short as the smoother's (more of them, shorter in-chunk recursions).
+constexpr int SCAN2_MIN_CHUNKS = 128;
+
+struct Scan2 { bool on; int g, k, G; };
+
+static Scan2 scan2_of(const LargePlan& p) {
+    Scan2 s{false, p.cps, 0, 1};
+    if (p.cps < SCAN2_MIN_CHUNKS) return s;
+    s.on = true;
+    int k = 1;
+    while ((1 << (2 * k)) < p.cps) ++k;          // 2^k >= sqrt(chunks)
+    if (k > 1 && (1 << (2 * k - 1)) >= p.cps) --k;   // nearer power of two
+    s.k = k;
+    s.g = 1 << k;
+    s.G = (p.cps + s.g - 1) / s.g;
+    return s;
+}
+
 static LargePlan viterbi_plan(int Dr, long long T, int batch) {
     LargePlan p = large_plan(Dr, T, batch);
+    if (p.DP < 128) p = element_plan(Dr, T, batch);
     const int vcpw = p.DP >= 128 ? 1 : p.DP >= 64 ? 2 : 4;   // chunks sharing a workgroup in the forward kernel
     const int cap = (48 * 1024) / (p.DP * vcpw) / 16 * 16;
     if (p.Lc > cap) {
@@ -1259,7 +1343,7 @@ static LargePlan viterbi_plan(int Dr, long long T, int batch) {
     return p;
 }
 
-struct LargeViterbiWs { size_t agg, vin, bp, cmap, xend, xstar, part, total; };
+struct LargeViterbiWs { size_t agg, vin, bp, cmap, xend, xstar, part, lvl[2][2], gvin, gmap, xg, total; };
 
 static LargeViterbiWs large_viterbi_ws(int Dr, long long T, int batch) {
     const LargePlan p = viterbi_plan(Dr, T, batch);
@@ -1273,6 +1357,18 @@ static LargeViterbiWs large_viterbi_ws(int Dr, long long T, int batch) {
     w.xend = o;  o = align_up(o + nc * sizeof(int), 256);
     w.xstar = o; o = align_up(o + (size_t)batch * sizeof(int), 256);
     w.part = o;  o = align_up(o + nc * sizeof(double), 256);
+    const Scan2 s2 = scan2_of(p);
+    size_t n = (size_t)p.cps;
+    for (int l = 0; l < 2; ++l) {   // tree levels alternate between two buffers
+        n = (n + 1) / 2;
+        const size_t cnt = s2.on ? n * batch : 0;
+        w.lvl[l][0] = o; o = align_up(o + cnt * D * D * sizeof(float), 256);
+        w.lvl[l][1] = o; o = align_up(o + cnt * 8 * sizeof(float), 256);
+    }
+    const size_t ng = s2.on ? (size_t)s2.G * batch : 0;
+    w.gvin = o;  o = align_up(o + ng * D * sizeof(float), 256);
+    w.gmap = o;  o = align_up(o + ng * D, 256);
+    w.xg = o;    o = align_up(o + ng * sizeof(int), 256);
     w.total = o;
     return w;
 }
@@ -1299,12 +1395,37 @@ static int large_viterbi_impl(const LargeArgs& a, int32_t* path, double* logprob
     const dim3 block(256);
     launch("lv_aggregate", lv_aggregate_systolic_kernel<D>, dim3((unsigned)((p.nchunks + M::CPW - 1) / M::CPW)), block,
            st, a.A, a.ll, a.T, a.D, p.Lc, p.cps, p.nchunks, a.shared_model, agg, static_cast<float*>(nullptr));
-    if constexpr (D <= 32)
-        launch("lv_carry", lv_carry_wave_kernel<D>, dim3((unsigned)a.batch), dim3(64), st, a.prior, a.D, p.cps,
-               a.shared_model, agg, vin, static_cast<const float*>(nullptr), static_cast<float*>(nullptr));
-    else
-        launch("lv_carry", lv_carry_kernel<D>, dim3((unsigned)a.batch), block, st, a.prior, a.D, p.cps, a.shared_model,
-               agg, vin, static_cast<const float*>(nullptr), static_cast<float*>(nullptr));
+    const Scan2 s2 = scan2_of(p);
+    auto carry = [&](int cps, const float* mats, float* out, int seglen, int nseg, const float* start) {
+        const unsigned blocks = (unsigned)a.batch * (unsigned)nseg;
+        if constexpr (D <= 32)
+            launch("lv_carry", lv_carry_wave_kernel<D>, dim3(blocks), dim3(64), st, a.prior, a.D, cps, a.shared_model, mats,
+                   out, static_cast<const float*>(nullptr), static_cast<float*>(nullptr), seglen, nseg, start);
+        else
+            launch("lv_carry", lv_carry_kernel<D>, dim3(blocks), block, st, a.prior, a.D, cps, a.shared_model, mats, out,
+                   static_cast<const float*>(nullptr), static_cast<float*>(nullptr), seglen, nseg, start);
+    };
+    if (s2.on) {
+        constexpr int transposed = (D <= 32) ? 1 : 0;
+        float* gvin = reinterpret_cast<float*>(ws + w.gvin);
+        const float* cur = agg;
+        const float* curm = nullptr;
+        int n = p.cps;
+        for (int l = 0; l < s2.k; ++l) {
+            const int n_out = (n + 1) / 2;
+            float* o = reinterpret_cast<float*>(ws + w.lvl[l & 1][0]);
+            float* om = reinterpret_cast<float*>(ws + w.lvl[l & 1][1]);
+            launch("lv_tree_product", lv_tree_product_kernel<D>, dim3((unsigned)((long long)n_out * a.batch * (D / 16))), block,
+                   st, cur, static_cast<const double*>(nullptr), curm, n, n_out, transposed, o, static_cast<double*>(nullptr),
+                   om);
+            cur = o; curm = om;
+            n = n_out;
+        }
+        carry(s2.G, cur, gvin, s2.G, 1, nullptr);            // V before every group
+        carry(p.cps, agg, vin, s2.g, s2.G, gvin);             // V before every chunk, all groups at once
+    } else {
+        carry(p.cps, agg, vin, p.cps, 1, nullptr);
+    }
     bool row_forward = false;
     if constexpr (D == 16) {
         if (p.Lc <= ROW_FORWARD_MAX_LC) {
@@ -1319,8 +1440,20 @@ static int large_viterbi_impl(const LargeArgs& a, int32_t* path, double* logprob
         launch_dyn("lv_forward", lv_forward_kernel<D>, dim3((unsigned)((p.nchunks + C::VCPW - 1) / C::VCPW)), block, fwd_lds,
                    st, a.prior, a.A, a.ll, a.T, a.D, p.Lc, p.cps, p.nchunks, a.shared_model, vin, bp, cmap, xstar, part);
     }
-    launch("lv_suffix", lv_suffix_kernel<D>, dim3((unsigned)a.batch), block, st, cmap, xstar, p.cps, xend, part,
-           logprob_out);
+    if (s2.on) {
+        uint8_t* gmap = reinterpret_cast<uint8_t*>(ws + w.gmap);
+        int* xg = reinterpret_cast<int*>(ws + w.xg);
+        const dim3 groups((unsigned)a.batch * (unsigned)s2.G);
+        launch_dyn("lv_group_maps", lv_group_maps_kernel<D>, groups, dim3(128), (size_t)s2.g * D, st, (const uint8_t*)cmap,
+                   p.cps, s2.g, s2.G, gmap);
+        launch("lv_suffix", lv_suffix_kernel<D>, dim3((unsigned)a.batch), block, st, (const uint8_t*)gmap, (const int*)xstar,
+               s2.G, xg, (const double*)part, p.cps, logprob_out);
+        launch_dyn("lv_group_chase", lv_group_chase_kernel<D>, groups, dim3(128), (size_t)s2.g * D, st, (const uint8_t*)cmap,
+                   (const int*)xg, p.cps, s2.g, s2.G, xend);
+    } else {
+        launch("lv_suffix", lv_suffix_kernel<D>, dim3((unsigned)a.batch), block, st, (const uint8_t*)cmap, (const int*)xstar,
+               p.cps, xend, (const double*)part, p.cps, logprob_out);
+    }
     const size_t path_lds = (size_t)p.Lc * D + (size_t)p.Lc * sizeof(int32_t);
     launch_dyn("lv_path", lv_path_kernel<D>, dim3((unsigned)p.nchunks), block, path_lds, st, a.T, p.Lc, p.cps, p.nchunks,
                bp, xend, path);
@@ -1376,10 +1509,12 @@ static int large_max_product_impl(const LargeArgs& a, float* mm, int32_t* path, 
            st, a.A, a.ll, a.T, a.D, p.Lc, p.cps, p.nchunks, a.shared_model, agg, agg_other);
     if constexpr (D <= 32)
         launch("lm_carry", lv_carry_wave_kernel<D>, dim3(2u * (unsigned)a.batch), dim3(64), st, a.prior, a.D, p.cps,
-               a.shared_model, agg, vin, static_cast<const float*>(agg_other), bout);
+               a.shared_model, agg, vin, static_cast<const float*>(agg_other), bout, p.cps, 1,
+               static_cast<const float*>(nullptr));
     else
         launch("lm_carry", lv_carry_kernel<D>, dim3(2u * (unsigned)a.batch), block, st, a.prior, a.D, p.cps,
-               a.shared_model, agg, vin, static_cast<const float*>(agg_other), bout);
+               a.shared_model, agg, vin, static_cast<const float*>(agg_other), bout, p.cps, 1,
+               static_cast<const float*>(nullptr));
     if constexpr (D <= 32) {
         const int half = (int)((p.nchunks + 15) / 16);
         launch("lm_apply", lm_apply_row_kernel<D>, dim3(2u * (unsigned)half), block, st, a.prior, a.A, a.ll, a.T, a.D, p.Lc,
