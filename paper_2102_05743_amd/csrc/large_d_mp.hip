@@ -256,12 +256,14 @@ __global__ __launch_bounds__(256) void lv_carry_kernel(const float* __restrict__
                                                        int shared_model, const float* __restrict__ agg,
                                                        float* __restrict__ vin, const float* __restrict__ agg_other,
                                                        float* __restrict__ bout, int seglen, int nseg,
-                                                       const float* __restrict__ start) {
+                                                       const float* __restrict__ start,
+                                                       const float* __restrict__ start_b) {
     // With bout given the grid is doubled: odd workgroups run the backward direction, the same
     // recursion on the aggregates' other orientation, over the chunks right to left, from the zero
     // vector: bout[c] = backward potential at chunk c's last step.
-    // Forward only: the chunks of a sequence may be cut into nseg segments of seglen chunks, walked
-    // independently (one workgroup each) from start[segment] = V just before the segment.
+    // The chunks of a sequence may be cut into nseg segments of seglen chunks, walked independently (one
+    // workgroup per segment and direction) from start[segment] = V just before the segment, resp.
+    // start_b[segment] = backward potential at the segment's last step.
     constexpr int Q = 256 / D;
     constexpr int RPT = D / Q;
     __shared__ float vec[D];
@@ -277,7 +279,7 @@ __global__ __launch_bounds__(256) void lv_carry_kernel(const float* __restrict__
     const float* mats = (dir ? agg_other : agg) + (size_t)seq * cps * D * D;
     float* out = (dir ? bout : vin) + (size_t)seq * cps * D;
     float v;
-    if (dir) v = (j < Dr) ? 0.0f : -INFINITY;
+    if (dir) v = (start_b != nullptr) ? start_b[(size_t)unit * D + j] : ((j < Dr) ? 0.0f : -INFINITY);
     else if (start != nullptr) v = start[(size_t)unit * D + j];
     else v = (j < Dr) ? safe_log(prior[(shared_model ? 0 : (size_t)seq * Dr) + j]) : -INFINITY;
     float pv[RPT];
@@ -328,7 +330,8 @@ __global__ __launch_bounds__(64) void lv_carry_wave_kernel(const float* __restri
                                                            float* __restrict__ vin,
                                                            const float* __restrict__ agg_other,
                                                            float* __restrict__ bout, int seglen, int nseg,
-                                                           const float* __restrict__ start) {
+                                                           const float* __restrict__ start,
+                                                           const float* __restrict__ start_b) {
     // With bout given the grid is doubled and odd workgroups run the backward direction; forward walks may
     // be cut into segments with their own start vectors (see lv_carry_kernel).
     static_assert(D <= 32, "one wave covers the columns");
@@ -348,7 +351,7 @@ __global__ __launch_bounds__(64) void lv_carry_wave_kernel(const float* __restri
     const float* mats = (dir ? agg_other : agg) + (size_t)seq * cps * D * D;
     float* out = (dir ? bout : vin) + (size_t)seq * cps * D;
     float v;
-    if (dir) v = (j < Dr) ? 0.0f : -INFINITY;
+    if (dir) v = (start_b != nullptr) ? start_b[(size_t)unit * D + j] : ((j < Dr) ? 0.0f : -INFINITY);
     else if (start != nullptr) v = start[(size_t)unit * D + j];
     else v = (j < Dr) ? safe_log(prior[(shared_model ? 0 : (size_t)seq * Dr) + j]) : -INFINITY;
     settle_loaded(v);
@@ -1400,10 +1403,12 @@ static int large_viterbi_impl(const LargeArgs& a, int32_t* path, double* logprob
         const unsigned blocks = (unsigned)a.batch * (unsigned)nseg;
         if constexpr (D <= 32)
             launch("lv_carry", lv_carry_wave_kernel<D>, dim3(blocks), dim3(64), st, a.prior, a.D, cps, a.shared_model, mats,
-                   out, static_cast<const float*>(nullptr), static_cast<float*>(nullptr), seglen, nseg, start);
+                   out, static_cast<const float*>(nullptr), static_cast<float*>(nullptr), seglen, nseg, start,
+                   static_cast<const float*>(nullptr));
         else
             launch("lv_carry", lv_carry_kernel<D>, dim3(blocks), block, st, a.prior, a.D, cps, a.shared_model, mats, out,
-                   static_cast<const float*>(nullptr), static_cast<float*>(nullptr), seglen, nseg, start);
+                   static_cast<const float*>(nullptr), static_cast<float*>(nullptr), seglen, nseg, start,
+                   static_cast<const float*>(nullptr));
     };
     if (s2.on) {
         constexpr int transposed = (D <= 32) ? 1 : 0;
@@ -1460,10 +1465,11 @@ static int large_viterbi_impl(const LargeArgs& a, int32_t* path, double* logprob
     return hipGetLastError() == hipSuccess ? 0 : 4;
 }
 
-struct LargeMmWs { size_t agg, agg_other, vin, bout, F, Bv, part, total; };
+struct LargeMmWs { size_t agg, agg_other, vin, bout, F, Bv, part, lvl[2][2][2], gvin, gbout, total; };
 
 static LargePlan max_product_plan(int Dr, long long T, int batch) {
     LargePlan p = large_plan(Dr, T, batch);
+    if (p.DP < 128) p = element_plan(Dr, T, batch);   // short chunks: long sequences get the second scan level
     fill_last_round(p, T, batch);
     return p;
 }
@@ -1480,6 +1486,19 @@ static LargeMmWs large_mm_ws(int Dr, long long T, int batch) {
     w.F = o;         o = align_up(o + rows * Dr * sizeof(float), 256);
     w.Bv = o;        o = align_up(o + rows * Dr * sizeof(float), 256);
     w.part = o;      o = align_up(o + nc * sizeof(double), 256);
+    const Scan2 s2 = scan2_of(p);
+    for (int dir = 0; dir < 2; ++dir) {
+        size_t n = (size_t)p.cps;
+        for (int l = 0; l < 2; ++l) {
+            n = (n + 1) / 2;
+            const size_t cnt = s2.on ? n * batch : 0;
+            w.lvl[dir][l][0] = o; o = align_up(o + cnt * D * D * sizeof(float), 256);
+            w.lvl[dir][l][1] = o; o = align_up(o + cnt * 8 * sizeof(float), 256);
+        }
+    }
+    const size_t ng = s2.on ? (size_t)s2.G * batch : 0;
+    w.gvin = o;      o = align_up(o + ng * D * sizeof(float), 256);
+    w.gbout = o;     o = align_up(o + ng * D * sizeof(float), 256);
     w.total = o;
     return w;
 }
@@ -1507,14 +1526,45 @@ static int large_max_product_impl(const LargeArgs& a, float* mm, int32_t* path, 
     const dim3 block(256);
     launch("lv_aggregate", lv_aggregate_systolic_kernel<D>, dim3((unsigned)((p.nchunks + M::CPW - 1) / M::CPW)), block,
            st, a.A, a.ll, a.T, a.D, p.Lc, p.cps, p.nchunks, a.shared_model, agg, agg_other);
-    if constexpr (D <= 32)
-        launch("lm_carry", lv_carry_wave_kernel<D>, dim3(2u * (unsigned)a.batch), dim3(64), st, a.prior, a.D, p.cps,
-               a.shared_model, agg, vin, static_cast<const float*>(agg_other), bout, p.cps, 1,
-               static_cast<const float*>(nullptr));
-    else
-        launch("lm_carry", lv_carry_kernel<D>, dim3(2u * (unsigned)a.batch), block, st, a.prior, a.D, p.cps,
-               a.shared_model, agg, vin, static_cast<const float*>(agg_other), bout, p.cps, 1,
-               static_cast<const float*>(nullptr));
+    const Scan2 s2 = scan2_of(p);
+    auto carry = [&](int cps, const float* mats, const float* mats_other, float* out, float* out_b, int seglen, int nseg,
+                     const float* start, const float* start_b) {
+        const unsigned blocks = 2u * (unsigned)a.batch * (unsigned)nseg;
+        if constexpr (D <= 32)
+            launch("lm_carry", lv_carry_wave_kernel<D>, dim3(blocks), dim3(64), st, a.prior, a.D, cps, a.shared_model, mats,
+                   out, mats_other, out_b, seglen, nseg, start, start_b);
+        else
+            launch("lm_carry", lv_carry_kernel<D>, dim3(blocks), block, st, a.prior, a.D, cps, a.shared_model, mats, out,
+                   mats_other, out_b, seglen, nseg, start, start_b);
+    };
+    if (s2.on) {
+        // group aggregates in both orientations: the other orientation holds transposes, whose ordered product is
+        // the transpose of the product in reverse order, so its operands trade places
+        constexpr int transposed = (D <= 32) ? 1 : 0;
+        float* gvin = reinterpret_cast<float*>(ws + w.gvin);
+        float* gbout = reinterpret_cast<float*>(ws + w.gbout);
+        const float* top[2] = {agg, agg_other};
+        for (int dir = 0; dir < 2; ++dir) {
+            const float* cur = top[dir];
+            const float* curm = nullptr;
+            int n = p.cps;
+            for (int l = 0; l < s2.k; ++l) {
+                const int n_out = (n + 1) / 2;
+                float* o = reinterpret_cast<float*>(ws + w.lvl[dir][l & 1][0]);
+                float* om = reinterpret_cast<float*>(ws + w.lvl[dir][l & 1][1]);
+                launch("lv_tree_product", lv_tree_product_kernel<D>, dim3((unsigned)((long long)n_out * a.batch * (D / 16))),
+                       block, st, cur, static_cast<const double*>(nullptr), curm, n, n_out, dir == 0 ? transposed : 1 - transposed,
+                       o, static_cast<double*>(nullptr), om);
+                cur = o; curm = om;
+                n = n_out;
+            }
+            top[dir] = cur;
+        }
+        carry(s2.G, top[0], top[1], gvin, gbout, s2.G, 1, nullptr, nullptr);
+        carry(p.cps, agg, agg_other, vin, bout, s2.g, s2.G, gvin, gbout);
+    } else {
+        carry(p.cps, agg, agg_other, vin, bout, p.cps, 1, nullptr, nullptr);
+    }
     if constexpr (D <= 32) {
         const int half = (int)((p.nchunks + 15) / 16);
         launch("lm_apply", lm_apply_row_kernel<D>, dim3(2u * (unsigned)half), block, st, a.prior, a.A, a.ll, a.T, a.D, p.Lc,
