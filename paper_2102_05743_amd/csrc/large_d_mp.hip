@@ -3,12 +3,15 @@
 // Max-product operator of Definition 5 on logarithms, (a v b)(i,k) = max_j [a(i,j) + b(j,k)]:
 // no matrix-core form exists for (max,+), so chunk aggregates are built on the vector ALUs.
 //   aggregate  chunk aggregates P_c = psi_{k0} v ... v psi_{k1-1}, psi_k(i,j) = log A(i,j) + ll_k(j)
-//   carry      V at chunk boundaries: v <- v v P_c, sequential over the chunks of a sequence
+//   carry      V at chunk boundaries: v <- v v P_c along the chunks of a sequence; long sequences get a
+//              second scan level (aggregates of groups of chunks by a tree of pairwise products, a walk
+//              over the groups, then walks inside all groups at once)
 //   forward    V_k and back-pointers u_{k-1}(x_k) inside each chunk (Sec. IV-A), the chunk's
 //              back-pointer map (state at its last step -> state at the previous chunk's last
 //              step), x*_T = argmax V_T in the sequence's last chunk, chunk-local log-probability
 //   suffix     reversed all-prefix-sums under composition over the chunk maps, collapsed to the
-//              single state it is applied to: the state at every chunk's last step; log-probability
+//              single state it is applied to: the state at every chunk's last step (grouped the same
+//              way for long sequences); log-probability
 //   path       back-pointer walk inside each chunk
 // Aggregates and carries are scale-free (offsets are dropped); the log-probability is the sum of the
 // chunk-local growths of max_j V, each measured from a carry renormalised to max 0.
@@ -16,6 +19,9 @@
 // The same aggregates and carries, run in both directions, also serve the paper's parallel
 // max-product algorithm as printed (Algorithm 5): maximum forward and backward potentials inside
 // the chunks and Theorem 4's per-step combination (lm_apply, lm_combine, lm_finalize below).
+// Aggregates that keep their offsets and the tree of products also give the block-wise elements of
+// Sec. V-B under this operator (lv_aggregate_offsets, lv_tree_product, lv_element_finish).
+// For D <= 32 the in-chunk recursions have row-parallel variants (one chunk per DPP row of 16 lanes).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 

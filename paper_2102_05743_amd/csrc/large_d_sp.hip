@@ -3,8 +3,10 @@
 // Chunked all-prefix-sums ("block-wise elements", Sec. V-B): time is cut into chunks of Lc steps.
 //   rowmax     m_t = max_j ll_t(j)                                   (one pass over the input)
 //   aggregate  chunk aggregates a_{k0-1:k0} (x) ... (x) a_{k1-2:k1-1} on the FP32 matrix cores
-//   carry      forward / backward potentials at chunk boundaries (vector x aggregate, sequential
-//              over the chunks of a sequence, both directions concurrently)
+//   product    aggregates of groups of consecutive chunks (second scan level of long sequences; applied
+//              repeatedly it also reduces a block to its single element, Sec. V-B)
+//   carry      forward / backward potentials at chunk boundaries (vector x aggregate along the groups,
+//              then inside all groups at once; both directions concurrently)
 //   forward    a_{0:k} inside each chunk (Theorem 1), written normalised = filtering distribution
 //   backward   a_{k:T+1} inside each chunk (Theorem 2)
 //   combine    p(x_k) = a_{0:k} a_{k:T+1} / Z_k, and log Z from the chunk-local evidences
