@@ -97,6 +97,19 @@ def test_long_sequences_use_the_second_scan_level(gu, D, T, B, shared):
     gu.check_viterbi(p, label=f"two-level D={D} T={T} B={B}")
 
 
+@pytest.mark.parametrize("D,T,B", [(16, 127 * 32, 1), (16, 128 * 32, 1), (16, 128 * 32 + 5, 2), (16, 1000 * 32 + 7, 1),
+                                   (32, 127 * 32, 1), (32, 128 * 32 + 1, 1), (32, 300 * 32 + 1, 2), (64, 128 * 32, 1),
+                                   (64, 129 * 32 + 3, 2), (128, 128 * 256 + 9, 1), (128, 127 * 256, 1)])
+def test_chunk_counts_around_the_second_level_threshold(gu, D, T, B):
+    """Sequence lengths that put the chunk count just below, at and above the point where the max-plus
+    paths switch to two scan levels, with ragged last groups and more than one sequence: decoding,
+    max-marginals and the smoother on the same inputs."""
+    p = wl.random_problem(D, T, batch=B, shared_model=(B == 1), seed=977 + D + T % 13)
+    gu.check_viterbi(p, label=f"threshold D={D} T={T} B={B}")
+    gu.check_max_product(p, label=f"threshold D={D} T={T} B={B}")
+    gu.check_smooth(p, label=f"threshold D={D} T={T} B={B}")
+
+
 # ---- the configurations at their full sizes, element by element against the oracle ----
 def test_config3_full_size(gu):
     p = wl.config3()
