@@ -9,6 +9,7 @@ Infinity Cache.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C2|C3|C4|C5]
     python bench.py --ge-sweep      (the paper's Gilbert-Elliott model over a range of T, Sec. VI)
+    python bench.py --machine-peaks (what library copy / GEMM kernels sustain on this GPU, beside the published peaks)
 
 --workload selects one of the other synthetic configurations (D=32 long sequence, 256 x D=16
 batch, D=128 compute-bound) for the same measurement; the headline line is the default, C2.
@@ -127,6 +128,51 @@ def ge_sweep() -> int:
     return 0
 
 
+def machine_peaks() -> int:
+    """What this GPU sustains on plain library kernels, beside the published peaks the rooflines use: device
+    copy, fill and read bandwidth over 1 GiB buffers and an FP32 GEMM.  Context for the roofline fractions (a
+    fraction of the published peak understates a kernel that runs at the rate the memory system can deliver)."""
+    import torch
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    dev = torch.device("cuda:0")
+    props = torch.cuda.get_device_properties(0)
+    n = 1 << 28                                   # 1 GiB of float32, four times the Infinity Cache
+    a = torch.ones(n, dtype=torch.float32, device=dev)
+    b = torch.empty_like(a)
+
+    def timed(fn, reps=20):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / reps
+
+    t_copy = timed(lambda: b.copy_(a))
+    t_fill = timed(lambda: b.fill_(1.0))
+    t_read = timed(lambda: torch.max(a))
+    m = 8192
+    x = torch.randn((m, m), dtype=torch.float32, device=dev)
+    y = torch.randn((m, m), dtype=torch.float32, device=dev)
+    z = torch.empty_like(x)
+    prev = torch.backends.cuda.matmul.allow_tf32
+    torch.backends.cuda.matmul.allow_tf32 = False
+    t_gemm = timed(lambda: torch.matmul(x, y, out=z), reps=10)
+    torch.backends.cuda.matmul.allow_tf32 = prev
+    out = {"device": props.name, "compute_units": props.multi_processor_count,
+           "memory_GiB": round(props.total_memory / 2 ** 30, 1),
+           "copy_GBs": 2 * 4 * n / t_copy / 1e9, "fill_GBs": 4 * n / t_fill / 1e9, "read_GBs": 4 * n / t_read / 1e9,
+           "sgemm_8192_TFLOPs": 2.0 * m ** 3 / t_gemm / 1e12,
+           "published": {"hbm_GBs": HBM_PEAK_GBS, "mfma_f32_TFLOPs": MFMA_F32_PEAK_TFLOPS, "valu_f32_TOPs": VALU_F32_PEAK_TOPS}}
+    print(json.dumps(out))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -144,7 +190,11 @@ def main() -> int:
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings)")
     ap.add_argument("--ge-sweep", action="store_true",
                     help="time both calls on the paper's Gilbert-Elliott model for T = 1e2 ... 2^24 instead")
+    ap.add_argument("--machine-peaks", action="store_true",
+                    help="measure what plain library kernels sustain on this GPU (copy / fill / read bandwidth, FP32 GEMM)")
     args = ap.parse_args()
+    if args.machine_peaks:
+        return machine_peaks()
     if args.ge_sweep:
         if args.gpus != 1:
             print("bench.py: this build runs on ONE GPU only; run it with --gpus 1", file=sys.stderr)
