@@ -53,3 +53,17 @@ def test_many_short_sequences(gu, D, T, B, shared):
     gu.check_viterbi(p, label=label)
     gu.check_max_product(p, label=label)
     gu.check_transition_counts(p, label=label)
+
+
+@pytest.mark.parametrize("D,T,B,ll_scale,zero_frac", [(16, 3000, 4, 30.0, 0.0), (16, 3000, 4, 8.0, 0.5), (32, 5000, 2, 30.0, 0.3),
+                                                      (12, 40000, 1, 20.0, 0.2), (4, 50000, 1, 40.0, 0.0), (64, 3000, 1, 30.0, 0.0),
+                                                      (128, 3000, 1, 30.0, 0.3), (24, 200, 50, 15.0, 0.6)])
+def test_wide_dynamic_range(gu, D, T, B, ll_scale, zero_frac):
+    """Log-likelihoods spread over tens of nats per step (emission factors down to e^-90 and below single-precision
+    range after a few steps) and models with many forbidden transitions: every rescaling in the kernels is exercised."""
+    p = wl.random_problem(D, T, batch=B, shared_model=(B == 1), seed=D + T + B, ll_scale=ll_scale, zero_frac=zero_frac)
+    label = f"D={D} T={T} B={B} ll_scale={ll_scale} zero_frac={zero_frac}"
+    gu.check_smooth(p, want_filtered=True, label=label)
+    gu.check_viterbi(p, label=label)
+    gu.check_max_product(p, label=label)
+    gu.check_transition_counts(p, label=label)
