@@ -78,88 +78,6 @@ __global__ __launch_bounds__(256) void tc_small_kernel(const float* __restrict__
 }
 
 // ---------------------------------------------------------------------------------------------
-// 9 <= D <= 128 (padded to DP): the workgroup's 16 x 16 threads each own a (DP/16)^2 block of the
-// matrix; SB steps are staged through LDS per round, their predictions reduced over the thread rows.
-template <int DP>
-__global__ __launch_bounds__(256) void tc_large_kernel(const float* __restrict__ A, const float* __restrict__ filt,
-                                                       const float* __restrict__ marg, long long T, int Dr, int G,
-                                                       int shared_model, float* __restrict__ partial) {
-    constexpr int TT = DP / 16;   // edge of a thread's block
-    constexpr int SB = 4;         // steps per round
-    __shared__ float fbuf[SB * DP];       // fh_{k-1} of the round's steps
-    __shared__ float gbuf[SB * DP];       // gamma_k
-    __shared__ float pbuf[4 * SB * DP];   // per-wave partial predictions
-    const int seq = blockIdx.x / G, g = blockIdx.x % G;
-    const StepRange sr = step_range(T, G, g);
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int ti = tid / 16, tj = tid % 16;
-    const float* Am = A + (shared_model ? 0 : (size_t)seq * Dr * Dr);
-    float a[TT][TT], acc[TT][TT];
-#pragma unroll
-    for (int r = 0; r < TT; ++r)
-#pragma unroll
-        for (int c = 0; c < TT; ++c) {
-            const int i = ti * TT + r, j = tj * TT + c;
-            a[r][c] = (i < Dr && j < Dr) ? Am[(size_t)i * Dr + j] : 0.0f;
-            acc[r][c] = 0.0f;
-        }
-    const float* fs = filt + (size_t)seq * T * Dr;
-    const float* ms = marg + (size_t)seq * T * Dr;
-    for (long long kb = sr.k0; kb < sr.k1; kb += SB) {
-        for (int idx = tid; idx < SB * DP; idx += 256) {
-            const int s = idx / DP, j = idx % DP;
-            const bool valid = (kb + s < sr.k1) && j < Dr;
-            fbuf[idx] = valid ? fs[(size_t)(kb + s - 1) * Dr + j] : 0.0f;
-            gbuf[idx] = valid ? ms[(size_t)(kb + s) * Dr + j] : 0.0f;
-        }
-        __syncthreads();
-        float fr[SB][TT], pp[SB][TT];
-#pragma unroll
-        for (int s = 0; s < SB; ++s) {
-#pragma unroll
-            for (int r = 0; r < TT; ++r) fr[s][r] = fbuf[s * DP + ti * TT + r];
-#pragma unroll
-            for (int c = 0; c < TT; ++c) {
-                float v = 0.0f;
-#pragma unroll
-                for (int r = 0; r < TT; ++r) v = fmaf(fr[s][r], a[r][c], v);
-                v += __shfl_xor(v, 16, 64);   // the wave's four thread rows
-                v += __shfl_xor(v, 32, 64);
-                pp[s][c] = v;
-            }
-        }
-        if (lane < 16) {
-#pragma unroll
-            for (int s = 0; s < SB; ++s)
-#pragma unroll
-                for (int c = 0; c < TT; ++c) pbuf[(wave * SB + s) * DP + tj * TT + c] = pp[s][c];
-        }
-        __syncthreads();
-#pragma unroll
-        for (int s = 0; s < SB; ++s) {
-            float w[TT];
-#pragma unroll
-            for (int c = 0; c < TT; ++c) {
-                const int j = tj * TT + c;
-                const float pred = (pbuf[(0 * SB + s) * DP + j] + pbuf[(1 * SB + s) * DP + j]) +
-                                   (pbuf[(2 * SB + s) * DP + j] + pbuf[(3 * SB + s) * DP + j]);
-                w[c] = pred > 0.0f ? gbuf[s * DP + j] / pred : 0.0f;
-            }
-#pragma unroll
-            for (int r = 0; r < TT; ++r)
-#pragma unroll
-                for (int c = 0; c < TT; ++c) acc[r][c] = fmaf(fr[s][r], w[c], acc[r][c]);
-        }
-        __syncthreads();   // the next round overwrites the staging buffers
-    }
-#pragma unroll
-    for (int r = 0; r < TT; ++r)
-#pragma unroll
-        for (int c = 0; c < TT; ++c)
-            partial[(size_t)blockIdx.x * DP * DP + (size_t)(ti * TT + r) * DP + tj * TT + c] = acc[r][c] * a[r][c];
-}
-
-// ---------------------------------------------------------------------------------------------
 // 9 <= D <= 32 (padded to DP = 16 or 32): one time step per DPP row of 16 lanes, sixteen steps per
 // workgroup round, no LDS in the loop.  Lane l holds components 16 q + l of fh_{k-1} and gamma_k.  Both the
 // prediction pred_k(j) = sum_i fh_{k-1}(i) A(i,j) and the outer product fh_{k-1}(i) w_k(j) pair component
@@ -249,6 +167,134 @@ __global__ __launch_bounds__(256) void tc_row_kernel(const float* __restrict__ A
         partial[(size_t)blockIdx.x * DP * DP + e] = (red[e] + red[DP * DP + e]) + (red[2 * DP * DP + e] + red[3 * DP * DP + e]);
 }
 
+// ---------------------------------------------------------------------------------------------
+// D > 32 (padded to DP = 64 or 128): both sums are dense contractions over a slab of 32 time steps and
+// run on the FP32 matrix cores (v_mfma_f32_32x32x2_f32):
+//     pred  (32 x DP)  = F_slab (32 x DP) * A (DP x DP)           first operand from LDS, second (A) in registers
+//     W     (32 x DP)  = Gamma_slab / pred                        element-wise on the result registers
+//     C     (DP x DP) += F_slab^T (DP x 32) * W (32 x DP)         first operand from LDS, second = the W registers
+// A wave owns a block of 32 columns j.  A result register r of lane group g = lane / 32 holds row
+// 8 (r / 4) + 4 g + r % 4 of its tile, and the second operand of the next product wants one row of W per
+// lane group: enumerating the time steps of the slab in exactly that order (first operand read from LDS
+// accordingly) lets the W registers be fed back as they are.  With DP = 64 there are two column blocks;
+// the other two waves take every second slab and the two partial results are added at the end.
+template <int DP>
+__global__ __launch_bounds__(256) void tc_mfma_kernel(const float* __restrict__ A, const float* __restrict__ filt,
+                                                      const float* __restrict__ marg, long long T, int Dr, int G,
+                                                      int shared_model, float* __restrict__ partial) {
+    static_assert(DP == 64 || DP == 128, "column blocks of 32");
+    constexpr int NB = DP / 32;          // column blocks = row blocks
+    constexpr int SPW = 4 / NB;          // waves sharing a column block, each on its own slabs
+    constexpr int SLAB = 32;
+    constexpr int STR = DP + 1;          // LDS row stride (floats): conflict-free for both access patterns
+    constexpr int PER = SPW * SLAB * DP / 256;   // staged values per thread and array
+    typedef float v16 __attribute__((ext_vector_type(16)));
+    __shared__ float fs[SPW * SLAB * STR];
+    __shared__ float gs[SPW * SLAB * STR];
+    const int seq = blockIdx.x / G, g = blockIdx.x % G;
+    const StepRange sr = step_range(T, G, g);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int cb = wave % NB, sp = wave / NB;
+    const int lg = lane >> 5, ln = lane & 31;
+    const float* Am = A + (shared_model ? 0 : (size_t)seq * Dr * Dr);
+    const float* fsq = filt + (size_t)seq * T * Dr;
+    const float* msq = marg + (size_t)seq * T * Dr;
+    // second operand of the first product: breg[kk] = A(2 kk + lg, 32 cb + ln)
+    float breg[DP / 2];
+#pragma unroll
+    for (int kk = 0; kk < DP / 2; ++kk) {
+        const int i = 2 * kk + lg, j = 32 * cb + ln;
+        breg[kk] = (i < Dr && j < Dr) ? Am[(size_t)i * Dr + j] : 0.0f;
+    }
+    v16 acc[NB];
+#pragma unroll
+    for (int rb = 0; rb < NB; ++rb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[rb][r] = 0.0f;
+    auto tile_row = [&](int r) { return 8 * (r / 4) + 4 * lg + (r % 4); };
+    float pf[PER], pg[PER];
+    auto load_round = [&](long long kb) {   // the SPW slabs starting at step kb, SLAB steps each
+#pragma unroll
+        for (int q = 0; q < PER; ++q) {
+            const int idx = q * 256 + tid;
+            const int s = idx / DP, i = idx % DP;        // s over SPW * SLAB steps
+            const long long k = kb + s;
+            const bool valid = k < sr.k1 && i < Dr;
+            pf[q] = valid ? fsq[(size_t)(k - 1) * Dr + i] : 0.0f;
+            pg[q] = valid ? msq[(size_t)k * Dr + i] : 0.0f;
+        }
+    };
+    auto store_round = [&]() {
+#pragma unroll
+        for (int q = 0; q < PER; ++q) {
+            const int idx = q * 256 + tid;
+            const int s = idx / DP, i = idx % DP;
+            fs[s * STR + i] = pf[q];
+            gs[s * STR + i] = pg[q];
+        }
+    };
+    const long long round_steps = (long long)SPW * SLAB;
+    if (sr.k0 < sr.k1) load_round(sr.k0);
+    for (long long kb = sr.k0; kb < sr.k1; kb += round_steps) {
+        __syncthreads();                 // the previous round's reads of the staging buffers are done
+        store_round();
+        __syncthreads();
+        if (kb + round_steps < sr.k1) load_round(kb + round_steps);   // in flight during the products
+        const float* fw = fs + sp * SLAB * STR;     // this wave's slab
+        const float* gw = gs + sp * SLAB * STR;
+        // pred = F_slab * A: rows = steps (ln), reduction over states i = 2 kk + lg
+        v16 pred;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) pred[r] = 0.0f;
+#pragma unroll
+        for (int kk = 0; kk < DP / 2; ++kk)
+            pred = __builtin_amdgcn_mfma_f32_32x32x2f32(fw[ln * STR + 2 * kk + lg], breg[kk], pred, 0, 0, 0);
+        // W = Gamma / pred in place (row tile_row(r), column 32 cb + ln)
+        v16 w;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const float gm = gw[tile_row(r) * STR + 32 * cb + ln];
+            w[r] = pred[r] > 0.0f ? gm * __builtin_amdgcn_rcpf(pred[r]) : 0.0f;
+        }
+        // C(row block rb) += F_slab^T * W: reduction over the slab's steps in the order of the result rows
+#pragma unroll
+        for (int rb = 0; rb < NB; ++rb)
+#pragma unroll
+            for (int pr = 0; pr < 16; ++pr)
+                acc[rb] = __builtin_amdgcn_mfma_f32_32x32x2f32(fw[tile_row(pr) * STR + 32 * rb + ln], w[pr], acc[rb], 0, 0, 0);
+    }
+    // entries times A(i, j); with two waves per column block their results are added through LDS first
+    __syncthreads();
+    if constexpr (SPW == 2) {
+        // waves with sp = 1 deposit into the (now free) staging buffers, waves with sp = 0 add
+        static_assert(SPW * SLAB * STR >= NB * 16 * 64, "room for a wave's partial results");
+        float* buf = (cb == 0) ? fs : gs;
+        if (sp == 1) {
+#pragma unroll
+            for (int rb = 0; rb < NB; ++rb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) buf[(rb * 16 + r) * 64 + lane] = acc[rb][r];
+        }
+        __syncthreads();
+        if (sp == 0) {
+#pragma unroll
+            for (int rb = 0; rb < NB; ++rb)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[rb][r] += buf[(rb * 16 + r) * 64 + lane];
+        }
+    }
+    if (sp == 0) {
+#pragma unroll
+        for (int rb = 0; rb < NB; ++rb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int i = 32 * rb + tile_row(r), j = 32 * cb + ln;
+                const float a = (i < Dr && j < Dr) ? Am[(size_t)i * Dr + j] : 0.0f;
+                partial[(size_t)blockIdx.x * DP * DP + (size_t)i * DP + j] = acc[rb][r] * a;
+            }
+    }
+}
+
 // counts[seq][i][j] = sum over the sequence's G partial sums, in fp64.  blockIdx.x = sequence,
 // blockIdx.y = group of EPB entries; the 256 threads are (entry, slice of the partial sums), slices
 // added in a fixed order.
@@ -300,14 +346,14 @@ static void launch_small(const EstepArgs& a, int G, float* partial) {
 }
 
 template <int DP>
-static void launch_large(const EstepArgs& a, int G, float* partial) {
-    launch("tc_accumulate", tc_large_kernel<DP>, dim3((unsigned)(a.batch * G)), dim3(256), a.stream, a.A, a.filtered,
+static void launch_row(const EstepArgs& a, int G, float* partial) {
+    launch("tc_accumulate", tc_row_kernel<DP>, dim3((unsigned)(a.batch * G)), dim3(256), a.stream, a.A, a.filtered,
            a.marginals, a.T, a.D, G, a.shared_model, partial);
 }
 
 template <int DP>
-static void launch_row(const EstepArgs& a, int G, float* partial) {
-    launch("tc_accumulate", tc_row_kernel<DP>, dim3((unsigned)(a.batch * G)), dim3(256), a.stream, a.A, a.filtered,
+static void launch_mfma(const EstepArgs& a, int G, float* partial) {
+    launch("tc_accumulate", tc_mfma_kernel<DP>, dim3((unsigned)(a.batch * G)), dim3(256), a.stream, a.A, a.filtered,
            a.marginals, a.T, a.D, G, a.shared_model, partial);
 }
 
@@ -328,8 +374,8 @@ int transition_counts(const EstepArgs& a, double* counts) {
         case 8: launch_small<8>(a, G, partial); break;
         case 16: launch_row<16>(a, G, partial); break;
         case 32: launch_row<32>(a, G, partial); break;
-        case 64: launch_large<64>(a, G, partial); break;
-        case 128: launch_large<128>(a, G, partial); break;
+        case 64: launch_mfma<64>(a, G, partial); break;
+        case 128: launch_mfma<128>(a, G, partial); break;
         default: return 2;
     }
     const int E = a.D * a.D;
