@@ -99,3 +99,20 @@ def test_argument_errors_are_caught_on_the_host():
     assert lib.hmm_block_carries(fake, fake, fake, fake, 3, 129, 1, 1, 1, fake, fake, fake, null) == 2
     for shape in [(1 << 20, 4, 1), (1 << 16, 128, 1), (4096, 16, 256), (1, 9, 1)]:
         assert hmm.hmm_block_element_workspace_bytes(*shape) >= 256
+
+
+def test_a_missing_library_is_an_error_not_a_fallback(monkeypatch, tmp_path):
+    """The product path has no CPU fallback: without the built HIP library every call must fail loudly."""
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "libhmmscan.so"))
+    with pytest.raises(RuntimeError, match="missing"):
+        binding.load_library()
+    with pytest.raises(RuntimeError, match="missing"):
+        hmm.hmm_workspace_bytes(1024, 4, 1)
+    # and nothing in the package reaches for the oracle
+    pkg = os.path.join(ROOT, "paper_2102_05743_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for fn in files:
+            if fn.endswith((".py", ".hip", ".hpp", ".h")):
+                text = open(os.path.join(dirpath, fn)).read()
+                assert "import oracle" not in text and "from oracle" not in text and "hmm_oracle" not in text, fn
