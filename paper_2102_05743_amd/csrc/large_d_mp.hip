@@ -793,31 +793,49 @@ __global__ __launch_bounds__(128) void lv_group_chase_kernel(const uint8_t* __re
 }
 
 // ---------------------------------------------------------------------------------------------
-// Back-pointer walk inside each chunk from the state at its last step; coalesced path write.
+// Back-pointer walk inside each chunk from the state at its last step; coalesced path write.  One wave
+// per chunk (the walk itself is a chain of dependent LDS look-ups by one lane; several chunks per
+// workgroup keep more of those chains in flight per compute unit), cpw chunks per workgroup.
 template <int D>
-__global__ __launch_bounds__(256) void lv_path_kernel(long long T, int Lc, int cps, long long nchunks,
+__global__ __launch_bounds__(256) void lv_path_kernel(long long T, int Lc, int cps, long long nchunks, int cpw,
                                                       const uint8_t* __restrict__ bp, const int* __restrict__ xend,
                                                       int32_t* __restrict__ path) {
-    extern __shared__ __align__(16) unsigned char dyn_lds[];   // [Lc*D] back-pointers, then [Lc] path (int32)
-    const long long chunk = blockIdx.x;
+    extern __shared__ __align__(16) unsigned char dyn_lds[];   // per chunk: [Lc*D] back-pointers, then [Lc] path (int32)
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    if (wave >= cpw) return;                                   // uniform over the wave; no workgroup barrier below
+    const long long chunk = (long long)blockIdx.x * cpw + wave;
     const ChunkCoord cc = chunk_coord(chunk, nchunks, cps, T, Lc);
-    uint8_t* bpl = dyn_lds;
-    int32_t* pl = reinterpret_cast<int32_t*>(dyn_lds + (size_t)Lc * D);
+    if (cc.nsteps == 0) return;
+    unsigned char* base = dyn_lds + (size_t)wave * ((size_t)Lc * D + (size_t)Lc * sizeof(int32_t));
+    uint8_t* bpl = base;
+    int32_t* pl = reinterpret_cast<int32_t*>(base + (size_t)Lc * D);
     const uint8_t* src = bp + ((size_t)cc.seq * T + cc.t0) * D;
     const int nbytes = cc.nsteps * D;
-    for (int idx = threadIdx.x * 4; idx < nbytes; idx += 256 * 4)
-        *reinterpret_cast<uint32_t*>(bpl + idx) = *reinterpret_cast<const uint32_t*>(src + idx);
-    __syncthreads();
-    if (threadIdx.x == 0) {
+    // 16-byte pieces, four loads in flight per lane (the wave copies its chunk alone)
+    for (int idx = lane * 16; idx < nbytes; idx += 4 * 64 * 16) {
+        uint4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int o = idx + u * 64 * 16;
+            v[u] = *reinterpret_cast<const uint4*>(src + (o < nbytes ? o : idx));
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int o = idx + u * 64 * 16;
+            if (o < nbytes) *reinterpret_cast<uint4*>(bpl + o) = v[u];
+        }
+    }
+    wave_lds_sync();
+    if (lane == 0) {
         int x = xend[chunk];
         for (int s = cc.nsteps - 1; s >= 0; --s) {
             pl[s] = x;
             x = bpl[(size_t)s * D + x];
         }
     }
-    __syncthreads();
+    wave_lds_sync();
     int32_t* dst = path + (size_t)cc.seq * T + cc.t0;
-    for (int s = threadIdx.x; s < cc.nsteps; s += 256) dst[s] = pl[s];
+    for (int s = lane; s < cc.nsteps; s += 64) dst[s] = pl[s];
 }
 
 // =============================================================================================
@@ -1465,9 +1483,10 @@ static int large_viterbi_impl(const LargeArgs& a, int32_t* path, double* logprob
         launch("lv_suffix", lv_suffix_kernel<D>, dim3((unsigned)a.batch), block, st, (const uint8_t*)cmap, (const int*)xstar,
                p.cps, xend, (const double*)part, p.cps, logprob_out);
     }
-    const size_t path_lds = (size_t)p.Lc * D + (size_t)p.Lc * sizeof(int32_t);
-    launch_dyn("lv_path", lv_path_kernel<D>, dim3((unsigned)p.nchunks), block, path_lds, st, a.T, p.Lc, p.cps, p.nchunks,
-               bp, xend, path);
+    const size_t path_lds = (size_t)p.Lc * D + (size_t)p.Lc * sizeof(int32_t);   // per chunk
+    const int cpw = path_lds * 4 <= 48 * 1024 ? 4 : path_lds * 2 <= 48 * 1024 ? 2 : 1;
+    launch_dyn("lv_path", lv_path_kernel<D>, dim3((unsigned)((p.nchunks + cpw - 1) / cpw)), block, path_lds * cpw, st, a.T,
+               p.Lc, p.cps, p.nchunks, cpw, (const uint8_t*)bp, (const int*)xend, path);
     return hipGetLastError() == hipSuccess ? 0 : 4;
 }
 
