@@ -18,6 +18,12 @@
  * whose evidence is impossible under every state (a log-likelihood row that is
  * all -inf, or Z = 0) is not an error: the returned log-likelihood /
  * log-probability is then -inf or NaN and the marginals / path are unspecified.
+ * The same holds for evidence that is impossible within single-precision range:
+ * hmm_smooth works on probabilities (fp32, rescaled by powers of two), so a state
+ * whose filtered probability falls below 2^-126 of the step's largest is lost; if
+ * zero transitions then leave only states that later evidence rules out by more
+ * than about e^87, the log-likelihood is NaN.  The max-product calls work on
+ * logarithms and have no such limit.
  *
  * Concurrency.  Calls may be enqueued back to back on one stream.  For small state
  * spaces (D <= 8) and shapes whose tiles all fit the device at once, a call is a

@@ -22,6 +22,8 @@ def block_elements(A, blocks, max_product: bool = False):
     import torch
     els, lss = [], []
     for ll in blocks:
+        if ll.data_ptr() % 16 != 0 or not ll.is_contiguous():
+            ll = ll.clone(memory_format=torch.contiguous_format)   # a view into a longer array: the library wants 16-byte alignment
         el, ls = _b.hmm_block_element(A, ll, max_product=max_product)
         els.append(el)
         lss.append(ls)

@@ -167,6 +167,23 @@ def test_blockwise_max_marginals_equal_the_whole_sequence(kind, kw, cuts):
     assert worst <= 1.0
 
 
+def test_blocks_that_are_unaligned_views_of_a_longer_array():
+    """Blocks cut out of one resident array at odd D are contiguous views that start off a 16-byte boundary."""
+    p = wl.random_problem(65, 300, seed=41)
+    ll = _dev(p.loglik)
+    blocks = [ll[:, :113], ll[:, 113:114], ll[:, 114:]]
+    assert any(b.data_ptr() % 16 for b in blocks)
+    margs, _, total = blockwise.smooth_blocks(_dev(p.prior), _dev(p.A), blocks)
+    paths, lp = blockwise.viterbi_blocks(_dev(p.prior), _dev(p.A), blocks)
+    torch.cuda.synchronize()
+    m0, _, L0 = oracle.smooth(p.prior[0], p.A[0], p.loglik[0], want_filtered=False)
+    p0, lp0 = oracle.viterbi(p.prior[0], p.A[0], p.loglik[0])
+    assert np.abs(torch.cat(margs, dim=1).cpu().numpy()[0] - m0).max() <= gu.MARG_ATOL
+    assert abs(float(total[0]) - L0) <= gu.LOGLIK_RTOL * abs(L0)
+    assert abs(float(lp[0]) - lp0) <= gu.LOGPROB_RTOL * abs(lp0)
+    assert (torch.cat(paths, dim=1).cpu().numpy()[0] == p0).all()
+
+
 def test_blockwise_argument_errors():
     A = torch.zeros((1, 4, 4), device="cuda:0")
     ll = torch.zeros((1, 10, 4), device="cuda:0")
