@@ -892,24 +892,19 @@ __global__ __launch_bounds__(256) void ld_apply_kernel(const float* __restrict__
 // by r lanes (a DPP modifier), multiplied by a register that is constant per (r, block pair).
 // Sixteen chunks advance per workgroup, independently; the normaliser of a step is computed beside
 // the next step's products and applied one step late, so a step's dependent chain is the products
-// and two multiplications.  First half of the grid: forward chunks, second half: backward chunks.
-template <int D>
-__global__ __launch_bounds__(256) void ld_apply_row_kernel(const float* __restrict__ prior, const float* __restrict__ A,
-                                                           const float* __restrict__ ll,
-                                                           const float* __restrict__ rowmax, long long T, int Dr,
-                                                           int Lc, int cps, long long nchunks, int shared_model,
-                                                           const float* __restrict__ fin,
-                                                           const float* __restrict__ bout, float* __restrict__ F,
-                                                           float* __restrict__ Bv, double* __restrict__ part,
-                                                           int half) {
-    static_assert(D == 16 || D == 32, "one DPP row per chunk");
+// and two multiplications.  FUSED (enough chunks to fill the machine with one row each): a row first
+// runs the forward recursion of its chunk, which leaves the filtering distributions in F, then the
+// backward recursion, which reads them back (every lane the values it stored itself) and writes the
+// marginals f_k b_k / Z_k, so that backward potentials never reach memory.  Otherwise the two recursions
+// of a chunk run concurrently in different workgroups (first half of the grid forward, second half
+// backward, writing the backward potentials) and a separate pass forms the marginals.
+template <int D, bool BACKWARD, bool FUSED>
+HMM_DEV void apply_row_pass(const float* __restrict__ Am, const float* __restrict__ lseq,
+                            const float* __restrict__ mseq, const ChunkCoord& cc, int Dr, int Lc, bool first_chunk,
+                            const float (&start)[D / 16], float* fseq, float* __restrict__ gseq, double* part_out) {
     constexpr int NQ = D / 16;
     constexpr int PFD = 8;                                  // steps of log-likelihoods in flight
-    const bool backward = (int)blockIdx.x >= half;
     const int l = threadIdx.x & 15;
-    const long long chunk = (long long)(backward ? blockIdx.x - half : blockIdx.x) * 16 + (threadIdx.x >> 4);
-    const ChunkCoord cc = chunk_coord(chunk, nchunks, cps, T, Lc);
-    const float* Am = A + (shared_model ? 0 : (size_t)cc.seq * Dr * Dr);
     // forward: a[(qs, qd, r)] = A(16 qs + (l - r) mod 16, 16 qd + l); backward: A(16 qd + l, 16 qs + (l - r) mod 16)
     float a[NQ * NQ * 16];
 #pragma unroll
@@ -919,58 +914,50 @@ __global__ __launch_bounds__(256) void ld_apply_row_kernel(const float* __restri
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int src = 16 * qs + ((l - r) & 15), dst = 16 * qd + l;
-                const int i = backward ? dst : src, j = backward ? src : dst;
+                const int i = BACKWARD ? dst : src, j = BACKWARD ? src : dst;
                 float v = (i == j) ? 1.0f : 0.0f;
                 if (i < Dr && j < Dr) v = Am[(size_t)i * Dr + j];
                 a[(qs * NQ + qd) * 16 + r] = v;
             }
-    const float* lseq = ll + (size_t)cc.seq * T * Dr;
-    const float* mseq = rowmax + (size_t)cc.seq * T;
-    float* oseq = (backward ? Bv : F) + (size_t)cc.seq * T * Dr;
-    const bool first_chunk = cc.nsteps > 0 && (chunk % cps) == 0;
     // step order: forward s = 0, 1, ...; backward s = nsteps-1, nsteps-2, ...  (pos = position in that order)
-    auto step_at = [&](int pos) { return backward ? cc.nsteps - 1 - pos : pos; };
-    float xq[PFD][NQ], mq[PFD];
+    auto step_at = [&](int pos) { return BACKWARD ? cc.nsteps - 1 - pos : pos; };
+    float xq[PFD][NQ], mq[PFD], fq[PFD][NQ];
     // Running pointers instead of index arithmetic per step.  Fetches are unconditional (the compiler
     // can then count outstanding loads exactly); past the chunk's end they repeat its last position.
     const int s_first = cc.nsteps > 0 ? step_at(0) : 0;
-    const long long stride = backward ? -(long long)Dr : (long long)Dr;
+    const long long stride = BACKWARD ? -(long long)Dr : (long long)Dr;
     const float* lp = lseq + (size_t)(cc.t0 + s_first) * Dr;
     const float* mp = mseq + (cc.t0 + s_first);
-    float* op = oseq + (size_t)(cc.t0 + s_first) * Dr;
+    const float* fp = fseq + (size_t)(cc.t0 + s_first) * Dr;
+    float* op = (BACKWARD ? gseq : fseq) + (size_t)(cc.t0 + s_first) * Dr;
     int colq[NQ];
 #pragma unroll
     for (int q = 0; q < NQ; ++q) colq[q] = (16 * q + l) < Dr ? 16 * q + l : 0;
     int fetched = 0;
-    auto fetch = [&](float (&x)[NQ], float& m) {
+    auto fetch = [&](float (&x)[NQ], float (&f)[NQ], float& m) {
         m = *mp;
 #pragma unroll
-        for (int q = 0; q < NQ; ++q) x[q] = lp[colq[q]];
+        for (int q = 0; q < NQ; ++q) {
+            x[q] = lp[colq[q]];
+            if constexpr (BACKWARD && FUSED) f[q] = fp[colq[q]];
+        }
         ++fetched;
         if (fetched < cc.nsteps) {
             lp += stride;
-            mp += backward ? -1 : 1;
+            fp += stride;
+            mp += BACKWARD ? -1 : 1;
         }
     };
     float h[NQ];
 #pragma unroll
-    for (int q = 0; q < NQ; ++q) {
-        const int j = 16 * q + l;
-        float v = 0.0f;
-        if (cc.nsteps > 0) {
-            if (backward) v = bout[(size_t)chunk * D + j];
-            else if (first_chunk) v = (j < Dr) ? prior[(shared_model ? 0 : (size_t)cc.seq * Dr) + j] : 0.0f;
-            else v = fin[(size_t)chunk * D + j];
-        }
-        h[q] = v;
-    }
+    for (int q = 0; q < NQ; ++q) h[q] = start[q];
 #pragma unroll
-    for (int p = 0; p < PFD; ++p) fetch(xq[p], mq[p]);
+    for (int p = 0; p < PFD; ++p) fetch(xq[p], fq[p], mq[p]);
     float hs = h[0];
 #pragma unroll
     for (int q = 1; q < NQ; ++q) hs += h[q];
     // forward: every chunk but the sequence's first starts from a vector summing to one; backward: any scale
-    float inv = (!backward && first_chunk) ? 1.0f : __builtin_amdgcn_rcpf(row_allsum(hs));
+    float inv = (!BACKWARD && first_chunk) ? 1.0f : __builtin_amdgcn_rcpf(row_allsum(hs));
     // chunk evidence: sum of the steps' emission maxima, and the product of the steps' normalisers kept as
     // mantissa and binary exponent (one logarithm per chunk instead of one per step)
     float msum = 0.0f, cmant = 1.0f;
@@ -980,17 +967,18 @@ __global__ __launch_bounds__(256) void ld_apply_row_kernel(const float* __restri
         for (int p = 0; p < PFD; ++p) {
             const int pos = p0 + p;
             const bool active = pos < cc.nsteps;
-            const int s = step_at(pos);
-            const long long t = cc.t0 + s;
+            const long long t = cc.t0 + step_at(pos);
             const float mm = (mq[p] == -INFINITY) ? 0.0f : mq[p];
-            float e[NQ];
+            float e[NQ], fk[NQ];
 #pragma unroll
             for (int q = 0; q < NQ; ++q) {
-                const float x = (16 * q + l) < Dr ? xq[p][q] : -INFINITY;
+                const bool real = (16 * q + l) < Dr;
+                const float x = real ? xq[p][q] : -INFINITY;
                 e[q] = __builtin_amdgcn_exp2f(fmaf(x, LOG2E, -LOG2E * mm));
+                fk[q] = (BACKWARD && FUSED && real) ? fq[p][q] : 0.0f;
             }
-            fetch(xq[p], mq[p]);
-            if (!backward) {
+            fetch(xq[p], fq[p], mq[p]);
+            if constexpr (!BACKWARD) {
                 float g[NQ];
                 float acc[NQ][4];
                 row_matvec_terms<NQ>(h, a, acc);
@@ -1018,22 +1006,27 @@ __global__ __launch_bounds__(256) void ld_apply_row_kernel(const float* __restri
                     cexp += __builtin_amdgcn_frexp_expf(cp);
                 }
             } else {
-                float bs[NQ], u[NQ];
+                float bs[NQ], u[NQ], gam[NQ];
 #pragma unroll
                 for (int q = 0; q < NQ; ++q) {
-                    bs[q] = h[q] * inv;        // any positive scale will do: the marginal is normalised afterwards
+                    bs[q] = h[q] * inv;        // any positive scale will do: the marginal is normalised below
                     u[q] = e[q] * bs[q];
+                    gam[q] = fk[q] * bs[q];
                 }
-                float ss = bs[0];
+                float ss = bs[0], gs = gam[0];
 #pragma unroll
-                for (int q = 1; q < NQ; ++q) ss += bs[q];
+                for (int q = 1; q < NQ; ++q) {
+                    ss += bs[q];
+                    gs += gam[q];
+                }
                 const float ic = __builtin_amdgcn_rcpf(row_allsum(ss));
+                const float ig = __builtin_amdgcn_rcpf(row_allsum(gs));   // 1 / Z_k in this scaling
                 float acc[NQ][4];
                 row_matvec_terms<NQ>(u, a, acc);
                 if (active) {
 #pragma unroll
                     for (int q = 0; q < NQ; ++q) {
-                        if (16 * q + l < Dr) op[16 * q + l] = bs[q];
+                        if (16 * q + l < Dr) op[16 * q + l] = FUSED ? gam[q] * ig : bs[q];   // p(x_t | y_{1:T}), or b_t
                         if (t > 0) h[q] = (acc[q][0] + acc[q][1]) + (acc[q][2] + acc[q][3]);
                     }
                     op += stride;
@@ -1042,8 +1035,47 @@ __global__ __launch_bounds__(256) void ld_apply_row_kernel(const float* __restri
             }
         }
     }
-    if (!backward && cc.nsteps > 0 && l == 0)
-        part[chunk] = (double)msum + (double)logf(cmant) + 0.6931471805599453 * (double)cexp;
+    if constexpr (!BACKWARD) {
+        if (cc.nsteps > 0 && l == 0)
+            *part_out = (double)msum + (double)logf(cmant) + 0.6931471805599453 * (double)cexp;
+    }
+}
+
+// out: the marginals (FUSED) or the backward potentials; half: workgroups per direction (not FUSED)
+template <int D, bool FUSED>
+__global__ __launch_bounds__(256) void ld_apply_row_kernel(const float* __restrict__ prior, const float* __restrict__ A,
+                                                           const float* __restrict__ ll,
+                                                           const float* __restrict__ rowmax, long long T, int Dr,
+                                                           int Lc, int cps, long long nchunks, int shared_model,
+                                                           const float* __restrict__ fin,
+                                                           const float* __restrict__ bout, float* F,
+                                                           float* __restrict__ out, double* __restrict__ part,
+                                                           int half) {
+    static_assert(D == 16 || D == 32, "one DPP row per chunk");
+    constexpr int NQ = D / 16;
+    const int l = threadIdx.x & 15;
+    const bool backward = !FUSED && (int)blockIdx.x >= half;
+    const long long chunk = (long long)(backward ? blockIdx.x - half : blockIdx.x) * 16 + (threadIdx.x >> 4);
+    const ChunkCoord cc = chunk_coord(chunk, nchunks, cps, T, Lc);
+    const float* Am = A + (shared_model ? 0 : (size_t)cc.seq * Dr * Dr);
+    const float* lseq = ll + (size_t)cc.seq * T * Dr;
+    const float* mseq = rowmax + (size_t)cc.seq * T;
+    float* fseq = F + (size_t)cc.seq * T * Dr;
+    float* gseq = out + (size_t)cc.seq * T * Dr;
+    const bool first_chunk = cc.nsteps > 0 && (chunk % cps) == 0;
+    float hf[NQ], hb[NQ];
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) {
+        const int j = 16 * q + l;
+        hf[q] = hb[q] = 0.0f;
+        if (cc.nsteps > 0) {
+            if (first_chunk) hf[q] = (j < Dr) ? prior[(shared_model ? 0 : (size_t)cc.seq * Dr) + j] : 0.0f;
+            else hf[q] = fin[(size_t)chunk * D + j];
+            hb[q] = bout[(size_t)chunk * D + j];
+        }
+    }
+    if (!backward) apply_row_pass<D, false, FUSED>(Am, lseq, mseq, cc, Dr, Lc, first_chunk, hf, fseq, gseq, part + chunk);
+    if (FUSED || backward) apply_row_pass<D, true, FUSED>(Am, lseq, mseq, cc, Dr, Lc, first_chunk, hb, fseq, gseq, nullptr);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1220,7 +1252,7 @@ LargePlan large_plan(int Dr, long long T, int batch) {
 // of g chunks whose aggregates are formed by ld_product.  With a product hop costing about 8.4
 // (D >= 64) or 5.4 (D <= 32) vector hops, g + chunks/g vector hops and g product hops are fewest in
 // total near g = sqrt(0.106 chunks) resp. sqrt(0.156 chunks).
-struct SmoothPlan { int DP, Lc, cps; long long nchunks; int g, G; bool two_level; };
+struct SmoothPlan { int DP, Lc, cps; long long nchunks; int g, G; bool two_level, fused_apply; };
 
 static SmoothPlan smooth_plan(int Dr, long long T, int batch) {
     SmoothPlan p;
@@ -1236,6 +1268,9 @@ static SmoothPlan smooth_plan(int Dr, long long T, int batch) {
     p.Lc = (int)Lc;
     p.cps = (int)((T + p.Lc - 1) / p.Lc);
     p.nchunks = (long long)p.cps * batch;
+    // D <= 32: forward, backward and marginals in one pass per chunk once that alone gives every SIMD a wave
+    // (four chunks per wave); below that the two directions run side by side
+    p.fused_apply = p.DP <= 32 && p.nchunks >= 4096;
     p.two_level = p.cps > 96;
     if (p.two_level) {
         int g = (int)sqrt((p.DP >= 64 ? 0.106 : 0.156) * (double)p.cps);
@@ -1268,7 +1303,7 @@ static LargeSmoothWs large_smooth_ws(int Dr, long long T, int batch, bool own_F)
     w.gfin = o;   o = align_up(o + ng * D * sizeof(float), 256);
     w.gbout = o;  o = align_up(o + ng * D * sizeof(float), 256);
     w.F = o;      o = align_up(o + (own_F ? rows * Dr * sizeof(float) : 0), 256);
-    w.Bv = o;     o = align_up(o + rows * Dr * sizeof(float), 256);
+    w.Bv = o;     o = align_up(o + (p.fused_apply ? 0 : rows * Dr * sizeof(float)), 256);
     w.part = o;   o = align_up(o + nc * sizeof(double), 256);
     w.total = o;
     return w;
@@ -1335,20 +1370,30 @@ static int large_smooth_impl(const LargeArgs& a, float* marg, float* filt, doubl
         launch_carry<D>(st, a, p.cps, agg, aggT, exps, fin, bout, p.cps, 1, nullptr, nullptr);
     }
     const int half = (int)((p.nchunks + C::VCPW - 1) / C::VCPW);
+    bool marginals_done = false;
     if constexpr (D <= 32) {
         const int rhalf = (int)((p.nchunks + 15) / 16);
-        launch("ld_apply", ld_apply_row_kernel<D>, dim3(2u * (unsigned)rhalf), block, st, a.prior, a.A, a.ll, rowmax, a.T,
-               a.D, p.Lc, p.cps, p.nchunks, a.shared_model, fin, bout, F, Bv, part, rhalf);
+        if (p.fused_apply) {
+            // both recursions and the marginals in one pass over the chunks
+            launch("ld_apply", ld_apply_row_kernel<D, true>, dim3((unsigned)rhalf), block, st, a.prior, a.A, a.ll, rowmax,
+                   a.T, a.D, p.Lc, p.cps, p.nchunks, a.shared_model, fin, bout, F, marg, part, rhalf);
+            marginals_done = true;
+        } else {
+            launch("ld_apply", ld_apply_row_kernel<D, false>, dim3(2u * (unsigned)rhalf), block, st, a.prior, a.A, a.ll,
+                   rowmax, a.T, a.D, p.Lc, p.cps, p.nchunks, a.shared_model, fin, bout, F, Bv, part, rhalf);
+        }
     } else {
         launch("ld_apply", ld_apply_kernel<D>, dim3(2u * (unsigned)half), block, st, a.prior, a.A, a.ll, rowmax, a.T, a.D,
                p.Lc, p.cps, p.nchunks, a.shared_model, fin, bout, F, Bv, part, half);
     }
-    const int lpr = (a.D + 3) / 4;
-    int width = 1;
-    while (width < lpr) width <<= 1;
-    const long long rows_per_block = 4LL * STREAM_UNROLL * (64 / width);
-    launch("ld_combine", ld_combine_kernel, dim3((unsigned)((rows + rows_per_block - 1) / rows_per_block)), block, st, F, Bv,
-           rows, a.D, marg);
+    if (!marginals_done) {
+        const int lpr = (a.D + 3) / 4;
+        int width = 1;
+        while (width < lpr) width <<= 1;
+        const long long rows_per_block = 4LL * STREAM_UNROLL * (64 / width);
+        launch("ld_combine", ld_combine_kernel, dim3((unsigned)((rows + rows_per_block - 1) / rows_per_block)), block, st, F,
+               Bv, rows, a.D, marg);
+    }
     launch("ld_finalize", ld_finalize_kernel, dim3((unsigned)a.batch), block, st, part, p.cps, loglik_out);
     return hipGetLastError() == hipSuccess ? 0 : 4;
 }
