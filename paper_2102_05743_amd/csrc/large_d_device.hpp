@@ -137,6 +137,13 @@ HMM_DEV float row_allmax(float v) {
     v = fmaxf(v, row_rot<1>(v));
     return v;
 }
+HMM_DEV float row_allmin(float v) {
+    v = fminf(v, row_rot<8>(v));
+    v = fminf(v, row_rot<4>(v));
+    v = fminf(v, row_rot<2>(v));
+    v = fminf(v, row_rot<1>(v));
+    return v;
+}
 
 // acc[r & 3] += (x rotated by r lanes inside its DPP row) * a[r] for r = 0..15: sixteen multiply-adds
 // whose first operand is read through the DPP rotation itself (v_fmac_f32 with a row_ror modifier),

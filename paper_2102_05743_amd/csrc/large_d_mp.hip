@@ -987,21 +987,18 @@ __global__ __launch_bounds__(256) void lm_apply_kernel(const float* __restrict__
 // row's vector rotated by r lanes (an operand modifier of the add) against constants
 // la[qd][16 qs + r] = log A(16 qs + (l - r) mod 16, 16 qd + l)   (forward; transposed for the backward pass),
 // and the row's maximum takes four rotate-and-max steps.  Log-likelihoods are prefetched PFD steps ahead.
-template <int D>
-__global__ __launch_bounds__(256) void lm_apply_row_kernel(const float* __restrict__ prior, const float* __restrict__ A,
-                                                           const float* __restrict__ ll, long long T, int Dr, int Lc,
-                                                           int cps, long long nchunks, int shared_model,
-                                                           const float* __restrict__ vin, const float* __restrict__ bout,
-                                                           float* __restrict__ F, float* __restrict__ Bv,
-                                                           double* __restrict__ part, int half) {
-    static_assert(D == 16 || D == 32, "one DPP row per chunk");
+// FUSED (enough chunks to fill the machine with one row each): a row runs the forward pass of its chunk,
+// which leaves log psi~^f in F, then the backward pass, which reads it back (every lane the values it stored
+// itself) and writes Theorem 4's combination -- max-marginals and their lowest maximiser -- directly.
+// Otherwise the two passes of a chunk run in different workgroups (first half of the grid forward, second
+// half backward, writing log psi~^b) and lm_combine follows.
+template <int D, bool BACKWARD, bool FUSED>
+HMM_DEV void lm_row_pass(const float* __restrict__ Am, const float* __restrict__ lseq, const ChunkCoord& cc, int Dr, int Lc,
+                         bool first_chunk, const float (&start_v)[D / 16], float* fseq, float* __restrict__ gseq,
+                         int32_t* __restrict__ pseq, double* part_out) {
     constexpr int NQ = D / 16;
     constexpr int PFD = 8;
-    const bool backward = (int)blockIdx.x >= half;
     const int l = threadIdx.x & 15;
-    const long long chunk = (long long)(backward ? blockIdx.x - half : blockIdx.x) * 16 + (threadIdx.x >> 4);
-    const ChunkCoord cc = chunk_coord(chunk, nchunks, cps, T, Lc);
-    const float* Am = A + (shared_model ? 0 : (size_t)cc.seq * Dr * Dr);
     float la[NQ][D];
 #pragma unroll
     for (int qd = 0; qd < NQ; ++qd)
@@ -1010,28 +1007,36 @@ __global__ __launch_bounds__(256) void lm_apply_row_kernel(const float* __restri
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int src = 16 * qs + ((l - r) & 15), dst = 16 * qd + l;
-                const int i = backward ? dst : src, j = backward ? src : dst;
+                const int i = BACKWARD ? dst : src, j = BACKWARD ? src : dst;
                 float v = (i == j) ? 0.0f : -INFINITY;
                 if (i < Dr && j < Dr) v = safe_log(Am[(size_t)i * Dr + j]);
                 la[qd][16 * qs + r] = v;
             }
     const bool live = cc.nsteps > 0;
-    const bool first_chunk = (chunk % cps) == 0;
     bool have[NQ];
     int col[NQ];
 #pragma unroll
     for (int q = 0; q < NQ; ++q) { have[q] = 16 * q + l < Dr; col[q] = have[q] ? 16 * q + l : 0; }
-    const long long s_first = backward ? (long long)cc.nsteps - 1 : 0;
-    const long long stride = backward ? -(long long)Dr : (long long)Dr;
-    const float* lp = ll + ((size_t)cc.seq * T + cc.t0 + (live ? s_first : 0)) * Dr;
-    float* op = (backward ? Bv : F) + ((size_t)cc.seq * T + cc.t0 + (live ? s_first : 0)) * Dr;
+    const long long s_first = BACKWARD ? (long long)cc.nsteps - 1 : 0;
+    const long long stride = BACKWARD ? -(long long)Dr : (long long)Dr;
+    const long long at = cc.t0 + (live ? s_first : 0);
+    const float* lp = lseq + (size_t)at * Dr;
+    const float* fp = fseq + (size_t)at * Dr;
+    float* op = (BACKWARD ? gseq : fseq) + (size_t)at * Dr;
+    int32_t* pp = pseq ? pseq + at : nullptr;
     int fetched = 0;
-    float xq[PFD][NQ];
-    auto fetch = [&](float (&x)[NQ]) {
+    float xq[PFD][NQ], fq[PFD][NQ];
+    auto fetch = [&](float (&x)[NQ], float (&f)[NQ]) {
 #pragma unroll
-        for (int q = 0; q < NQ; ++q) x[q] = lp[col[q]];
+        for (int q = 0; q < NQ; ++q) {
+            x[q] = lp[col[q]];
+            if constexpr (BACKWARD && FUSED) f[q] = fp[col[q]];
+        }
         ++fetched;
-        if (fetched < cc.nsteps) lp += stride;
+        if (fetched < cc.nsteps) {
+            lp += stride;
+            fp += stride;
+        }
     };
     auto row_max_of = [&](const float (&v)[NQ]) {
         float m = v[0];
@@ -1042,19 +1047,10 @@ __global__ __launch_bounds__(256) void lm_apply_row_kernel(const float* __restri
     };
     float v[NQ];
 #pragma unroll
-    for (int q = 0; q < NQ; ++q) {
-        const int j = 16 * q + l;
-        float x = -INFINITY;
-        if (live) {
-            if (backward) x = bout[(size_t)chunk * D + j];
-            else if (first_chunk) x = have[q] ? safe_log(prior[(shared_model ? 0 : (size_t)cc.seq * Dr) + j]) : -INFINITY;
-            else x = vin[(size_t)chunk * D + j];
-        }
-        v[q] = x;
-    }
+    for (int q = 0; q < NQ; ++q) v[q] = start_v[q];
 #pragma unroll
-    for (int p = 0; p < PFD; ++p) fetch(xq[p]);
-    if (!backward) {
+    for (int p = 0; p < PFD; ++p) fetch(xq[p], fq[p]);
+    if constexpr (!BACKWARD) {
         // level the chunk starts from: 0 for the log prior (used as given), else the carry's maximum
         const float start = first_chunk ? 0.0f : row_max_of(v);
         float off = start;
@@ -1067,7 +1063,7 @@ __global__ __launch_bounds__(256) void lm_apply_row_kernel(const float* __restri
                 float x[NQ];
 #pragma unroll
                 for (int q = 0; q < NQ; ++q) x[q] = have[q] ? xq[p][q] : -INFINITY;
-                fetch(xq[p]);
+                fetch(xq[p], fq[p]);
                 const bool seq_start = (cc.t0 + s == 0);   // psi~^f_1 = log prior + ll_1
                 float g[NQ];
 #pragma unroll
@@ -1089,7 +1085,7 @@ __global__ __launch_bounds__(256) void lm_apply_row_kernel(const float* __restri
                 }
             }
         }
-        if (live && l == 0) part[chunk] = osum + (double)off - (double)start;
+        if (live && l == 0) *part_out = osum + (double)off - (double)start;
     } else {
         // v = psi~^b at the current step, shifted by the previous step's maximum
         for (int s0 = 0; s0 < Lc; s0 += PFD) {
@@ -1098,10 +1094,13 @@ __global__ __launch_bounds__(256) void lm_apply_row_kernel(const float* __restri
                 const int pos = s0 + p;
                 const bool active = pos < cc.nsteps;
                 const int s = cc.nsteps - 1 - pos;
-                float t[NQ];
+                float t[NQ], gm[NQ];
 #pragma unroll
-                for (int q = 0; q < NQ; ++q) t[q] = (have[q] ? xq[p][q] : -INFINITY) + v[q];   // emission part of psi_s + psi~^b_s
-                fetch(xq[p]);
+                for (int q = 0; q < NQ; ++q) {
+                    t[q] = (have[q] ? xq[p][q] : -INFINITY) + v[q];   // emission part of psi_s + psi~^b_s
+                    gm[q] = (FUSED && have[q]) ? fq[p][q] + v[q] : -INFINITY;   // Theorem 4: log psi~^f_s + log psi~^b_s
+                }
+                fetch(xq[p], fq[p]);
                 float nv[NQ];
                 const float m = row_max_of(v);
 #pragma unroll
@@ -1110,17 +1109,74 @@ __global__ __launch_bounds__(256) void lm_apply_row_kernel(const float* __restri
                     systolic_terms<D, 0, 0>(t, la[qd], best);
                     nv[qd] = best - m;
                 }
+                float gbest = 0.0f, garg = 0.0f;
+                if constexpr (FUSED) {
+                    gbest = gm[0];
+#pragma unroll
+                    for (int q = 1; q < NQ; ++q) gbest = fmaxf(gbest, gm[q]);
+                    gbest = row_allmax(gbest);
+                    garg = 1.0e9f;                       // lowest state reaching the maximum (states are exact in float)
+#pragma unroll
+                    for (int q = NQ - 1; q >= 0; --q)
+                        if (have[q] && gm[q] == gbest) garg = (float)(16 * q + l);
+                    garg = row_allmin(garg);
+                }
                 if (active) {
+                    const float shift = (gbest == -INFINITY) ? 0.0f : gbest;
 #pragma unroll
                     for (int q = 0; q < NQ; ++q) {
-                        if (have[q]) op[16 * q + l] = v[q];
+                        if (have[q]) op[16 * q + l] = FUSED ? gm[q] - shift : v[q];
                         if (s > 0) v[q] = nv[q];
                     }
                     op += stride;
+                    if constexpr (FUSED) {
+                        if (pp != nullptr) {
+                            if (l == 0) *pp = (int32_t)garg;
+                            --pp;
+                        }
+                    }
                 }
             }
         }
     }
+}
+
+// out: the max-marginals (FUSED; path: their maximisers, may be null) or log psi~^b; half: workgroups per direction
+// (not FUSED)
+template <int D, bool FUSED>
+__global__ __launch_bounds__(256) void lm_apply_row_kernel(const float* __restrict__ prior, const float* __restrict__ A,
+                                                           const float* __restrict__ ll, long long T, int Dr, int Lc,
+                                                           int cps, long long nchunks, int shared_model,
+                                                           const float* __restrict__ vin, const float* __restrict__ bout,
+                                                           float* F, float* __restrict__ out,
+                                                           int32_t* __restrict__ path, double* __restrict__ part,
+                                                           int half) {
+    static_assert(D == 16 || D == 32, "one DPP row per chunk");
+    constexpr int NQ = D / 16;
+    const bool backward = !FUSED && (int)blockIdx.x >= half;
+    const int l = threadIdx.x & 15;
+    const long long chunk = (long long)(backward ? blockIdx.x - half : blockIdx.x) * 16 + (threadIdx.x >> 4);
+    const ChunkCoord cc = chunk_coord(chunk, nchunks, cps, T, Lc);
+    const float* Am = A + (shared_model ? 0 : (size_t)cc.seq * Dr * Dr);
+    const float* lseq = ll + (size_t)cc.seq * T * Dr;
+    float* fseq = F + (size_t)cc.seq * T * Dr;
+    float* gseq = out + (size_t)cc.seq * T * Dr;
+    int32_t* pseq = (FUSED && path != nullptr) ? path + (size_t)cc.seq * T : nullptr;
+    const bool live = cc.nsteps > 0;
+    const bool first_chunk = (chunk % cps) == 0;
+    float vf[NQ], vb[NQ];
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) {
+        const int j = 16 * q + l;
+        vf[q] = vb[q] = -INFINITY;
+        if (live) {
+            if (first_chunk) vf[q] = (j < Dr) ? safe_log(prior[(shared_model ? 0 : (size_t)cc.seq * Dr) + j]) : -INFINITY;
+            else vf[q] = vin[(size_t)chunk * D + j];
+            vb[q] = bout[(size_t)chunk * D + j];
+        }
+    }
+    if (!backward) lm_row_pass<D, false, FUSED>(Am, lseq, cc, Dr, Lc, first_chunk, vf, fseq, gseq, pseq, part + chunk);
+    if (FUSED || backward) lm_row_pass<D, true, FUSED>(Am, lseq, cc, Dr, Lc, first_chunk, vb, fseq, gseq, pseq, nullptr);
 }
 
 // Theorem 4: max-marginal log psi~^f_k + log psi~^b_k, shifted so that the step's largest entry is 0,
@@ -1499,6 +1555,12 @@ static LargePlan max_product_plan(int Dr, long long T, int batch) {
     return p;
 }
 
+// D <= 32: forward pass, backward pass and combination of a chunk in one workgroup once that alone gives every
+// SIMD four waves (four chunks per wave; the chains of maxima are latency-bound, and with fewer waves the two
+// passes side by side plus lm_combine are as fast or faster: 102 against 106 us at 8192 chunks of D = 16,
+// 203 against 189 us at 16384).
+static bool one_pass_apply(const LargePlan& p) { return p.DP <= 32 && p.nchunks >= 16384; }
+
 static LargeMmWs large_mm_ws(int Dr, long long T, int batch) {
     const LargePlan p = max_product_plan(Dr, T, batch);
     const size_t D = p.DP, nc = (size_t)p.nchunks, rows = (size_t)T * batch;
@@ -1509,7 +1571,7 @@ static LargeMmWs large_mm_ws(int Dr, long long T, int batch) {
     w.vin = o;       o = align_up(o + nc * D * sizeof(float), 256);
     w.bout = o;      o = align_up(o + nc * D * sizeof(float), 256);
     w.F = o;         o = align_up(o + rows * Dr * sizeof(float), 256);
-    w.Bv = o;        o = align_up(o + rows * Dr * sizeof(float), 256);
+    w.Bv = o;        o = align_up(o + (one_pass_apply(p) ? 0 : rows * Dr * sizeof(float)), 256);
     w.part = o;      o = align_up(o + nc * sizeof(double), 256);
     const Scan2 s2 = scan2_of(p);
     for (int dir = 0; dir < 2; ++dir) {
@@ -1590,21 +1652,31 @@ static int large_max_product_impl(const LargeArgs& a, float* mm, int32_t* path, 
     } else {
         carry(p.cps, agg, agg_other, vin, bout, p.cps, 1, nullptr, nullptr);
     }
+    bool combined = false;
     if constexpr (D <= 32) {
         const int half = (int)((p.nchunks + 15) / 16);
-        launch("lm_apply", lm_apply_row_kernel<D>, dim3(2u * (unsigned)half), block, st, a.prior, a.A, a.ll, a.T, a.D, p.Lc,
-               p.cps, p.nchunks, a.shared_model, vin, bout, F, Bv, part, half);
+        if (one_pass_apply(p)) {
+            // both passes and Theorem 4's combination in one pass over the chunks
+            launch("lm_apply", lm_apply_row_kernel<D, true>, dim3((unsigned)half), block, st, a.prior, a.A, a.ll, a.T, a.D,
+                   p.Lc, p.cps, p.nchunks, a.shared_model, vin, bout, F, mm, path, part, half);
+            combined = true;
+        } else {
+            launch("lm_apply", lm_apply_row_kernel<D, false>, dim3(2u * (unsigned)half), block, st, a.prior, a.A, a.ll, a.T,
+                   a.D, p.Lc, p.cps, p.nchunks, a.shared_model, vin, bout, F, Bv, static_cast<int32_t*>(nullptr), part, half);
+        }
     } else {
         const int half = (int)((p.nchunks + C::VCPW - 1) / C::VCPW);
         launch("lm_apply", lm_apply_kernel<D>, dim3(2u * (unsigned)half), block, st, a.prior, a.A, a.ll, a.T, a.D, p.Lc,
                p.cps, p.nchunks, a.shared_model, vin, bout, F, Bv, part, half);
     }
-    const int lpr = (a.D + 3) / 4;
-    int width = 1;
-    while (width < lpr) width <<= 1;
-    const long long rows_per_block = 4LL * COMBINE_UNROLL * (64 / width);
-    launch("lm_combine", lm_combine_kernel, dim3((unsigned)((rows + rows_per_block - 1) / rows_per_block)), block, st, F, Bv,
-           rows, a.D, mm, path);
+    if (!combined) {
+        const int lpr = (a.D + 3) / 4;
+        int width = 1;
+        while (width < lpr) width <<= 1;
+        const long long rows_per_block = 4LL * COMBINE_UNROLL * (64 / width);
+        launch("lm_combine", lm_combine_kernel, dim3((unsigned)((rows + rows_per_block - 1) / rows_per_block)), block, st, F,
+               Bv, rows, a.D, mm, path);
+    }
     launch("lm_finalize", lm_finalize_kernel, dim3((unsigned)a.batch), dim3(64), st, part, p.cps, logprob_out);
     return hipGetLastError() == hipSuccess ? 0 : 4;
 }

@@ -111,13 +111,16 @@ def test_chunk_counts_around_the_second_level_threshold(gu, D, T, B):
 
 
 @pytest.mark.parametrize("D,T,B,shared", [(16, 100, 5000, True), (11, 70, 3000, False), (31, 100, 1200, False),
-                                          (20, 33, 4100, True), (32, 530000, 1, True), (16, 131075, 2, False)])
+                                          (20, 33, 4100, True), (32, 530000, 1, True), (16, 131075, 2, False),
+                                          (9, 20, 17000, False), (16, 2200000, 1, True)])
 def test_enough_chunks_for_the_one_pass_apply(gu, D, T, B, shared):
     """From 4096 chunks on, the D <= 32 smoother runs forward recursion, backward recursion and marginals of a
-    chunk in one pass (the filtering distributions go through memory, the backward potentials do not): many
-    short sequences with ragged last chunks, and single sequences long enough for it."""
+    chunk in one pass (the filtering distributions go through memory, the backward potentials do not), and
+    from 16384 chunks on so does the max-product call: many short sequences with ragged last chunks, and
+    single sequences long enough for it."""
     p = wl.random_problem(D, T, batch=B, shared_model=shared, seed=7 * D + T % 11 + B)
     gu.check_smooth(p, want_filtered=(B % 2 == 0), label=f"one-pass apply D={D} T={T} B={B}")
+    gu.check_max_product(p, label=f"one-pass apply D={D} T={T} B={B}")   # the max-product call switches the same way
 
 
 # ---- the configurations at their full sizes, element by element against the oracle ----
