@@ -19,6 +19,11 @@
 namespace hmm {
 
 // transitions k = 1..T-1 (0-based step index of the later state) of one sequence, split over G workgroups
+// A predicted probability pred_k(j) below the smallest normal number counts as zero: the pairwise posteriors it
+// scales sum to gamma_k(j) <= pred_k(j) e_k(j) b_k(j) / Z_k, i.e. nothing at this precision, while the fast
+// reciprocal of a subnormal is infinite and would turn a marginal that has itself underflowed to zero into NaN.
+constexpr float PRED_MIN = 1.17549435e-38f;
+
 struct StepRange { long long k0, k1; };
 HMM_DEV StepRange step_range(long long T, int G, int g) {
     const long long n = T - 1;
@@ -56,7 +61,7 @@ __global__ __launch_bounds__(256) void tc_small_kernel(const float* __restrict__
             float pred = 0.0f;
 #pragma unroll
             for (int i = 0; i < D; ++i) pred = fmaf(f[i], a[i * D + j], pred);
-            w[j] = pred > 0.0f ? gm[j] / pred : 0.0f;
+            w[j] = pred >= PRED_MIN ? gm[j] / pred : 0.0f;
         }
 #pragma unroll
         for (int i = 0; i < D; ++i)
@@ -140,7 +145,7 @@ __global__ __launch_bounds__(256) void tc_row_kernel(const float* __restrict__ A
 #pragma unroll
             for (int qd = 0; qd < NQ; ++qd) {
                 const float pred = (pp[qd][0] + pp[qd][1]) + (pp[qd][2] + pp[qd][3]);
-                const float w = (pred > 0.0f && have[qd]) ? gm[u][qd] * __builtin_amdgcn_rcpf(pred) : 0.0f;
+                const float w = (pred >= PRED_MIN && have[qd]) ? gm[u][qd] * __builtin_amdgcn_rcpf(pred) : 0.0f;
 #pragma unroll
                 for (int qs = 0; qs < NQ; ++qs) row_outer16(fv[qs], w, acc[qs * NQ + qd]);
             }
@@ -254,7 +259,7 @@ __global__ __launch_bounds__(256) void tc_mfma_kernel(const float* __restrict__ 
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const float gm = gw[tile_row(r) * STR + 32 * cb + ln];
-            w[r] = pred[r] > 0.0f ? gm * __builtin_amdgcn_rcpf(pred[r]) : 0.0f;
+            w[r] = pred[r] >= PRED_MIN ? gm * __builtin_amdgcn_rcpf(pred[r]) : 0.0f;
         }
         // C(row block rb) += F_slab^T * W: reduction over the slab's steps in the order of the result rows
 #pragma unroll

@@ -67,3 +67,24 @@ def test_wide_dynamic_range(gu, D, T, B, ll_scale, zero_frac):
     gu.check_viterbi(p, label=label)
     gu.check_max_product(p, label=label)
     gu.check_transition_counts(p, label=label)
+
+
+@pytest.mark.parametrize("D", [4, 10, 40, 100])
+def test_state_fading_through_the_subnormal_range(gu, D):
+    """A state that can only be reached from itself and that the evidence disfavours at every step: its filtered
+    probability decays through the subnormal range to zero (at e^-7 per step, after about a dozen steps), and so does
+    the predicted probability that the transition statistic divides by."""
+    p = wl.random_problem(D, 40, batch=3, shared_model=True, seed=90 + D)
+    k = D // 2
+    A = p.A.copy()
+    A[0, :, k] = 0.0
+    A[0, k, :] = 0.0
+    A[0, k, k] = 1.0
+    A[0] /= A[0].sum(axis=1, keepdims=True)
+    p.A[...] = A.astype(np.float32)
+    p.loglik[:, :, k] -= 7.0
+    label = f"fading state D={D}"
+    gu.check_smooth(p, want_filtered=True, label=label)
+    gu.check_viterbi(p, label=label)
+    gu.check_max_product(p, label=label)
+    gu.check_transition_counts(p, label=label)
