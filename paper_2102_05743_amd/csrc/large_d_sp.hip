@@ -146,12 +146,13 @@ __global__ __launch_bounds__(256, (D <= 32) ? 2 : 1) void ld_aggregate_kernel(co
 #pragma unroll
             for (int r = 0; r < C::NACC; ++r) m = fmaxf(m, acc[mt][r]);
         m = wave_max_nonneg(m);   // products of non-negative factors
+        // the exponent goes into every entry directly: as a factor, 2^-ex overflows to infinity for a strip
+        // whose largest entry has become subnormal (ex < -127), and the strip would turn into infinities and NaNs
         const int ex = __builtin_amdgcn_frexp_expf(m);
-        const float sc = ldexpf(1.0f, -ex);
 #pragma unroll
         for (int mt = 0; mt < C::MT; ++mt)
 #pragma unroll
-            for (int r = 0; r < C::NACC; ++r) acc[mt][r] *= sc;
+            for (int r = 0; r < C::NACC; ++r) acc[mt][r] = ldexpf(acc[mt][r], -ex);
         exsum += ex;
         return m;
     };
@@ -315,12 +316,13 @@ __global__ __launch_bounds__(256) void ld_product_kernel(const float* __restrict
 #pragma unroll
             for (int r = 0; r < C::NACC; ++r) m = fmaxf(m, acc[mt][r]);
         m = wave_max_nonneg(m);   // products of non-negative factors
+        // the exponent goes into every entry directly: as a factor, 2^-ex overflows to infinity for a strip
+        // whose largest entry has become subnormal (ex < -127), and the strip would turn into infinities and NaNs
         const int ex = __builtin_amdgcn_frexp_expf(m);
-        const float sc = ldexpf(1.0f, -ex);
 #pragma unroll
         for (int mt = 0; mt < C::MT; ++mt)
 #pragma unroll
-            for (int r = 0; r < C::NACC; ++r) acc[mt][r] *= sc;
+            for (int r = 0; r < C::NACC; ++r) acc[mt][r] = ldexpf(acc[mt][r], -ex);
         exsum += ex;
         return m;
     };

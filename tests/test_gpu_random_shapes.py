@@ -88,3 +88,26 @@ def test_state_fading_through_the_subnormal_range(gu, D):
     gu.check_viterbi(p, label=label)
     gu.check_max_product(p, label=label)
     gu.check_transition_counts(p, label=label)
+
+
+@pytest.mark.parametrize("D,T", [(17, 3000), (20, 700), (40, 2000), (100, 1500)])
+def test_start_states_barely_possible_at_the_first_step(gu, D, T):
+    """The first observation leaves the states of the last 16- or 32-state strip with emission factors just above
+    the smallest normal number (e^-85): the part of the first chunk's aggregate that starts from them turns subnormal
+    within a few steps, before its first rescaling."""
+    p = wl.random_problem(D, T, batch=2, shared_model=True, seed=300 + D, ll_scale=10.0)
+    strip = 16 if D <= 32 else 32
+    lo = (D - 1) // strip * strip
+    p.loglik[:, 0, lo:] = p.loglik[:, 0, :lo].max(axis=1, keepdims=True) - 85.0
+    label = f"barely possible start states D={D}"
+    gu.check_smooth(p, want_filtered=True, label=label)
+    gu.check_max_product(p, label=label)
+    gu.check_transition_counts(p, label=label)
+
+
+def test_subnormal_strip_in_a_drawn_problem(gu):
+    """The drawn problem in which the case above was met: log-likelihoods spread over 40 nats, D = 17 (one real
+    state in the second strip), whose factor at the first step of one sequence is 1.4e-37."""
+    p = wl.random_problem(17, 17235, batch=7, shared_model=True, seed=9242, ll_scale=40.0)
+    gu.check_smooth(p, want_filtered=True, label="drawn D=17")
+    gu.check_transition_counts(p, label="drawn D=17")
