@@ -606,14 +606,25 @@ __global__ __launch_bounds__(256) void sd_smooth_fused_kernel(const float* __res
     block_prefix<S, D>(P, Q, wagg);
     __syncthreads();
     HMM_STAMP(3);
-    grid_publish<S, D>(wagg, ws);
+    const bool alone = tps == 1;   // the sequence is this one tile: nothing to exchange, no wait anywhere
+    if (!alone) grid_publish<S, D>(wagg, ws);
     HMM_STAMP(4);
     // the suffix scan needs nothing from other tiles: it runs while their aggregates arrive
 #pragma unroll
     for (int e = 0; e < D * D; ++e) R[e] = P[e];
     wave_scan_suffix<S, D>(R);
     float cf[D], cb[D];
-    const bool ok = grid_gather<S, D, true>(tc, tps, prior + (shared_model ? 0 : (size_t)tc.seq * D), ws, gl, cf, cb);
+    bool ok = true;
+    if (alone) {
+        const float* pr = prior + (shared_model ? 0 : (size_t)tc.seq * D);
+#pragma unroll
+        for (int j = 0; j < D; ++j) {
+            cf[j] = S::is_max_plus ? logf(pr[j]) : pr[j];
+            cb[j] = S::one();
+        }
+    } else {
+        ok = grid_gather<S, D, true>(tc, tps, prior + (shared_model ? 0 : (size_t)tc.seq * D), ws, gl, cf, cb);
+    }
     HMM_STAMP(6);
     float f[D], b[D];
     carry_forward<S, D>(Q, wagg, cf, f);
@@ -624,13 +635,15 @@ __global__ __launch_bounds__(256) void sd_smooth_fused_kernel(const float* __res
     if (!ok) delta = __builtin_nan("");   // an expired wait makes the call's log evidence NaN
     HMM_STAMP(8);
     const double tile_delta = block_sum(delta, dsum);   // contains a barrier: all marginals are in LDS
-    if (threadIdx.x == 0)
-        coherent_store(reinterpret_cast<unsigned long long*>(ws.part) + blockIdx.x, publish_bits(tile_delta));
+    if (threadIdx.x == 0) {
+        if (alone) loglik_out[tc.seq] = tile_delta;
+        else coherent_store(reinterpret_cast<unsigned long long*>(ws.part) + blockIdx.x, publish_bits(tile_delta));
+    }
     HMM_STAMP(9);
     store_tile<D>(marg + tc.base * D, tc.nvalid, lds);
     if (argmax != nullptr) store_argmax_tile<D>(argmax + tc.base, tc.nvalid, lds);
     HMM_STAMP(10);
-    if (tc.tile == 0) grid_sum_parts(blockIdx.x, tps, ws, dsum, loglik_out, tc.seq);
+    if (!alone && tc.tile == 0) grid_sum_parts(blockIdx.x, tps, ws, dsum, loglik_out, tc.seq);
     HMM_STAMP(11);
 }
 
@@ -668,10 +681,18 @@ __global__ __launch_bounds__(256) void sd_viterbi_fused_kernel(const float* __re
     block_prefix<S, D>(P, Q, wagg);
     __syncthreads();
     HMM_STAMP(3);
-    grid_publish<S, D>(wagg, ws);
-    HMM_STAMP(4);
+    const bool alone = tps == 1;   // the sequence is this one tile: nothing to exchange, no wait anywhere
     float cf[D], cb[D];
-    const bool ok = grid_gather<S, D, false>(tc, tps, prior + (shared_model ? 0 : (size_t)tc.seq * D), ws, gl, cf, cb);
+    bool ok = true;
+    if (alone) {
+        const float* pr = prior + (shared_model ? 0 : (size_t)tc.seq * D);
+#pragma unroll
+        for (int j = 0; j < D; ++j) cf[j] = logf(pr[j]);
+    } else {
+        grid_publish<S, D>(wagg, ws);
+        HMM_STAMP(4);
+        ok = grid_gather<S, D, false>(tc, tps, prior + (shared_model ? 0 : (size_t)tc.seq * D), ws, gl, cf, cb);
+    }
     HMM_STAMP(6);
     float v[D];
     carry_forward<S, D>(Q, wagg, cf, v);
@@ -682,33 +703,42 @@ __global__ __launch_bounds__(256) void sd_viterbi_fused_kernel(const float* __re
     HMM_STAMP(8);
     uint32_t excl;
     const uint32_t total = block_map_suffix<D>(h, excl, wmaps);
-    if (threadIdx.x == 0) coherent_store(ws.tmap + blockIdx.x, total);   // a map uses 24 bits: never the sentinel
+    if (!alone && threadIdx.x == 0) coherent_store(ws.tmap + blockIdx.x, total);   // a map uses 24 bits: never the sentinel
     HMM_STAMP(9);
     const double tile_delta = block_sum(osum, dsum);   // other tiles wait for the map, not for this
-    if (threadIdx.x == 0)
-        coherent_store(reinterpret_cast<unsigned long long*>(ws.part) + blockIdx.x, publish_bits(tile_delta));
-    // the tile maps of the sequence; state at this tile's last step = maps of later tiles composed
-    uint32_t tm = map_identity<D>();
-    bool ok2 = false;
-    for (int spin = 0; spin < ws.spin_limit; ++spin) {
-        bool valid = true;
-        if ((int)threadIdx.x < tps) {
-            tm = coherent_load(ws.tmap + tile0 + threadIdx.x);
-            valid = tm != SENTINEL32;
+    if (threadIdx.x == 0) {
+        if (alone) logprob_out[tc.seq] = tile_delta;
+        else coherent_store(reinterpret_cast<unsigned long long*>(ws.part) + blockIdx.x, publish_bits(tile_delta));
+    }
+    bool ok2 = true;
+    uint32_t x;
+    if (alone) {
+        // the maps after a lane's chunk end with the last chunk's, which is constant: any argument will do
+        x = map_apply<D>(excl, 0u);
+    } else {
+        // the tile maps of the sequence; state at this tile's last step = maps of later tiles composed
+        uint32_t tm = map_identity<D>();
+        ok2 = false;
+        for (int spin = 0; spin < ws.spin_limit; ++spin) {
+            bool valid = true;
+            if ((int)threadIdx.x < tps) {
+                tm = coherent_load(ws.tmap + tile0 + threadIdx.x);
+                valid = tm != SENTINEL32;
+            }
+            if (__syncthreads_and(valid ? 1 : 0)) { ok2 = true; break; }
+            __builtin_amdgcn_s_sleep(1);
         }
-        if (__syncthreads_and(valid ? 1 : 0)) { ok2 = true; break; }
-        __builtin_amdgcn_s_sleep(1);
+        if (!ok2) {
+            if (threadIdx.x == 0) atomicOr(ws.err, 1u);
+            tm = map_identity<D>();
+        }
+        HMM_STAMP(10);
+        uint32_t texcl;
+        block_map_suffix<D>(tm, texcl, wmaps2);
+        if ((int)threadIdx.x == tc.tile) xend_lds = map_apply<D>(texcl, 0u);   // last tile's map is constant
+        __syncthreads();
+        x = map_apply<D>(excl, xend_lds);
     }
-    if (!ok2) {
-        if (threadIdx.x == 0) atomicOr(ws.err, 1u);
-        tm = map_identity<D>();
-    }
-    HMM_STAMP(10);
-    uint32_t texcl;
-    block_map_suffix<D>(tm, texcl, wmaps2);
-    if ((int)threadIdx.x == tc.tile) xend_lds = map_apply<D>(texcl, 0u);   // last tile's map is constant
-    __syncthreads();
-    uint32_t x = map_apply<D>(excl, xend_lds);
     if (last) x = xs;
     HMM_STAMP(11);
     int32_t* stage = reinterpret_cast<int32_t*>(lds);   // the log-likelihood tile is no longer needed
@@ -717,7 +747,7 @@ __global__ __launch_bounds__(256) void sd_viterbi_fused_kernel(const float* __re
     HMM_STAMP(12);
     store_path_tile<D>(path + tc.base, tc.nvalid, stage);
     HMM_STAMP(13);
-    if (tc.tile == 0) {
+    if (!alone && tc.tile == 0) {
         if (ok2) grid_sum_parts(blockIdx.x, tps, ws, dsum, logprob_out, tc.seq);
         else if (threadIdx.x == 0) logprob_out[tc.seq] = __builtin_nan("");   // the wait for the tile maps ran out
     }
@@ -966,13 +996,16 @@ static int two_filter(const SmallArgs& a, float* marg, float* filt, int32_t* arg
     }
     if (!filt) cap = resident_capacity<(MP ? 5 : 1)>(sd_smooth_fused_kernel<S, D, false>);
     if (MP && filt) return 2;   // no filtered output is defined for the max-product plan
-    if (!force_multi_launch() && tps <= C::NT && nt <= cap) {
+    // Sequences of one tile each exchange nothing: the single-launch kernel then runs for any number of them
+    // (no workgroup waits for another, so they need not be resident together) and no slot is cleared.
+    if (!force_multi_launch() && (tps == 1 || (tps <= C::NT && nt <= cap))) {
         const XchLayout xl = xch_layout<D>((size_t)nt);
         FusedWs fw{reinterpret_cast<float*>(xch + xl.agg), reinterpret_cast<double*>(xch + xl.part), xch + xl.tmap,
                    xch + xl.err, spin_limit()};
         const int nwords = (int)xl.words;
-        launch(MP ? "sd_clear_mm" : "sd_clear_sp", sd_clear_kernel<D>, dim3((nwords + 255) / 256), dim3(256), st, xch,
-               nwords);
+        if (tps > 1)
+            launch(MP ? "sd_clear_mm" : "sd_clear_sp", sd_clear_kernel<D>, dim3((nwords + 255) / 256), dim3(256), st, xch,
+                   nwords);
         const char* name = MP ? "sd_maxprod_fused" : "sd_smooth_fused";
         if constexpr (!MP) {
             if (filt)
@@ -1032,12 +1065,12 @@ int SmallD<D>::viterbi(const SmallArgs& a, int32_t* path, double* logprob_out) {
     const dim3 grid((unsigned)nt), block(C::NT), seqs((unsigned)a.batch);
     const int itps = (int)tps;
     const long long cap = resident_capacity<2>(sd_viterbi_fused_kernel<D>);
-    if (!force_multi_launch() && tps <= C::NT && nt <= cap) {
+    if (!force_multi_launch() && (tps == 1 || (tps <= C::NT && nt <= cap))) {   // one tile per sequence: see two_filter
         const XchLayout xl = xch_layout<D>((size_t)nt);
         FusedWs fw{reinterpret_cast<float*>(xch + xl.agg), reinterpret_cast<double*>(xch + xl.part), xch + xl.tmap,
                    xch + xl.err, spin_limit()};
         const int nwords = (int)xl.words;
-        launch("sd_clear_mp", sd_clear_kernel<D>, dim3((nwords + 255) / 256), dim3(256), st, xch, nwords);
+        if (tps > 1) launch("sd_clear_mp", sd_clear_kernel<D>, dim3((nwords + 255) / 256), dim3(256), st, xch, nwords);
         launch("sd_viterbi_fused", sd_viterbi_fused_kernel<D>, grid, block, st, a.prior, a.A, a.ll, a.T, itps,
                a.shared_model, path, logprob_out, fw);
     } else {
