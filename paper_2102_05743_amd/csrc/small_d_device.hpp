@@ -840,6 +840,273 @@ HMM_DEV void store_path_tile(int32_t* __restrict__ dst, int nvalid, const int32_
 }
 
 // ---------------------------------------------------------------------------------------------
+// Several short sequences per workgroup.  A sequence of at most 64 L steps takes cpl = 2^lcpl consecutive
+// lanes (one chunk of L steps each, the last ones possibly empty), aligned to a multiple of cpl, so a wave
+// holds 64 / cpl whole sequences and the scans over chunk aggregates stop at the groups' boundaries: they
+// are the wave scans above cut off after lcpl levels, with the shifts inside a row of 16 lanes masked to
+// the group.  The batch is contiguous in memory, so the sequences of a workgroup are one contiguous range
+// and are staged through LDS with the same coalesced accesses as a tile, only the owner of an element is
+// found by a division by the sequence length.
+struct PackCoord {
+    int seq0;    // first sequence of the workgroup
+    int nseq;    // sequences of the workgroup (the last workgroup may hold fewer)
+    int c;       // the lane's chunk inside its sequence
+    int seq;     // the lane's sequence (clamped to the batch: lanes past it hold no steps)
+    int n;       // valid steps of the lane's chunk
+    bool first;  // the chunk starts its sequence
+    bool last;   // the chunk holds its sequence's last step
+};
+
+template <int D>
+HMM_DEV PackCoord pack_coord(long long T, int batch, int lcpl) {
+    using C = SmallCfg<D>;
+    PackCoord p;
+    const int spw = C::NT >> lcpl;
+    p.seq0 = (int)blockIdx.x * spw;
+    p.nseq = min(spw, batch - p.seq0);
+    const int q = (int)threadIdx.x >> lcpl;
+    p.c = (int)threadIdx.x & ((1 << lcpl) - 1);
+    const bool live = q < p.nseq;
+    p.seq = p.seq0 + (live ? q : 0);
+    const long long rem = T - (long long)p.c * C::L;
+    p.n = live ? (int)(rem < 0 ? 0 : rem > C::L ? C::L : rem) : 0;
+    p.first = p.n > 0 && p.c == 0;
+    p.last = p.n > 0 && rem <= C::L;
+    return p;
+}
+
+// x / d and x % d for 0 <= x < 2^23 through the reciprocal, corrected by one either way
+HMM_DEV int div_by(int x, int d, float inv_d, int& rem) {
+    int q = (int)((float)x * inv_d);
+    int r = x - q * d;
+    if (r < 0) { --q; r += d; }
+    else if (r >= d) { ++q; r -= d; }
+    rem = r;
+    return q;
+}
+
+// LDS position of element `fl` (a float index into the workgroup's range of the batch; rowlen floats per sequence)
+template <int D>
+HMM_DEV int packed_slot(int fl, int rowlen, float inv_rowlen, int lcpl) {
+    using C = SmallCfg<D>;
+    int w;
+    const int q = div_by(fl, rowlen, inv_rowlen, w);
+    const int c = w / C::ROW;
+    return ((q << lcpl) + c) * C::STRIDE + (w - c * C::ROW);
+}
+
+template <int D, class F = NoWork>
+HMM_DEV void load_packed(const float* __restrict__ g, int nfl, int rowlen, int lcpl, float* lds, F between = F()) {
+    using C = SmallCfg<D>;
+    const float inv = 1.0f / (float)rowlen;
+    if constexpr (C::VEC == 4) {
+        constexpr int NIT = C::ROW / 4;
+        const float4* g4 = reinterpret_cast<const float4*>(g);
+        const int last = nfl / 4 - 1;
+        float4 x[NIT];
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) {
+            const int v = it * C::NT + threadIdx.x;
+            typedef float nt4 __attribute__((ext_vector_type(4)));
+            const nt4 y = __builtin_nontemporal_load(reinterpret_cast<const nt4*>(g4 + (v < last ? v : last)));
+            x[it] = make_float4(y.x, y.y, y.z, y.w);
+        }
+        between();
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) {
+            const int fl = (it * C::NT + threadIdx.x) * 4;
+            if (fl < nfl) *reinterpret_cast<float4*>(lds + packed_slot<D>(fl, rowlen, inv, lcpl)) = x[it];
+        }
+    } else {
+        constexpr int CH = 8;
+        const int last = nfl - 1;
+        for (int it0 = 0; it0 < C::ROW; it0 += CH) {
+            float x[CH];
+#pragma unroll
+            for (int q = 0; q < CH; ++q) {
+                const int fl = (it0 + q) * C::NT + threadIdx.x;
+                x[q] = g[fl < last ? fl : last];
+            }
+            if (it0 == 0) between();
+#pragma unroll
+            for (int q = 0; q < CH; ++q) {
+                const int fl = (it0 + q) * C::NT + threadIdx.x;
+                if (fl < nfl) lds[packed_slot<D>(fl, rowlen, inv, lcpl)] = x[q];
+            }
+        }
+    }
+}
+
+template <int D>
+HMM_DEV void store_packed(float* __restrict__ g, int nfl, int rowlen, int lcpl, const float* lds) {
+    using C = SmallCfg<D>;
+    const float inv = 1.0f / (float)rowlen;
+    if constexpr (C::VEC == 4) {
+        float4* g4 = reinterpret_cast<float4*>(g);
+#pragma unroll
+        for (int it = 0; it < C::ROW / 4; ++it) {
+            const int v = it * C::NT + threadIdx.x;
+            const int fl = v * 4;
+            if (fl < nfl) {
+                typedef float nt4 __attribute__((ext_vector_type(4)));
+                const nt4 x = *reinterpret_cast<const nt4*>(lds + packed_slot<D>(fl, rowlen, inv, lcpl));
+                __builtin_nontemporal_store(x, reinterpret_cast<nt4*>(g4 + v));
+            }
+        }
+    } else {
+#pragma unroll 8
+        for (int it = 0; it < C::ROW; ++it) {
+            const int fl = it * C::NT + threadIdx.x;
+            if (fl < nfl) g[fl] = lds[packed_slot<D>(fl, rowlen, inv, lcpl)];
+        }
+    }
+}
+
+// Row (lane) and step inside the row of time step s of the workgroup's range (T steps per sequence)
+template <int D>
+HMM_DEV int packed_step_owner(int s, int T, float inv_T, int lcpl, int& k) {
+    using C = SmallCfg<D>;
+    int w;
+    const int q = div_by(s, T, inv_T, w);
+    const int c = w / C::L;
+    k = w - c * C::L;
+    return (q << lcpl) + c;
+}
+
+template <int D>
+HMM_DEV void store_argmax_packed(int32_t* __restrict__ dst, int nsteps, int T, int lcpl, const float* lds) {
+    using C = SmallCfg<D>;
+    const float inv = 1.0f / (float)T;
+#pragma unroll 4
+    for (int it = 0; it < C::L; ++it) {
+        const int s = it * C::NT + threadIdx.x;
+        if (s < nsteps) {
+            int k;
+            const int owner = packed_step_owner<D>(s, T, inv, lcpl, k);
+            const float* p = lds + owner * C::STRIDE + k * D;
+            float best = p[0];
+            int arg = 0;
+#pragma unroll
+            for (int j = 1; j < D; ++j) {
+                const float x = p[j];
+                const bool gt = x > best;
+                best = gt ? x : best;
+                arg = gt ? j : arg;
+            }
+            __builtin_nontemporal_store((int32_t)arg, dst + s);
+        }
+    }
+}
+
+template <int D>
+HMM_DEV void store_path_packed(int32_t* __restrict__ dst, int nsteps, int T, int lcpl, const int32_t* stage) {
+    using C = SmallCfg<D>;
+    const float inv = 1.0f / (float)T;
+#pragma unroll
+    for (int it = 0; it < C::L; ++it) {
+        const int s = it * C::NT + threadIdx.x;
+        if (s < nsteps) {
+            int k;
+            const int owner = packed_step_owner<D>(s, T, inv, lcpl, k);
+            __builtin_nontemporal_store(stage[owner * C::PSTRIDE + k], dst + s);
+        }
+    }
+}
+
+// One level of the scan towards higher lanes in which a lane takes its partner only if `take`.
+template <class S, int D, bool SWAP, int CTRL, int ROW_MASK>
+HMM_DEV void wave_scan_level_if(float (&Q)[D * D], bool take) {
+    float Pn[D * D], Z[D * D];
+#pragma unroll
+    for (int i = 0; i < D; ++i)
+#pragma unroll
+        for (int j = 0; j < D; ++j) {
+            const float id = (i == j) ? S::one() : S::zero();
+            const float m = dpp_move<CTRL, ROW_MASK>(id, Q[i * D + j]);
+            Pn[i * D + j] = take ? m : id;
+        }
+    if constexpr (SWAP) mat_mul<S, D>(Q, Pn, Z);
+    else mat_mul<S, D>(Pn, Q, Z);
+    renorm<S, D * D>(Z);
+#pragma unroll
+    for (int e = 0; e < D * D; ++e) Q[e] = Z[e];
+}
+
+// Inclusive scan towards higher lanes inside every aligned group of 2^lcpl lanes.
+template <class S, int D, bool SWAP>
+HMM_DEV void group_scan_up(float (&Q)[D * D], int lcpl) {
+    const int pos = (int)(threadIdx.x & 63) & ((1 << lcpl) - 1);
+    if (lcpl > 0) wave_scan_level_if<S, D, SWAP, 0x111, 0xF>(Q, pos >= 1);   // row_shr:1
+    if (lcpl > 1) wave_scan_level_if<S, D, SWAP, 0x112, 0xF>(Q, pos >= 2);   // row_shr:2
+    if (lcpl > 2) wave_scan_level_if<S, D, SWAP, 0x114, 0xF>(Q, pos >= 4);   // row_shr:4
+    if (lcpl > 3) wave_scan_level_if<S, D, SWAP, 0x118, 0xF>(Q, pos >= 8);   // row_shr:8
+    if (lcpl > 4) wave_scan_level<S, D, SWAP, 0x142, 0xA>(Q);               // row_bcast:15 into rows 1 and 3
+    if (lcpl > 5) wave_scan_level<S, D, SWAP, 0x143, 0xC>(Q);               // row_bcast:31 into rows 2 and 3
+}
+
+// Forward potential entering every chunk and backward potential at every chunk's last step, for sequences
+// that start from `start` (the prior, in the operator's domain) and end inside their group.
+template <class S, int D, bool BWD>
+HMM_DEV void group_exchange(const float (&P)[D * D], int lcpl, int c, const float (&start)[D], float (&fin)[D],
+                            float (&bout)[D]) {
+    float Q[D * D], r[D];
+#pragma unroll
+    for (int e = 0; e < D * D; ++e) Q[e] = P[e];
+    group_scan_up<S, D, false>(Q, lcpl);
+    float Qp[D * D];
+#pragma unroll
+    for (int e = 0; e < D * D; ++e) Qp[e] = __shfl_up(Q[e], 1, 64);
+    vec_mat<S, D>(start, Qp, r);
+#pragma unroll
+    for (int j = 0; j < D; ++j) fin[j] = (c == 0) ? start[j] : r[j];
+    if constexpr (BWD) {
+        const int mirror = 63 - (int)(threadIdx.x & 63);
+        float R[D * D], ones[D];
+#pragma unroll
+        for (int e = 0; e < D * D; ++e) R[e] = __shfl(P[e], mirror, 64);
+        group_scan_up<S, D, true>(R, lcpl);
+#pragma unroll
+        for (int e = 0; e < D * D; ++e) R[e] = __shfl(R[e], mirror, 64);
+        float Rn[D * D];
+#pragma unroll
+        for (int e = 0; e < D * D; ++e) Rn[e] = __shfl_down(R[e], 1, 64);
+#pragma unroll
+        for (int j = 0; j < D; ++j) ones[j] = S::one();
+        mat_vec<S, D>(Rn, ones, r);
+#pragma unroll
+        for (int j = 0; j < D; ++j) bout[j] = (c == (1 << lcpl) - 1) ? ones[j] : r[j];
+    }
+}
+
+// Sum of one double per lane over every aligned group of 2^lcpl lanes, in a fixed order; valid in the
+// group's first lane.
+HMM_DEV double group_sum(double v, int lcpl) {
+    for (int d = (1 << lcpl) >> 1; d >= 1; d >>= 1) v += __shfl_down(v, d, 64);
+    return v;
+}
+
+// excl = g_{c+1} o ... o g_{cpl-1} inside every aligned group of cpl = 2^lcpl lanes
+template <int D>
+HMM_DEV uint32_t group_map_suffix(uint32_t g, int lcpl, int c) {
+    constexpr bool BYTES = D <= 4;
+    auto comp = [](uint32_t a, uint32_t b) {
+        if constexpr (BYTES) return bytes_compose(a, b);
+        else return map_compose<D>(a, b);
+    };
+    const uint32_t ident = BYTES ? 0x03020100u : map_identity<D>();
+    const int cpl = 1 << lcpl;
+    uint32_t G = BYTES ? map_to_bytes<D>(g) : g;   // inclusive: g_c o ... o g_{cpl-1}
+    for (int d = 1; d < cpl; d <<= 1) {
+        const uint32_t o = __shfl_down(G, d, 64);
+        const uint32_t cc = comp(G, o);
+        G = (c + d < cpl) ? cc : G;
+    }
+    uint32_t nxt = __shfl_down(G, 1, 64);
+    nxt = (c == cpl - 1) ? ident : nxt;
+    return BYTES ? map_from_bytes<D>(nxt) : nxt;
+}
+
+// ---------------------------------------------------------------------------------------------
 // Exchange between co-resident workgroups (single-launch kernels) through self-validating words.
 //
 // Before the kernel starts, every exchange slot in the workspace holds the all-ones bit pattern

@@ -754,6 +754,91 @@ __global__ __launch_bounds__(256) void sd_viterbi_fused_kernel(const float* __re
 }
 
 // =============================================================================================
+// Short sequences (at most 64 chunks): several per workgroup, nothing exchanged between workgroups
+// =============================================================================================
+
+// Smoother / max-product two-filter pass for sequences of at most 64 L steps, 256 >> lcpl of them per
+// workgroup (see pack_coord).  The chunk-level scans run inside each sequence's group of lanes; the
+// lane-level work is that of the other plans.
+template <class S, int D, bool WRITE_FILT>
+__global__ __launch_bounds__(256) void sd_smooth_packed_kernel(const float* __restrict__ prior,
+                                                               const float* __restrict__ A,
+                                                               const float* __restrict__ ll, long long T, int batch,
+                                                               int lcpl, int shared_model, float* __restrict__ marg,
+                                                               float* __restrict__ filt, int32_t* __restrict__ argmax,
+                                                               double* __restrict__ out) {
+    using C = SmallCfg<D>;
+    __shared__ float lds[C::LDS_FLOATS];
+    const PackCoord pc = pack_coord<D>(T, batch, lcpl);
+    const int rowlen = (int)T * D;
+    const int nfl = pc.nseq * rowlen;
+    float Am[D * D];
+    load_model_raw<D>(A + (shared_model ? 0 : (size_t)pc.seq * D * D), Am);
+    load_packed<D>(ll + (size_t)pc.seq0 * rowlen, nfl, rowlen, lcpl, lds, [&]() { model_to_domain<S, D>(Am); });
+    float start[D];
+#pragma unroll
+    for (int j = 0; j < D; ++j) {
+        const float pr = prior[(shared_model ? 0 : (size_t)pc.seq * D) + j];
+        start[j] = S::is_max_plus ? logf(pr) : pr;
+    }
+    __syncthreads();
+    float* row = lds + threadIdx.x * C::STRIDE;
+    float P[D * D];
+    double msum;
+    chunk_aggregate<S, D, true>(row, pc.n, pc.first, Am, P, msum);
+    float f[D], b[D];
+    group_exchange<S, D, true>(P, lcpl, pc.c, start, f, b);
+    float* fdst = WRITE_FILT ? filt + ((size_t)pc.seq * T + (size_t)pc.c * C::L) * D : nullptr;
+    const double delta = smooth_chunk<S, D, WRITE_FILT>(row, pc.n, pc.first, Am, f, b, msum, fdst);
+    const double total = group_sum(delta, lcpl);
+    if (pc.first) out[pc.seq] = total;
+    __syncthreads();   // all (max-)marginals are in LDS
+    store_packed<D>(marg + (size_t)pc.seq0 * rowlen, nfl, rowlen, lcpl, lds);
+    if (argmax != nullptr) store_argmax_packed<D>(argmax + (size_t)pc.seq0 * T, pc.nseq * (int)T, (int)T, lcpl, lds);
+}
+
+// Viterbi for the same sequences: forward scan with back-pointers, the reversed scan under composition
+// inside each group of lanes, walk and coalesced path write.
+template <int D>
+__global__ __launch_bounds__(256) void sd_viterbi_packed_kernel(const float* __restrict__ prior,
+                                                                const float* __restrict__ A,
+                                                                const float* __restrict__ ll, long long T, int batch,
+                                                                int lcpl, int shared_model, int32_t* __restrict__ path,
+                                                                double* __restrict__ logprob_out) {
+    using C = SmallCfg<D>;
+    using S = MaxPlus;
+    __shared__ float lds[C::LDS_FLOATS];
+    const PackCoord pc = pack_coord<D>(T, batch, lcpl);
+    const int rowlen = (int)T * D;
+    const int nfl = pc.nseq * rowlen;
+    float Am[D * D];
+    load_model_raw<D>(A + (shared_model ? 0 : (size_t)pc.seq * D * D), Am);
+    load_packed<D>(ll + (size_t)pc.seq0 * rowlen, nfl, rowlen, lcpl, lds, [&]() { model_to_domain<S, D>(Am); });
+    float start[D];
+#pragma unroll
+    for (int j = 0; j < D; ++j) start[j] = logf(prior[(shared_model ? 0 : (size_t)pc.seq * D) + j]);
+    __syncthreads();
+    const float* row = lds + threadIdx.x * C::STRIDE;
+    float P[D * D];
+    double msum;
+    chunk_aggregate<S, D, false>(const_cast<float*>(row), pc.n, pc.first, Am, P, msum);
+    float v[D], unused[D];
+    group_exchange<S, D, false>(P, lcpl, pc.c, start, v, unused);
+    uint32_t bp[C::W], h, xs;
+    const double osum = viterbi_chunk<D>(row, pc.n, pc.first, pc.last, Am, v, bp, h, xs);
+    const double total = group_sum(osum, lcpl);
+    if (pc.first) logprob_out[pc.seq] = total;
+    // the maps after a lane's chunk end with the last chunk's, which is constant: any argument will do
+    uint32_t x = map_apply<D>(group_map_suffix<D>(h, lcpl, pc.c), 0u);
+    if (pc.last) x = xs;
+    __syncthreads();   // the log-likelihood rows are no longer needed: their space stages the path
+    int32_t* stage = reinterpret_cast<int32_t*>(lds);
+    walk_chunk<D>(bp, pc.n, pc.first, x, stage + threadIdx.x * C::PSTRIDE);
+    __syncthreads();
+    store_path_packed<D>(path + (size_t)pc.seq0 * T, pc.nseq * (int)T, (int)T, lcpl, stage);
+}
+
+// =============================================================================================
 // Block-wise elements (Sec. V-B): the element of the whole block, with its scale
 // =============================================================================================
 
@@ -965,6 +1050,17 @@ static int spin_limit() {
     return (int)(v < 0 ? 0 : v > (1L << 24) ? (1L << 24) : v);
 }
 
+// Short sequences: lanes per sequence as a power of two (log2), or -1 if a sequence needs more than a wave.
+template <int D>
+static int packed_log2_lanes(long long T) {
+    using C = SmallCfg<D>;
+    if (T > 64LL * C::L) return -1;
+    const int chunks = (int)((T + C::L - 1) / C::L);
+    int l = 0;
+    while ((1 << l) < chunks) ++l;
+    return l;
+}
+
 static bool force_multi_launch() {
     const char* e = getenv("HMMSCAN_PLAN");
     return e != nullptr && e[0] == 'm';   // HMMSCAN_PLAN=multi forces the multi-launch plan
@@ -996,6 +1092,22 @@ static int two_filter(const SmallArgs& a, float* marg, float* filt, int32_t* arg
     }
     if (!filt) cap = resident_capacity<(MP ? 5 : 1)>(sd_smooth_fused_kernel<S, D, false>);
     if (MP && filt) return 2;   // no filtered output is defined for the max-product plan
+    const int lcpl = packed_log2_lanes<D>(a.T);
+    if (!force_multi_launch() && lcpl >= 0) {
+        // short sequences, several per workgroup: one launch, no workspace
+        const int spw = C::NT >> lcpl;
+        const dim3 pgrid((unsigned)((a.batch + spw - 1) / spw));
+        const char* name = MP ? "sd_maxprod_packed" : "sd_smooth_packed";
+        if constexpr (!MP) {
+            if (filt)
+                launch(name, sd_smooth_packed_kernel<S, D, true>, pgrid, block, st, a.prior, a.A, a.ll, a.T, a.batch, lcpl,
+                       a.shared_model, marg, filt, argmax, out);
+        }
+        if (!filt)
+            launch(name, sd_smooth_packed_kernel<S, D, false>, pgrid, block, st, a.prior, a.A, a.ll, a.T, a.batch, lcpl,
+                   a.shared_model, marg, filt, argmax, out);
+        return hipGetLastError() == hipSuccess ? 0 : 4;
+    }
     // Sequences of one tile each exchange nothing: the single-launch kernel then runs for any number of them
     // (no workgroup waits for another, so they need not be resident together) and no slot is cleared.
     if (!force_multi_launch() && (tps == 1 || (tps <= C::NT && nt <= cap))) {
@@ -1064,6 +1176,13 @@ int SmallD<D>::viterbi(const SmallArgs& a, int32_t* path, double* logprob_out) {
     hipStream_t st = a.stream;
     const dim3 grid((unsigned)nt), block(C::NT), seqs((unsigned)a.batch);
     const int itps = (int)tps;
+    const int lcpl = packed_log2_lanes<D>(a.T);
+    if (!force_multi_launch() && lcpl >= 0) {
+        const int spw = C::NT >> lcpl;
+        launch("sd_viterbi_packed", sd_viterbi_packed_kernel<D>, dim3((unsigned)((a.batch + spw - 1) / spw)), block, st,
+               a.prior, a.A, a.ll, a.T, a.batch, lcpl, a.shared_model, path, logprob_out);
+        return hipGetLastError() == hipSuccess ? 0 : 4;
+    }
     const long long cap = resident_capacity<2>(sd_viterbi_fused_kernel<D>);
     if (!force_multi_launch() && (tps == 1 || (tps <= C::NT && nt <= cap))) {   // one tile per sequence: see two_filter
         const XchLayout xl = xch_layout<D>((size_t)nt);

@@ -115,3 +115,21 @@ def test_expired_wait_is_reported_not_hung(gu, plan, monkeypatch):
     torch.cuda.synchronize()
     m0, _, L0 = gu.oracle.smooth(p.prior[0], p.A[0], p.loglik[0], want_filtered=False)
     assert np.abs(marg.cpu().numpy()[0] - m0).max() <= gu.MARG_ATOL and abs(float(L[0]) - L0) <= gu.LOGLIK_RTOL * abs(L0)
+
+
+@pytest.mark.parametrize("D,T,B,shared", [
+    (4, 16, 300, True), (4, 17, 129, False), (4, 31, 64, False), (4, 32, 7, True), (4, 33, 1000, False),
+    (4, 127, 50, True), (4, 129, 33, False), (4, 511, 9, False), (4, 513, 5, True), (4, 1023, 3, False),
+    (4, 1024, 6, True), (4, 1025, 6, False), (1, 5, 999, True), (2, 16, 257, False), (3, 100, 70, False),
+    (5, 8, 400, False), (5, 9, 401, True), (6, 63, 100, False), (7, 65, 31, True), (8, 511, 4, False),
+    (8, 512, 5, True), (8, 513, 5, False)])
+def test_short_sequences_packed_into_workgroups(gu, D, T, B, shared):
+    """Sequences of at most 64 chunks (1024 steps at D <= 4, 512 above) share workgroups, a power-of-two
+    group of lanes each: lengths at and around the group sizes' limits, batches that do not fill the last
+    workgroup, per-sequence models; one step beyond the limit the one-sequence-per-workgroup form takes over."""
+    p = wl.random_problem(D, T, batch=B, shared_model=shared, seed=11 * D + T + B)
+    label = f"packed D={D} T={T} B={B} shared={shared}"
+    gu.check_smooth(p, want_filtered=(T % 2 == 0), label=label)
+    gu.check_viterbi(p, label=label)
+    gu.check_max_product(p, label=label)
+    gu.check_transition_counts(p, label=label)
