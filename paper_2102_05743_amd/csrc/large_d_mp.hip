@@ -946,7 +946,9 @@ __global__ __launch_bounds__(256) void lm_apply_kernel(const float* __restrict__
         if (cc.nsteps > 0 && lane == 0 && wv == 0) part[chunk] = osum + (double)off - (double)start;
     } else {
         // u = psi~^b at the current step, component j, shifted by the previous step's maximum
-        float u = (cc.nsteps > 0) ? bout[(size_t)chunk * D + j] : -INFINITY;
+        // without carries (sequences of one chunk) the backward potential at the last step is the operator's unit
+        float u = -INFINITY;
+        if (cc.nsteps > 0) u = bout != nullptr ? bout[(size_t)chunk * D + j] : (j < Dr ? 0.0f : -INFINITY);
         int cur = 0;
         float xn = -INFINITY;
         if (cc.nsteps > 0 && j < Dr) xn = lseq[(size_t)(cc.t0 + cc.nsteps - 1) * Dr + j];
@@ -1172,7 +1174,7 @@ __global__ __launch_bounds__(256) void lm_apply_row_kernel(const float* __restri
         if (live) {
             if (first_chunk) vf[q] = (j < Dr) ? safe_log(prior[(shared_model ? 0 : (size_t)cc.seq * Dr) + j]) : -INFINITY;
             else vf[q] = vin[(size_t)chunk * D + j];
-            vb[q] = bout[(size_t)chunk * D + j];
+            vb[q] = bout != nullptr ? bout[(size_t)chunk * D + j] : (j < Dr ? 0.0f : -INFINITY);   // one chunk per sequence: the unit
         }
     }
     if (!backward) lm_row_pass<D, false, FUSED>(Am, lseq, cc, Dr, Lc, first_chunk, vf, fseq, gseq, pseq, part + chunk);
@@ -1476,8 +1478,10 @@ static int large_viterbi_impl(const LargeArgs& a, int32_t* path, double* logprob
     double* part = reinterpret_cast<double*>(ws + w.part);
     hipStream_t st = a.stream;
     const dim3 block(256);
-    launch("lv_aggregate", lv_aggregate_systolic_kernel<D>, dim3((unsigned)((p.nchunks + M::CPW - 1) / M::CPW)), block,
-           st, a.A, a.ll, a.T, a.D, p.Lc, p.cps, p.nchunks, a.shared_model, agg, static_cast<float*>(nullptr));
+    // a sequence of one chunk starts from the prior: no aggregates, no carries
+    if (p.cps > 1)
+        launch("lv_aggregate", lv_aggregate_systolic_kernel<D>, dim3((unsigned)((p.nchunks + M::CPW - 1) / M::CPW)), block,
+               st, a.A, a.ll, a.T, a.D, p.Lc, p.cps, p.nchunks, a.shared_model, agg, static_cast<float*>(nullptr));
     const Scan2 s2 = scan2_of(p);
     auto carry = [&](int cps, const float* mats, float* out, int seglen, int nseg, const float* start) {
         const unsigned blocks = (unsigned)a.batch * (unsigned)nseg;
@@ -1508,7 +1512,7 @@ static int large_viterbi_impl(const LargeArgs& a, int32_t* path, double* logprob
         }
         carry(s2.G, cur, gvin, s2.G, 1, nullptr);            // V before every group
         carry(p.cps, agg, vin, s2.g, s2.G, gvin);             // V before every chunk, all groups at once
-    } else {
+    } else if (p.cps > 1) {
         carry(p.cps, agg, vin, p.cps, 1, nullptr);
     }
     bool row_forward = false;
@@ -1611,8 +1615,13 @@ static int large_max_product_impl(const LargeArgs& a, float* mm, int32_t* path, 
     double* part = reinterpret_cast<double*>(ws + w.part);
     hipStream_t st = a.stream;
     const dim3 block(256);
-    launch("lv_aggregate", lv_aggregate_systolic_kernel<D>, dim3((unsigned)((p.nchunks + M::CPW - 1) / M::CPW)), block,
-           st, a.A, a.ll, a.T, a.D, p.Lc, p.cps, p.nchunks, a.shared_model, agg, agg_other);
+    if (p.cps == 1) {
+        // a sequence of one chunk starts from the prior and ends with the operator's unit: no aggregates, no carries
+        bout = nullptr;
+    } else {
+        launch("lv_aggregate", lv_aggregate_systolic_kernel<D>, dim3((unsigned)((p.nchunks + M::CPW - 1) / M::CPW)), block,
+               st, a.A, a.ll, a.T, a.D, p.Lc, p.cps, p.nchunks, a.shared_model, agg, agg_other);
+    }
     const Scan2 s2 = scan2_of(p);
     auto carry = [&](int cps, const float* mats, const float* mats_other, float* out, float* out_b, int seglen, int nseg,
                      const float* start, const float* start_b) {
@@ -1649,7 +1658,7 @@ static int large_max_product_impl(const LargeArgs& a, float* mm, int32_t* path, 
         }
         carry(s2.G, top[0], top[1], gvin, gbout, s2.G, 1, nullptr, nullptr);
         carry(p.cps, agg, agg_other, vin, bout, s2.g, s2.G, gvin, gbout);
-    } else {
+    } else if (p.cps > 1) {
         carry(p.cps, agg, agg_other, vin, bout, p.cps, 1, nullptr, nullptr);
     }
     bool combined = false;

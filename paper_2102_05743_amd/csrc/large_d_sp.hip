@@ -823,7 +823,9 @@ HMM_DEV void backward_chunk(const float* __restrict__ A, const float* __restrict
     eb.tic = threadIdx.x - cl * EBt::LPCH;
     float* ubuf = L.vbuf;
     float* wsum = L.wsum;
-    float b = (cc.nsteps > 0) ? bout[(size_t)chunk * D + i] : 0.0f;   // b at the chunk's last step
+    // b at the chunk's last step; without carries (sequences of one chunk) that is the all-ones vector
+    float b = 0.0f;
+    if (cc.nsteps > 0) b = bout != nullptr ? bout[(size_t)chunk * D + i] : (i < Dr ? 1.0f : 0.0f);
     float inv = 1.0f;
     int cur = 0;
     const int nb = (nloop + EBt::EB - 1) / EBt::EB;
@@ -1073,7 +1075,7 @@ __global__ __launch_bounds__(256) void ld_apply_row_kernel(const float* __restri
         if (cc.nsteps > 0) {
             if (first_chunk) hf[q] = (j < Dr) ? prior[(shared_model ? 0 : (size_t)cc.seq * Dr) + j] : 0.0f;
             else hf[q] = fin[(size_t)chunk * D + j];
-            hb[q] = bout[(size_t)chunk * D + j];
+            hb[q] = bout != nullptr ? bout[(size_t)chunk * D + j] : (j < Dr ? 1.0f : 0.0f);   // one chunk per sequence: all ones
         }
     }
     if (!backward) apply_row_pass<D, false, FUSED>(Am, lseq, mseq, cc, Dr, Lc, first_chunk, hf, fseq, gseq, part + chunk);
@@ -1359,16 +1361,22 @@ static int large_smooth_impl(const LargeArgs& a, float* marg, float* filt, doubl
         const long long rpb = 4LL * STREAM_UNROLL * (64 / width);   // rows per workgroup
         launch("ld_rowmax", ld_rowmax_kernel, dim3((unsigned)((rows + rpb - 1) / rpb)), block, st, a.ll, rows, a.D, rowmax);
     }
-    launch("ld_aggregate", ld_aggregate_kernel<D>, dim3((unsigned)((p.nchunks + C::CPW - 1) / C::CPW)), block, st, a.A,
-           a.ll, rowmax, a.T, a.D, p.Lc, p.cps, p.nchunks, a.shared_model, agg, aggT, exps);
-    if (p.two_level) {
+    if (p.cps == 1) {
+        // a sequence is one chunk: it starts from the prior and ends with the all-ones vector; no aggregates, no carries
+        fin = nullptr;
+        bout = nullptr;
+    } else {
+        launch("ld_aggregate", ld_aggregate_kernel<D>, dim3((unsigned)((p.nchunks + C::CPW - 1) / C::CPW)), block, st, a.A,
+               a.ll, rowmax, a.T, a.D, p.Lc, p.cps, p.nchunks, a.shared_model, agg, aggT, exps);
+    }
+    if (p.cps > 1 && p.two_level) {
         const long long ngroups = (long long)p.G * a.batch;
         launch("ld_product", ld_product_kernel<D>, dim3((unsigned)((ngroups + C::CPW - 1) / C::CPW)), block, st,
                (const float*)aggT, (const int*)exps, p.cps, p.g, p.G, ngroups, gagg, gaggT, gexps);
         // carries at the group boundaries, then inside every group from those
         launch_carry<D>(st, a, p.G, gagg, gaggT, gexps, gfin, gbout, p.G, 1, nullptr, nullptr);
         launch_carry<D>(st, a, p.cps, agg, aggT, exps, fin, bout, p.g, p.G, gfin, gbout);
-    } else {
+    } else if (p.cps > 1) {
         launch_carry<D>(st, a, p.cps, agg, aggT, exps, fin, bout, p.cps, 1, nullptr, nullptr);
     }
     const int half = (int)((p.nchunks + C::VCPW - 1) / C::VCPW);

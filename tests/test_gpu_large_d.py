@@ -123,6 +123,19 @@ def test_enough_chunks_for_the_one_pass_apply(gu, D, T, B, shared):
     gu.check_max_product(p, label=f"one-pass apply D={D} T={T} B={B}")   # the max-product call switches the same way
 
 
+@pytest.mark.parametrize("D,T,B,shared", [(16, 100, 9000, True), (12, 7, 20000, False), (32, 90, 2100, False),
+                                          (64, 40, 1100, True), (128, 60, 600, False), (100, 1, 700, True)])
+def test_one_chunk_per_sequence_needs_no_aggregates(gu, D, T, B, shared):
+    """Batches large enough that every sequence is a single chunk: the recursions start from the prior and end
+    with the all-ones vector (the operator's unit), and neither chunk aggregates nor carries are computed."""
+    p = wl.random_problem(D, T, batch=B, shared_model=shared, seed=3 * D + T + B)
+    label = f"one chunk per sequence D={D} T={T} B={B}"
+    gu.check_smooth(p, want_filtered=(T % 2 == 0), label=label)
+    gu.check_viterbi(p, label=label)
+    gu.check_max_product(p, label=label)
+    gu.check_transition_counts(p, label=label)
+
+
 # ---- the configurations at their full sizes, element by element against the oracle ----
 def test_config3_full_size(gu):
     p = wl.config3()
