@@ -82,6 +82,52 @@ __global__ __launch_bounds__(256) void tc_small_kernel(const float* __restrict__
             (red[threadIdx.x] + red[D * D + threadIdx.x]) + (red[2 * D * D + threadIdx.x] + red[3 * D * D + threadIdx.x]);
 }
 
+// The same for short sequences (at most 1025 steps): a sequence takes an aligned group of 2^lg lanes of a
+// wave (at most 16 steps per lane), several sequences share a workgroup, the group's lanes are summed by
+// shuffles and its first lane writes the sequence's counts directly: one launch, no partial sums.
+template <int D>
+__global__ __launch_bounds__(256) void tc_small_packed_kernel(const float* __restrict__ A, const float* __restrict__ filt,
+                                                              const float* __restrict__ marg, long long T, int batch,
+                                                              int lg, int shared_model, double* __restrict__ counts) {
+    const int gsz = 1 << lg;
+    const int spw = 256 >> lg;
+    const int q = (int)threadIdx.x >> lg, c = (int)threadIdx.x & (gsz - 1);
+    const long long seq_raw = (long long)blockIdx.x * spw + q;
+    const bool live = seq_raw < batch;
+    const size_t seq = live ? (size_t)seq_raw : 0;
+    const float* Am = A + (shared_model ? 0 : seq * D * D);
+    float a[D * D], acc[D * D];
+#pragma unroll
+    for (int e = 0; e < D * D; ++e) { a[e] = Am[e]; acc[e] = 0.0f; }
+    const float* fs = filt + seq * T * D;
+    const float* ms = marg + seq * T * D;
+    if (live) {
+        for (long long k = 1 + c; k < T; k += gsz) {
+            float f[D], gm[D];
+#pragma unroll
+            for (int j = 0; j < D; ++j) { f[j] = fs[(size_t)(k - 1) * D + j]; gm[j] = ms[(size_t)k * D + j]; }
+            float w[D];
+#pragma unroll
+            for (int j = 0; j < D; ++j) {
+                float pred = 0.0f;
+#pragma unroll
+                for (int i = 0; i < D; ++i) pred = fmaf(f[i], a[i * D + j], pred);
+                w[j] = pred >= PRED_MIN ? gm[j] / pred : 0.0f;
+            }
+#pragma unroll
+            for (int i = 0; i < D; ++i)
+#pragma unroll
+                for (int j = 0; j < D; ++j) acc[i * D + j] = fmaf(f[i], w[j], acc[i * D + j]);
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < D * D; ++e) {
+        float v = acc[e] * a[e];
+        for (int d = gsz >> 1; d >= 1; d >>= 1) v += __shfl_down(v, d, 64);
+        if (live && c == 0) counts[seq * D * D + e] = (double)v;
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
 // 9 <= D <= 32 (padded to DP = 16 or 32): one time step per DPP row of 16 lanes, sixteen steps per
 // workgroup round, no LDS in the loop.  Lane l holds components 16 q + l of fh_{k-1} and gamma_k.  Both the
@@ -300,6 +346,87 @@ __global__ __launch_bounds__(256) void tc_mfma_kernel(const float* __restrict__ 
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// 9 <= D <= 32 for large batches of short sequences: a DPP row of 16 lanes takes one whole sequence, step
+// after step (four steps' loads in flight), sixteen sequences per workgroup; nothing is summed across rows,
+// and every lane writes the entries it accumulated directly.
+template <int DP>
+__global__ __launch_bounds__(256) void tc_row_packed_kernel(const float* __restrict__ A, const float* __restrict__ filt,
+                                                            const float* __restrict__ marg, long long T, int Dr,
+                                                            int batch, int shared_model, double* __restrict__ counts) {
+    static_assert(DP == 16 || DP == 32, "one DPP row per sequence");
+    constexpr int NQ = DP / 16;
+    constexpr int UNR = 4;
+    const int l = threadIdx.x & 15, row = threadIdx.x >> 4;
+    const long long seq_raw = (long long)blockIdx.x * 16 + row;
+    const bool live = seq_raw < batch;
+    const size_t seq = live ? (size_t)seq_raw : 0;
+    const float* Am = A + (shared_model ? 0 : seq * Dr * Dr);
+    float a[NQ * NQ * 16];
+#pragma unroll
+    for (int qs = 0; qs < NQ; ++qs)
+#pragma unroll
+        for (int qd = 0; qd < NQ; ++qd)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int i = 16 * qs + ((l - r) & 15), j = 16 * qd + l;
+                a[(qs * NQ + qd) * 16 + r] = (i < Dr && j < Dr) ? Am[(size_t)i * Dr + j] : 0.0f;
+            }
+    float acc[NQ * NQ][16];
+#pragma unroll
+    for (int b = 0; b < NQ * NQ; ++b)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[b][r] = 0.0f;
+    const float* fs = filt + seq * T * Dr;
+    const float* ms = marg + seq * T * Dr;
+    int col[NQ];
+    bool have[NQ];
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) { have[q] = 16 * q + l < Dr; col[q] = have[q] ? 16 * q + l : 0; }
+    const long long kend = live ? T : 1;     // rows past the batch take no steps (all rows run the same instructions)
+    for (long long kb = 1; kb < T; kb += UNR) {
+        float f[UNR][NQ], gm[UNR][NQ];
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const long long k = kb + u;
+            const long long kc = k < T ? k : T - 1;   // past the end: a valid step, contribution masked below
+#pragma unroll
+            for (int q = 0; q < NQ; ++q) {
+                f[u][q] = fs[(size_t)(kc - 1) * Dr + col[q]];
+                gm[u][q] = ms[(size_t)kc * Dr + col[q]];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const bool valid = kb + u < kend;
+            float fv[NQ];
+#pragma unroll
+            for (int q = 0; q < NQ; ++q) fv[q] = (valid && have[q]) ? f[u][q] : 0.0f;
+            float pp[NQ][4];
+            row_matvec_terms<NQ>(fv, a, pp);
+#pragma unroll
+            for (int qd = 0; qd < NQ; ++qd) {
+                const float pred = (pp[qd][0] + pp[qd][1]) + (pp[qd][2] + pp[qd][3]);
+                const float w = (pred >= PRED_MIN && have[qd]) ? gm[u][qd] * __builtin_amdgcn_rcpf(pred) : 0.0f;
+#pragma unroll
+                for (int qs = 0; qs < NQ; ++qs) row_outer16(fv[qs], w, acc[qs * NQ + qd]);
+            }
+        }
+    }
+    if (live) {
+#pragma unroll
+        for (int qs = 0; qs < NQ; ++qs)
+#pragma unroll
+            for (int qd = 0; qd < NQ; ++qd)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int i = 16 * qs + ((l - r) & 15), j = 16 * qd + l;
+                    if (i < Dr && j < Dr)
+                        counts[(seq * Dr + i) * Dr + j] = (double)(acc[qs * NQ + qd][r] * a[(qs * NQ + qd) * 16 + r]);
+                }
+    }
+}
+
 // counts[seq][i][j] = sum over the sequence's G partial sums, in fp64.  blockIdx.x = sequence,
 // blockIdx.y = group of EPB entries; the 256 threads are (entry, slice of the partial sums), slices
 // added in a fixed order.
@@ -350,10 +477,32 @@ static void launch_small(const EstepArgs& a, int G, float* partial) {
            a.marginals, a.T, G, a.shared_model, partial);
 }
 
+// D <= 8, at most 1025 steps: lanes per sequence (log2) of the packed form
+static int packed_group_log2(long long T) {
+    const long long n = T - 1;                  // transitions
+    int lg = 0;
+    while ((1LL << lg) < n && lg < 6) ++lg;
+    return lg;
+}
+
+template <int D>
+static void launch_small_packed(const EstepArgs& a, double* counts) {
+    const int lg = packed_group_log2(a.T);
+    const int spw = 256 >> lg;
+    launch("tc_accumulate", tc_small_packed_kernel<D>, dim3((unsigned)((a.batch + spw - 1) / spw)), dim3(256), a.stream,
+           a.A, a.filtered, a.marginals, a.T, a.batch, lg, a.shared_model, counts);
+}
+
 template <int DP>
 static void launch_row(const EstepArgs& a, int G, float* partial) {
     launch("tc_accumulate", tc_row_kernel<DP>, dim3((unsigned)(a.batch * G)), dim3(256), a.stream, a.A, a.filtered,
            a.marginals, a.T, a.D, G, a.shared_model, partial);
+}
+
+template <int DP>
+static void launch_row_packed(const EstepArgs& a, double* counts) {
+    launch("tc_accumulate", tc_row_packed_kernel<DP>, dim3((unsigned)((a.batch + 15) / 16)), dim3(256), a.stream, a.A,
+           a.filtered, a.marginals, a.T, a.D, a.batch, a.shared_model, counts);
 }
 
 template <int DP>
@@ -368,6 +517,25 @@ int transition_counts(const EstepArgs& a, double* counts) {
     if (a.ws_bytes < transition_counts_ws_bytes(a.D, a.T, a.batch)) return 3;
     float* partial = static_cast<float*>(a.ws);
     const int PS = padded(a.D);
+    if (PS <= 8 && a.T <= 1025) {
+        switch (PS) {
+            case 1: launch_small_packed<1>(a, counts); break;
+            case 2: launch_small_packed<2>(a, counts); break;
+            case 3: launch_small_packed<3>(a, counts); break;
+            case 4: launch_small_packed<4>(a, counts); break;
+            case 5: launch_small_packed<5>(a, counts); break;
+            case 6: launch_small_packed<6>(a, counts); break;
+            case 7: launch_small_packed<7>(a, counts); break;
+            default: launch_small_packed<8>(a, counts); break;
+        }
+        return hipGetLastError() == hipSuccess ? 0 : 4;
+    }
+    if ((PS == 16 || PS == 32) && a.T <= 257 && a.batch >= 1024) {
+        // large batches of short sequences: a row of lanes per sequence, counts written directly
+        if (PS == 16) launch_row_packed<16>(a, counts);
+        else launch_row_packed<32>(a, counts);
+        return hipGetLastError() == hipSuccess ? 0 : 4;
+    }
     switch (PS) {
         case 1: launch_small<1>(a, G, partial); break;
         case 2: launch_small<2>(a, G, partial); break;
