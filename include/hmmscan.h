@@ -26,10 +26,11 @@
  * logarithms and have no such limit.
  *
  * Concurrency.  Calls may be enqueued back to back on one stream.  For small state
- * spaces (D <= 8) and shapes whose tiles all fit the device at once, a call is a
+ * spaces (D <= 8), sequences longer than one tile (4096 steps at D <= 4, 2048
+ * above) and shapes whose tiles all fit the device at once, a call is a
  * single kernel whose workgroups wait for one another's partial results, which
  * needs them all resident together; the host checks this against an otherwise
- * idle device.  If other work (another stream, another process) occupies compute
+ * idle device.  (Shorter sequences never wait for one another.)  If other work (another stream, another process) occupies compute
  * units for the whole duration, the wait is bounded: the kernel then terminates
  * by itself and the call's log-likelihood / log-probability output is NaN (its
  * other outputs are then meaningless).  HMMSCAN_SPIN_LIMIT=<polls> overrides the
