@@ -199,6 +199,8 @@ __global__ __launch_bounds__(256) void sd_smooth_apply_kernel(const float* __res
     chunk_aggregate<S, D, true>(row, n, first, Am, P, msum);
     float f[D], b[D];
     block_exchange<S, D, true>(P, cf, cb, f, b, wagg);
+    // (the filtering distributions go to memory lane by lane here: a second staging tile would halve the
+    // workgroups per compute unit, which costs more than the scattered stores)
     float* fdst = WRITE_FILT ? filt + (tc.base + (long long)threadIdx.x * C::L) * D : nullptr;
     const double delta = smooth_chunk<S, D, WRITE_FILT>(row, n, first, Am, f, b, msum, fdst);
     const double tile_delta = block_sum(delta, dsum);
@@ -580,8 +582,15 @@ __global__ __launch_bounds__(256) void sd_smooth_fused_kernel(const float* __res
                                                               double* __restrict__ loglik_out, FusedWs ws) {
     using C = SmallCfg<D>;
     __shared__ float lds[C::LDS_FLOATS];
+    // the filtering distributions of the tile are staged like the marginals, in the space the inter-tile exchange
+    // has finished with by then (both do not fit beside the tile at D >= 7)
+    __shared__ union FusedShared {
+        GridLds<D> gl;
+        float flds[WRITE_FILT ? C::LDS_FLOATS : 1];
+    } sh;
+    GridLds<D>& gl = sh.gl;
+    float* flds = sh.flds;
     __shared__ float wagg[C::NW * D * D];
-    __shared__ GridLds<D> gl;
     __shared__ double dsum[C::NW];
     HMM_STAMP(0);
 #ifdef HMM_PHASE_STAMPS
@@ -624,13 +633,14 @@ __global__ __launch_bounds__(256) void sd_smooth_fused_kernel(const float* __res
         }
     } else {
         ok = grid_gather<S, D, true>(tc, tps, prior + (shared_model ? 0 : (size_t)tc.seq * D), ws, gl, cf, cb);
+        if constexpr (WRITE_FILT) __syncthreads();   // every wave is done with the exchange area before it is reused
     }
     HMM_STAMP(6);
     float f[D], b[D];
     carry_forward<S, D>(Q, wagg, cf, f);
     carry_backward<S, D>(R, wagg, cb, b);
     HMM_STAMP(7);
-    float* fdst = WRITE_FILT ? filt + (tc.base + (long long)threadIdx.x * C::L) * D : nullptr;
+    float* fdst = WRITE_FILT ? flds + threadIdx.x * C::STRIDE : nullptr;
     double delta = smooth_chunk<S, D, WRITE_FILT>(row, n, first, Am, f, b, msum, fdst);
     if (!ok) delta = __builtin_nan("");   // an expired wait makes the call's log evidence NaN
     HMM_STAMP(8);
@@ -641,6 +651,7 @@ __global__ __launch_bounds__(256) void sd_smooth_fused_kernel(const float* __res
     }
     HMM_STAMP(9);
     store_tile<D>(marg + tc.base * D, tc.nvalid, lds);
+    if constexpr (WRITE_FILT) store_tile<D>(filt + tc.base * D, tc.nvalid, flds);
     if (argmax != nullptr) store_argmax_tile<D>(argmax + tc.base, tc.nvalid, lds);
     HMM_STAMP(10);
     if (!alone && tc.tile == 0) grid_sum_parts(blockIdx.x, tps, ws, dsum, loglik_out, tc.seq);
@@ -788,7 +799,7 @@ __global__ __launch_bounds__(256) void sd_smooth_packed_kernel(const float* __re
     chunk_aggregate<S, D, true>(row, pc.n, pc.first, Am, P, msum);
     float f[D], b[D];
     group_exchange<S, D, true>(P, lcpl, pc.c, start, f, b);
-    float* fdst = WRITE_FILT ? filt + ((size_t)pc.seq * T + (size_t)pc.c * C::L) * D : nullptr;
+    float* fdst = WRITE_FILT ? filt + ((size_t)pc.seq * T + (size_t)pc.c * C::L) * D : nullptr;   // lane by lane, as in the apply kernel
     const double delta = smooth_chunk<S, D, WRITE_FILT>(row, pc.n, pc.first, Am, f, b, msum, fdst);
     const double total = group_sum(delta, lcpl);
     if (pc.first) out[pc.seq] = total;
