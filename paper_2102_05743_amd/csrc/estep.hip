@@ -41,7 +41,8 @@ HMM_DEV StepRange step_range(long long T, int G, int g) {
 template <int D>
 __global__ __launch_bounds__(256) void tc_small_kernel(const float* __restrict__ A, const float* __restrict__ filt,
                                                        const float* __restrict__ marg, long long T, int G,
-                                                       int shared_model, float* __restrict__ partial) {
+                                                       int shared_model, float* __restrict__ partial,
+                                                       double* __restrict__ direct) {
     __shared__ float red[4 * D * D];
     const int seq = blockIdx.x / G, g = blockIdx.x % G;
     const StepRange sr = step_range(T, G, g);
@@ -77,9 +78,13 @@ __global__ __launch_bounds__(256) void tc_small_kernel(const float* __restrict__
         if (lane == 0) red[wave * D * D + e] = v;
     }
     __syncthreads();
-    if (threadIdx.x < D * D)
-        partial[(size_t)blockIdx.x * D * D + threadIdx.x] =
+    if (threadIdx.x < D * D) {
+        const float v =
             (red[threadIdx.x] + red[D * D + threadIdx.x]) + (red[2 * D * D + threadIdx.x] + red[3 * D * D + threadIdx.x]);
+        // one workgroup per sequence (G == 1): the sum is the sequence's count, written without a second pass
+        if (direct != nullptr) direct[(size_t)blockIdx.x * D * D + threadIdx.x] = (double)v;
+        else partial[(size_t)blockIdx.x * D * D + threadIdx.x] = v;
+    }
 }
 
 // The same for short sequences (at most 1025 steps): a sequence takes an aligned group of 2^lg lanes of a
@@ -138,7 +143,8 @@ __global__ __launch_bounds__(256) void tc_small_packed_kernel(const float* __res
 template <int DP>
 __global__ __launch_bounds__(256) void tc_row_kernel(const float* __restrict__ A, const float* __restrict__ filt,
                                                      const float* __restrict__ marg, long long T, int Dr, int G,
-                                                     int shared_model, float* __restrict__ partial) {
+                                                     int shared_model, float* __restrict__ partial,
+                                                     double* __restrict__ direct) {
     static_assert(DP == 16 || DP == 32, "one DPP row per step");
     constexpr int NQ = DP / 16;
     constexpr int UNR = 4;
@@ -214,8 +220,15 @@ __global__ __launch_bounds__(256) void tc_row_kernel(const float* __restrict__ A
                 }
             }
     __syncthreads();
-    for (int e = threadIdx.x; e < DP * DP; e += 256)
-        partial[(size_t)blockIdx.x * DP * DP + e] = (red[e] + red[DP * DP + e]) + (red[2 * DP * DP + e] + red[3 * DP * DP + e]);
+    for (int e = threadIdx.x; e < DP * DP; e += 256) {
+        const float v = (red[e] + red[DP * DP + e]) + (red[2 * DP * DP + e] + red[3 * DP * DP + e]);
+        if (direct != nullptr) {   // G == 1: the sequence's count itself
+            const int i = e / DP, j = e % DP;
+            if (i < Dr && j < Dr) direct[((size_t)blockIdx.x * Dr + i) * Dr + j] = (double)v;
+        } else {
+            partial[(size_t)blockIdx.x * DP * DP + e] = v;
+        }
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -232,7 +245,8 @@ __global__ __launch_bounds__(256) void tc_row_kernel(const float* __restrict__ A
 template <int DP>
 __global__ __launch_bounds__(256) void tc_mfma_kernel(const float* __restrict__ A, const float* __restrict__ filt,
                                                       const float* __restrict__ marg, long long T, int Dr, int G,
-                                                      int shared_model, float* __restrict__ partial) {
+                                                      int shared_model, float* __restrict__ partial,
+                                                      double* __restrict__ direct) {
     static_assert(DP == 64 || DP == 128, "column blocks of 32");
     constexpr int NB = DP / 32;          // column blocks = row blocks
     constexpr int SPW = 4 / NB;          // waves sharing a column block, each on its own slabs
@@ -341,7 +355,11 @@ __global__ __launch_bounds__(256) void tc_mfma_kernel(const float* __restrict__ 
             for (int r = 0; r < 16; ++r) {
                 const int i = 32 * rb + tile_row(r), j = 32 * cb + ln;
                 const float a = (i < Dr && j < Dr) ? Am[(size_t)i * Dr + j] : 0.0f;
-                partial[(size_t)blockIdx.x * DP * DP + (size_t)i * DP + j] = acc[rb][r] * a;
+                if (direct != nullptr) {   // G == 1: the sequence's count itself
+                    if (i < Dr && j < Dr) direct[((size_t)blockIdx.x * Dr + i) * Dr + j] = (double)(acc[rb][r] * a);
+                } else {
+                    partial[(size_t)blockIdx.x * DP * DP + (size_t)i * DP + j] = acc[rb][r] * a;
+                }
             }
     }
 }
@@ -472,9 +490,9 @@ size_t transition_counts_ws_bytes(int D, long long T, int batch) {
 }
 
 template <int D>
-static void launch_small(const EstepArgs& a, int G, float* partial) {
+static void launch_small(const EstepArgs& a, int G, float* partial, double* direct) {
     launch("tc_accumulate", tc_small_kernel<D>, dim3((unsigned)(a.batch * G)), dim3(256), a.stream, a.A, a.filtered,
-           a.marginals, a.T, G, a.shared_model, partial);
+           a.marginals, a.T, G, a.shared_model, partial, direct);
 }
 
 // D <= 8, at most 1025 steps: lanes per sequence (log2) of the packed form
@@ -494,9 +512,9 @@ static void launch_small_packed(const EstepArgs& a, double* counts) {
 }
 
 template <int DP>
-static void launch_row(const EstepArgs& a, int G, float* partial) {
+static void launch_row(const EstepArgs& a, int G, float* partial, double* direct) {
     launch("tc_accumulate", tc_row_kernel<DP>, dim3((unsigned)(a.batch * G)), dim3(256), a.stream, a.A, a.filtered,
-           a.marginals, a.T, a.D, G, a.shared_model, partial);
+           a.marginals, a.T, a.D, G, a.shared_model, partial, direct);
 }
 
 template <int DP>
@@ -506,9 +524,9 @@ static void launch_row_packed(const EstepArgs& a, double* counts) {
 }
 
 template <int DP>
-static void launch_mfma(const EstepArgs& a, int G, float* partial) {
+static void launch_mfma(const EstepArgs& a, int G, float* partial, double* direct) {
     launch("tc_accumulate", tc_mfma_kernel<DP>, dim3((unsigned)(a.batch * G)), dim3(256), a.stream, a.A, a.filtered,
-           a.marginals, a.T, a.D, G, a.shared_model, partial);
+           a.marginals, a.T, a.D, G, a.shared_model, partial, direct);
 }
 
 int transition_counts(const EstepArgs& a, double* counts) {
@@ -536,21 +554,23 @@ int transition_counts(const EstepArgs& a, double* counts) {
         else launch_row_packed<32>(a, counts);
         return hipGetLastError() == hipSuccess ? 0 : 4;
     }
+    double* direct = (G == 1) ? counts : nullptr;   // one workgroup per sequence writes the counts itself
     switch (PS) {
-        case 1: launch_small<1>(a, G, partial); break;
-        case 2: launch_small<2>(a, G, partial); break;
-        case 3: launch_small<3>(a, G, partial); break;
-        case 4: launch_small<4>(a, G, partial); break;
-        case 5: launch_small<5>(a, G, partial); break;
-        case 6: launch_small<6>(a, G, partial); break;
-        case 7: launch_small<7>(a, G, partial); break;
-        case 8: launch_small<8>(a, G, partial); break;
-        case 16: launch_row<16>(a, G, partial); break;
-        case 32: launch_row<32>(a, G, partial); break;
-        case 64: launch_mfma<64>(a, G, partial); break;
-        case 128: launch_mfma<128>(a, G, partial); break;
+        case 1: launch_small<1>(a, G, partial, direct); break;
+        case 2: launch_small<2>(a, G, partial, direct); break;
+        case 3: launch_small<3>(a, G, partial, direct); break;
+        case 4: launch_small<4>(a, G, partial, direct); break;
+        case 5: launch_small<5>(a, G, partial, direct); break;
+        case 6: launch_small<6>(a, G, partial, direct); break;
+        case 7: launch_small<7>(a, G, partial, direct); break;
+        case 8: launch_small<8>(a, G, partial, direct); break;
+        case 16: launch_row<16>(a, G, partial, direct); break;
+        case 32: launch_row<32>(a, G, partial, direct); break;
+        case 64: launch_mfma<64>(a, G, partial, direct); break;
+        case 128: launch_mfma<128>(a, G, partial, direct); break;
         default: return 2;
     }
+    if (direct != nullptr) return hipGetLastError() == hipSuccess ? 0 : 4;
     const int E = a.D * a.D;
     int EPB = 1;                       // entries per workgroup: few, so that many workgroups share the partial sums
     while (EPB < E && EPB < 32) EPB <<= 1;

@@ -122,7 +122,7 @@ def test_expired_wait_is_reported_not_hung(gu, plan, monkeypatch):
     (4, 127, 50, True), (4, 129, 33, False), (4, 511, 9, False), (4, 513, 5, True), (4, 1023, 3, False),
     (4, 1024, 6, True), (4, 1025, 6, False), (1, 5, 999, True), (2, 16, 257, False), (3, 100, 70, False),
     (5, 8, 400, False), (5, 9, 401, True), (6, 63, 100, False), (7, 65, 31, True), (8, 511, 4, False),
-    (8, 512, 5, True), (8, 513, 5, False)])
+    (8, 512, 5, True), (8, 513, 5, False), (4, 1100, 1200, True), (6, 1030, 1030, False)])
 def test_short_sequences_packed_into_workgroups(gu, D, T, B, shared):
     """Sequences of at most 64 chunks (1024 steps at D <= 4, 512 above) share workgroups, a power-of-two
     group of lanes each: lengths at and around the group sizes' limits, batches that do not fill the last
