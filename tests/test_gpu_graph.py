@@ -19,10 +19,15 @@ def _problems(kind):
         return wl.config2(T=(1 << 20) + 4097), wl.config2(T=(1 << 20) + 4097, seed=992)
     if kind == "c3":
         return wl.config3(T=30000), wl.config3(T=30000, seed=993)
+    if kind == "short":      # several short sequences per workgroup, no workspace
+        return (wl.random_problem(4, 300, batch=500, shared_model=True, seed=5),
+                wl.random_problem(4, 300, batch=500, shared_model=True, seed=6))
+    if kind == "c4_full":    # enough chunks for the one-pass vector recursions
+        return wl.config4(), wl.config4(seed=995)
     return wl.config4(batch=8, T=1000), wl.config4(batch=8, T=1000, seed=994)
 
 
-@pytest.mark.parametrize("kind", ["c2", "c2_multi", "c3", "c4"])
+@pytest.mark.parametrize("kind", ["c2", "c2_multi", "c3", "c4", "short", "c4_full"])
 def test_captured_calls_replay_exactly(kind):
     pa, pb = _problems(kind)
     dev = torch.device("cuda:0")
