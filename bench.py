@@ -326,20 +326,24 @@ def main() -> int:
     viterbi_us = sum(v["avg_us"] * v["launches"] for k, v in per_kernel.items() if k in VITERBI_KERNELS) / args.steps
     dom = max(per_kernel.items(), key=lambda kv: kv[1]["avg_us"] * kv[1]["launches"])
     dom_name, dom_us = dom[0], dom[1]["avg_us"]
-    roofline = kernel_roofline(dom_name, dom_us, B, T, D)
-    tfile = os.path.join(ROOT, "profiles", "traffic_" + dom_name + "_" + args.workload + ".json")
-    if os.path.exists(tfile):
-        try:
-            roofline["traffic"] = json.load(open(tfile)).get("traffic_bytes_per_launch")
-        except Exception:
-            pass
+    def with_traffic(r, name):
+        """HBM bytes per launch from the committed rocprofv3 counter summary of this kernel and workload, if there is one."""
+        tfile = os.path.join(ROOT, "profiles", "traffic_" + name + "_" + args.workload + ".json")
+        if os.path.exists(tfile):
+            try:
+                r["traffic"] = json.load(open(tfile)).get("traffic_bytes_per_launch")
+            except Exception:
+                pass
+        return r
+
+    roofline = with_traffic(kernel_roofline(dom_name, dom_us, B, T, D), dom_name)
     roofline["smooth_call"] = {"kernel_us": smooth_us,
                                "frac": (B * T * 8 * D) / (smooth_us * 1e-6) / 1e9 / HBM_PEAK_GBS if smooth_us > 0 else None}
     roofline["viterbi_call"] = {"kernel_us": viterbi_us,
                                 "frac": (B * T * (4 * D + 4)) / (viterbi_us * 1e-6) / 1e9 / HBM_PEAK_GBS
                                 if viterbi_us > 0 else None}
     # every kernel that takes at least a tenth of the step, against its own bound
-    other_rooflines = [kernel_roofline(k, v["avg_us"], B, T, D) for k, v in per_kernel.items()
+    other_rooflines = [with_traffic(kernel_roofline(k, v["avg_us"], B, T, D), k) for k, v in per_kernel.items()
                        if k != dom_name and v["avg_us"] * v["launches"] / args.steps >= 0.1 * (smooth_us + viterbi_us)]
 
     cpu_baseline = None
