@@ -133,3 +133,13 @@ def test_short_sequences_packed_into_workgroups(gu, D, T, B, shared):
     gu.check_viterbi(p, label=label)
     gu.check_max_product(p, label=label)
     gu.check_transition_counts(p, label=label)
+
+
+def test_very_long_sequence(gu, plan):
+    """2^23 + 5 steps in one sequence: 2049 tiles, far more than fit the device at once, so the multi-launch
+    kernels run whatever plan is asked for; every marginal and the whole path against the oracle."""
+    if plan == "multi":
+        pytest.skip("the same kernels as under the default plan at this length")
+    p = wl.config2(T=(1 << 23) + 5, seed=77)
+    gu.check_smooth(p, label="C2 model, T=2^23+5")
+    gu.check_viterbi(p, label="C2 model, T=2^23+5")
