@@ -111,3 +111,45 @@ def test_subnormal_strip_in_a_drawn_problem(gu):
     p = wl.random_problem(17, 17235, batch=7, shared_model=True, seed=9242, ll_scale=40.0)
     gu.check_smooth(p, want_filtered=True, label="drawn D=17")
     gu.check_transition_counts(p, label="drawn D=17")
+
+
+@pytest.mark.parametrize("D", [3, 4, 16, 40])
+@pytest.mark.parametrize("kind", ["identical_rows", "permutation", "identity", "constant_evidence", "one_way_chain"])
+def test_degenerate_models(gu, D, kind):
+    """Transition structures at the corners of the method: independent steps (identical rows: every element has
+    rank one), deterministic dynamics (a permutation, the identity: elements are scaled permutation matrices and
+    log A is -inf almost everywhere), evidence that says nothing, and a left-to-right chain with an absorbing end.
+    Lengths and likelihood spreads keep the exact posterior inside single-precision range."""
+    rng = np.random.default_rng(17 * D + len(kind))
+    T, B, scale = 3000, 2, 2.0
+    p = wl.random_problem(D, T, batch=B, shared_model=True, seed=400 + D)
+    A = np.zeros((D, D))
+    if kind == "identical_rows":
+        A[:] = rng.dirichlet(np.ones(D))[None, :]
+    elif kind == "permutation":
+        A[np.arange(D), rng.permutation(D)] = 1.0
+        T, scale = 160, 0.3
+    elif kind == "identity":
+        A[np.arange(D), np.arange(D)] = 1.0
+        T, scale = 120, 0.3
+    elif kind == "constant_evidence":
+        A = rng.dirichlet(np.ones(D), size=D)
+        scale = 0.0
+    else:
+        for i in range(D):
+            A[i, i] = 0.9 if i + 1 < D else 1.0
+            if i + 1 < D:
+                A[i, i + 1] = 0.1
+        T, scale = 40 * D, 0.5
+    p = wl.random_problem(D, T, batch=B, shared_model=True, seed=400 + D, ll_scale=max(scale, 1e-3))
+    if kind == "constant_evidence":
+        p.loglik[...] = -1.25
+    p.A[0] = A.astype(np.float32)
+    if kind == "one_way_chain":
+        p.prior[0] = 0.0
+        p.prior[0, 0] = 1.0
+    label = f"{kind} D={D}"
+    gu.check_smooth(p, want_filtered=True, label=label)
+    gu.check_viterbi(p, label=label)
+    gu.check_max_product(p, label=label)
+    gu.check_transition_counts(p, label=label)
