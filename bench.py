@@ -336,14 +336,29 @@ def main() -> int:
                 pass
         return r
 
-    roofline = with_traffic(kernel_roofline(dom_name, dom_us, B, T, D), dom_name)
+    def with_issue(r, name):
+        """Vector-issue view beside the HBM one: wave instructions per launch (committed counter summary) x 4 cycles
+        (a 64-lane instruction on a 16-lane SIMD) against the launch's duration on all SIMDs."""
+        vfile = os.path.join(ROOT, "profiles", "valu_instr_" + args.workload + ".json")
+        if os.path.exists(vfile):
+            try:
+                n = json.load(open(vfile))["valu_instr_per_launch"].get(name)
+                if n:
+                    simds, clock = 256 * 4, 2.4e9
+                    r["valu_issue"] = {"bound": "alu", "wave_instr_per_launch": n,
+                                       "frac": n * 4.0 / (r["avg_us"] * 1e-6 * clock * simds)}
+            except Exception:
+                pass
+        return r
+
+    roofline = with_issue(with_traffic(kernel_roofline(dom_name, dom_us, B, T, D), dom_name), dom_name)
     roofline["smooth_call"] = {"kernel_us": smooth_us,
                                "frac": (B * T * 8 * D) / (smooth_us * 1e-6) / 1e9 / HBM_PEAK_GBS if smooth_us > 0 else None}
     roofline["viterbi_call"] = {"kernel_us": viterbi_us,
                                 "frac": (B * T * (4 * D + 4)) / (viterbi_us * 1e-6) / 1e9 / HBM_PEAK_GBS
                                 if viterbi_us > 0 else None}
     # every kernel that takes at least a tenth of the step, against its own bound
-    other_rooflines = [with_traffic(kernel_roofline(k, v["avg_us"], B, T, D), k) for k, v in per_kernel.items()
+    other_rooflines = [with_issue(with_traffic(kernel_roofline(k, v["avg_us"], B, T, D), k), k) for k, v in per_kernel.items()
                        if k != dom_name and v["avg_us"] * v["launches"] / args.steps >= 0.1 * (smooth_us + viterbi_us)]
 
     cpu_baseline = None
