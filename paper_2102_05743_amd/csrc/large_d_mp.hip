@@ -485,6 +485,8 @@ __global__ __launch_bounds__(256) void lv_forward_kernel(const float* __restrict
             if (cc.t0 + s == 0) {
                 gval = vc[j] + x;   // V_1 = log prior + ll_1
             } else {
+                // groups of four candidates are ranked independently and merged in index order (short dependent
+                // chains); strict comparisons throughout, so the lowest index wins ties
                 float best = -INFINITY;
                 int bi = h * C::RPP;
 #pragma unroll
@@ -492,10 +494,12 @@ __global__ __launch_bounds__(256) void lv_forward_kernel(const float* __restrict
                     const float4 v4 = *reinterpret_cast<const float4*>(vc + h * C::RPP + r4);
                     const float c0 = v4.x + lareg[r4], c1 = v4.y + lareg[r4 + 1];
                     const float c2 = v4.z + lareg[r4 + 2], c3 = v4.w + lareg[r4 + 3];
-                    if (c0 > best) { best = c0; bi = h * C::RPP + r4; }        // strict: lowest index wins ties
-                    if (c1 > best) { best = c1; bi = h * C::RPP + r4 + 1; }
-                    if (c2 > best) { best = c2; bi = h * C::RPP + r4 + 2; }
-                    if (c3 > best) { best = c3; bi = h * C::RPP + r4 + 3; }
+                    float ba = c0, bb = c2;
+                    int ia = h * C::RPP + r4, ib = h * C::RPP + r4 + 2;
+                    if (c1 > ba) { ba = c1; ia = h * C::RPP + r4 + 1; }
+                    if (c3 > bb) { bb = c3; ib = h * C::RPP + r4 + 3; }
+                    if (bb > ba) { ba = bb; ia = ib; }
+                    if (r4 == 0 || ba > best) { best = ba; bi = ia; }
                 }
                 // combine the parts: a higher part wins only if strictly better
 #pragma unroll
@@ -516,7 +520,8 @@ __global__ __launch_bounds__(256) void lv_forward_kernel(const float* __restrict
             const float mw = wave_max(gval);
             if (lane == 0) wn[wv] = mw;
         }
-        lds_barrier();
+        if constexpr (C::VWPC > 1) lds_barrier();   // a chunk of D <= 32 is one wave: its LDS traffic is ordered as issued
+        else wave_lds_sync();
         if (active) {
             float m = wn[0];
 #pragma unroll
