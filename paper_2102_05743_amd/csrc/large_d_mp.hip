@@ -485,8 +485,8 @@ __global__ __launch_bounds__(256) void lv_forward_kernel(const float* __restrict
             if (cc.t0 + s == 0) {
                 gval = vc[j] + x;   // V_1 = log prior + ll_1
             } else {
-                // groups of four candidates are ranked independently and merged in index order (short dependent
-                // chains); strict comparisons throughout, so the lowest index wins ties
+                // D <= 32: groups of four candidates are ranked independently and merged in index order (short
+                // dependent chains); strict comparisons throughout, so the lowest index wins ties
                 float best = -INFINITY;
                 int bi = h * C::RPP;
 #pragma unroll
@@ -494,12 +494,19 @@ __global__ __launch_bounds__(256) void lv_forward_kernel(const float* __restrict
                     const float4 v4 = *reinterpret_cast<const float4*>(vc + h * C::RPP + r4);
                     const float c0 = v4.x + lareg[r4], c1 = v4.y + lareg[r4 + 1];
                     const float c2 = v4.z + lareg[r4 + 2], c3 = v4.w + lareg[r4 + 3];
-                    float ba = c0, bb = c2;
-                    int ia = h * C::RPP + r4, ib = h * C::RPP + r4 + 2;
-                    if (c1 > ba) { ba = c1; ia = h * C::RPP + r4 + 1; }
-                    if (c3 > bb) { bb = c3; ib = h * C::RPP + r4 + 3; }
-                    if (bb > ba) { ba = bb; ia = ib; }
-                    if (r4 == 0 || ba > best) { best = ba; bi = ia; }
+                    if constexpr (C::VWPC == 1) {
+                        float ba = c0, bb = c2;
+                        int ia = h * C::RPP + r4, ib = h * C::RPP + r4 + 2;
+                        if (c1 > ba) { ba = c1; ia = h * C::RPP + r4 + 1; }
+                        if (c3 > bb) { bb = c3; ib = h * C::RPP + r4 + 3; }
+                        if (bb > ba) { ba = bb; ia = ib; }
+                        if (r4 == 0 || ba > best) { best = ba; bi = ia; }
+                    } else {   // long rows (D >= 64): one chain, fewer instructions (measured faster there)
+                        if (c0 > best) { best = c0; bi = h * C::RPP + r4; }
+                        if (c1 > best) { best = c1; bi = h * C::RPP + r4 + 1; }
+                        if (c2 > best) { best = c2; bi = h * C::RPP + r4 + 2; }
+                        if (c3 > best) { best = c3; bi = h * C::RPP + r4 + 3; }
+                    }
                 }
                 // combine the parts: a higher part wins only if strictly better
 #pragma unroll
