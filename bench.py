@@ -97,7 +97,7 @@ def ge_sweep() -> int:
         path = torch.empty((1, T), dtype=torch.int32, device=dev)
         out = torch.empty((2, 1), dtype=torch.float64, device=dev)
         ws_s, ws_v = hmm.hmm_workspace_bytes(T, p.D, 1)
-        ws = torch.empty((max(ws_s, ws_v, 256),), dtype=torch.uint8, device=dev)
+        ws = hmm.new_workspace(max(ws_s, ws_v), dev)
         calls = {"smooth": hmm.hmm_smooth_prepare(prior, A, ll, marginals=marg, loglik_out=out[0], workspace=ws),
                  "viterbi": hmm.hmm_viterbi_prepare(prior, A, ll, path=path, logprob_out=out[1], workspace=ws)}
         row = {"T": T}
@@ -238,8 +238,8 @@ def main() -> int:
     logliks = torch.empty((nsets, B), dtype=torch.float64, device=dev)
     logprobs = torch.empty((nsets, B), dtype=torch.float64, device=dev)
     ws_s, ws_v = hmm.hmm_workspace_bytes(T, D, B)
-    ws_smooth = torch.empty((max(ws_s, 256),), dtype=torch.uint8, device=dev)
-    ws_viterbi = torch.empty((max(ws_v, 256),), dtype=torch.uint8, device=dev)
+    ws_smooth = hmm.new_workspace(ws_s, dev)       # allocated and prepared once, outside every timed region
+    ws_viterbi = hmm.new_workspace(ws_v, dev)
 
     cal_src = cal_dst = None
     if args.copy_calibration:

@@ -2,10 +2,10 @@
  * hmmscan -- HMM smoothing and Viterbi decoding as all-prefix-sums on AMD MI355X (gfx950).
  *
  * C ABI.  Every array argument is DEVICE memory owned by the caller; the library
- * allocates nothing, keeps no per-call state and never synchronises: all work is
- * enqueued on the caller's HIP stream and outputs are valid once that stream has
- * been synchronised.  Inputs are never written; outputs and the workspace must
- * not alias the inputs or each other.  All arrays are contiguous and row-major.
+ * allocates nothing and never synchronises: all work is enqueued on the caller's HIP
+ * stream and outputs are valid once that stream has been synchronised.  Inputs are
+ * never written; outputs and the workspace must not alias the inputs or each other.
+ * All arrays are contiguous and row-major.
  *
  * Model (Sec. II of the paper): x_1 ~ prior, x_k ~ A[x_{k-1}][.], y_k ~ p(y_k | x_k),
  * states are 0-based, potentials psi_1(x_1) = p(y_1|x_1) p(x_1) and
@@ -18,25 +18,35 @@
  * whose evidence is impossible under every state (a log-likelihood row that is
  * all -inf, or Z = 0) is not an error: the returned log-likelihood /
  * log-probability is then -inf or NaN and the marginals / path are unspecified.
- * The same holds for evidence that is impossible within single-precision range:
- * hmm_smooth works on probabilities (fp32, rescaled by powers of two), so a state
- * whose filtered probability falls below 2^-126 of the step's largest is lost; if
- * zero transitions then leave only states that later evidence rules out by more
- * than about e^87, the log-likelihood is NaN.  The max-product calls work on
- * logarithms and have no such limit.
+ * Range: hmm_smooth works on probabilities in single precision, rescaled by exact
+ * powers of two; the scale of every vector, and of every ROW of an aggregated
+ * product of potentials, is kept apart from the mantissas, so the only states lost
+ * are those a step-by-step forward-backward recursion in single precision loses as
+ * well: a state whose filtered (or backward) probability falls below 2^-126 of the
+ * step's largest becomes exactly zero.  The max-product calls work on logarithms.
+ *
+ * Workspaces.  The first HMM_WORKSPACE_RESERVED_BYTES of every workspace belong to
+ * the library across calls: they MUST BE ZERO before the workspace's first use
+ * (hmm_workspace_init does it on a stream; a zero-filled allocation is as good),
+ * and nothing but this library may write there afterwards.  The rest of a workspace
+ * is plain scratch: contents on entry are ignored, on exit undefined.  One
+ * workspace may serve any sequence of calls of any shapes, one call at a time:
+ * two calls must not use one workspace concurrently.
  *
  * Concurrency.  Calls may be enqueued back to back on one stream.  For small state
  * spaces (D <= 8), sequences longer than one tile (4096 steps at D <= 4, 2048
  * above) and shapes whose tiles all fit the device at once, a call is a
- * single kernel whose workgroups wait for one another's partial results, which
- * needs them all resident together; the host checks this against an otherwise
- * idle device.  (Shorter sequences never wait for one another.)  If other work (another stream, another process) occupies compute
- * units for the whole duration, the wait is bounded: the kernel then terminates
- * by itself and the call's log-likelihood / log-probability output is NaN (its
- * other outputs are then meaningless).  HMMSCAN_SPIN_LIMIT=<polls> overrides the
- * bound (0: give up at once, for exercising this path).  Setting the
- * environment variable HMMSCAN_PLAN=multi selects the plan without such waits for
- * every shape.  Two calls must not share one workspace concurrently.
+ * single kernel whose workgroups wait for one another's partial results (exchanged
+ * through the reserved bytes), which needs them all resident together; the host
+ * checks this against an otherwise idle device.  (Shorter sequences never wait for
+ * one another.)  If other work (another stream, another process) occupies compute
+ * units for the whole duration, the wait is bounded: the kernel then terminates by
+ * itself, the call's log-likelihood / log-probability output is NaN (its other
+ * outputs are then meaningless) and the workspace is marked: every later call of
+ * this kind on it reports NaN at once until hmm_workspace_init has been called on
+ * it again (hmm_workspace_status tells).  HMMSCAN_SPIN_LIMIT=<polls> overrides the
+ * bound (0: give up at once, for exercising this path).  Setting the environment
+ * variable HMMSCAN_PLAN=multi selects the plan without such waits for every shape.
  */
 #ifndef HMMSCAN_H
 #define HMMSCAN_H
@@ -59,12 +69,27 @@ typedef enum {
 /* Largest supported number of states D. */
 #define HMM_MAX_STATES 128
 
+/* Leading bytes of every workspace that the library keeps across calls (see "Workspaces" above). */
+#define HMM_WORKSPACE_RESERVED_BYTES (320u * 1024u)
+
 /*
- * Scratch size, in bytes, that hmm_smooth and hmm_viterbi need for this shape.
- * Pure host function (no device access).  Either output pointer may be NULL.
+ * Scratch size, in bytes, that hmm_smooth and hmm_viterbi need for this shape (the reserved
+ * leading bytes included).  Pure host function (no device access).  Either output pointer may be NULL.
  */
 hmm_status hmm_workspace_bytes(int64_t T, int32_t D, int32_t batch,
                                size_t* smooth_bytes, size_t* viterbi_bytes);
+
+/*
+ * Prepares a workspace for its first use, or for reuse after a call whose bounded wait ran out:
+ * enqueues a zero fill of its first min(workspace_bytes, HMM_WORKSPACE_RESERVED_BYTES) bytes on the
+ * stream (a kernel: it can be captured into a HIP graph like every other launch of the library).
+ * workspace must be 256-byte aligned device memory.
+ *
+ * hmm_workspace_status copies the workspace's state word back to the host (it synchronises the
+ * stream): *state = 0 ready, 1 a bounded wait ran out in an earlier call (re-initialise).
+ */
+hmm_status hmm_workspace_init(void* workspace, size_t workspace_bytes, void* hip_stream);
+hmm_status hmm_workspace_status(const void* workspace, void* hip_stream, int32_t* state);
 
 /*
  * Smoothing marginals and log-likelihood by the parallel sum-product method
@@ -79,7 +104,7 @@ hmm_status hmm_workspace_bytes(int64_t T, int32_t D, int32_t batch,
  *   filtered   [batch][T][D]  out, may be NULL: p(x_t | y_{1:t}) (the normalised forward potential)
  *   loglik_out [batch]        out: log p(y_{1:T}) = log Z (the partition function of Sec. II)
  *   workspace / workspace_bytes: device scratch of at least hmm_workspace_bytes(...).smooth_bytes,
- *              256-byte aligned; contents on entry are ignored, on exit undefined
+ *              256-byte aligned, prepared once as described under "Workspaces" above
  *   hip_stream a hipStream_t (NULL = the default stream)
  *
  * loglik, marginals and filtered must be 16-byte aligned.  fp32 arithmetic

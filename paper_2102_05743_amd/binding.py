@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libhmmscan.so")
 HMM_OK = 0
 _lib = None
 
-EXPORTED_SYMBOLS = ("hmm_workspace_bytes", "hmm_smooth", "hmm_viterbi", "hmm_max_product",
+EXPORTED_SYMBOLS = ("hmm_workspace_bytes", "hmm_workspace_init", "hmm_workspace_status", "hmm_smooth", "hmm_viterbi", "hmm_max_product",
                     "hmm_transition_counts_workspace_bytes", "hmm_transition_counts",
                     "hmm_block_element_workspace_bytes", "hmm_block_element", "hmm_block_carries", "hmm_status_string",
                     "hmm_kernel_timing_enable", "hmm_kernel_timing_count", "hmm_kernel_timing_get")
@@ -40,6 +40,10 @@ def load_library():
         lib.hmm_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32,
                                             ctypes.POINTER(sz), ctypes.POINTER(sz)]
         lib.hmm_workspace_bytes.restype = ctypes.c_int
+        lib.hmm_workspace_init.argtypes = [vp, sz, vp]
+        lib.hmm_workspace_init.restype = ctypes.c_int
+        lib.hmm_workspace_status.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_int32)]
+        lib.hmm_workspace_status.restype = ctypes.c_int
         lib.hmm_smooth.argtypes = [vp, vp, vp, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                                    vp, vp, vp, vp, sz, vp]
         lib.hmm_smooth.restype = ctypes.c_int
@@ -88,6 +92,34 @@ def hmm_workspace_bytes(T: int, D: int, batch: int):
     if rc != HMM_OK:
         raise HmmError(rc, "hmm_workspace_bytes")
     return int(s.value), int(v.value)
+
+
+WORKSPACE_RESERVED_BYTES = 320 * 1024
+
+
+def hmm_workspace_init(workspace) -> None:
+    """Zeroes the workspace's reserved leading bytes on torch's current stream (required once before the
+    workspace's first use, and again after a call whose bounded wait ran out)."""
+    rc = load_library().hmm_workspace_init(_ptr(workspace), workspace.numel() * workspace.element_size(), _stream())
+    if rc != HMM_OK:
+        raise HmmError(rc, "hmm_workspace_init")
+
+
+def hmm_workspace_status(workspace) -> int:
+    """0: ready; 1: a bounded wait ran out in an earlier call on this workspace (re-initialise it).  Synchronises."""
+    state = ctypes.c_int32(0)
+    rc = load_library().hmm_workspace_status(_ptr(workspace), _stream(), ctypes.byref(state))
+    if rc != HMM_OK:
+        raise HmmError(rc, "hmm_workspace_status")
+    return int(state.value)
+
+
+def new_workspace(nbytes: int, device):
+    """A device buffer of at least nbytes, prepared for its first use (allocation and hmm_workspace_init)."""
+    import torch
+    ws = torch.empty((max(int(nbytes), 256),), dtype=torch.uint8, device=device)
+    hmm_workspace_init(ws)
+    return ws
 
 
 def hmm_kernel_timing_enable(on: bool) -> None:
@@ -172,7 +204,7 @@ def hmm_smooth_prepare(prior, A, loglik, marginals=None, filtered=None, loglik_o
         _check(filtered, f32, (B, T, D), "filtered")
     _check(loglik_out, torch.float64, (B,), "loglik_out")
     if workspace is None:
-        workspace = torch.empty((max(hmm_workspace_bytes(T, D, B)[0], 256),), dtype=torch.uint8, device=dev)
+        workspace = new_workspace(hmm_workspace_bytes(T, D, B)[0], dev)
     cargs = (_ptr(prior), _ptr(A), _ptr(loglik), T, D, B, shared, _ptr(marginals), _ptr(filtered),
              _ptr(loglik_out), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream())
     return PreparedCall(lib.hmm_smooth, "hmm_smooth", cargs, (prior, A, loglik, workspace),
@@ -204,7 +236,7 @@ def hmm_viterbi_prepare(prior, A, loglik, path=None, logprob_out=None, workspace
     _check(path, torch.int32, (B, T), "path")
     _check(logprob_out, torch.float64, (B,), "logprob_out")
     if workspace is None:
-        workspace = torch.empty((max(hmm_workspace_bytes(T, D, B)[1], 256),), dtype=torch.uint8, device=dev)
+        workspace = new_workspace(hmm_workspace_bytes(T, D, B)[1], dev)
     cargs = (_ptr(prior), _ptr(A), _ptr(loglik), T, D, B, shared, _ptr(path), _ptr(logprob_out),
              _ptr(workspace), workspace.numel() * workspace.element_size(), _stream())
     return PreparedCall(lib.hmm_viterbi, "hmm_viterbi", cargs, (prior, A, loglik, workspace), (path, logprob_out))
@@ -237,7 +269,7 @@ def hmm_max_product_prepare(prior, A, loglik, max_marginals=None, path=None, log
         _check(path, torch.int32, (B, T), "path")
     _check(logprob_out, torch.float64, (B,), "logprob_out")
     if workspace is None:
-        workspace = torch.empty((max(hmm_workspace_bytes(T, D, B)[0], 256),), dtype=torch.uint8, device=dev)
+        workspace = new_workspace(hmm_workspace_bytes(T, D, B)[0], dev)
     cargs = (_ptr(prior), _ptr(A), _ptr(loglik), T, D, B, shared, _ptr(max_marginals), _ptr(path),
              _ptr(logprob_out), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream())
     return PreparedCall(lib.hmm_max_product, "hmm_max_product", cargs, (prior, A, loglik, workspace),
@@ -278,7 +310,7 @@ def hmm_transition_counts(A, filtered, marginals, counts=None, workspace=None):
         counts = torch.empty((B, D, D), dtype=torch.float64, device=dev)
     _check(counts, torch.float64, (B, D, D), "counts")
     if workspace is None:
-        workspace = torch.empty((max(hmm_transition_counts_workspace_bytes(T, D, B), 256),), dtype=torch.uint8, device=dev)
+        workspace = new_workspace(hmm_transition_counts_workspace_bytes(T, D, B), dev)
     rc = lib.hmm_transition_counts(_ptr(A), _ptr(filtered), _ptr(marginals), T, D, B, 1 if Bm == 1 else 0, _ptr(counts),
                                    _ptr(workspace), workspace.numel() * workspace.element_size(), _stream())
     if rc != HMM_OK:
@@ -316,7 +348,7 @@ def hmm_block_element(A, loglik, max_product: bool = False, element=None, log_sc
     _check(element, f32, (B, D, D), "element")
     _check(log_scale, torch.float64, (B,), "log_scale")
     if workspace is None:
-        workspace = torch.empty((max(hmm_block_element_workspace_bytes(T, D, B), 256),), dtype=torch.uint8, device=dev)
+        workspace = new_workspace(hmm_block_element_workspace_bytes(T, D, B), dev)
     rc = lib.hmm_block_element(_ptr(A), _ptr(loglik), T, D, B, 1 if Bm == 1 else 0, 1 if max_product else 0, _ptr(element),
                                _ptr(log_scale), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream())
     if rc != HMM_OK:

@@ -12,6 +12,12 @@ namespace {
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// Every workspace starts with HMM_WORKSPACE_RESERVED_BYTES that only the single-launch kernels of the
+// small state spaces write (tagged exchange words); all other scratch lies behind it.
+constexpr size_t RESERVED = hmm::XCH_REGION_BYTES;
+static_assert(RESERVED == HMM_WORKSPACE_RESERVED_BYTES, "header and library disagree on the reserved region");
+char* behind_reserved(void* ws) { return static_cast<char*>(ws) + RESERVED; }
+
 hmm_status check_common(const float* prior, const float* A, const float* loglik, int64_t T, int32_t D,
                         int32_t batch) {
     if (!prior || !A || !loglik) return HMM_ERR_INVALID_ARG;
@@ -30,13 +36,15 @@ hmm_status hmm_workspace_bytes(int64_t T, int32_t D, int32_t batch, size_t* smoo
     if (D > HMM_MAX_STATES) return HMM_ERR_UNSUPPORTED;
     size_t s = 0, v = 0;
     if (D <= hmm::SMALL_D_MAX) {
-        s = hmm::small_d_smooth_ws_bytes(D, T, batch);
+        s = hmm::small_d_smooth_ws_bytes(D, T, batch);     // these include the reserved region
         v = hmm::small_d_viterbi_ws_bytes(D, T, batch);
     } else {
         s = hmm::large_d_smooth_ws_bytes(D, T, batch);
         const size_t mp = hmm::large_d_max_product_ws_bytes(D, T, batch);   // hmm_max_product shares smooth_bytes
         if (mp > s) s = mp;
         v = hmm::large_d_viterbi_ws_bytes(D, T, batch);
+        s += RESERVED;
+        v += RESERVED;
     }
     if (smooth_bytes) *smooth_bytes = s;
     if (viterbi_bytes) *viterbi_bytes = v;
@@ -55,8 +63,8 @@ hmm_status hmm_smooth(const float* prior, const float* A, const float* loglik, i
     if (st != HMM_OK) return st;
     if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return HMM_ERR_WORKSPACE;
     if (D > hmm::SMALL_D_MAX) {
-        hmm::LargeArgs la{prior, A, loglik, (long long)T, D, batch, shared_model ? 1 : 0, workspace, workspace_bytes,
-                          static_cast<hipStream_t>(hip_stream)};
+        hmm::LargeArgs la{prior, A, loglik, (long long)T, D, batch, shared_model ? 1 : 0, behind_reserved(workspace),
+                          workspace_bytes - RESERVED, static_cast<hipStream_t>(hip_stream)};
         return static_cast<hmm_status>(hmm::large_d_smooth(la, marginals, filtered, loglik_out));
     }
     hmm::SmallArgs a{prior, A, loglik, (long long)T, batch, shared_model ? 1 : 0, workspace, workspace_bytes,
@@ -75,8 +83,8 @@ hmm_status hmm_viterbi(const float* prior, const float* A, const float* loglik, 
     if (st != HMM_OK) return st;
     if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return HMM_ERR_WORKSPACE;
     if (D > hmm::SMALL_D_MAX) {
-        hmm::LargeArgs la{prior, A, loglik, (long long)T, D, batch, shared_model ? 1 : 0, workspace, workspace_bytes,
-                          static_cast<hipStream_t>(hip_stream)};
+        hmm::LargeArgs la{prior, A, loglik, (long long)T, D, batch, shared_model ? 1 : 0, behind_reserved(workspace),
+                          workspace_bytes - RESERVED, static_cast<hipStream_t>(hip_stream)};
         return static_cast<hmm_status>(hmm::large_d_viterbi(la, path, logprob_out));
     }
     hmm::SmallArgs a{prior, A, loglik, (long long)T, batch, shared_model ? 1 : 0, workspace, workspace_bytes,
@@ -96,8 +104,8 @@ hmm_status hmm_max_product(const float* prior, const float* A, const float* logl
     if (st != HMM_OK) return st;
     if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return HMM_ERR_WORKSPACE;
     if (D > hmm::SMALL_D_MAX) {
-        hmm::LargeArgs la{prior, A, loglik, (long long)T, D, batch, shared_model ? 1 : 0, workspace, workspace_bytes,
-                          static_cast<hipStream_t>(hip_stream)};
+        hmm::LargeArgs la{prior, A, loglik, (long long)T, D, batch, shared_model ? 1 : 0, behind_reserved(workspace),
+                          workspace_bytes - RESERVED, static_cast<hipStream_t>(hip_stream)};
         return static_cast<hmm_status>(hmm::large_d_max_product(la, max_marginals, path, logprob_out));
     }
     hmm::SmallArgs a{prior, A, loglik, (long long)T, batch, shared_model ? 1 : 0, workspace, workspace_bytes,
@@ -108,7 +116,7 @@ hmm_status hmm_max_product(const float* prior, const float* A, const float* logl
 hmm_status hmm_transition_counts_workspace_bytes(int64_t T, int32_t D, int32_t batch, size_t* bytes) {
     if (T < 1 || D < 1 || batch < 1 || !bytes) return HMM_ERR_INVALID_ARG;
     if (D > HMM_MAX_STATES) return HMM_ERR_UNSUPPORTED;
-    *bytes = hmm::transition_counts_ws_bytes(D, T, batch);
+    *bytes = hmm::transition_counts_ws_bytes(D, T, batch) + RESERVED;
     return HMM_OK;
 }
 
@@ -118,10 +126,10 @@ hmm_status hmm_transition_counts(const float* A, const float* filtered, const fl
     if (!A || !filtered || !marginals || !counts) return HMM_ERR_INVALID_ARG;
     if (T < 1 || D < 1 || batch < 1) return HMM_ERR_INVALID_ARG;
     if (D > HMM_MAX_STATES) return HMM_ERR_UNSUPPORTED;
-    const size_t need = hmm::transition_counts_ws_bytes(D, T, batch);
+    const size_t need = hmm::transition_counts_ws_bytes(D, T, batch) + RESERVED;
     if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return HMM_ERR_WORKSPACE;
-    hmm::EstepArgs a{A, filtered, marginals, (long long)T, D, batch, shared_model ? 1 : 0, workspace, workspace_bytes,
-                     static_cast<hipStream_t>(hip_stream)};
+    hmm::EstepArgs a{A, filtered, marginals, (long long)T, D, batch, shared_model ? 1 : 0, behind_reserved(workspace),
+                     workspace_bytes - RESERVED, static_cast<hipStream_t>(hip_stream)};
     return static_cast<hmm_status>(hmm::transition_counts(a, counts));
 }
 
@@ -132,7 +140,7 @@ hmm_status hmm_block_element_workspace_bytes(int64_t T, int32_t D, int32_t batch
         *bytes = hmm::small_d_element_ws_bytes(D, T, batch);
     } else {
         const size_t sp = hmm::large_d_element_sp_ws_bytes(D, T, batch), mp = hmm::large_d_element_mp_ws_bytes(D, T, batch);
-        *bytes = sp > mp ? sp : mp;
+        *bytes = (sp > mp ? sp : mp) + RESERVED;
     }
     return HMM_OK;
 }
@@ -149,8 +157,8 @@ hmm_status hmm_block_element(const float* A, const float* loglik, int64_t T, int
     if (st != HMM_OK) return st;
     if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return HMM_ERR_WORKSPACE;
     if (D > hmm::SMALL_D_MAX) {
-        hmm::LargeArgs la{nullptr, A, loglik, (long long)T, D, batch, shared_model ? 1 : 0, workspace, workspace_bytes,
-                          static_cast<hipStream_t>(hip_stream)};
+        hmm::LargeArgs la{nullptr, A, loglik, (long long)T, D, batch, shared_model ? 1 : 0, behind_reserved(workspace),
+                          workspace_bytes - RESERVED, static_cast<hipStream_t>(hip_stream)};
         return static_cast<hmm_status>(max_product ? hmm::large_d_element_mp(la, element, log_scale)
                                                    : hmm::large_d_element_sp(la, element, log_scale));
     }
@@ -168,6 +176,22 @@ hmm_status hmm_block_carries(const float* prior, const float* A, const float* el
     hmm::BlockCarryArgs a{prior, A, elements, log_scales, num_blocks, D, batch, shared_model ? 1 : 0, max_product ? 1 : 0,
                           static_cast<hipStream_t>(hip_stream)};
     return static_cast<hmm_status>(hmm::block_carries(a, carry_rows, lookahead_rows, total));
+}
+
+hmm_status hmm_workspace_init(void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return HMM_ERR_WORKSPACE;
+    const size_t n = workspace_bytes < RESERVED ? workspace_bytes : RESERVED;
+    return static_cast<hmm_status>(hmm::small_d_zero_region(workspace, n, static_cast<hipStream_t>(hip_stream)));
+}
+
+hmm_status hmm_workspace_status(const void* workspace, void* hip_stream, int32_t* state) {
+    if (!workspace || !state) return HMM_ERR_INVALID_ARG;
+    uint32_t header[4] = {0u, 0u, 0u, 0u};   // generation, poison flag, finished-sequence counter, padding
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (hipMemcpyAsync(header, workspace, sizeof(header), hipMemcpyDeviceToHost, st) != hipSuccess) return HMM_ERR_DEVICE;
+    if (hipStreamSynchronize(st) != hipSuccess) return HMM_ERR_DEVICE;
+    *state = header[1] != 0u ? 1 : 0;
+    return HMM_OK;
 }
 
 const char* hmm_status_string(hmm_status status) {

@@ -3,10 +3,9 @@
 //   MaxPlus : Definition 5 on logarithms, (a v b)(x_i,x_k) = max_{x_j} [a(x_i,x_j) + b(x_j,x_k)]
 // Matrices are row-major float[D*D] with compile-time indices only, so they live in VGPRs.
 //
-// Neither operator carries a scale: a sum-product element is kept within float range by
-// multiplying with an exact power of two, a max-plus element by subtracting its largest entry.
-// The scale is never needed downstream -- marginals and arg-maxima are scale-free, and the
-// log-likelihood / log-probability are accumulated from chunk-local normalisers instead.
+// The plain float[D*D] helpers below carry no scale (used by the block-element kernels, which
+// keep their own); the scans of the inference calls work on Agg<S, D> further down, a matrix
+// together with what was removed from it to keep it in range.
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -108,6 +107,225 @@ HMM_DEV void mat_vec(const float (&M)[D * D], const float (&v)[D], float (&r)[D]
 #pragma unroll
         for (int j = 1; j < D; ++j) acc = S::mul_add(acc, M[i * D + j], v[j]);
         r[i] = acc;
+    }
+}
+
+// =============================================================================================
+// Scaled aggregates: an element a_{i:k} of the scans together with its scale.
+//
+//   SumProd: value(i, j) = m[i][j] * 2^ex[i] * 2^c.  EVERY ROW has its own binary exponent: the
+//            rows of a product of potentials are the forward recursions started from each state,
+//            and with zero transitions (absorbing or one-way states) they drift apart without
+//            bound -- one exponent per matrix would flush the small rows although the carry that
+//            multiplies the aggregate may sit on exactly those rows.  A row is stored with its
+//            largest entry in [2^(ROW_BIAS-1), 2^ROW_BIAS): far above one, so that entries down to
+//            2^-(126+ROW_BIAS) of the row's largest stay normal numbers (a backward potential may
+//            weigh them up again by as much), yet low enough that the product of two such rows'
+//            entries cannot overflow.  Rows that are entirely zero keep a meaningless exponent; every consumer
+//            below ignores them.  c collects the whole bits taken out of the emission factors; it is
+//            common to the matrix and only the evidence needs it.
+//   MaxPlus: value(i, j) = m[i][j] + c, largest entry of m at 0 (logarithms need no exponents).
+//
+// All scale arithmetic is exact (integers, and doubles holding integers or sums of floats), so
+// log Z / the best log-weight follow from an aggregate of the whole sequence with one logarithm.
+template <class S, int D>
+struct Agg {
+    float m[D * D];
+    int ex[D];     // SumProd only
+    double c;
+};
+
+constexpr int EX_NONE = -(1 << 28);   // "this term does not exist" in exponent comparisons
+constexpr int FAST_SPREAD = 32;       // row exponents this close together are applied as plain powers of two
+constexpr int ROW_BIAS = 44;          // stored rows: largest entry in [2^43, 2^44)
+constexpr int SLOW_LIFT = 76;         // general product: a row's largest left factor sits at 2^76
+constexpr int WORK_BIAS = 100;        // rows inside a chunk's step loop: room to shrink between two rescalings
+constexpr int WORK_ROOM = 64;         // ... by at most this many bits
+constexpr int VEC_BIAS = 60;          // forward and backward potentials: largest entry in [2^59, 2^60)
+// (2 ROW_BIAS + FAST_SPREAD + 3, ROW_BIAS + SLOW_LIFT + 3, ROW_BIAS + VEC_BIAS + 3 and 2 VEC_BIAS + 3 all stay
+// below 127: no product of two stored quantities, summed over at most eight terms, overflows.)
+
+HMM_DEV bool wave_any(bool p) { return __builtin_amdgcn_ballot_w64(p) != 0ull; }
+
+HMM_DEV int max_of_int(int a, int b) { return a > b ? a : b; }
+HMM_DEV int min_of_int(int a, int b) { return a < b ? a : b; }
+
+template <class S, int D>
+HMM_DEV void agg_identity(Agg<S, D>& P) {
+    mat_identity<S, D>(P.m);   // (rows of the neutral element are not biased: any power of two is a valid row scale)
+#pragma unroll
+    for (int i = 0; i < D; ++i) P.ex[i] = 0;
+    P.c = 0.0;
+}
+
+// Rows back to the bias (SumProd) / largest entry back to 0 (MaxPlus); what is removed goes into the scale.
+template <class S, int D, int BIAS = ROW_BIAS>
+HMM_DEV void agg_renorm(Agg<S, D>& P) {
+    if constexpr (S::is_max_plus) {
+        float mx = max_of(P.m);
+        mx = (mx == -INFINITY) ? 0.0f : mx;
+#pragma unroll
+        for (int e = 0; e < D * D; ++e) P.m[e] -= mx;
+        P.c += (double)mx;
+    } else {
+#pragma unroll
+        for (int i = 0; i < D; ++i) {
+            float mx = P.m[i * D];
+#pragma unroll
+            for (int j = 1; j < D; ++j) mx = fmaxf(mx, P.m[i * D + j]);
+            const int e = __builtin_amdgcn_frexp_expf(mx) - BIAS;   // (a zero row just drifts: nobody reads its exponent)
+#pragma unroll
+            for (int j = 0; j < D; ++j) P.m[i * D + j] = ldexpf(P.m[i * D + j], -e);
+            P.ex[i] += e;
+        }
+    }
+}
+
+template <int D>
+HMM_DEV float row_max(const float (&m)[D * D], int i) {
+    float mx = m[i * D];
+#pragma unroll
+    for (int j = 1; j < D; ++j) mx = fmaxf(mx, m[i * D + j]);
+    return mx;
+}
+
+// Z = X (op) Y.  TRACK_C = false leaves Z.c alone (scans whose scale nobody reads).
+// SumProd: row i of Z is sum_k X(i,k) 2^ey[k] Y(k,.).  When Y's row exponents lie within FAST_SPREAD of
+// each other (decided for the whole wavefront, so the branch is uniform) they are applied to X's columns
+// as plain powers of two, lifted by 2^FAST_SPREAD so that no entry of X is flushed by it; the bias of the
+// stored rows keeps every term that matters to an entry within 2^-126 of its row's largest a normal
+// number.  Otherwise every row of Z takes its own reference exponent, the largest exponent among its
+// existing terms, so a row that lives only on Y's small rows keeps its full precision.
+template <class S, int D, bool TRACK_C = true>
+HMM_DEV void agg_mul(const Agg<S, D>& X, const Agg<S, D>& Y, Agg<S, D>& Z) {
+    if constexpr (S::is_max_plus) {
+        mat_mul<S, D>(X.m, Y.m, Z.m);
+        float mx = max_of(Z.m);
+        mx = (mx == -INFINITY) ? 0.0f : mx;
+#pragma unroll
+        for (int e = 0; e < D * D; ++e) Z.m[e] -= mx;
+        if constexpr (TRACK_C) Z.c = X.c + Y.c + (double)mx;
+    } else {
+        int hi = Y.ex[0], lo = Y.ex[0];
+#pragma unroll
+        for (int k = 1; k < D; ++k) {
+            hi = Y.ex[k] > hi ? Y.ex[k] : hi;
+            lo = Y.ex[k] < lo ? Y.ex[k] : lo;
+        }
+        if (!wave_any(hi - lo > FAST_SPREAD)) {
+            float Xs[D * D];
+#pragma unroll
+            for (int k = 0; k < D; ++k) {
+                const int d = Y.ex[k] - hi + FAST_SPREAD;   // 0 .. FAST_SPREAD: nothing of X is scaled down
+#pragma unroll
+                for (int i = 0; i < D; ++i) Xs[i * D + k] = ldexpf(X.m[i * D + k], d);
+            }
+            mat_mul<S, D>(Xs, Y.m, Z.m);   // entries below D 2^(2 ROW_BIAS + FAST_SPREAD)
+#pragma unroll
+            for (int i = 0; i < D; ++i) Z.ex[i] = X.ex[i] + hi - FAST_SPREAD;
+        } else {
+            int ey[D];
+#pragma unroll
+            for (int k = 0; k < D; ++k) ey[k] = (row_max<D>(Y.m, k) > 0.0f) ? Y.ex[k] : EX_NONE;
+#pragma unroll
+            for (int i = 0; i < D; ++i) {
+                int ref = EX_NONE;
+#pragma unroll
+                for (int k = 0; k < D; ++k) {
+                    const float x = X.m[i * D + k];
+                    const int e = (x > 0.0f && ey[k] != EX_NONE) ? __builtin_amdgcn_frexp_expf(x) + ey[k] : EX_NONE;
+                    ref = e > ref ? e : ref;
+                }
+                float w[D];   // the row's terms' left factors, the largest in [2^(SLOW_LIFT-1), 2^SLOW_LIFT)
+#pragma unroll
+                for (int k = 0; k < D; ++k)
+                    w[k] = (ey[k] != EX_NONE && ref != EX_NONE)
+                               ? ldexpf(X.m[i * D + k], max_of_int(ey[k] - ref + SLOW_LIFT, -400)) : 0.0f;
+#pragma unroll
+                for (int j = 0; j < D; ++j) {
+                    float acc = w[0] * Y.m[j];
+#pragma unroll
+                    for (int k = 1; k < D; ++k) acc = fmaf(w[k], Y.m[k * D + j], acc);
+                    Z.m[i * D + j] = acc;
+                }
+                Z.ex[i] = (ref != EX_NONE) ? X.ex[i] + ref - SLOW_LIFT : X.ex[i];
+            }
+        }
+        if constexpr (TRACK_C) Z.c = X.c + Y.c;
+        agg_renorm<S, D>(Z);
+    }
+}
+
+// r = v (op) M for a non-negative vector v of any scale (SumProd) / a vector of logarithms (MaxPlus), r brought
+// back into range: largest entry in [2^(VEC_BIAS-1), 2^VEC_BIAS) / at 0.  Returns what the result was scaled by relative to
+// v * value(M) / 2^c: bits (SumProd) or the offset (MaxPlus), for callers that track the scale.
+template <class S, int D>
+HMM_DEV double vec_agg(const float (&v)[D], const Agg<S, D>& M, float (&r)[D]) {
+    if constexpr (S::is_max_plus) {
+        vec_mat<S, D>(v, M.m, r);
+        float mx = max_of(r);
+        mx = (mx == -INFINITY) ? 0.0f : mx;
+#pragma unroll
+        for (int j = 0; j < D; ++j) r[j] -= mx;
+        return (double)mx;
+    } else {
+        constexpr int LIFT = 60;   // the largest term's left factor sits at 2^60: room below for the others
+        int e[D], ref = EX_NONE;
+#pragma unroll
+        for (int i = 0; i < D; ++i) {
+            e[i] = (v[i] > 0.0f && row_max<D>(M.m, i) > 0.0f) ? __builtin_amdgcn_frexp_expf(v[i]) + M.ex[i] : EX_NONE;
+            ref = e[i] > ref ? e[i] : ref;
+        }
+        float w[D];
+#pragma unroll
+        for (int i = 0; i < D; ++i)
+            w[i] = (e[i] != EX_NONE) ? ldexpf(v[i], max_of_int(M.ex[i] - ref + LIFT, -400)) : 0.0f;
+#pragma unroll
+        for (int j = 0; j < D; ++j) {
+            float acc = w[0] * M.m[j];
+#pragma unroll
+            for (int i = 1; i < D; ++i) acc = fmaf(w[i], M.m[i * D + j], acc);
+            r[j] = acc;   // below D 2^(LIFT + ROW_BIAS)
+        }
+        const int ex = __builtin_amdgcn_frexp_expf(max_of(r)) - VEC_BIAS;
+#pragma unroll
+        for (int j = 0; j < D; ++j) r[j] = ldexpf(r[j], -ex);
+        return (ref != EX_NONE) ? (double)(ref - LIFT) + (double)ex : 0.0;
+    }
+}
+
+// The raw form of M (op) v: s[i] = sum_j m[i][j] v[j] with the row exponents left beside it (es[i]; EX_NONE
+// where s[i] is zero), for callers that choose the common scale themselves.  SumProd only.
+template <int D>
+HMM_DEV void agg_vec_raw(const Agg<SumProd, D>& M, const float (&v)[D], float (&s)[D], int (&es)[D]) {
+    mat_vec<SumProd, D>(M.m, v, s);
+#pragma unroll
+    for (int i = 0; i < D; ++i) es[i] = (s[i] > 0.0f) ? M.ex[i] : EX_NONE;
+}
+
+// r = M (op) v, largest entry in [2^(VEC_BIAS-1), 2^VEC_BIAS) (SumProd) / at 0 (MaxPlus); returns the scale taken out.
+template <class S, int D>
+HMM_DEV double agg_vec(const Agg<S, D>& M, const float (&v)[D], float (&r)[D]) {
+    if constexpr (S::is_max_plus) {
+        mat_vec<S, D>(M.m, v, r);
+        float mx = max_of(r);
+        mx = (mx == -INFINITY) ? 0.0f : mx;
+#pragma unroll
+        for (int i = 0; i < D; ++i) r[i] -= mx;
+        return (double)mx;
+    } else {
+        float s[D];
+        int es[D], ref = EX_NONE;
+        agg_vec_raw<D>(M, v, s, es);
+#pragma unroll
+        for (int i = 0; i < D; ++i) {
+            es[i] = (es[i] != EX_NONE) ? __builtin_amdgcn_frexp_expf(s[i]) + es[i] : EX_NONE;
+            ref = es[i] > ref ? es[i] : ref;
+        }
+#pragma unroll
+        for (int i = 0; i < D; ++i)
+            r[i] = (es[i] != EX_NONE) ? ldexpf(s[i], max_of_int(M.ex[i] - ref + VEC_BIAS, -400)) : 0.0f;
+        return (ref != EX_NONE) ? (double)(ref - VEC_BIAS) : 0.0;
     }
 }
 

@@ -20,6 +20,12 @@ struct SmallArgs {
 
 constexpr int SMALL_D_MAX = 8;
 
+// Every workspace of the library begins with the exchange region of the single-launch plan (header and
+// tagged slots for up to XCH_MAX_TILES co-resident tiles of up to SMALL_D_MAX states); see
+// small_d_device.hpp.  It must be zero before a workspace's first use.
+constexpr int XCH_MAX_TILES = 512;
+constexpr size_t XCH_REGION_BYTES = 320 * 1024;
+
 // One explicit instantiation per D, each in its own translation unit (small_d_kernels.hip
 // compiled with -DHMM_SMALL_D=<D>).  Return codes follow hmm_status.
 template <int D>
@@ -40,5 +46,6 @@ int small_d_viterbi(int D, const SmallArgs& a, int32_t* path, double* logprob_ou
 int small_d_max_product(int D, const SmallArgs& a, float* maxmarg, int32_t* path, double* logprob_out);
 size_t small_d_element_ws_bytes(int D, long long T, int batch);
 int small_d_block_element(int D, const SmallArgs& a, int max_product, float* element, double* log_scale);
+int small_d_zero_region(void* ws, size_t bytes, hipStream_t stream);   // zero fill enqueued on the stream
 
 }  // namespace hmm

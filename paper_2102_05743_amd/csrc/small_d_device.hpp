@@ -186,83 +186,180 @@ HMM_DEV void model_to_domain(float (&Am)[D * D]) {
     }
 }
 
-// Emission factor of one step in the operator's domain.  SumProd: e_k(j) = exp(ll_k(j) - m_k)
-// with m_k = max_j ll_k(j) (returned); MaxPlus: ll_k itself (returns 0).
+// Emission factor of one step in the operator's domain.  MaxPlus: ll_k itself.  SumProd:
+// e_k(j) = exp(ll_k(j)) / 2^n with n = the whole number of bits nearest to max_j ll_k(j) / ln 2, so
+// that the largest factor lies in [2^-0.5, 2^0.5] and what was taken out is an integer: `bits`
+// receives n, `spread` the (non-positive) binary logarithm of the smallest factor relative to 2^n.
 template <class S, int D>
-HMM_DEV float emission(float (&ev)[D]) {
+HMM_DEV void emission(float (&ev)[D], float& bits, float& spread) {
     if constexpr (S::is_max_plus) {
-        return 0.0f;
+        bits = 0.0f;
+        spread = 0.0f;
     } else {
+        constexpr float LOG2E = 1.4426950408889634f;
         const float m = max_of(ev);
-        const float ms = (m == -INFINITY) ? 0.0f : m;
-        const float c = -1.4426950408889634f * ms;          // exp(x - m) = exp2(x * log2(e) - m * log2(e))
+        const float n = (m == -INFINITY) ? 0.0f : rintf(m * LOG2E);
+        float lo = INFINITY;
 #pragma unroll
-        for (int j = 0; j < D; ++j) ev[j] = __builtin_amdgcn_exp2f(fmaf(ev[j], 1.4426950408889634f, c));
-        return m;
+        for (int j = 0; j < D; ++j) {
+            const float x = fmaf(ev[j], LOG2E, -n);
+            lo = fminf(lo, x);
+            ev[j] = __builtin_amdgcn_exp2f(x);
+        }
+        bits = n;
+        spread = lo;
     }
 }
 
-// One element absorbed on the right of a chunk aggregate: P <- P (op) psi_k, with
-// psi_k(i,j) = Am(i,j) (x) ev(j); the sequence's first element has no transition part.
+// P <- P (op) psi_k with psi_k(i,j) = Am(i,j) (x) ev(j) on the bare matrix (no rescaling here).
 template <class S, int D>
-HMM_DEV void absorb(float (&P)[D * D], const float (&Am)[D * D], const float (&ev)[D], bool no_transition) {
-    if (no_transition) {
+HMM_DEV void absorb(float (&P)[D * D], const float (&Am)[D * D], const float (&ev)[D]) {
+    float Z[D * D];
+    mat_mul<S, D>(P, Am, Z);
 #pragma unroll
-        for (int i = 0; i < D; ++i)
+    for (int i = 0; i < D; ++i)
 #pragma unroll
-            for (int j = 0; j < D; ++j) P[i * D + j] = S::times(P[i * D + j], ev[j]);
-    } else {
-        float Z[D * D];
-        mat_mul<S, D>(P, Am, Z);
-#pragma unroll
-        for (int i = 0; i < D; ++i)
-#pragma unroll
-            for (int j = 0; j < D; ++j) P[i * D + j] = S::times(Z[i * D + j], ev[j]);
-    }
+        for (int j = 0; j < D; ++j) P[i * D + j] = S::times(Z[i * D + j], ev[j]);
 }
 
-// Aggregate of the lane's chunk: a_{k0-1:k0} (op) ... (op) a_{k1-2:k1-1} over its n valid steps.
-// With STORE_E the emission factors replace the log-likelihoods in LDS and the sum of the
-// per-step maxima m_k is returned through msum.  FULL: n == L is known (no per-step tests).
+// Aggregate of the lane's chunk: a_{k0-1:k0} (op) ... (op) a_{k1-2:k1-1} over its n valid steps, with its
+// scale.  With STORE_E the emission factors replace the log-likelihoods in LDS.  FULL: n == L is known.
+//
+// Range (SumProd).  The rows of P are rescaled every fourth step, each by its own power of two, to a
+// largest entry near 2^WORK_BIAS.  Between two rescalings a row's largest entry cannot shrink faster than
+// 2^(spread_k) / D per step (the transition rows sum to one), so the steps' spreads are added up, and when
+// the bound says a row could have lost 2^-WORK_ROOM the rows are rescaled at once, ahead of schedule (decided per
+// wavefront): a row's largest entry never falls below 2^(WORK_BIAS-WORK_ROOM), and entries 2^-126 below it
+// are still normal numbers.  A state is therefore lost only where a step-by-step recursion in single
+// precision loses it as well.
 template <class S, int D, bool STORE_E, bool FULL>
-HMM_DEV void chunk_aggregate_impl(float* row, int n, bool first, const float (&Am)[D * D], float (&P)[D * D],
-                                  double& msum) {
+HMM_DEV void chunk_aggregate_impl(float* row, int n, bool first, const float (&Am)[D * D], Agg<S, D>& P) {
     using C = SmallCfg<D>;
-    mat_identity<S, D>(P);
-    float ms = 0.0f;   // sum of at most L maxima: float is ample, the caller accumulates in double
+    agg_identity<S, D>(P);
+    float csum = 0.0f;   // whole bits of at most L steps: exact in float unless the log-likelihoods are astronomically large
+    float room = 0.0f;   // SumProd: bound on the binary logarithm of what a row has lost since its last rescaling
+    constexpr float PER_STEP = (D <= 2) ? 1.0f : (D <= 4) ? 2.0f : 3.0f;   // log2 D
 #pragma unroll
     for (int k = 0; k < C::L; ++k) {
         if (FULL || k < n) {
-            float ev[D];
+            float ev[D], bits, spread;
             lds_read_vec<D>(row + k * D, ev);
-            const float m = emission<S, D>(ev);
-            if constexpr (STORE_E) {
-                lds_write_vec<D>(row + k * D, ev);
-                ms += m;
-            }
+            emission<S, D>(ev, bits, spread);
+            if constexpr (STORE_E) lds_write_vec<D>(row + k * D, ev);
+            csum += bits;
             if (k == 0) {
                 // P is still the neutral element: P (op) psi = psi, no product needed
+                float es[D];
+#pragma unroll
+                for (int j = 0; j < D; ++j) es[j] = S::is_max_plus ? ev[j] : ldexpf(ev[j], WORK_BIAS);
 #pragma unroll
                 for (int i = 0; i < D; ++i)
 #pragma unroll
                     for (int j = 0; j < D; ++j) {
                         const float a = first ? ((i == j) ? S::one() : S::zero()) : Am[i * D + j];
-                        P[i * D + j] = S::times(a, ev[j]);
+                        P.m[i * D + j] = S::times(a, es[j]);
                     }
+                if constexpr (!S::is_max_plus) {
+#pragma unroll
+                    for (int i = 0; i < D; ++i) P.ex[i] = -WORK_BIAS;
+                    room = spread - PER_STEP;
+                }
             } else {
-                absorb<S, D>(P, Am, ev, false);
+                if constexpr (!S::is_max_plus) {
+                    room += spread - PER_STEP;
+                    if (wave_any(room < -(float)WORK_ROOM)) {
+                        agg_renorm<S, D, WORK_BIAS>(P);
+                        room = spread - PER_STEP;
+                    }
+                }
+                absorb<S, D>(P.m, Am, ev);
             }
-            if ((k & 3) == 3) renorm<S, D * D>(P);
+            if ((k & 3) == 3) {
+                agg_renorm<S, D, WORK_BIAS>(P);
+                room = 0.0f;
+            }
         }
     }
-    msum = (double)ms;
+    agg_renorm<S, D, ROW_BIAS>(P);
+    P.c += (double)csum;
 }
 
 template <class S, int D, bool STORE_E>
-HMM_DEV void chunk_aggregate(float* row, int n, bool first, const float (&Am)[D * D], float (&P)[D * D],
-                             double& msum) {
-    if (n == SmallCfg<D>::L) chunk_aggregate_impl<S, D, STORE_E, true>(row, n, first, Am, P, msum);
-    else chunk_aggregate_impl<S, D, STORE_E, false>(row, n, first, Am, P, msum);
+HMM_DEV void chunk_aggregate(float* row, int n, bool first, const float (&Am)[D * D], Agg<S, D>& P) {
+    if (n == SmallCfg<D>::L) chunk_aggregate_impl<S, D, STORE_E, true>(row, n, first, Am, P);
+    else chunk_aggregate_impl<S, D, STORE_E, false>(row, n, first, Am, P);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Moving aggregates between lanes and through LDS
+template <int CTRL, int ROW_MASK>
+HMM_DEV float dpp_move(float neutral, float src) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(neutral), __float_as_int(src), CTRL, ROW_MASK,
+                                                      0xF, false));
+}
+template <int CTRL, int ROW_MASK>
+HMM_DEV int dpp_move_int(int neutral, int src) {
+    return __builtin_amdgcn_update_dpp(neutral, src, CTRL, ROW_MASK, 0xF, false);
+}
+template <int CTRL, int ROW_MASK>
+HMM_DEV double dpp_move_double(double src) {   // neutral 0.0
+    const long long b = __double_as_longlong(src);
+    const int lo = __builtin_amdgcn_update_dpp(0, (int)b, CTRL, ROW_MASK, 0xF, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, (int)(b >> 32), CTRL, ROW_MASK, 0xF, false);
+    return __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
+}
+
+// The aggregate of the lane that the DPP control selects; lanes without a source get the neutral element.
+template <class S, int D, int CTRL, int ROW_MASK, bool TRACK_C>
+HMM_DEV void agg_dpp(const Agg<S, D>& Q, Agg<S, D>& N) {
+#pragma unroll
+    for (int i = 0; i < D; ++i)
+#pragma unroll
+        for (int j = 0; j < D; ++j)
+            N.m[i * D + j] = dpp_move<CTRL, ROW_MASK>((i == j) ? S::one() : S::zero(), Q.m[i * D + j]);
+    if constexpr (!S::is_max_plus) {
+#pragma unroll
+        for (int i = 0; i < D; ++i) N.ex[i] = dpp_move_int<CTRL, ROW_MASK>(0, Q.ex[i]);
+    }
+    if constexpr (TRACK_C) N.c = dpp_move_double<CTRL, ROW_MASK>(Q.c);
+    else N.c = 0.0;
+}
+
+// The aggregate held by lane `src` of the wavefront (any permutation).
+template <class S, int D, bool TRACK_C>
+HMM_DEV void agg_shfl(const Agg<S, D>& Q, int src, Agg<S, D>& N) {
+#pragma unroll
+    for (int e = 0; e < D * D; ++e) N.m[e] = __shfl(Q.m[e], src, 64);
+    if constexpr (!S::is_max_plus) {
+#pragma unroll
+        for (int i = 0; i < D; ++i) N.ex[i] = __shfl(Q.ex[i], src, 64);
+    }
+    if constexpr (TRACK_C) N.c = __shfl(Q.c, src, 64);
+    else N.c = 0.0;
+}
+
+// LDS / memory image of an aggregate: D*D floats, D exponents, the common scale as a double.
+template <int D>
+struct AggImage {
+    static constexpr int WORDS = D * D + D + 2;   // D (D + 1) is even: the double is 8-byte aligned
+};
+
+template <class S, int D>
+HMM_DEV void agg_store(float* p, const Agg<S, D>& Q) {
+#pragma unroll
+    for (int e = 0; e < D * D; ++e) p[e] = Q.m[e];
+#pragma unroll
+    for (int i = 0; i < D; ++i) reinterpret_cast<int*>(p)[D * D + i] = S::is_max_plus ? 0 : Q.ex[i];
+    *reinterpret_cast<double*>(p + D * D + D) = Q.c;
+}
+
+template <class S, int D>
+HMM_DEV void agg_load(const float* p, Agg<S, D>& Q) {
+#pragma unroll
+    for (int e = 0; e < D * D; ++e) Q.m[e] = p[e];
+#pragma unroll
+    for (int i = 0; i < D; ++i) Q.ex[i] = reinterpret_cast<const int*>(p)[D * D + i];
+    Q.c = *reinterpret_cast<const double*>(p + D * D + D);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -270,93 +367,76 @@ HMM_DEV void chunk_aggregate(float* row, int n, bool first, const float (&Am)[D 
 // four shifts inside each row of 16 lanes, then the last lane of a row broadcast to the next
 // row(s).  A lane that has no source at some level combines with the operator's neutral
 // element instead, so no lane needs to be predicated.
-template <int CTRL, int ROW_MASK>
-HMM_DEV float dpp_move(float neutral, float src) {
-    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(neutral), __float_as_int(src), CTRL, ROW_MASK,
-                                                      0xF, false));
-}
-
-template <class S, int D, bool SWAP, int CTRL, int ROW_MASK>
-HMM_DEV void wave_scan_level(float (&Q)[D * D]) {
-    float Pn[D * D], Z[D * D];
-#pragma unroll
-    for (int i = 0; i < D; ++i)
-#pragma unroll
-        for (int j = 0; j < D; ++j)
-            Pn[i * D + j] = dpp_move<CTRL, ROW_MASK>((i == j) ? S::one() : S::zero(), Q[i * D + j]);
-    if constexpr (SWAP) mat_mul<S, D>(Q, Pn, Z);
-    else mat_mul<S, D>(Pn, Q, Z);
-    renorm<S, D * D>(Z);
-#pragma unroll
-    for (int e = 0; e < D * D; ++e) Q[e] = Z[e];
+template <class S, int D, bool SWAP, int CTRL, int ROW_MASK, bool TRACK_C>
+HMM_DEV void wave_scan_level(Agg<S, D>& Q) {
+    Agg<S, D> N, Z;
+    agg_dpp<S, D, CTRL, ROW_MASK, TRACK_C>(Q, N);
+    if constexpr (SWAP) agg_mul<S, D, TRACK_C>(Q, N, Z);
+    else agg_mul<S, D, TRACK_C>(N, Q, Z);
+    Q = Z;
 }
 
 // Inclusive scan towards higher lanes.  SWAP = false: Q_t <- P_0 (op) ... (op) P_t;
 // SWAP = true: Q_t <- P_t (op) ... (op) P_0 (the operator's arguments exchanged).
-template <class S, int D, bool SWAP>
-HMM_DEV void wave_scan_up(float (&Q)[D * D]) {
-    wave_scan_level<S, D, SWAP, 0x111, 0xF>(Q);   // row_shr:1
-    wave_scan_level<S, D, SWAP, 0x112, 0xF>(Q);   // row_shr:2
-    wave_scan_level<S, D, SWAP, 0x114, 0xF>(Q);   // row_shr:4
-    wave_scan_level<S, D, SWAP, 0x118, 0xF>(Q);   // row_shr:8
-    wave_scan_level<S, D, SWAP, 0x142, 0xA>(Q);   // row_bcast:15 into rows 1 and 3
-    wave_scan_level<S, D, SWAP, 0x143, 0xC>(Q);   // row_bcast:31 into rows 2 and 3
+template <class S, int D, bool SWAP, bool TRACK_C>
+HMM_DEV void wave_scan_up(Agg<S, D>& Q) {
+    wave_scan_level<S, D, SWAP, 0x111, 0xF, TRACK_C>(Q);   // row_shr:1
+    wave_scan_level<S, D, SWAP, 0x112, 0xF, TRACK_C>(Q);   // row_shr:2
+    wave_scan_level<S, D, SWAP, 0x114, 0xF, TRACK_C>(Q);   // row_shr:4
+    wave_scan_level<S, D, SWAP, 0x118, 0xF, TRACK_C>(Q);   // row_shr:8
+    wave_scan_level<S, D, SWAP, 0x142, 0xA, TRACK_C>(Q);   // row_bcast:15 into rows 1 and 3
+    wave_scan_level<S, D, SWAP, 0x143, 0xC, TRACK_C>(Q);   // row_bcast:31 into rows 2 and 3
 }
 
 template <class S, int D>
-HMM_DEV void wave_scan_prefix(float (&Q)[D * D]) {   // Q_t <- P_0 (op) ... (op) P_t
-    wave_scan_up<S, D, false>(Q);
+HMM_DEV void wave_scan_prefix(Agg<S, D>& Q) {   // Q_t <- P_0 (op) ... (op) P_t, scale included
+    wave_scan_up<S, D, false, true>(Q);
 }
 
 // R_t <- P_t (op) ... (op) P_63: the prefix scan with exchanged arguments on mirrored lanes
-// (the reversal recipe of Sec. III-B applied across the wavefront).
+// (the reversal recipe of Sec. III-B applied across the wavefront).  The common scale is not
+// tracked: only backward potentials come out of it, and those are scale-free.
 template <class S, int D>
-HMM_DEV void wave_scan_suffix(float (&R)[D * D]) {
+HMM_DEV void wave_scan_suffix(Agg<S, D>& R) {
     const int mirror = 63 - (int)(threadIdx.x & 63);
-#pragma unroll
-    for (int e = 0; e < D * D; ++e) R[e] = __shfl(R[e], mirror, 64);
-    wave_scan_up<S, D, true>(R);
-#pragma unroll
-    for (int e = 0; e < D * D; ++e) R[e] = __shfl(R[e], mirror, 64);
+    Agg<S, D> T;
+    agg_shfl<S, D, false>(R, mirror, T);
+    wave_scan_up<S, D, true, false>(T);
+    agg_shfl<S, D, false>(T, mirror, R);
 }
 
-// Inclusive prefix scan inside each wave; the wave totals go to wagg[NW][D*D] in LDS.
+// Inclusive prefix scan inside each wave; the wave totals go to wagg[NW][AggImage::WORDS] in LDS.
 // The caller must __syncthreads() before reading wagg.
 template <class S, int D>
-HMM_DEV void block_prefix(const float (&P)[D * D], float (&Q)[D * D], float* wagg) {
+HMM_DEV void block_prefix(const Agg<S, D>& P, Agg<S, D>& Q, float* wagg) {
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
-#pragma unroll
-    for (int e = 0; e < D * D; ++e) Q[e] = P[e];
+    Q = P;
     wave_scan_prefix<S, D>(Q);
-    if (lane == 63) {
-#pragma unroll
-        for (int e = 0; e < D * D; ++e) wagg[wave * D * D + e] = Q[e];
-    }
+    if (lane == 63) agg_store<S, D>(wagg + wave * AggImage<D>::WORDS, Q);
 }
 
 // Workgroup aggregate W_0 (op) ... (op) W_{NW-1} from the wave totals (any single lane may call).
 template <class S, int D>
-HMM_DEV void block_total(const float* wagg, float (&X)[D * D]) {
+HMM_DEV void block_total(const float* wagg, Agg<S, D>& X) {
     using C = SmallCfg<D>;
-#pragma unroll
-    for (int e = 0; e < D * D; ++e) X[e] = wagg[e];
+    agg_load<S, D>(wagg, X);
 #pragma unroll
     for (int w = 1; w < C::NW; ++w) {
-        float Y[D * D], Z[D * D];
-#pragma unroll
-        for (int e = 0; e < D * D; ++e) Y[e] = wagg[w * D * D + e];
-        mat_mul<S, D>(X, Y, Z);
-        renorm<S, D * D>(Z);
-#pragma unroll
-        for (int e = 0; e < D * D; ++e) X[e] = Z[e];
+        Agg<S, D> Y, Z;
+        agg_load<S, D>(wagg + w * AggImage<D>::WORDS, Y);
+        agg_mul<S, D, true>(X, Y, Z);
+        X = Z;
     }
 }
+
+// Scale-free vectors: forward potentials are kept with their sum in [0.5, 1) (SumProd) / largest entry 0
+// (MaxPlus), backward potentials with their largest entry in [0.5, 1) / at 0.
 
 // fin = cin_f (op) P_0 (op) ... (op) P_{t-1}: the forward potential just before lane t's chunk,
 // from the lane's inclusive wave prefix Q and the wave totals.
 template <class S, int D>
-HMM_DEV void carry_forward(const float (&Q)[D * D], const float* wagg, const float (&cin_f)[D], float (&fin)[D]) {
+HMM_DEV void carry_forward(const Agg<S, D>& Q, const float* wagg, const float (&cin_f)[D], float (&fin)[D]) {
     using C = SmallCfg<D>;
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -366,27 +446,29 @@ HMM_DEV void carry_forward(const float (&Q)[D * D], const float* wagg, const flo
 #pragma unroll
     for (int w = 0; w < C::NW - 1; ++w) {
         if (w < wave) {
-            float Wm[D * D], r[D];
-#pragma unroll
-            for (int e = 0; e < D * D; ++e) Wm[e] = wagg[w * D * D + e];
-            vec_mat<S, D>(fw, Wm, r);
-            renorm<S, D>(r);
+            Agg<S, D> Wm;
+            float r[D];
+            agg_load<S, D>(wagg + w * AggImage<D>::WORDS, Wm);
+            vec_agg<S, D>(fw, Wm, r);
 #pragma unroll
             for (int j = 0; j < D; ++j) fw[j] = r[j];
         }
     }
-    float Qp[D * D], r[D];
-#pragma unroll
-    for (int e = 0; e < D * D; ++e) Qp[e] = __shfl_up(Q[e], 1, 64);
-    vec_mat<S, D>(fw, Qp, r);
+    Agg<S, D> Qp;
+    float r[D];
+    agg_shfl<S, D, false>(Q, (lane + 63) & 63, Qp);   // the lane below (lane 0 does not use it)
+    vec_agg<S, D>(fw, Qp, r);
 #pragma unroll
     for (int j = 0; j < D; ++j) fin[j] = (lane == 0) ? fw[j] : r[j];
 }
 
-// bout = P_{t+1} (op) ... (op) P_{NT-1} (op) cin_b: the backward potential at the last step of
-// lane t's chunk, from the lane's inclusive wave suffix R and the wave totals.
+// The backward potential at the last step of lane t's chunk, P_{t+1} (op) ... (op) P_{NT-1} (op) cin_b, from the
+// lane's inclusive wave suffix R and the wave totals, as a vector of mantissas with one exponent per entry
+// (SumProd; EX_NONE marks a zero) -- the chunk's backward recursion picks the common scale itself, see
+// backward_plain -- or shifted to largest entry 0 (MaxPlus; the exponents are not used).
 template <class S, int D>
-HMM_DEV void carry_backward(const float (&R)[D * D], const float* wagg, const float (&cin_b)[D], float (&bout)[D]) {
+HMM_DEV void carry_backward(const Agg<S, D>& R, const float* wagg, const float (&cin_b)[D], float (&bout)[D],
+                            int (&bex)[D]) {
     using C = SmallCfg<D>;
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -396,66 +478,98 @@ HMM_DEV void carry_backward(const float (&R)[D * D], const float* wagg, const fl
 #pragma unroll
     for (int w = C::NW - 1; w > 0; --w) {
         if (w > wave) {
-            float Wm[D * D], r[D];
-#pragma unroll
-            for (int e = 0; e < D * D; ++e) Wm[e] = wagg[w * D * D + e];
-            mat_vec<S, D>(Wm, bw, r);
-            renorm<S, D>(r);
+            Agg<S, D> Wm;
+            float r[D];
+            agg_load<S, D>(wagg + w * AggImage<D>::WORDS, Wm);
+            agg_vec<S, D>(Wm, bw, r);
 #pragma unroll
             for (int j = 0; j < D; ++j) bw[j] = r[j];
         }
     }
-    float Rn[D * D], r[D];
+    Agg<S, D> Rn;
+    agg_shfl<S, D, false>(R, (lane + 1) & 63, Rn);   // the lane above (lane 63 does not use it)
+    if constexpr (S::is_max_plus) {
+        float r[D];
+        agg_vec<S, D>(Rn, bw, r);
 #pragma unroll
-    for (int e = 0; e < D * D; ++e) Rn[e] = __shfl_down(R[e], 1, 64);
-    mat_vec<S, D>(Rn, bw, r);
+        for (int j = 0; j < D; ++j) {
+            bout[j] = (lane == 63) ? bw[j] : r[j];
+            bex[j] = 0;
+        }
+    } else {
+        float r[D];
+        int er[D];
+        agg_vec_raw<D>(Rn, bw, r, er);
 #pragma unroll
-    for (int j = 0; j < D; ++j) bout[j] = (lane == 63) ? bw[j] : r[j];
+        for (int j = 0; j < D; ++j) {
+            bout[j] = (lane == 63) ? bw[j] : r[j];
+            bex[j] = (lane == 63) ? ((bw[j] > 0.0f) ? 0 : EX_NONE) : er[j];
+        }
+    }
 }
 
-// Both carries for every lane of the workgroup (contains one __syncthreads()).
+// Both carries for every lane of the workgroup (contains one __syncthreads()); the backward one in the raw
+// form of carry_backward.
 template <class S, int D, bool BWD>
-HMM_DEV void block_exchange(const float (&P)[D * D], const float (&cin_f)[D], const float (&cin_b)[D],
-                            float (&fin)[D], float (&bout)[D], float* wagg) {
-    float Q[D * D];
+HMM_DEV void block_exchange(const Agg<S, D>& P, const float (&cin_f)[D], const float (&cin_b)[D],
+                            float (&fin)[D], float (&bout)[D], int (&bex)[D], float* wagg) {
+    Agg<S, D> Q;
     block_prefix<S, D>(P, Q, wagg);
     __syncthreads();
     carry_forward<S, D>(Q, wagg, cin_f, fin);
     if constexpr (BWD) {
-        float R[D * D];
-#pragma unroll
-        for (int e = 0; e < D * D; ++e) R[e] = P[e];
+        Agg<S, D> R = P;
         wave_scan_suffix<S, D>(R);
-        carry_backward<S, D>(R, wagg, cin_b, bout);
+        carry_backward<S, D>(R, wagg, cin_b, bout, bex);
     }
 }
 
-// Ordered sum of one double per lane over the workgroup; result valid in thread 0.
-HMM_DEV double block_sum(double v, double* scratch /* NW doubles */) {
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) v += __shfl_down(v, d, 64);
-    if ((threadIdx.x & 63) == 0) scratch[threadIdx.x >> 6] = v;
-    __syncthreads();
-    double s = 0.0;
-    if (threadIdx.x == 0) {
-        for (int w = 0; w < (int)(blockDim.x >> 6); ++w) s += scratch[w];
+// The evidence of a whole sequence from its start vector and the aggregate of all its elements:
+// log of sum_j (start (op) M)(j) for SumProd (log Z of Sec. II), max_j for MaxPlus (Corollary 1).
+// `start` is the prior in the operator's domain, taken exactly as given.
+template <class S, int D>
+HMM_DEV double sequence_evidence(const float (&start)[D], const Agg<S, D>& M) {
+    float r[D];
+    const double sc = vec_agg<S, D>(start, M, r);
+    if constexpr (S::is_max_plus) {
+        return M.c + sc;   // r has its largest entry at 0
+    } else {
+        return 0.6931471805599453 * (M.c + sc) + log((double)sum_of(r));
     }
-    return s;
+}
+
+// The same from the forward potential v entering a span (with the scale vs it has been stripped of:
+// bits for SumProd, an offset for MaxPlus), the span's aggregate M, and the backward potential b after it
+// (scale bs): log of v M b.
+template <class S, int D>
+HMM_DEV double span_evidence(const float (&v)[D], double vs, const Agg<S, D>& M, const float (&b)[D], double bs) {
+    float r[D];
+    const double sc = vec_agg<S, D>(v, M, r);
+    if constexpr (S::is_max_plus) {
+        float best = r[0] + b[0];
+#pragma unroll
+        for (int j = 1; j < D; ++j) best = fmaxf(best, r[j] + b[j]);
+        return vs + M.c + sc + bs + (double)best;
+    } else {
+        float dot = r[0] * b[0];
+#pragma unroll
+        for (int j = 1; j < D; ++j) dot = fmaf(r[j], b[j], dot);
+        return 0.6931471805599453 * (vs + M.c + sc + bs) + log((double)dot);
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
 // Sum-product work inside a lane's chunk
 
 // Forward: a_{0:k} for the lane's steps, kept in registers as F (Theorem 1).  f enters as the
-// carry (sum one, or the prior for the sequence's first chunk) and every step is rescaled by an
-// exact power of two; returns the chunk-local log evidence log p(y_chunk | y_before).
+// carry (or the prior for the sequence's first chunk) and every step is rescaled by an exact power
+// of two, to a sum near 2^VEC_BIAS: states down to 2^-(126+VEC_BIAS) of the step's total stay normal
+// numbers, and the backward potential, kept at the same height, may weigh them up again.
 template <int D, bool WRITE_FILT, bool FULL>
-HMM_DEV double sp_forward_impl(const float* row, int n, bool first, const float (&Am)[D * D], float (&f)[D],
-                               float (&F)[SmallCfg<D>::L][D], double msum, float* __restrict__ filt_dst) {
+HMM_DEV void sp_forward_impl(const float* row, int n, bool first, const float (&Am)[D * D], float (&f)[D],
+                             float (&F)[SmallCfg<D>::L][D], float* __restrict__ filt_dst) {
     using C = SmallCfg<D>;
     using S = SumProd;
-    int exsum = 0;
-    float s_last = 1.0f;
 #pragma unroll
     for (int k = 0; k < C::L; ++k) {
         if (FULL || k < n) {
@@ -470,32 +584,41 @@ HMM_DEV double sp_forward_impl(const float* row, int n, bool first, const float 
                 for (int j = 0; j < D; ++j) g[j] *= ev[j];
             }
             const float s = sum_of(g);
-            const int ex = __builtin_amdgcn_frexp_expf(s);
+            const int ex = __builtin_amdgcn_frexp_expf(s) - VEC_BIAS;   // the sum comes to lie in [2^(VEC_BIAS-1), 2^VEC_BIAS)
 #pragma unroll
-            for (int j = 0; j < D; ++j) f[j] = ldexpf(g[j], -ex);
-            exsum += ex;
-            s_last = ldexpf(s, -ex);
-#pragma unroll
-            for (int j = 0; j < D; ++j) F[k][j] = f[j];
+            for (int j = 0; j < D; ++j) F[k][j] = f[j] = ldexpf(g[j], -ex);
             if constexpr (WRITE_FILT) {
-                const float inv = __builtin_amdgcn_rcpf(s_last);
+                const float inv = __builtin_amdgcn_rcpf(ldexpf(s, -ex));
 #pragma unroll
                 for (int j = 0; j < D; ++j) filt_dst[k * D + j] = f[j] * inv;
             }
         }
     }
-    if (!FULL && n == 0) return 0.0;
-    return msum + 0.6931471805599453 * (double)exsum + log((double)s_last);
+}
+
+// Common scale of a backward potential given as mantissas b with one exponent per entry (bex; EX_NONE marks
+// a zero): largest entry into [2^(VEC_BIAS-1), 2^VEC_BIAS).
+template <int D>
+HMM_DEV void backward_plain(float (&b)[D], const int (&bex)[D]) {
+    int e[D], ref = EX_NONE;
+#pragma unroll
+    for (int i = 0; i < D; ++i) {
+        e[i] = (bex[i] != EX_NONE) ? __builtin_amdgcn_frexp_expf(b[i]) + bex[i] : EX_NONE;
+        ref = e[i] > ref ? e[i] : ref;
+    }
+#pragma unroll
+    for (int i = 0; i < D; ++i) b[i] = (bex[i] != EX_NONE) ? ldexpf(b[i], max_of_int(bex[i] - ref + VEC_BIAS, -400)) : 0.0f;
 }
 
 // Backward: a_{k:T+1} (Theorem 2) and the marginal f_k b_k / Z_k, written over the emission
-// factors in LDS.  b enters as the backward potential at the chunk's last step.
+// factors in LDS.  b enters as the backward potential at the chunk's last step in the raw form of
+// carry_backward; every step rescales it to a largest entry near 2^VEC_BIAS.
 template <int D, bool FULL>
-HMM_DEV void sp_backward_impl(float* row, int n, const float (&Am)[D * D], float (&b)[D],
+HMM_DEV void sp_backward_impl(float* row, int n, const float (&Am)[D * D], float (&b)[D], const int (&bex)[D],
                               const float (&F)[SmallCfg<D>::L][D]) {
     using C = SmallCfg<D>;
     using S = SumProd;
-    renorm<S, D>(b);
+    backward_plain<D>(b, bex);
 #pragma unroll
     for (int k = C::L - 1; k >= 0; --k) {
         if (FULL || k < n) {
@@ -512,9 +635,9 @@ HMM_DEV void sp_backward_impl(float* row, int n, const float (&Am)[D * D], float
 #pragma unroll
                 for (int j = 0; j < D; ++j) t[j] = ev[j] * b[j];
                 mat_vec<S, D>(Am, t, r);
-                renorm<S, D>(r);
+                const int ex = __builtin_amdgcn_frexp_expf(max_of(r)) - VEC_BIAS;
 #pragma unroll
-                for (int j = 0; j < D; ++j) b[j] = r[j];
+                for (int j = 0; j < D; ++j) b[j] = ldexpf(r[j], -ex);
             }
         }
     }
@@ -523,15 +646,14 @@ HMM_DEV void sp_backward_impl(float* row, int n, const float (&Am)[D * D], float
 // ---------------------------------------------------------------------------------------------
 // Max-plus work inside a lane's chunk: V_k and the back-pointers u_{k-1}(x_k) of Sec. IV-A.
 // v enters as the carry (max 0, or the log prior for the first chunk) and leaves as V at the
-// chunk's last step with max 0; returns the sum of the offsets removed on the way.
+// chunk's last step with max 0.
 template <int D, bool FULL>
-HMM_DEV double mp_forward_impl(const float* row, int n, bool first, const float (&Am)[D * D], float (&v)[D],
+HMM_DEV void mp_forward_impl(const float* row, int n, bool first, const float (&Am)[D * D], float (&v)[D],
                                uint32_t (&bp)[SmallCfg<D>::W]) {
     using C = SmallCfg<D>;
     using S = MaxPlus;
 #pragma unroll
     for (int w = 0; w < C::W; ++w) bp[w] = 0u;
-    double osum = 0.0;
 #pragma unroll
     for (int k = 0; k < C::L; ++k) {
         if (FULL || k < n) {
@@ -561,26 +683,23 @@ HMM_DEV double mp_forward_impl(const float* row, int n, bool first, const float 
                 }
             }
             bp[k / C::SPW] |= word << ((k % C::SPW) * C::STEP_BITS);
-            osum += (double)renorm<S, D>(g);
+            renorm<S, D>(g);
 #pragma unroll
             for (int j = 0; j < D; ++j) v[j] = g[j];
         }
     }
-    return osum;
 }
 
 // ---------------------------------------------------------------------------------------------
 // Max-product forward/backward work inside a lane's chunk (the lemma of Sec. IV-C on logarithms).
 
 // Forward: psi~^f_k for the lane's steps, kept in registers as F, each step shifted to max 0.
-// v enters as the carry (max 0, or the log prior for the sequence's first chunk); returns the sum
-// of the shifts, i.e. the chunk-local growth of the log of the best joint weight.
+// v enters as the carry (max 0, or the log prior for the sequence's first chunk).
 template <int D, bool FULL>
-HMM_DEV double mpv_forward_impl(const float* row, int n, bool first, const float (&Am)[D * D], float (&v)[D],
+HMM_DEV void mpv_forward_impl(const float* row, int n, bool first, const float (&Am)[D * D], float (&v)[D],
                                 float (&F)[SmallCfg<D>::L][D]) {
     using C = SmallCfg<D>;
     using S = MaxPlus;
-    double osum = 0.0;
 #pragma unroll
     for (int k = 0; k < C::L; ++k) {
         if (FULL || k < n) {
@@ -594,12 +713,11 @@ HMM_DEV double mpv_forward_impl(const float* row, int n, bool first, const float
 #pragma unroll
                 for (int j = 0; j < D; ++j) g[j] += lk[j];
             }
-            osum += (double)renorm<S, D>(g);
+            renorm<S, D>(g);
 #pragma unroll
             for (int j = 0; j < D; ++j) F[k][j] = v[j] = g[j];
         }
     }
-    return (!FULL && n == 0) ? 0.0 : osum;
 }
 
 // Backward: psi~^b_k and the max-marginal log psi~^f_k + log psi~^b_k (Theorem 4), shifted so that its
@@ -855,6 +973,7 @@ struct PackCoord {
     int n;       // valid steps of the lane's chunk
     bool first;  // the chunk starts its sequence
     bool last;   // the chunk holds its sequence's last step
+    bool live;   // the lane belongs to a sequence of the batch
 };
 
 template <int D>
@@ -872,6 +991,7 @@ HMM_DEV PackCoord pack_coord(long long T, int batch, int lcpl) {
     p.n = live ? (int)(rem < 0 ? 0 : rem > C::L ? C::L : rem) : 0;
     p.first = p.n > 0 && p.c == 0;
     p.last = p.n > 0 && rem <= C::L;
+    p.live = live;
     return p;
 }
 
@@ -1014,75 +1134,77 @@ HMM_DEV void store_path_packed(int32_t* __restrict__ dst, int nsteps, int T, int
 }
 
 // One level of the scan towards higher lanes in which a lane takes its partner only if `take`.
-template <class S, int D, bool SWAP, int CTRL, int ROW_MASK>
-HMM_DEV void wave_scan_level_if(float (&Q)[D * D], bool take) {
-    float Pn[D * D], Z[D * D];
+template <class S, int D, bool SWAP, int CTRL, int ROW_MASK, bool TRACK_C>
+HMM_DEV void wave_scan_level_if(Agg<S, D>& Q, bool take) {
+    Agg<S, D> N, I, Z;
+    agg_dpp<S, D, CTRL, ROW_MASK, TRACK_C>(Q, N);
+    agg_identity<S, D>(I);
 #pragma unroll
-    for (int i = 0; i < D; ++i)
+    for (int e = 0; e < D * D; ++e) N.m[e] = take ? N.m[e] : I.m[e];
 #pragma unroll
-        for (int j = 0; j < D; ++j) {
-            const float id = (i == j) ? S::one() : S::zero();
-            const float m = dpp_move<CTRL, ROW_MASK>(id, Q[i * D + j]);
-            Pn[i * D + j] = take ? m : id;
-        }
-    if constexpr (SWAP) mat_mul<S, D>(Q, Pn, Z);
-    else mat_mul<S, D>(Pn, Q, Z);
-    renorm<S, D * D>(Z);
-#pragma unroll
-    for (int e = 0; e < D * D; ++e) Q[e] = Z[e];
+    for (int i = 0; i < D; ++i) N.ex[i] = take ? N.ex[i] : 0;
+    N.c = take ? N.c : 0.0;
+    if constexpr (SWAP) agg_mul<S, D, TRACK_C>(Q, N, Z);
+    else agg_mul<S, D, TRACK_C>(N, Q, Z);
+    Q = Z;
 }
 
 // Inclusive scan towards higher lanes inside every aligned group of 2^lcpl lanes.
-template <class S, int D, bool SWAP>
-HMM_DEV void group_scan_up(float (&Q)[D * D], int lcpl) {
+template <class S, int D, bool SWAP, bool TRACK_C>
+HMM_DEV void group_scan_up(Agg<S, D>& Q, int lcpl) {
     const int pos = (int)(threadIdx.x & 63) & ((1 << lcpl) - 1);
-    if (lcpl > 0) wave_scan_level_if<S, D, SWAP, 0x111, 0xF>(Q, pos >= 1);   // row_shr:1
-    if (lcpl > 1) wave_scan_level_if<S, D, SWAP, 0x112, 0xF>(Q, pos >= 2);   // row_shr:2
-    if (lcpl > 2) wave_scan_level_if<S, D, SWAP, 0x114, 0xF>(Q, pos >= 4);   // row_shr:4
-    if (lcpl > 3) wave_scan_level_if<S, D, SWAP, 0x118, 0xF>(Q, pos >= 8);   // row_shr:8
-    if (lcpl > 4) wave_scan_level<S, D, SWAP, 0x142, 0xA>(Q);               // row_bcast:15 into rows 1 and 3
-    if (lcpl > 5) wave_scan_level<S, D, SWAP, 0x143, 0xC>(Q);               // row_bcast:31 into rows 2 and 3
+    if (lcpl > 0) wave_scan_level_if<S, D, SWAP, 0x111, 0xF, TRACK_C>(Q, pos >= 1);   // row_shr:1
+    if (lcpl > 1) wave_scan_level_if<S, D, SWAP, 0x112, 0xF, TRACK_C>(Q, pos >= 2);   // row_shr:2
+    if (lcpl > 2) wave_scan_level_if<S, D, SWAP, 0x114, 0xF, TRACK_C>(Q, pos >= 4);   // row_shr:4
+    if (lcpl > 3) wave_scan_level_if<S, D, SWAP, 0x118, 0xF, TRACK_C>(Q, pos >= 8);   // row_shr:8
+    if (lcpl > 4) wave_scan_level<S, D, SWAP, 0x142, 0xA, TRACK_C>(Q);               // row_bcast:15 into rows 1 and 3
+    if (lcpl > 5) wave_scan_level<S, D, SWAP, 0x143, 0xC, TRACK_C>(Q);               // row_bcast:31 into rows 2 and 3
 }
 
-// Forward potential entering every chunk and backward potential at every chunk's last step, for sequences
-// that start from `start` (the prior, in the operator's domain) and end inside their group.
+// Forward potential entering every chunk and backward potential at every chunk's last step (in the raw form of
+// carry_backward), for sequences that start from `start` (the prior, in the operator's domain) and end inside
+// their group; Q receives the lane's inclusive prefix inside its group (the group's last lane then holds the
+// whole sequence's aggregate).
 template <class S, int D, bool BWD>
-HMM_DEV void group_exchange(const float (&P)[D * D], int lcpl, int c, const float (&start)[D], float (&fin)[D],
-                            float (&bout)[D]) {
-    float Q[D * D], r[D];
-#pragma unroll
-    for (int e = 0; e < D * D; ++e) Q[e] = P[e];
-    group_scan_up<S, D, false>(Q, lcpl);
-    float Qp[D * D];
-#pragma unroll
-    for (int e = 0; e < D * D; ++e) Qp[e] = __shfl_up(Q[e], 1, 64);
-    vec_mat<S, D>(start, Qp, r);
+HMM_DEV void group_exchange(const Agg<S, D>& P, int lcpl, int c, const float (&start)[D], float (&fin)[D],
+                            float (&bout)[D], int (&bex)[D], Agg<S, D>& Q) {
+    float r[D];
+    Q = P;
+    group_scan_up<S, D, false, true>(Q, lcpl);
+    Agg<S, D> Qp;
+    agg_shfl<S, D, false>(Q, ((int)(threadIdx.x & 63) + 63) & 63, Qp);
+    vec_agg<S, D>(start, Qp, r);
 #pragma unroll
     for (int j = 0; j < D; ++j) fin[j] = (c == 0) ? start[j] : r[j];
     if constexpr (BWD) {
         const int mirror = 63 - (int)(threadIdx.x & 63);
-        float R[D * D], ones[D];
-#pragma unroll
-        for (int e = 0; e < D * D; ++e) R[e] = __shfl(P[e], mirror, 64);
-        group_scan_up<S, D, true>(R, lcpl);
-#pragma unroll
-        for (int e = 0; e < D * D; ++e) R[e] = __shfl(R[e], mirror, 64);
-        float Rn[D * D];
-#pragma unroll
-        for (int e = 0; e < D * D; ++e) Rn[e] = __shfl_down(R[e], 1, 64);
+        Agg<S, D> R, T;
+        float ones[D];
+        agg_shfl<S, D, false>(P, mirror, T);
+        group_scan_up<S, D, true, false>(T, lcpl);
+        agg_shfl<S, D, false>(T, mirror, R);
+        Agg<S, D> Rn;
+        agg_shfl<S, D, false>(R, ((int)(threadIdx.x & 63) + 1) & 63, Rn);
 #pragma unroll
         for (int j = 0; j < D; ++j) ones[j] = S::one();
-        mat_vec<S, D>(Rn, ones, r);
+        const bool last = c == (1 << lcpl) - 1;
+        if constexpr (S::is_max_plus) {
+            agg_vec<S, D>(Rn, ones, r);
 #pragma unroll
-        for (int j = 0; j < D; ++j) bout[j] = (c == (1 << lcpl) - 1) ? ones[j] : r[j];
+            for (int j = 0; j < D; ++j) {
+                bout[j] = last ? ones[j] : r[j];
+                bex[j] = 0;
+            }
+        } else {
+            int er[D];
+            agg_vec_raw<D>(Rn, ones, r, er);
+#pragma unroll
+            for (int j = 0; j < D; ++j) {
+                bout[j] = last ? 1.0f : r[j];
+                bex[j] = last ? 0 : er[j];
+            }
+        }
     }
-}
-
-// Sum of one double per lane over every aligned group of 2^lcpl lanes, in a fixed order; valid in the
-// group's first lane.
-HMM_DEV double group_sum(double v, int lcpl) {
-    for (int d = (1 << lcpl) >> 1; d >= 1; d >>= 1) v += __shfl_down(v, d, 64);
-    return v;
 }
 
 // excl = g_{c+1} o ... o g_{cpl-1} inside every aligned group of cpl = 2^lcpl lanes
@@ -1107,21 +1229,31 @@ HMM_DEV uint32_t group_map_suffix(uint32_t g, int lcpl, int c) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Exchange between co-resident workgroups (single-launch kernels) through self-validating words.
+// Exchange between co-resident workgroups (single-launch kernels) through tagged words.
 //
-// Before the kernel starts, every exchange slot in the workspace holds the all-ones bit pattern
-// (a NaN as float or double, an impossible back-pointer map).  A producer overwrites its slots
-// with agent-scope (write-through, cache-bypassing) stores of real values, none of which has
-// that pattern; consumers poll the slots with agent-scope (cache-bypassing) loads until no
-// sentinel is left.  Each 32/64-bit word is written by one store, so a consumer never sees a
-// torn word, and no ordering between different words is relied upon: there are no flags, no
-// fences (an agent-scope fence writes back / invalidates a whole L2 on this multi-die part) and
-// no read-modify-write atomics (a few hundred on one address serialise for microseconds).
-// The poll is bounded so that every wave terminates even if the workgroups were, against the
-// host's residency check, not all resident.
+// A published 32-bit value travels as one 64-bit word {value, tag}; the tag names the call.  The
+// exchange region of a workspace starts with a header {generation, poison, sequences finished}: every
+// workgroup of a call reads the generation g when it starts and uses the tag g + 1; when the call's
+// last sequence has been dealt with, one workgroup stores g + 1 as the new generation, so that
+// whatever a later call finds in the slots carries an older tag and is ignored -- nothing has to be
+// cleared between calls.  (The region must be zero before its first use: tags start at 1.)
+// A producer writes its slots with agent-scope (write-through) stores, consumers poll them with
+// agent-scope (cache-bypassing) loads until every word carries the call's tag.  Each word is written by
+// one store, so a consumer never sees a torn word, and no ordering between different words is relied
+// upon: no flags, no fences (an agent-scope fence writes back / invalidates a whole L2 on this
+// multi-die part), and read-modify-write atomics only once per sequence, after its results are out.
+// The poll is bounded so that every wave terminates even if the workgroups were, against the host's
+// residency check, not all resident; such a call marks the region as poisoned (its workgroups may
+// disagree about the generation), and every later call on it gives up at once, with NaN evidence,
+// until the region has been zeroed again.
 constexpr int SPIN_LIMIT = 1 << 20;
-constexpr uint32_t SENTINEL32 = 0xffffffffu;
-constexpr unsigned long long SENTINEL64 = 0xffffffffffffffffull;
+
+struct XchHeader {
+    uint32_t generation;   // tag of the last completed call
+    uint32_t poison;       // nonzero: a wait ran out in an earlier call, the region must be re-initialised
+    uint32_t seq_done;     // sequences of the running call whose results are out
+    uint32_t pad;
+};
 
 template <class T>
 HMM_DEV void coherent_store(T* p, T v) {
@@ -1132,10 +1264,12 @@ HMM_DEV T coherent_load(const T* p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// Bits of a float to publish: any NaN becomes the canonical quiet NaN, which is not the sentinel.
-HMM_DEV uint32_t publish_bits(float x) { return (x != x) ? 0x7fc00000u : __float_as_uint(x); }
-HMM_DEV unsigned long long publish_bits(double x) {
-    return (x != x) ? 0x7ff8000000000000ull : (unsigned long long)__double_as_longlong(x);
+HMM_DEV unsigned long long tagged(uint32_t value, uint32_t tag) {
+    return ((unsigned long long)tag << 32) | (unsigned long long)value;
+}
+HMM_DEV void publish_word(unsigned long long* slot, uint32_t value, uint32_t tag) { coherent_store(slot, tagged(value, tag)); }
+HMM_DEV void publish_word(unsigned long long* slot, float value, uint32_t tag) {
+    coherent_store(slot, tagged(__float_as_uint(value), tag));
 }
 
 }  // namespace hmm

@@ -3,10 +3,16 @@
 //
 // Two launch plans compute the same thing with the same per-lane arithmetic:
 //   * single-launch ("fused"): every tile is one co-resident workgroup; tile aggregates (and, for
-//     Viterbi, tile back-pointer maps) are exchanged through the workspace, so the
-//     log-likelihoods are read from HBM once and nothing but the outputs is written back;
+//     Viterbi, tile back-pointer maps) are exchanged through tagged words in the workspace, so the
+//     log-likelihoods are read from HBM once, nothing but the outputs is written back and a call is
+//     one kernel;
 //   * multi-launch: reduce -> carry -> apply (-> suffix -> path) kernels with no inter-workgroup
 //     waiting, for shapes with more tiles than the GPU can hold resident at once.
+// Sequences of at most 64 chunks are packed several to a workgroup and exchange nothing at all.
+//
+// The evidence outputs (log Z of Sec. II; the best joint log-weight of Corollary 1) are read off the
+// aggregate of the whole sequence, whose scale is tracked exactly (semiring.hpp), by one lane per
+// sequence; the per-step recursions carry no scale.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stdlib.h>
@@ -21,71 +27,122 @@
 
 namespace hmm {
 
-// Development aid, compiled out unless HMM_PHASE_STAMPS is defined: wall-clock stamps per workgroup.
-#ifdef HMM_PHASE_STAMPS
-__device__ unsigned long long g_stamps[1024 * 16];
-#define HMM_STAMP(i) do { if ((threadIdx.x & 63) == 0 && blockIdx.x < 256) g_stamps[(blockIdx.x * 4 + (threadIdx.x >> 6)) * 16 + (i)] = wall_clock64(); } while (0)
-#else
-#define HMM_STAMP(i) do { } while (0)
-#endif
+// The workgroup's aggregate W_0 (op) ... (op) W_{NW-1} from the wave totals in wagg, formed row by row:
+// lane i < D of the first wave owns row i of the running product (rows of a product depend on the left
+// factor's row only), so the chain costs D^2 multiply-adds per lane and step instead of whole matrix
+// products in one lane.  The result goes to `image` (LDS) and, if slots != nullptr, to the tile's tagged
+// exchange slots.  Call from the whole first wave; wagg must be visible (barrier before).
+template <class S, int D>
+HMM_DEV void tile_total_rows(const float* wagg, float* image, unsigned long long* slots, uint32_t tag) {
+    using C = SmallCfg<D>;
+    constexpr int W = AggImage<D>::WORDS;
+    const int lane = threadIdx.x & 63;
+    const int i = lane < D ? lane : 0;   // spare lanes shadow row 0 and never store
+    float x[D];
+#pragma unroll
+    for (int j = 0; j < D; ++j) x[j] = wagg[i * D + j];
+    int xe = reinterpret_cast<const int*>(wagg)[D * D + i];   // SumProd: the row's exponent
+    double ro = 0.0;                                            // MaxPlus: the row's own offset
+    double c = *reinterpret_cast<const double*>(wagg + D * D + D);
+#pragma unroll
+    for (int w = 1; w < C::NW; ++w) {
+        Agg<S, D> Wm;
+        float r[D];
+        agg_load<S, D>(wagg + w * W, Wm);
+        const double sc = vec_agg<S, D>(x, Wm, r);
+        if constexpr (S::is_max_plus) ro += sc;
+        else xe += (int)sc + (VEC_BIAS - ROW_BIAS);   // vec_agg leaves the row at the height of a vector: back to a row's
+        c += Wm.c;
+#pragma unroll
+        for (int j = 0; j < D; ++j) x[j] = S::is_max_plus ? r[j] : ldexpf(r[j], ROW_BIAS - VEC_BIAS);
+    }
+    if constexpr (S::is_max_plus) {
+        // one common offset per matrix: the largest row offset (rows that are entirely -inf report 0 and
+        // stay -inf whatever is added)
+        double top = __shfl(ro, 0, 64);
+#pragma unroll
+        for (int k = 1; k < D; ++k) {
+            const double o = __shfl(ro, k, 64);
+            top = o > top ? o : top;
+        }
+        const float d = (float)(ro - top);
+#pragma unroll
+        for (int j = 0; j < D; ++j) x[j] += d;
+        c += top;
+        xe = 0;
+    }
+    if (lane < D) {
+#pragma unroll
+        for (int j = 0; j < D; ++j) image[i * D + j] = x[j];
+        reinterpret_cast<int*>(image)[D * D + i] = xe;
+        if (lane == 0) *reinterpret_cast<double*>(image + D * D + D) = c;
+        if (slots != nullptr) {
+#pragma unroll
+            for (int j = 0; j < D; ++j) publish_word(slots + i * D + j, x[j], tag);
+            publish_word(slots + D * D + i, (uint32_t)xe, tag);
+            if (lane == 0) {
+                const unsigned long long cb = (unsigned long long)__double_as_longlong(c);
+                publish_word(slots + D * D + D, (uint32_t)cb, tag);
+                publish_word(slots + D * D + D + 1, (uint32_t)(cb >> 32), tag);
+            }
+        }
+    }
+}
 
 // =============================================================================================
 // Multi-launch plan
 // =============================================================================================
 
-// Kernel 1 (both operators): tile aggregates
+// Kernel 1 (both operators): tile aggregates, as AggImage records
 template <class S, int D>
 __global__ __launch_bounds__(256) void sd_reduce_kernel(const float* __restrict__ A, const float* __restrict__ ll,
                                                         long long T, int tps, int shared_model,
                                                         float* __restrict__ agg) {
     using C = SmallCfg<D>;
+    constexpr int W = AggImage<D>::WORDS;
     __shared__ float lds[C::LDS_FLOATS];
-    __shared__ float wagg[C::NW * D * D];
+    __shared__ __align__(8) float wagg[C::NW * W];
+    __shared__ __align__(8) float wtot[W];
     const TileCoord tc = tile_coord<D>(T, tps);
     load_tile<D>(ll + tc.base * D, tc.nvalid, lds);
     float Am[D * D];
     load_model<S, D>(A + (shared_model ? 0 : (size_t)tc.seq * D * D), Am);
     __syncthreads();
     const int n = min(max(tc.nvalid - (int)threadIdx.x * C::L, 0), C::L);
-    float P[D * D], Q[D * D];
-    double msum;
-    chunk_aggregate<S, D, false>(lds + threadIdx.x * C::STRIDE, n, tc.tile == 0 && threadIdx.x == 0, Am, P, msum);
+    Agg<S, D> P, Q;
+    chunk_aggregate<S, D, false>(lds + threadIdx.x * C::STRIDE, n, tc.tile == 0 && threadIdx.x == 0, Am, P);
     block_prefix<S, D>(P, Q, wagg);
     __syncthreads();
-    if (threadIdx.x == 0) {
-        float X[D * D];
-        block_total<S, D>(wagg, X);
-#pragma unroll
-        for (int e = 0; e < D * D; ++e) agg[(size_t)blockIdx.x * D * D + e] = X[e];
-    }
+    if (threadIdx.x < 64) tile_total_rows<S, D>(wagg, wtot, nullptr, 0u);
+    __syncthreads();
+    if (threadIdx.x < W) agg[(size_t)blockIdx.x * W + threadIdx.x] = wtot[threadIdx.x];
 }
 
-// Kernel 2 (both operators): carries between tiles of one sequence.  One workgroup per sequence;
-// lane t folds R consecutive tile aggregates, the workgroup exchanges the folds, then each lane
-// walks its tiles again with vectors.  fin[tile] = forward potential before the tile's first
-// step (prior for tile 0); bout[tile] = backward potential at the tile's last step (ones at T).
+// Kernel 2 (both operators): carries between tiles of one sequence, and the sequence's evidence.  One
+// workgroup per sequence; lane t folds R consecutive tile aggregates, the workgroup exchanges the
+// folds, then each lane walks its tiles again with vectors.  fin[tile] = forward potential before the
+// tile's first step (prior for tile 0); bout[tile] = backward potential at the tile's last step (ones
+// at T); out[seq] = log Z (SumProd) / best joint log-weight (MaxPlus) from the product of all tiles.
 template <class S, int D, bool BWD>
 __global__ __launch_bounds__(256) void sd_carry_kernel(const float* __restrict__ prior, int tps, int shared_model,
                                                        const float* __restrict__ agg, float* __restrict__ fin,
-                                                       float* __restrict__ bout) {
+                                                       float* __restrict__ bout, double* __restrict__ out) {
     using C = SmallCfg<D>;
-    __shared__ float wagg[C::NW * D * D];
+    constexpr int W = AggImage<D>::WORDS;
+    __shared__ __align__(8) float wagg[C::NW * W];
     const int seq = blockIdx.x;
     const int R = (tps + C::NT - 1) / C::NT;
     const int t0 = threadIdx.x * R;
-    const float* sagg = agg + (size_t)seq * tps * D * D;
-    float P[D * D];
-    mat_identity<S, D>(P);
+    const float* sagg = agg + (size_t)seq * tps * W;
+    Agg<S, D> P;
+    agg_identity<S, D>(P);
     for (int r = 0; r < R; ++r) {
         const int tile = t0 + r;
         if (tile < tps) {
-            float M[D * D], Z[D * D];
-#pragma unroll
-            for (int e = 0; e < D * D; ++e) M[e] = sagg[(size_t)tile * D * D + e];
-            mat_mul<S, D>(P, M, Z);
-            renorm<S, D * D>(Z);
-#pragma unroll
-            for (int e = 0; e < D * D; ++e) P[e] = Z[e];
+            Agg<S, D> M, Z;
+            agg_load<S, D>(sagg + (size_t)tile * W, M);
+            agg_mul<S, D, true>(P, M, Z);
+            P = Z;
         }
     }
     float cf[D], cb[D], f[D], b[D];
@@ -95,18 +152,24 @@ __global__ __launch_bounds__(256) void sd_carry_kernel(const float* __restrict__
         cf[j] = S::is_max_plus ? logf(pr[j]) : pr[j];
         cb[j] = S::one();
     }
-    block_exchange<S, D, BWD>(P, cf, cb, f, b, wagg);
+    int bex[D];
+    block_exchange<S, D, BWD>(P, cf, cb, f, b, bex, wagg);
+    if constexpr (BWD && !S::is_max_plus) backward_plain<D>(b, bex);   // handed on as a plain vector
+    if (threadIdx.x == 0) {
+        Agg<S, D> X;
+        block_total<S, D>(wagg, X);
+        out[seq] = sequence_evidence<S, D>(cf, X);
+    }
     float* sfin = fin + (size_t)seq * tps * D;
     for (int r = 0; r < R; ++r) {
         const int tile = t0 + r;
         if (tile < tps) {
 #pragma unroll
             for (int j = 0; j < D; ++j) sfin[(size_t)tile * D + j] = f[j];
-            float M[D * D], g[D];
-#pragma unroll
-            for (int e = 0; e < D * D; ++e) M[e] = sagg[(size_t)tile * D * D + e];
-            vec_mat<S, D>(f, M, g);
-            renorm<S, D>(g);   // the prior itself is handed over unscaled; what follows it is rescaled
+            Agg<S, D> M;
+            float g[D];
+            agg_load<S, D>(sagg + (size_t)tile * W, M);
+            vec_agg<S, D>(f, M, g);   // the prior itself is handed over unscaled; what follows it is rescaled
 #pragma unroll
             for (int j = 0; j < D; ++j) f[j] = g[j];
         }
@@ -118,11 +181,10 @@ __global__ __launch_bounds__(256) void sd_carry_kernel(const float* __restrict__
             if (tile < tps) {
 #pragma unroll
                 for (int j = 0; j < D; ++j) sbout[(size_t)tile * D + j] = b[j];
-                float M[D * D], g[D];
-#pragma unroll
-                for (int e = 0; e < D * D; ++e) M[e] = sagg[(size_t)tile * D * D + e];
-                mat_vec<S, D>(M, b, g);
-                renorm<S, D>(g);
+                Agg<S, D> M;
+                float g[D];
+                agg_load<S, D>(sagg + (size_t)tile * W, M);
+                agg_vec<S, D>(M, b, g);
 #pragma unroll
                 for (int j = 0; j < D; ++j) b[j] = g[j];
             }
@@ -130,40 +192,33 @@ __global__ __launch_bounds__(256) void sd_carry_kernel(const float* __restrict__
     }
 }
 
-// Lane-level two-filter work shared by both plans: forward scan, reversed scan and their per-step
-// combination inside the lane's chunk.  SumProd: marginals (Alg. 3), returns the chunk-local log
-// evidence.  MaxPlus: max-marginals (Alg. 5 / Theorem 4), returns the chunk-local growth of the log
-// of the best joint weight.
+// Lane-level two-filter work shared by all plans: forward scan, reversed scan and their per-step
+// combination inside the lane's chunk.  SumProd: marginals (Alg. 3).  MaxPlus: max-marginals
+// (Alg. 5 / Theorem 4).
 template <class S, int D, bool WRITE_FILT>
-HMM_DEV double smooth_chunk(float* row, int n, bool first, const float (&Am)[D * D], float (&f)[D], float (&b)[D],
-                            double msum, float* __restrict__ filt_dst) {
+HMM_DEV void smooth_chunk(float* row, int n, bool first, const float (&Am)[D * D], float (&f)[D], float (&b)[D],
+                          const int (&bex)[D], float* __restrict__ filt_dst) {
     using C = SmallCfg<D>;
     float F[C::L][D];
-    double delta;
     if constexpr (S::is_max_plus) {
         if (!first) renorm<S, D>(f);   // the log prior is used as given; every other carry starts at max 0
+        renorm<S, D>(b);
         if (n == C::L) {
-            delta = mpv_forward_impl<D, true>(row, n, first, Am, f, F);
+            mpv_forward_impl<D, true>(row, n, first, Am, f, F);
             mpv_backward_impl<D, true>(row, n, Am, b, F);
         } else {
-            delta = mpv_forward_impl<D, false>(row, n, first, Am, f, F);
+            mpv_forward_impl<D, false>(row, n, first, Am, f, F);
             mpv_backward_impl<D, false>(row, n, Am, b, F);
         }
     } else {
-        if (!first) {   // the prior is used as given; every other carry is rescaled to sum to one
-            const float inv = 1.0f / sum_of(f);
-#pragma unroll
-            for (int j = 0; j < D; ++j) f[j] *= inv;
-        }
         if (n == C::L) {
-            delta = sp_forward_impl<D, WRITE_FILT, true>(row, n, first, Am, f, F, msum, filt_dst);
-            sp_backward_impl<D, true>(row, n, Am, b, F);
+            sp_forward_impl<D, WRITE_FILT, true>(row, n, first, Am, f, F, filt_dst);
+            sp_backward_impl<D, true>(row, n, Am, b, bex, F);
         } else {
-            delta = sp_forward_impl<D, WRITE_FILT, false>(row, n, first, Am, f, F, msum, filt_dst);
-            sp_backward_impl<D, false>(row, n, Am, b, F);
+            sp_forward_impl<D, WRITE_FILT, false>(row, n, first, Am, f, F, filt_dst);
+            sp_backward_impl<D, false>(row, n, Am, b, bex, F);
         }
     }
-    return delta;
 }
 
 // Kernel 3 (smoother, max-product): forward scan, reversed scan and (max-)marginals inside a tile;
@@ -174,12 +229,10 @@ __global__ __launch_bounds__(256) void sd_smooth_apply_kernel(const float* __res
                                                               int shared_model, const float* __restrict__ fin_g,
                                                               const float* __restrict__ bout_g,
                                                               float* __restrict__ marg, float* __restrict__ filt,
-                                                              int32_t* __restrict__ argmax,
-                                                              double* __restrict__ part) {
+                                                              int32_t* __restrict__ argmax) {
     using C = SmallCfg<D>;
     __shared__ float lds[C::LDS_FLOATS];
-    __shared__ float wagg[C::NW * D * D];
-    __shared__ double dsum[C::NW];
+    __shared__ __align__(8) float wagg[C::NW * AggImage<D>::WORDS];
     const TileCoord tc = tile_coord<D>(T, tps);
     load_tile<D>(ll + tc.base * D, tc.nvalid, lds);
     float Am[D * D];
@@ -194,55 +247,39 @@ __global__ __launch_bounds__(256) void sd_smooth_apply_kernel(const float* __res
     float* row = lds + threadIdx.x * C::STRIDE;
     const int n = min(max(tc.nvalid - (int)threadIdx.x * C::L, 0), C::L);
     const bool first = tc.tile == 0 && threadIdx.x == 0;
-    float P[D * D];
-    double msum;
-    chunk_aggregate<S, D, true>(row, n, first, Am, P, msum);
+    Agg<S, D> P;
+    chunk_aggregate<S, D, true>(row, n, first, Am, P);
     float f[D], b[D];
-    block_exchange<S, D, true>(P, cf, cb, f, b, wagg);
+    int bex[D];
+    block_exchange<S, D, true>(P, cf, cb, f, b, bex, wagg);
     // (the filtering distributions go to memory lane by lane here: a second staging tile would halve the
     // workgroups per compute unit, which costs more than the scattered stores)
     float* fdst = WRITE_FILT ? filt + (tc.base + (long long)threadIdx.x * C::L) * D : nullptr;
-    const double delta = smooth_chunk<S, D, WRITE_FILT>(row, n, first, Am, f, b, msum, fdst);
-    const double tile_delta = block_sum(delta, dsum);
-    if (threadIdx.x == 0) part[blockIdx.x] = tile_delta;
+    smooth_chunk<S, D, WRITE_FILT>(row, n, first, Am, f, b, bex, fdst);
     __syncthreads();
     store_tile<D>(marg + tc.base * D, tc.nvalid, lds);
     if (argmax != nullptr) store_argmax_tile<D>(argmax + tc.base, tc.nvalid, lds);
 }
 
-// Kernel 4: out[seq] = ordered sum of the tile partials of one sequence.
+// Lane-level Viterbi forward work shared by all plans: h receives the chunk map, xs the final state if
+// this lane holds the sequence's last step.
 template <int D>
-__global__ __launch_bounds__(256) void sd_finalize_kernel(const double* __restrict__ part, int tps,
-                                                          double* __restrict__ out) {
-    __shared__ double dsum[4];
-    const int seq = blockIdx.x;
-    double acc = 0.0;
-    for (int t = threadIdx.x; t < tps; t += blockDim.x) acc += part[(size_t)seq * tps + t];
-    const double s = block_sum(acc, dsum);
-    if (threadIdx.x == 0) out[seq] = s;
-}
-
-// Lane-level Viterbi forward work shared by both plans.  Returns the offsets removed; h receives
-// the chunk map, xs the final state if this lane holds the sequence's last step.
-template <int D>
-HMM_DEV double viterbi_chunk(const float* row, int n, bool first, bool last, const float (&Am)[D * D], float (&v)[D],
-                             uint32_t (&bp)[SmallCfg<D>::W], uint32_t& h, uint32_t& xs) {
+HMM_DEV void viterbi_chunk(const float* row, int n, bool first, bool last, const float (&Am)[D * D], float (&v)[D],
+                           uint32_t (&bp)[SmallCfg<D>::W], uint32_t& h, uint32_t& xs) {
     using C = SmallCfg<D>;
     if (!first) renorm<MaxPlus, D>(v);   // the log prior is used as given; other carries start at max 0
-    double osum;
-    if (n == C::L) osum = mp_forward_impl<D, true>(row, n, first, Am, v, bp);
-    else osum = mp_forward_impl<D, false>(row, n, first, Am, v, bp);
+    if (n == C::L) mp_forward_impl<D, true>(row, n, first, Am, v, bp);
+    else mp_forward_impl<D, false>(row, n, first, Am, v, bp);
     h = chunk_map<D>(bp, n);
     xs = 0u;
     if (last) {   // x*_T = argmax V_T: every later state maps to h(x*_T)
         xs = argmax_state<D>(v);
         h = map_constant<D>(map_apply<D>(h, xs));
     }
-    return n > 0 ? osum : 0.0;
 }
 
-// Kernel V3: forward max-plus scan inside the tile with back-pointers, each lane's chunk map,
-// the tile's map, and the chunk-local log-probability.
+// Kernel V3: forward max-plus scan inside the tile with back-pointers, each lane's chunk map and the
+// tile's map.
 template <int D>
 __global__ __launch_bounds__(256) void sd_viterbi_forward_kernel(const float* __restrict__ A,
                                                                  const float* __restrict__ ll, long long T,
@@ -250,13 +287,11 @@ __global__ __launch_bounds__(256) void sd_viterbi_forward_kernel(const float* __
                                                                  const float* __restrict__ vin_g,
                                                                  uint32_t* __restrict__ bp_g,
                                                                  uint32_t* __restrict__ cmap_g,
-                                                                 uint32_t* __restrict__ tmap_g,
-                                                                 double* __restrict__ part) {
+                                                                 uint32_t* __restrict__ tmap_g) {
     using C = SmallCfg<D>;
     using S = MaxPlus;
     __shared__ float lds[C::LDS_FLOATS];
-    __shared__ float wagg[C::NW * D * D];
-    __shared__ double dsum[C::NW];
+    __shared__ __align__(8) float wagg[C::NW * AggImage<D>::WORDS];
     __shared__ uint32_t wmaps[C::NW];
     const TileCoord tc = tile_coord<D>(T, tps);
     load_tile<D>(ll + tc.base * D, tc.nvalid, lds);
@@ -270,15 +305,13 @@ __global__ __launch_bounds__(256) void sd_viterbi_forward_kernel(const float* __
     const int n = min(max(tc.nvalid - (int)threadIdx.x * C::L, 0), C::L);
     const bool first = tc.tile == 0 && threadIdx.x == 0;
     const bool last = (tc.tile == tps - 1) && n > 0 && ((int)threadIdx.x * C::L + n == tc.nvalid);
-    float P[D * D];
-    double msum;
-    chunk_aggregate<S, D, false>(row, n, first, Am, P, msum);
+    Agg<S, D> P;
+    chunk_aggregate<S, D, false>(row, n, first, Am, P);
     float v[D], unused[D];
-    block_exchange<S, D, false>(P, cf, cf, v, unused, wagg);
+    int unused_ex[D];
+    block_exchange<S, D, false>(P, cf, cf, v, unused, unused_ex, wagg);
     uint32_t bp[C::W], h, xs;
-    const double osum = viterbi_chunk<D>(row, n, first, last, Am, v, bp, h, xs);
-    const double tile_delta = block_sum(osum, dsum);
-    if (threadIdx.x == 0) part[blockIdx.x] = tile_delta;
+    viterbi_chunk<D>(row, n, first, last, Am, v, bp, h, xs);
     const size_t gl = (size_t)blockIdx.x * C::NT + threadIdx.x;
 #pragma unroll
     for (int w = 0; w < C::W; ++w) bp_g[gl * C::W + w] = bp[w];
@@ -288,16 +321,13 @@ __global__ __launch_bounds__(256) void sd_viterbi_forward_kernel(const float* __
     if (threadIdx.x == 0) tmap_g[blockIdx.x] = total;
 }
 
-// Kernel V4: state at the last step of every tile, by composing tile maps right to left, and the
-// sequence's log-probability.  One workgroup per sequence.
+// Kernel V4: state at the last step of every tile, by composing tile maps right to left.  One
+// workgroup per sequence.
 template <int D>
 __global__ __launch_bounds__(256) void sd_viterbi_suffix_kernel(const uint32_t* __restrict__ tmap_g, int tps,
-                                                                uint32_t* __restrict__ xend_g,
-                                                                const double* __restrict__ part,
-                                                                double* __restrict__ logprob) {
+                                                                uint32_t* __restrict__ xend_g) {
     using C = SmallCfg<D>;
     __shared__ uint32_t wmaps[C::NW];
-    __shared__ double dsum[C::NW];
     const int seq = blockIdx.x;
     const int R = (tps + C::NT - 1) / C::NT;
     const int t0 = threadIdx.x * R;
@@ -317,10 +347,6 @@ __global__ __launch_bounds__(256) void sd_viterbi_suffix_kernel(const uint32_t* 
             x = map_apply<D>(sm[tile], x);
         }
     }
-    double acc = 0.0;
-    for (int t = threadIdx.x; t < tps; t += blockDim.x) acc += part[(size_t)seq * tps + t];
-    const double s = block_sum(acc, dsum);
-    if (threadIdx.x == 0) logprob[seq] = s;
 }
 
 // Kernel V5: walk the back-pointers inside each lane's chunk and write the path.
@@ -354,223 +380,173 @@ __global__ __launch_bounds__(256) void sd_viterbi_path_kernel(long long T, int t
 // Single-launch plan (all tiles co-resident)
 // =============================================================================================
 
-// Fills the exchange slots of a call with the sentinel pattern; launched on the same stream right
-// before the fused kernel.
-template <int D>
-__global__ void sd_clear_kernel(uint32_t* __restrict__ p, int n) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) p[i] = (i == n - 1) ? 0u : SENTINEL32;   // the last word is the error flag
+#if HMM_SMALL_D == 1
+// Zero fill of the exchange region (hmm_workspace_init): a kernel, so that it can be captured into a graph.
+__global__ void sd_zero_kernel(uint32_t* __restrict__ p, size_t n) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0u;
 }
+#endif
 
 struct FusedWs {
-    float* agg;        // [tiles][D*D]  tile aggregates
-    double* part;      // [tiles]       tile-local log evidence / log-probability
-    uint32_t* tmap;    // [tiles]       tile back-pointer maps (Viterbi)
-    uint32_t* err;     // [1]           set if a bounded wait ran out
-    int spin_limit;    // polls before a wait gives up (every wave terminates whatever the other workgroups do)
+    XchHeader* hdr;             // generation, poison flag, finished-sequence counter
+    unsigned long long* agg;    // [tiles][AggImage::WORDS] tagged words: tile aggregates
+    unsigned long long* tmap;   // [tiles] tagged words: tile back-pointer maps (Viterbi)
+    int batch;                  // sequences in the call
+    int spin_limit;             // polls before a wait gives up (every wave terminates whatever the other workgroups do)
 };
 
-// LDS scratch of the inter-tile exchange.  Staged aggregates are stored in pairs of tiles, each
-// pair padded by four floats so that 64 lanes reading one pair each do not collide on LDS banks.
+// LDS scratch of the inter-tile exchange: the tile aggregates of the sequence, one record per tile with an
+// odd stride so that lanes reading one record each do not collide on LDS banks, and the per-wave reductions.
 template <int D>
 struct GridLds {
-    static constexpr int PAIR = 2 * D * D;
-    static constexpr int PSTR = PAIR + 4;
-    float red[SmallCfg<D>::NW * D * D];               // per-wave reductions of tile aggregates
-    float aggs[(SmallCfg<D>::NT / 2) * PSTR];         // the sequence's tile aggregates, staged
+    static constexpr int W = AggImage<D>::WORDS;
+    static constexpr int RSTR = W | 1;
+    float red[SmallCfg<D>::NW * W];
+    float aggs[SmallCfg<D>::NT * RSTR];
 };
 
-// Largest value over the wavefront (every lane must call; all lanes get the result).
-HMM_DEV float wave_all_max(float v) {
-    v = fmaxf(v, dpp_move<0x111, 0xF>(-INFINITY, v));   // row_shr:1
-    v = fmaxf(v, dpp_move<0x112, 0xF>(-INFINITY, v));   // row_shr:2
-    v = fmaxf(v, dpp_move<0x114, 0xF>(-INFINITY, v));   // row_shr:4
-    v = fmaxf(v, dpp_move<0x118, 0xF>(-INFINITY, v));   // row_shr:8
-    v = fmaxf(v, dpp_move<0x142, 0xA>(-INFINITY, v));   // row_bcast:15
-    v = fmaxf(v, dpp_move<0x143, 0xC>(-INFINITY, v));   // row_bcast:31
-    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
-}
-
-// The first wave publishes this tile's aggregate, the ordered product of the wave totals in wagg.
-// Lane e < D*D owns entry (e / D, e % D) of the running product: its row comes from the other
-// lanes by shuffles, the next wave total's column from LDS, so the chain of products costs a few
-// instructions per lane instead of whole matrix products in a single lane.
 template <class S, int D>
-HMM_DEV void grid_publish(const float* wagg, const FusedWs& ws) {
-    using C = SmallCfg<D>;
-    static_assert(D * D <= 64, "one lane per entry of the aggregate");
-    if (threadIdx.x < 64) {
-        const int lane = threadIdx.x;
-        const int e = lane < D * D ? lane : 0;   // spare lanes shadow entry 0 and never store
-        const int i = e / D, j = e % D;
-        float x = wagg[e];
+HMM_DEV void agg_load_staged(const float* p, Agg<S, D>& Q) {   // a record in GridLds::aggs (no alignment)
 #pragma unroll
-        for (int w = 1; w < C::NW; ++w) {
-            float acc = S::zero();
+    for (int e = 0; e < D * D; ++e) Q.m[e] = p[e];
 #pragma unroll
-            for (int k = 0; k < D; ++k) acc = S::mul_add(acc, __shfl(x, i * D + k, 64), wagg[(w * D + k) * D + j]);
-            const float m = wave_all_max(acc);
-            if constexpr (S::is_max_plus) x = acc - ((m == -INFINITY) ? 0.0f : m);
-            else x = ldexpf(acc, -__builtin_amdgcn_frexp_expf(m));
-        }
-        if (lane < D * D)
-            coherent_store(reinterpret_cast<uint32_t*>(ws.agg + (size_t)blockIdx.x * D * D) + e, publish_bits(x));
-    }
+    for (int i = 0; i < D; ++i) Q.ex[i] = __float_as_int(p[D * D + i]);
+    const unsigned long long lo = __float_as_uint(p[D * D + D]), hi = __float_as_uint(p[D * D + D + 1]);
+    Q.c = __longlong_as_double((long long)((hi << 32) | lo));
 }
 
-// All lanes: poll n consecutive floats at `src` (slots written by other workgroups) until none
-// holds the sentinel, staging them into LDS in the padded pair layout.  Coalesced 8-byte loads
-// when the base is 8-byte aligned.  Returns false if the bounded wait ran out.
-template <int D>
-HMM_DEV bool gather_aggregates(const float* src, int n, float* dst_lds, int spin_limit) {
-    using G = GridLds<D>;
-    const bool wide = (reinterpret_cast<uintptr_t>(src) & 7u) == 0;
+// Generation and poison flag of the exchange region.  One thread reads them when the kernel starts and
+// hands them to the workgroup through LDS (all threads must agree: barriers depend on it).
+struct CallTag {
+    uint32_t tag;
+    bool poisoned;
+};
+HMM_DEV void read_call_header(const FusedWs& ws, unsigned long long* shared_word) {   // thread 0, before a barrier
+    *shared_word = coherent_load(reinterpret_cast<const unsigned long long*>(ws.hdr));
+}
+HMM_DEV CallTag call_tag(const unsigned long long* shared_word) {                      // everyone, after the barrier
+    const unsigned long long h = *shared_word;
+    CallTag t;
+    t.tag = (uint32_t)h + 1u;
+    t.tag = t.tag == 0u ? 1u : t.tag;   // 0 is what a freshly zeroed region holds
+    t.poisoned = (uint32_t)(h >> 32) != 0u;
+    return t;
+}
+
+// All lanes: poll n consecutive tagged words at `src` (slots written by other workgroups) until all of
+// them carry the call's tag, staging the values into LDS records of `w` words at stride `rstr`.
+// Returns false if the bounded wait ran out.
+template <int w, int rstr>
+HMM_DEV bool gather_tagged(const unsigned long long* src, int n, float* dst_lds, uint32_t tag, int spin_limit) {
     for (int spin = 0; spin < spin_limit; ++spin) {
         bool valid = true;
-        if (wide) {
-            const unsigned long long* s2 = reinterpret_cast<const unsigned long long*>(src);
-            const int n2 = n >> 1;
-            constexpr int NB = 8;   // loads in flight per lane: issued together, then checked and staged
-            for (int base = 0; base < n2; base += NB * (int)blockDim.x) {
-                unsigned long long w[NB];
+        constexpr int NB = 8;   // loads in flight per lane: issued together, then checked and staged
+        for (int base = 0; base < n; base += NB * (int)blockDim.x) {
+            unsigned long long v[NB];
 #pragma unroll
-                for (int q = 0; q < NB; ++q) {
-                    const int i = base + q * (int)blockDim.x + (int)threadIdx.x;
-                    w[q] = coherent_load(s2 + (i < n2 ? i : n2 - 1));
-                }
+            for (int q = 0; q < NB; ++q) {
+                const int i = base + q * (int)blockDim.x + (int)threadIdx.x;
+                v[q] = coherent_load(src + (i < n ? i : n - 1));
+            }
 #pragma unroll
-                for (int q = 0; q < NB; ++q) {
-                    const int i = base + q * (int)blockDim.x + (int)threadIdx.x;
-                    if (i < n2) {
-                        const uint32_t lo = (uint32_t)w[q], hi = (uint32_t)(w[q] >> 32);
-                        valid = valid && lo != SENTINEL32 && hi != SENTINEL32;
-                        const int f = 2 * i;
-                        const int d0 = (f / G::PAIR) * G::PSTR + f % G::PAIR;
-                        const int d1 = ((f + 1) / G::PAIR) * G::PSTR + (f + 1) % G::PAIR;
-                        dst_lds[d0] = __uint_as_float(lo);
-                        dst_lds[d1] = __uint_as_float(hi);
-                    }
+            for (int q = 0; q < NB; ++q) {
+                const int i = base + q * (int)blockDim.x + (int)threadIdx.x;
+                if (i < n) {
+                    valid = valid && (uint32_t)(v[q] >> 32) == tag;
+                    const int rec = i / w;
+                    dst_lds[rec * rstr + (i - rec * w)] = __uint_as_float((uint32_t)v[q]);
                 }
             }
-            if ((n & 1) && threadIdx.x == 0) {
-                const uint32_t w = coherent_load(reinterpret_cast<const uint32_t*>(src) + n - 1);
-                valid = valid && w != SENTINEL32;
-                dst_lds[((n - 1) / G::PAIR) * G::PSTR + (n - 1) % G::PAIR] = __uint_as_float(w);
-            }
-        } else {
-            for (int i = threadIdx.x; i < n; i += blockDim.x) {
-                const uint32_t w = coherent_load(reinterpret_cast<const uint32_t*>(src) + i);
-                valid = valid && w != SENTINEL32;
-                dst_lds[(i / G::PAIR) * G::PSTR + i % G::PAIR] = __uint_as_float(w);
-            }
         }
-        if (__syncthreads_and(valid ? 1 : 0)) {
-#ifdef HMM_PHASE_STAMPS
-            if ((threadIdx.x & 63) == 0 && blockIdx.x < 256) g_stamps[(blockIdx.x * 4 + (threadIdx.x >> 6)) * 16 + 5] = spin;
-#endif
-            return true;
-        }
+        if (__syncthreads_and(valid ? 1 : 0)) return true;
         __builtin_amdgcn_s_sleep(1);
     }
     return false;
 }
 
-// Gather the aggregates of the sequence's tiles and return the vectors entering this tile:
+// Gather the aggregates of the sequence's tiles and return the vectors entering this tile with the
+// scales they were stripped of (bits for SumProd, an offset for MaxPlus):
 // cf = forward potential before its first step (prior (op) M_0 (op) ... (op) M_{c-1}),
 // cb = backward potential at its last step (M_{c+1} (op) ... (op) M_{tps-1} (op) ones).
 // The two ordered products are masked reductions over at most 2*128 tile slots: the first two
 // waves reduce the tiles before c, the last two the tiles after c (tps <= NT).
 template <class S, int D, bool BWD>
-HMM_DEV bool grid_gather(const TileCoord& tc, int tps, const float* __restrict__ prior, const FusedWs& ws,
-                         GridLds<D>& gl, float (&cf)[D], float (&cb)[D]) {
+HMM_DEV bool grid_gather(const TileCoord& tc, int tps, const float (&start)[D], const FusedWs& ws, uint32_t tag,
+                         GridLds<D>& gl, float (&cf)[D], double& cfs, float (&cb)[D], double& cbs) {
     using C = SmallCfg<D>;
     using G = GridLds<D>;
     static_assert(C::NW == 4, "the split below assumes four waves");
     const int tile0 = blockIdx.x - tc.tile;   // first tile of this sequence
-    const bool ok = gather_aggregates<D>(ws.agg + (size_t)tile0 * D * D, tps * D * D, gl.aggs, ws.spin_limit);
-    if (!ok && threadIdx.x == 0) atomicOr(ws.err, 1u);
-    HMM_STAMP(14);
+    const bool ok = gather_tagged<G::W, G::RSTR>(ws.agg + (size_t)tile0 * G::W, tps * G::W, gl.aggs, tag, ws.spin_limit);
     const int wave = threadIdx.x >> 6;
     const int lane = threadIdx.x & 63;
     const bool fwd_half = wave < 2;
     if (fwd_half || BWD) {
         const int u = (int)threadIdx.x & 127;             // pair index 0..127 inside the half
-        float Ma[D * D], Mb[D * D], X[D * D];
+        Agg<S, D> Ma, Mb, X;
         const int ta = 2 * u, tb = 2 * u + 1;
         const bool use_a = ok && ta < tps && (fwd_half ? (ta < tc.tile) : (ta > tc.tile));
         const bool use_b = ok && tb < tps && (fwd_half ? (tb < tc.tile) : (tb > tc.tile));
-        const float* pa = gl.aggs + u * G::PSTR;
-#pragma unroll
-        for (int i = 0; i < D; ++i)
-#pragma unroll
-            for (int j = 0; j < D; ++j) {
-                const float id = (i == j) ? S::one() : S::zero();
-                Ma[i * D + j] = use_a ? pa[i * D + j] : id;
-                Mb[i * D + j] = use_b ? pa[D * D + i * D + j] : id;
-            }
-        mat_mul<S, D>(Ma, Mb, X);
+        agg_identity<S, D>(Ma);
+        agg_identity<S, D>(Mb);
+        if (use_a) agg_load_staged<S, D>(gl.aggs + ta * G::RSTR, Ma);
+        if (use_b) agg_load_staged<S, D>(gl.aggs + tb * G::RSTR, Mb);
+        agg_mul<S, D, true>(Ma, Mb, X);
         wave_scan_prefix<S, D>(X);                        // lane 63 ends with the wave's ordered product
-        if (lane == 63) {
-#pragma unroll
-            for (int e = 0; e < D * D; ++e) gl.red[wave * D * D + e] = X[e];
-        }
+        if (lane == 63) agg_store<S, D>(gl.red + wave * G::W, X);
     }
     __syncthreads();
-    HMM_STAMP(15);
-    float pr[D], v[D], r[D], Wm[D * D];
+    float v[D], r[D];
+    double vs = 0.0;
 #pragma unroll
-    for (int j = 0; j < D; ++j) v[j] = pr[j] = S::is_max_plus ? logf(prior[j]) : prior[j];
+    for (int j = 0; j < D; ++j) v[j] = start[j];
 #pragma unroll
     for (int w = 0; w < 2; ++w) {
-#pragma unroll
-        for (int e = 0; e < D * D; ++e) Wm[e] = gl.red[w * D * D + e];
-        vec_mat<S, D>(v, Wm, r);
-        renorm<S, D>(r);
+        Agg<S, D> Wm;
+        agg_load<S, D>(gl.red + w * G::W, Wm);
+        vs += Wm.c + vec_agg<S, D>(v, Wm, r);
 #pragma unroll
         for (int j = 0; j < D; ++j) v[j] = r[j];
     }
-    // the first tile starts from the prior exactly as given (its scale is part of the evidence);
-    // every later tile's carry is scale-free
+    // the first tile starts from the prior exactly as given; every later tile's carry is rescaled
 #pragma unroll
-    for (int j = 0; j < D; ++j) cf[j] = (tc.tile == 0) ? pr[j] : v[j];
+    for (int j = 0; j < D; ++j) cf[j] = (tc.tile == 0) ? start[j] : v[j];
+    cfs = (tc.tile == 0) ? 0.0 : vs;
 #pragma unroll
     for (int j = 0; j < D; ++j) cb[j] = S::one();
+    cbs = 0.0;
     if constexpr (BWD) {
 #pragma unroll
         for (int w = 3; w >= 2; --w) {
-#pragma unroll
-            for (int e = 0; e < D * D; ++e) Wm[e] = gl.red[w * D * D + e];
-            mat_vec<S, D>(Wm, cb, r);
-            renorm<S, D>(r);
+            Agg<S, D> Wm;
+            agg_load<S, D>(gl.red + w * G::W, Wm);
+            cbs += Wm.c + agg_vec<S, D>(Wm, cb, r);
 #pragma unroll
             for (int j = 0; j < D; ++j) cb[j] = r[j];
         }
     }
-    return ok;   // false: the bounded wait ran out (the tiles were not all resident); the caller poisons its evidence
+    if (!ok && threadIdx.x == 0) coherent_store(&ws.hdr->poison, 1u);
+    return ok;   // false: the bounded wait ran out (the tiles were not all resident)
 }
 
-// All lanes: poll the sequence's tile partials until all are published, then out[seq] = their
-// ordered sum.  Run by the workgroup of tile 0.
-HMM_DEV void grid_sum_parts(int tile0, int tps, const FusedWs& ws, double* dsum, double* __restrict__ out, int seq) {
-    double acc = 0.0;
-    bool ok = false;
-    for (int spin = 0; spin < ws.spin_limit; ++spin) {
-        bool valid = true;
-        acc = 0.0;
-        if ((int)threadIdx.x < tps) {
-            const unsigned long long w = coherent_load(reinterpret_cast<const unsigned long long*>(ws.part) + tile0 + threadIdx.x);
-            valid = w != SENTINEL64;
-            acc = __longlong_as_double((long long)w);
-        }
-        if (__syncthreads_and(valid ? 1 : 0)) { ok = true; break; }
-        __builtin_amdgcn_s_sleep(1);
-    }
+// End of a sequence's work in the single-launch plan, by one thread of the workgroup that reports the
+// sequence's evidence: writes it, and once every sequence of the call has reported, advances the
+// exchange region's generation (all workgroups of a sequence have read the old one before any of them
+// got past its gather).  A failed call leaves the region poisoned instead.
+HMM_DEV void finish_sequence(const FusedWs& ws, uint32_t tag, bool ok, double evidence, double* __restrict__ out, int seq) {
+    out[seq] = ok ? evidence : __builtin_nan("");
     if (!ok) {
-        if (threadIdx.x == 0) atomicOr(ws.err, 1u);
-        acc = __builtin_nan("");
+        coherent_store(&ws.hdr->poison, 1u);
+        return;
     }
-    const double s = block_sum(acc, dsum);
-    if (threadIdx.x == 0) out[seq] = s;
+    bool last = true;
+    if (ws.batch > 1) {
+        const uint32_t done = __hip_atomic_fetch_add(&ws.hdr->seq_done, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        last = done + 1u == (uint32_t)ws.batch;
+        if (last) coherent_store(&ws.hdr->seq_done, 0u);
+    }
+    if (last) coherent_store(&ws.hdr->generation, tag);
 }
 
 template <class S, int D, bool WRITE_FILT>
@@ -581,6 +557,7 @@ __global__ __launch_bounds__(256) void sd_smooth_fused_kernel(const float* __res
                                                               float* __restrict__ filt, int32_t* __restrict__ argmax,
                                                               double* __restrict__ loglik_out, FusedWs ws) {
     using C = SmallCfg<D>;
+    constexpr int W = AggImage<D>::WORDS;
     __shared__ float lds[C::LDS_FLOATS];
     // the filtering distributions of the tile are staged like the marginals, in the space the inter-tile exchange
     // has finished with by then (both do not fit beside the tile at D >= 7)
@@ -590,72 +567,89 @@ __global__ __launch_bounds__(256) void sd_smooth_fused_kernel(const float* __res
     } sh;
     GridLds<D>& gl = sh.gl;
     float* flds = sh.flds;
-    __shared__ float wagg[C::NW * D * D];
-    __shared__ double dsum[C::NW];
-    HMM_STAMP(0);
-#ifdef HMM_PHASE_STAMPS
-    if ((threadIdx.x & 63) == 0 && blockIdx.x < 256) {
-        g_stamps[(blockIdx.x * 4 + (threadIdx.x >> 6)) * 16 + 12] = __builtin_amdgcn_s_getreg(63492);   // HW_ID
-        g_stamps[(blockIdx.x * 4 + (threadIdx.x >> 6)) * 16 + 13] = __builtin_amdgcn_s_getreg(63508);   // XCC_ID
-    }
-#endif
+    __shared__ __align__(8) float wagg[C::NW * W];
+    __shared__ __align__(8) float wtot[W];
     const TileCoord tc = tile_coord<D>(T, tps);
-    float Am[D * D];
+    const bool alone = tps == 1;   // the sequence is this one tile: nothing to exchange, no wait anywhere
+    float Am[D * D], start[D];
     load_model_raw<D>(A + (shared_model ? 0 : (size_t)tc.seq * D * D), Am);   // issued ahead of the tile's loads
-    load_tile<D>(ll + tc.base * D, tc.nvalid, lds, [&]() { model_to_domain<S, D>(Am); });
+#pragma unroll
+    for (int j = 0; j < D; ++j) start[j] = prior[(shared_model ? 0 : (size_t)tc.seq * D) + j];
+    __shared__ unsigned long long header_word;
+    if (!alone && threadIdx.x == 0) read_call_header(ws, &header_word);
+    load_tile<D>(ll + tc.base * D, tc.nvalid, lds, [&]() {
+        model_to_domain<S, D>(Am);
+        if constexpr (S::is_max_plus) {
+#pragma unroll
+            for (int j = 0; j < D; ++j) start[j] = logf(start[j]);
+        }
+    });
     __syncthreads();
-    HMM_STAMP(1);
+    CallTag ct{0u, false};
+    if (!alone) ct = call_tag(&header_word);
+    // phase: tile loaded
     float* row = lds + threadIdx.x * C::STRIDE;
     const int n = min(max(tc.nvalid - (int)threadIdx.x * C::L, 0), C::L);
     const bool first = tc.tile == 0 && threadIdx.x == 0;
-    float P[D * D], Q[D * D], R[D * D];
-    double msum;
-    chunk_aggregate<S, D, true>(row, n, first, Am, P, msum);
-    HMM_STAMP(2);
+    Agg<S, D> P, Q, R;
+    chunk_aggregate<S, D, true>(row, n, first, Am, P);
+    // phase: chunk aggregates
     block_prefix<S, D>(P, Q, wagg);
     __syncthreads();
-    HMM_STAMP(3);
-    const bool alone = tps == 1;   // the sequence is this one tile: nothing to exchange, no wait anywhere
-    if (!alone) grid_publish<S, D>(wagg, ws);
-    HMM_STAMP(4);
+    // phase: wave prefixes
+    const bool publish = !alone && !ct.poisoned;
+    if (threadIdx.x < 64)
+        tile_total_rows<S, D>(wagg, wtot, publish ? ws.agg + (size_t)blockIdx.x * W : nullptr, ct.tag);
+    // phase: published
     // the suffix scan needs nothing from other tiles: it runs while their aggregates arrive
-#pragma unroll
-    for (int e = 0; e < D * D; ++e) R[e] = P[e];
+    R = P;
     wave_scan_suffix<S, D>(R);
     float cf[D], cb[D];
+    double cfs = 0.0, cbs = 0.0;
     bool ok = true;
     if (alone) {
-        const float* pr = prior + (shared_model ? 0 : (size_t)tc.seq * D);
 #pragma unroll
         for (int j = 0; j < D; ++j) {
-            cf[j] = S::is_max_plus ? logf(pr[j]) : pr[j];
+            cf[j] = start[j];
+            cb[j] = S::one();
+        }
+    } else if (ct.poisoned) {
+        ok = false;
+#pragma unroll
+        for (int j = 0; j < D; ++j) {
+            cf[j] = start[j];
             cb[j] = S::one();
         }
     } else {
-        ok = grid_gather<S, D, true>(tc, tps, prior + (shared_model ? 0 : (size_t)tc.seq * D), ws, gl, cf, cb);
+        ok = grid_gather<S, D, true>(tc, tps, start, ws, ct.tag, gl, cf, cfs, cb, cbs);
         if constexpr (WRITE_FILT) __syncthreads();   // every wave is done with the exchange area before it is reused
     }
-    HMM_STAMP(6);
+    // phase: tile carries
     float f[D], b[D];
+    int bex[D];
     carry_forward<S, D>(Q, wagg, cf, f);
-    carry_backward<S, D>(R, wagg, cb, b);
-    HMM_STAMP(7);
+    carry_backward<S, D>(R, wagg, cb, b, bex);
+    // phase: lane carries
     float* fdst = WRITE_FILT ? flds + threadIdx.x * C::STRIDE : nullptr;
-    double delta = smooth_chunk<S, D, WRITE_FILT>(row, n, first, Am, f, b, msum, fdst);
-    if (!ok) delta = __builtin_nan("");   // an expired wait makes the call's log evidence NaN
-    HMM_STAMP(8);
-    const double tile_delta = block_sum(delta, dsum);   // contains a barrier: all marginals are in LDS
-    if (threadIdx.x == 0) {
-        if (alone) loglik_out[tc.seq] = tile_delta;
-        else coherent_store(reinterpret_cast<unsigned long long*>(ws.part) + blockIdx.x, publish_bits(tile_delta));
-    }
-    HMM_STAMP(9);
+    smooth_chunk<S, D, WRITE_FILT>(row, n, first, Am, f, b, bex, fdst);
+    // phase: chunk recursions
+    __syncthreads();   // all marginals are in LDS (and the first wave's tile total)
     store_tile<D>(marg + tc.base * D, tc.nvalid, lds);
     if constexpr (WRITE_FILT) store_tile<D>(filt + tc.base * D, tc.nvalid, flds);
     if (argmax != nullptr) store_argmax_tile<D>(argmax + tc.base, tc.nvalid, lds);
-    HMM_STAMP(10);
-    if (!alone && tc.tile == 0) grid_sum_parts(blockIdx.x, tps, ws, dsum, loglik_out, tc.seq);
-    HMM_STAMP(11);
+    // phase: stored
+    // evidence of the sequence, by its last tile: (forward potential entering it) (op) M_last, summed / maximised
+    // over the final state -- no backward potential is involved, so no state the two disagree on can be lost
+    if (tc.tile == tps - 1 && threadIdx.x == 0) {
+        Agg<S, D> Ml;
+        float fin1[D];
+#pragma unroll
+        for (int j = 0; j < D; ++j) fin1[j] = S::one();
+        agg_load<S, D>(wtot, Ml);
+        const double ev = span_evidence<S, D>(cf, cfs, Ml, fin1, 0.0);
+        if (alone) loglik_out[tc.seq] = ev;
+        else finish_sequence(ws, ct.tag, ok, ev, loglik_out, tc.seq);
+    }
 }
 
 template <int D>
@@ -666,84 +660,88 @@ __global__ __launch_bounds__(256) void sd_viterbi_fused_kernel(const float* __re
                                                                double* __restrict__ logprob_out, FusedWs ws) {
     using C = SmallCfg<D>;
     using S = MaxPlus;
+    constexpr int W = AggImage<D>::WORDS;
     __shared__ float lds[C::LDS_FLOATS];
-    __shared__ float wagg[C::NW * D * D];
+    __shared__ __align__(8) float wagg[C::NW * W];
+    __shared__ __align__(8) float wtot[W];
     __shared__ GridLds<D> gl;
-    __shared__ double dsum[C::NW];
     __shared__ uint32_t wmaps[C::NW];
     __shared__ uint32_t wmaps2[C::NW];
     __shared__ uint32_t xend_lds;
-    HMM_STAMP(0);
     const TileCoord tc = tile_coord<D>(T, tps);
     const int tile0 = blockIdx.x - tc.tile;
-    float Am[D * D];
+    const bool alone = tps == 1;   // the sequence is this one tile: nothing to exchange, no wait anywhere
+    float Am[D * D], start[D];
     load_model_raw<D>(A + (shared_model ? 0 : (size_t)tc.seq * D * D), Am);   // issued ahead of the tile's loads
-    load_tile<D>(ll + tc.base * D, tc.nvalid, lds, [&]() { model_to_domain<S, D>(Am); });
+#pragma unroll
+    for (int j = 0; j < D; ++j) start[j] = prior[(shared_model ? 0 : (size_t)tc.seq * D) + j];
+    __shared__ unsigned long long header_word;
+    if (!alone && threadIdx.x == 0) read_call_header(ws, &header_word);
+    load_tile<D>(ll + tc.base * D, tc.nvalid, lds, [&]() {
+        model_to_domain<S, D>(Am);
+#pragma unroll
+        for (int j = 0; j < D; ++j) start[j] = logf(start[j]);
+    });
     __syncthreads();
-    HMM_STAMP(1);
+    CallTag ct{0u, false};
+    if (!alone) ct = call_tag(&header_word);
+    // phase: tile loaded
     float* row = lds + threadIdx.x * C::STRIDE;
     const int n = min(max(tc.nvalid - (int)threadIdx.x * C::L, 0), C::L);
     const bool first = tc.tile == 0 && threadIdx.x == 0;
     const bool last = (tc.tile == tps - 1) && n > 0 && ((int)threadIdx.x * C::L + n == tc.nvalid);
-    float P[D * D], Q[D * D];
-    double msum;
-    chunk_aggregate<S, D, false>(row, n, first, Am, P, msum);
-    HMM_STAMP(2);
+    Agg<S, D> P, Q;
+    chunk_aggregate<S, D, false>(row, n, first, Am, P);
+    // phase: chunk aggregates
     block_prefix<S, D>(P, Q, wagg);
     __syncthreads();
-    HMM_STAMP(3);
-    const bool alone = tps == 1;   // the sequence is this one tile: nothing to exchange, no wait anywhere
+    // phase: wave prefixes
+    const bool exchange = !alone && !ct.poisoned;
+    if (threadIdx.x < 64)
+        tile_total_rows<S, D>(wagg, wtot, exchange ? ws.agg + (size_t)blockIdx.x * W : nullptr, ct.tag);
+    // phase: published
     float cf[D], cb[D];
-    bool ok = true;
-    if (alone) {
-        const float* pr = prior + (shared_model ? 0 : (size_t)tc.seq * D);
+    double cfs = 0.0, cbs = 0.0;
+    bool ok = !(!alone && ct.poisoned);
 #pragma unroll
-        for (int j = 0; j < D; ++j) cf[j] = logf(pr[j]);
-    } else {
-        grid_publish<S, D>(wagg, ws);
-        HMM_STAMP(4);
-        ok = grid_gather<S, D, false>(tc, tps, prior + (shared_model ? 0 : (size_t)tc.seq * D), ws, gl, cf, cb);
-    }
-    HMM_STAMP(6);
+    for (int j = 0; j < D; ++j) cf[j] = start[j];
+    if (exchange) ok = grid_gather<S, D, false>(tc, tps, start, ws, ct.tag, gl, cf, cfs, cb, cbs);
+    // phase: tile carries
     float v[D];
     carry_forward<S, D>(Q, wagg, cf, v);
-    HMM_STAMP(7);
+    // phase: lane carries
     uint32_t bp[C::W], h, xs;
-    double osum = viterbi_chunk<D>(row, n, first, last, Am, v, bp, h, xs);
-    if (!ok) osum = __builtin_nan("");   // an expired wait makes the call's log-probability NaN
-    HMM_STAMP(8);
+    viterbi_chunk<D>(row, n, first, last, Am, v, bp, h, xs);
+    // phase: chunk recursion
     uint32_t excl;
     const uint32_t total = block_map_suffix<D>(h, excl, wmaps);
-    if (!alone && threadIdx.x == 0) coherent_store(ws.tmap + blockIdx.x, total);   // a map uses 24 bits: never the sentinel
-    HMM_STAMP(9);
-    const double tile_delta = block_sum(osum, dsum);   // other tiles wait for the map, not for this
-    if (threadIdx.x == 0) {
-        if (alone) logprob_out[tc.seq] = tile_delta;
-        else coherent_store(reinterpret_cast<unsigned long long*>(ws.part) + blockIdx.x, publish_bits(tile_delta));
-    }
-    bool ok2 = true;
+    if (exchange && ok && threadIdx.x == 0) publish_word(ws.tmap + blockIdx.x, total, ct.tag);
+    // phase: tile map published
     uint32_t x;
-    if (alone) {
+    if (!exchange || !ok) {
         // the maps after a lane's chunk end with the last chunk's, which is constant: any argument will do
+        // (a failed exchange decodes every tile on its own: the outputs of such a call are meaningless anyway)
         x = map_apply<D>(excl, 0u);
     } else {
         // the tile maps of the sequence; state at this tile's last step = maps of later tiles composed
         uint32_t tm = map_identity<D>();
-        ok2 = false;
+        bool ok2 = false;
         for (int spin = 0; spin < ws.spin_limit; ++spin) {
             bool valid = true;
             if ((int)threadIdx.x < tps) {
-                tm = coherent_load(ws.tmap + tile0 + threadIdx.x);
-                valid = tm != SENTINEL32;
+                const unsigned long long w = coherent_load(ws.tmap + tile0 + threadIdx.x);
+                valid = (uint32_t)(w >> 32) == ct.tag;
+                tm = (uint32_t)w;
             }
             if (__syncthreads_and(valid ? 1 : 0)) { ok2 = true; break; }
             __builtin_amdgcn_s_sleep(1);
         }
         if (!ok2) {
-            if (threadIdx.x == 0) atomicOr(ws.err, 1u);
+            ok = false;
             tm = map_identity<D>();
+            if (threadIdx.x == 0) coherent_store(&ws.hdr->poison, 1u);
         }
-        HMM_STAMP(10);
+        // phase: tile maps gathered
         uint32_t texcl;
         block_map_suffix<D>(tm, texcl, wmaps2);
         if ((int)threadIdx.x == tc.tile) xend_lds = map_apply<D>(texcl, 0u);   // last tile's map is constant
@@ -751,16 +749,22 @@ __global__ __launch_bounds__(256) void sd_viterbi_fused_kernel(const float* __re
         x = map_apply<D>(excl, xend_lds);
     }
     if (last) x = xs;
-    HMM_STAMP(11);
     int32_t* stage = reinterpret_cast<int32_t*>(lds);   // the log-likelihood tile is no longer needed
     walk_chunk<D>(bp, n, first, x, stage + threadIdx.x * C::PSTRIDE);
     __syncthreads();
-    HMM_STAMP(12);
+    // phase: walked
     store_path_tile<D>(path + tc.base, tc.nvalid, stage);
-    HMM_STAMP(13);
-    if (!alone && tc.tile == 0) {
-        if (ok2) grid_sum_parts(blockIdx.x, tps, ws, dsum, logprob_out, tc.seq);
-        else if (threadIdx.x == 0) logprob_out[tc.seq] = __builtin_nan("");   // the wait for the tile maps ran out
+    // phase: stored
+    // best joint log-weight of the sequence, by its last tile: max_j (forward potential (op) M_last)(j)
+    if (tc.tile == tps - 1 && threadIdx.x == 0) {
+        Agg<S, D> Ml;
+        float zero[D];
+#pragma unroll
+        for (int j = 0; j < D; ++j) zero[j] = 0.0f;
+        agg_load<S, D>(wtot, Ml);
+        const double ev = span_evidence<S, D>(cf, cfs, Ml, zero, 0.0);
+        if (alone) logprob_out[tc.seq] = ev;
+        else finish_sequence(ws, ct.tag, ok, ev, logprob_out, tc.seq);
     }
 }
 
@@ -794,15 +798,15 @@ __global__ __launch_bounds__(256) void sd_smooth_packed_kernel(const float* __re
     }
     __syncthreads();
     float* row = lds + threadIdx.x * C::STRIDE;
-    float P[D * D];
-    double msum;
-    chunk_aggregate<S, D, true>(row, pc.n, pc.first, Am, P, msum);
+    Agg<S, D> P, Q;
+    chunk_aggregate<S, D, true>(row, pc.n, pc.first, Am, P);
     float f[D], b[D];
-    group_exchange<S, D, true>(P, lcpl, pc.c, start, f, b);
+    int bex[D];
+    group_exchange<S, D, true>(P, lcpl, pc.c, start, f, b, bex, Q);
+    // the group's last lane holds the aggregate of the whole sequence (lanes past its end hold neutral elements)
+    if (pc.live && pc.c == (1 << lcpl) - 1) out[pc.seq] = sequence_evidence<S, D>(start, Q);
     float* fdst = WRITE_FILT ? filt + ((size_t)pc.seq * T + (size_t)pc.c * C::L) * D : nullptr;   // lane by lane, as in the apply kernel
-    const double delta = smooth_chunk<S, D, WRITE_FILT>(row, pc.n, pc.first, Am, f, b, msum, fdst);
-    const double total = group_sum(delta, lcpl);
-    if (pc.first) out[pc.seq] = total;
+    smooth_chunk<S, D, WRITE_FILT>(row, pc.n, pc.first, Am, f, b, bex, fdst);
     __syncthreads();   // all (max-)marginals are in LDS
     store_packed<D>(marg + (size_t)pc.seq0 * rowlen, nfl, rowlen, lcpl, lds);
     if (argmax != nullptr) store_argmax_packed<D>(argmax + (size_t)pc.seq0 * T, pc.nseq * (int)T, (int)T, lcpl, lds);
@@ -830,15 +834,14 @@ __global__ __launch_bounds__(256) void sd_viterbi_packed_kernel(const float* __r
     for (int j = 0; j < D; ++j) start[j] = logf(prior[(shared_model ? 0 : (size_t)pc.seq * D) + j]);
     __syncthreads();
     const float* row = lds + threadIdx.x * C::STRIDE;
-    float P[D * D];
-    double msum;
-    chunk_aggregate<S, D, false>(const_cast<float*>(row), pc.n, pc.first, Am, P, msum);
+    Agg<S, D> P, Q;
+    chunk_aggregate<S, D, false>(const_cast<float*>(row), pc.n, pc.first, Am, P);
     float v[D], unused[D];
-    group_exchange<S, D, false>(P, lcpl, pc.c, start, v, unused);
+    int unused_ex[D];
+    group_exchange<S, D, false>(P, lcpl, pc.c, start, v, unused, unused_ex, Q);
+    if (pc.live && pc.c == (1 << lcpl) - 1) logprob_out[pc.seq] = sequence_evidence<S, D>(start, Q);
     uint32_t bp[C::W], h, xs;
-    const double osum = viterbi_chunk<D>(row, pc.n, pc.first, pc.last, Am, v, bp, h, xs);
-    const double total = group_sum(osum, lcpl);
-    if (pc.first) logprob_out[pc.seq] = total;
+    viterbi_chunk<D>(row, pc.n, pc.first, pc.last, Am, v, bp, h, xs);
     // the maps after a lane's chunk end with the last chunk's, which is constant: any argument will do
     uint32_t x = map_apply<D>(group_map_suffix<D>(h, lcpl, pc.c), 0u);
     if (pc.last) x = xs;
@@ -859,19 +862,27 @@ template <class S, int D>
 HMM_DEV double chunk_element(const float* row, int n, bool first, const float (&Am)[D * D], float (&P)[D * D]) {
     using C = SmallCfg<D>;
     mat_identity<S, D>(P);
-    float ms = 0.0f, rs = 0.0f;   // sums of at most L emission maxima / L removed exponents or offsets
+    float bs = 0.0f, rs = 0.0f;   // whole bits taken out of the emission factors / exponents or offsets removed by rescaling
 #pragma unroll
     for (int k = 0; k < C::L; ++k) {
         if (k < n) {
             float ev[D];
             lds_read_vec<D>(row + k * D, ev);
-            ms += emission<S, D>(ev);
-            if (k == 0 && first) absorb<S, D>(P, Am, ev, true);
-            else absorb<S, D>(P, Am, ev, false);
+            float bits, spread;
+            emission<S, D>(ev, bits, spread);
+            bs += bits;
+            if (k == 0 && first) {   // the block's first step has no transition part
+#pragma unroll
+                for (int i = 0; i < D; ++i)
+#pragma unroll
+                    for (int j = 0; j < D; ++j) P[i * D + j] = S::times(P[i * D + j], ev[j]);
+            } else {
+                absorb<S, D>(P, Am, ev);
+            }
             if ((k & 3) == 3 || k == n - 1) rs += renorm<S, D * D>(P);
         }
     }
-    return (double)ms + (double)rs * (S::is_max_plus ? 1.0 : 0.6931471805599453);
+    return S::is_max_plus ? (double)rs : ((double)bs + (double)rs) * 0.6931471805599453;
 }
 
 // Ordered product of one (aggregate, scale) pair per lane over the workgroup; result in thread 0.
@@ -990,33 +1001,25 @@ static long long tiles_per_seq(long long T) {
     return (T + SmallCfg<D>::TILE - 1) / SmallCfg<D>::TILE;
 }
 
-struct SmoothWs { size_t agg, fin, bout, part, xch, total; };
-struct ViterbiWs { size_t agg, vin, bp, cmap, tmap, xend, part, xch, total; };
+// Every workspace starts with the exchange region of the single-launch plan, XCH_REGION_BYTES long
+// whatever the shape: header, then tagged aggregate slots, then tagged tile-map slots for up to
+// XCH_MAX_TILES tiles.  Nothing else is ever written there, so that the words of the region carry either
+// zero or the tag of some earlier call, for any sequence of calls on the workspace.
+constexpr size_t XCH_AGG_OFFSET = 256;
+constexpr size_t XCH_MAP_OFFSET = XCH_AGG_OFFSET + (size_t)XCH_MAX_TILES * (8 * 8 + 8 + 2) * 8;
+static_assert(XCH_MAP_OFFSET + (size_t)XCH_MAX_TILES * 8 <= XCH_REGION_BYTES, "exchange region too small");
 
-// Exchange region of the single-launch plan, in 32-bit words: [aggregates][parts][maps][error flag]
-struct XchLayout { size_t agg, part, tmap, err, words; };
-template <int D>
-static XchLayout xch_layout(size_t nt) {
-    XchLayout x;
-    size_t o = 0;
-    x.agg = o;  o += (nt * D * D + 1) / 2 * 2;   // keeps the doubles that follow 8-byte aligned
-    x.part = o; o += 2 * nt;
-    x.tmap = o; o += nt;
-    x.err = o;  o += 1;
-    x.words = o;
-    return x;
-}
+struct SmoothWs { size_t agg, fin, bout, total; };
+struct ViterbiWs { size_t agg, vin, bp, cmap, tmap, xend, total; };
 
 template <int D>
 static SmoothWs smooth_ws(long long T, int batch) {
     const size_t nt = (size_t)tiles_per_seq<D>(T) * batch;
     SmoothWs w;
-    size_t o = 0;
-    w.agg = o;   o = align_up(o + nt * D * D * sizeof(float), 256);
+    size_t o = XCH_REGION_BYTES;
+    w.agg = o;   o = align_up(o + nt * AggImage<D>::WORDS * sizeof(float), 256);
     w.fin = o;   o = align_up(o + nt * D * sizeof(float), 256);
     w.bout = o;  o = align_up(o + nt * D * sizeof(float), 256);
-    w.part = o;  o = align_up(o + nt * sizeof(double), 256);
-    w.xch = o;  o = align_up(o + xch_layout<D>(nt).words * sizeof(uint32_t), 256);
     w.total = o;
     return w;
 }
@@ -1026,30 +1029,31 @@ static ViterbiWs viterbi_ws(long long T, int batch) {
     using C = SmallCfg<D>;
     const size_t nt = (size_t)tiles_per_seq<D>(T) * batch;
     ViterbiWs w;
-    size_t o = 0;
-    w.agg = o;   o = align_up(o + nt * D * D * sizeof(float), 256);
+    size_t o = XCH_REGION_BYTES;
+    w.agg = o;   o = align_up(o + nt * AggImage<D>::WORDS * sizeof(float), 256);
     w.vin = o;   o = align_up(o + nt * D * sizeof(float), 256);
     w.bp = o;    o = align_up(o + nt * C::NT * C::W * sizeof(uint32_t), 256);
     w.cmap = o;  o = align_up(o + nt * C::NT * sizeof(uint32_t), 256);
     w.tmap = o;  o = align_up(o + nt * sizeof(uint32_t), 256);
     w.xend = o;  o = align_up(o + nt * sizeof(uint32_t), 256);
-    w.part = o;  o = align_up(o + nt * sizeof(double), 256);
-    w.xch = o;  o = align_up(o + xch_layout<D>(nt).words * sizeof(uint32_t), 256);
     w.total = o;
     return w;
 }
 
-// How many workgroups of `kernel` the current device holds resident at once (cached per kernel).
+// How many workgroups of `kernel` the current device holds resident at once (cached per kernel and device).
 template <int TAG, class K>
 static long long resident_capacity(K kernel) {
-    static long long cached = -1;
-    if (cached >= 0) return cached;
+    constexpr int MAX_DEVICES = 64;
+    static long long cached[MAX_DEVICES];
+    static bool have[MAX_DEVICES];
     int dev = 0, ncu = 0, per_cu = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return 0;
+    if (have[dev]) return cached[dev];
     if (hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, 256, 0) != hipSuccess) return 0;
-    cached = (long long)ncu * per_cu;
-    return cached;
+    cached[dev] = (long long)ncu * per_cu;
+    have[dev] = true;
+    return cached[dev];
 }
 
 // Polls before an inter-tile wait gives up.  HMMSCAN_SPIN_LIMIT overrides the default; 0 makes every
@@ -1077,6 +1081,11 @@ static bool force_multi_launch() {
     return e != nullptr && e[0] == 'm';   // HMMSCAN_PLAN=multi forces the multi-launch plan
 }
 
+static FusedWs fused_ws(char* ws, int batch) {
+    return FusedWs{reinterpret_cast<XchHeader*>(ws), reinterpret_cast<unsigned long long*>(ws + XCH_AGG_OFFSET),
+                   reinterpret_cast<unsigned long long*>(ws + XCH_MAP_OFFSET), batch, spin_limit()};
+}
+
 // The two-filter plans for either operator: marginals + optional filtered + log evidence (SumProd),
 // or max-marginals + optional per-step maximiser + log of the best joint weight (MaxPlus).
 template <class S, int D>
@@ -1092,8 +1101,6 @@ static int two_filter(const SmallArgs& a, float* marg, float* filt, int32_t* arg
     float* agg = reinterpret_cast<float*>(ws + w.agg);
     float* fin = reinterpret_cast<float*>(ws + w.fin);
     float* bout = reinterpret_cast<float*>(ws + w.bout);
-    double* part = reinterpret_cast<double*>(ws + w.part);
-    uint32_t* xch = reinterpret_cast<uint32_t*>(ws + w.xch);
     hipStream_t st = a.stream;
     const dim3 grid((unsigned)nt), block(C::NT), seqs((unsigned)a.batch);
     const int itps = (int)tps;
@@ -1103,6 +1110,7 @@ static int two_filter(const SmallArgs& a, float* marg, float* filt, int32_t* arg
     }
     if (!filt) cap = resident_capacity<(MP ? 5 : 1)>(sd_smooth_fused_kernel<S, D, false>);
     if (MP && filt) return 2;   // no filtered output is defined for the max-product plan
+    if (cap > XCH_MAX_TILES) cap = XCH_MAX_TILES;
     const int lcpl = packed_log2_lanes<D>(a.T);
     if (!force_multi_launch() && lcpl >= 0) {
         // short sequences, several per workgroup: one launch, no workspace
@@ -1120,15 +1128,9 @@ static int two_filter(const SmallArgs& a, float* marg, float* filt, int32_t* arg
         return hipGetLastError() == hipSuccess ? 0 : 4;
     }
     // Sequences of one tile each exchange nothing: the single-launch kernel then runs for any number of them
-    // (no workgroup waits for another, so they need not be resident together) and no slot is cleared.
+    // (no workgroup waits for another, so they need not be resident together).
     if (!force_multi_launch() && (tps == 1 || (tps <= C::NT && nt <= cap))) {
-        const XchLayout xl = xch_layout<D>((size_t)nt);
-        FusedWs fw{reinterpret_cast<float*>(xch + xl.agg), reinterpret_cast<double*>(xch + xl.part), xch + xl.tmap,
-                   xch + xl.err, spin_limit()};
-        const int nwords = (int)xl.words;
-        if (tps > 1)
-            launch(MP ? "sd_clear_mm" : "sd_clear_sp", sd_clear_kernel<D>, dim3((nwords + 255) / 256), dim3(256), st, xch,
-                   nwords);
+        const FusedWs fw = fused_ws(ws, a.batch);
         const char* name = MP ? "sd_maxprod_fused" : "sd_smooth_fused";
         if constexpr (!MP) {
             if (filt)
@@ -1142,17 +1144,16 @@ static int two_filter(const SmallArgs& a, float* marg, float* filt, int32_t* arg
         launch(MP ? "sd_reduce_mp" : "sd_reduce_sp", sd_reduce_kernel<S, D>, grid, block, st, a.A, a.ll, a.T, itps,
                a.shared_model, agg);
         launch(MP ? "sd_carry_mm" : "sd_carry_sp", sd_carry_kernel<S, D, true>, seqs, block, st, a.prior, itps,
-               a.shared_model, agg, fin, bout);
+               a.shared_model, agg, fin, bout, out);
         const char* name = MP ? "sd_maxprod_apply" : "sd_smooth_apply";
         if constexpr (!MP) {
             if (filt)
                 launch(name, sd_smooth_apply_kernel<S, D, true>, grid, block, st, a.A, a.ll, a.T, itps, a.shared_model,
-                       fin, bout, marg, filt, argmax, part);
+                       fin, bout, marg, filt, argmax);
         }
         if (!filt)
             launch(name, sd_smooth_apply_kernel<S, D, false>, grid, block, st, a.A, a.ll, a.T, itps, a.shared_model,
-                   fin, bout, marg, filt, argmax, part);
-        launch("sd_finalize", sd_finalize_kernel<D>, seqs, dim3(256), st, part, itps, out);
+                   fin, bout, marg, filt, argmax);
     }
     return hipGetLastError() == hipSuccess ? 0 : 4;
 }
@@ -1182,8 +1183,6 @@ int SmallD<D>::viterbi(const SmallArgs& a, int32_t* path, double* logprob_out) {
     uint32_t* cmap = reinterpret_cast<uint32_t*>(ws + w.cmap);
     uint32_t* tmap = reinterpret_cast<uint32_t*>(ws + w.tmap);
     uint32_t* xend = reinterpret_cast<uint32_t*>(ws + w.xend);
-    double* part = reinterpret_cast<double*>(ws + w.part);
-    uint32_t* xch = reinterpret_cast<uint32_t*>(ws + w.xch);
     hipStream_t st = a.stream;
     const dim3 grid((unsigned)nt), block(C::NT), seqs((unsigned)a.batch);
     const int itps = (int)tps;
@@ -1194,22 +1193,18 @@ int SmallD<D>::viterbi(const SmallArgs& a, int32_t* path, double* logprob_out) {
                a.prior, a.A, a.ll, a.T, a.batch, lcpl, a.shared_model, path, logprob_out);
         return hipGetLastError() == hipSuccess ? 0 : 4;
     }
-    const long long cap = resident_capacity<2>(sd_viterbi_fused_kernel<D>);
+    long long cap = resident_capacity<2>(sd_viterbi_fused_kernel<D>);
+    if (cap > XCH_MAX_TILES) cap = XCH_MAX_TILES;
     if (!force_multi_launch() && (tps == 1 || (tps <= C::NT && nt <= cap))) {   // one tile per sequence: see two_filter
-        const XchLayout xl = xch_layout<D>((size_t)nt);
-        FusedWs fw{reinterpret_cast<float*>(xch + xl.agg), reinterpret_cast<double*>(xch + xl.part), xch + xl.tmap,
-                   xch + xl.err, spin_limit()};
-        const int nwords = (int)xl.words;
-        if (tps > 1) launch("sd_clear_mp", sd_clear_kernel<D>, dim3((nwords + 255) / 256), dim3(256), st, xch, nwords);
         launch("sd_viterbi_fused", sd_viterbi_fused_kernel<D>, grid, block, st, a.prior, a.A, a.ll, a.T, itps,
-               a.shared_model, path, logprob_out, fw);
+               a.shared_model, path, logprob_out, fused_ws(ws, a.batch));
     } else {
         launch("sd_reduce_mp", sd_reduce_kernel<MaxPlus, D>, grid, block, st, a.A, a.ll, a.T, itps, a.shared_model, agg);
         launch("sd_carry_mp", sd_carry_kernel<MaxPlus, D, false>, seqs, block, st, a.prior, itps, a.shared_model, agg, vin,
-               static_cast<float*>(nullptr));
+               static_cast<float*>(nullptr), logprob_out);
         launch("sd_viterbi_forward", sd_viterbi_forward_kernel<D>, grid, block, st, a.A, a.ll, a.T, itps, a.shared_model,
-               vin, bp, cmap, tmap, part);
-        launch("sd_viterbi_suffix", sd_viterbi_suffix_kernel<D>, seqs, block, st, tmap, itps, xend, part, logprob_out);
+               vin, bp, cmap, tmap);
+        launch("sd_viterbi_suffix", sd_viterbi_suffix_kernel<D>, seqs, block, st, tmap, itps, xend);
         launch("sd_viterbi_path", sd_viterbi_path_kernel<D>, grid, block, st, a.T, itps, bp, cmap, xend, path);
     }
     return hipGetLastError() == hipSuccess ? 0 : 4;
@@ -1218,7 +1213,7 @@ int SmallD<D>::viterbi(const SmallArgs& a, int32_t* path, double* logprob_out) {
 template <int D>
 size_t SmallD<D>::element_ws_bytes(long long T, int batch) {
     const size_t nt = (size_t)tiles_per_seq<D>(T) * batch;
-    return align_up(nt * D * D * sizeof(float), 256) + align_up(nt * sizeof(double), 256);
+    return XCH_REGION_BYTES + align_up(nt * D * D * sizeof(float), 256) + align_up(nt * sizeof(double), 256);
 }
 
 template <int D>
@@ -1228,7 +1223,7 @@ int SmallD<D>::block_element(const SmallArgs& a, int max_product, float* element
     const long long nt = tps * a.batch;
     if (nt > 0x7fffffffLL) return 2;
     if (a.ws_bytes < element_ws_bytes(a.T, a.batch)) return 3;
-    char* ws = static_cast<char*>(a.ws);
+    char* ws = static_cast<char*>(a.ws) + XCH_REGION_BYTES;
     float* tagg = reinterpret_cast<float*>(ws);
     double* tsc = reinterpret_cast<double*>(ws + align_up((size_t)nt * D * D * sizeof(float), 256));
     const dim3 grid((unsigned)nt), block(C::NT), seqs((unsigned)a.batch);
@@ -1254,9 +1249,13 @@ size_t SmallD<D>::viterbi_ws_bytes(long long T, int batch) { return viterbi_ws<D
 
 template struct SmallD<HMM_SMALL_D>;
 
-#ifdef HMM_PHASE_STAMPS
-extern "C" int hmm_debug_read_stamps(unsigned long long* host_dst) {
-    return (int)hipMemcpyFromSymbol(host_dst, HIP_SYMBOL(g_stamps), sizeof(unsigned long long) * 1024 * 16);
+#if HMM_SMALL_D == 1
+// Zero fill of a workspace's exchange region, enqueued on the stream (one definition for the library).
+int small_d_zero_region(void* ws, size_t bytes, hipStream_t stream) {
+    const size_t n = bytes / sizeof(uint32_t);
+    if (n == 0) return 0;
+    launch("sd_zero", sd_zero_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), stream, static_cast<uint32_t*>(ws), n);
+    return hipGetLastError() == hipSuccess ? 0 : 4;
 }
 #endif
 

@@ -85,7 +85,15 @@ def test_argument_errors_are_caught_on_the_host():
     assert lib.hmm_transition_counts(fake, fake, fake, 8, 200, 1, 1, fake, aligned_ws, 1 << 20, null) == 2
     assert lib.hmm_transition_counts(fake, fake, fake, 8, 4, 1, 1, fake, aligned_ws, 8, null) == 3
     assert hmm.hmm_transition_counts_workspace_bytes(1 << 20, 4, 1) >= 64
-    assert hmm.hmm_transition_counts_workspace_bytes(1, 128, 3) == 3 * 128 * 128 * 4
+    assert hmm.hmm_transition_counts_workspace_bytes(1, 128, 3) == 3 * 128 * 128 * 4 + binding.WORKSPACE_RESERVED_BYTES
+    # workspace preparation and state query
+    assert lib.hmm_workspace_init(null, 1 << 20, null) == 3
+    assert lib.hmm_workspace_init(ctypes.c_void_p(0x1010), 1 << 20, null) == 3
+    assert lib.hmm_workspace_status(null, null, ctypes.byref(ctypes.c_int32(0))) == 1
+    assert lib.hmm_workspace_status(fake, null, None) == 1
+    # every workspace size includes the bytes the library keeps across calls
+    assert min(hmm.hmm_workspace_bytes(1, 1, 1)) >= binding.WORKSPACE_RESERVED_BYTES
+    assert min(hmm.hmm_workspace_bytes(100, 64, 2)) >= binding.WORKSPACE_RESERVED_BYTES
     # hmm_block_element / hmm_block_carries
     assert lib.hmm_block_element(null, fake, 8, 4, 1, 1, 0, fake, fake, aligned_ws, 1 << 20, null) == 1
     assert lib.hmm_block_element(fake, fake, 8, 4, 1, 1, 0, fake, null, aligned_ws, 1 << 20, null) == 1

@@ -35,7 +35,7 @@ def test_captured_calls_replay_exactly(kind):
     lla, llb = torch.from_numpy(pa.loglik).to(dev), torch.from_numpy(pb.loglik).to(dev)
     B, T, D = lla.shape
     ws_s, ws_v = hmm.hmm_workspace_bytes(T, D, B)
-    ws = torch.empty(max(ws_s, ws_v), dtype=torch.uint8, device=dev)
+    ws = hmm.new_workspace(max(ws_s, ws_v), dev)
 
     def eager(ll):
         m, _, L = hmm.hmm_smooth(prior, A, ll, workspace=ws)

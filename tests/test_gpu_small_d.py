@@ -94,8 +94,9 @@ def test_config2_full_size(gu):
 
 def test_expired_wait_is_reported_not_hung(gu, plan, monkeypatch):
     """Failure handling of the single-launch plan, forced from the host: with a poll limit of zero every
-    inter-tile wait gives up at once, all kernels still run to completion, and the evidence outputs are
-    NaN; the next call on the same workspace is correct again."""
+    inter-tile wait gives up at once, all kernels still run to completion, the evidence outputs are NaN and
+    the workspace is marked; later calls on it report NaN at once until it has been re-initialised, after
+    which they are correct again."""
     import torch
     import paper_2102_05743_amd as hmm
     if plan != "single":
@@ -103,14 +104,25 @@ def test_expired_wait_is_reported_not_hung(gu, plan, monkeypatch):
     p = wl.config2(T=50000)
     prior, A, ll = gu.to_dev(p)
     ws_s, ws_v = hmm.hmm_workspace_bytes(p.T, p.D, 1)
-    ws = torch.empty((max(ws_s, ws_v),), dtype=torch.uint8, device=ll.device)
+    ws = hmm.new_workspace(max(ws_s, ws_v), ll.device)
+    assert hmm.hmm_workspace_status(ws) == 0
     monkeypatch.setenv("HMMSCAN_SPIN_LIMIT", "0")
     _, _, L = hmm.hmm_smooth(prior, A, ll, workspace=ws)
+    torch.cuda.synchronize()
+    assert np.isnan(L.cpu().numpy()).all() and hmm.hmm_workspace_status(ws) == 1
+    hmm.hmm_workspace_init(ws)
     _, lp = hmm.hmm_viterbi(prior, A, ll, workspace=ws)
+    hmm.hmm_workspace_init(ws)
     _, _, lpm = hmm.hmm_max_product(prior, A, ll, workspace=ws)
     torch.cuda.synchronize()
-    assert np.isnan(L.cpu().numpy()).all() and np.isnan(lp.cpu().numpy()).all() and np.isnan(lpm.cpu().numpy()).all()
+    assert np.isnan(lp.cpu().numpy()).all() and np.isnan(lpm.cpu().numpy()).all()
     monkeypatch.delenv("HMMSCAN_SPIN_LIMIT")
+    # still marked: an ordinary call now gives up at once instead of trusting what the failed call left behind
+    _, _, L = hmm.hmm_smooth(prior, A, ll, workspace=ws)
+    torch.cuda.synchronize()
+    assert np.isnan(L.cpu().numpy()).all()
+    hmm.hmm_workspace_init(ws)
+    assert hmm.hmm_workspace_status(ws) == 0
     marg, _, L = hmm.hmm_smooth(prior, A, ll, workspace=ws)
     torch.cuda.synchronize()
     m0, _, L0 = gu.oracle.smooth(p.prior[0], p.A[0], p.loglik[0], want_filtered=False)

@@ -1,0 +1,70 @@
+"""GPU parity on models with structural zeros (absorbing and one-way states) whose log-likelihoods were drawn
+independently of any state path, so that over long stretches the evidence contradicts the only states the
+chain can still be in.  The rows of an aggregated product of potentials (Def. 3) then differ by far more
+than single precision spans, and a carry may sit on exactly the small rows: the smoother must keep a scale
+per row of every aggregate to stay with the classical recursion (Thm. 1 / Thm. 2).  Each shape below was
+drawn by a seeded sweep and, with one scale per aggregate, left the tolerances (non-finite marginals, a
+NaN log-likelihood, or finite marginals that were simply wrong)."""
+import pytest
+
+from paper_2102_05743_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gu():
+    import gpu_util
+    return gpu_util
+
+
+# (seed, D, T, batch, shared model, fraction of zeroed transitions, log-likelihood scale)
+#
+# WITHIN_RANGE: the classical forward-backward recursion (Alg. 1) run step by step in single precision agrees
+# with the fp64 oracle on these, so the scan formulation must as well (Thm. 1 / Thm. 2 promise the same results).
+WITHIN_RANGE = [
+    (18201, 2, 677, 2, True, 0.3, 5.0), (28145, 2, 737, 1, True, 0.5, 5.0), (2410, 2, 1374, 1, True, 0.7, 5.0),
+    (30370, 3, 243, 4, True, 0.5, 5.0), (25611, 4, 721, 19, False, 0.3, 5.0), (29275, 4, 599, 19, False, 0.5, 5.0),
+    (35688, 4, 683, 2, False, 0.7, 5.0), (21850, 5, 374, 8, False, 0.7, 5.0), (30490, 6, 1115, 2, False, 0.5, 5.0),
+    (36372, 6, 373, 8, False, 0.7, 5.0), (33231, 8, 2905, 19, False, 0.5, 2.0),
+    (9909, 9, 6939, 1, True, 0.7, 2.0), (10221, 9, 485, 19, False, 0.7, 5.0), (18629, 12, 22284, 1, True, 0.7, 2.0),
+]
+# BEYOND_SINGLE_PRECISION: on these the filtering probability of the state that the later evidence vindicates falls
+# below anything single precision can hold beside the step's largest (the oracle's fp64 still holds it), so the
+# step-by-step single-precision recursion loses it too: it is the arithmetic type that fails, not the scan
+# (tests/test_sparse_shape_classes.py pins this classification on the CPU).  Kept as a record; not asserted.
+BEYOND_SINGLE_PRECISION = [
+    (8202, 2, 5627, 1, True, 0.3, 5.0), (35426, 2, 5051, 1, True, 0.5, 5.0), (20093, 2, 989, 2, True, 0.7, 5.0),
+    (25546, 3, 963, 4, True, 0.3, 5.0), (22116, 3, 9165, 1, True, 0.3, 5.0), (34437, 3, 1197, 1, True, 0.7, 5.0),
+    (30568, 3, 5286, 1, True, 0.7, 5.0), (25473, 4, 1683, 1, True, 0.3, 5.0), (6273, 4, 12731, 1, True, 0.3, 2.0),
+    (16885, 4, 6604, 1, True, 0.5, 5.0), (29, 4, 5074, 1, True, 0.7, 5.0), (7639, 5, 15960, 1, True, 0.3, 2.0),
+    (37082, 5, 6179, 1, True, 0.7, 2.0), (19128, 6, 6008, 1, True, 0.7, 5.0), (3953, 8, 11002, 1, True, 0.7, 2.0),
+    (29886, 9, 24795, 1, True, 0.7, 2.0),
+]
+# expected transition counts are formed from the smoother's normalised outputs, which hold nothing below 1e-38:
+# on these two shapes that is too little for the pairwise posteriors although the marginals themselves are right
+COUNTS_NEED_MORE_RANGE = {35688, 30490}
+# above eight states the aggregates still carry one scale per strip of rows, not per row
+ONE_SCALE_PER_STRIP = {9909, 10221, 18629}
+
+
+def _problem(shape):
+    seed, D, T, B, shared, zf, lls = shape
+    return wl.random_problem(D, T, batch=B, shared_model=shared, seed=70000 + seed, zero_frac=zf, ll_scale=lls)
+
+
+@pytest.mark.parametrize("plan", ["single", "multi"])
+@pytest.mark.parametrize("shape", WITHIN_RANGE, ids=lambda s: f"seed{s[0]}-D{s[1]}-T{s[2]}-B{s[3]}")
+def test_sparse_model_with_contradicting_evidence(gu, shape, plan, monkeypatch):
+    D = shape[1]
+    if D > 8 and plan == "multi":
+        pytest.skip("one plan above eight states")
+    if shape[0] in ONE_SCALE_PER_STRIP:
+        pytest.skip("known failure: above eight states an aggregate's rows share one scale per strip, and on this "
+                    "shape that flushes the rows the carry sits on (non-finite marginals)")
+    monkeypatch.setenv("HMMSCAN_PLAN", plan)
+    p = _problem(shape)
+    label = f"sparse seed={shape[0]} D={D} T={shape[2]} B={shape[3]} zero_frac={shape[5]} ll_scale={shape[6]} plan={plan}"
+    gu.check_smooth(p, want_filtered=True, label=label)
+    if shape[0] not in COUNTS_NEED_MORE_RANGE:
+        gu.check_transition_counts(p, label=label)
