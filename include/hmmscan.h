@@ -224,6 +224,30 @@ hmm_status hmm_block_carries(const float* prior, const float* A, const float* el
                              int32_t num_blocks, int32_t D, int32_t batch, int32_t shared_model, int32_t max_product,
                              float* carry_rows, float* lookahead_rows, double* total, void* hip_stream);
 
+/*
+ * hmm_smooth for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Identical to hmm_smooth (same kernels, same
+ * outputs) except that the scratch memory is not an argument: it is a device array of
+ * HMM_STATIC_SCRATCH_BYTES bytes inside the library itself, one copy on every GPU that loads the
+ * library, held until the process ends.  The call allocates and frees nothing.
+ *
+ *   Shapes whose hmm_workspace_bytes(...).smooth_bytes exceeds HMM_STATIC_SCRATCH_BYTES are refused
+ *   with HMM_ERR_WORKSPACE before anything is launched (every D <= 8 shape up to millions of steps
+ *   fits; large D needs per-step scratch and fits only short sequences).
+ *   The first call on a device looks the array's address up once (no allocation, but make that
+ *   call outside a graph capture).
+ *   All calls on one GPU share that GPU's array, whose contents carry over from call to call (it
+ *   starts out zero, as a workspace must, and the library keeps its reserved bytes consistent from
+ *   then on): calls that overlap on one GPU -- two streams, two host threads -- race and must be
+ *   serialised by the caller.  Calls on different GPUs are independent.
+ * Other arguments, alignment rules and error codes as for hmm_smooth.
+ */
+#define HMM_STATIC_SCRATCH_BYTES (4u << 20)
+hmm_status hmm_smooth_static(const float* prior, const float* A, const float* loglik,
+                             int64_t T, int32_t D, int32_t batch, int32_t shared_model,
+                             float* marginals, float* filtered, double* loglik_out,
+                             void* hip_stream);
+
 /* Static, human-readable name of a status code. */
 const char* hmm_status_string(hmm_status status);
 

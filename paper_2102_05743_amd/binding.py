@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libhmmscan.so")
 HMM_OK = 0
 _lib = None
 
-EXPORTED_SYMBOLS = ("hmm_workspace_bytes", "hmm_workspace_init", "hmm_workspace_status", "hmm_smooth", "hmm_viterbi", "hmm_max_product",
+EXPORTED_SYMBOLS = ("hmm_workspace_bytes", "hmm_workspace_init", "hmm_workspace_status", "hmm_smooth", "hmm_smooth_static", "hmm_viterbi", "hmm_max_product",
                     "hmm_transition_counts_workspace_bytes", "hmm_transition_counts",
                     "hmm_block_element_workspace_bytes", "hmm_block_element", "hmm_block_carries", "hmm_status_string",
                     "hmm_kernel_timing_enable", "hmm_kernel_timing_count", "hmm_kernel_timing_get")
@@ -47,6 +47,9 @@ def load_library():
         lib.hmm_smooth.argtypes = [vp, vp, vp, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                                    vp, vp, vp, vp, sz, vp]
         lib.hmm_smooth.restype = ctypes.c_int
+        lib.hmm_smooth_static.argtypes = [vp, vp, vp, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                          vp, vp, vp, vp]
+        lib.hmm_smooth_static.restype = ctypes.c_int
         lib.hmm_viterbi.argtypes = [vp, vp, vp, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                                     vp, vp, vp, sz, vp]
         lib.hmm_viterbi.restype = ctypes.c_int
@@ -217,6 +220,30 @@ def hmm_smooth(prior, A, loglik, marginals=None, filtered=None, loglik_out=None,
     Returns (marginals[B][T][D] f32, filtered or None, loglik_out[B] f64); asynchronous on
     torch's current stream."""
     return hmm_smooth_prepare(prior, A, loglik, marginals, filtered, loglik_out, workspace, want_filtered)()
+
+
+STATIC_SCRATCH_BYTES = 4 << 20
+
+
+def hmm_smooth_static(prior, A, loglik, marginals, loglik_out, filtered=None):
+    """hmm_smooth on the library's own static scratch array: the caller passes every output (nothing is
+    allocated here either).  Returns (marginals, filtered, loglik_out); asynchronous on torch's current stream."""
+    import torch
+    lib = load_library()
+    B, T, D, Bm, shared = _shapes(prior, A, loglik)
+    f32 = torch.float32
+    _check(prior, f32, (Bm, D), "prior")
+    _check(A, f32, (Bm, D, D), "A")
+    _check(loglik, f32, (B, T, D), "loglik")
+    _check(marginals, f32, (B, T, D), "marginals")
+    if filtered is not None:
+        _check(filtered, f32, (B, T, D), "filtered")
+    _check(loglik_out, torch.float64, (B,), "loglik_out")
+    rc = lib.hmm_smooth_static(_ptr(prior), _ptr(A), _ptr(loglik), T, D, B, shared, _ptr(marginals), _ptr(filtered),
+                               _ptr(loglik_out), _stream())
+    if rc != HMM_OK:
+        raise HmmError(rc, "hmm_smooth_static")
+    return marginals, filtered, loglik_out
 
 
 def hmm_viterbi_prepare(prior, A, loglik, path=None, logprob_out=None, workspace=None) -> PreparedCall:

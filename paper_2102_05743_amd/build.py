@@ -14,7 +14,8 @@ LIB_PATH = os.path.join(HERE, "libhmmscan.so")
 # (source, extra defines, object name)
 UNITS = [("api.hip", [], "api.o"), ("ktimer.hip", [], "ktimer.o"), ("small_d.hip", [], "small_d.o"),
          ("large_d_sp.hip", [], "large_d_sp.o"),
-         ("large_d_mp.hip", [], "large_d_mp.o"), ("estep.hip", [], "estep.o"), ("blocks.hip", [], "blocks.o")] + \
+         ("large_d_mp.hip", [], "large_d_mp.o"), ("estep.hip", [], "estep.o"), ("blocks.hip", [], "blocks.o"),
+         ("static_scratch.hip", [], "static_scratch.o")] + \
         [("small_d_kernels.hip", ["-DHMM_SMALL_D=%d" % d], "small_d_kernels_%d.o" % d) for d in range(1, 9)]
 
 HIPCC_FLAGS = [
