@@ -137,7 +137,8 @@ struct Agg {
 
 constexpr int EX_NONE = -(1 << 28);   // "this term does not exist" in exponent comparisons
 constexpr int FAST_SPREAD = 32;       // row exponents this close together are applied as plain powers of two
-constexpr int ROW_BIAS = 44;          // stored rows: largest entry in [2^43, 2^44)
+constexpr int UNIFORM_SPREAD = 20;    // rows whose largest entries are this close together share one exponent
+constexpr int ROW_BIAS = 44;          // stored rows: largest entry below 2^44 (and above 2^(43 - UNIFORM_SPREAD))
 constexpr int SLOW_LIFT = 76;         // general product: a row's largest left factor sits at 2^76
 constexpr int WORK_BIAS = 100;        // rows inside a chunk's step loop: room to shrink between two rescalings
 constexpr int WORK_ROOM = 64;         // ... by at most this many bits
@@ -158,7 +159,18 @@ HMM_DEV void agg_identity(Agg<S, D>& P) {
     P.c = 0.0;
 }
 
+template <int D>
+HMM_DEV float row_max(const float (&m)[D * D], int i) {
+    float mx = m[i * D];
+#pragma unroll
+    for (int j = 1; j < D; ++j) mx = fmaxf(mx, m[i * D + j]);
+    return mx;
+}
+
 // Rows back to the bias (SumProd) / largest entry back to 0 (MaxPlus); what is removed goes into the scale.
+// SumProd: if the rows' largest entries lie within 2^UNIFORM_SPREAD of one another (decided for the whole
+// wavefront) they all take the exponent of the largest, so that rows whose exponents were equal keep equal
+// exponents -- the usual case, for which products need no alignment at all.  Otherwise every row takes its own.
 template <class S, int D, int BIAS = ROW_BIAS>
 HMM_DEV void agg_renorm(Agg<S, D>& P) {
     if constexpr (S::is_max_plus) {
@@ -168,25 +180,26 @@ HMM_DEV void agg_renorm(Agg<S, D>& P) {
         for (int e = 0; e < D * D; ++e) P.m[e] -= mx;
         P.c += (double)mx;
     } else {
+        int e[D];
+#pragma unroll
+        for (int i = 0; i < D; ++i) e[i] = __builtin_amdgcn_frexp_expf(row_max<D>(P.m, i)) - BIAS;   // (a zero row just drifts: nobody reads its exponent)
+        int hi = e[0], lo = e[0];
+#pragma unroll
+        for (int i = 1; i < D; ++i) {
+            hi = e[i] > hi ? e[i] : hi;
+            lo = e[i] < lo ? e[i] : lo;
+        }
+        if (!wave_any(hi - lo > UNIFORM_SPREAD)) {
+#pragma unroll
+            for (int i = 0; i < D; ++i) e[i] = hi;
+        }
 #pragma unroll
         for (int i = 0; i < D; ++i) {
-            float mx = P.m[i * D];
 #pragma unroll
-            for (int j = 1; j < D; ++j) mx = fmaxf(mx, P.m[i * D + j]);
-            const int e = __builtin_amdgcn_frexp_expf(mx) - BIAS;   // (a zero row just drifts: nobody reads its exponent)
-#pragma unroll
-            for (int j = 0; j < D; ++j) P.m[i * D + j] = ldexpf(P.m[i * D + j], -e);
-            P.ex[i] += e;
+            for (int j = 0; j < D; ++j) P.m[i * D + j] = ldexpf(P.m[i * D + j], -e[i]);
+            P.ex[i] += e[i];
         }
     }
-}
-
-template <int D>
-HMM_DEV float row_max(const float (&m)[D * D], int i) {
-    float mx = m[i * D];
-#pragma unroll
-    for (int j = 1; j < D; ++j) mx = fmaxf(mx, m[i * D + j]);
-    return mx;
 }
 
 // Z = X (op) Y.  TRACK_C = false leaves Z.c alone (scans whose scale nobody reads).
@@ -212,7 +225,12 @@ HMM_DEV void agg_mul(const Agg<S, D>& X, const Agg<S, D>& Y, Agg<S, D>& Z) {
             hi = Y.ex[k] > hi ? Y.ex[k] : hi;
             lo = Y.ex[k] < lo ? Y.ex[k] : lo;
         }
-        if (!wave_any(hi - lo > FAST_SPREAD)) {
+        if (!wave_any(hi != lo)) {
+            // all of Y's rows share one exponent: the plain product (entries below D 2^(2 ROW_BIAS))
+            mat_mul<S, D>(X.m, Y.m, Z.m);
+#pragma unroll
+            for (int i = 0; i < D; ++i) Z.ex[i] = X.ex[i] + hi;
+        } else if (!wave_any(hi - lo > FAST_SPREAD)) {
             float Xs[D * D];
 #pragma unroll
             for (int k = 0; k < D; ++k) {
@@ -270,6 +288,23 @@ HMM_DEV double vec_agg(const float (&v)[D], const Agg<S, D>& M, float (&r)[D]) {
         return (double)mx;
     } else {
         constexpr int LIFT = 60;   // the largest term's left factor sits at 2^60: room below for the others
+        {
+            int hi = M.ex[0], lo = M.ex[0];
+#pragma unroll
+            for (int i = 1; i < D; ++i) {
+                hi = M.ex[i] > hi ? M.ex[i] : hi;
+                lo = M.ex[i] < lo ? M.ex[i] : lo;
+            }
+            if (!wave_any(hi != lo)) {
+                // all rows share one exponent: the plain product, brought to a largest entry near 2^VEC_BIAS
+                // (v is a potential of at most 2^VEC_BIAS: entries below D 2^(VEC_BIAS + ROW_BIAS))
+                vec_mat<S, D>(v, M.m, r);
+                const int ex = __builtin_amdgcn_frexp_expf(max_of(r)) - VEC_BIAS;
+#pragma unroll
+                for (int j = 0; j < D; ++j) r[j] = ldexpf(r[j], -ex);
+                return (double)hi + (double)ex;
+            }
+        }
         int e[D], ref = EX_NONE;
 #pragma unroll
         for (int i = 0; i < D; ++i) {
@@ -315,6 +350,21 @@ HMM_DEV double agg_vec(const Agg<S, D>& M, const float (&v)[D], float (&r)[D]) {
         return (double)mx;
     } else {
         float s[D];
+        {
+            int hi = M.ex[0], lo = M.ex[0];
+#pragma unroll
+            for (int i = 1; i < D; ++i) {
+                hi = M.ex[i] > hi ? M.ex[i] : hi;
+                lo = M.ex[i] < lo ? M.ex[i] : lo;
+            }
+            if (!wave_any(hi != lo)) {
+                mat_vec<S, D>(M.m, v, s);
+                const int ex = __builtin_amdgcn_frexp_expf(max_of(s)) - VEC_BIAS;
+#pragma unroll
+                for (int i = 0; i < D; ++i) r[i] = ldexpf(s[i], -ex);
+                return (double)hi + (double)ex;
+            }
+        }
         int es[D], ref = EX_NONE;
         agg_vec_raw<D>(M, v, s, es);
 #pragma unroll
@@ -327,6 +377,95 @@ HMM_DEV double agg_vec(const Agg<S, D>& M, const float (&v)[D], float (&r)[D]) {
             r[i] = (es[i] != EX_NONE) ? ldexpf(s[i], max_of_int(M.ex[i] - ref + VEC_BIAS, -400)) : 0.0f;
         return (ref != EX_NONE) ? (double)(ref - VEC_BIAS) : 0.0;
     }
+}
+
+// =============================================================================================
+// Uniform mode (SumProd).  In well-conditioned models the rows of every aggregate stay within
+// 2^UNIFORM_SPREAD of one another and all share one exponent; the operations above then always take
+// their first branch.  The *_u operations below are those first branches on their own: straight-line
+// code that assumes its arguments' row exponents are all equal (it reads ex[0]), produces results
+// with equal row exponents, and reports in `bad` whenever the general operation would have left its
+// first branch (the test is slightly stricter, never laxer).  A caller runs a whole phase in uniform
+// mode and, if any lane of the wavefront reported `bad`, runs the phase again with the general
+// operations: what comes out is bit for bit what the general operations alone produce, but the
+// usual case has no branch per operation.
+template <int D>
+HMM_DEV bool agg_is_uniform(const Agg<SumProd, D>& P) {
+    bool u = true;
+#pragma unroll
+    for (int i = 1; i < D; ++i) u = u && (P.ex[i] == P.ex[0]);
+    return u;
+}
+
+template <int D, int BIAS = ROW_BIAS>
+HMM_DEV void agg_renorm_u(Agg<SumProd, D>& P, bool& bad) {
+    float hi = row_max<D>(P.m, 0), lo = hi;
+#pragma unroll
+    for (int i = 1; i < D; ++i) {
+        const float r = row_max<D>(P.m, i);
+        hi = fmaxf(hi, r);
+        lo = fminf(lo, r);
+    }
+    // rows more than 2^UNIFORM_SPREAD apart (a zero row beside a non-zero one included) need their own exponents
+    bad = bad || (lo < hi * (1.0f / (float)(1 << UNIFORM_SPREAD)));
+    const int e = __builtin_amdgcn_frexp_expf(hi) - BIAS;
+#pragma unroll
+    for (int k = 0; k < D * D; ++k) P.m[k] = ldexpf(P.m[k], -e);
+    const int ne = P.ex[0] + e;
+#pragma unroll
+    for (int i = 0; i < D; ++i) P.ex[i] = ne;
+}
+
+template <int D, bool TRACK_C = true>
+HMM_DEV void agg_mul_u(const Agg<SumProd, D>& X, const Agg<SumProd, D>& Y, Agg<SumProd, D>& Z, bool& bad) {
+    mat_mul<SumProd, D>(X.m, Y.m, Z.m);
+    const int e = X.ex[0] + Y.ex[0];
+#pragma unroll
+    for (int i = 0; i < D; ++i) Z.ex[i] = e;
+    if constexpr (TRACK_C) Z.c = X.c + Y.c;
+    agg_renorm_u<D>(Z, bad);
+}
+
+template <int D>
+HMM_DEV double vec_agg_u(const float (&v)[D], const Agg<SumProd, D>& M, float (&r)[D]) {
+    vec_mat<SumProd, D>(v, M.m, r);
+    const int ex = __builtin_amdgcn_frexp_expf(max_of(r)) - VEC_BIAS;
+#pragma unroll
+    for (int j = 0; j < D; ++j) r[j] = ldexpf(r[j], -ex);
+    return (double)M.ex[0] + (double)ex;
+}
+
+template <int D>
+HMM_DEV double agg_vec_u(const Agg<SumProd, D>& M, const float (&v)[D], float (&r)[D]) {
+    float s[D];
+    mat_vec<SumProd, D>(M.m, v, s);
+    const int ex = __builtin_amdgcn_frexp_expf(max_of(s)) - VEC_BIAS;
+#pragma unroll
+    for (int i = 0; i < D; ++i) r[i] = ldexpf(s[i], -ex);
+    return (double)M.ex[0] + (double)ex;
+}
+
+// One spelling for both modes: U selects the uniform operation (SumProd only; MaxPlus has no branches to
+// avoid and always runs the general one).
+template <bool U, class S, int D, bool TRACK_C>
+HMM_DEV void agg_mul_m(const Agg<S, D>& X, const Agg<S, D>& Y, Agg<S, D>& Z, bool& bad) {
+    if constexpr (U && !S::is_max_plus) agg_mul_u<D, TRACK_C>(X, Y, Z, bad);
+    else agg_mul<S, D, TRACK_C>(X, Y, Z);
+}
+template <bool U, class S, int D, int BIAS>
+HMM_DEV void agg_renorm_m(Agg<S, D>& P, bool& bad) {
+    if constexpr (U && !S::is_max_plus) agg_renorm_u<D, BIAS>(P, bad);
+    else agg_renorm<S, D, BIAS>(P);
+}
+template <bool U, class S, int D>
+HMM_DEV double vec_agg_m(const float (&v)[D], const Agg<S, D>& M, float (&r)[D]) {
+    if constexpr (U && !S::is_max_plus) return vec_agg_u<D>(v, M, r);
+    else return vec_agg<S, D>(v, M, r);
+}
+template <bool U, class S, int D>
+HMM_DEV double agg_vec_m(const Agg<S, D>& M, const float (&v)[D], float (&r)[D]) {
+    if constexpr (U && !S::is_max_plus) return agg_vec_u<D>(M, v, r);
+    else return agg_vec<S, D>(M, v, r);
 }
 
 }  // namespace hmm

@@ -225,69 +225,129 @@ HMM_DEV void absorb(float (&P)[D * D], const float (&Am)[D * D], const float (&e
 // Aggregate of the lane's chunk: a_{k0-1:k0} (op) ... (op) a_{k1-2:k1-1} over its n valid steps, with its
 // scale.  With STORE_E the emission factors replace the log-likelihoods in LDS.  FULL: n == L is known.
 //
-// Range (SumProd).  The rows of P are rescaled every fourth step, each by its own power of two, to a
+// The emission factors of all steps are formed first (one straight run of independent loads and
+// exponentials), then the chain of products runs from registers in blocks of four steps.
+//
+// Range (SumProd).  The rows of P are rescaled after every block, each by its own power of two, to a
 // largest entry near 2^WORK_BIAS.  Between two rescalings a row's largest entry cannot shrink faster than
-// 2^(spread_k) / D per step (the transition rows sum to one), so the steps' spreads are added up, and when
-// the bound says a row could have lost 2^-WORK_ROOM the rows are rescaled at once, ahead of schedule (decided per
-// wavefront): a row's largest entry never falls below 2^(WORK_BIAS-WORK_ROOM), and entries 2^-126 below it
-// are still normal numbers.  A state is therefore lost only where a step-by-step recursion in single
-// precision loses it as well.
-template <class S, int D, bool STORE_E, bool FULL>
-HMM_DEV void chunk_aggregate_impl(float* row, int n, bool first, const float (&Am)[D * D], Agg<S, D>& P) {
+// 2^(spread_k) / D per step (the transition rows sum to one); the spreads of a block's steps are added
+// up beforehand, and a block that could cost a row more than 2^-WORK_ROOM rescales before every step
+// instead (decided per wavefront): a row's largest entry never falls below 2^(WORK_BIAS-WORK_ROOM-spread of
+// one step), and entries 2^-126 below it are still normal numbers.  A state is therefore lost only where a
+// step-by-step recursion in single precision loses it as well.
+template <class S, int D>
+struct ChunkFactors {
     using C = SmallCfg<D>;
-    agg_identity<S, D>(P);
-    float csum = 0.0f;   // whole bits of at most L steps: exact in float unless the log-likelihoods are astronomically large
-    float room = 0.0f;   // SumProd: bound on the binary logarithm of what a row has lost since its last rescaling
+    float E[C::L][D];       // emission factors of the lane's steps
+    float lost[C::L / 4];   // SumProd: bound on the binary logarithm of what a row can lose during a block of four steps
+    float csum;             // whole bits taken out of the factors (at most L steps: exact in float unless the log-likelihoods are astronomically large)
+};
+
+template <class S, int D, bool STORE_E, bool FULL>
+HMM_DEV void chunk_emissions(float* row, int n, ChunkFactors<S, D>& F) {
+    using C = SmallCfg<D>;
+    static_assert(C::L % 4 == 0, "blocks of four steps");
     constexpr float PER_STEP = (D <= 2) ? 1.0f : (D <= 4) ? 2.0f : 3.0f;   // log2 D
+    F.csum = 0.0f;
+#pragma unroll
+    for (int b = 0; b < C::L / 4; ++b) F.lost[b] = 0.0f;
 #pragma unroll
     for (int k = 0; k < C::L; ++k) {
         if (FULL || k < n) {
-            float ev[D], bits, spread;
-            lds_read_vec<D>(row + k * D, ev);
-            emission<S, D>(ev, bits, spread);
-            if constexpr (STORE_E) lds_write_vec<D>(row + k * D, ev);
-            csum += bits;
-            if (k == 0) {
-                // P is still the neutral element: P (op) psi = psi, no product needed
-                float es[D];
-#pragma unroll
-                for (int j = 0; j < D; ++j) es[j] = S::is_max_plus ? ev[j] : ldexpf(ev[j], WORK_BIAS);
-#pragma unroll
-                for (int i = 0; i < D; ++i)
-#pragma unroll
-                    for (int j = 0; j < D; ++j) {
-                        const float a = first ? ((i == j) ? S::one() : S::zero()) : Am[i * D + j];
-                        P.m[i * D + j] = S::times(a, es[j]);
-                    }
-                if constexpr (!S::is_max_plus) {
-#pragma unroll
-                    for (int i = 0; i < D; ++i) P.ex[i] = -WORK_BIAS;
-                    room = spread - PER_STEP;
-                }
-            } else {
-                if constexpr (!S::is_max_plus) {
-                    room += spread - PER_STEP;
-                    if (wave_any(room < -(float)WORK_ROOM)) {
-                        agg_renorm<S, D, WORK_BIAS>(P);
-                        room = spread - PER_STEP;
-                    }
-                }
-                absorb<S, D>(P.m, Am, ev);
-            }
-            if ((k & 3) == 3) {
-                agg_renorm<S, D, WORK_BIAS>(P);
-                room = 0.0f;
-            }
+            float bits, spread;
+            lds_read_vec<D>(row + k * D, F.E[k]);
+            emission<S, D>(F.E[k], bits, spread);
+            if constexpr (STORE_E) lds_write_vec<D>(row + k * D, F.E[k]);
+            F.csum += bits;
+            F.lost[k / 4] += spread - PER_STEP;
         }
     }
-    agg_renorm<S, D, ROW_BIAS>(P);
-    P.c += (double)csum;
+}
+
+// U: uniform mode (see the *_u operations): `bad` reports that the general operations are needed.
+template <class S, int D, bool FULL, bool U>
+HMM_DEV void chunk_products(const ChunkFactors<S, D>& F, int n, bool first, const float (&Am)[D * D], Agg<S, D>& P,
+                            bool& bad) {
+    using C = SmallCfg<D>;
+    agg_identity<S, D>(P);
+#pragma unroll
+    for (int b = 0; b < C::L / 4; ++b) {
+        if (FULL || 4 * b < n) {
+            bool tight = false;
+            if constexpr (!S::is_max_plus) {
+                if constexpr (U) bad = bad || (F.lost[b] < -(float)WORK_ROOM);
+                else tight = wave_any(F.lost[b] < -(float)WORK_ROOM);
+            }
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+                const int k = 4 * b + kk;
+                if (FULL || k < n) {
+                    if (k == 0) {
+                        // P is still the neutral element: P (op) psi = psi, no product needed
+                        float es[D];
+#pragma unroll
+                        for (int j = 0; j < D; ++j) es[j] = S::is_max_plus ? F.E[0][j] : ldexpf(F.E[0][j], WORK_BIAS);
+#pragma unroll
+                        for (int i = 0; i < D; ++i)
+#pragma unroll
+                            for (int j = 0; j < D; ++j) {
+                                const float a = first ? ((i == j) ? S::one() : S::zero()) : Am[i * D + j];
+                                P.m[i * D + j] = S::times(a, es[j]);
+                            }
+                        if constexpr (!S::is_max_plus) {
+#pragma unroll
+                            for (int i = 0; i < D; ++i) P.ex[i] = -WORK_BIAS;
+                        }
+                    } else {
+                        if constexpr (!U) {
+                            if (tight && kk > 0) agg_renorm<S, D, WORK_BIAS>(P);
+                        }
+                        absorb<S, D>(P.m, Am, F.E[k]);
+                    }
+                }
+            }
+            if (4 * b + 4 == C::L) agg_renorm_m<U, S, D, ROW_BIAS>(P, bad);   // (b is a constant once the loop is unrolled)
+            else agg_renorm_m<U, S, D, WORK_BIAS>(P, bad);
+        }
+    }
+    if constexpr (!FULL) agg_renorm_m<U, S, D, ROW_BIAS>(P, bad);
+    P.c += (double)F.csum;
+}
+
+template <class S, int D, bool STORE_E, bool FULL>
+HMM_DEV void chunk_aggregate_impl(float* row, int n, bool first, const float (&Am)[D * D], Agg<S, D>& P) {
+    ChunkFactors<S, D> F;
+    bool unused = false;
+    chunk_emissions<S, D, STORE_E, FULL>(row, n, F);
+    chunk_products<S, D, FULL, false>(F, n, first, Am, P, unused);
 }
 
 template <class S, int D, bool STORE_E>
 HMM_DEV void chunk_aggregate(float* row, int n, bool first, const float (&Am)[D * D], Agg<S, D>& P) {
     if (n == SmallCfg<D>::L) chunk_aggregate_impl<S, D, STORE_E, true>(row, n, first, Am, P);
     else chunk_aggregate_impl<S, D, STORE_E, false>(row, n, first, Am, P);
+}
+
+// The same, in uniform mode where the data allow it (decided per wavefront).  uni: every lane's P came out
+// of the uniform operations (its row exponents are all equal).
+template <class S, int D, bool STORE_E, bool FULL>
+HMM_DEV bool chunk_aggregate_auto_impl(float* row, int n, bool first, const float (&Am)[D * D], Agg<S, D>& P) {
+    ChunkFactors<S, D> F;
+    chunk_emissions<S, D, STORE_E, FULL>(row, n, F);
+    bool bad = false;
+    chunk_products<S, D, FULL, true>(F, n, first, Am, P, bad);
+    if constexpr (S::is_max_plus) return false;
+    if (!wave_any(bad)) return false;
+    chunk_products<S, D, FULL, false>(F, n, first, Am, P, bad);
+    return true;
+}
+
+template <class S, int D, bool STORE_E>
+HMM_DEV void chunk_aggregate_auto(float* row, int n, bool first, const float (&Am)[D * D], Agg<S, D>& P, bool& uni) {
+    bool general;
+    if (n == SmallCfg<D>::L) general = chunk_aggregate_auto_impl<S, D, STORE_E, true>(row, n, first, Am, P);
+    else general = chunk_aggregate_auto_impl<S, D, STORE_E, false>(row, n, first, Am, P);
+    uni = !wave_any(general);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -367,25 +427,56 @@ HMM_DEV void agg_load(const float* p, Agg<S, D>& Q) {
 // four shifts inside each row of 16 lanes, then the last lane of a row broadcast to the next
 // row(s).  A lane that has no source at some level combines with the operator's neutral
 // element instead, so no lane needs to be predicated.
-template <class S, int D, bool SWAP, int CTRL, int ROW_MASK, bool TRACK_C>
-HMM_DEV void wave_scan_level(Agg<S, D>& Q) {
+template <class S, int D, bool SWAP, int CTRL, int ROW_MASK, bool TRACK_C, bool U>
+HMM_DEV void wave_scan_level(Agg<S, D>& Q, bool& bad) {
     Agg<S, D> N, Z;
     agg_dpp<S, D, CTRL, ROW_MASK, TRACK_C>(Q, N);
-    if constexpr (SWAP) agg_mul<S, D, TRACK_C>(Q, N, Z);
-    else agg_mul<S, D, TRACK_C>(N, Q, Z);
+    if constexpr (SWAP) agg_mul_m<U, S, D, TRACK_C>(Q, N, Z, bad);
+    else agg_mul_m<U, S, D, TRACK_C>(N, Q, Z, bad);
     Q = Z;
+}
+
+template <class S, int D, bool SWAP, int CTRL, int ROW_MASK, bool TRACK_C>
+HMM_DEV void wave_scan_level(Agg<S, D>& Q) {
+    bool unused = false;
+    wave_scan_level<S, D, SWAP, CTRL, ROW_MASK, TRACK_C, false>(Q, unused);
 }
 
 // Inclusive scan towards higher lanes.  SWAP = false: Q_t <- P_0 (op) ... (op) P_t;
 // SWAP = true: Q_t <- P_t (op) ... (op) P_0 (the operator's arguments exchanged).
+// U: uniform mode, `bad` as in the *_u operations.
+template <class S, int D, bool SWAP, bool TRACK_C, bool U>
+HMM_DEV void wave_scan_up(Agg<S, D>& Q, bool& bad) {
+    wave_scan_level<S, D, SWAP, 0x111, 0xF, TRACK_C, U>(Q, bad);   // row_shr:1
+    wave_scan_level<S, D, SWAP, 0x112, 0xF, TRACK_C, U>(Q, bad);   // row_shr:2
+    wave_scan_level<S, D, SWAP, 0x114, 0xF, TRACK_C, U>(Q, bad);   // row_shr:4
+    wave_scan_level<S, D, SWAP, 0x118, 0xF, TRACK_C, U>(Q, bad);   // row_shr:8
+    wave_scan_level<S, D, SWAP, 0x142, 0xA, TRACK_C, U>(Q, bad);   // row_bcast:15 into rows 1 and 3
+    wave_scan_level<S, D, SWAP, 0x143, 0xC, TRACK_C, U>(Q, bad);   // row_bcast:31 into rows 2 and 3
+}
 template <class S, int D, bool SWAP, bool TRACK_C>
 HMM_DEV void wave_scan_up(Agg<S, D>& Q) {
-    wave_scan_level<S, D, SWAP, 0x111, 0xF, TRACK_C>(Q);   // row_shr:1
-    wave_scan_level<S, D, SWAP, 0x112, 0xF, TRACK_C>(Q);   // row_shr:2
-    wave_scan_level<S, D, SWAP, 0x114, 0xF, TRACK_C>(Q);   // row_shr:4
-    wave_scan_level<S, D, SWAP, 0x118, 0xF, TRACK_C>(Q);   // row_shr:8
-    wave_scan_level<S, D, SWAP, 0x142, 0xA, TRACK_C>(Q);   // row_bcast:15 into rows 1 and 3
-    wave_scan_level<S, D, SWAP, 0x143, 0xC, TRACK_C>(Q);   // row_bcast:31 into rows 2 and 3
+    bool unused = false;
+    wave_scan_up<S, D, SWAP, TRACK_C, false>(Q, unused);
+}
+
+// The scan in uniform mode if every lane's element is uniform (uni, a fact about the whole wavefront) and stays
+// so, else with the general operations; uni is updated to describe the results.
+template <class S, int D, bool SWAP, bool TRACK_C>
+HMM_DEV void wave_scan_up_auto(Agg<S, D>& Q, bool& uni) {
+    if constexpr (S::is_max_plus) {
+        wave_scan_up<S, D, SWAP, TRACK_C>(Q);
+    } else {
+        if (uni) {
+            const Agg<S, D> Q0 = Q;
+            bool bad = false;
+            wave_scan_up<S, D, SWAP, TRACK_C, true>(Q, bad);
+            if (!wave_any(bad)) return;
+            Q = Q0;
+            uni = false;
+        }
+        wave_scan_up<S, D, SWAP, TRACK_C>(Q);
+    }
 }
 
 template <class S, int D>
@@ -405,14 +496,53 @@ HMM_DEV void wave_scan_suffix(Agg<S, D>& R) {
     agg_shfl<S, D, false>(T, mirror, R);
 }
 
+template <class S, int D>
+HMM_DEV void wave_scan_suffix_auto(Agg<S, D>& R, bool& uni) {
+    const int mirror = 63 - (int)(threadIdx.x & 63);
+    Agg<S, D> T;
+    agg_shfl<S, D, false>(R, mirror, T);
+    wave_scan_up_auto<S, D, true, false>(T, uni);
+    agg_shfl<S, D, false>(T, mirror, R);
+}
+
+// Sum of one double per lane over the wavefront (every lane gets it).
+HMM_DEV double wave_sum(double v) {
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) v += __shfl_xor(v, d, 64);
+    return v;
+}
+
 // Inclusive prefix scan inside each wave; the wave totals go to wagg[NW][AggImage::WORDS] in LDS.
-// The caller must __syncthreads() before reading wagg.
+// The caller must __syncthreads() before reading wagg.  SumProd: the common scale c of an aggregate is a
+// plain sum over its elements, so it does not ride along the scan; only the wave total gets it (the scanned
+// aggregates Q of the other lanes carry no c).
 template <class S, int D>
 HMM_DEV void block_prefix(const Agg<S, D>& P, Agg<S, D>& Q, float* wagg) {
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     Q = P;
-    wave_scan_prefix<S, D>(Q);
+    if constexpr (S::is_max_plus) {
+        wave_scan_up<S, D, false, true>(Q);
+    } else {
+        wave_scan_up<S, D, false, false>(Q);
+        Q.c = wave_sum(P.c);
+    }
+    if (lane == 63) agg_store<S, D>(wagg + wave * AggImage<D>::WORDS, Q);
+}
+
+// The same with the scan in uniform mode where possible; uni: in, the P of every lane of the wavefront are
+// uniform; out, so are the Q.
+template <class S, int D>
+HMM_DEV void block_prefix_auto(const Agg<S, D>& P, Agg<S, D>& Q, float* wagg, bool& uni) {
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    Q = P;
+    if constexpr (S::is_max_plus) {
+        wave_scan_up<S, D, false, true>(Q);
+    } else {
+        wave_scan_up_auto<S, D, false, false>(Q, uni);
+        Q.c = wave_sum(P.c);
+    }
     if (lane == 63) agg_store<S, D>(wagg + wave * AggImage<D>::WORDS, Q);
 }
 
@@ -433,57 +563,102 @@ HMM_DEV void block_total(const float* wagg, Agg<S, D>& X) {
 // Scale-free vectors: forward potentials are kept with their sum in [0.5, 1) (SumProd) / largest entry 0
 // (MaxPlus), backward potentials with their largest entry in [0.5, 1) / at 0.
 
+// Products of the wave totals, formed once per workgroup by wave_products (below) while nothing else is
+// pending: wpre[w-1] = W_0 (op) ... (op) W_{w-1} and wsuf[w-1] = W_w (op) ... (op) W_{NW-1} for w = 1 .. NW-1,
+// as aggregate images.  With them a lane reaches its carries in two steps instead of up to NW.
+template <int D>
+struct WaveProducts {
+    static constexpr int W = AggImage<D>::WORDS;
+    alignas(8) float wpre[(SmallCfg<D>::NW - 1) * W];
+    alignas(8) float wsuf[(SmallCfg<D>::NW - 1) * W];
+};
+
 // fin = cin_f (op) P_0 (op) ... (op) P_{t-1}: the forward potential just before lane t's chunk,
-// from the lane's inclusive wave prefix Q and the wave totals.
-template <class S, int D>
-HMM_DEV void carry_forward(const Agg<S, D>& Q, const float* wagg, const float (&cin_f)[D], float (&fin)[D]) {
+// from the lane's inclusive wave prefix Q and the wave totals (wp != nullptr: their products).
+// U: uniform mode (Q must be uniform; `bad` reports a wave product that is not).
+template <class S, int D, bool U>
+HMM_DEV void carry_forward(const Agg<S, D>& Q, const float* wagg, const WaveProducts<D>* wp, const float (&cin_f)[D],
+                           float (&fin)[D], bool& bad) {
     using C = SmallCfg<D>;
+    constexpr int W = AggImage<D>::WORDS;
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     float fw[D];
 #pragma unroll
     for (int j = 0; j < D; ++j) fw[j] = cin_f[j];
+    auto through = [&](const float* src) {
+        Agg<S, D> Wm;
+        float r[D];
+        agg_load<S, D>(src, Wm);
+        if constexpr (U && !S::is_max_plus) bad = bad || !agg_is_uniform<D>(Wm);
+        vec_agg_m<U, S, D>(fw, Wm, r);
 #pragma unroll
-    for (int w = 0; w < C::NW - 1; ++w) {
-        if (w < wave) {
-            Agg<S, D> Wm;
-            float r[D];
-            agg_load<S, D>(wagg + w * AggImage<D>::WORDS, Wm);
-            vec_agg<S, D>(fw, Wm, r);
+        for (int j = 0; j < D; ++j) fw[j] = r[j];
+    };
+    if (wp != nullptr) {
+        if (wave > 0) through(wp->wpre + (wave - 1) * W);
+    } else {
 #pragma unroll
-            for (int j = 0; j < D; ++j) fw[j] = r[j];
+        for (int w = 0; w < C::NW - 1; ++w) {
+            if (w < wave) through(wagg + w * W);
         }
     }
     Agg<S, D> Qp;
     float r[D];
     agg_shfl<S, D, false>(Q, (lane + 63) & 63, Qp);   // the lane below (lane 0 does not use it)
-    vec_agg<S, D>(fw, Qp, r);
+    vec_agg_m<U, S, D>(fw, Qp, r);
 #pragma unroll
     for (int j = 0; j < D; ++j) fin[j] = (lane == 0) ? fw[j] : r[j];
+}
+template <class S, int D>
+HMM_DEV void carry_forward(const Agg<S, D>& Q, const float* wagg, const WaveProducts<D>* wp, const float (&cin_f)[D],
+                           float (&fin)[D]) {
+    bool unused = false;
+    carry_forward<S, D, false>(Q, wagg, wp, cin_f, fin, unused);
+}
+// uni: every lane's Q is uniform
+template <class S, int D>
+HMM_DEV void carry_forward_auto(const Agg<S, D>& Q, bool uni, const float* wagg, const WaveProducts<D>* wp,
+                                const float (&cin_f)[D], float (&fin)[D]) {
+    if constexpr (!S::is_max_plus) {
+        if (uni) {
+            bool bad = false;
+            carry_forward<S, D, true>(Q, wagg, wp, cin_f, fin, bad);
+            if (!wave_any(bad)) return;
+        }
+    }
+    carry_forward<S, D>(Q, wagg, wp, cin_f, fin);
 }
 
 // The backward potential at the last step of lane t's chunk, P_{t+1} (op) ... (op) P_{NT-1} (op) cin_b, from the
 // lane's inclusive wave suffix R and the wave totals, as a vector of mantissas with one exponent per entry
 // (SumProd; EX_NONE marks a zero) -- the chunk's backward recursion picks the common scale itself, see
 // backward_plain -- or shifted to largest entry 0 (MaxPlus; the exponents are not used).
-template <class S, int D>
-HMM_DEV void carry_backward(const Agg<S, D>& R, const float* wagg, const float (&cin_b)[D], float (&bout)[D],
-                            int (&bex)[D]) {
+template <class S, int D, bool U>
+HMM_DEV void carry_backward(const Agg<S, D>& R, const float* wagg, const WaveProducts<D>* wp, const float (&cin_b)[D],
+                            float (&bout)[D], int (&bex)[D], bool& bad) {
     using C = SmallCfg<D>;
+    constexpr int W = AggImage<D>::WORDS;
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     float bw[D];
 #pragma unroll
     for (int j = 0; j < D; ++j) bw[j] = cin_b[j];
+    auto through = [&](const float* src) {
+        Agg<S, D> Wm;
+        float r[D];
+        agg_load<S, D>(src, Wm);
+        if constexpr (U && !S::is_max_plus) bad = bad || !agg_is_uniform<D>(Wm);
+        agg_vec_m<U, S, D>(Wm, bw, r);
 #pragma unroll
-    for (int w = C::NW - 1; w > 0; --w) {
-        if (w > wave) {
-            Agg<S, D> Wm;
-            float r[D];
-            agg_load<S, D>(wagg + w * AggImage<D>::WORDS, Wm);
-            agg_vec<S, D>(Wm, bw, r);
+        for (int j = 0; j < D; ++j) bw[j] = r[j];
+    };
+    if (wp != nullptr) {
+        if (wave < C::NW - 1) through(wp->wsuf + wave * W);   // W_{wave+1} (op) ... (op) W_{NW-1}
+    } else {
 #pragma unroll
-            for (int j = 0; j < D; ++j) bw[j] = r[j];
+        for (int w = C::NW - 1; w > 0; --w) {
+            if (w > wave) through(wagg + w * W);
         }
     }
     Agg<S, D> Rn;
@@ -508,6 +683,26 @@ HMM_DEV void carry_backward(const Agg<S, D>& R, const float* wagg, const float (
     }
 }
 
+template <class S, int D>
+HMM_DEV void carry_backward(const Agg<S, D>& R, const float* wagg, const WaveProducts<D>* wp, const float (&cin_b)[D],
+                            float (&bout)[D], int (&bex)[D]) {
+    bool unused = false;
+    carry_backward<S, D, false>(R, wagg, wp, cin_b, bout, bex, unused);
+}
+// uni: every lane's R is uniform (the last step, R against the wave's vector, is the same in both modes)
+template <class S, int D>
+HMM_DEV void carry_backward_auto(const Agg<S, D>& R, bool uni, const float* wagg, const WaveProducts<D>* wp,
+                                 const float (&cin_b)[D], float (&bout)[D], int (&bex)[D]) {
+    if constexpr (!S::is_max_plus) {
+        if (uni) {
+            bool bad = false;
+            carry_backward<S, D, true>(R, wagg, wp, cin_b, bout, bex, bad);
+            if (!wave_any(bad)) return;
+        }
+    }
+    carry_backward<S, D>(R, wagg, wp, cin_b, bout, bex);
+}
+
 // Both carries for every lane of the workgroup (contains one __syncthreads()); the backward one in the raw
 // form of carry_backward.
 template <class S, int D, bool BWD>
@@ -516,11 +711,11 @@ HMM_DEV void block_exchange(const Agg<S, D>& P, const float (&cin_f)[D], const f
     Agg<S, D> Q;
     block_prefix<S, D>(P, Q, wagg);
     __syncthreads();
-    carry_forward<S, D>(Q, wagg, cin_f, fin);
+    carry_forward<S, D>(Q, wagg, nullptr, cin_f, fin);
     if constexpr (BWD) {
         Agg<S, D> R = P;
         wave_scan_suffix<S, D>(R);
-        carry_backward<S, D>(R, wagg, cin_b, bout, bex);
+        carry_backward<S, D>(R, wagg, nullptr, cin_b, bout, bex);
     }
 }
 

@@ -14,6 +14,8 @@
 // aggregate of the whole sequence, whose scale is tracked exactly (semiring.hpp), by one lane per
 // sequence; the per-step recursions carry no scale.
 #include <hip/hip_runtime.h>
+
+#include <type_traits>
 #include <stdint.h>
 #include <stdlib.h>
 
@@ -27,64 +29,153 @@
 
 namespace hmm {
 
-// The workgroup's aggregate W_0 (op) ... (op) W_{NW-1} from the wave totals in wagg, formed row by row:
-// lane i < D of the first wave owns row i of the running product (rows of a product depend on the left
-// factor's row only), so the chain costs D^2 multiply-adds per lane and step instead of whole matrix
-// products in one lane.  The result goes to `image` (LDS) and, if slots != nullptr, to the tile's tagged
-// exchange slots.  Call from the whole first wave; wagg must be visible (barrier before).
-template <class S, int D>
-HMM_DEV void tile_total_rows(const float* wagg, float* image, unsigned long long* slots, uint32_t tag) {
+// An exchange record in the workspace: the AggImage words as tagged words, one record per tile.  Every word
+// validates itself (no ordering between stores is relied upon); the tile's seal, a tagged word in a separate
+// array written after the record, only tells readers when reading the record is worth while, so that the
+// wait polls one word per tile instead of whole records.
+template <int D>
+struct SlotRecord {
+    static constexpr int W = AggImage<D>::WORDS;
+    static constexpr int STRIDE = W;
+};
+
+// Products of the wave totals in wagg, formed row by row: lane i < D of a wave owns row i of the running
+// product (rows of a product depend on the left factor's row only), so a step costs D^2 multiply-adds per
+// lane instead of a whole matrix product in one lane.
+//   wave 0: W_0 (op) ... (op) W_w for w = 1 .. NW-1; the last one is the workgroup's aggregate, which goes
+//           to `image` (LDS) and is returned as the calling lane's row (x, xe, c) for publication; the
+//           others go to wp->wpre if wp != nullptr;
+//   wave 1: W_w (op) ... (op) W_{NW-1} for w = NW-1 .. 1, to wp->wsuf (only if wp != nullptr).
+// U: uniform mode -- the wave totals must be uniform and the products are kept uniform (all rows take the
+// exponent of the largest); `bad` reports where that fails.
+template <class S, int D, bool U>
+HMM_DEV void wave_products_impl(const float* wagg, float* image, WaveProducts<D>* wp, float (&x)[D], int& xe, double& c,
+                                bool& bad) {
     using C = SmallCfg<D>;
     constexpr int W = AggImage<D>::WORDS;
+    constexpr int NW = C::NW;
+    constexpr bool UNI = U && !S::is_max_plus;
+    const int wave = threadIdx.x >> 6;
     const int lane = threadIdx.x & 63;
     const int i = lane < D ? lane : 0;   // spare lanes shadow row 0 and never store
-    float x[D];
+    auto take_row = [&](const float* src) {
 #pragma unroll
-    for (int j = 0; j < D; ++j) x[j] = wagg[i * D + j];
-    int xe = reinterpret_cast<const int*>(wagg)[D * D + i];   // SumProd: the row's exponent
-    double ro = 0.0;                                            // MaxPlus: the row's own offset
-    double c = *reinterpret_cast<const double*>(wagg + D * D + D);
+        for (int j = 0; j < D; ++j) x[j] = src[i * D + j];
+        xe = reinterpret_cast<const int*>(src)[D * D + i];   // SumProd: the row's exponent
+        c = *reinterpret_cast<const double*>(src + D * D + D);
+        if constexpr (UNI) bad = bad || (xe != reinterpret_cast<const int*>(src)[D * D]);
+    };
+    auto put_row = [&](float* dst) {
+        if (lane < D) {
 #pragma unroll
-    for (int w = 1; w < C::NW; ++w) {
-        Agg<S, D> Wm;
-        float r[D];
-        agg_load<S, D>(wagg + w * W, Wm);
-        const double sc = vec_agg<S, D>(x, Wm, r);
-        if constexpr (S::is_max_plus) ro += sc;
-        else xe += (int)sc + (VEC_BIAS - ROW_BIAS);   // vec_agg leaves the row at the height of a vector: back to a row's
-        c += Wm.c;
-#pragma unroll
-        for (int j = 0; j < D; ++j) x[j] = S::is_max_plus ? r[j] : ldexpf(r[j], ROW_BIAS - VEC_BIAS);
-    }
-    if constexpr (S::is_max_plus) {
-        // one common offset per matrix: the largest row offset (rows that are entirely -inf report 0 and
-        // stay -inf whatever is added)
-        double top = __shfl(ro, 0, 64);
-#pragma unroll
-        for (int k = 1; k < D; ++k) {
-            const double o = __shfl(ro, k, 64);
-            top = o > top ? o : top;
+            for (int j = 0; j < D; ++j) dst[i * D + j] = x[j];
+            reinterpret_cast<int*>(dst)[D * D + i] = xe;
+            if (lane == 0) *reinterpret_cast<double*>(dst + D * D + D) = c;
         }
-        const float d = (float)(ro - top);
+    };
+    // row (op) M, as a row of an aggregate again
+    auto times = [&](const float* src) {
+        Agg<S, D> M;
+        float r[D];
+        agg_load<S, D>(src, M);
+        if constexpr (UNI) bad = bad || !agg_is_uniform<D>(M);
+        const double sc = vec_agg_m<U, S, D>(x, M, r);
+        c += M.c;
+        if constexpr (S::is_max_plus) {
+            // each row comes out with an offset of its own; an aggregate has one: the largest (rows that are
+            // entirely -inf report 0 and stay -inf whatever is added)
+            double top = __shfl(sc, 0, 64);
 #pragma unroll
-        for (int j = 0; j < D; ++j) x[j] += d;
-        c += top;
-        xe = 0;
-    }
-    if (lane < D) {
-#pragma unroll
-        for (int j = 0; j < D; ++j) image[i * D + j] = x[j];
-        reinterpret_cast<int*>(image)[D * D + i] = xe;
-        if (lane == 0) *reinterpret_cast<double*>(image + D * D + D) = c;
-        if (slots != nullptr) {
-#pragma unroll
-            for (int j = 0; j < D; ++j) publish_word(slots + i * D + j, x[j], tag);
-            publish_word(slots + D * D + i, (uint32_t)xe, tag);
-            if (lane == 0) {
-                const unsigned long long cb = (unsigned long long)__double_as_longlong(c);
-                publish_word(slots + D * D + D, (uint32_t)cb, tag);
-                publish_word(slots + D * D + D + 1, (uint32_t)(cb >> 32), tag);
+            for (int k = 1; k < D; ++k) {
+                const double o = __shfl(sc, k, 64);
+                top = o > top ? o : top;
             }
+            const float d = (float)(sc - top);
+#pragma unroll
+            for (int j = 0; j < D; ++j) x[j] = r[j] + d;
+            c += top;
+        } else if constexpr (UNI) {
+            // the row came out at the height of a vector with its own exponent: all rows take the largest
+            const int own = xe + (int)sc;
+            int top = __shfl(own, 0, 64);
+#pragma unroll
+            for (int k = 1; k < D; ++k) top = max_of_int(top, __shfl(own, k, 64));
+            bad = bad || (top - own > UNIFORM_SPREAD);
+            const int down = max_of_int(own - top, -200);
+#pragma unroll
+            for (int j = 0; j < D; ++j) x[j] = ldexpf(r[j], ROW_BIAS - VEC_BIAS + down);
+            xe = top + (VEC_BIAS - ROW_BIAS);
+        } else {
+            // vec_agg leaves the row at the height of a vector: back to a row's
+            xe += (int)sc + (VEC_BIAS - ROW_BIAS);
+#pragma unroll
+            for (int j = 0; j < D; ++j) x[j] = ldexpf(r[j], ROW_BIAS - VEC_BIAS);
+        }
+    };
+    if (wave == 0) {
+        take_row(wagg);
+        if (wp != nullptr) put_row(wp->wpre);
+#pragma unroll
+        for (int w = 1; w < NW; ++w) {
+            times(wagg + w * W);
+            if (w < NW - 1) {
+                if (wp != nullptr) put_row(wp->wpre + w * W);
+            }
+        }
+        put_row(image);
+    } else {
+        take_row(wagg + (NW - 1) * W);
+        put_row(wp->wsuf + (NW - 2) * W);
+#pragma unroll
+        for (int w = NW - 2; w >= 1; --w) {
+            // the product so far was written by this wave's own lanes just above: order the reads behind it
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            take_row(wagg + w * W);
+            times(wp->wsuf + w * W);
+            put_row(wp->wsuf + (w - 1) * W);
+        }
+    }
+}
+
+// Call from the whole workgroup after the barrier that makes wagg visible; the LDS results are visible to the
+// other waves after the next barrier.  If slots != nullptr the workgroup's aggregate also goes to the tile's
+// exchange record, followed by its seal.  AUTO: uniform mode where the wave totals allow it.
+template <class S, int D, bool AUTO>
+HMM_DEV void wave_products(const float* wagg, float* image, WaveProducts<D>* wp, unsigned long long* slots,
+                           unsigned long long* seal, uint32_t tag) {
+    const int wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    if (wave > 1 || (wave == 1 && wp == nullptr)) return;
+    float x[D];
+    int xe;
+    double c;
+    bool general = true;
+    if constexpr (AUTO && !S::is_max_plus) {
+        bool bad = false;
+        wave_products_impl<S, D, true>(wagg, image, wp, x, xe, c, bad);
+        general = wave_any(bad);
+        if (general) {   // what the uniform pass left in LDS is rewritten from scratch
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        }
+    }
+    if (general) {
+        bool unused = false;
+        wave_products_impl<S, D, false>(wagg, image, wp, x, xe, c, unused);
+    }
+    if (wave == 0 && slots != nullptr && lane < D) {
+        const int i = lane;
+#pragma unroll
+        for (int j = 0; j < D; ++j) publish_word(slots + i * D + j, x[j], tag);
+        publish_word(slots + D * D + i, (uint32_t)(S::is_max_plus ? 0 : xe), tag);
+        if (lane == 0) {
+            const unsigned long long cb = (unsigned long long)__double_as_longlong(c);
+            publish_word(slots + D * D + D, (uint32_t)cb, tag);
+            publish_word(slots + D * D + D + 1, (uint32_t)(cb >> 32), tag);
+            publish_word(seal, 1u, tag);
         }
     }
 }
@@ -113,7 +204,7 @@ __global__ __launch_bounds__(256) void sd_reduce_kernel(const float* __restrict_
     chunk_aggregate<S, D, false>(lds + threadIdx.x * C::STRIDE, n, tc.tile == 0 && threadIdx.x == 0, Am, P);
     block_prefix<S, D>(P, Q, wagg);
     __syncthreads();
-    if (threadIdx.x < 64) tile_total_rows<S, D>(wagg, wtot, nullptr, 0u);
+    wave_products<S, D, false>(wagg, wtot, nullptr, nullptr, nullptr, 0u);
     __syncthreads();
     if (threadIdx.x < W) agg[(size_t)blockIdx.x * W + threadIdx.x] = wtot[threadIdx.x];
 }
@@ -390,7 +481,8 @@ __global__ void sd_zero_kernel(uint32_t* __restrict__ p, size_t n) {
 
 struct FusedWs {
     XchHeader* hdr;             // generation, poison flag, finished-sequence counter
-    unsigned long long* agg;    // [tiles][AggImage::WORDS] tagged words: tile aggregates
+    unsigned long long* agg;    // [tiles][SlotRecord::STRIDE] tagged words: tile aggregates
+    unsigned long long* seal;   // [tiles] tagged words: the tile's record is complete
     unsigned long long* tmap;   // [tiles] tagged words: tile back-pointer maps (Viterbi)
     int batch;                  // sequences in the call
     int spin_limit;             // polls before a wait gives up (every wave terminates whatever the other workgroups do)
@@ -399,10 +491,10 @@ struct FusedWs {
 // LDS scratch of the inter-tile exchange: the tile aggregates of the sequence, one record per tile with an
 // odd stride so that lanes reading one record each do not collide on LDS banks, and the per-wave reductions.
 template <int D>
-struct GridLds {
+struct alignas(8) GridLds {
     static constexpr int W = AggImage<D>::WORDS;
     static constexpr int RSTR = W | 1;
-    float red[SmallCfg<D>::NW * W];
+    alignas(8) float red[SmallCfg<D>::NW * W];   // (aggregate images hold a double: 8-byte alignment)
     float aggs[SmallCfg<D>::NT * RSTR];
 };
 
@@ -434,14 +526,36 @@ HMM_DEV CallTag call_tag(const unsigned long long* shared_word) {               
     return t;
 }
 
-// All lanes: poll n consecutive tagged words at `src` (slots written by other workgroups) until all of
-// them carry the call's tag, staging the values into LDS records of `w` words at stride `rstr`.
-// Returns false if the bounded wait ran out.
-template <int w, int rstr>
-HMM_DEV bool gather_tagged(const unsigned long long* src, int n, float* dst_lds, uint32_t tag, int spin_limit) {
+// All lanes: wait until `nrec` (<= blockDim.x) consecutive tagged words starting at `src` carry the call's tag,
+// one lane per word; lane t < nrec gets word t's value.  Returns false if the bounded wait ran out.
+HMM_DEV bool await_words(const unsigned long long* src, int nrec, uint32_t tag, int spin_limit, uint32_t& value) {
+    const bool mine = (int)threadIdx.x < nrec;
+    const unsigned long long* p = src + (mine ? (int)threadIdx.x : 0);
+    // two polls in flight: the next one is already under way while the barrier judges this one, so a word
+    // is seen one memory round trip after it lands instead of up to two
+    unsigned long long v0 = coherent_load(p);
     for (int spin = 0; spin < spin_limit; ++spin) {
+        const unsigned long long v1 = coherent_load(p);
+        const bool valid = !mine || (uint32_t)(v0 >> 32) == tag;
+        if (__syncthreads_and(valid ? 1 : 0)) {
+            value = (uint32_t)v0;
+            return true;
+        }
+        v0 = v1;
+    }
+    return false;
+}
+
+// All lanes: the records of `nrec` consecutive tiles into LDS records at stride RSTR, re-read until every word
+// carries the call's tag (after the seals have been seen that is normally the first attempt).  Returns false
+// if the bounded wait ran out.  Contains the barrier after which everyone may read the staged records.
+template <int D>
+HMM_DEV bool stage_records(const unsigned long long* src, int nrec, float* dst_lds, uint32_t tag, int spin_limit) {
+    using G = GridLds<D>;
+    constexpr int NB = 8;   // loads in flight per lane
+    const int n = nrec * G::W;
+    for (int spin = 0; spin <= spin_limit; ++spin) {
         bool valid = true;
-        constexpr int NB = 8;   // loads in flight per lane: issued together, then checked and staged
         for (int base = 0; base < n; base += NB * (int)blockDim.x) {
             unsigned long long v[NB];
 #pragma unroll
@@ -454,20 +568,19 @@ HMM_DEV bool gather_tagged(const unsigned long long* src, int n, float* dst_lds,
                 const int i = base + q * (int)blockDim.x + (int)threadIdx.x;
                 if (i < n) {
                     valid = valid && (uint32_t)(v[q] >> 32) == tag;
-                    const int rec = i / w;
-                    dst_lds[rec * rstr + (i - rec * w)] = __uint_as_float((uint32_t)v[q]);
+                    const int rec = i / G::W;
+                    dst_lds[rec * G::RSTR + (i - rec * G::W)] = __uint_as_float((uint32_t)v[q]);
                 }
             }
         }
         if (__syncthreads_and(valid ? 1 : 0)) return true;
-        __builtin_amdgcn_s_sleep(1);
     }
     return false;
 }
 
 // Gather the aggregates of the sequence's tiles and return the vectors entering this tile with the
 // scales they were stripped of (bits for SumProd, an offset for MaxPlus):
-// cf = forward potential before its first step (prior (op) M_0 (op) ... (op) M_{c-1}),
+// cf = forward potential before its first step (start (op) M_0 (op) ... (op) M_{c-1}),
 // cb = backward potential at its last step (M_{c+1} (op) ... (op) M_{tps-1} (op) ones).
 // The two ordered products are masked reductions over at most 2*128 tile slots: the first two
 // waves reduce the tiles before c, the last two the tiles after c (tps <= NT).
@@ -478,7 +591,11 @@ HMM_DEV bool grid_gather(const TileCoord& tc, int tps, const float (&start)[D], 
     using G = GridLds<D>;
     static_assert(C::NW == 4, "the split below assumes four waves");
     const int tile0 = blockIdx.x - tc.tile;   // first tile of this sequence
-    const bool ok = gather_tagged<G::W, G::RSTR>(ws.agg + (size_t)tile0 * G::W, tps * G::W, gl.aggs, tag, ws.spin_limit);
+    uint32_t sealed;
+    bool ok = await_words(ws.seal + tile0, tps, tag, ws.spin_limit, sealed);
+    // phase@12: seals seen
+    if (ok) ok = stage_records<D>(ws.agg + (size_t)tile0 * SlotRecord<D>::STRIDE, tps, gl.aggs, tag, ws.spin_limit);
+    // phase@13: aggregates staged
     const int wave = threadIdx.x >> 6;
     const int lane = threadIdx.x & 63;
     const bool fwd_half = wave < 2;
@@ -492,40 +609,71 @@ HMM_DEV bool grid_gather(const TileCoord& tc, int tps, const float (&start)[D], 
         agg_identity<S, D>(Mb);
         if (use_a) agg_load_staged<S, D>(gl.aggs + ta * G::RSTR, Ma);
         if (use_b) agg_load_staged<S, D>(gl.aggs + tb * G::RSTR, Mb);
-        agg_mul<S, D, true>(Ma, Mb, X);
-        wave_scan_prefix<S, D>(X);                        // lane 63 ends with the wave's ordered product
+        // lane 63 ends with the wave's ordered product
+        if constexpr (S::is_max_plus) {
+            agg_mul<S, D, true>(Ma, Mb, X);
+            wave_scan_prefix<S, D>(X);
+        } else {
+            const double cs = wave_sum(Ma.c + Mb.c);      // the common scales just add up: no need to scan them
+            bool general = wave_any(!(agg_is_uniform<D>(Ma) && agg_is_uniform<D>(Mb)));
+            if (!general) {
+                bool bad = false;
+                agg_mul_u<D, false>(Ma, Mb, X, bad);
+                wave_scan_up<S, D, false, false, true>(X, bad);
+                general = wave_any(bad);
+            }
+            if (general) {
+                agg_mul<S, D, false>(Ma, Mb, X);
+                wave_scan_up<S, D, false, false>(X);
+            }
+            X.c = cs;
+        }
         if (lane == 63) agg_store<S, D>(gl.red + wave * G::W, X);
     }
     __syncthreads();
-    float v[D], r[D];
-    double vs = 0.0;
-#pragma unroll
-    for (int j = 0; j < D; ++j) v[j] = start[j];
-#pragma unroll
-    for (int w = 0; w < 2; ++w) {
-        Agg<S, D> Wm;
-        agg_load<S, D>(gl.red + w * G::W, Wm);
-        vs += Wm.c + vec_agg<S, D>(v, Wm, r);
-#pragma unroll
-        for (int j = 0; j < D; ++j) v[j] = r[j];
-    }
-    // the first tile starts from the prior exactly as given; every later tile's carry is rescaled
-#pragma unroll
-    for (int j = 0; j < D; ++j) cf[j] = (tc.tile == 0) ? start[j] : v[j];
-    cfs = (tc.tile == 0) ? 0.0 : vs;
-#pragma unroll
-    for (int j = 0; j < D; ++j) cb[j] = S::one();
-    cbs = 0.0;
+    // phase@15: reduced
+    // the wave products through the start vector / the vector of ones (every lane does the same work: no branch
+    // below diverges)
+    Agg<S, D> Wf[2], Wb[2];
+    agg_load<S, D>(gl.red + 0 * G::W, Wf[0]);
+    agg_load<S, D>(gl.red + 1 * G::W, Wf[1]);
+    bool uni = !S::is_max_plus;
+    if constexpr (!S::is_max_plus) uni = agg_is_uniform<D>(Wf[0]) && agg_is_uniform<D>(Wf[1]);
     if constexpr (BWD) {
-#pragma unroll
-        for (int w = 3; w >= 2; --w) {
-            Agg<S, D> Wm;
-            agg_load<S, D>(gl.red + w * G::W, Wm);
-            cbs += Wm.c + agg_vec<S, D>(Wm, cb, r);
-#pragma unroll
-            for (int j = 0; j < D; ++j) cb[j] = r[j];
-        }
+        agg_load<S, D>(gl.red + 2 * G::W, Wb[0]);
+        agg_load<S, D>(gl.red + 3 * G::W, Wb[1]);
+        if constexpr (!S::is_max_plus) uni = uni && agg_is_uniform<D>(Wb[0]) && agg_is_uniform<D>(Wb[1]);
     }
+    auto vectors = [&](auto mode) {
+        constexpr bool U = decltype(mode)::value;
+        float v[D], r[D];
+        double vs = 0.0;
+#pragma unroll
+        for (int j = 0; j < D; ++j) v[j] = start[j];
+#pragma unroll
+        for (int w = 0; w < 2; ++w) {
+            vs += Wf[w].c + vec_agg_m<U, S, D>(v, Wf[w], r);
+#pragma unroll
+            for (int j = 0; j < D; ++j) v[j] = r[j];
+        }
+        // the first tile starts from the prior exactly as given; every later tile's carry is rescaled
+#pragma unroll
+        for (int j = 0; j < D; ++j) cf[j] = (tc.tile == 0) ? start[j] : v[j];
+        cfs = (tc.tile == 0) ? 0.0 : vs;
+#pragma unroll
+        for (int j = 0; j < D; ++j) cb[j] = S::one();
+        cbs = 0.0;
+        if constexpr (BWD) {
+#pragma unroll
+            for (int w = 1; w >= 0; --w) {
+                cbs += Wb[w].c + agg_vec_m<U, S, D>(Wb[w], cb, r);
+#pragma unroll
+                for (int j = 0; j < D; ++j) cb[j] = r[j];
+            }
+        }
+    };
+    if (!wave_any(!uni)) vectors(std::true_type{});
+    else vectors(std::false_type{});
     if (!ok && threadIdx.x == 0) coherent_store(&ws.hdr->poison, 1u);
     return ok;   // false: the bounded wait ran out (the tiles were not all resident)
 }
@@ -561,7 +709,7 @@ __global__ __launch_bounds__(256) void sd_smooth_fused_kernel(const float* __res
     __shared__ float lds[C::LDS_FLOATS];
     // the filtering distributions of the tile are staged like the marginals, in the space the inter-tile exchange
     // has finished with by then (both do not fit beside the tile at D >= 7)
-    __shared__ union FusedShared {
+    __shared__ union alignas(8) FusedShared {
         GridLds<D> gl;
         float flds[WRITE_FILT ? C::LDS_FLOATS : 1];
     } sh;
@@ -569,6 +717,8 @@ __global__ __launch_bounds__(256) void sd_smooth_fused_kernel(const float* __res
     float* flds = sh.flds;
     __shared__ __align__(8) float wagg[C::NW * W];
     __shared__ __align__(8) float wtot[W];
+    __shared__ WaveProducts<D> wprod;
+    // phase: start
     const TileCoord tc = tile_coord<D>(T, tps);
     const bool alone = tps == 1;   // the sequence is this one tile: nothing to exchange, no wait anywhere
     float Am[D * D], start[D];
@@ -592,34 +742,33 @@ __global__ __launch_bounds__(256) void sd_smooth_fused_kernel(const float* __res
     const int n = min(max(tc.nvalid - (int)threadIdx.x * C::L, 0), C::L);
     const bool first = tc.tile == 0 && threadIdx.x == 0;
     Agg<S, D> P, Q, R;
-    chunk_aggregate<S, D, true>(row, n, first, Am, P);
+    bool uni_p, uni_q, uni_r;   // per wavefront: the lanes' P / Q / R all have equal row exponents
+    chunk_aggregate_auto<S, D, true>(row, n, first, Am, P, uni_p);
     // phase: chunk aggregates
-    block_prefix<S, D>(P, Q, wagg);
+    uni_q = uni_p;
+    block_prefix_auto<S, D>(P, Q, wagg, uni_q);
     __syncthreads();
     // phase: wave prefixes
     const bool publish = !alone && !ct.poisoned;
-    if (threadIdx.x < 64)
-        tile_total_rows<S, D>(wagg, wtot, publish ? ws.agg + (size_t)blockIdx.x * W : nullptr, ct.tag);
+    wave_products<S, D, true>(wagg, wtot, &wprod, publish ? ws.agg + (size_t)blockIdx.x * SlotRecord<D>::STRIDE : nullptr,
+                        ws.seal + blockIdx.x, ct.tag);
     // phase: published
     // the suffix scan needs nothing from other tiles: it runs while their aggregates arrive
     R = P;
-    wave_scan_suffix<S, D>(R);
+    uni_r = uni_p;
+    wave_scan_suffix_auto<S, D>(R, uni_r);
+    // phase: suffix scan
     float cf[D], cb[D];
     double cfs = 0.0, cbs = 0.0;
     bool ok = true;
-    if (alone) {
+    if (alone || ct.poisoned) {
+        ok = alone;
 #pragma unroll
         for (int j = 0; j < D; ++j) {
             cf[j] = start[j];
             cb[j] = S::one();
         }
-    } else if (ct.poisoned) {
-        ok = false;
-#pragma unroll
-        for (int j = 0; j < D; ++j) {
-            cf[j] = start[j];
-            cb[j] = S::one();
-        }
+        __syncthreads();   // the products of the wave totals
     } else {
         ok = grid_gather<S, D, true>(tc, tps, start, ws, ct.tag, gl, cf, cfs, cb, cbs);
         if constexpr (WRITE_FILT) __syncthreads();   // every wave is done with the exchange area before it is reused
@@ -627,8 +776,8 @@ __global__ __launch_bounds__(256) void sd_smooth_fused_kernel(const float* __res
     // phase: tile carries
     float f[D], b[D];
     int bex[D];
-    carry_forward<S, D>(Q, wagg, cf, f);
-    carry_backward<S, D>(R, wagg, cb, b, bex);
+    carry_forward_auto<S, D>(Q, uni_q, wagg, &wprod, cf, f);
+    carry_backward_auto<S, D>(R, uni_r, wagg, &wprod, cb, b, bex);
     // phase: lane carries
     float* fdst = WRITE_FILT ? flds + threadIdx.x * C::STRIDE : nullptr;
     smooth_chunk<S, D, WRITE_FILT>(row, n, first, Am, f, b, bex, fdst);
@@ -665,9 +814,11 @@ __global__ __launch_bounds__(256) void sd_viterbi_fused_kernel(const float* __re
     __shared__ __align__(8) float wagg[C::NW * W];
     __shared__ __align__(8) float wtot[W];
     __shared__ GridLds<D> gl;
+    __shared__ WaveProducts<D> wprod;
     __shared__ uint32_t wmaps[C::NW];
     __shared__ uint32_t wmaps2[C::NW];
     __shared__ uint32_t xend_lds;
+    // phase: start
     const TileCoord tc = tile_coord<D>(T, tps);
     const int tile0 = blockIdx.x - tc.tile;
     const bool alone = tps == 1;   // the sequence is this one tile: nothing to exchange, no wait anywhere
@@ -697,8 +848,8 @@ __global__ __launch_bounds__(256) void sd_viterbi_fused_kernel(const float* __re
     __syncthreads();
     // phase: wave prefixes
     const bool exchange = !alone && !ct.poisoned;
-    if (threadIdx.x < 64)
-        tile_total_rows<S, D>(wagg, wtot, exchange ? ws.agg + (size_t)blockIdx.x * W : nullptr, ct.tag);
+    wave_products<S, D, true>(wagg, wtot, &wprod, exchange ? ws.agg + (size_t)blockIdx.x * SlotRecord<D>::STRIDE : nullptr,
+                        ws.seal + blockIdx.x, ct.tag);
     // phase: published
     float cf[D], cb[D];
     double cfs = 0.0, cbs = 0.0;
@@ -706,9 +857,10 @@ __global__ __launch_bounds__(256) void sd_viterbi_fused_kernel(const float* __re
 #pragma unroll
     for (int j = 0; j < D; ++j) cf[j] = start[j];
     if (exchange) ok = grid_gather<S, D, false>(tc, tps, start, ws, ct.tag, gl, cf, cfs, cb, cbs);
+    else __syncthreads();   // the products of the wave totals
     // phase: tile carries
     float v[D];
-    carry_forward<S, D>(Q, wagg, cf, v);
+    carry_forward<S, D>(Q, wagg, &wprod, cf, v);
     // phase: lane carries
     uint32_t bp[C::W], h, xs;
     viterbi_chunk<D>(row, n, first, last, Am, v, bp, h, xs);
@@ -725,17 +877,8 @@ __global__ __launch_bounds__(256) void sd_viterbi_fused_kernel(const float* __re
     } else {
         // the tile maps of the sequence; state at this tile's last step = maps of later tiles composed
         uint32_t tm = map_identity<D>();
-        bool ok2 = false;
-        for (int spin = 0; spin < ws.spin_limit; ++spin) {
-            bool valid = true;
-            if ((int)threadIdx.x < tps) {
-                const unsigned long long w = coherent_load(ws.tmap + tile0 + threadIdx.x);
-                valid = (uint32_t)(w >> 32) == ct.tag;
-                tm = (uint32_t)w;
-            }
-            if (__syncthreads_and(valid ? 1 : 0)) { ok2 = true; break; }
-            __builtin_amdgcn_s_sleep(1);
-        }
+        const bool ok2 = await_words(ws.tmap + tile0, tps, ct.tag, ws.spin_limit, tm);
+        if ((int)threadIdx.x >= tps) tm = map_identity<D>();
         if (!ok2) {
             ok = false;
             tm = map_identity<D>();
@@ -1006,7 +1149,8 @@ static long long tiles_per_seq(long long T) {
 // XCH_MAX_TILES tiles.  Nothing else is ever written there, so that the words of the region carry either
 // zero or the tag of some earlier call, for any sequence of calls on the workspace.
 constexpr size_t XCH_AGG_OFFSET = 256;
-constexpr size_t XCH_MAP_OFFSET = XCH_AGG_OFFSET + (size_t)XCH_MAX_TILES * (8 * 8 + 8 + 2) * 8;
+constexpr size_t XCH_SEAL_OFFSET = XCH_AGG_OFFSET + (size_t)XCH_MAX_TILES * SlotRecord<SMALL_D_MAX>::STRIDE * 8;
+constexpr size_t XCH_MAP_OFFSET = XCH_SEAL_OFFSET + (size_t)XCH_MAX_TILES * 8;
 static_assert(XCH_MAP_OFFSET + (size_t)XCH_MAX_TILES * 8 <= XCH_REGION_BYTES, "exchange region too small");
 
 struct SmoothWs { size_t agg, fin, bout, total; };
@@ -1083,6 +1227,7 @@ static bool force_multi_launch() {
 
 static FusedWs fused_ws(char* ws, int batch) {
     return FusedWs{reinterpret_cast<XchHeader*>(ws), reinterpret_cast<unsigned long long*>(ws + XCH_AGG_OFFSET),
+                   reinterpret_cast<unsigned long long*>(ws + XCH_SEAL_OFFSET),
                    reinterpret_cast<unsigned long long*>(ws + XCH_MAP_OFFSET), batch, spin_limit()};
 }
 
