@@ -70,7 +70,7 @@ typedef enum {
 #define HMM_MAX_STATES 128
 
 /* Leading bytes of every workspace that the library keeps across calls (see "Workspaces" above). */
-#define HMM_WORKSPACE_RESERVED_BYTES (320u * 1024u)
+#define HMM_WORKSPACE_RESERVED_BYTES (384u * 1024u)
 
 /*
  * Scratch size, in bytes, that hmm_smooth and hmm_viterbi need for this shape (the reserved

@@ -97,7 +97,7 @@ def hmm_workspace_bytes(T: int, D: int, batch: int):
     return int(s.value), int(v.value)
 
 
-WORKSPACE_RESERVED_BYTES = 320 * 1024
+WORKSPACE_RESERVED_BYTES = 384 * 1024
 
 
 def hmm_workspace_init(workspace) -> None:

@@ -24,7 +24,7 @@ constexpr int SMALL_D_MAX = 8;
 // tagged slots for up to XCH_MAX_TILES co-resident tiles of up to SMALL_D_MAX states); see
 // small_d_device.hpp.  It must be zero before a workspace's first use.
 constexpr int XCH_MAX_TILES = 512;
-constexpr size_t XCH_REGION_BYTES = 320 * 1024;
+constexpr size_t XCH_REGION_BYTES = 384 * 1024;
 
 // One explicit instantiation per D, each in its own translation unit (small_d_kernels.hip
 // compiled with -DHMM_SMALL_D=<D>).  Return codes follow hmm_status.

@@ -39,6 +39,19 @@ struct SlotRecord {
     static constexpr int STRIDE = W;
 };
 
+// Seals and tile maps are what every workgroup polls while it waits, all of them the same few cache lines:
+// the polls of 256 workgroups queue up at one memory channel, and the stores they are waiting for queue up
+// behind them.  So each seal and each map is published XCH_COPIES times, in arrays that lie apart, and
+// workgroup b polls copy b mod XCH_COPIES.  (Records are read once per workgroup, after the seals: one copy.)
+constexpr int XCH_COPIES = 8;
+constexpr size_t XCH_COPY_WORDS = XCH_MAX_TILES;   // 64-bit words from one copy of the seals / maps to the next
+// The tile maps are published by all workgroups at nearly the same moment, and nothing is visible elsewhere
+// sooner than a microsecond later: the first poll waits this long (s_sleep units of 64 clocks).
+#ifndef HMM_X_MAPS_HEAD_START
+#define HMM_X_MAPS_HEAD_START 25
+#endif
+constexpr int MAPS_HEAD_START = HMM_X_MAPS_HEAD_START;
+
 // Products of the wave totals in wagg, formed row by row: lane i < D of a wave owns row i of the running
 // product (rows of a product depend on the left factor's row only), so a step costs D^2 multiply-adds per
 // lane instead of a whole matrix product in one lane.
@@ -175,7 +188,8 @@ HMM_DEV void wave_products(const float* wagg, float* image, WaveProducts<D>* wp,
             const unsigned long long cb = (unsigned long long)__double_as_longlong(c);
             publish_word(slots + D * D + D, (uint32_t)cb, tag);
             publish_word(slots + D * D + D + 1, (uint32_t)(cb >> 32), tag);
-            publish_word(seal, 1u, tag);
+#pragma unroll
+            for (int k = 0; k < XCH_COPIES; ++k) publish_word(seal + k * XCH_COPY_WORDS, 1u, tag);
         }
     }
 }
@@ -482,8 +496,8 @@ __global__ void sd_zero_kernel(uint32_t* __restrict__ p, size_t n) {
 struct FusedWs {
     XchHeader* hdr;             // generation, poison flag, finished-sequence counter
     unsigned long long* agg;    // [tiles][SlotRecord::STRIDE] tagged words: tile aggregates
-    unsigned long long* seal;   // [tiles] tagged words: the tile's record is complete
-    unsigned long long* tmap;   // [tiles] tagged words: tile back-pointer maps (Viterbi)
+    unsigned long long* seal;   // [XCH_COPIES][XCH_MAX_TILES] tagged words: the tile's record is complete
+    unsigned long long* tmap;   // [XCH_COPIES][XCH_MAX_TILES] tagged words: tile back-pointer maps (Viterbi)
     int batch;                  // sequences in the call
     int spin_limit;             // polls before a wait gives up (every wave terminates whatever the other workgroups do)
 };
@@ -528,20 +542,25 @@ HMM_DEV CallTag call_tag(const unsigned long long* shared_word) {               
 
 // All lanes: wait until `nrec` (<= blockDim.x) consecutive tagged words starting at `src` carry the call's tag,
 // one lane per word; lane t < nrec gets word t's value.  Returns false if the bounded wait ran out.
+// A poll takes a memory round trip of about a microsecond, and polls that cannot succeed yet only delay the
+// stores they wait for: HEAD_START (s_sleep units of 64 clocks) is how long the first poll is held back
+// where the caller knows that the words were stored only just now.
+#ifndef HMM_X_BACKOFF
+#define HMM_X_BACKOFF 4
+#endif
+template <int HEAD_START>
 HMM_DEV bool await_words(const unsigned long long* src, int nrec, uint32_t tag, int spin_limit, uint32_t& value) {
     const bool mine = (int)threadIdx.x < nrec;
     const unsigned long long* p = src + (mine ? (int)threadIdx.x : 0);
-    // two polls in flight: the next one is already under way while the barrier judges this one, so a word
-    // is seen one memory round trip after it lands instead of up to two
-    unsigned long long v0 = coherent_load(p);
+    if constexpr (HEAD_START > 0) __builtin_amdgcn_s_sleep(HEAD_START);
     for (int spin = 0; spin < spin_limit; ++spin) {
-        const unsigned long long v1 = coherent_load(p);
-        const bool valid = !mine || (uint32_t)(v0 >> 32) == tag;
+        const unsigned long long v = coherent_load(p);
+        const bool valid = !mine || (uint32_t)(v >> 32) == tag;
         if (__syncthreads_and(valid ? 1 : 0)) {
-            value = (uint32_t)v0;
+            value = (uint32_t)v;
             return true;
         }
-        v0 = v1;
+        __builtin_amdgcn_s_sleep(HMM_X_BACKOFF);
     }
     return false;
 }
@@ -552,7 +571,9 @@ HMM_DEV bool await_words(const unsigned long long* src, int nrec, uint32_t tag, 
 template <int D>
 HMM_DEV bool stage_records(const unsigned long long* src, int nrec, float* dst_lds, uint32_t tag, int spin_limit) {
     using G = GridLds<D>;
-    constexpr int NB = 8;   // loads in flight per lane
+    // loads in flight per lane: the whole sequence in one round trip where the registers allow (nrec <= NT
+    // records of W words over NT lanes: W words per lane at most)
+    constexpr int NB = G::W <= 24 ? G::W : 20;
     const int n = nrec * G::W;
     for (int spin = 0; spin <= spin_limit; ++spin) {
         bool valid = true;
@@ -592,7 +613,8 @@ HMM_DEV bool grid_gather(const TileCoord& tc, int tps, const float (&start)[D], 
     static_assert(C::NW == 4, "the split below assumes four waves");
     const int tile0 = blockIdx.x - tc.tile;   // first tile of this sequence
     uint32_t sealed;
-    bool ok = await_words(ws.seal + tile0, tps, tag, ws.spin_limit, sealed);
+    const size_t copy = (size_t)(blockIdx.x % XCH_COPIES) * XCH_COPY_WORDS;   // the copy this workgroup polls
+    bool ok = await_words<0>(ws.seal + copy + tile0, tps, tag, ws.spin_limit, sealed);
     // phase@12: seals seen
     if (ok) ok = stage_records<D>(ws.agg + (size_t)tile0 * SlotRecord<D>::STRIDE, tps, gl.aggs, tag, ws.spin_limit);
     // phase@13: aggregates staged
@@ -867,7 +889,8 @@ __global__ __launch_bounds__(256) void sd_viterbi_fused_kernel(const float* __re
     // phase: chunk recursion
     uint32_t excl;
     const uint32_t total = block_map_suffix<D>(h, excl, wmaps);
-    if (exchange && ok && threadIdx.x == 0) publish_word(ws.tmap + blockIdx.x, total, ct.tag);
+    if (exchange && ok && (int)threadIdx.x < XCH_COPIES)
+        publish_word(ws.tmap + threadIdx.x * XCH_COPY_WORDS + blockIdx.x, total, ct.tag);
     // phase: tile map published
     uint32_t x;
     if (!exchange || !ok) {
@@ -877,7 +900,8 @@ __global__ __launch_bounds__(256) void sd_viterbi_fused_kernel(const float* __re
     } else {
         // the tile maps of the sequence; state at this tile's last step = maps of later tiles composed
         uint32_t tm = map_identity<D>();
-        const bool ok2 = await_words(ws.tmap + tile0, tps, ct.tag, ws.spin_limit, tm);
+        const bool ok2 = await_words<MAPS_HEAD_START>(ws.tmap + (blockIdx.x % XCH_COPIES) * XCH_COPY_WORDS + tile0, tps, ct.tag,
+                                                      ws.spin_limit, tm);
         if ((int)threadIdx.x >= tps) tm = map_identity<D>();
         if (!ok2) {
             ok = false;
@@ -1150,8 +1174,8 @@ static long long tiles_per_seq(long long T) {
 // zero or the tag of some earlier call, for any sequence of calls on the workspace.
 constexpr size_t XCH_AGG_OFFSET = 256;
 constexpr size_t XCH_SEAL_OFFSET = XCH_AGG_OFFSET + (size_t)XCH_MAX_TILES * SlotRecord<SMALL_D_MAX>::STRIDE * 8;
-constexpr size_t XCH_MAP_OFFSET = XCH_SEAL_OFFSET + (size_t)XCH_MAX_TILES * 8;
-static_assert(XCH_MAP_OFFSET + (size_t)XCH_MAX_TILES * 8 <= XCH_REGION_BYTES, "exchange region too small");
+constexpr size_t XCH_MAP_OFFSET = XCH_SEAL_OFFSET + XCH_COPIES * XCH_COPY_WORDS * 8;
+static_assert(XCH_MAP_OFFSET + XCH_COPIES * XCH_COPY_WORDS * 8 <= XCH_REGION_BYTES, "exchange region too small");
 
 struct SmoothWs { size_t agg, fin, bout, total; };
 struct ViterbiWs { size_t agg, vin, bp, cmap, tmap, xend, total; };
