@@ -460,19 +460,20 @@ HMM_DEV void wave_scan_up(Agg<S, D>& Q) {
     wave_scan_up<S, D, SWAP, TRACK_C, false>(Q, unused);
 }
 
-// The scan in uniform mode if every lane's element is uniform (uni, a fact about the whole wavefront) and stays
-// so, else with the general operations; uni is updated to describe the results.
-template <class S, int D, bool SWAP, bool TRACK_C>
-HMM_DEV void wave_scan_up_auto(Agg<S, D>& Q, bool& uni) {
+// Q <- inclusive scan of the elements `make()` returns, in uniform mode if every lane's element is uniform (uni,
+// a fact about the whole wavefront) and stays so, else with the general operations; uni is updated to describe
+// the results.  (make is called again for the second attempt rather than keeping a copy of the elements alive.)
+template <class S, int D, bool SWAP, bool TRACK_C, class MAKE>
+HMM_DEV void wave_scan_up_auto(Agg<S, D>& Q, bool& uni, MAKE make) {
+    make(Q);
     if constexpr (S::is_max_plus) {
         wave_scan_up<S, D, SWAP, TRACK_C>(Q);
     } else {
         if (uni) {
-            const Agg<S, D> Q0 = Q;
             bool bad = false;
             wave_scan_up<S, D, SWAP, TRACK_C, true>(Q, bad);
             if (!wave_any(bad)) return;
-            Q = Q0;
+            make(Q);
             uni = false;
         }
         wave_scan_up<S, D, SWAP, TRACK_C>(Q);
@@ -496,12 +497,12 @@ HMM_DEV void wave_scan_suffix(Agg<S, D>& R) {
     agg_shfl<S, D, false>(T, mirror, R);
 }
 
+// R <- P_t (op) ... (op) P_63 from the lanes' P
 template <class S, int D>
-HMM_DEV void wave_scan_suffix_auto(Agg<S, D>& R, bool& uni) {
+HMM_DEV void wave_scan_suffix_auto(const Agg<S, D>& P, Agg<S, D>& R, bool& uni) {
     const int mirror = 63 - (int)(threadIdx.x & 63);
     Agg<S, D> T;
-    agg_shfl<S, D, false>(R, mirror, T);
-    wave_scan_up_auto<S, D, true, false>(T, uni);
+    wave_scan_up_auto<S, D, true, false>(T, uni, [&](Agg<S, D>& X) { agg_shfl<S, D, false>(P, mirror, X); });
     agg_shfl<S, D, false>(T, mirror, R);
 }
 
@@ -536,11 +537,11 @@ template <class S, int D>
 HMM_DEV void block_prefix_auto(const Agg<S, D>& P, Agg<S, D>& Q, float* wagg, bool& uni) {
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
-    Q = P;
     if constexpr (S::is_max_plus) {
+        Q = P;
         wave_scan_up<S, D, false, true>(Q);
     } else {
-        wave_scan_up_auto<S, D, false, false>(Q, uni);
+        wave_scan_up_auto<S, D, false, false>(Q, uni, [&](Agg<S, D>& X) { X = P; });
         Q.c = wave_sum(P.c);
     }
     if (lane == 63) agg_store<S, D>(wagg + wave * AggImage<D>::WORDS, Q);

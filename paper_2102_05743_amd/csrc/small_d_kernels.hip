@@ -29,15 +29,17 @@
 
 namespace hmm {
 
-// An exchange record in the workspace: the AggImage words as tagged words, one record per tile.  Every word
-// validates itself (no ordering between stores is relied upon); the tile's seal, a tagged word in a separate
-// array written after the record, only tells readers when reading the record is worth while, so that the
-// wait polls one word per tile instead of whole records.
+// An exchange record in the workspace: the AggImage words of a tile's aggregate as tagged words, stored word
+// by word across tiles -- word w of tile t at [w * XCH_MAX_TILES + t] -- so that the lanes of a wavefront,
+// each fetching the records of two neighbouring tiles, read consecutive addresses.  Every word validates
+// itself (no ordering between stores is relied upon); the tile's seal, a tagged word in a separate array
+// written after the record, only tells readers when reading the record is worth while, so that the wait
+// polls one word per tile instead of whole records.
 template <int D>
 struct SlotRecord {
     static constexpr int W = AggImage<D>::WORDS;
-    static constexpr int STRIDE = W;
 };
+constexpr size_t XCH_WORD_STRIDE = XCH_MAX_TILES;   // 64-bit words from one word of a record to the next
 
 // Seals and tile maps are what every workgroup polls while it waits, all of them the same few cache lines:
 // the polls of 256 workgroups queue up at one memory channel, and the stores they are waiting for queue up
@@ -182,12 +184,12 @@ HMM_DEV void wave_products(const float* wagg, float* image, WaveProducts<D>* wp,
     if (wave == 0 && slots != nullptr && lane < D) {
         const int i = lane;
 #pragma unroll
-        for (int j = 0; j < D; ++j) publish_word(slots + i * D + j, x[j], tag);
-        publish_word(slots + D * D + i, (uint32_t)(S::is_max_plus ? 0 : xe), tag);
+        for (int j = 0; j < D; ++j) publish_word(slots + (i * D + j) * XCH_WORD_STRIDE, x[j], tag);
+        publish_word(slots + (D * D + i) * XCH_WORD_STRIDE, (uint32_t)(S::is_max_plus ? 0 : xe), tag);
         if (lane == 0) {
             const unsigned long long cb = (unsigned long long)__double_as_longlong(c);
-            publish_word(slots + D * D + D, (uint32_t)cb, tag);
-            publish_word(slots + D * D + D + 1, (uint32_t)(cb >> 32), tag);
+            publish_word(slots + (D * D + D) * XCH_WORD_STRIDE, (uint32_t)cb, tag);
+            publish_word(slots + (D * D + D + 1) * XCH_WORD_STRIDE, (uint32_t)(cb >> 32), tag);
 #pragma unroll
             for (int k = 0; k < XCH_COPIES; ++k) publish_word(seal + k * XCH_COPY_WORDS, 1u, tag);
         }
@@ -495,32 +497,19 @@ __global__ void sd_zero_kernel(uint32_t* __restrict__ p, size_t n) {
 
 struct FusedWs {
     XchHeader* hdr;             // generation, poison flag, finished-sequence counter
-    unsigned long long* agg;    // [tiles][SlotRecord::STRIDE] tagged words: tile aggregates
+    unsigned long long* agg;    // [SlotRecord::W][XCH_MAX_TILES] tagged words: tile aggregates
     unsigned long long* seal;   // [XCH_COPIES][XCH_MAX_TILES] tagged words: the tile's record is complete
     unsigned long long* tmap;   // [XCH_COPIES][XCH_MAX_TILES] tagged words: tile back-pointer maps (Viterbi)
     int batch;                  // sequences in the call
     int spin_limit;             // polls before a wait gives up (every wave terminates whatever the other workgroups do)
 };
 
-// LDS scratch of the inter-tile exchange: the tile aggregates of the sequence, one record per tile with an
-// odd stride so that lanes reading one record each do not collide on LDS banks, and the per-wave reductions.
+// LDS scratch of the inter-tile exchange: the per-wave reductions.
 template <int D>
 struct alignas(8) GridLds {
     static constexpr int W = AggImage<D>::WORDS;
-    static constexpr int RSTR = W | 1;
     alignas(8) float red[SmallCfg<D>::NW * W];   // (aggregate images hold a double: 8-byte alignment)
-    float aggs[SmallCfg<D>::NT * RSTR];
 };
-
-template <class S, int D>
-HMM_DEV void agg_load_staged(const float* p, Agg<S, D>& Q) {   // a record in GridLds::aggs (no alignment)
-#pragma unroll
-    for (int e = 0; e < D * D; ++e) Q.m[e] = p[e];
-#pragma unroll
-    for (int i = 0; i < D; ++i) Q.ex[i] = __float_as_int(p[D * D + i]);
-    const unsigned long long lo = __float_as_uint(p[D * D + D]), hi = __float_as_uint(p[D * D + D + 1]);
-    Q.c = __longlong_as_double((long long)((hi << 32) | lo));
-}
 
 // Generation and poison flag of the exchange region.  One thread reads them when the kernel starts and
 // hands them to the workgroup through LDS (all threads must agree: barriers depend on it).
@@ -565,38 +554,45 @@ HMM_DEV bool await_words(const unsigned long long* src, int nrec, uint32_t tag, 
     return false;
 }
 
-// All lanes: the records of `nrec` consecutive tiles into LDS records at stride RSTR, re-read until every word
-// carries the call's tag (after the seals have been seen that is normally the first attempt).  Returns false
-// if the bounded wait ran out.  Contains the barrier after which everyone may read the staged records.
-template <int D>
-HMM_DEV bool stage_records(const unsigned long long* src, int nrec, float* dst_lds, uint32_t tag, int spin_limit) {
-    using G = GridLds<D>;
-    // loads in flight per lane: the whole sequence in one round trip where the registers allow (nrec <= NT
-    // records of W words over NT lanes: W words per lane at most)
-    constexpr int NB = G::W <= 24 ? G::W : 20;
-    const int n = nrec * G::W;
-    for (int spin = 0; spin <= spin_limit; ++spin) {
-        bool valid = true;
-        for (int base = 0; base < n; base += NB * (int)blockDim.x) {
-            unsigned long long v[NB];
+// One tile's record into registers (the calling lane's own copy); false if a word does not carry the call's tag.
+// Small records are fetched in one round trip; larger ones in batches, so that the words in flight do not
+// crowd out the aggregates the caller holds.
+template <class S, int D>
+HMM_DEV bool fetch_record(const unsigned long long* records, uint32_t tile, uint32_t tag, Agg<S, D>& M) {
+    constexpr int W = AggImage<D>::WORDS;
+    constexpr int NB = W <= 24 ? W : 16;
+    bool valid = true;
+    uint32_t clo = 0u, chi = 0u;
+    uint32_t lane_off = tile * 8u;
+    // (opaque to the optimiser: otherwise it forms one 64-bit address per word ahead of the retry loop and
+    // keeps them all alive)
+    asm volatile("" : "+v"(lane_off));
 #pragma unroll
-            for (int q = 0; q < NB; ++q) {
-                const int i = base + q * (int)blockDim.x + (int)threadIdx.x;
-                v[q] = coherent_load(src + (i < n ? i : n - 1));
+    for (int base = 0; base < W; base += NB) {
+        unsigned long long v[NB];
+#pragma unroll
+        for (int q = 0; q < NB; ++q)
+            if (base + q < W) {
+                // a uniform base per word plus one 32-bit lane offset: one address register for the whole record
+                const char* wbase = reinterpret_cast<const char*>(records + (base + q) * XCH_WORD_STRIDE);
+                v[q] = coherent_load(reinterpret_cast<const unsigned long long*>(wbase + lane_off));
             }
 #pragma unroll
-            for (int q = 0; q < NB; ++q) {
-                const int i = base + q * (int)blockDim.x + (int)threadIdx.x;
-                if (i < n) {
-                    valid = valid && (uint32_t)(v[q] >> 32) == tag;
-                    const int rec = i / G::W;
-                    dst_lds[rec * G::RSTR + (i - rec * G::W)] = __uint_as_float((uint32_t)v[q]);
-                }
+        for (int q = 0; q < NB; ++q) {
+            const int w = base + q;
+            if (w < W) {
+                valid = valid && (uint32_t)(v[q] >> 32) == tag;
+                const uint32_t bits = (uint32_t)v[q];
+                if (w < D * D) M.m[w] = __uint_as_float(bits);
+                else if (w < D * D + D) M.ex[w - D * D] = (int)bits;
+                else if (w == D * D + D) clo = bits;
+                else chi = bits;
             }
         }
-        if (__syncthreads_and(valid ? 1 : 0)) return true;
+        if constexpr (NB < W) __builtin_amdgcn_sched_barrier(0);   // keep the batches apart
     }
-    return false;
+    M.c = __longlong_as_double((long long)(((unsigned long long)chi << 32) | clo));
+    return valid;
 }
 
 // Gather the aggregates of the sequence's tiles and return the vectors entering this tile with the
@@ -616,21 +612,34 @@ HMM_DEV bool grid_gather(const TileCoord& tc, int tps, const float (&start)[D], 
     const size_t copy = (size_t)(blockIdx.x % XCH_COPIES) * XCH_COPY_WORDS;   // the copy this workgroup polls
     bool ok = await_words<0>(ws.seal + copy + tile0, tps, tag, ws.spin_limit, sealed);
     // phase@12: seals seen
-    if (ok) ok = stage_records<D>(ws.agg + (size_t)tile0 * SlotRecord<D>::STRIDE, tps, gl.aggs, tag, ws.spin_limit);
-    // phase@13: aggregates staged
     const int wave = threadIdx.x >> 6;
     const int lane = threadIdx.x & 63;
     const bool fwd_half = wave < 2;
-    if (fwd_half || BWD) {
-        const int u = (int)threadIdx.x & 127;             // pair index 0..127 inside the half
-        Agg<S, D> Ma, Mb, X;
-        const int ta = 2 * u, tb = 2 * u + 1;
-        const bool use_a = ok && ta < tps && (fwd_half ? (ta < tc.tile) : (ta > tc.tile));
-        const bool use_b = ok && tb < tps && (fwd_half ? (tb < tc.tile) : (tb > tc.tile));
-        agg_identity<S, D>(Ma);
-        agg_identity<S, D>(Mb);
-        if (use_a) agg_load_staged<S, D>(gl.aggs + ta * G::RSTR, Ma);
-        if (use_b) agg_load_staged<S, D>(gl.aggs + tb * G::RSTR, Mb);
+    // every lane of a half takes two neighbouring tiles of its side of this tile, straight into registers; after
+    // the seals the records are normally complete at the first attempt
+    const int u = (int)threadIdx.x & 127;                 // pair index 0..127 inside the half
+    const int ta = 2 * u, tb = 2 * u + 1;
+    const bool side = fwd_half || BWD;
+    const bool use_a = side && ta < tps && (fwd_half ? (ta < tc.tile) : (ta > tc.tile));
+    const bool use_b = side && tb < tps && (fwd_half ? (tb < tc.tile) : (tb > tc.tile));
+    Agg<S, D> Ma, Mb;
+    if (ok) {
+        ok = false;
+        for (int spin = 0; spin <= ws.spin_limit; ++spin) {
+            bool valid = true;
+            if (use_a) valid = fetch_record<S, D>(ws.agg, (uint32_t)(tile0 + ta), tag, Ma);
+            if (use_b) valid = fetch_record<S, D>(ws.agg, (uint32_t)(tile0 + tb), tag, Mb) && valid;
+            if (__syncthreads_and(valid ? 1 : 0)) {
+                ok = true;
+                break;
+            }
+        }
+    }
+    // phase@13: aggregates staged
+    if (side) {
+        Agg<S, D> X;
+        if (!(ok && use_a)) agg_identity<S, D>(Ma);
+        if (!(ok && use_b)) agg_identity<S, D>(Mb);
         // lane 63 ends with the wave's ordered product
         if constexpr (S::is_max_plus) {
             agg_mul<S, D, true>(Ma, Mb, X);
@@ -729,14 +738,9 @@ __global__ __launch_bounds__(256) void sd_smooth_fused_kernel(const float* __res
     using C = SmallCfg<D>;
     constexpr int W = AggImage<D>::WORDS;
     __shared__ float lds[C::LDS_FLOATS];
-    // the filtering distributions of the tile are staged like the marginals, in the space the inter-tile exchange
-    // has finished with by then (both do not fit beside the tile at D >= 7)
-    __shared__ union alignas(8) FusedShared {
-        GridLds<D> gl;
-        float flds[WRITE_FILT ? C::LDS_FLOATS : 1];
-    } sh;
-    GridLds<D>& gl = sh.gl;
-    float* flds = sh.flds;
+    // the filtering distributions of the tile are staged like the marginals, in a tile of their own
+    __shared__ float flds[WRITE_FILT ? C::LDS_FLOATS : 1];
+    __shared__ GridLds<D> gl;
     __shared__ __align__(8) float wagg[C::NW * W];
     __shared__ __align__(8) float wtot[W];
     __shared__ WaveProducts<D> wprod;
@@ -772,13 +776,12 @@ __global__ __launch_bounds__(256) void sd_smooth_fused_kernel(const float* __res
     __syncthreads();
     // phase: wave prefixes
     const bool publish = !alone && !ct.poisoned;
-    wave_products<S, D, true>(wagg, wtot, &wprod, publish ? ws.agg + (size_t)blockIdx.x * SlotRecord<D>::STRIDE : nullptr,
+    wave_products<S, D, true>(wagg, wtot, &wprod, publish ? ws.agg + blockIdx.x : nullptr,
                         ws.seal + blockIdx.x, ct.tag);
     // phase: published
     // the suffix scan needs nothing from other tiles: it runs while their aggregates arrive
-    R = P;
     uni_r = uni_p;
-    wave_scan_suffix_auto<S, D>(R, uni_r);
+    wave_scan_suffix_auto<S, D>(P, R, uni_r);
     // phase: suffix scan
     float cf[D], cb[D];
     double cfs = 0.0, cbs = 0.0;
@@ -793,7 +796,6 @@ __global__ __launch_bounds__(256) void sd_smooth_fused_kernel(const float* __res
         __syncthreads();   // the products of the wave totals
     } else {
         ok = grid_gather<S, D, true>(tc, tps, start, ws, ct.tag, gl, cf, cfs, cb, cbs);
-        if constexpr (WRITE_FILT) __syncthreads();   // every wave is done with the exchange area before it is reused
     }
     // phase: tile carries
     float f[D], b[D];
@@ -870,7 +872,7 @@ __global__ __launch_bounds__(256) void sd_viterbi_fused_kernel(const float* __re
     __syncthreads();
     // phase: wave prefixes
     const bool exchange = !alone && !ct.poisoned;
-    wave_products<S, D, true>(wagg, wtot, &wprod, exchange ? ws.agg + (size_t)blockIdx.x * SlotRecord<D>::STRIDE : nullptr,
+    wave_products<S, D, true>(wagg, wtot, &wprod, exchange ? ws.agg + blockIdx.x : nullptr,
                         ws.seal + blockIdx.x, ct.tag);
     // phase: published
     float cf[D], cb[D];
@@ -1173,7 +1175,7 @@ static long long tiles_per_seq(long long T) {
 // XCH_MAX_TILES tiles.  Nothing else is ever written there, so that the words of the region carry either
 // zero or the tag of some earlier call, for any sequence of calls on the workspace.
 constexpr size_t XCH_AGG_OFFSET = 256;
-constexpr size_t XCH_SEAL_OFFSET = XCH_AGG_OFFSET + (size_t)XCH_MAX_TILES * SlotRecord<SMALL_D_MAX>::STRIDE * 8;
+constexpr size_t XCH_SEAL_OFFSET = XCH_AGG_OFFSET + (size_t)XCH_MAX_TILES * SlotRecord<SMALL_D_MAX>::W * 8;
 constexpr size_t XCH_MAP_OFFSET = XCH_SEAL_OFFSET + XCH_COPIES * XCH_COPY_WORDS * 8;
 static_assert(XCH_MAP_OFFSET + XCH_COPIES * XCH_COPY_WORDS * 8 <= XCH_REGION_BYTES, "exchange region too small");
 
