@@ -54,25 +54,31 @@ constexpr size_t XCH_COPY_WORDS = XCH_MAX_TILES;   // 64-bit words from one copy
 #endif
 constexpr int MAPS_HEAD_START = HMM_X_MAPS_HEAD_START;
 
-// Products of the wave totals in wagg, formed row by row: lane i < D of a wave owns row i of the running
-// product (rows of a product depend on the left factor's row only), so a step costs D^2 multiply-adds per
-// lane instead of a whole matrix product in one lane.
-//   wave 0: W_0 (op) ... (op) W_w for w = 1 .. NW-1; the last one is the workgroup's aggregate, which goes
-//           to `image` (LDS) and is returned as the calling lane's row (x, xe, c) for publication; the
-//           others go to wp->wpre if wp != nullptr;
-//   wave 1: W_w (op) ... (op) W_{NW-1} for w = NW-1 .. 1, to wp->wsuf (only if wp != nullptr).
+// Products of the four wave totals in wagg, formed row by row by the first wavefront: a group of D lanes owns
+// one product, lane i of the group its row i (rows of a product depend on the left factor's row only), so a
+// product costs D^2 multiply-adds per lane instead of a whole matrix product in one lane, and the three
+// products of a step run side by side:
+//   step 1   group 0: W_0 W_1                     group 1: W_2 W_3
+//   step 2   group 0: (W_0 W_1)(W_2 W_3)          group 1: (W_0 W_1) W_2          group 2: W_1 (W_2 W_3)
+// The workgroup's aggregate (step 2, group 0) goes to `image` and is returned as the calling lane's row
+// (x, xe, c) for publication.  With wp != nullptr the prefixes W_0 .. W_{w-1} go to wp->wpre[w-1] and the
+// suffixes W_w .. W_3 to wp->wsuf[w-1], w = 1 .. 3.
 // U: uniform mode -- the wave totals must be uniform and the products are kept uniform (all rows take the
 // exponent of the largest); `bad` reports where that fails.
 template <class S, int D, bool U>
-HMM_DEV void wave_products_impl(const float* wagg, float* image, WaveProducts<D>* wp, float (&x)[D], int& xe, double& c,
-                                bool& bad) {
+HMM_DEV void wave_products_impl(const float* wagg, float* image, WaveProducts<D>* wp, float* own_lds, float (&x)[D],
+                                int& xe, double& c, bool& bad) {
     using C = SmallCfg<D>;
+    static_assert(C::NW == 4, "the schedule above is for four waves");
     constexpr int W = AggImage<D>::WORDS;
-    constexpr int NW = C::NW;
     constexpr bool UNI = U && !S::is_max_plus;
-    const int wave = threadIdx.x >> 6;
     const int lane = threadIdx.x & 63;
-    const int i = lane < D ? lane : 0;   // spare lanes shadow row 0 and never store
+    const int g = (lane < 3 * D) ? lane / D : 0;   // spare lanes shadow group 0 and never store
+    const int i = lane - (lane / D) * D;
+    const bool stores = lane < 3 * D;
+    // scratch images for the two step-1 products when the caller keeps none
+    float* p01 = wp != nullptr ? wp->wpre + 1 * W : own_lds;
+    float* p23 = wp != nullptr ? wp->wsuf + 1 * W : own_lds + W;
     auto take_row = [&](const float* src) {
 #pragma unroll
         for (int j = 0; j < D; ++j) x[j] = src[i * D + j];
@@ -80,15 +86,15 @@ HMM_DEV void wave_products_impl(const float* wagg, float* image, WaveProducts<D>
         c = *reinterpret_cast<const double*>(src + D * D + D);
         if constexpr (UNI) bad = bad || (xe != reinterpret_cast<const int*>(src)[D * D]);
     };
-    auto put_row = [&](float* dst) {
-        if (lane < D) {
+    auto put_row = [&](float* dst, bool on) {
+        if (on) {
 #pragma unroll
             for (int j = 0; j < D; ++j) dst[i * D + j] = x[j];
             reinterpret_cast<int*>(dst)[D * D + i] = xe;
-            if (lane == 0) *reinterpret_cast<double*>(dst + D * D + D) = c;
+            if (i == 0) *reinterpret_cast<double*>(dst + D * D + D) = c;
         }
     };
-    // row (op) M, as a row of an aggregate again
+    // row (op) M, as a row of an aggregate again; the D lanes of a group settle the common scale among themselves
     auto times = [&](const float* src) {
         Agg<S, D> M;
         float r[D];
@@ -96,13 +102,14 @@ HMM_DEV void wave_products_impl(const float* wagg, float* image, WaveProducts<D>
         if constexpr (UNI) bad = bad || !agg_is_uniform<D>(M);
         const double sc = vec_agg_m<U, S, D>(x, M, r);
         c += M.c;
+        const int g0 = g * D;
         if constexpr (S::is_max_plus) {
             // each row comes out with an offset of its own; an aggregate has one: the largest (rows that are
             // entirely -inf report 0 and stay -inf whatever is added)
-            double top = __shfl(sc, 0, 64);
+            double top = __shfl(sc, g0, 64);
 #pragma unroll
             for (int k = 1; k < D; ++k) {
-                const double o = __shfl(sc, k, 64);
+                const double o = __shfl(sc, g0 + k, 64);
                 top = o > top ? o : top;
             }
             const float d = (float)(sc - top);
@@ -112,9 +119,9 @@ HMM_DEV void wave_products_impl(const float* wagg, float* image, WaveProducts<D>
         } else if constexpr (UNI) {
             // the row came out at the height of a vector with its own exponent: all rows take the largest
             const int own = xe + (int)sc;
-            int top = __shfl(own, 0, 64);
+            int top = __shfl(own, g0, 64);
 #pragma unroll
-            for (int k = 1; k < D; ++k) top = max_of_int(top, __shfl(own, k, 64));
+            for (int k = 1; k < D; ++k) top = max_of_int(top, __shfl(own, g0 + k, 64));
             bad = bad || (top - own > UNIFORM_SPREAD);
             const int down = max_of_int(own - top, -200);
 #pragma unroll
@@ -127,49 +134,59 @@ HMM_DEV void wave_products_impl(const float* wagg, float* image, WaveProducts<D>
             for (int j = 0; j < D; ++j) x[j] = ldexpf(r[j], ROW_BIAS - VEC_BIAS);
         }
     };
-    if (wave == 0) {
-        take_row(wagg);
-        if (wp != nullptr) put_row(wp->wpre);
-#pragma unroll
-        for (int w = 1; w < NW; ++w) {
-            times(wagg + w * W);
-            if (w < NW - 1) {
-                if (wp != nullptr) put_row(wp->wpre + w * W);
-            }
+    auto wave_sync = [&]() {   // this wave's own LDS writes before its reads
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    };
+    // step 1 (groups 0 and 1; group 2 repeats group 0's work and stores nothing)
+    {
+        const int left = (g == 1) ? 2 : 0;
+        take_row(wagg + left * W);
+        times(wagg + (left + 1) * W);
+        put_row(g == 1 ? p23 : p01, stores && g < 2);
+    }
+    wave_sync();
+    // step 2
+    {
+        const float* xsrc = (g == 2) ? wagg + 1 * W : p01;
+        const float* msrc = (g == 1) ? wagg + 2 * W : p23;
+        take_row(xsrc);
+        times(msrc);
+        float* dst = (g == 0) ? image : (g == 1) ? (wp != nullptr ? wp->wpre + 2 * W : nullptr)
+                                                 : (wp != nullptr ? wp->wsuf + 0 * W : nullptr);
+        put_row(dst, stores && dst != nullptr);
+    }
+    if (wp != nullptr) {
+        // the one-factor ends of both lists: W_0 and W_3 as they are
+        if (lane < W) {
+            wp->wpre[lane] = wagg[lane];
+            wp->wsuf[2 * W + lane] = wagg[3 * W + lane];
         }
-        put_row(image);
-    } else {
-        take_row(wagg + (NW - 1) * W);
-        put_row(wp->wsuf + (NW - 2) * W);
-#pragma unroll
-        for (int w = NW - 2; w >= 1; --w) {
-            // the product so far was written by this wave's own lanes just above: order the reads behind it
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-            take_row(wagg + w * W);
-            times(wp->wsuf + w * W);
-            put_row(wp->wsuf + (w - 1) * W);
+        if (W > 64 && lane + 64 < W) {
+            wp->wpre[lane + 64] = wagg[lane + 64];
+            wp->wsuf[2 * W + lane + 64] = wagg[3 * W + lane + 64];
         }
     }
 }
 
-// Call from the whole workgroup after the barrier that makes wagg visible; the LDS results are visible to the
-// other waves after the next barrier.  If slots != nullptr the workgroup's aggregate also goes to the tile's
+// Call from the whole workgroup after the barrier that makes wagg visible (only the first wavefront works); the
+// LDS results are visible to the other waves after the next barrier.  own_lds: 2 AggImage::WORDS floats of LDS
+// scratch, needed only when wp == nullptr.  If slots != nullptr the workgroup's aggregate also goes to the tile's
 // exchange record, followed by its seal.  AUTO: uniform mode where the wave totals allow it.
 template <class S, int D, bool AUTO>
-HMM_DEV void wave_products(const float* wagg, float* image, WaveProducts<D>* wp, unsigned long long* slots,
+HMM_DEV void wave_products(const float* wagg, float* image, WaveProducts<D>* wp, float* own_lds, unsigned long long* slots,
                            unsigned long long* seal, uint32_t tag) {
     const int wave = threadIdx.x >> 6;
     const int lane = threadIdx.x & 63;
-    if (wave > 1 || (wave == 1 && wp == nullptr)) return;
+    if (wave != 0) return;
     float x[D];
     int xe;
     double c;
     bool general = true;
     if constexpr (AUTO && !S::is_max_plus) {
         bool bad = false;
-        wave_products_impl<S, D, true>(wagg, image, wp, x, xe, c, bad);
+        wave_products_impl<S, D, true>(wagg, image, wp, own_lds, x, xe, c, bad);
         general = wave_any(bad);
         if (general) {   // what the uniform pass left in LDS is rewritten from scratch
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -179,7 +196,7 @@ HMM_DEV void wave_products(const float* wagg, float* image, WaveProducts<D>* wp,
     }
     if (general) {
         bool unused = false;
-        wave_products_impl<S, D, false>(wagg, image, wp, x, xe, c, unused);
+        wave_products_impl<S, D, false>(wagg, image, wp, own_lds, x, xe, c, unused);
     }
     if (wave == 0 && slots != nullptr && lane < D) {
         const int i = lane;
@@ -210,6 +227,7 @@ __global__ __launch_bounds__(256) void sd_reduce_kernel(const float* __restrict_
     __shared__ float lds[C::LDS_FLOATS];
     __shared__ __align__(8) float wagg[C::NW * W];
     __shared__ __align__(8) float wtot[W];
+    __shared__ __align__(8) float wtmp[2 * W];
     const TileCoord tc = tile_coord<D>(T, tps);
     load_tile<D>(ll + tc.base * D, tc.nvalid, lds);
     float Am[D * D];
@@ -220,7 +238,7 @@ __global__ __launch_bounds__(256) void sd_reduce_kernel(const float* __restrict_
     chunk_aggregate<S, D, false>(lds + threadIdx.x * C::STRIDE, n, tc.tile == 0 && threadIdx.x == 0, Am, P);
     block_prefix<S, D>(P, Q, wagg);
     __syncthreads();
-    wave_products<S, D, false>(wagg, wtot, nullptr, nullptr, nullptr, 0u);
+    wave_products<S, D, false>(wagg, wtot, nullptr, wtmp, nullptr, nullptr, 0u);
     __syncthreads();
     if (threadIdx.x < W) agg[(size_t)blockIdx.x * W + threadIdx.x] = wtot[threadIdx.x];
 }
@@ -776,7 +794,7 @@ __global__ __launch_bounds__(256) void sd_smooth_fused_kernel(const float* __res
     __syncthreads();
     // phase: wave prefixes
     const bool publish = !alone && !ct.poisoned;
-    wave_products<S, D, true>(wagg, wtot, &wprod, publish ? ws.agg + blockIdx.x : nullptr,
+    wave_products<S, D, true>(wagg, wtot, &wprod, nullptr, publish ? ws.agg + blockIdx.x : nullptr,
                         ws.seal + blockIdx.x, ct.tag);
     // phase: published
     // the suffix scan needs nothing from other tiles: it runs while their aggregates arrive
@@ -872,7 +890,7 @@ __global__ __launch_bounds__(256) void sd_viterbi_fused_kernel(const float* __re
     __syncthreads();
     // phase: wave prefixes
     const bool exchange = !alone && !ct.poisoned;
-    wave_products<S, D, true>(wagg, wtot, &wprod, exchange ? ws.agg + blockIdx.x : nullptr,
+    wave_products<S, D, true>(wagg, wtot, &wprod, nullptr, exchange ? ws.agg + blockIdx.x : nullptr,
                         ws.seal + blockIdx.x, ct.tag);
     // phase: published
     float cf[D], cb[D];
