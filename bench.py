@@ -32,10 +32,10 @@ MFMA_F32_PEAK_TFLOPS = 157.3   # MI355X published dense FP32 matrix-core rate
 # units issue 256 CUs x 128 lanes x 2.4 GHz = 78.6e12 such instructions per second (half the FMA-based
 # 157.3 TFLOP/s figure, which counts two operations per lane and clock).
 VALU_F32_PEAK_TOPS = 78.6
-SMOOTH_KERNELS = ("sd_reduce_sp", "sd_carry_sp", "sd_smooth_apply", "sd_finalize", "sd_clear_sp", "sd_smooth_fused",
+SMOOTH_KERNELS = ("sd_reduce_sp", "sd_carry_sp", "sd_smooth_apply", "sd_smooth_fused",
                   "ld_rowmax", "ld_aggregate", "ld_product", "ld_carry", "ld_apply", "ld_combine", "ld_finalize")
 VITERBI_KERNELS = ("sd_reduce_mp", "sd_carry_mp", "sd_viterbi_forward", "sd_viterbi_suffix", "sd_viterbi_path",
-                   "sd_clear_mp", "sd_viterbi_fused",
+                   "sd_viterbi_fused",
                    "lv_aggregate", "lv_tree_product", "lv_carry", "lv_forward", "lv_group_maps", "lv_suffix",
                    "lv_group_chase", "lv_path")
 WORKLOADS = {
@@ -69,6 +69,54 @@ def kernel_roofline(name: str, avg_us: float, B: int, T: int, D: int) -> dict:
     ach = alg_bytes / sec / 1e9
     return {"bound": "hbm", "kernel": name, "avg_us": avg_us, "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": ach / HBM_PEAK_GBS, "traffic": None, "algorithmic_bytes_per_launch": alg_bytes}
+
+
+def c5_leg(steps: int = 10, warmup: int = 3) -> dict:
+    """The compute-bound configuration beside the headline one: hmm_smooth on C5 (D=128, T=2^16), timed the same way
+    (inputs resident, `steps` calls between two synchronisations, then the same calls with per-kernel events).
+    The D x D element products of the sum-product scan run on the matrix cores: ld_aggregate's rate, and the whole
+    call's, against the published dense FP32 matrix rate."""
+    import torch
+
+    import paper_2102_05743_amd as hmm
+    from paper_2102_05743_amd import workloads as wl
+
+    dev = torch.device("cuda:0")
+    p = wl.config5()
+    T, D, B = p.T, p.D, p.batch
+    prior, A = torch.from_numpy(p.prior).to(dev), torch.from_numpy(p.A).to(dev)
+    nsets = 4
+    ll0 = torch.from_numpy(p.loglik).to(dev)
+    lls = [ll0] + [ll0.clone() for _ in range(nsets - 1)]
+    margs = [torch.empty((B, T, D), dtype=torch.float32, device=dev) for _ in range(nsets)]
+    logliks = torch.empty((nsets, B), dtype=torch.float64, device=dev)
+    ws = hmm.new_workspace(hmm.hmm_workspace_bytes(T, D, B)[0], dev)
+    calls = [hmm.hmm_smooth_prepare(prior, A, lls[s], marginals=margs[s], loglik_out=logliks[s], workspace=ws)
+             for s in range(nsets)]
+    for i in range(warmup):
+        calls[i % nsets]()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        calls[(warmup + i) % nsets]()
+    torch.cuda.synchronize()
+    smooth_ms = (time.perf_counter() - t0) * 1e3 / steps
+    hmm.hmm_kernel_timing_enable(True)
+    for i in range(steps):
+        calls[(warmup + i) % nsets]()
+    torch.cuda.synchronize()
+    kt = hmm.hmm_kernel_timing_get()
+    hmm.hmm_kernel_timing_enable(False)
+    agg_ms, agg_n = kt.get("ld_aggregate", (0.0, 0))
+    agg_us = 1e3 * agg_ms / max(agg_n, 1)
+    call_us = sum(1e3 * ms for ms, _ in kt.values()) / steps
+    flops = 2.0 * D ** 3 * B * T        # one D x D by D x D product per element (Definition 3)
+    return {"workload": "C5: " + WORKLOADS["C5"][1], "steps": steps, "warmup": warmup, "smooth_ms": smooth_ms,
+            "ld_aggregate_us": agg_us, "call_kernel_us": call_us,
+            "mfma_frac_kernel": flops / (agg_us * 1e-6) / 1e12 / MFMA_F32_PEAK_TFLOPS if agg_us > 0 else None,
+            "mfma_frac_call": flops / (call_us * 1e-6) / 1e12 / MFMA_F32_PEAK_TFLOPS if call_us > 0 else None,
+            "mfma_frac_call_wall": flops / (smooth_ms * 1e-3) / 1e12 / MFMA_F32_PEAK_TFLOPS,
+            "peak_TFLOPs": MFMA_F32_PEAK_TFLOPS, "loglik": float(logliks[0, 0])}
 
 
 def ge_sweep() -> int:
@@ -185,6 +233,8 @@ def main() -> int:
                     help="run this many copies of the workload's sequences as one batch (a scaled run that shows the "
                          "kernels' streaming rate; supporting evidence, not the configured shape)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-c5", action="store_true", help="skip the short C5 (D=128) leg that a default C2 run appends")
+    ap.add_argument("--repeats", type=int, default=5, help="further timed regions of K steps, for the spread in `extra`")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain device copy of 32 MiB per step (a kernel of known traffic, for scaling "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings)")
@@ -272,6 +322,16 @@ def main() -> int:
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
 
+    # ---- the spread: the same region a few more times (the headline stays the first one)
+    region_ms = [ms_per_step]
+    for _ in range(max(0, args.repeats)):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            step(args.warmup + i)
+        torch.cuda.synchronize()
+        region_ms.append((time.perf_counter() - t0) * 1e3 / args.steps)
+
     # ---- the same K steps again with a HIP start/stop event pair attached to every kernel dispatch
     # (hipExtLaunchKernel, same stream): per-kernel durations for the roofline.  Kept out of the
     # region above because the instrumented launch path costs host time per launch.
@@ -299,6 +359,7 @@ def main() -> int:
     # kernel, so calls can be captured): what a serving loop pays per step without per-launch host work.
     # One graph holds a step on every buffer set, so replays stay cold-cache.  Supporting figure only.
     ms_per_step_graph = None
+    ms_per_step_two_streams = None
     if not args.copy_calibration:
         try:
             side = torch.cuda.Stream()
@@ -317,6 +378,33 @@ def main() -> int:
             ms_per_step_graph = (time.perf_counter() - t0) * 1e3 / (reps * nsets)
         except Exception as e:   # never let the supporting figure break the benchmark line
             print(f"bench.py: graph replay skipped ({e})", file=sys.stderr)
+        # ---- the same graph with the two calls of a step on two streams (they are independent: both only read the
+        # inputs), joined before the next step: the two kernels share the compute units.  Supporting figure only.
+        try:
+            side, side2 = torch.cuda.Stream(), torch.cuda.Stream()
+            graph2 = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph2, stream=side):
+                for s in range(nsets):
+                    side2.wait_stream(side)
+                    hmm.hmm_smooth(prior, A, lls[s], marginals=margs[s], loglik_out=logliks[s], workspace=ws_smooth)
+                    with torch.cuda.stream(side2):
+                        hmm.hmm_viterbi(prior, A, lls[s], path=paths[s], logprob_out=logprobs[s], workspace=ws_viterbi)
+                    side.wait_stream(side2)
+            reps = max(1, args.steps // nsets)
+            graph2.replay()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                graph2.replay()
+            torch.cuda.synchronize()
+            ms_per_step_two_streams = (time.perf_counter() - t0) * 1e3 / (reps * nsets)
+            for ws_ in (ws_smooth, ws_viterbi):   # both kernels need all their tiles resident: check that they were
+                if hmm.hmm_workspace_status(ws_) != 0:
+                    ms_per_step_two_streams = None
+                    hmm.hmm_workspace_init(ws_)
+            torch.cuda.synchronize()
+        except Exception as e:
+            print(f"bench.py: two-stream graph replay skipped ({e})", file=sys.stderr)
 
     state_steps = B * T * D
     value = state_steps / (ms_per_step * 1e-3)
@@ -396,13 +484,24 @@ def main() -> int:
                    "batch": B, "buffer_sets": nsets, "step": "hmm_smooth + hmm_viterbi"},
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
-        "extra": {"ms_per_step_with_kernel_events": ms_per_step_events, "ms_per_step_warm_cache": ms_per_step_warm,
+        "extra": {"ms_per_step_regions": {"n": len(region_ms), "median": float(np.median(region_ms)),
+                                          "min": min(region_ms), "max": max(region_ms)},
+                  "ms_per_step_graph_replay_two_streams": ms_per_step_two_streams,
+                  "ms_per_step_with_kernel_events": ms_per_step_events, "ms_per_step_warm_cache": ms_per_step_warm,
                   "ms_per_step_graph_replay": ms_per_step_graph,
                   "smooth_state_steps_per_s": state_steps / (smooth_us * 1e-6) if smooth_us > 0 else None,
                   "viterbi_state_steps_per_s": state_steps / (viterbi_us * 1e-6) if viterbi_us > 0 else None,
                   "per_kernel": per_kernel, "other_rooflines": other_rooflines,
                   "loglik": float(logliks[0, 0]), "logprob": float(logprobs[0, 0])},
     }
+    if args.workload == "C2" and not args.no_c5 and args.T is None and args.batch_copies == 1 and not args.copy_calibration:
+        del lls, margs, paths
+        torch.cuda.empty_cache()
+        try:
+            out["extra"]["c5"] = c5_leg()
+        except Exception as e:
+            print(f"bench.py: C5 leg failed ({e})", file=sys.stderr)
+            out["extra"]["c5"] = None
     print(json.dumps(out))
     return 0
 
