@@ -33,7 +33,7 @@ MFMA_F32_PEAK_TFLOPS = 157.3   # MI355X published dense FP32 matrix-core rate
 # 157.3 TFLOP/s figure, which counts two operations per lane and clock).
 VALU_F32_PEAK_TOPS = 78.6
 SMOOTH_KERNELS = ("sd_reduce_sp", "sd_carry_sp", "sd_smooth_apply", "sd_smooth_fused",
-                  "ld_rowmax", "ld_aggregate", "ld_product", "ld_carry", "ld_apply", "ld_combine", "ld_finalize")
+                  "ld_rowmax", "ld_aggregate", "ld_product", "ld_carry", "ld_apply", "ld_combine", "ld_finalize", "ld_repair")
 VITERBI_KERNELS = ("sd_reduce_mp", "sd_carry_mp", "sd_viterbi_forward", "sd_viterbi_suffix", "sd_viterbi_path",
                    "sd_viterbi_fused",
                    "lv_aggregate", "lv_tree_product", "lv_carry", "lv_forward", "lv_group_maps", "lv_suffix",

@@ -19,11 +19,19 @@
  * all -inf, or Z = 0) is not an error: the returned log-likelihood /
  * log-probability is then -inf or NaN and the marginals / path are unspecified.
  * Range: hmm_smooth works on probabilities in single precision, rescaled by exact
- * powers of two; the scale of every vector, and of every ROW of an aggregated
- * product of potentials, is kept apart from the mantissas, so the only states lost
- * are those a step-by-step forward-backward recursion in single precision loses as
- * well: a state whose filtered (or backward) probability falls below 2^-126 of the
- * step's largest becomes exactly zero.  The max-product calls work on logarithms.
+ * powers of two; the scale of every vector is kept apart from the mantissas, so the
+ * only states lost are those a step-by-step forward-backward recursion in single
+ * precision loses as well: a state whose filtered (or backward) probability falls
+ * below 2^-126 of the step's largest becomes exactly zero.  For D <= 8 every ROW of
+ * an aggregated product of potentials has its own scale (while all rows of an
+ * aggregate stay within 2^20 of one another the kernels run a shorter code path
+ * with one scale, and fall back per phase and wavefront otherwise).  Above eight
+ * states the rows of an aggregate share a scale per strip of 16 or 32 rows; a
+ * sequence whose carries meet rows far below that scale (a product of a carry and
+ * an aggregate that comes out more than 2^32 below its factors, or a result that
+ * is not a number) is computed again inside the same call by the step-by-step
+ * recursion itself, one workgroup walking its T steps twice -- correct, and slow
+ * for that sequence only.  The max-product calls work on logarithms.
  *
  * Workspaces.  The first HMM_WORKSPACE_RESERVED_BYTES of every workspace belong to
  * the library across calls: they MUST BE ZERO before the workspace's first use

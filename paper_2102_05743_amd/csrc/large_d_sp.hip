@@ -24,6 +24,13 @@ namespace hmm {
 
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr int ZERO_STRIP_EXP = -(1 << 28);   // power-of-two scale recorded for an all-zero strip of an aggregate
+// Rows of an aggregate share a scale per strip, and strips are reconciled to the largest scale where they meet
+// a carry.  That is harmless while the carry puts weight on the rows that set those scales, which it does when
+// the evidence of the chunk agrees with where the chain was: the product carry x aggregate then comes out near
+// the size of its factors (both are kept at a largest entry in [1/2, 1)).  A product that comes out smaller
+// than this limit means that the carry sat on rows far below the scale -- rows that may have lost entries to
+// it -- and the sequence is marked for ld_repair.
+constexpr float HOP_LOSS_LIMIT = 0x1p-32f;
 
 // ---------------------------------------------------------------------------------------------
 // m_t = max_j ll_t(j).  A power-of-two group of lanes per row, four consecutive values per lane, so
@@ -33,7 +40,11 @@ constexpr int ZERO_STRIP_EXP = -(1 << 28);   // power-of-two scale recorded for 
 constexpr int STREAM_UNROLL = 4;
 
 __global__ __launch_bounds__(256) void ld_rowmax_kernel(const float* __restrict__ ll, long long rows, int Dr,
-                                                        float* __restrict__ rowmax) {
+                                                        float* __restrict__ rowmax, int* __restrict__ suspect,
+                                                        int batch) {
+    // (first kernel of a call: it also clears the per-sequence flags that the aggregate kernels may raise)
+    if (suspect != nullptr && blockIdx.x == 0)
+        for (int i = threadIdx.x; i < batch; i += 256) suspect[i] = 0;
     const int lpr = (Dr + 3) / 4;                  // lanes per row
     int width = 1;
     while (width < lpr) width <<= 1;               // power of two <= 32 for Dr <= 128
@@ -403,7 +414,7 @@ __global__ __launch_bounds__(256) void ld_carry_kernel(const float* __restrict__
                                                        const float* __restrict__ aggT, const int* __restrict__ exps,
                                                        float* __restrict__ fin, float* __restrict__ bout,
                                                        int seglen, int nseg, const float* __restrict__ start_f,
-                                                       const float* __restrict__ start_b) {
+                                                       const float* __restrict__ start_b, int* __restrict__ suspect) {
     // The chunks of a sequence may be cut into nseg segments of seglen chunks that are walked
     // independently (blockIdx = 2*(seq*nseg + seg) + dir), each from its own start vector: the
     // forward potential before the segment (start_f) or the backward potential at its last step
@@ -496,6 +507,7 @@ __global__ __launch_bounds__(256) void ld_carry_kernel(const float* __restrict__
             lds_barrier();
             m = fmaxf(wmx[0], wmx[1]);
         }
+        if (m < HOP_LOSS_LIMIT && tid == 0) suspect[seq] = 1;   // (see HOP_LOSS_LIMIT)
         v = ldexpf(g, -__builtin_amdgcn_frexp_expf(m));
         c = cn;
     }
@@ -513,7 +525,7 @@ __global__ __launch_bounds__(64) void ld_carry_wave_kernel(const float* __restri
                                                            const int* __restrict__ exps, float* __restrict__ fin,
                                                            float* __restrict__ bout, int seglen, int nseg,
                                                            const float* __restrict__ start_f,
-                                                           const float* __restrict__ start_b) {
+                                                           const float* __restrict__ start_b, int* __restrict__ suspect) {
     using C = LargeCfg<D>;
     static_assert(D <= 32, "one wave covers the columns");
     constexpr int PARTS = 64 / D;       // 2 or 4 lanes per column
@@ -541,6 +553,7 @@ __global__ __launch_bounds__(64) void ld_carry_wave_kernel(const float* __restri
     settle_loaded(v);
     float pm[PF][RPT];
     int exn[PF][C::WPC];
+    bool lost = false;
     auto chunk_of = [&](int it) { return dir == 0 ? c_begin + it : c_end - 1 - it; };
     // Loads are unconditional (the hop index is clamped) and the exponents come through vector loads:
     // the compiler can then count outstanding loads exactly and wait only for the slot it needs,
@@ -588,6 +601,7 @@ __global__ __launch_bounds__(64) void ld_carry_wave_kernel(const float* __restri
         const float g = (dir == 1) ? ldexpf(acc, exj - exmax) : acc;
         // keep the vector in range with an exact power of two (its scale is irrelevant downstream)
         const float mx = wave_max(g);
+        lost = lost || (mx < HOP_LOSS_LIMIT);   // (see HOP_LOSS_LIMIT)
         v = ldexpf(g, -__builtin_amdgcn_frexp_expf(mx));
     };
 #pragma unroll
@@ -603,6 +617,7 @@ __global__ __launch_bounds__(64) void ld_carry_wave_kernel(const float* __restri
 #pragma unroll
     for (int p = 0; p < PF; ++p)
         if (nfull + p < nhops) hop(nfull + p, pm[p], exn[p]);   // slot p holds hop nfull + p
+    if (lost && lane == 0) suspect[seq] = 1;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1221,6 +1236,112 @@ __global__ __launch_bounds__(256) void ld_element_finish_kernel(const float* __r
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Repair pass.  The aggregates above carry one scale per strip of rows; where the rows of an aggregate have
+// drifted apart by more than that can hold (models with zero transitions under evidence that contradicts the
+// states the chain can still be in), a carry that sits on the small rows loses them.  Such sequences were
+// marked on the way (suspect[seq], raised by the carries; or a log-likelihood that is not a number) and are
+// redone here by the classical recursion itself, step by step in single precision with a rescaling at every
+// step (Alg. 1; forward potentials scaled to sum one, backward ones to maximum one): slow, one workgroup
+// per sequence walking its T steps twice, but it is by definition what the scans have to agree with.
+// Sequences that were not marked leave at once.  The forward potentials wait in `marg` itself until the
+// backward sweep overwrites them with the marginals.
+constexpr int REPAIR_THREADS = 128;   // one thread per state (D <= 128)
+constexpr int REPAIR_ASTR = 129;      // row stride of A in LDS: conflict-free by rows and by columns
+constexpr int REPAIR_BIAS = 50;       // potentials are held near 2^50 (two of them multiplied and summed over 128 states stay finite)
+
+HMM_DEV float repair_block_sum(float v, float* red) {   // all REPAIR_THREADS threads; two barriers
+    const float w = wave_sum(v);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = w;
+    __syncthreads();
+    return red[0] + red[1];
+}
+HMM_DEV float repair_block_max(float v, float* red) {
+    const float w = wave_max(v);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = w;
+    __syncthreads();
+    return fmaxf(red[0], red[1]);
+}
+
+__global__ __launch_bounds__(REPAIR_THREADS) void ld_repair_kernel(
+    const int* __restrict__ suspect, const float* __restrict__ prior, const float* __restrict__ A, const float* __restrict__ ll,
+    const float* __restrict__ rowmax, long long T, int Dr, int shared_model, float* __restrict__ marg,
+    float* __restrict__ filt, double* __restrict__ loglik_out) {
+    __shared__ float Al[128 * REPAIR_ASTR];
+    __shared__ float vec[128];
+    __shared__ float red[2];
+    const int seq = blockIdx.x;
+    const int j = threadIdx.x;
+    // marked on the way, or a result that is not a number
+    const bool redo = suspect[seq] != 0 || !(loglik_out[seq] == loglik_out[seq]);
+    if (!__syncthreads_or(redo ? 1 : 0)) return;
+
+    const bool live = j < Dr;
+    const float* Am = A + (shared_model ? 0 : (size_t)seq * Dr * Dr);
+    for (int idx = j; idx < Dr * Dr; idx += REPAIR_THREADS) Al[(idx / Dr) * REPAIR_ASTR + idx % Dr] = Am[idx];
+    const float* lseq = ll + (size_t)seq * T * Dr;
+    const float* mseq = rowmax + (size_t)seq * T;
+    float* F = filt != nullptr ? filt + (size_t)seq * T * Dr : nullptr;
+    float* G_ = marg + (size_t)seq * T * Dr;
+    auto factor = [&](long long t) {   // e_t(j), largest one at 1 (as in the aggregate kernels)
+        float m = mseq[t];
+        m = (m == -INFINITY) ? 0.0f : m;
+        return live ? __builtin_amdgcn_exp2f(fmaf(lseq[(size_t)t * Dr + j], LOG2E, -LOG2E * m)) : 0.0f;
+    };
+    // Both potentials are held far above one (sums / maxima near 2^REPAIR_BIAS, by exact powers of two): an entry
+    // 2^-126 below the largest is then still a normal number, and the state that later evidence vindicates
+    // is usually such an entry.
+    double L = 0.0;
+    float S_prev = 1.0f;   // sum of the stored forward vector of the previous step (the prior sums to one)
+    __syncthreads();
+    // forward sweep: u_t = f_t * 2^k_t into marg (and f_t itself into filt if asked for)
+    for (long long t = 0; t < T; ++t) {
+        float pred = 0.0f;
+        if (live) {
+            if (t == 0) {
+                pred = prior[(shared_model ? 0 : (size_t)seq * Dr) + j];
+            } else {
+                for (int i = 0; i < Dr; ++i) pred = fmaf(vec[i], Al[i * REPAIR_ASTR + j], pred);
+            }
+        }
+        const float g = pred * factor(t);
+        const float s = repair_block_sum(g, red);   // (its barriers also order the reads of vec above before the write below)
+        const int k = REPAIR_BIAS - __builtin_amdgcn_frexp_expf(s);
+        const float u = ldexpf(g, k);
+        if (live) {
+            vec[j] = u;
+            G_[(size_t)t * Dr + j] = u;
+            if (filt != nullptr) F[(size_t)t * Dr + j] = g / s;
+        }
+        if (j == 0) {
+            float m = mseq[t];
+            m = (m == -INFINITY) ? 0.0f : m;
+            L += (double)m + log((double)s) - log((double)S_prev);
+        }
+        S_prev = ldexpf(s, k);   // = the sum of u: scaling by a power of two commutes with the rounding of the sum
+        __syncthreads();
+    }
+    if (j == 0) loglik_out[seq] = L;
+    // backward sweep: marginals over the stored u_t
+    float b = live ? 1.0f : 0.0f;
+    for (long long t = T - 1; t >= 0; --t) {
+        const float uj = live ? G_[(size_t)t * Dr + j] : 0.0f;
+        const float gam = uj * b;
+        const float z = repair_block_sum(gam, red);
+        if (live) G_[(size_t)t * Dr + j] = gam / z;
+        if (t == 0) break;
+        if (live) vec[j] = factor(t) * b;
+        __syncthreads();
+        float r = 0.0f;
+        if (live)
+            for (int q = 0; q < Dr; ++q) r = fmaf(Al[j * REPAIR_ASTR + q], vec[q], r);
+        const float mx = repair_block_max(r, red);
+        b = ldexpf(r, REPAIR_BIAS - __builtin_amdgcn_frexp_expf(mx));
+    }
+}
+
 // =============================================================================================
 // Host side
 // =============================================================================================
@@ -1287,7 +1408,7 @@ static SmoothPlan smooth_plan(int Dr, long long T, int batch) {
     return p;
 }
 
-struct LargeSmoothWs { size_t rowmax, agg, aggT, exps, fin, bout, gagg, gaggT, gexps, gfin, gbout, F, Bv, part, total; };
+struct LargeSmoothWs { size_t rowmax, agg, aggT, exps, fin, bout, gagg, gaggT, gexps, gfin, gbout, F, Bv, part, suspect, total; };
 
 static LargeSmoothWs large_smooth_ws(int Dr, long long T, int batch, bool own_F) {
     const SmoothPlan p = smooth_plan(Dr, T, batch);
@@ -1309,6 +1430,7 @@ static LargeSmoothWs large_smooth_ws(int Dr, long long T, int batch, bool own_F)
     w.F = o;      o = align_up(o + (own_F ? rows * Dr * sizeof(float) : 0), 256);
     w.Bv = o;     o = align_up(o + (p.fused_apply ? 0 : rows * Dr * sizeof(float)), 256);
     w.part = o;   o = align_up(o + nc * sizeof(double), 256);
+    w.suspect = o; o = align_up(o + (size_t)batch * sizeof(int), 256);
     w.total = o;
     return w;
 }
@@ -1320,14 +1442,14 @@ size_t large_d_smooth_ws_bytes(int Dr, long long T, int batch) {
 template <int D>
 static void launch_carry(hipStream_t st, const LargeArgs& a, int cps, const float* agg, const float* aggT,
                          const int* exps, float* fin, float* bout, int seglen, int nseg, const float* start_f,
-                         const float* start_b) {
+                         const float* start_b, int* suspect) {
     const unsigned blocks = 2u * (unsigned)a.batch * (unsigned)nseg;
     if constexpr (D <= 32)
         launch("ld_carry", ld_carry_wave_kernel<D>, dim3(blocks), dim3(64), st, a.prior, a.D, cps, a.shared_model, agg,
-               aggT, exps, fin, bout, seglen, nseg, start_f, start_b);
+               aggT, exps, fin, bout, seglen, nseg, start_f, start_b, suspect);
     else
         launch("ld_carry", ld_carry_kernel<D>, dim3(blocks), dim3(256), st, a.prior, a.D, cps, a.shared_model, agg, aggT,
-               exps, fin, bout, seglen, nseg, start_f, start_b);
+               exps, fin, bout, seglen, nseg, start_f, start_b, suspect);
 }
 
 template <int D>
@@ -1353,13 +1475,14 @@ static int large_smooth_impl(const LargeArgs& a, float* marg, float* filt, doubl
     float* F = filt ? filt : reinterpret_cast<float*>(ws + w.F);
     float* Bv = reinterpret_cast<float*>(ws + w.Bv);
     double* part = reinterpret_cast<double*>(ws + w.part);
+    int* suspect = reinterpret_cast<int*>(ws + w.suspect);
     hipStream_t st = a.stream;
     const dim3 block(256);
     {
         int width = 1;
         while (width < (a.D + 3) / 4) width <<= 1;
         const long long rpb = 4LL * STREAM_UNROLL * (64 / width);   // rows per workgroup
-        launch("ld_rowmax", ld_rowmax_kernel, dim3((unsigned)((rows + rpb - 1) / rpb)), block, st, a.ll, rows, a.D, rowmax);
+        launch("ld_rowmax", ld_rowmax_kernel, dim3((unsigned)((rows + rpb - 1) / rpb)), block, st, a.ll, rows, a.D, rowmax, suspect, a.batch);
     }
     if (p.cps == 1) {
         // a sequence is one chunk: it starts from the prior and ends with the all-ones vector; no aggregates, no carries
@@ -1374,10 +1497,10 @@ static int large_smooth_impl(const LargeArgs& a, float* marg, float* filt, doubl
         launch("ld_product", ld_product_kernel<D>, dim3((unsigned)((ngroups + C::CPW - 1) / C::CPW)), block, st,
                (const float*)aggT, (const int*)exps, p.cps, p.g, p.G, ngroups, gagg, gaggT, gexps);
         // carries at the group boundaries, then inside every group from those
-        launch_carry<D>(st, a, p.G, gagg, gaggT, gexps, gfin, gbout, p.G, 1, nullptr, nullptr);
-        launch_carry<D>(st, a, p.cps, agg, aggT, exps, fin, bout, p.g, p.G, gfin, gbout);
+        launch_carry<D>(st, a, p.G, gagg, gaggT, gexps, gfin, gbout, p.G, 1, nullptr, nullptr, suspect);
+        launch_carry<D>(st, a, p.cps, agg, aggT, exps, fin, bout, p.g, p.G, gfin, gbout, suspect);
     } else if (p.cps > 1) {
-        launch_carry<D>(st, a, p.cps, agg, aggT, exps, fin, bout, p.cps, 1, nullptr, nullptr);
+        launch_carry<D>(st, a, p.cps, agg, aggT, exps, fin, bout, p.cps, 1, nullptr, nullptr, suspect);
     }
     const int half = (int)((p.nchunks + C::VCPW - 1) / C::VCPW);
     bool marginals_done = false;
@@ -1405,6 +1528,9 @@ static int large_smooth_impl(const LargeArgs& a, float* marg, float* filt, doubl
                Bv, rows, a.D, marg);
     }
     launch("ld_finalize", ld_finalize_kernel, dim3((unsigned)a.batch), block, st, part, p.cps, loglik_out);
+    if (p.cps > 1)
+        launch("ld_repair", ld_repair_kernel, dim3((unsigned)a.batch), dim3(REPAIR_THREADS), st, (const int*)suspect, a.prior, a.A, a.ll,
+               (const float*)rowmax, a.T, a.D, a.shared_model, marg, filt, loglik_out);
     return hipGetLastError() == hipSuccess ? 0 : 4;
 }
 
@@ -1463,7 +1589,7 @@ static int large_element_sp_impl(const LargeArgs& a, float* element, double* log
         int width = 1;
         while (width < (a.D + 3) / 4) width <<= 1;
         const long long rpb = 4LL * STREAM_UNROLL * (64 / width);
-        launch("ld_rowmax", ld_rowmax_kernel, dim3((unsigned)((rows + rpb - 1) / rpb)), block, st, a.ll, rows, a.D, rowmax);
+        launch("ld_rowmax", ld_rowmax_kernel, dim3((unsigned)((rows + rpb - 1) / rpb)), block, st, a.ll, rows, a.D, rowmax, (int*)nullptr, 0);
     }
     launch("ld_aggregate", ld_aggregate_kernel<D>, dim3((unsigned)((p.nchunks + C::CPW - 1) / C::CPW)), block, st, a.A,
            a.ll, rowmax, a.T, a.D, p.Lc, p.cps, p.nchunks, a.shared_model, agg, aggT, exps);

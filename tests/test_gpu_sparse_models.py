@@ -42,11 +42,8 @@ BEYOND_SINGLE_PRECISION = [
     (29886, 9, 24795, 1, True, 0.7, 2.0),
 ]
 # expected transition counts are formed from the smoother's normalised outputs, which hold nothing below 1e-38:
-# on these two shapes that is too little for the pairwise posteriors although the marginals themselves are right
-COUNTS_NEED_MORE_RANGE = {35688, 30490}
-# above eight states the aggregates still carry one scale per strip of rows, not per row
-ONE_SCALE_PER_STRIP = {9909, 10221, 18629}
-
+# on these shapes that is too little for the pairwise posteriors although the marginals themselves are right
+COUNTS_NEED_MORE_RANGE = {35688, 30490, 9909}
 
 def _problem(shape):
     seed, D, T, B, shared, zf, lls = shape
@@ -59,9 +56,6 @@ def test_sparse_model_with_contradicting_evidence(gu, shape, plan, monkeypatch):
     D = shape[1]
     if D > 8 and plan == "multi":
         pytest.skip("one plan above eight states")
-    if shape[0] in ONE_SCALE_PER_STRIP:
-        pytest.skip("known failure: above eight states an aggregate's rows share one scale per strip, and on this "
-                    "shape that flushes the rows the carry sits on (non-finite marginals)")
     monkeypatch.setenv("HMMSCAN_PLAN", plan)
     p = _problem(shape)
     label = f"sparse seed={shape[0]} D={D} T={shape[2]} B={shape[3]} zero_frac={shape[5]} ll_scale={shape[6]} plan={plan}"
