@@ -606,7 +606,7 @@ HMM_DEV void carry_forward(const Agg<S, D>& Q, const float* wagg, const WaveProd
     }
     Agg<S, D> Qp;
     float r[D];
-    agg_shfl<S, D, false>(Q, (lane + 63) & 63, Qp);   // the lane below (lane 0 does not use it)
+    agg_dpp<S, D, 0x138, 0xF, false>(Q, Qp);   // wave_shr:1, the lane below (lane 0 gets the neutral element and does not use it)
     vec_agg_m<U, S, D>(fw, Qp, r);
 #pragma unroll
     for (int j = 0; j < D; ++j) fin[j] = (lane == 0) ? fw[j] : r[j];
@@ -663,7 +663,7 @@ HMM_DEV void carry_backward(const Agg<S, D>& R, const float* wagg, const WavePro
         }
     }
     Agg<S, D> Rn;
-    agg_shfl<S, D, false>(R, (lane + 1) & 63, Rn);   // the lane above (lane 63 does not use it)
+    agg_dpp<S, D, 0x130, 0xF, false>(R, Rn);   // wave_shl:1, the lane above (lane 63 gets the neutral element and does not use it)
     if constexpr (S::is_max_plus) {
         float r[D];
         agg_vec<S, D>(Rn, bw, r);
