@@ -234,6 +234,9 @@ def main() -> int:
                          "kernels' streaming rate; supporting evidence, not the configured shape)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-c5", action="store_true", help="skip the short C5 (D=128) leg that a default C2 run appends")
+    ap.add_argument("--two-streams", action="store_true",
+                    help="also replay a graph that runs the two calls of a step on two streams (supporting figure; left out "
+                         "by default so that every launch of a default run is an undisturbed one)")
     ap.add_argument("--repeats", type=int, default=5, help="further timed regions of K steps, for the spread in `extra`")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain device copy of 32 MiB per step (a kernel of known traffic, for scaling "
@@ -381,6 +384,8 @@ def main() -> int:
         # ---- the same graph with the two calls of a step on two streams (they are independent: both only read the
         # inputs), joined before the next step: the two kernels share the compute units.  Supporting figure only.
         try:
+            if not args.two_streams:
+                raise StopIteration
             side, side2 = torch.cuda.Stream(), torch.cuda.Stream()
             graph2 = torch.cuda.CUDAGraph()
             with torch.cuda.graph(graph2, stream=side):
@@ -403,6 +408,8 @@ def main() -> int:
                     ms_per_step_two_streams = None
                     hmm.hmm_workspace_init(ws_)
             torch.cuda.synchronize()
+        except StopIteration:
+            pass
         except Exception as e:
             print(f"bench.py: two-stream graph replay skipped ({e})", file=sys.stderr)
 
