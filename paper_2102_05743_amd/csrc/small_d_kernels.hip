@@ -49,10 +49,8 @@ constexpr int XCH_COPIES = 8;
 constexpr size_t XCH_COPY_WORDS = XCH_MAX_TILES;   // 64-bit words from one copy of the seals / maps to the next
 // The tile maps are published by all workgroups at nearly the same moment, and nothing is visible elsewhere
 // sooner than a microsecond later: the first poll waits this long (s_sleep units of 64 clocks).
-#ifndef HMM_X_MAPS_HEAD_START
-#define HMM_X_MAPS_HEAD_START 25
-#endif
-constexpr int MAPS_HEAD_START = HMM_X_MAPS_HEAD_START;
+constexpr int MAPS_HEAD_START = 25;
+constexpr int POLL_BACKOFF = 4;   // s_sleep units between two polls of a wait
 
 // Products of the four wave totals in wagg, formed row by row by the first wavefront: a group of D lanes owns
 // one product, lane i of the group its row i (rows of a product depend on the left factor's row only), so a
@@ -552,9 +550,6 @@ HMM_DEV CallTag call_tag(const unsigned long long* shared_word) {               
 // A poll takes a memory round trip of about a microsecond, and polls that cannot succeed yet only delay the
 // stores they wait for: HEAD_START (s_sleep units of 64 clocks) is how long the first poll is held back
 // where the caller knows that the words were stored only just now.
-#ifndef HMM_X_BACKOFF
-#define HMM_X_BACKOFF 4
-#endif
 template <int HEAD_START>
 HMM_DEV bool await_words(const unsigned long long* src, int nrec, uint32_t tag, int spin_limit, uint32_t& value) {
     const bool mine = (int)threadIdx.x < nrec;
@@ -567,7 +562,7 @@ HMM_DEV bool await_words(const unsigned long long* src, int nrec, uint32_t tag, 
             value = (uint32_t)v;
             return true;
         }
-        __builtin_amdgcn_s_sleep(HMM_X_BACKOFF);
+        __builtin_amdgcn_s_sleep(POLL_BACKOFF);
     }
     return false;
 }
