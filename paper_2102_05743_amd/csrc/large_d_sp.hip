@@ -91,10 +91,14 @@ __global__ __launch_bounds__(256) void ld_rowmax_kernel(const float* __restrict_
 // which evolve independently); WPC waves make a chunk, CPW chunks share a workgroup.
 template <int D>
 __global__ __launch_bounds__(256, (D <= 32) ? 2 : 1) void ld_aggregate_kernel(const float* __restrict__ A, const float* __restrict__ ll,
-                                                           const float* __restrict__ rowmax, long long T, int Dr,
+                                                           float* __restrict__ rowmax, int own_rowmax, long long T, int Dr,
                                                            int Lc, int cps, long long nchunks, int shared_model,
                                                            float* __restrict__ agg, float* __restrict__ aggT,
-                                                           int* __restrict__ exps) {
+                                                           int* __restrict__ exps, int* __restrict__ suspect, int batch) {
+    // own_rowmax (D <= 32 only): this is the first kernel of the call -- it forms the row maxima itself and
+    // clears the per-sequence flags that the carries may raise
+    if (suspect != nullptr && blockIdx.x == 0)
+        for (int i = threadIdx.x; i < batch; i += 256) suspect[i] = 0;
     using C = LargeCfg<D>;
     using Acc = typename AccT<C::TS>::type;
     constexpr int EPT = C::EB * D / (C::WPC * 64);   // emission values per lane per batch
@@ -121,8 +125,37 @@ __global__ __launch_bounds__(256, (D <= 32) ? 2 : 1) void ld_aggregate_kernel(co
         }
     }
     const float* lseq = ll + (size_t)cc.seq * T * Dr;
-    const float* mseq = rowmax + (size_t)cc.seq * T;
+    float* mseq = rowmax + (size_t)cc.seq * T;
     auto load_batch = [&](int b, float (&er)[EPT]) {
+        if constexpr (D <= 32) {
+            if (own_rowmax) {
+                // m_t = max_j ll_t(j) formed here: the D values of a step sit in D consecutive lanes of one wave
+                // (aligned), so the maximum is a few cross-lane steps, and the separate pass over the
+                // log-likelihoods is not needed; m_t is stored for the kernels that follow
+                float x[EPT];
+#pragma unroll
+                for (int q = 0; q < EPT; ++q) {
+                    const int idx = q * (C::WPC * 64) + tic;
+                    const int sb = idx / D, j = idx - sb * D;
+                    const int step = b * C::EB + sb;
+                    x[q] = -INFINITY;
+                    if (step < cc.nsteps && j < Dr) x[q] = lseq[(size_t)(cc.t0 + step) * Dr + j];
+                }
+#pragma unroll
+                for (int q = 0; q < EPT; ++q) {
+                    const int idx = q * (C::WPC * 64) + tic;
+                    const int sb = idx / D, j = idx - sb * D;
+                    const int step = b * C::EB + sb;
+                    float m = x[q];
+#pragma unroll
+                    for (int d = 1; d < D; d <<= 1) m = fmaxf(m, __shfl_xor(m, d, 64));
+                    if (j == 0 && step < cc.nsteps) mseq[cc.t0 + step] = m;
+                    m = (m == -INFINITY) ? 0.0f : m;
+                    er[q] = __builtin_amdgcn_exp2f(fmaf(x[q], LOG2E, -LOG2E * m));
+                }
+                return;
+            }
+        }
 #pragma unroll
         for (int q = 0; q < EPT; ++q) {
             const int idx = q * (C::WPC * 64) + tic;
@@ -1266,7 +1299,7 @@ HMM_DEV float repair_block_max(float v, float* red) {
 }
 
 __global__ __launch_bounds__(REPAIR_THREADS) void ld_repair_kernel(
-    const int* __restrict__ suspect, const float* __restrict__ prior, const float* __restrict__ A, const float* __restrict__ ll,
+    const double* __restrict__ part, int cps, const int* __restrict__ suspect, const float* __restrict__ prior, const float* __restrict__ A, const float* __restrict__ ll,
     const float* __restrict__ rowmax, long long T, int Dr, int shared_model, float* __restrict__ marg,
     float* __restrict__ filt, double* __restrict__ loglik_out) {
     __shared__ float Al[128 * REPAIR_ASTR];
@@ -1274,8 +1307,23 @@ __global__ __launch_bounds__(REPAIR_THREADS) void ld_repair_kernel(
     __shared__ float red[2];
     const int seq = blockIdx.x;
     const int j = threadIdx.x;
+    // log Z of the scans first: the ordered sum of the chunk evidences (what ld_finalize does where this
+    // kernel is not launched)
+    __shared__ double ev[REPAIR_THREADS];
+    {
+        double acc = 0.0;
+        for (int c = j; c < cps; c += REPAIR_THREADS) acc += part[(size_t)seq * cps + c];
+        ev[j] = acc;
+        __syncthreads();
+        for (int d = REPAIR_THREADS / 2; d >= 1; d >>= 1) {
+            if (j < d) ev[j] += ev[j + d];
+            __syncthreads();
+        }
+    }
+    const double logz = ev[0];
     // marked on the way, or a result that is not a number
-    const bool redo = suspect[seq] != 0 || !(loglik_out[seq] == loglik_out[seq]);
+    const bool redo = suspect[seq] != 0 || !(logz == logz);
+    if (j == 0 && !redo) loglik_out[seq] = logz;
     if (!__syncthreads_or(redo ? 1 : 0)) return;
 
     const bool live = j < Dr;
@@ -1478,7 +1526,9 @@ static int large_smooth_impl(const LargeArgs& a, float* marg, float* filt, doubl
     int* suspect = reinterpret_cast<int*>(ws + w.suspect);
     hipStream_t st = a.stream;
     const dim3 block(256);
-    {
+    // up to 32 states the aggregate kernel forms the row maxima on its way (when there is one: cps > 1)
+    const bool fold_rowmax = D <= 32 && p.cps > 1;
+    if (!fold_rowmax) {
         int width = 1;
         while (width < (a.D + 3) / 4) width <<= 1;
         const long long rpb = 4LL * STREAM_UNROLL * (64 / width);   // rows per workgroup
@@ -1490,7 +1540,8 @@ static int large_smooth_impl(const LargeArgs& a, float* marg, float* filt, doubl
         bout = nullptr;
     } else {
         launch("ld_aggregate", ld_aggregate_kernel<D>, dim3((unsigned)((p.nchunks + C::CPW - 1) / C::CPW)), block, st, a.A,
-               a.ll, rowmax, a.T, a.D, p.Lc, p.cps, p.nchunks, a.shared_model, agg, aggT, exps);
+               a.ll, rowmax, fold_rowmax ? 1 : 0, a.T, a.D, p.Lc, p.cps, p.nchunks, a.shared_model, agg, aggT, exps,
+               fold_rowmax ? suspect : (int*)nullptr, a.batch);
     }
     if (p.cps > 1 && p.two_level) {
         const long long ngroups = (long long)p.G * a.batch;
@@ -1527,9 +1578,11 @@ static int large_smooth_impl(const LargeArgs& a, float* marg, float* filt, doubl
         launch("ld_combine", ld_combine_kernel, dim3((unsigned)((rows + rows_per_block - 1) / rows_per_block)), block, st, F,
                Bv, rows, a.D, marg);
     }
-    launch("ld_finalize", ld_finalize_kernel, dim3((unsigned)a.batch), block, st, part, p.cps, loglik_out);
-    if (p.cps > 1)
-        launch("ld_repair", ld_repair_kernel, dim3((unsigned)a.batch), dim3(REPAIR_THREADS), st, (const int*)suspect, a.prior, a.A, a.ll,
+    if (p.cps == 1)
+        launch("ld_finalize", ld_finalize_kernel, dim3((unsigned)a.batch), block, st, part, p.cps, loglik_out);
+    else   // the sum of the chunk evidences, and the sequences that the carries marked
+        launch("ld_repair", ld_repair_kernel, dim3((unsigned)a.batch), dim3(REPAIR_THREADS), st, (const double*)part, p.cps,
+               (const int*)suspect, a.prior, a.A, a.ll,
                (const float*)rowmax, a.T, a.D, a.shared_model, marg, filt, loglik_out);
     return hipGetLastError() == hipSuccess ? 0 : 4;
 }
@@ -1592,7 +1645,7 @@ static int large_element_sp_impl(const LargeArgs& a, float* element, double* log
         launch("ld_rowmax", ld_rowmax_kernel, dim3((unsigned)((rows + rpb - 1) / rpb)), block, st, a.ll, rows, a.D, rowmax, (int*)nullptr, 0);
     }
     launch("ld_aggregate", ld_aggregate_kernel<D>, dim3((unsigned)((p.nchunks + C::CPW - 1) / C::CPW)), block, st, a.A,
-           a.ll, rowmax, a.T, a.D, p.Lc, p.cps, p.nchunks, a.shared_model, agg, aggT, exps);
+           a.ll, rowmax, 0, a.T, a.D, p.Lc, p.cps, p.nchunks, a.shared_model, agg, aggT, exps, (int*)nullptr, 0);
     const float* cur = agg;
     const float* curT = aggT;
     const int* cure = exps;
