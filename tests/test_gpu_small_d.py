@@ -147,6 +147,21 @@ def test_short_sequences_packed_into_workgroups(gu, D, T, B, shared):
     gu.check_transition_counts(p, label=label)
 
 
+def test_two_workgroups_per_compute_unit(gu):
+    """Two sequences of 2^20 - 3 steps in one call: 512 tiles, which fit the device only with two workgroups
+    resident per compute unit; the single-launch plan takes them, every tile waits for the 255 others of its
+    own sequence, and the two sequences' exchanges must not mix."""
+    import paper_2102_05743_amd as hmm
+    p = wl.random_problem(4, (1 << 20) - 3, batch=2, shared_model=False, seed=4242)
+    hmm.hmm_kernel_timing_enable(True)
+    try:
+        gu.check_smooth(p, label="2 x (2^20 - 3), D=4")
+        gu.check_viterbi(p, label="2 x (2^20 - 3), D=4")
+        print("kernels:", sorted(hmm.hmm_kernel_timing_get()), flush=True)
+    finally:
+        hmm.hmm_kernel_timing_enable(False)
+
+
 def test_very_long_sequence(gu, plan):
     """2^23 + 5 steps in one sequence: 2049 tiles, far more than fit the device at once, so the multi-launch
     kernels run whatever plan is asked for; every marginal and the whole path against the oracle."""
