@@ -256,8 +256,8 @@ hmm_status hmm_smooth_static(const float* prior, const float* A, const float* lo
                              float* marginals, float* filtered, double* loglik_out,
                              void* hip_stream);
 
-/* Static, human-readable name of a status code. */
-const char* hmm_status_string(hmm_status status);
+/* Static, human-readable name of a status code (an hmm_status; any other integer gives "HMM_ERR_UNKNOWN"). */
+const char* hmm_status_string(int32_t status);
 
 /*
  * Measurement aid (not part of the method): per-kernel timing with HIP events.

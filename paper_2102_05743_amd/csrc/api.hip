@@ -194,7 +194,7 @@ hmm_status hmm_workspace_status(const void* workspace, void* hip_stream, int32_t
     return HMM_OK;
 }
 
-const char* hmm_status_string(hmm_status status) {
+const char* hmm_status_string(int32_t status) {   // (an integer, not the enum: callers may pass anything)
     switch (status) {
         case HMM_OK: return "HMM_OK";
         case HMM_ERR_INVALID_ARG: return "HMM_ERR_INVALID_ARG";

@@ -39,7 +39,12 @@ hmm_status scratch_address(void** out) {
 extern "C" hmm_status hmm_smooth_static(const float* prior, const float* A, const float* loglik, int64_t T, int32_t D,
                                         int32_t batch, int32_t shared_model, float* marginals, float* filtered,
                                         double* loglik_out, void* hip_stream) {
-    // the shape's scratch need is known on the host: too large a shape is refused before anything else
+    // argument errors first, exactly as hmm_smooth reports them: with no workspace a call with valid arguments
+    // can only end in HMM_ERR_WORKSPACE, anything else is the verdict on the arguments
+    const hmm_status args = hmm_smooth(prior, A, loglik, T, D, batch, shared_model, marginals, filtered, loglik_out,
+                                       nullptr, 0, hip_stream);
+    if (args != HMM_ERR_WORKSPACE) return args;
+    // the shape's scratch need is known on the host: too large a shape is refused before any device call
     size_t need = 0;
     const hmm_status st = hmm_workspace_bytes(T, D, batch, &need, nullptr);
     if (st != HMM_OK) return st;
