@@ -612,8 +612,8 @@ HMM_DEV bool fetch_record(const unsigned long long* records, uint32_t tile, uint
 // scales they were stripped of (bits for SumProd, an offset for MaxPlus):
 // cf = forward potential before its first step (start (op) M_0 (op) ... (op) M_{c-1}),
 // cb = backward potential at its last step (M_{c+1} (op) ... (op) M_{tps-1} (op) ones).
-// The two ordered products are masked reductions over at most 2*128 tile slots: the first two
-// waves reduce the tiles before c, the last two the tiles after c (tps <= NT).
+// The ordered products are masked reductions over the tile slots (tps <= NT): with both directions the first two
+// waves reduce the tiles before c and the last two the tiles after c; forward only, all four reduce those before c.
 template <class S, int D, bool BWD>
 HMM_DEV bool grid_gather(const TileCoord& tc, int tps, const float (&start)[D], const FusedWs& ws, uint32_t tag,
                          GridLds<D>& gl, float (&cf)[D], double& cfs, float (&cb)[D], double& cbs) {
@@ -627,21 +627,24 @@ HMM_DEV bool grid_gather(const TileCoord& tc, int tps, const float (&start)[D], 
     // phase@12: seals seen
     const int wave = threadIdx.x >> 6;
     const int lane = threadIdx.x & 63;
-    const bool fwd_half = wave < 2;
-    // every lane of a half takes two neighbouring tiles of its side of this tile, straight into registers; after
-    // the seals the records are normally complete at the first attempt
-    const int u = (int)threadIdx.x & 127;                 // pair index 0..127 inside the half
-    const int ta = 2 * u, tb = 2 * u + 1;
-    const bool side = fwd_half || BWD;
-    const bool use_a = side && ta < tps && (fwd_half ? (ta < tc.tile) : (ta > tc.tile));
-    const bool use_b = side && tb < tps && (fwd_half ? (tb < tc.tile) : (tb > tc.tile));
+    // With both directions wanted, the first two waves take the tiles before this one and the last two those after
+    // it, every lane two neighbouring tiles; forward only, all four waves take the tiles before it, one per lane.
+    // Records go straight into registers; after the seals they are normally complete at the first attempt.
+    constexpr int NF = BWD ? 2 : 4;                       // waves on the forward side
+    const bool fwd_half = wave < NF;
+    const int u = (int)threadIdx.x & 127;                 // pair index 0..127 inside a half (both directions)
+    const int ta = BWD ? 2 * u : (int)threadIdx.x, tb = 2 * u + 1;
+    const bool use_a = ta < tps && (fwd_half ? (ta < tc.tile) : (ta > tc.tile));
+    const bool use_b = BWD && tb < tps && (fwd_half ? (tb < tc.tile) : (tb > tc.tile));
     Agg<S, D> Ma, Mb;
     if (ok) {
         ok = false;
         for (int spin = 0; spin <= ws.spin_limit; ++spin) {
             bool valid = true;
             if (use_a) valid = fetch_record<S, D>(ws.agg, (uint32_t)(tile0 + ta), tag, Ma);
-            if (use_b) valid = fetch_record<S, D>(ws.agg, (uint32_t)(tile0 + tb), tag, Mb) && valid;
+            if constexpr (BWD) {
+                if (use_b) valid = fetch_record<S, D>(ws.agg, (uint32_t)(tile0 + tb), tag, Mb) && valid;
+            }
             if (__syncthreads_and(valid ? 1 : 0)) {
                 ok = true;
                 break;
@@ -649,25 +652,36 @@ HMM_DEV bool grid_gather(const TileCoord& tc, int tps, const float (&start)[D], 
         }
     }
     // phase@13: aggregates staged
-    if (side) {
+    {
         Agg<S, D> X;
         if (!(ok && use_a)) agg_identity<S, D>(Ma);
-        if (!(ok && use_b)) agg_identity<S, D>(Mb);
+        if constexpr (BWD) {
+            if (!(ok && use_b)) agg_identity<S, D>(Mb);
+        }
         // lane 63 ends with the wave's ordered product
         if constexpr (S::is_max_plus) {
-            agg_mul<S, D, true>(Ma, Mb, X);
+            if constexpr (BWD) agg_mul<S, D, true>(Ma, Mb, X);
+            else X = Ma;
             wave_scan_prefix<S, D>(X);
         } else {
-            const double cs = wave_sum(Ma.c + Mb.c);      // the common scales just add up: no need to scan them
-            bool general = wave_any(!(agg_is_uniform<D>(Ma) && agg_is_uniform<D>(Mb)));
+            double cs = Ma.c;
+            bool general = !agg_is_uniform<D>(Ma);
+            if constexpr (BWD) {
+                cs += Mb.c;
+                general = general || !agg_is_uniform<D>(Mb);
+            }
+            cs = wave_sum(cs);                            // the common scales just add up: no need to scan them
+            general = wave_any(general);
             if (!general) {
                 bool bad = false;
-                agg_mul_u<D, false>(Ma, Mb, X, bad);
+                if constexpr (BWD) agg_mul_u<D, false>(Ma, Mb, X, bad);
+                else X = Ma;
                 wave_scan_up<S, D, false, false, true>(X, bad);
                 general = wave_any(bad);
             }
             if (general) {
-                agg_mul<S, D, false>(Ma, Mb, X);
+                if constexpr (BWD) agg_mul<S, D, false>(Ma, Mb, X);
+                else X = Ma;
                 wave_scan_up<S, D, false, false>(X);
             }
             X.c = cs;
@@ -678,11 +692,13 @@ HMM_DEV bool grid_gather(const TileCoord& tc, int tps, const float (&start)[D], 
     // phase@15: reduced
     // the wave products through the start vector / the vector of ones (every lane does the same work: no branch
     // below diverges)
-    Agg<S, D> Wf[2], Wb[2];
-    agg_load<S, D>(gl.red + 0 * G::W, Wf[0]);
-    agg_load<S, D>(gl.red + 1 * G::W, Wf[1]);
+    Agg<S, D> Wf[NF], Wb[2];
     bool uni = !S::is_max_plus;
-    if constexpr (!S::is_max_plus) uni = agg_is_uniform<D>(Wf[0]) && agg_is_uniform<D>(Wf[1]);
+#pragma unroll
+    for (int w = 0; w < NF; ++w) {
+        agg_load<S, D>(gl.red + w * G::W, Wf[w]);
+        if constexpr (!S::is_max_plus) uni = uni && agg_is_uniform<D>(Wf[w]);
+    }
     if constexpr (BWD) {
         agg_load<S, D>(gl.red + 2 * G::W, Wb[0]);
         agg_load<S, D>(gl.red + 3 * G::W, Wb[1]);
@@ -695,7 +711,7 @@ HMM_DEV bool grid_gather(const TileCoord& tc, int tps, const float (&start)[D], 
 #pragma unroll
         for (int j = 0; j < D; ++j) v[j] = start[j];
 #pragma unroll
-        for (int w = 0; w < 2; ++w) {
+        for (int w = 0; w < NF; ++w) {
             vs += Wf[w].c + vec_agg_m<U, S, D>(v, Wf[w], r);
 #pragma unroll
             for (int j = 0; j < D; ++j) v[j] = r[j];
