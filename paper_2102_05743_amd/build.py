@@ -18,6 +18,14 @@ UNITS = [("api.hip", [], "api.o"), ("ktimer.hip", [], "ktimer.o"), ("small_d.hip
          ("static_scratch.hip", [], "static_scratch.o")] + \
         [("small_d_kernels.hip", ["-DHMM_SMALL_D=%d" % d], "small_d_kernels_%d.o" % d) for d in range(1, 9)]
 
+# A second, small library for the tests: the same code with D = 4 only and tiles half as long (8 steps per lane
+# instead of 16), so that results can be shown not to depend on where the tile boundaries fall.
+VARIANT_LIB_PATH = os.path.join(HERE, "libhmmscan_tile8.so")
+VARIANT_UNITS = [("small_d_kernels.hip", ["-DHMM_SMALL_D=4", "-DHMM_ONLY_SMALL_D=4", "-DHMM_TILE_STEPS_PER_LANE=8"],
+                  "small_d_kernels_4_tile8.o"),
+                 ("small_d.hip", ["-DHMM_ONLY_SMALL_D=4"], "small_d_only4.o")]
+VARIANT_SHARED = ["api.o", "ktimer.o", "large_d_sp.o", "large_d_mp.o", "estep.o", "blocks.o", "static_scratch.o"]
+
 HIPCC_FLAGS = [
     "-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC",
     # packed-FP32 instructions are kept out of the generated code on purpose
@@ -47,16 +55,19 @@ def _compile(unit) -> str:
 def build_library(verbose: bool = True) -> str:
     os.makedirs(OBJ_DIR, exist_ok=True)
     with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1)) as ex:
-        objs = list(ex.map(_compile, UNITS))
-    tmp = LIB_PATH + ".tmp.%d" % os.getpid()
-    r = subprocess.run([_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs],
-                       capture_output=True, text=True)
-    if r.returncode != 0:
-        sys.stderr.write(r.stdout + r.stderr)
-        raise RuntimeError("link failed")
-    os.replace(tmp, LIB_PATH)
-    if verbose:
-        print("built", LIB_PATH)
+        all_objs = list(ex.map(_compile, UNITS + VARIANT_UNITS))
+    objs, variant_objs = all_objs[:len(UNITS)], all_objs[len(UNITS):]
+    variant_objs += [os.path.join(OBJ_DIR, o) for o in VARIANT_SHARED]
+    for path, members in ((LIB_PATH, objs), (VARIANT_LIB_PATH, variant_objs)):
+        tmp = path + ".tmp.%d" % os.getpid()
+        r = subprocess.run([_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *members],
+                           capture_output=True, text=True)
+        if r.returncode != 0:
+            sys.stderr.write(r.stdout + r.stderr)
+            raise RuntimeError("link failed")
+        os.replace(tmp, path)
+        if verbose:
+            print("built", path)
     return LIB_PATH
 
 

@@ -3,6 +3,14 @@
 
 namespace hmm {
 
+#ifdef HMM_ONLY_SMALL_D
+// A library that holds one state-space size only (the tile-size variant that the tests compare with the full
+// library): every other size is reported as unsupported.
+extern template struct SmallD<HMM_ONLY_SMALL_D>;
+
+#define HMM_DISPATCH_SMALL_D(D_, CALL) \
+    if ((D_) == HMM_ONLY_SMALL_D) return SmallD<HMM_ONLY_SMALL_D>::CALL;
+#else
 extern template struct SmallD<1>;
 extern template struct SmallD<2>;
 extern template struct SmallD<3>;
@@ -24,6 +32,7 @@ extern template struct SmallD<8>;
         case 8: return SmallD<8>::CALL; \
         default: break;                \
     }
+#endif
 
 size_t small_d_smooth_ws_bytes(int D, long long T, int batch) {
     HMM_DISPATCH_SMALL_D(D, smooth_ws_bytes(T, batch))

@@ -18,7 +18,11 @@ template <int D>
 struct SmallCfg {
     static constexpr int NT = 256;                    // lanes per workgroup
     static constexpr int NW = NT / 64;                // wavefronts per workgroup
+#ifdef HMM_TILE_STEPS_PER_LANE
+    static constexpr int L = HMM_TILE_STEPS_PER_LANE; // (build-time override for tile-size experiments: a multiple of four)
+#else
     static constexpr int L = (D <= 4) ? 16 : 8;       // time steps per lane
+#endif
     static constexpr int TILE = NT * L;               // time steps per workgroup
     static constexpr int ROW = L * D;                 // floats per lane in LDS
     static constexpr int VEC = (D % 4 == 0) ? 4 : 1;  // floats per global access

@@ -503,7 +503,7 @@ __global__ __launch_bounds__(256) void sd_viterbi_path_kernel(long long T, int t
 // Single-launch plan (all tiles co-resident)
 // =============================================================================================
 
-#if HMM_SMALL_D == 1
+#if HMM_SMALL_D == 1 || defined(HMM_ONLY_SMALL_D)
 // Zero fill of the exchange region (hmm_workspace_init): a kernel, so that it can be captured into a graph.
 __global__ void sd_zero_kernel(uint32_t* __restrict__ p, size_t n) {
     const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -1449,7 +1449,7 @@ size_t SmallD<D>::viterbi_ws_bytes(long long T, int batch) { return viterbi_ws<D
 
 template struct SmallD<HMM_SMALL_D>;
 
-#if HMM_SMALL_D == 1
+#if HMM_SMALL_D == 1 || defined(HMM_ONLY_SMALL_D)
 // Zero fill of a workspace's exchange region, enqueued on the stream (one definition for the library).
 int small_d_zero_region(void* ws, size_t bytes, hipStream_t stream) {
     const size_t n = bytes / sizeof(uint32_t);

@@ -31,8 +31,9 @@ def test_boundary_clean_under_asan_and_ubsan(tmp_path):
                            capture_output=True, text=True)
         assert r.returncode == 0, r.stderr
         objs.append(obj)
+    from paper_2102_05743_amd import build
     taken = {s.replace(".hip", ".o") for s in SANITIZED}
-    objs += [os.path.join(objdir, f) for f in sorted(os.listdir(objdir)) if f.endswith(".o") and f not in taken]
+    objs += [os.path.join(objdir, name) for _, _, name in build.UNITS if name not in taken]   # the main library's units
     lib = str(tmp_path / "libhmmscan_san.so")
     r = subprocess.run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-fsanitize=address,undefined",
                         "-fno-gpu-sanitize", "-o", lib, *objs], capture_output=True, text=True)

@@ -170,3 +170,43 @@ def test_very_long_sequence(gu, plan):
     p = wl.config2(T=(1 << 23) + 5, seed=77)
     gu.check_smooth(p, label="C2 model, T=2^23+5")
     gu.check_viterbi(p, label="C2 model, T=2^23+5")
+
+
+@pytest.mark.parametrize("T,B", [(2048 * 5 + 77, 1), (4096 * 3, 2), (1 << 18, 1), (100, 3)])
+def test_results_do_not_depend_on_the_tile_size(gu, T, B, monkeypatch):
+    """The same calls through a second build of the library whose tiles are half as long (8 steps per lane
+    instead of 16, D = 4 only): tile boundaries, chunk boundaries and the number of exchanged aggregates all
+    move, the results must not.  Each build is checked against the oracle; between the builds the decoded
+    paths must be identical and the marginals agree to rounding."""
+    import os
+
+    import numpy as np
+    import torch
+
+    import paper_2102_05743_amd as hmm
+    from paper_2102_05743_amd import binding
+
+    variant = os.path.join(os.path.dirname(binding.LIB_PATH), "libhmmscan_tile8.so")
+    if not os.path.exists(variant):
+        pytest.skip("the tile-size variant library is not built")
+    p = wl.random_problem(4, T, batch=B, shared_model=(B == 1), seed=900 + B)
+
+    def run():
+        dev = torch.device("cuda:0")
+        prior, A, ll = (torch.from_numpy(x).to(dev) for x in (p.prior, p.A, p.loglik))
+        marg, _, L = hmm.hmm_smooth(prior, A, ll)
+        path, lp = hmm.hmm_viterbi(prior, A, ll)
+        torch.cuda.synchronize()
+        return marg.cpu().numpy(), L.cpu().numpy(), path.cpu().numpy(), lp.cpu().numpy()
+
+    main = run()
+    gu.check_smooth(p, label=f"main build T={T} B={B}")
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", variant)
+    other = run()
+    gu.check_smooth(p, label=f"tile-size variant T={T} B={B}")
+    gu.check_viterbi(p, label=f"tile-size variant T={T} B={B}")
+    monkeypatch.setattr(binding, "_lib", None)   # the next user loads the main library again
+    assert np.array_equal(main[2], other[2]), "decoded paths differ between tile sizes"
+    assert float(np.abs(main[0] - other[0]).max()) <= 2e-5
+    assert np.allclose(main[1], other[1], rtol=1e-7) and np.allclose(main[3], other[3], rtol=1e-7)   # single-precision sums in another order
