@@ -186,6 +186,24 @@ hmm_status hmm_transition_counts(const float* A, const float* filtered, const fl
                                  void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * hmm_smooth and the expected transition counts in one call (the whole expectation step of Sec. V-C).
+ *   marginals[B][T][D], loglik_out[B]: as hmm_smooth.  counts[B][D][D] (fp64): as hmm_transition_counts.
+ * Up to eight states the smoother's backward recursion itself sums the pairwise posteriors
+ * p(x_{k-1}=i, x_k=j | y) = psi^f_{k-1}(i) psi_k(i,j) psi^b_k(j) / Z from the scaled potentials it holds in
+ * registers: no filtering distributions in memory, no second pass, and a state whose normalised probability
+ * lies below single-precision range still contributes (sequences of at most 1024 steps at D <= 4, 512 above,
+ * take a workgroup each here instead of sharing one).  Above eight states the call runs hmm_smooth (filtering
+ * distributions into the workspace) followed by hmm_transition_counts.
+ * Workspace: hmm_smooth_counts_workspace_bytes (includes the reserved bytes); same rules as hmm_smooth.
+ * Errors as hmm_smooth, plus HMM_ERR_INVALID_ARG for a null counts pointer.
+ */
+hmm_status hmm_smooth_counts_workspace_bytes(int64_t T, int32_t D, int32_t batch, size_t* bytes);
+hmm_status hmm_smooth_counts(const float* prior, const float* A, const float* loglik,
+                             int64_t T, int32_t D, int32_t batch, int32_t shared_model,
+                             float* marginals, double* loglik_out, double* counts,
+                             void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * Block-wise processing (Sec. V-B: a block of consecutive observations and states is ONE element of
  * the scan).  For sequences that are not resident in device memory as a whole, or whose blocks are
  * processed in different places: every block is reduced to its element, the elements give the

@@ -17,6 +17,7 @@ _lib = None
 
 EXPORTED_SYMBOLS = ("hmm_workspace_bytes", "hmm_workspace_init", "hmm_workspace_status", "hmm_smooth", "hmm_smooth_static", "hmm_viterbi", "hmm_max_product",
                     "hmm_transition_counts_workspace_bytes", "hmm_transition_counts",
+                    "hmm_smooth_counts_workspace_bytes", "hmm_smooth_counts",
                     "hmm_block_element_workspace_bytes", "hmm_block_element", "hmm_block_carries", "hmm_status_string",
                     "hmm_kernel_timing_enable", "hmm_kernel_timing_count", "hmm_kernel_timing_get")
 
@@ -62,6 +63,11 @@ def load_library():
         lib.hmm_transition_counts.argtypes = [vp, vp, vp, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                                               vp, vp, sz, vp]
         lib.hmm_transition_counts.restype = ctypes.c_int
+        lib.hmm_smooth_counts_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.POINTER(sz)]
+        lib.hmm_smooth_counts_workspace_bytes.restype = ctypes.c_int
+        lib.hmm_smooth_counts.argtypes = [vp, vp, vp, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
+                                          vp, vp, vp, vp, sz, vp]
+        lib.hmm_smooth_counts.restype = ctypes.c_int
         lib.hmm_block_element_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.POINTER(sz)]
         lib.hmm_block_element_workspace_bytes.restype = ctypes.c_int
         lib.hmm_block_element.argtypes = [vp, vp, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
@@ -343,6 +349,44 @@ def hmm_transition_counts(A, filtered, marginals, counts=None, workspace=None):
     if rc != HMM_OK:
         raise HmmError(rc, "hmm_transition_counts")
     return counts
+
+
+def hmm_smooth_counts_workspace_bytes(T: int, D: int, batch: int) -> int:
+    lib = load_library()
+    n = ctypes.c_size_t(0)
+    rc = lib.hmm_smooth_counts_workspace_bytes(int(T), int(D), int(batch), ctypes.byref(n))
+    if rc != HMM_OK:
+        raise HmmError(rc, "hmm_smooth_counts_workspace_bytes")
+    return int(n.value)
+
+
+def hmm_smooth_counts(prior, A, loglik, marginals=None, loglik_out=None, counts=None, workspace=None):
+    """The expectation step in one call.  Returns (marginals[B][T][D] f32, loglik_out[B] f64, counts[B][D][D] f64);
+    asynchronous on torch's current stream."""
+    import torch
+    lib = load_library()
+    B, T, D, Bm, shared = _shapes(prior, A, loglik)
+    f32 = torch.float32
+    _check(prior, f32, (Bm, D), "prior")
+    _check(A, f32, (Bm, D, D), "A")
+    _check(loglik, f32, (B, T, D), "loglik")
+    dev = loglik.device
+    if marginals is None:
+        marginals = torch.empty((B, T, D), dtype=f32, device=dev)
+    if loglik_out is None:
+        loglik_out = torch.empty((B,), dtype=torch.float64, device=dev)
+    if counts is None:
+        counts = torch.empty((B, D, D), dtype=torch.float64, device=dev)
+    _check(marginals, f32, (B, T, D), "marginals")
+    _check(loglik_out, torch.float64, (B,), "loglik_out")
+    _check(counts, torch.float64, (B, D, D), "counts")
+    if workspace is None:
+        workspace = new_workspace(hmm_smooth_counts_workspace_bytes(T, D, B), dev)
+    rc = lib.hmm_smooth_counts(_ptr(prior), _ptr(A), _ptr(loglik), T, D, B, shared, _ptr(marginals), _ptr(loglik_out),
+                               _ptr(counts), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream())
+    if rc != HMM_OK:
+        raise HmmError(rc, "hmm_smooth_counts")
+    return marginals, loglik_out, counts
 
 
 def hmm_block_element_workspace_bytes(T: int, D: int, batch: int) -> int:

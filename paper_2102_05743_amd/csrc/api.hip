@@ -133,6 +133,59 @@ hmm_status hmm_transition_counts(const float* A, const float* filtered, const fl
     return static_cast<hmm_status>(hmm::transition_counts(a, counts));
 }
 
+namespace {
+size_t align256(size_t x) { return (x + 255) / 256 * 256; }
+// Workspace of hmm_smooth_counts: the smoother's own, then either the per-tile pair sums (D <= 8, sequences
+// longer than the packed plan takes) or, for the two-call form, the filtering distributions and the scratch of
+// the counting kernels.
+struct CountsWs { size_t smooth, extra, total; };
+CountsWs counts_ws(int64_t T, int32_t D, int32_t batch) {
+    CountsWs w{0, 0, 0};
+    hmm_workspace_bytes(T, D, batch, &w.smooth, nullptr);
+    w.extra = align256(w.smooth);
+    const size_t two_calls = align256((size_t)T * D * batch * sizeof(float)) + hmm::transition_counts_ws_bytes(D, T, batch);
+    size_t pairs = 0;
+    if (D <= hmm::SMALL_D_MAX) pairs = (size_t)hmm::small_d_tiles(D, T) * batch * D * D * sizeof(float);
+    w.total = w.extra + (two_calls > pairs ? two_calls : pairs);
+    return w;
+}
+}  // namespace
+
+hmm_status hmm_smooth_counts_workspace_bytes(int64_t T, int32_t D, int32_t batch, size_t* bytes) {
+    if (T < 1 || D < 1 || batch < 1 || !bytes) return HMM_ERR_INVALID_ARG;
+    if (D > HMM_MAX_STATES) return HMM_ERR_UNSUPPORTED;
+    *bytes = counts_ws(T, D, batch).total;
+    return HMM_OK;
+}
+
+hmm_status hmm_smooth_counts(const float* prior, const float* A, const float* loglik, int64_t T, int32_t D, int32_t batch,
+                             int32_t shared_model, float* marginals, double* loglik_out, double* counts, void* workspace,
+                             size_t workspace_bytes, void* hip_stream) {
+    hmm_status st = check_common(prior, A, loglik, T, D, batch);
+    if (st != HMM_OK) return st;
+    if (!marginals || !loglik_out || !counts || !aligned16(marginals)) return HMM_ERR_INVALID_ARG;
+    const CountsWs w = counts_ws(T, D, batch);
+    if (!workspace || workspace_bytes < w.total || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return HMM_ERR_WORKSPACE;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    char* extra = static_cast<char*>(workspace) + w.extra;
+    if (D <= hmm::SMALL_D_MAX) {
+        // one pass: the smoother's backward recursion sums the pairwise posteriors where it has both potentials
+        hmm::SmallArgs a{prior, A, loglik, (long long)T, batch, shared_model ? 1 : 0, workspace, w.smooth, stream};
+        long long tiles = 0;
+        const int rc = hmm::small_d_smooth_pairs(D, a, marginals, loglik_out, reinterpret_cast<float*>(extra), &tiles);
+        if (rc != 0) return static_cast<hmm_status>(rc);
+        return static_cast<hmm_status>(
+            hmm::reduce_pair_partials(reinterpret_cast<const float*>(extra), (int)tiles, D, batch, counts, stream));
+    }
+    float* filtered = reinterpret_cast<float*>(extra);
+    st = hmm_smooth(prior, A, loglik, T, D, batch, shared_model, marginals, filtered, loglik_out, workspace, w.smooth, hip_stream);
+    if (st != HMM_OK) return st;
+    char* tc = extra + align256((size_t)T * D * batch * sizeof(float));
+    hmm::EstepArgs e{A, filtered, marginals, (long long)T, D, batch, shared_model ? 1 : 0, tc,
+                     workspace_bytes - (size_t)(tc - static_cast<char*>(workspace)), stream};
+    return static_cast<hmm_status>(hmm::transition_counts(e, counts));
+}
+
 hmm_status hmm_block_element_workspace_bytes(int64_t T, int32_t D, int32_t batch, size_t* bytes) {
     if (T < 1 || D < 1 || batch < 1 || !bytes) return HMM_ERR_INVALID_ARG;
     if (D > HMM_MAX_STATES) return HMM_ERR_UNSUPPORTED;

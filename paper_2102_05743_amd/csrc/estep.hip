@@ -579,4 +579,13 @@ int transition_counts(const EstepArgs& a, double* counts) {
     return hipGetLastError() == hipSuccess ? 0 : 4;
 }
 
+int reduce_pair_partials(const float* partial, int G, int D, int batch, double* counts, hipStream_t stream) {
+    const int E = D * D;
+    int EPB = 1;
+    while (EPB < E && EPB < 32) EPB <<= 1;
+    launch("tc_reduce", tc_reduce_kernel, dim3((unsigned)batch, (unsigned)((E + EPB - 1) / EPB)), dim3(256), stream, partial,
+           G, D, D, EPB, counts);
+    return hipGetLastError() == hipSuccess ? 0 : 4;
+}
+
 }  // namespace hmm

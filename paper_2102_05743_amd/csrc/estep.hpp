@@ -22,5 +22,7 @@ struct EstepArgs {
 // Return codes follow hmm_status (0 ok, 2 unsupported, 3 workspace, 4 device).
 size_t transition_counts_ws_bytes(int D, long long T, int batch);
 int transition_counts(const EstepArgs& a, double* counts);
+// counts[seq] = sum over the sequence's G partial sums (partial[seq][G][D*D] floats, D <= 8), in fp64
+int reduce_pair_partials(const float* partial, int G, int D, int batch, double* counts, hipStream_t stream);
 
 }  // namespace hmm

@@ -49,6 +49,16 @@ int small_d_smooth(int D, const SmallArgs& a, float* marg, float* filt, double* 
     return 2;
 }
 
+int small_d_smooth_pairs(int D, const SmallArgs& a, float* marg, double* loglik_out, float* pair_partial, long long* tiles) {
+    HMM_DISPATCH_SMALL_D(D, smooth_pairs(a, marg, loglik_out, pair_partial, tiles))
+    return 2;
+}
+
+long long small_d_tiles(int D, long long T) {
+    HMM_DISPATCH_SMALL_D(D, tiles(T))
+    return 0;
+}
+
 int small_d_viterbi(int D, const SmallArgs& a, int32_t* path, double* logprob_out) {
     HMM_DISPATCH_SMALL_D(D, viterbi(a, path, logprob_out))
     return 2;

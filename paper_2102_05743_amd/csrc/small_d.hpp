@@ -31,8 +31,12 @@ constexpr size_t XCH_REGION_BYTES = 384 * 1024;
 template <int D>
 struct SmallD {
     static size_t smooth_ws_bytes(long long T, int batch);
+    static long long tiles(long long T);   // tiles per sequence
     static size_t viterbi_ws_bytes(long long T, int batch);
     static int smooth(const SmallArgs& a, float* marg, float* filt, double* loglik_out);
+    // the smoother that also leaves per-tile sums of pairwise posteriors (pair_partial[batch * tiles][D*D], tiles =
+    // tiles per sequence, reported)
+    static int smooth_pairs(const SmallArgs& a, float* marg, double* loglik_out, float* pair_partial, long long* tiles);
     static int viterbi(const SmallArgs& a, int32_t* path, double* logprob_out);
     static int max_product(const SmallArgs& a, float* maxmarg, int32_t* path, double* logprob_out);
     static size_t element_ws_bytes(long long T, int batch);
@@ -42,6 +46,8 @@ struct SmallD {
 size_t small_d_smooth_ws_bytes(int D, long long T, int batch);
 size_t small_d_viterbi_ws_bytes(int D, long long T, int batch);
 int small_d_smooth(int D, const SmallArgs& a, float* marg, float* filt, double* loglik_out);
+int small_d_smooth_pairs(int D, const SmallArgs& a, float* marg, double* loglik_out, float* pair_partial, long long* tiles);
+long long small_d_tiles(int D, long long T);   // tiles per sequence (0 for sizes this path does not take)
 int small_d_viterbi(int D, const SmallArgs& a, int32_t* path, double* logprob_out);
 int small_d_max_product(int D, const SmallArgs& a, float* maxmarg, int32_t* path, double* logprob_out);
 size_t small_d_element_ws_bytes(int D, long long T, int batch);

@@ -813,12 +813,35 @@ HMM_DEV void backward_plain(float (&b)[D], const int (&bex)[D]) {
 // Backward: a_{k:T+1} (Theorem 2) and the marginal f_k b_k / Z_k, written over the emission
 // factors in LDS.  b enters as the backward potential at the chunk's last step in the raw form of
 // carry_backward; every step rescales it to a largest entry near 2^VEC_BIAS.
-template <int D, bool FULL>
-HMM_DEV void sp_backward_impl(float* row, int n, const float (&Am)[D * D], float (&b)[D], const int (&bex)[D],
-                              const float (&F)[SmallCfg<D>::L][D]) {
+// COUNTS: also accumulate the pairwise posteriors of the transitions INTO the lane's steps (the expectation
+// step's statistic, Sec. V-C), p(x_{k-1}=i, x_k=j | y) = f_{k-1}(i) A(i,j) e_k(j) b_k(j) / s_k, where
+// s_k = sum_i f_{k-1}(i) (A (e_k o b_k))(i) is the normaliser of the marginal at k-1: with t = e_k o b_k and
+// r = A t already formed for the backward step, that is acc(i,j) += (f_{k-1}(i) / s_k) t(j); the factor A(i,j) is
+// applied once at the end by the caller, which also discards the sums of forbidden transitions (A(i,j) = 0: their
+// terms are not posteriors and may have overflowed).  fin = forward potential entering the chunk (f_{k-1} for the chunk's
+// first step; unused where that step is the sequence's first, which has no transition).  The potentials are
+// the scaled ones (largest entries near 2^VEC_BIAS): nothing is lost that the marginals themselves keep.
+template <int D, bool FULL, bool COUNTS>
+HMM_DEV void sp_backward_impl(float* row, int n, bool first, const float (&Am)[D * D], float (&b)[D],
+                              const int (&bex)[D], const float (&F)[SmallCfg<D>::L][D], const float (&fin)[D],
+                              float (&acc)[COUNTS ? D * D : 1]) {
     using C = SmallCfg<D>;
     using S = SumProd;
     backward_plain<D>(b, bex);
+    // bn = r 2^-ex is the rescaled backward potential of step k-1: the normaliser is taken against it (a plain
+    // number near 2^(2 VEC_BIAS) even where r itself is far down), and 2^-ex goes into the left factor
+    auto pair_sums = [&](const float (&fprev)[D], const float (&t)[D], const float (&bn)[D], int ex) {
+        float s = fprev[0] * bn[0];
+#pragma unroll
+        for (int i = 1; i < D; ++i) s = fmaf(fprev[i], bn[i], s);
+        const float inv = (s > 0.0f) ? __builtin_amdgcn_rcpf(s) : 0.0f;
+#pragma unroll
+        for (int i = 0; i < D; ++i) {
+            const float w = ldexpf(fprev[i] * inv, -ex);
+#pragma unroll
+            for (int j = 0; j < D; ++j) acc[i * D + j] = fmaf(w, t[j], acc[i * D + j]);
+        }
+    };
 #pragma unroll
     for (int k = C::L - 1; k >= 0; --k) {
         if (FULL || k < n) {
@@ -830,7 +853,7 @@ HMM_DEV void sp_backward_impl(float* row, int n, const float (&Am)[D * D], float
 #pragma unroll
             for (int j = 0; j < D; ++j) gam[j] *= inv;
             lds_write_vec<D>(row + k * D, gam);
-            if (k > 0) {
+            if (k > 0 || (COUNTS && !first)) {
                 float t[D], r[D];
 #pragma unroll
                 for (int j = 0; j < D; ++j) t[j] = ev[j] * b[j];
@@ -838,15 +861,15 @@ HMM_DEV void sp_backward_impl(float* row, int n, const float (&Am)[D * D], float
                 const int ex = __builtin_amdgcn_frexp_expf(max_of(r)) - VEC_BIAS;
 #pragma unroll
                 for (int j = 0; j < D; ++j) b[j] = ldexpf(r[j], -ex);
+                if constexpr (COUNTS) {
+                    if (k > 0) pair_sums(F[k - 1], t, b, ex);
+                    else pair_sums(fin, t, b, ex);
+                }
             }
         }
     }
 }
 
-// ---------------------------------------------------------------------------------------------
-// Max-plus work inside a lane's chunk: V_k and the back-pointers u_{k-1}(x_k) of Sec. IV-A.
-// v enters as the carry (max 0, or the log prior for the first chunk) and leaves as V at the
-// chunk's last step with max 0.
 template <int D, bool FULL>
 HMM_DEV void mp_forward_impl(const float* row, int n, bool first, const float (&Am)[D * D], float (&v)[D],
                                uint32_t (&bp)[SmallCfg<D>::W]) {

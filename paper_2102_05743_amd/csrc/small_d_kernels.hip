@@ -318,9 +318,9 @@ __global__ __launch_bounds__(256) void sd_carry_kernel(const float* __restrict__
 // Lane-level two-filter work shared by all plans: forward scan, reversed scan and their per-step
 // combination inside the lane's chunk.  SumProd: marginals (Alg. 3).  MaxPlus: max-marginals
 // (Alg. 5 / Theorem 4).
-template <class S, int D, bool WRITE_FILT>
+template <class S, int D, bool WRITE_FILT, bool COUNTS = false>
 HMM_DEV void smooth_chunk(float* row, int n, bool first, const float (&Am)[D * D], float (&f)[D], float (&b)[D],
-                          const int (&bex)[D], float* __restrict__ filt_dst) {
+                          const int (&bex)[D], float* __restrict__ filt_dst, float (&acc)[COUNTS ? D * D : 1]) {
     using C = SmallCfg<D>;
     float F[C::L][D];
     if constexpr (S::is_max_plus) {
@@ -334,28 +334,63 @@ HMM_DEV void smooth_chunk(float* row, int n, bool first, const float (&Am)[D * D
             mpv_backward_impl<D, false>(row, n, Am, b, F);
         }
     } else {
+        float fin[D];
+#pragma unroll
+        for (int j = 0; j < D; ++j) fin[j] = f[j];
         if (n == C::L) {
             sp_forward_impl<D, WRITE_FILT, true>(row, n, first, Am, f, F, filt_dst);
-            sp_backward_impl<D, true>(row, n, Am, b, bex, F);
+            sp_backward_impl<D, true, COUNTS>(row, n, first, Am, b, bex, F, fin, acc);
         } else {
             sp_forward_impl<D, WRITE_FILT, false>(row, n, first, Am, f, F, filt_dst);
-            sp_backward_impl<D, false>(row, n, Am, b, bex, F);
+            sp_backward_impl<D, false, COUNTS>(row, n, first, Am, b, bex, F, fin, acc);
         }
+    }
+}
+template <class S, int D, bool WRITE_FILT>
+HMM_DEV void smooth_chunk(float* row, int n, bool first, const float (&Am)[D * D], float (&f)[D], float (&b)[D],
+                          const int (&bex)[D], float* __restrict__ filt_dst) {
+    float unused[1];
+    smooth_chunk<S, D, WRITE_FILT, false>(row, n, first, Am, f, b, bex, filt_dst, unused);
+}
+
+// The lanes' pairwise-posterior sums of a workgroup added up, multiplied by the transition probabilities and
+// written as the workgroup's partial sum (D*D floats).  `red`: NW * D * D floats of LDS.  Contains a barrier.
+template <class S, int D>
+HMM_DEV void store_pair_sums(const float (&acc)[D * D], const float (&Am)[D * D], float* red, float* __restrict__ dst) {
+    using C = SmallCfg<D>;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int e = 0; e < D * D; ++e) {
+        float v = (Am[e] > 0.0f) ? acc[e] * Am[e] : 0.0f;   // (a forbidden transition's sum is not a posterior: see sp_backward_impl)
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) v += __shfl_down(v, d, 64);
+        if (lane == 0) red[wave * D * D + e] = v;
+    }
+    __syncthreads();
+    if ((int)threadIdx.x < D * D) {
+        float v = 0.0f;
+#pragma unroll
+        for (int w = 0; w < C::NW; ++w) v += red[w * D * D + threadIdx.x];
+        dst[threadIdx.x] = v;
     }
 }
 
 // Kernel 3 (smoother, max-product): forward scan, reversed scan and (max-)marginals inside a tile;
 // `argmax`, if given, receives the per-step maximiser (Theorem 4).
-template <class S, int D, bool WRITE_FILT>
+// COUNTS (sum-product): each workgroup also leaves the sum of the pairwise posteriors of its steps' transitions,
+// times A, in pair_partial[workgroup][D*D] (the expectation step's statistic; added up per sequence afterwards).
+template <class S, int D, bool WRITE_FILT, bool COUNTS = false>
 __global__ __launch_bounds__(256) void sd_smooth_apply_kernel(const float* __restrict__ A,
                                                               const float* __restrict__ ll, long long T, int tps,
                                                               int shared_model, const float* __restrict__ fin_g,
                                                               const float* __restrict__ bout_g,
                                                               float* __restrict__ marg, float* __restrict__ filt,
-                                                              int32_t* __restrict__ argmax) {
+                                                              int32_t* __restrict__ argmax,
+                                                              float* __restrict__ pair_partial) {
     using C = SmallCfg<D>;
     __shared__ float lds[C::LDS_FLOATS];
     __shared__ __align__(8) float wagg[C::NW * AggImage<D>::WORDS];
+    __shared__ float pair_red[COUNTS ? C::NW * D * D : 1];
     const TileCoord tc = tile_coord<D>(T, tps);
     load_tile<D>(ll + tc.base * D, tc.nvalid, lds);
     float Am[D * D];
@@ -378,10 +413,14 @@ __global__ __launch_bounds__(256) void sd_smooth_apply_kernel(const float* __res
     // (the filtering distributions go to memory lane by lane here: a second staging tile would halve the
     // workgroups per compute unit, which costs more than the scattered stores)
     float* fdst = WRITE_FILT ? filt + (tc.base + (long long)threadIdx.x * C::L) * D : nullptr;
-    smooth_chunk<S, D, WRITE_FILT>(row, n, first, Am, f, b, bex, fdst);
+    float acc[COUNTS ? D * D : 1];
+#pragma unroll
+    for (int e = 0; e < (COUNTS ? D * D : 1); ++e) acc[e] = 0.0f;
+    smooth_chunk<S, D, WRITE_FILT, COUNTS>(row, n, first, Am, f, b, bex, fdst, acc);
     __syncthreads();
     store_tile<D>(marg + tc.base * D, tc.nvalid, lds);
     if (argmax != nullptr) store_argmax_tile<D>(argmax + tc.base, tc.nvalid, lds);
+    if constexpr (COUNTS) store_pair_sums<S, D>(acc, Am, pair_red, pair_partial + (size_t)blockIdx.x * D * D);
 }
 
 // Lane-level Viterbi forward work shared by all plans: h receives the chunk map, xs the final state if
@@ -757,18 +796,20 @@ HMM_DEV void finish_sequence(const FusedWs& ws, uint32_t tag, bool ok, double ev
     if (last) coherent_store(&ws.hdr->generation, tag);
 }
 
-template <class S, int D, bool WRITE_FILT>
+template <class S, int D, bool WRITE_FILT, bool COUNTS = false>
 __global__ __launch_bounds__(256) void sd_smooth_fused_kernel(const float* __restrict__ prior,
                                                               const float* __restrict__ A,
                                                               const float* __restrict__ ll, long long T, int tps,
                                                               int shared_model, float* __restrict__ marg,
                                                               float* __restrict__ filt, int32_t* __restrict__ argmax,
-                                                              double* __restrict__ loglik_out, FusedWs ws) {
+                                                              double* __restrict__ loglik_out, FusedWs ws,
+                                                              float* __restrict__ pair_partial) {
     using C = SmallCfg<D>;
     constexpr int W = AggImage<D>::WORDS;
     __shared__ float lds[C::LDS_FLOATS];
     // the filtering distributions of the tile are staged like the marginals, in a tile of their own
     __shared__ float flds[WRITE_FILT ? C::LDS_FLOATS : 1];
+    __shared__ float pair_red[COUNTS ? C::NW * D * D : 1];   // (COUNTS: see sd_smooth_apply_kernel)
     __shared__ GridLds<D> gl;
     __shared__ __align__(8) float wagg[C::NW * W];
     __shared__ __align__(8) float wtot[W];
@@ -833,12 +874,16 @@ __global__ __launch_bounds__(256) void sd_smooth_fused_kernel(const float* __res
     carry_backward_auto<S, D>(R, uni_r, wagg, &wprod, cb, b, bex);
     // phase: lane carries
     float* fdst = WRITE_FILT ? flds + threadIdx.x * C::STRIDE : nullptr;
-    smooth_chunk<S, D, WRITE_FILT>(row, n, first, Am, f, b, bex, fdst);
+    float acc[COUNTS ? D * D : 1];
+#pragma unroll
+    for (int e = 0; e < (COUNTS ? D * D : 1); ++e) acc[e] = 0.0f;
+    smooth_chunk<S, D, WRITE_FILT, COUNTS>(row, n, first, Am, f, b, bex, fdst, acc);
     // phase: chunk recursions
     __syncthreads();   // all marginals are in LDS (and the first wave's tile total)
     store_tile<D>(marg + tc.base * D, tc.nvalid, lds);
     if constexpr (WRITE_FILT) store_tile<D>(filt + tc.base * D, tc.nvalid, flds);
     if (argmax != nullptr) store_argmax_tile<D>(argmax + tc.base, tc.nvalid, lds);
+    if constexpr (COUNTS) store_pair_sums<S, D>(acc, Am, pair_red, pair_partial + (size_t)blockIdx.x * D * D);
     // phase: stored
     // evidence of the sequence, by its last tile: (forward potential entering it) (op) M_last, summed / maximised
     // over the final state -- no backward potential is involved, so no state the two disagree on can be lost
@@ -1288,10 +1333,15 @@ static FusedWs fused_ws(char* ws, int batch) {
 
 // The two-filter plans for either operator: marginals + optional filtered + log evidence (SumProd),
 // or max-marginals + optional per-step maximiser + log of the best joint weight (MaxPlus).
+// pair_partial (SumProd without a filtered output only): the kernels also leave, per tile, the sum of the pairwise
+// posteriors of the tile's transitions (D*D floats each).  Sequences short enough to share workgroups then take a
+// workgroup each (the packed kernels have no such output).
 template <class S, int D>
-static int two_filter(const SmallArgs& a, float* marg, float* filt, int32_t* argmax, double* out) {
+static int two_filter(const SmallArgs& a, float* marg, float* filt, int32_t* argmax, double* out,
+                      float* pair_partial = nullptr) {
     using C = SmallCfg<D>;
     constexpr bool MP = S::is_max_plus;
+    if (pair_partial != nullptr && (MP || filt != nullptr)) return 2;
     const long long tps = tiles_per_seq<D>(a.T);
     const long long nt = tps * a.batch;
     if (nt > 0x7fffffffLL) return 2;
@@ -1309,10 +1359,13 @@ static int two_filter(const SmallArgs& a, float* marg, float* filt, int32_t* arg
         if (filt) cap = resident_capacity<0>(sd_smooth_fused_kernel<S, D, true>);
     }
     if (!filt) cap = resident_capacity<(MP ? 5 : 1)>(sd_smooth_fused_kernel<S, D, false>);
+    if constexpr (!MP) {
+        if (pair_partial) cap = resident_capacity<6>(sd_smooth_fused_kernel<S, D, false, true>);
+    }
     if (MP && filt) return 2;   // no filtered output is defined for the max-product plan
     if (cap > XCH_MAX_TILES) cap = XCH_MAX_TILES;
     const int lcpl = packed_log2_lanes<D>(a.T);
-    if (!force_multi_launch() && lcpl >= 0) {
+    if (!force_multi_launch() && lcpl >= 0 && pair_partial == nullptr) {
         // short sequences, several per workgroup: one launch, no workspace
         const int spw = C::NT >> lcpl;
         const dim3 pgrid((unsigned)((a.batch + spw - 1) / spw));
@@ -1335,11 +1388,16 @@ static int two_filter(const SmallArgs& a, float* marg, float* filt, int32_t* arg
         if constexpr (!MP) {
             if (filt)
                 launch(name, sd_smooth_fused_kernel<S, D, true>, grid, block, st, a.prior, a.A, a.ll, a.T, itps,
-                       a.shared_model, marg, filt, argmax, out, fw);
+                       a.shared_model, marg, filt, argmax, out, fw, (float*)nullptr);
         }
-        if (!filt)
+        if constexpr (!MP) {
+            if (pair_partial)
+                launch(name, sd_smooth_fused_kernel<S, D, false, true>, grid, block, st, a.prior, a.A, a.ll, a.T, itps,
+                       a.shared_model, marg, filt, argmax, out, fw, pair_partial);
+        }
+        if (!filt && !pair_partial)
             launch(name, sd_smooth_fused_kernel<S, D, false>, grid, block, st, a.prior, a.A, a.ll, a.T, itps,
-                   a.shared_model, marg, filt, argmax, out, fw);
+                   a.shared_model, marg, filt, argmax, out, fw, (float*)nullptr);
     } else {
         launch(MP ? "sd_reduce_mp" : "sd_reduce_sp", sd_reduce_kernel<S, D>, grid, block, st, a.A, a.ll, a.T, itps,
                a.shared_model, agg);
@@ -1349,11 +1407,16 @@ static int two_filter(const SmallArgs& a, float* marg, float* filt, int32_t* arg
         if constexpr (!MP) {
             if (filt)
                 launch(name, sd_smooth_apply_kernel<S, D, true>, grid, block, st, a.A, a.ll, a.T, itps, a.shared_model,
-                       fin, bout, marg, filt, argmax);
+                       fin, bout, marg, filt, argmax, (float*)nullptr);
         }
-        if (!filt)
+        if constexpr (!MP) {
+            if (pair_partial)
+                launch(name, sd_smooth_apply_kernel<S, D, false, true>, grid, block, st, a.A, a.ll, a.T, itps,
+                       a.shared_model, fin, bout, marg, filt, argmax, pair_partial);
+        }
+        if (!filt && !pair_partial)
             launch(name, sd_smooth_apply_kernel<S, D, false>, grid, block, st, a.A, a.ll, a.T, itps, a.shared_model,
-                   fin, bout, marg, filt, argmax);
+                   fin, bout, marg, filt, argmax, (float*)nullptr);
     }
     return hipGetLastError() == hipSuccess ? 0 : 4;
 }
@@ -1361,6 +1424,15 @@ static int two_filter(const SmallArgs& a, float* marg, float* filt, int32_t* arg
 template <int D>
 int SmallD<D>::smooth(const SmallArgs& a, float* marg, float* filt, double* loglik_out) {
     return two_filter<SumProd, D>(a, marg, filt, nullptr, loglik_out);
+}
+
+template <int D>
+long long SmallD<D>::tiles(long long T) { return tiles_per_seq<D>(T); }
+
+template <int D>
+int SmallD<D>::smooth_pairs(const SmallArgs& a, float* marg, double* loglik_out, float* pair_partial, long long* tiles) {
+    *tiles = tiles_per_seq<D>(a.T);
+    return two_filter<SumProd, D>(a, marg, nullptr, nullptr, loglik_out, pair_partial);
 }
 
 template <int D>

@@ -135,3 +135,29 @@ def check_transition_counts(p, label=""):
     Am = np.broadcast_to(p.A, (p.batch,) + p.A.shape[1:])
     assert (N[Am == 0] == 0).all(), f"{label}: a forbidden transition was counted"
     return err
+
+
+def check_smooth_counts(p, label=""):
+    """hmm_smooth_counts (marginals, log-likelihood and expected transition counts in one call) against the
+    oracle: marginals and log-likelihood to check_smooth's bounds, counts to check_transition_counts's."""
+    prior, A, ll = to_dev(p)
+    marg, L, counts = hmm.hmm_smooth_counts(prior, A, ll)
+    torch.cuda.synchronize()
+    marg, L, N = marg.cpu().numpy(), L.cpu().numpy(), counts.cpu().numpy()
+    m0, _, L0 = oracle.smooth_batch(p.prior, p.A, p.loglik, p.shared_model, want_filtered=False)
+    N0 = oracle.transition_counts_batch(p.prior, p.A, p.loglik, p.shared_model)
+    assert np.isfinite(marg).all(), f"{label}: non-finite marginals"
+    merr = float(np.abs(marg - m0).max())
+    rel = float(np.abs((L - L0) / L0).max()) if np.all(L0 != 0) else float(np.abs(L - L0).max())
+    n = max(p.T - 1, 0)
+    tol = 1e-4 * np.sqrt(n) + 1e-6 * n + 1e-12
+    err = float(np.abs(N - N0).max()) if n else float(np.abs(N).max())
+    print(f"[smooth+counts {label or p.name}] B={p.batch} T={p.T} D={p.D} max|dmarg|={merr:.3e} rel dloglik={rel:.3e} "
+          f"max|dN|={err:.3e} (tol {tol:.3e})", flush=True)
+    assert merr <= MARG_ATOL and rel <= LOGLIK_RTOL, f"{label}: marginals off by {merr}, log-likelihood by {rel}"
+    assert np.isfinite(N).all() and (N >= 0).all(), f"{label}: counts must be finite and non-negative"
+    assert err <= tol, f"{label}: transition counts off by {err} (tolerance {tol})"
+    assert np.abs(N.sum(axis=(1, 2)) - n).max() <= 1e-5 * n + 1e-9, f"{label}: counts must sum to T-1"
+    Am = np.broadcast_to(p.A, (p.batch,) + p.A.shape[1:])
+    assert (N[Am == 0] == 0).all(), f"{label}: a forbidden transition was counted"
+    return err

@@ -86,6 +86,12 @@ def test_argument_errors_are_caught_on_the_host():
     assert lib.hmm_transition_counts(fake, fake, fake, 8, 4, 1, 1, fake, aligned_ws, 8, null) == 3
     assert hmm.hmm_transition_counts_workspace_bytes(1 << 20, 4, 1) >= 64
     assert hmm.hmm_transition_counts_workspace_bytes(1, 128, 3) == 3 * 128 * 128 * 4 + binding.WORKSPACE_RESERVED_BYTES
+    # hmm_smooth_counts
+    assert lib.hmm_smooth_counts(fake, fake, fake, 8, 4, 1, 1, fake, fake, null, aligned_ws, 1 << 22, null) == 1
+    assert lib.hmm_smooth_counts(fake, fake, fake, 8, 4, 1, 1, null, fake, fake, aligned_ws, 1 << 22, null) == 1
+    assert lib.hmm_smooth_counts(fake, fake, fake, 8, 200, 1, 1, fake, fake, fake, aligned_ws, 1 << 22, null) == 2
+    assert lib.hmm_smooth_counts(fake, fake, fake, 8, 4, 1, 1, fake, fake, fake, aligned_ws, 64, null) == 3
+    assert hmm.hmm_smooth_counts_workspace_bytes(1 << 20, 4, 1) > hmm.hmm_workspace_bytes(1 << 20, 4, 1)[0]
     # workspace preparation and state query
     assert lib.hmm_workspace_init(null, 1 << 20, null) == 3
     assert lib.hmm_workspace_init(ctypes.c_void_p(0x1010), 1 << 20, null) == 3

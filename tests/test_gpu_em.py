@@ -71,3 +71,18 @@ def test_baum_welch_iterations_follow_the_oracle_and_never_lose_evidence(D, K, T
     for it in range(1, len(L_gpu)):
         assert L_gpu[it] >= L_gpu[it - 1] - 2e-6 * abs(L_gpu[it]), f"evidence fell at iteration {it}: {L_gpu}"
     assert L_gpu[-1] > L_gpu[0]
+
+
+@pytest.mark.parametrize("plan", ["single", "multi"])
+@pytest.mark.parametrize("D,T,B,shared", [(4, 20000, 1, True), (4, 4097, 5, False), (3, 100, 17, False), (8, 6100, 2, False),
+                                          (2, 9000, 2, True), (6, 1, 3, True), (4, 1 << 20, 1, True), (16, 5000, 2, True)])
+def test_expectation_step_in_one_call(D, T, B, shared, plan, monkeypatch):
+    """hmm_smooth_counts: marginals, evidence and expected transition counts from one call.  Up to eight states the
+    counts come out of the smoother's own backward recursion (both launch plans, any length); above that (here
+    D = 16) the call takes the two-call form inside the library."""
+    import gpu_util
+    if D > 8 and plan == "multi":
+        pytest.skip("one plan above eight states")
+    monkeypatch.setenv("HMMSCAN_PLAN", plan)
+    p = wl.config2() if T == 1 << 20 else wl.random_problem(D, T, batch=B, shared_model=shared, seed=5 * D + B)
+    gpu_util.check_smooth_counts(p, label=f"D={D} T={T} B={B} plan={plan}")

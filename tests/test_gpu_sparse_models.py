@@ -62,3 +62,7 @@ def test_sparse_model_with_contradicting_evidence(gu, shape, plan, monkeypatch):
     gu.check_smooth(p, want_filtered=True, label=label)
     if shape[0] not in COUNTS_NEED_MORE_RANGE:
         gu.check_transition_counts(p, label=label)
+    # the one-call expectation step sums the pairwise posteriors from the scaled potentials themselves: up to eight
+    # states (sequences longer than the packed plan's) it holds on every asserted shape
+    if D <= 8 or shape[0] not in COUNTS_NEED_MORE_RANGE:
+        gu.check_smooth_counts(p, label=label)
