@@ -16,6 +16,8 @@
 #include <math.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "ktimer.hpp"
 #include "large_d.hpp"
 #include "large_d_device.hpp"
@@ -126,8 +128,32 @@ __global__ __launch_bounds__(256, (D <= 32) ? 2 : 1) void ld_aggregate_kernel(co
     }
     const float* lseq = ll + (size_t)cc.seq * T * Dr;
     float* mseq = rowmax + (size_t)cc.seq * T;
+    // Whole batches of an unpadded model whose rows are 16-byte aligned: a batch is EB * D consecutive floats, four
+    // per lane in one 16-byte load (EPT = 4), a step's D values in D / 4 neighbouring lanes.  Everything in this
+    // kernel that is not a matrix instruction takes issue cycles from the matrix pipe of its SIMD, and forming the
+    // emission factors is most of it; this path needs about a fifth of the instructions of the general one below.
+    const bool vec_rows = D <= 32 && own_rowmax && Dr == D && (reinterpret_cast<uintptr_t>(ll) & 15) == 0;
+    bool vec_batch = false;   // layout of the batch held in er: four consecutive values per lane, or strided
     auto load_batch = [&](int b, float (&er)[EPT]) {
         if constexpr (D <= 32) {
+            static_assert(EPT == 4, "one 16-byte load per lane and batch");
+            vec_batch = vec_rows && (b + 1) * C::EB <= cc.nsteps;
+            if (vec_batch) {
+                const int sb = (4 * tic) / D, j0 = (4 * tic) % D;
+                const long long t = cc.t0 + b * C::EB + sb;
+                const float4 x = *reinterpret_cast<const float4*>(lseq + (size_t)t * D + j0);
+                float m = fmaxf(fmaxf(x.x, x.y), fmaxf(x.z, x.w));
+#pragma unroll
+                for (int d = 1; d < D / 4; d <<= 1) m = fmaxf(m, __shfl_xor(m, d, 64));
+                if (j0 == 0) mseq[t] = m;
+                m = (m == -INFINITY) ? 0.0f : m;
+                const float off = -LOG2E * m;
+                er[0] = __builtin_amdgcn_exp2f(fmaf(x.x, LOG2E, off));
+                er[1] = __builtin_amdgcn_exp2f(fmaf(x.y, LOG2E, off));
+                er[2] = __builtin_amdgcn_exp2f(fmaf(x.z, LOG2E, off));
+                er[3] = __builtin_amdgcn_exp2f(fmaf(x.w, LOG2E, off));
+                return;
+            }
             if (own_rowmax) {
                 // m_t = max_j ll_t(j) formed here: the D values of a step sit in D consecutive lanes of one wave
                 // (aligned), so the maximum is a few cross-lane steps, and the separate pass over the
@@ -172,6 +198,12 @@ __global__ __launch_bounds__(256, (D <= 32) ? 2 : 1) void ld_aggregate_kernel(co
     };
     auto store_batch = [&](int b, const float (&er)[EPT]) {
         float* eb = e_all + ((b & 1) * C::CPW + cl) * C::EB * D;
+        if constexpr (D <= 32) {
+            if (vec_batch) {
+                *reinterpret_cast<float4*>(eb + 4 * tic) = make_float4(er[0], er[1], er[2], er[3]);
+                return;
+            }
+        }
 #pragma unroll
         for (int q = 0; q < EPT; ++q) eb[q * (C::WPC * 64) + tic] = er[q];
     };
@@ -223,16 +255,27 @@ __global__ __launch_bounds__(256, (D <= 32) ? 2 : 1) void ld_aggregate_kernel(co
                 areg[mo][s4] = a4.x; areg[mo][s4 + 1] = a4.y; areg[mo][s4 + 2] = a4.z; areg[mo][s4 + 3] = a4.w;
             }
         auto advance = [&](const float (&a)[C::MT][C::NS], const float* erow) {
-            Acc nw[C::MT];
+            // All first operands before the first matrix instruction: formed one by one between them, each would be
+            // followed by the wait states a matrix instruction needs after a write of its operand.  The two result
+            // tiles of D = 32 alternate, so that an instruction does not follow the one whose result it adds to.
+            float ae[C::MT][C::NS];
 #pragma unroll
             for (int mo = 0; mo < C::MT; ++mo) {
                 const float em = erow[C::TS * mo + lane % C::TS];
 #pragma unroll
+                for (int s = 0; s < C::NS; ++s) ae[mo][s] = a[mo][s] * em;
+            }
+            __builtin_amdgcn_sched_barrier(0);   // (the scheduler would interleave them again)
+            Acc nw[C::MT];
+#pragma unroll
+            for (int mo = 0; mo < C::MT; ++mo)
+#pragma unroll
                 for (int r = 0; r < C::NACC; ++r) nw[mo][r] = 0.0f;
 #pragma unroll
-                for (int s = 0; s < C::NS; ++s)
-                    nw[mo] = mfma_step<C::TS>(a[mo][s] * em, acc[s / C::NACC][s % C::NACC], nw[mo]);
-            }
+            for (int s = 0; s < C::NS; ++s)
+#pragma unroll
+                for (int mo = 0; mo < C::MT; ++mo)
+                    nw[mo] = mfma_step<C::TS>(ae[mo][s], acc[s / C::NACC][s % C::NACC], nw[mo]);
 #pragma unroll
             for (int mo = 0; mo < C::MT; ++mo) acc[mo] = nw[mo];
         };
@@ -950,7 +993,7 @@ __global__ __launch_bounds__(256) void ld_apply_kernel(const float* __restrict__
 // marginals f_k b_k / Z_k, so that backward potentials never reach memory.  Otherwise the two recursions
 // of a chunk run concurrently in different workgroups (first half of the grid forward, second half
 // backward, writing the backward potentials) and a separate pass forms the marginals.
-template <int D, bool BACKWARD, bool FUSED>
+template <int D, bool BACKWARD, bool FUSED, bool FULL>
 HMM_DEV void apply_row_pass(const float* __restrict__ Am, const float* __restrict__ lseq,
                             const float* __restrict__ mseq, const ChunkCoord& cc, int Dr, int Lc, bool first_chunk,
                             const float (&start)[D / 16], float* fseq, float* __restrict__ gseq, double* part_out) {
@@ -994,7 +1037,8 @@ HMM_DEV void apply_row_pass(const float* __restrict__ Am, const float* __restric
             if constexpr (BACKWARD && FUSED) f[q] = fp[colq[q]];
         }
         ++fetched;
-        if (fetched < cc.nsteps) {
+        // FULL: the caller fetches exactly the chunk's positions; the pointers end one position outside it, unused
+        if (FULL || fetched < cc.nsteps) {
             lp += stride;
             fp += stride;
             mp += BACKWARD ? -1 : 1;
@@ -1014,22 +1058,32 @@ HMM_DEV void apply_row_pass(const float* __restrict__ Am, const float* __restric
     // mantissa and binary exponent (one logarithm per chunk instead of one per step)
     float msum = 0.0f, cmant = 1.0f;
     int cexp = 0;
-    for (int p0 = 0; p0 < Lc; p0 += PFD) {
+    // FULL (decided for the whole wavefront): every row's chunk has exactly Lc steps, Lc is a multiple of 2 PFD and the
+    // model is not padded -- no step is inactive, no lane idle, the sequence's first step can only be a chunk's
+    // position 0, and the last PFD steps fetch nothing.
+    // A group consumes the PFD positions fetched into (xc, fc, mc) and fetches, PFD positions ahead, into (xn, fn, mn):
+    // the same arrays (refilled in place), or a second set -- then nothing waits for a load younger than the one it
+    // needs, and a position's data has a whole group's time to arrive.
+    auto group = [&](int p0, auto do_fetch, float (&xc)[PFD][NQ], float (&fc)[PFD][NQ], float (&mc)[PFD],
+                     float (&xn)[PFD][NQ], float (&fn)[PFD][NQ], float (&mn)[PFD]) {
+        const bool at_t0 = FULL && first_chunk && p0 == (BACKWARD ? Lc - PFD : 0);
 #pragma unroll
         for (int p = 0; p < PFD; ++p) {
             const int pos = p0 + p;
-            const bool active = pos < cc.nsteps;
+            const bool active = FULL || pos < cc.nsteps;
             const long long t = cc.t0 + step_at(pos);
-            const float mm = (mq[p] == -INFINITY) ? 0.0f : mq[p];
+            // is this the sequence's first step?
+            const bool is_t0 = FULL ? (at_t0 && p == (BACKWARD ? PFD - 1 : 0)) : (t == 0);
+            const float mm = (mc[p] == -INFINITY) ? 0.0f : mc[p];
             float e[NQ], fk[NQ];
 #pragma unroll
             for (int q = 0; q < NQ; ++q) {
-                const bool real = (16 * q + l) < Dr;
-                const float x = real ? xq[p][q] : -INFINITY;
+                const bool real = FULL || (16 * q + l) < Dr;
+                const float x = real ? xc[p][q] : -INFINITY;
                 e[q] = __builtin_amdgcn_exp2f(fmaf(x, LOG2E, -LOG2E * mm));
-                fk[q] = (BACKWARD && FUSED && real) ? fq[p][q] : 0.0f;
+                fk[q] = (BACKWARD && FUSED && real) ? fc[p][q] : 0.0f;
             }
-            fetch(xq[p], fq[p], mq[p]);
+            if constexpr (decltype(do_fetch)::value) fetch(xn[p], fn[p], mn[p]);
             if constexpr (!BACKWARD) {
                 float g[NQ];
                 float acc[NQ][4];
@@ -1037,7 +1091,9 @@ HMM_DEV void apply_row_pass(const float* __restrict__ Am, const float* __restric
 #pragma unroll
                 for (int q = 0; q < NQ; ++q) {
                     const float moved = ((acc[q][0] + acc[q][1]) + (acc[q][2] + acc[q][3])) * inv;
-                    g[q] = ((t == 0) ? h[q] : moved) * e[q];   // psi_1 = prior o e_1: no transition at the first step
+                    // psi_1 = prior o e_1: no transition at the first step (FULL: only a group's first step can be it)
+                    if constexpr (FULL) g[q] = ((p == 0 && is_t0) ? h[q] : moved) * e[q];
+                    else g[q] = (is_t0 ? h[q] : moved) * e[q];
                 }
                 float gs = g[0];
 #pragma unroll
@@ -1047,7 +1103,7 @@ HMM_DEV void apply_row_pass(const float* __restrict__ Am, const float* __restric
                 if (active) {
 #pragma unroll
                     for (int q = 0; q < NQ; ++q) {
-                        if (16 * q + l < Dr) op[16 * q + l] = g[q] * ic;   // p(x_t | y_{1:t})
+                        if (FULL || 16 * q + l < Dr) op[16 * q + l] = g[q] * ic;   // p(x_t | y_{1:t})
                         h[q] = g[q];
                     }
                     op += stride;
@@ -1078,14 +1134,26 @@ HMM_DEV void apply_row_pass(const float* __restrict__ Am, const float* __restric
                 if (active) {
 #pragma unroll
                     for (int q = 0; q < NQ; ++q) {
-                        if (16 * q + l < Dr) op[16 * q + l] = FUSED ? gam[q] * ig : bs[q];   // p(x_t | y_{1:T}), or b_t
-                        if (t > 0) h[q] = (acc[q][0] + acc[q][1]) + (acc[q][2] + acc[q][3]);
+                        if (FULL || 16 * q + l < Dr) op[16 * q + l] = FUSED ? gam[q] * ig : bs[q];   // p(x_t | y_{1:T}), or b_t
+                        // (FULL: after the sequence's first step, the last one this direction visits, h is not read again)
+                        if (FULL || !is_t0) h[q] = (acc[q][0] + acc[q][1]) + (acc[q][2] + acc[q][3]);
                     }
                     op += stride;
                     inv = ic;
                 }
             }
         }
+    };
+    if constexpr (FULL) {
+        float xr[PFD][NQ], mr[PFD], fr[PFD][NQ];   // Lc is a multiple of 2 PFD: groups alternate between the two sets
+        for (int p0 = 0; p0 < Lc - 2 * PFD; p0 += 2 * PFD) {
+            group(p0, std::true_type{}, xq, fq, mq, xr, fr, mr);
+            group(p0 + PFD, std::true_type{}, xr, fr, mr, xq, fq, mq);
+        }
+        group(Lc - 2 * PFD, std::true_type{}, xq, fq, mq, xr, fr, mr);
+        group(Lc - PFD, std::false_type{}, xr, fr, mr, xq, fq, mq);
+    } else {
+        for (int p0 = 0; p0 < Lc; p0 += PFD) group(p0, std::true_type{}, xq, fq, mq, xq, fq, mq);
     }
     if constexpr (!BACKWARD) {
         if (cc.nsteps > 0 && l == 0)
@@ -1126,8 +1194,15 @@ __global__ __launch_bounds__(256) void ld_apply_row_kernel(const float* __restri
             hb[q] = bout != nullptr ? bout[(size_t)chunk * D + j] : (j < Dr ? 1.0f : 0.0f);   // one chunk per sequence: all ones
         }
     }
-    if (!backward) apply_row_pass<D, false, FUSED>(Am, lseq, mseq, cc, Dr, Lc, first_chunk, hf, fseq, gseq, part + chunk);
-    if (FUSED || backward) apply_row_pass<D, true, FUSED>(Am, lseq, mseq, cc, Dr, Lc, first_chunk, hb, fseq, gseq, nullptr);
+    // the usual case, decided per wavefront: whole chunks of an unpadded model (see apply_row_pass)
+    const bool full = Dr == D && Lc % 16 == 0 && __builtin_amdgcn_ballot_w64(cc.nsteps != Lc) == 0;
+    if (full) {
+        if (!backward) apply_row_pass<D, false, FUSED, true>(Am, lseq, mseq, cc, Dr, Lc, first_chunk, hf, fseq, gseq, part + chunk);
+        if (FUSED || backward) apply_row_pass<D, true, FUSED, true>(Am, lseq, mseq, cc, Dr, Lc, first_chunk, hb, fseq, gseq, nullptr);
+    } else {
+        if (!backward) apply_row_pass<D, false, FUSED, false>(Am, lseq, mseq, cc, Dr, Lc, first_chunk, hf, fseq, gseq, part + chunk);
+        if (FUSED || backward) apply_row_pass<D, true, FUSED, false>(Am, lseq, mseq, cc, Dr, Lc, first_chunk, hb, fseq, gseq, nullptr);
+    }
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -663,7 +663,7 @@ HMM_DEV bool grid_gather(const TileCoord& tc, int tps, const float (&start)[D], 
     uint32_t sealed;
     const size_t copy = (size_t)(blockIdx.x % XCH_COPIES) * XCH_COPY_WORDS;   // the copy this workgroup polls
     bool ok = await_words<0>(ws.seal + copy + tile0, tps, tag, ws.spin_limit, sealed);
-    // phase@12: seals seen
+    // every seal of this sequence seen
     const int wave = threadIdx.x >> 6;
     const int lane = threadIdx.x & 63;
     // With both directions wanted, the first two waves take the tiles before this one and the last two those after
@@ -690,7 +690,7 @@ HMM_DEV bool grid_gather(const TileCoord& tc, int tps, const float (&start)[D], 
             }
         }
     }
-    // phase@13: aggregates staged
+    // every tile aggregate in registers
     {
         Agg<S, D> X;
         if (!(ok && use_a)) agg_identity<S, D>(Ma);
@@ -728,7 +728,7 @@ HMM_DEV bool grid_gather(const TileCoord& tc, int tps, const float (&start)[D], 
         if (lane == 63) agg_store<S, D>(gl.red + wave * G::W, X);
     }
     __syncthreads();
-    // phase@15: reduced
+    // wave products reduced
     // the wave products through the start vector / the vector of ones (every lane does the same work: no branch
     // below diverges)
     Agg<S, D> Wf[NF], Wb[2];
