@@ -302,48 +302,61 @@ __global__ __launch_bounds__(256, (D <= 32) ? 2 : 1) void ld_aggregate_kernel(co
             if (b + 1 < nb) store_batch(b + 1, er);
             __syncthreads();
         }
-    } else
-    for (int b = 0; b < nb; ++b) {
-        if (b + 1 < nb) load_batch(b + 1, er);
-        const float* eb = e_all + ((b & 1) * C::CPW + cl) * C::EB * D;
-#pragma unroll 1
-        for (int sb = 0; sb < C::EB; ++sb) {
-            const int step = b * C::EB + sb;
-            if (step < cc.nsteps) {
-                if (cc.t0 + step != 0) {   // the sequence's first element has no transition part
-                    Acc nw[C::MT];
+    } else {
+        // Loop bounds are scalars and the sequence's first element (no transition part: the strip is only scaled) is
+        // taken out of the loop, so that the loop body has no branch around the matrix instructions -- the compiler
+        // keeps their results in accumulation registers, and at a join with the path that skips them it copied the
+        // whole strip into those registers and back, every step.
+        const int nsteps = __builtin_amdgcn_readfirstlane(cc.nsteps);
+        const bool seq_start = __builtin_amdgcn_readfirstlane(cc.t0 == 0 ? 1 : 0) != 0;
+        auto scale_rows = [&](const float* erow) {   // rows of P^T scaled by a step's emission factors
 #pragma unroll
-                    for (int mo = 0; mo < C::MT; ++mo) {
+            for (int mo = 0; mo < C::MT; ++mo)
 #pragma unroll
-                        for (int r = 0; r < C::NACC; ++r) nw[mo][r] = 0.0f;
-#pragma unroll
-                        for (int s4 = 0; s4 < C::NS; s4 += 4) {
-                            const float4 a4 = *reinterpret_cast<const float4*>(arow + mo * 64 * C::ASTR + s4);
-                            nw[mo] = mfma_step<C::TS>(a4.x, acc[(s4 + 0) / C::NACC][(s4 + 0) % C::NACC], nw[mo]);
-                            nw[mo] = mfma_step<C::TS>(a4.y, acc[(s4 + 1) / C::NACC][(s4 + 1) % C::NACC], nw[mo]);
-                            nw[mo] = mfma_step<C::TS>(a4.z, acc[(s4 + 2) / C::NACC][(s4 + 2) % C::NACC], nw[mo]);
-                            nw[mo] = mfma_step<C::TS>(a4.w, acc[(s4 + 3) / C::NACC][(s4 + 3) % C::NACC], nw[mo]);
-                        }
-                    }
-#pragma unroll
-                    for (int mo = 0; mo < C::MT; ++mo) acc[mo] = nw[mo];
+                for (int q = 0; q < C::NACC / 4; ++q) {
+                    const float4 e4 = *reinterpret_cast<const float4*>(erow + mfma_row<D>(mo, 4 * q, g));
+                    acc[mo][4 * q + 0] *= e4.x;
+                    acc[mo][4 * q + 1] *= e4.y;
+                    acc[mo][4 * q + 2] *= e4.z;
+                    acc[mo][4 * q + 3] *= e4.w;
                 }
-                // rows of P^T scaled by this step's emission factors
-#pragma unroll
-                for (int mo = 0; mo < C::MT; ++mo)
-#pragma unroll
-                    for (int q = 0; q < C::NACC / 4; ++q) {
-                        const float4 e4 = *reinterpret_cast<const float4*>(eb + sb * D + mfma_row<D>(mo, 4 * q, g));
-                        acc[mo][4 * q + 0] *= e4.x;
-                        acc[mo][4 * q + 1] *= e4.y;
-                        acc[mo][4 * q + 2] *= e4.z;
-                        acc[mo][4 * q + 3] *= e4.w;
-                    }
-                if ((step % C::NORM_EVERY) == C::NORM_EVERY - 1) rescale();
+        };
+        for (int b = 0; b < nb; ++b) {
+            if (b + 1 < nb) load_batch(b + 1, er);
+            const float* eb = e_all + ((b & 1) * C::CPW + cl) * C::EB * D;
+            const int s_end = min(C::EB, nsteps - b * C::EB);
+            int sb = 0;
+            if (b == 0 && seq_start && s_end > 0) {
+                scale_rows(eb);
+                sb = 1;
             }
+#pragma unroll 1
+            for (; sb < s_end; ++sb) {
+                // (the first operands are read from LDS again in every step: kept in registers across steps they would
+                // not fit beside the two strips)
+                asm volatile("" ::: "memory");
+                Acc nw[C::MT];
+#pragma unroll
+                for (int mo = 0; mo < C::MT; ++mo) {
+#pragma unroll
+                    for (int r = 0; r < C::NACC; ++r) nw[mo][r] = 0.0f;
+#pragma unroll
+                    for (int s4 = 0; s4 < C::NS; s4 += 4) {
+                        const float4 a4 = *reinterpret_cast<const float4*>(arow + mo * 64 * C::ASTR + s4);
+                        nw[mo] = mfma_step<C::TS>(a4.x, acc[(s4 + 0) / C::NACC][(s4 + 0) % C::NACC], nw[mo]);
+                        nw[mo] = mfma_step<C::TS>(a4.y, acc[(s4 + 1) / C::NACC][(s4 + 1) % C::NACC], nw[mo]);
+                        nw[mo] = mfma_step<C::TS>(a4.z, acc[(s4 + 2) / C::NACC][(s4 + 2) % C::NACC], nw[mo]);
+                        nw[mo] = mfma_step<C::TS>(a4.w, acc[(s4 + 3) / C::NACC][(s4 + 3) % C::NACC], nw[mo]);
+                    }
+                }
+#pragma unroll
+                for (int mo = 0; mo < C::MT; ++mo) acc[mo] = nw[mo];
+                scale_rows(eb + sb * D);
+                if (((b * C::EB + sb) % C::NORM_EVERY) == C::NORM_EVERY - 1) rescale();
+            }
+            if (b + 1 < nb) store_batch(b + 1, er);
+            __syncthreads();
         }
-        if (b + 1 < nb) store_batch(b + 1, er);
-        __syncthreads();
     }
     if (cc.nsteps > 0) {
         // a strip of zeros (start states the first observation excludes) has no scale of its own: give
