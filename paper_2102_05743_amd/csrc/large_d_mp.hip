@@ -25,6 +25,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "ktimer.hpp"
 #include "large_d.hpp"
 #include "large_d_device.hpp"
@@ -654,40 +656,56 @@ __global__ __launch_bounds__(256) void lv_forward_row_kernel(const float* __rest
     const float* lp = ll + ((size_t)cc.seq * T + cc.t0) * Dr + (l < Dr ? l : 0);
     int fetched = 0;
     float xq[PFD];
-    auto fetch = [&](float& x) {
-        x = *lp;
-        ++fetched;
-        if (fetched < cc.nsteps) lp += Dr;
-    };
+    // FULL (decided for the whole wavefront): every row's chunk has exactly Lc steps, Lc is a multiple of PFD and the
+    // model is not padded -- no step is inactive, no lane idle, only a chunk's step 0 can be the sequence's first,
+    // and the last PFD steps fetch nothing.
+    const bool full = Dr == D && Lc % PFD == 0 && Lc >= 2 * PFD && __builtin_amdgcn_ballot_w64(cc.nsteps != Lc) == 0;
+    auto run = [&](auto full_tag) {
+        constexpr bool FULL = decltype(full_tag)::value;
+        auto fetch = [&](float& x) {
+            x = *lp;
+            ++fetched;
+            if (FULL || fetched < cc.nsteps) lp += Dr;
+        };
 #pragma unroll
-    for (int p = 0; p < PFD; ++p) fetch(xq[p]);
-    for (int s0 = 0; s0 < Lc; s0 += PFD) {
+        for (int p = 0; p < PFD; ++p) fetch(xq[p]);
+        auto group = [&](int s0, auto do_fetch) {
 #pragma unroll
-        for (int p = 0; p < PFD; ++p) {
-            const int s = s0 + p;
-            const bool active = s < cc.nsteps;
-            const float x = (l < Dr) ? xq[p] : -INFINITY;
-            fetch(xq[p]);
-            float t[16];
-            row_candidates<0>(v, la, t);
-            float best = max3f(t[0], t[1], t[2]);
+            for (int p = 0; p < PFD; ++p) {
+                const int s = s0 + p;
+                const bool active = FULL || s < cc.nsteps;
+                const float x = (FULL || l < Dr) ? xq[p] : -INFINITY;
+                if constexpr (decltype(do_fetch)::value) fetch(xq[p]);
+                float t[16];
+                row_candidates<0>(v, la, t);
+                float best = max3f(t[0], t[1], t[2]);
 #pragma unroll
-            for (int r = 3; r < 15; r += 2) best = max3f(best, t[r], t[r + 1]);
-            best = fmaxf(best, t[15]);
-            unsigned arg = 255u;
+                for (int r = 3; r < 15; r += 2) best = max3f(best, t[r], t[r + 1]);
+                best = fmaxf(best, t[15]);
+                unsigned arg = 255u;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) arg = min(arg, (t[r] == best) ? kr[r] : 255u);   // lowest state among the maximisers
-            const bool seq_start = (cc.t0 + s == 0);            // V_1 = log prior + ll_1: no transition, no offset
-            const float gval = seq_start ? v + x : best + (x - off);
-            if (active) {
-                bpl[(size_t)s * D + l] = (uint8_t)(seq_start ? (unsigned)l : arg);
-                const float m = row_allmax(gval);
-                osum += (double)(seq_start ? 0.0f : off);
-                off = (m == -INFINITY) ? 0.0f : m;
-                v = gval;
+                for (int r = 0; r < 16; ++r) arg = min(arg, (t[r] == best) ? kr[r] : 255u);   // lowest state among the maximisers
+                // V_1 = log prior + ll_1: no transition, no offset
+                const bool seq_start = FULL ? (p == 0 && first_chunk && s0 == 0) : (cc.t0 + s == 0);
+                const float gval = seq_start ? v + x : best + (x - off);
+                if (active) {
+                    bpl[(size_t)s * D + l] = (uint8_t)(seq_start ? (unsigned)l : arg);
+                    const float m = row_allmax(gval);
+                    osum += (double)(seq_start ? 0.0f : off);
+                    off = (m == -INFINITY) ? 0.0f : m;
+                    v = gval;
+                }
             }
+        };
+        if constexpr (FULL) {
+            for (int s0 = 0; s0 < Lc - PFD; s0 += PFD) group(s0, std::true_type{});
+            group(Lc - PFD, std::false_type{});
+        } else {
+            for (int s0 = 0; s0 < Lc; s0 += PFD) group(s0, std::true_type{});
         }
-    }
+    };
+    if (full) run(std::true_type{});
+    else run(std::false_type{});
     if (live && l == 0) part[chunk] = osum + (double)off - (double)start;
     wave_lds_sync();   // the chunk's back-pointers were written by its own row of lanes
     if (live) {
