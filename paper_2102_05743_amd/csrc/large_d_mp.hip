@@ -158,24 +158,41 @@ HMM_DEV void lv_aggregate_systolic_body(const float* __restrict__ A, const float
     }
     float* p0 = pbuf + cl * 2 * D * D;
     float* p1 = p0 + D * D;
-    // neutral element: 0 on the diagonal, -inf elsewhere; element (i, k) lives at i*D + (k%16)*NQ + k/16
-    for (int r = 0; r < RPD; ++r) {
-        const int i = rs * RPD + r;
-        p0[i * D + l * NQ + cb] = (i == j) ? 0.0f : -INFINITY;
+    // The sequence's first element has no transition part: the aggregate after it is that step's log-likelihoods on
+    // the diagonal.  It is written here, in place of the neutral element (0 on the diagonal, -inf elsewhere), so that
+    // the step loop needs no case for it.  Element (i, k) lives at i*D + (k%16)*NQ + k/16.
+    const int s_begin = (cc.t0 == 0 && cc.nsteps > 0) ? 1 : 0;
+    float xn = -INFINITY;
+    if (j < Dr && cc.nsteps > 0) xn = lseq[(size_t)cc.t0 * Dr + j];
+    {
+        const float diag = s_begin ? xn : 0.0f;
+        for (int r = 0; r < RPD; ++r) {
+            const int i = rs * RPD + r;
+            p0[i * D + l * NQ + cb] = (i == j) ? diag : -INFINITY;
+        }
+        if (s_begin && s_begin < cc.nsteps && j < Dr) xn = lseq[(size_t)(cc.t0 + 1) * Dr + j];
     }
     chunk_sync<D>();
     float off = 0.0f;
     double offsum = 0.0;
     int cur = 0;
-    float xn = -INFINITY;
-    if (j < Dr && cc.nsteps > 0) xn = lseq[(size_t)cc.t0 * Dr + j];
-    for (int s = 0; s < cc.nsteps; ++s) {
+    if (s_begin == cc.nsteps && s_begin) {
+        // a chunk that is only that first element (uniform over the chunk's waves): its maximum is taken off here
+        float m = wave_max(xn);
+        if constexpr (WPCH == 4) {
+            if (lane == 0) wmax[wave] = m;
+            lds_barrier();
+            m = fmaxf(fmaxf(wmax[0], wmax[1]), fmaxf(wmax[2], wmax[3]));
+        }
+        off = (m == -INFINITY) ? 0.0f : m;
+        if constexpr (WITH_OFFSETS) offsum += (double)off;
+    }
+    for (int s = s_begin; s < cc.nsteps; ++s) {
         const float x = xn;
         if (s + 1 < cc.nsteps && j < Dr) xn = lseq[(size_t)(cc.t0 + s + 1) * Dr + j];
         const float* po = cur ? p1 : p0;
         float* pn = cur ? p0 : p1;
         const float add = x - off;
-        const bool no_transition = (cc.t0 + s == 0);
         float lmax = -INFINITY;
 #pragma unroll(RPD <= 4 ? RPD : 1)
         for (int r = 0; r < RPD; ++r) {
@@ -194,23 +211,22 @@ HMM_DEV void lv_aggregate_systolic_body(const float* __restrict__ A, const float
             } else {
                 pr[0] = src[0];
             }
-            float acc;
-            if (no_transition) {
-                acc = pr[cb];   // P is still the neutral element: P(i, j) itself
-            } else {
-                acc = -INFINITY;
-                systolic_terms<D, 0, 0>(pr, la, acc);
-            }
+            float acc = -INFINITY;
+            systolic_terms<D, 0, 0>(pr, la, acc);
             acc += add;
             lmax = fmaxf(lmax, acc);
             pn[i * D + l * NQ + cb] = acc;
         }
-        float m = wave_max(lmax);
+        // the running maximum is taken off every fourth step (and after the last one), one step late
+        const bool take = (s & 3) == 3 || s == cc.nsteps - 1;   // uniform over the workgroup
+        float m = 0.0f;
+        if (take) m = wave_max(lmax);
         if constexpr (WPCH == 4) {
-            if (lane == 0) wmax[(cur ^ 1) * 4 + wave] = m;
+            if (take && lane == 0) wmax[(cur ^ 1) * 4 + wave] = m;
             lds_barrier();
-            m = fmaxf(fmaxf(wmax[(cur ^ 1) * 4], wmax[(cur ^ 1) * 4 + 1]),
-                      fmaxf(wmax[(cur ^ 1) * 4 + 2], wmax[(cur ^ 1) * 4 + 3]));
+            if (take)
+                m = fmaxf(fmaxf(wmax[(cur ^ 1) * 4], wmax[(cur ^ 1) * 4 + 1]),
+                          fmaxf(wmax[(cur ^ 1) * 4 + 2], wmax[(cur ^ 1) * 4 + 3]));
         } else {
             chunk_sync<D>();
         }
