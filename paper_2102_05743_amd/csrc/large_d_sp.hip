@@ -255,29 +255,41 @@ __global__ __launch_bounds__(256, (D <= 32) ? 2 : 1) void ld_aggregate_kernel(co
                 areg[mo][s4] = a4.x; areg[mo][s4 + 1] = a4.y; areg[mo][s4 + 2] = a4.z; areg[mo][s4 + 3] = a4.w;
             }
         auto advance = [&](const float (&a)[C::MT][C::NS], const float* erow) {
-            // All first operands before the first matrix instruction: formed one by one between them, each would be
-            // followed by the wait states a matrix instruction needs after a write of its operand.  The two result
-            // tiles of D = 32 alternate, so that an instruction does not follow the one whose result it adds to.
-            float ae[C::MT][C::NS];
-#pragma unroll
-            for (int mo = 0; mo < C::MT; ++mo) {
-                const float em = erow[C::TS * mo + lane % C::TS];
-#pragma unroll
-                for (int s = 0; s < C::NS; ++s) ae[mo][s] = a[mo][s] * em;
-            }
-            __builtin_amdgcn_sched_barrier(0);   // (the scheduler would interleave them again)
             Acc nw[C::MT];
 #pragma unroll
             for (int mo = 0; mo < C::MT; ++mo)
 #pragma unroll
                 for (int r = 0; r < C::NACC; ++r) nw[mo][r] = 0.0f;
+            if constexpr (C::MT == 1) {
+                // All first operands, scaled by the emission factor of their row, before the first matrix instruction:
+                // formed one by one between them, each would be followed by the wait states a matrix instruction needs
+                // after a write of its operand.
+                float ae[C::NS];
+                const float em = erow[lane % C::TS];
 #pragma unroll
-            for (int s = 0; s < C::NS; ++s)
+                for (int s = 0; s < C::NS; ++s) ae[s] = a[0][s] * em;
+                __builtin_amdgcn_sched_barrier(0);   // (the scheduler would interleave them again)
 #pragma unroll
-                for (int mo = 0; mo < C::MT; ++mo)
-                    nw[mo] = mfma_step<C::TS>(ae[mo][s], acc[s / C::NACC][s % C::NACC], nw[mo]);
+                for (int s = 0; s < C::NS; ++s) nw[0] = mfma_step<C::TS>(ae[s], acc[0][s], nw[0]);
+                acc[0] = nw[0];
+            } else {
+                // Two result tiles: scaling the results (NACC registers per tile) takes half the multiplications that
+                // scaling the first operands would (NS per tile).  The tiles' instructions alternate, so that none
+                // follows the one whose result it adds to.
 #pragma unroll
-            for (int mo = 0; mo < C::MT; ++mo) acc[mo] = nw[mo];
+                for (int s = 0; s < C::NS; ++s)
+#pragma unroll
+                    for (int mo = 0; mo < C::MT; ++mo)
+                        nw[mo] = mfma_step<C::TS>(a[mo][s], acc[s / C::NACC][s % C::NACC], nw[mo]);
+#pragma unroll
+                for (int mo = 0; mo < C::MT; ++mo) {
+                    const float4 e4 = *reinterpret_cast<const float4*>(erow + mfma_row<D>(mo, 0, g));
+                    acc[mo][0] = nw[mo][0] * e4.x;
+                    acc[mo][1] = nw[mo][1] * e4.y;
+                    acc[mo][2] = nw[mo][2] * e4.z;
+                    acc[mo][3] = nw[mo][3] * e4.w;
+                }
+            }
         };
         for (int b = 0; b < nb; ++b) {
             if (b + 1 < nb) load_batch(b + 1, er);
@@ -1399,8 +1411,19 @@ __global__ __launch_bounds__(REPAIR_THREADS) void ld_repair_kernel(
     // kernel is not launched)
     __shared__ double ev[REPAIR_THREADS];
     {
+        // eight loads in flight per thread (a long sequence has thousands of chunks and one workgroup to add them up)
+        const double* pseq = part + (size_t)seq * cps;
+        constexpr int U = 8;
         double acc = 0.0;
-        for (int c = j; c < cps; c += REPAIR_THREADS) acc += part[(size_t)seq * cps + c];
+        int c = j;
+        for (; c + (U - 1) * REPAIR_THREADS < cps; c += U * REPAIR_THREADS) {
+            double v[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) v[u] = pseq[c + u * REPAIR_THREADS];
+#pragma unroll
+            for (int u = 0; u < U; ++u) acc += v[u];
+        }
+        for (; c < cps; c += REPAIR_THREADS) acc += pseq[c];
         ev[j] = acc;
         __syncthreads();
         for (int d = REPAIR_THREADS / 2; d >= 1; d >>= 1) {
@@ -1512,8 +1535,11 @@ LargePlan large_plan(int Dr, long long T, int batch) {
 // most 256 (D >= 64) or 128 steps, so that a long sequence gets more chunks rather than longer ones, and above 96 chunks per sequence a second scan level: groups
 // of g chunks whose aggregates are formed by ld_product.  With a product hop costing about 8.4
 // (D >= 64) or 5.4 (D <= 32) vector hops, g + chunks/g vector hops and g product hops are fewest in
-// total near g = sqrt(0.106 chunks) resp. sqrt(0.156 chunks).
-struct SmoothPlan { int DP, Lc, cps; long long nchunks; int g, G; bool two_level, fused_apply; };
+// total near g = sqrt(0.106 chunks) resp. sqrt(0.156 chunks).  Up to 32 states and from 1024 chunks per sequence
+// a third level: groups of g2 groups (ld_product applied to the group aggregates), carries over those, then inside
+// them over the groups, then inside the groups over the chunks -- 2 g product hops, 2 g + chunks / g^2 vector hops and
+// two more launches, fewest near g = cbrt(chunks / 6): a third to a half of the two-level plan's sequential time.
+struct SmoothPlan { int DP, Lc, cps; long long nchunks; int g, G, g2, G2; bool two_level, three_level, fused_apply; };
 
 static SmoothPlan smooth_plan(int Dr, long long T, int batch) {
     SmoothPlan p;
@@ -1533,7 +1559,16 @@ static SmoothPlan smooth_plan(int Dr, long long T, int batch) {
     // (four chunks per wave); below that the two directions run side by side
     p.fused_apply = p.DP <= 32 && p.nchunks >= 4096;
     p.two_level = p.cps > 96;
-    if (p.two_level) {
+    p.three_level = p.DP <= 32 && p.cps >= 1024;
+    p.g2 = 1;
+    p.G2 = 1;
+    if (p.three_level) {
+        int g = (int)(cbrt((double)p.cps / 6.0) + 0.5);
+        p.g = g < 2 ? 2 : g;
+        p.G = (p.cps + p.g - 1) / p.g;
+        p.g2 = p.g;
+        p.G2 = (p.G + p.g2 - 1) / p.g2;
+    } else if (p.two_level) {
         int g = (int)sqrt((p.DP >= 64 ? 0.106 : 0.156) * (double)p.cps);
         p.g = g < 2 ? 2 : g;
         p.G = (p.cps + p.g - 1) / p.g;
@@ -1544,12 +1579,13 @@ static SmoothPlan smooth_plan(int Dr, long long T, int batch) {
     return p;
 }
 
-struct LargeSmoothWs { size_t rowmax, agg, aggT, exps, fin, bout, gagg, gaggT, gexps, gfin, gbout, F, Bv, part, suspect, total; };
+struct LargeSmoothWs { size_t rowmax, agg, aggT, exps, fin, bout, gagg, gaggT, gexps, gfin, gbout, sagg, saggT, sexps, sfin, sbout, F, Bv, part, suspect, total; };
 
 static LargeSmoothWs large_smooth_ws(int Dr, long long T, int batch, bool own_F) {
     const SmoothPlan p = smooth_plan(Dr, T, batch);
     const size_t D = p.DP, nc = (size_t)p.nchunks, rows = (size_t)T * batch;
     const size_t ng = p.two_level ? (size_t)p.G * batch : 0;
+    const size_t ns = p.three_level ? (size_t)p.G2 * batch : 0;   // groups of groups
     LargeSmoothWs w;
     size_t o = 0;
     w.rowmax = o; o = align_up(o + rows * sizeof(float), 256);
@@ -1563,6 +1599,11 @@ static LargeSmoothWs large_smooth_ws(int Dr, long long T, int batch, bool own_F)
     w.gexps = o;  o = align_up(o + ng * 8 * sizeof(int), 256);
     w.gfin = o;   o = align_up(o + ng * D * sizeof(float), 256);
     w.gbout = o;  o = align_up(o + ng * D * sizeof(float), 256);
+    w.sagg = o;   o = align_up(o + ns * D * D * sizeof(float), 256);
+    w.saggT = o;  o = align_up(o + ns * D * D * sizeof(float), 256);
+    w.sexps = o;  o = align_up(o + ns * 8 * sizeof(int), 256);
+    w.sfin = o;   o = align_up(o + ns * D * sizeof(float), 256);
+    w.sbout = o;  o = align_up(o + ns * D * sizeof(float), 256);
     w.F = o;      o = align_up(o + (own_F ? rows * Dr * sizeof(float) : 0), 256);
     w.Bv = o;     o = align_up(o + (p.fused_apply ? 0 : rows * Dr * sizeof(float)), 256);
     w.part = o;   o = align_up(o + nc * sizeof(double), 256);
@@ -1608,6 +1649,11 @@ static int large_smooth_impl(const LargeArgs& a, float* marg, float* filt, doubl
     int* gexps = reinterpret_cast<int*>(ws + w.gexps);
     float* gfin = reinterpret_cast<float*>(ws + w.gfin);
     float* gbout = reinterpret_cast<float*>(ws + w.gbout);
+    float* sagg = reinterpret_cast<float*>(ws + w.sagg);
+    float* saggT = reinterpret_cast<float*>(ws + w.saggT);
+    int* sexps = reinterpret_cast<int*>(ws + w.sexps);
+    float* sfin = reinterpret_cast<float*>(ws + w.sfin);
+    float* sbout = reinterpret_cast<float*>(ws + w.sbout);
     float* F = filt ? filt : reinterpret_cast<float*>(ws + w.F);
     float* Bv = reinterpret_cast<float*>(ws + w.Bv);
     double* part = reinterpret_cast<double*>(ws + w.part);
@@ -1635,8 +1681,19 @@ static int large_smooth_impl(const LargeArgs& a, float* marg, float* filt, doubl
         const long long ngroups = (long long)p.G * a.batch;
         launch("ld_product", ld_product_kernel<D>, dim3((unsigned)((ngroups + C::CPW - 1) / C::CPW)), block, st,
                (const float*)aggT, (const int*)exps, p.cps, p.g, p.G, ngroups, gagg, gaggT, gexps);
-        // carries at the group boundaries, then inside every group from those
-        launch_carry<D>(st, a, p.G, gagg, gaggT, gexps, gfin, gbout, p.G, 1, nullptr, nullptr, suspect);
+        if (p.three_level) {
+            // the same once more over the groups; carries at the boundaries of the groups of groups, then inside each
+            // of them at the group boundaries
+            const long long nsuper = (long long)p.G2 * a.batch;
+            launch("ld_product", ld_product_kernel<D>, dim3((unsigned)((nsuper + C::CPW - 1) / C::CPW)), block, st,
+                   (const float*)gaggT, (const int*)gexps, p.G, p.g2, p.G2, nsuper, sagg, saggT, sexps);
+            launch_carry<D>(st, a, p.G2, sagg, saggT, sexps, sfin, sbout, p.G2, 1, nullptr, nullptr, suspect);
+            launch_carry<D>(st, a, p.G, gagg, gaggT, gexps, gfin, gbout, p.g2, p.G2, sfin, sbout, suspect);
+        } else {
+            // carries at the group boundaries
+            launch_carry<D>(st, a, p.G, gagg, gaggT, gexps, gfin, gbout, p.G, 1, nullptr, nullptr, suspect);
+        }
+        // inside every group from the carries at its boundaries
         launch_carry<D>(st, a, p.cps, agg, aggT, exps, fin, bout, p.g, p.G, gfin, gbout, suspect);
     } else if (p.cps > 1) {
         launch_carry<D>(st, a, p.cps, agg, aggT, exps, fin, bout, p.cps, 1, nullptr, nullptr, suspect);

@@ -110,6 +110,16 @@ def test_chunk_counts_around_the_second_level_threshold(gu, D, T, B):
     gu.check_smooth(p, label=f"threshold D={D} T={T} B={B}")
 
 
+@pytest.mark.parametrize("D,T,B", [(16, 1023 * 128, 1), (16, 1024 * 128, 1), (16, 1024 * 128 + 5, 2), (12, 1500 * 128 + 77, 1),
+                                   (32, 1023 * 128 + 1, 1), (32, 1024 * 128, 2), (32, 1025 * 128 - 3, 1), (27, 3000 * 128 + 9, 1)])
+def test_chunk_counts_around_the_third_level_threshold(gu, D, T, B):
+    """Up to 32 states the smoother's carries take a third scan level from 1024 chunks per sequence (groups of
+    groups of chunks): lengths that put the chunk count just below, at and above that point, with ragged last
+    groups on both levels, padded state counts and more than one sequence."""
+    p = wl.random_problem(D, T, batch=B, shared_model=(B == 1), seed=613 + D + T % 11)
+    gu.check_smooth(p, want_filtered=(B == 2), label=f"third level D={D} T={T} B={B}")
+
+
 @pytest.mark.parametrize("D,T,B,shared", [(16, 100, 5000, True), (11, 70, 3000, False), (31, 100, 1200, False),
                                           (20, 33, 4100, True), (32, 530000, 1, True), (16, 131075, 2, False),
                                           (9, 20, 17000, False), (16, 2200000, 1, True)])
