@@ -361,15 +361,28 @@ HMM_DEV float dpp_move(float neutral, float src) {
     return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(neutral), __float_as_int(src), CTRL, ROW_MASK,
                                                       0xF, false));
 }
+// The same with 0.0 for lanes without a source.  Where every row of lanes takes part (ROW_MASK 0xF), the zero is the
+// DPP read's own fill value for a missing source lane and the destination needs no initialising move.
+template <int CTRL, int ROW_MASK>
+HMM_DEV float dpp_move_or_zero(float src) {
+    if constexpr (ROW_MASK == 0xF)
+        return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(src), CTRL, 0xF, 0xF, true));
+    else
+        return dpp_move<CTRL, ROW_MASK>(0.0f, src);
+}
 template <int CTRL, int ROW_MASK>
 HMM_DEV int dpp_move_int(int neutral, int src) {
     return __builtin_amdgcn_update_dpp(neutral, src, CTRL, ROW_MASK, 0xF, false);
 }
 template <int CTRL, int ROW_MASK>
+HMM_DEV int dpp_move_int_or_zero(int src) {   // as dpp_move_or_zero
+    return __builtin_amdgcn_update_dpp(0, src, CTRL, ROW_MASK, 0xF, ROW_MASK == 0xF);
+}
+template <int CTRL, int ROW_MASK>
 HMM_DEV double dpp_move_double(double src) {   // neutral 0.0
     const long long b = __double_as_longlong(src);
-    const int lo = __builtin_amdgcn_update_dpp(0, (int)b, CTRL, ROW_MASK, 0xF, false);
-    const int hi = __builtin_amdgcn_update_dpp(0, (int)(b >> 32), CTRL, ROW_MASK, 0xF, false);
+    const int lo = dpp_move_int_or_zero<CTRL, ROW_MASK>((int)b);
+    const int hi = dpp_move_int_or_zero<CTRL, ROW_MASK>((int)(b >> 32));
     return __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
 }
 
@@ -380,10 +393,15 @@ HMM_DEV void agg_dpp(const Agg<S, D>& Q, Agg<S, D>& N) {
     for (int i = 0; i < D; ++i)
 #pragma unroll
         for (int j = 0; j < D; ++j)
-            N.m[i * D + j] = dpp_move<CTRL, ROW_MASK>((i == j) ? S::one() : S::zero(), Q.m[i * D + j]);
+            if constexpr (!S::is_max_plus) {   // neutral element: ones on the diagonal, zeros elsewhere
+                N.m[i * D + j] = (i == j) ? dpp_move<CTRL, ROW_MASK>(1.0f, Q.m[i * D + j])
+                                          : dpp_move_or_zero<CTRL, ROW_MASK>(Q.m[i * D + j]);
+            } else {
+                N.m[i * D + j] = dpp_move<CTRL, ROW_MASK>((i == j) ? S::one() : S::zero(), Q.m[i * D + j]);
+            }
     if constexpr (!S::is_max_plus) {
 #pragma unroll
-        for (int i = 0; i < D; ++i) N.ex[i] = dpp_move_int<CTRL, ROW_MASK>(0, Q.ex[i]);
+        for (int i = 0; i < D; ++i) N.ex[i] = dpp_move_int_or_zero<CTRL, ROW_MASK>(Q.ex[i]);
     }
     if constexpr (TRACK_C) N.c = dpp_move_double<CTRL, ROW_MASK>(Q.c);
     else N.c = 0.0;
