@@ -396,8 +396,9 @@ HMM_DEV void agg_dpp(const Agg<S, D>& Q, Agg<S, D>& N) {
             if constexpr (!S::is_max_plus) {   // neutral element: ones on the diagonal, zeros elsewhere
                 N.m[i * D + j] = (i == j) ? dpp_move<CTRL, ROW_MASK>(1.0f, Q.m[i * D + j])
                                           : dpp_move_or_zero<CTRL, ROW_MASK>(Q.m[i * D + j]);
-            } else {
-                N.m[i * D + j] = dpp_move<CTRL, ROW_MASK>((i == j) ? S::one() : S::zero(), Q.m[i * D + j]);
+            } else {                           // zeros on the diagonal, minus infinity elsewhere
+                N.m[i * D + j] = (i == j) ? dpp_move_or_zero<CTRL, ROW_MASK>(Q.m[i * D + j])
+                                          : dpp_move<CTRL, ROW_MASK>(-INFINITY, Q.m[i * D + j]);
             }
     if constexpr (!S::is_max_plus) {
 #pragma unroll
