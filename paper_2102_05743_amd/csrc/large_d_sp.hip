@@ -240,10 +240,11 @@ __global__ __launch_bounds__(256, (D <= 32) ? 2 : 1) void ld_aggregate_kernel(co
     __syncthreads();
     const float* arow = at + lane * C::ASTR;
     if constexpr (D <= 32) {
-        // Small tiles: the first operands of a wave fit in registers (MT * NS values), and the emission
-        // factor of result row m multiplies the first operand's row m instead of the result, so a step
-        // is MFMAs fed by the previous step's results and nothing else touches the accumulators.  The
-        // sequence's first element (no transition part) uses the identity in place of A^T.
+        // Small tiles: the first operands of a wave fit in registers (MT * NS values).  With one result tile
+        // (D = 16) the emission factor of result row m multiplies the first operand's row m instead of the
+        // result, so a step is MFMAs fed by the previous step's results and nothing else touches the
+        // accumulators; with two (D = 32) the results are scaled, which takes half as many multiplications.
+        // The sequence's first element (no transition part) uses the identity in place of A^T.
         const int nsteps = __builtin_amdgcn_readfirstlane(cc.nsteps);   // uniform over the wave: scalar loop bounds
         const bool seq_start = __builtin_amdgcn_readfirstlane(cc.t0 == 0 ? 1 : 0) != 0;
         float areg[C::MT][C::NS];
