@@ -112,34 +112,40 @@ HMM_DEV void lv_aggregate_systolic_body(const float* __restrict__ A, const float
         // so P never leaves the registers (four rows per DPP row of lanes), and its maximum is taken off
         // every fourth step only.
         float pr[RPD];
-#pragma unroll
-        for (int r = 0; r < RPD; ++r) pr[r] = (rs * RPD + r == j) ? 0.0f : -INFINITY;
-        float off = 0.0f;
-        double offsum = 0.0;
         float xn = -INFINITY;
         if (j < Dr && cc.nsteps > 0) xn = lseq[(size_t)cc.t0 * Dr + j];
-        for (int s = 0; s < cc.nsteps; ++s) {
+        // the sequence's first element has no transition part: the aggregate after it is that step's log-likelihoods
+        // on the diagonal, which is written here in place of the neutral element (0 on the diagonal)
+        const int s_begin = (cc.t0 == 0 && cc.nsteps > 0) ? 1 : 0;
+        {
+            const float diag = s_begin ? xn : 0.0f;
+#pragma unroll
+            for (int r = 0; r < RPD; ++r) pr[r] = (rs * RPD + r == j) ? diag : -INFINITY;
+            if (s_begin && s_begin < cc.nsteps && j < Dr) xn = lseq[(size_t)(cc.t0 + 1) * Dr + j];
+        }
+        float off = 0.0f;
+        double offsum = 0.0;
+        auto take_off_maximum = [&]() {
+            float lmax = pr[0];
+#pragma unroll
+            for (int r = 1; r < RPD; ++r) lmax = fmaxf(lmax, pr[r]);
+            const float m = wave_max(lmax);
+            off = (m == -INFINITY) ? 0.0f : m;
+            offsum += (double)off;
+        };
+        if (s_begin && cc.nsteps == 1) take_off_maximum();   // a chunk that is only that first element
+        for (int s = s_begin; s < cc.nsteps; ++s) {
             const float add = xn - off;
             if (s + 1 < cc.nsteps && j < Dr) xn = lseq[(size_t)(cc.t0 + s + 1) * Dr + j];
-            const bool no_transition = (cc.t0 + s == 0);
-            float lmax = -INFINITY;
 #pragma unroll
             for (int r = 0; r < RPD; ++r) {
-                float acc = pr[r];   // neutral element so far: P(i, j) itself
-                if (!no_transition) {
-                    const float one[1] = {pr[r]};
-                    acc = -INFINITY;
-                    systolic_terms<D, 0, 0>(one, la, acc);
-                }
+                const float one[1] = {pr[r]};
+                float acc = -INFINITY;
+                systolic_terms<D, 0, 0>(one, la, acc);
                 pr[r] = acc + add;
-                lmax = fmaxf(lmax, pr[r]);
             }
             off = 0.0f;
-            if ((s & 3) == 3 || s == cc.nsteps - 1) {
-                const float m = wave_max(lmax);
-                off = (m == -INFINITY) ? 0.0f : m;
-                offsum += (double)off;
-            }
+            if ((s & 3) == 3 || s == cc.nsteps - 1) take_off_maximum();
         }
         if (cc.nsteps > 0) {
             if constexpr (WITH_OFFSETS) {
