@@ -387,8 +387,9 @@ HMM_DEV double agg_vec(const Agg<S, D>& M, const float (&v)[D], float (&r)[D]) {
 // with equal row exponents, and reports in `bad` whenever the general operation would have left its
 // first branch (the test is slightly stricter, never laxer).  A caller runs a whole phase in uniform
 // mode and, if any lane of the wavefront reported `bad`, runs the phase again with the general
-// operations: what comes out is bit for bit what the general operations alone produce, but the
-// usual case has no branch per operation.
+// operations: what comes out is what the general operations alone produce (the same bits for every entry
+// within 2^-126 of its row's largest; scalings are exact powers of two), but the usual case has no branch
+// per operation.
 template <int D>
 HMM_DEV bool agg_is_uniform(const Agg<SumProd, D>& P) {
     bool u = true;
@@ -416,14 +417,14 @@ HMM_DEV void agg_renorm_u(Agg<SumProd, D>& P, bool& bad) {
     for (int i = 0; i < D; ++i) P.ex[i] = ne;
 }
 
-template <int D, bool TRACK_C = true>
+template <int D, bool TRACK_C = true, int BIAS = ROW_BIAS>
 HMM_DEV void agg_mul_u(const Agg<SumProd, D>& X, const Agg<SumProd, D>& Y, Agg<SumProd, D>& Z, bool& bad) {
     mat_mul<SumProd, D>(X.m, Y.m, Z.m);
     const int e = X.ex[0] + Y.ex[0];
 #pragma unroll
     for (int i = 0; i < D; ++i) Z.ex[i] = e;
     if constexpr (TRACK_C) Z.c = X.c + Y.c;
-    agg_renorm_u<D>(Z, bad);
+    if constexpr (BIAS >= 0) agg_renorm_u<D, BIAS>(Z, bad);
 }
 
 template <int D>

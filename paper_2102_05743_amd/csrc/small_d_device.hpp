@@ -450,12 +450,17 @@ HMM_DEV void agg_load(const float* p, Agg<S, D>& Q) {
 // four shifts inside each row of 16 lanes, then the last lane of a row broadcast to the next
 // row(s).  A lane that has no source at some level combines with the operator's neutral
 // element instead, so no lane needs to be predicated.
-template <class S, int D, bool SWAP, int CTRL, int ROW_MASK, bool TRACK_C, bool U>
+template <class S, int D, bool SWAP, int CTRL, int ROW_MASK, bool TRACK_C, bool U, int UBIAS = ROW_BIAS>
 HMM_DEV void wave_scan_level(Agg<S, D>& Q, bool& bad) {
     Agg<S, D> N, Z;
     agg_dpp<S, D, CTRL, ROW_MASK, TRACK_C>(Q, N);
-    if constexpr (SWAP) agg_mul_m<U, S, D, TRACK_C>(Q, N, Z, bad);
-    else agg_mul_m<U, S, D, TRACK_C>(N, Q, Z, bad);
+    if constexpr (U && !S::is_max_plus && UBIAS != ROW_BIAS) {
+        if constexpr (SWAP) agg_mul_u<D, TRACK_C, UBIAS>(Q, N, Z, bad);
+        else agg_mul_u<D, TRACK_C, UBIAS>(N, Q, Z, bad);
+    } else {
+        if constexpr (SWAP) agg_mul_m<U, S, D, TRACK_C>(Q, N, Z, bad);
+        else agg_mul_m<U, S, D, TRACK_C>(N, Q, Z, bad);
+    }
     Q = Z;
 }
 
@@ -470,6 +475,25 @@ HMM_DEV void wave_scan_level(Agg<S, D>& Q) {
 // U: uniform mode, `bad` as in the *_u operations.
 template <class S, int D, bool SWAP, bool TRACK_C, bool U>
 HMM_DEV void wave_scan_up(Agg<S, D>& Q, bool& bad) {
+    if constexpr (U && !S::is_max_plus) {
+        // Uniform mode renormalises after every other level only.  Rows enter with their largest entry below
+        // 2^ROW_BIAS; a renormalising level leaves it in [2^(MID-1), 2^MID), the next level's products are
+        // then below D 2^(2 MID) and are left as they are, and the products of those stay below
+        // D^3 2^(4 MID) <= 2^121 for D <= 8.  Downwards, a renormalising level has checked that every
+        // row's largest entry is at least 2^(MID-21), so after the level without renormalisation it is at least
+        // 2^(2 MID - 42) = 2^14: entries 2^-126 below their row's largest are still normal numbers.  The last
+        // level restores ROW_BIAS.  Powers of two are exact factors: the results have the mantissas they would
+        // have with a renormalisation at every level.
+        constexpr int MID = 28, NONE = -1;
+        static_assert(D <= 8, "range argument above");
+        wave_scan_level<S, D, SWAP, 0x111, 0xF, TRACK_C, U, MID>(Q, bad);    // row_shr:1
+        wave_scan_level<S, D, SWAP, 0x112, 0xF, TRACK_C, U, NONE>(Q, bad);   // row_shr:2
+        wave_scan_level<S, D, SWAP, 0x114, 0xF, TRACK_C, U, MID>(Q, bad);    // row_shr:4
+        wave_scan_level<S, D, SWAP, 0x118, 0xF, TRACK_C, U, NONE>(Q, bad);   // row_shr:8
+        wave_scan_level<S, D, SWAP, 0x142, 0xA, TRACK_C, U, MID>(Q, bad);    // row_bcast:15 into rows 1 and 3
+        wave_scan_level<S, D, SWAP, 0x143, 0xC, TRACK_C, U>(Q, bad);         // row_bcast:31 into rows 2 and 3
+        return;
+    }
     wave_scan_level<S, D, SWAP, 0x111, 0xF, TRACK_C, U>(Q, bad);   // row_shr:1
     wave_scan_level<S, D, SWAP, 0x112, 0xF, TRACK_C, U>(Q, bad);   // row_shr:2
     wave_scan_level<S, D, SWAP, 0x114, 0xF, TRACK_C, U>(Q, bad);   // row_shr:4
