@@ -209,15 +209,21 @@ HMM_DEV void agg_renorm(Agg<S, D>& P) {
 // stored rows keeps every term that matters to an entry within 2^-126 of its row's largest a normal
 // number.  Otherwise every row of Z takes its own reference exponent, the largest exponent among its
 // existing terms, so a row that lives only on Y's small rows keeps its full precision.
-template <class S, int D, bool TRACK_C = true>
+// MaxPlus: SHIFT = false leaves the largest entry where the product put it (below zero by at most what the factors'
+// entries allow) instead of moving it to zero.
+template <class S, int D, bool TRACK_C = true, bool SHIFT = true>
 HMM_DEV void agg_mul(const Agg<S, D>& X, const Agg<S, D>& Y, Agg<S, D>& Z) {
     if constexpr (S::is_max_plus) {
         mat_mul<S, D>(X.m, Y.m, Z.m);
-        float mx = max_of(Z.m);
-        mx = (mx == -INFINITY) ? 0.0f : mx;
+        if constexpr (SHIFT) {
+            float mx = max_of(Z.m);
+            mx = (mx == -INFINITY) ? 0.0f : mx;
 #pragma unroll
-        for (int e = 0; e < D * D; ++e) Z.m[e] -= mx;
-        if constexpr (TRACK_C) Z.c = X.c + Y.c + (double)mx;
+            for (int e = 0; e < D * D; ++e) Z.m[e] -= mx;
+            if constexpr (TRACK_C) Z.c = X.c + Y.c + (double)mx;
+        } else {
+            if constexpr (TRACK_C) Z.c = X.c + Y.c;
+        }
     } else {
         int hi = Y.ex[0], lo = Y.ex[0];
 #pragma unroll

@@ -457,6 +457,9 @@ HMM_DEV void wave_scan_level(Agg<S, D>& Q, bool& bad) {
     if constexpr (U && !S::is_max_plus && UBIAS != ROW_BIAS) {
         if constexpr (SWAP) agg_mul_u<D, TRACK_C, UBIAS>(Q, N, Z, bad);
         else agg_mul_u<D, TRACK_C, UBIAS>(N, Q, Z, bad);
+    } else if constexpr (S::is_max_plus && UBIAS != ROW_BIAS) {   // (max,+): a level that does not shift
+        if constexpr (SWAP) agg_mul<S, D, TRACK_C, false>(Q, N, Z);
+        else agg_mul<S, D, TRACK_C, false>(N, Q, Z);
     } else {
         if constexpr (SWAP) agg_mul_m<U, S, D, TRACK_C>(Q, N, Z, bad);
         else agg_mul_m<U, S, D, TRACK_C>(N, Q, Z, bad);
@@ -491,6 +494,19 @@ HMM_DEV void wave_scan_up(Agg<S, D>& Q, bool& bad) {
         wave_scan_level<S, D, SWAP, 0x114, 0xF, TRACK_C, U, MID>(Q, bad);    // row_shr:4
         wave_scan_level<S, D, SWAP, 0x118, 0xF, TRACK_C, U, NONE>(Q, bad);   // row_shr:8
         wave_scan_level<S, D, SWAP, 0x142, 0xA, TRACK_C, U, MID>(Q, bad);    // row_bcast:15 into rows 1 and 3
+        wave_scan_level<S, D, SWAP, 0x143, 0xC, TRACK_C, U>(Q, bad);         // row_bcast:31 into rows 2 and 3
+        return;
+    }
+    if constexpr (S::is_max_plus) {
+        // (max,+): the largest entry is moved to zero after every other level only.  Entries are at most zero, so
+        // a product's are too; left unshifted for one level they are at most twice as far from zero as they
+        // would otherwise be, which costs one bit of absolute precision in that level's sums.
+        constexpr int NONE = -1;
+        wave_scan_level<S, D, SWAP, 0x111, 0xF, TRACK_C, U, NONE>(Q, bad);   // row_shr:1
+        wave_scan_level<S, D, SWAP, 0x112, 0xF, TRACK_C, U>(Q, bad);         // row_shr:2
+        wave_scan_level<S, D, SWAP, 0x114, 0xF, TRACK_C, U, NONE>(Q, bad);   // row_shr:4
+        wave_scan_level<S, D, SWAP, 0x118, 0xF, TRACK_C, U>(Q, bad);         // row_shr:8
+        wave_scan_level<S, D, SWAP, 0x142, 0xA, TRACK_C, U, NONE>(Q, bad);   // row_bcast:15 into rows 1 and 3
         wave_scan_level<S, D, SWAP, 0x143, 0xC, TRACK_C, U>(Q, bad);         // row_bcast:31 into rows 2 and 3
         return;
     }
